@@ -1,0 +1,171 @@
+"""Pins of the oracle's reward, UCB1 and Thompson-Sampling code (CPU only)."""
+import math
+
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import oracle as orc
+
+
+def test_reward_hand_cases(golden):
+    rows = golden("reward_blend.txt")
+    assert rows[0] == ["alpha", "0.5"]
+    for m, n, g, r in rows[1:]:
+        assert orc.reward(int(m), int(n), int(g), 0.5) == float(r)      # dyadic rationals: exact
+    # alpha = 1 is the acceptance-length-only reward |Y| / gamma, alpha = 0 the acceptance rate
+    assert orc.reward(3, 4, 8, 1.0) == 3 / 8
+    assert orc.reward(3, 4, 8, 0.0) == 3 / 4
+    # bounds: 0 <= r <= 1, and r = 1 only when everything drafted up to the cap is accepted
+    for g in range(1, 9):
+        for n in range(1, g + 1):
+            for m in range(n + 1):
+                r = orc.reward(m, n, g)
+                assert 0.0 <= r <= 1.0 and (r == 1.0) == (m == n == g)
+
+
+def test_ucb1_plays_every_arm_once_in_index_order():
+    s, c = np.zeros(3), np.zeros(3, np.int64)
+    for expect in (0, 1, 2):
+        a, idx = orc.ucb1_select(s, c)
+        assert a == expect and np.isinf(idx[expect])
+        c[a] += 1
+        s[a] += 0.3
+
+
+def test_ucb1_hand_values():
+    # one play each, t = 4: the bonus sqrt(2 ln 4) is common, so argmax = best mean (lowest index on ties)
+    s, c = np.array([0.2, 0.7, 0.7]), np.array([1, 1, 1])
+    a, idx = orc.ucb1_select(s, c)
+    assert a == 1
+    b4 = math.sqrt(2 * math.log(4))
+    assert b4 == pytest.approx(1.6651092223153954, rel=1e-15)
+    np.testing.assert_allclose(idx, s + b4, rtol=1e-15)
+    # N = (2,1,1), t = 5: bonuses sqrt(2 ln5 / 2), sqrt(2 ln 5)
+    s, c = np.array([1.8, 0.4, 0.1]), np.array([2, 1, 1])
+    a, idx = orc.ucb1_select(s, c)
+    assert math.sqrt(math.log(5)) == pytest.approx(1.2686362411795196, rel=1e-15)
+    assert math.sqrt(2 * math.log(5)) == pytest.approx(1.7941225779941015, rel=1e-15)
+    np.testing.assert_allclose(idx, [0.9 + 1.2686362411795196, 0.4 + 1.7941225779941015, 0.1 + 1.7941225779941015],
+                               rtol=1e-15)
+    assert a == 1                         # 2.1941 beats 2.1686: exploration outweighs the better mean
+    # all equal: lowest index
+    assert orc.ucb1_select(np.array([.5, .5, .5]), np.array([4, 4, 4]))[0] == 0
+
+
+def test_ucb1_bonus_shrinks_with_plays_and_grows_with_time():
+    s = np.array([50.0, 5.0])
+    a, idx = orc.ucb1_select(s, np.array([100, 10]))
+    assert idx[1] - 0.5 > idx[0] - 0.5 > 0            # same mean 0.5: the less played arm has the larger bonus
+    assert a == 1
+    _, later = orc.ucb1_select(np.array([500.0, 5.0]), np.array([1000, 10]))
+    assert later[1] > idx[1]                          # ln t grew, N_1 did not
+
+
+def uniforms(g, n):
+    return g.random(n, np.float32)
+
+
+@pytest.mark.parametrize("shape", [1.0, 1.7, 4.0, 30.5])
+def test_gamma_sampler_law(shape):
+    g = np.random.default_rng(int(shape * 10))
+    N = 40000
+    draws = np.empty(N)
+    fails = 0
+    for i in range(N):
+        draws[i], ex = orc.gamma_draw(shape, uniforms(g, 24))
+        fails += ex
+    assert fails == 0
+    assert draws.mean() == pytest.approx(shape, rel=0.03)
+    assert draws.var() == pytest.approx(shape, rel=0.06)
+    assert stats.kstest(draws, stats.gamma(shape).cdf).pvalue > 1e-3
+
+
+@pytest.mark.parametrize("a,b", [(1.0, 1.0), (3.5, 1.25), (20.0, 60.0)])
+def test_beta_sampler_law(a, b):
+    g = np.random.default_rng(int(a * 7 + b))
+    N = 40000
+    draws = np.array([orc.beta_draw(a, b, uniforms(g, 48))[0] for _ in range(N)])
+    assert draws.mean() == pytest.approx(a / (a + b), abs=0.01)
+    assert draws.var() == pytest.approx(a * b / ((a + b) ** 2 * (a + b + 1)), rel=0.08)
+    assert stats.kstest(draws, stats.beta(a, b).cdf).pvalue > 1e-3
+
+
+def test_gamma_sampler_uses_uniforms_in_order_and_reports_exhaustion():
+    # u1 = 1 -> z = 0 -> v = 1 -> accepted iff ln u3 < 0: the first attempt returns d = shape - 1/3
+    u = np.full(24, 0.5, np.float32)
+    u[0] = 1.0
+    val, ex = orc.gamma_draw(2.0, u)
+    assert val == pytest.approx(2.0 - 1 / 3, rel=1e-15) and not ex
+    # z very negative makes v <= 0 on every attempt (u1 -> 2^-25 at u = 0, u2 = 0.5 -> cos = -1)
+    u = np.zeros(24, np.float32)
+    u[1::3] = 0.5
+    val, ex = orc.gamma_draw(1.0, u)
+    z = -math.sqrt(-2 * math.log(2.0 ** -25))
+    assert 1 + z / math.sqrt(9 * (1 - 1 / 3)) < 0          # indeed rejected
+    assert ex and val == 1.0
+    # only the second attempt usable: same value as when it comes first
+    u2 = np.zeros(24, np.float32); u2[1] = 0.5
+    u2[3:6] = (0.3, 0.2, 0.9 * 0 + 1e-9)
+    first = np.full(24, 0.5, np.float32); first[0:3] = u2[3:6]
+    assert orc.gamma_draw(3.0, u2)[0] == orc.gamma_draw(3.0, first)[0]
+
+
+def test_ts_select_is_argmax_of_posterior_draws_and_prefers_good_arm():
+    g = np.random.default_rng(2)
+    s, c = np.array([2.0, 45.0, 10.0]), np.array([50, 50, 50])
+    wins = np.zeros(3)
+    for _ in range(2000):
+        u = g.random((3, 48), np.float32)
+        a, th, ex = orc.ts_select(s, c, u)
+        assert a == int(np.argmax(th)) and not ex
+        for k in range(3):                                   # posterior = Beta(1 + S, 1 + N - S)
+            assert th[k] == orc.beta_draw(1 + s[k], 1 + c[k] - s[k], u[k])[0]
+        wins[a] += 1
+    assert wins[1] > 1990
+    # fresh bandit: uniform posteriors, every arm is chosen about a third of the time
+    wins = np.zeros(3)
+    for _ in range(3000):
+        wins[orc.ts_select(np.zeros(3), np.zeros(3, np.int64), g.random((3, 48), np.float32))[0]] += 1
+    assert (abs(wins / 3000 - 1 / 3) < 0.04).all()
+
+
+def test_batched_bandit_state_machine():
+    # per-sequence bandits: independent; update adds one play and the blended reward
+    bd = orc.Bandit(orc.POLICY_UCB1, n_bandits=2, n_arms=3)
+    arms, _ = bd.select(2)
+    assert arms.tolist() == [0, 0]
+    bd.update(arms, [3, 0], [4, 3], [8, 8])
+    assert bd.count.tolist() == [[1, 0, 0], [1, 0, 0]]
+    assert bd.sum_r[:, 0].tolist() == [0.5625, 0.0]
+    arms, _ = bd.select(2)
+    assert arms.tolist() == [1, 1]
+    bd.update(arms, [5, 2], [5, 8], [5, 8], active=[0, 1])      # inactive sequence: untouched
+    assert bd.count.tolist() == [[1, 0, 0], [1, 1, 0]] and bd.sum_r[1, 1] == 0.25
+    # shared bandit: one arm for the round, B plays applied in order
+    sh = orc.Bandit(orc.POLICY_UCB1, n_bandits=1, n_arms=3)
+    arms, _ = sh.select(4)
+    assert arms.tolist() == [0, 0, 0, 0]
+    sh.update(arms, [1, 2, 3, 4], [4, 4, 4, 4], [4, 4, 4, 4])
+    assert sh.count.tolist() == [[4, 0, 0]] and sh.sum_r[0, 0] == 0.25 + 0.5 + 0.75 + 1.0
+    # Thompson: the batched call equals the single call on each bandit's own uniforms
+    ts = orc.Bandit(orc.POLICY_TS_BETA, n_bandits=3, n_arms=3)
+    ts.sum_r[:] = [[1, 2, 3], [4, 1, 0.5], [0, 0, 0]]
+    ts.count[:] = [[5, 5, 5], [6, 2, 9], [0, 0, 0]]
+    u = np.random.default_rng(4).random((3, 3, 48), np.float32)
+    arms, fl = ts.select(3, u)
+    assert arms.tolist() == [orc.ts_select(ts.sum_r[b], ts.count[b], u[b])[0] for b in range(3)]
+    assert not fl.any()
+
+
+def test_ucb1_converges_to_best_arm():
+    # the bandit loop as a whole: arm 2 has the highest mean reward and ends up played most
+    g = np.random.default_rng(0)
+    bd = orc.Bandit(orc.POLICY_UCB1, 1, 3)
+    means = (0.3, 0.5, 0.7)
+    for _ in range(3000):
+        a = int(bd.select(1)[0][0])
+        m = int(g.random() < means[a]) * 8
+        bd.update([a], [m], [8], [8])
+    assert bd.count[0].argmax() == 2 and bd.count[0, 2] > 2000
+    np.testing.assert_allclose(bd.sum_r[0] / bd.count[0], means, atol=0.12)

@@ -1,0 +1,244 @@
+/*
+ * libtapout -- per-round logits processing of TapOut (bandit-controlled dynamic
+ * speculative decoding) on one AMD MI355X (gfx950).  C ABI, no C++ or torch
+ * types.
+ *
+ * One decode round (Algorithm 1 of the paper) maps onto four calls:
+ *
+ *   tapout_bandit_select   arm of every sequence for this drafting session
+ *   tapout_draft_stats     signals of the draft distributions + stop position
+ *   tapout_verify          accept the drafted prefix, draw the final token
+ *   tapout_bandit_update   blended reward -> bandit state
+ *
+ * General rules
+ *   Pointers.  Unless a parameter says "host", every array pointer is a DEVICE
+ *     pointer into memory owned by the caller; the library never keeps it
+ *     after the call returns.  "or NULL" marks optional arrays.
+ *   Asynchrony.  Calls enqueue kernels on `stream` (a hipStream_t passed as
+ *     void*, NULL = the default stream) and return without waiting.  Calls on
+ *     one context must be issued in stream order on one stream at a time: the
+ *     context owns scratch memory that consecutive calls reuse.
+ *   Memory.  Device memory is allocated in tapout_create and released in
+ *     tapout_destroy, never in between.
+ *   Errors.  Every call returns a tapout_status.  Argument errors are found on
+ *     the host before anything is launched and leave all outputs untouched;
+ *     tapout_last_error() describes the last failure on that context.
+ *     Data-dependent problems cannot be reported synchronously: they set bits
+ *     in the per-sequence device array `flags` and produce the documented
+ *     fallback result.
+ *   Determinism.  No floating-point atomics; same inputs give bit-identical
+ *     outputs from run to run.
+ *   Logits layout.  A logits tensor is [B, K, V] (draft) or [B, K+1, V]
+ *     (target) with the vocabulary axis contiguous; stride_b / stride_k are in
+ *     elements.  Rows may start at any element-aligned address; rows that are
+ *     16-byte aligned take the fast path.
+ */
+#ifndef TAPOUT_H
+#define TAPOUT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#if defined(__GNUC__)
+#define TAPOUT_API __attribute__((visibility("default")))
+#else
+#define TAPOUT_API
+#endif
+
+#define TAPOUT_MAX_ARMS 8
+/* caller uniforms per arm for one Thompson draw: 2 Gamma variates x 8 attempts x 3 */
+#define TAPOUT_TS_UNIFORMS_PER_ARM 48
+
+typedef struct tapout_ctx tapout_ctx;
+
+typedef enum {
+    TAPOUT_OK = 0,
+    TAPOUT_EINVAL = 1,       /* bad argument (see tapout_last_error)           */
+    TAPOUT_EUNSUPPORTED = 2, /* valid request the build does not implement      */
+    TAPOUT_ENOMEM = 3,       /* device allocation failed in tapout_create       */
+    TAPOUT_EHIP = 4          /* a HIP runtime call or kernel launch failed      */
+} tapout_status;
+
+typedef enum { TAPOUT_F32 = 0, TAPOUT_BF16 = 1 } tapout_dtype;
+
+/* Stop rules of Table 1 (threshold arms).  A rule fires, i.e. drafting stops
+ * after the current token, when its strict inequality holds:
+ *   SVIP     sqrt(H(p)) > h          h = 0.6
+ *   MAXCONF  p(top-1) < h            h = 0.8
+ *   MARGIN   p(top-1) - p(top-2) < h h = 0.2                                  */
+typedef enum { TAPOUT_RULE_SVIP = 0, TAPOUT_RULE_MAXCONF = 1, TAPOUT_RULE_MARGIN = 2 } tapout_rule;
+
+/* Bandit policies of Section 3.3 (sequence-level). */
+typedef enum { TAPOUT_UCB1 = 0, TAPOUT_TS_BETA = 1 } tapout_policy;
+
+/* per-sequence flag bits written by the kernels */
+#define TAPOUT_FLAG_BAD_ROW 1u           /* a processed row holds NaN or has no finite maximum */
+#define TAPOUT_FLAG_BAD_TOKEN 2u         /* drafted token id outside [0, V)                    */
+#define TAPOUT_FLAG_BAD_NDRAFT 4u        /* n_draft outside [1, K]                             */
+#define TAPOUT_FLAG_SAMPLER_EXHAUSTED 8u /* all Gamma attempts rejected (Thompson)             */
+
+typedef struct {
+    int32_t device;                       /* HIP device ordinal                                 */
+    int32_t max_batch;                    /* largest B of any call                              */
+    int32_t max_k;                        /* largest K (draft positions per sequence)           */
+    int32_t vocab;                        /* largest V of any call                              */
+    int32_t n_arms;                       /* 1 .. TAPOUT_MAX_ARMS                               */
+    int32_t rule[TAPOUT_MAX_ARMS];        /* tapout_rule of each arm                            */
+    float threshold[TAPOUT_MAX_ARMS];     /* h of each arm (Table 1 values are the defaults)    */
+    int32_t policy;                       /* tapout_policy                                      */
+    int32_t n_bandits;                    /* max_batch: one bandit per sequence slot; 1: shared */
+    double alpha;                         /* weight of |Y|/gamma in the blended reward (0.5)    */
+} tapout_config;
+
+typedef struct {
+    const void *ptr;                      /* device pointer to element [0,0,0]                  */
+    int32_t dtype;                        /* tapout_dtype                                       */
+    int64_t stride_b, stride_k;           /* elements; the vocabulary axis has stride 1         */
+} tapout_logits;
+
+/* Fill *cfg with the paper's set-up: three arms SVIP / MAXCONF / MARGIN at the
+ * Table 1 thresholds, UCB1, alpha = 0.5, one bandit per sequence.  host.     */
+TAPOUT_API void tapout_default_config(tapout_config *cfg, int32_t max_batch, int32_t max_k, int32_t vocab);
+
+/* Create a context on cfg->device: validates cfg (host), allocates scratch
+ * and bandit state (all plays zero).  *out is NULL on failure.               */
+TAPOUT_API tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg);
+TAPOUT_API tapout_status tapout_destroy(tapout_ctx *ctx);
+/* Text of the last error on ctx (valid until the next call on ctx); with
+ * ctx == NULL the text of the last failed tapout_create on this thread.      */
+TAPOUT_API const char *tapout_last_error(const tapout_ctx *ctx);
+
+/*
+ * Arm selection at the start of a drafting session (Section 3.1: sequence-
+ * level bandit; Section 3.3: UCB1, Thompson Sampling).
+ *   UCB1: an arm never played is chosen first (lowest index); otherwise
+ *     argmax_a  mean_a + sqrt(2 ln t / N_a),  t = 1 + sum_a N_a, lowest index
+ *     on exact ties.  fp64.
+ *   TS_BETA: theta_a ~ Beta(1 + S_a, 1 + N_a - S_a) (S_a = summed rewards),
+ *     argmax_a theta_a.  The draw is G1/(G1+G2), G ~ Gamma(shape) by
+ *     Marsaglia-Tsang driven by u_ts[b][a][0..47]: 8 attempts x (2 Box-Muller
+ *     uniforms, 1 acceptance uniform) for G1, then the same for G2; u = 0 is
+ *     read as 2^-25; if all attempts reject, G = shape and
+ *     TAPOUT_FLAG_SAMPLER_EXHAUSTED is set.  fp64.
+ * u_ts    [B, n_arms, 48] f32 in [0,1), required for TS_BETA, ignored for UCB1
+ * arm_out [B] i32
+ * flags   [B] u32 or NULL (overwritten)
+ * With a shared bandit (n_bandits == 1) every sequence gets the arm drawn for
+ * sequence 0.
+ */
+TAPOUT_API tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const float *u_ts,
+                                   int32_t *arm_out, uint32_t *flags, void *stream);
+
+/*
+ * Signals of the draft distributions and the stop position (Appendix A.1,
+ * Table 1; Algorithm 1 lines 2-8).  For every row (b,k), k < k_len[b], of the
+ * draft logits x, with p = softmax(x):
+ *   lse      = ln sum_j exp(x_j)
+ *   entropy  = -sum_j p_j ln p_j          (nats, 0 ln 0 = 0)
+ *   p_top1   = max_j p_j,  top1_id = smallest argmax index
+ *   p_top2   = second largest p_j counting duplicates (a tie at the top gives
+ *              p_top2 = p_top1), margin = p_top1 - p_top2
+ *   logq_tok = x[draft_tok] - lse
+ * and per sequence n_stop = (first k at which the rule of arm[b] fires) + 1,
+ * else k_len[b]: the token drafted at the firing step is kept.  The rule is
+ * evaluated on the returned binary32 signals, widened to double (SVIP compares
+ * sqrt(entropy)).  Rows k >= k_len[b] are neither read nor written.
+ *
+ * draft_tok [B,K] i32 or NULL (then logq_tok is not written)
+ * k_len     [B] i32 or NULL (= K for all)
+ * arm       [B] i32 or NULL (then n_stop / stop_fired are not written)
+ * lse, entropy, p_top1, p_top2, margin, logq_tok [B,K] f32, each or NULL
+ * top1_id   [B,K] i32 or NULL
+ * n_stop    [B] i32 or NULL;  stop_fired [B,K] u8 or NULL
+ * flags     [B] u32 or NULL (overwritten): BAD_ROW, BAD_TOKEN.  A bad row
+ *           yields NaN signals (its rule does not fire); a bad token NaN
+ *           logq_tok.
+ */
+TAPOUT_API tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
+                                 int32_t B, int32_t K, int32_t V,
+                                 const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
+                                 int32_t *top1_id, float *logq_tok,
+                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream);
+
+/*
+ * Verification of the drafted tokens and the final token (Algorithm 1 lines
+ * 10-11, with "verify" meaning speculative sampling as in the works the
+ * paper's introduction cites).  n = n_draft[b] tokens were drafted; target
+ * rows 0..n are read (row n is the distribution after all n tokens).
+ *   sampled sequence: token k is accepted iff
+ *       u_accept[b,k] < exp(logp_tok[b,k] - logq_tok[b,k]),
+ *     logp_tok = target[b,k,tok] - lse(target[b,k]) rounded to binary32, the
+ *     comparison in double.  accept_len m = number of leading accepts.
+ *     Final token: m < n: inverse CDF of max(0, p_m - q_m) (softmaxes of
+ *     target / draft row m) at u_sample[b]; m = n: inverse CDF of p_n.
+ *     Inverse CDF = smallest j whose inclusive prefix sum exceeds u * total;
+ *     accumulated in double.  An all-zero residual falls back to p_m.
+ *   greedy sequence (greedy[b] != 0): accepted iff tok == argmax target row k
+ *     (smallest index); final token = argmax of target row m.
+ *   out_tok[b] = accepted tokens, the final token, then -1 up to K+1 entries;
+ *   n_out = m + 1.  (The paper's acceptance length m excludes the final token.)
+ * A sequence with BAD_NDRAFT, BAD_TOKEN or BAD_ROW (any target row 0..n, or
+ * the draft row it would resample from) gets accept_len 0 and the argmax of
+ * target row 0 as its token, except that a bad draft row found only at the
+ * residual step falls back to sampling from p_m.
+ *
+ * target     [B,K+1,V], draft [B,K,V]
+ * draft_lse  [B,K] f32: lse from tapout_draft_stats (exponent reference of
+ *            the draft row when the residual is formed)
+ * logq_tok   [B,K] f32 from tapout_draft_stats
+ * draft_tok  [B,K] i32;  n_draft [B] i32 in [1,K]
+ * greedy     [B] u8 or NULL (all sampled)
+ * u_accept   [B,K] f32 in [0,1);  u_sample [B] f32 in [0,1)
+ * accept_len [B] i32;  out_tok [B,K+1] i32;  n_out [B] i32
+ * target_lse [B,K+1] f32 or NULL;  logp_tok [B,K] f32 or NULL;
+ * target_top1 [B,K+1] i32 or NULL  (rows > n_draft[b] untouched)
+ * flags      [B] u32 or NULL (overwritten)
+ */
+TAPOUT_API tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const tapout_logits *draft,
+                            int32_t B, int32_t K, int32_t V,
+                            const float *draft_lse, const float *logq_tok,
+                            const int32_t *draft_tok, const int32_t *n_draft, const uint8_t *greedy,
+                            const float *u_accept, const float *u_sample,
+                            int32_t *accept_len, int32_t *out_tok, int32_t *n_out,
+                            float *target_lse, float *logp_tok, int32_t *target_top1,
+                            uint32_t *flags, void *stream);
+
+/*
+ * Bandit update after verification (Algorithm 1 line 12; Section 3.2):
+ *   r = alpha * m / gamma + (1 - alpha) * m / n,  m = accept_len, n = n_draft,
+ *   evaluated in double as (alpha*m)/gamma + ((1-alpha)*m)/n without fused
+ *   multiply-add; then N[arm] += 1, S[arm] += r.
+ * Sequences with active[b] == 0, an arm outside [0, n_arms), n_draft < 1 or
+ * gamma < 1 are skipped.  With a shared bandit the B rewards are applied in
+ * index order, each as one play.
+ * arm, accept_len, n_draft, gamma [B] i32;  active [B] u8 or NULL
+ */
+TAPOUT_API tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *arm,
+                                   const int32_t *accept_len, const int32_t *n_draft,
+                                   const int32_t *gamma, const uint8_t *active, void *stream);
+
+/* Bandit state read-out (the arm values of Section 4.3 are sum_r / count) and
+ * restore.  sum_r, count: HOST arrays [n_bandits, n_arms] (f64, i64).  Both
+ * calls synchronise `stream`.                                                 */
+TAPOUT_API tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, int64_t *count, void *stream);
+TAPOUT_API tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *sum_r, const int64_t *count, void *stream);
+
+/*
+ * Launch-shape tuning (host; takes effect from the next call).  Names:
+ *   "wgs_target"  workgroups a streaming launch aims for (rows are cut into
+ *                 slices until the launch has about this many), default 4096
+ *   "min_slice"   smallest slice of a row, in elements, default 4096
+ *   "sample_wgs"  workgroups the final-token passes aim for, default 2048
+ * Results do not depend on these values except through the rounding of the
+ * binary32 partial sums.
+ */
+TAPOUT_API tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAPOUT_H */

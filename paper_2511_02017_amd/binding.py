@@ -1,0 +1,245 @@
+"""ctypes binding of libtapout.so (include/tapout.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels.  torch supplies device memory and the stream; nothing here computes.
+The binding fails loudly if the built library is missing: there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libtapout.so")
+
+MAX_ARMS = 8
+TS_UNIFORMS_PER_ARM = 48
+F32, BF16 = 0, 1
+RULE_SVIP, RULE_MAXCONF, RULE_MARGIN = 0, 1, 2
+UCB1, TS_BETA = 0, 1
+FLAG_BAD_ROW, FLAG_BAD_TOKEN, FLAG_BAD_NDRAFT, FLAG_SAMPLER_EXHAUSTED = 1, 2, 4, 8
+STATUS = {0: "TAPOUT_OK", 1: "TAPOUT_EINVAL", 2: "TAPOUT_EUNSUPPORTED", 3: "TAPOUT_ENOMEM", 4: "TAPOUT_EHIP"}
+
+EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_last_error",
+           "tapout_bandit_select", "tapout_draft_stats", "tapout_verify", "tapout_bandit_update",
+           "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_set_option")
+
+
+class TapoutConfig(C.Structure):
+    _fields_ = [("device", C.c_int32), ("max_batch", C.c_int32), ("max_k", C.c_int32), ("vocab", C.c_int32),
+                ("n_arms", C.c_int32), ("rule", C.c_int32 * MAX_ARMS), ("threshold", C.c_float * MAX_ARMS),
+                ("policy", C.c_int32), ("n_bandits", C.c_int32), ("alpha", C.c_double)]
+
+
+class TapoutLogits(C.Structure):
+    _fields_ = [("ptr", C.c_void_p), ("dtype", C.c_int32), ("stride_b", C.c_int64), ("stride_k", C.c_int64)]
+
+
+class TapoutError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"{STATUS.get(status, status)}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load_library():
+    """Load the in-tree libtapout.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_02017_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        vp, i32 = C.c_void_p, C.c_int32
+        lib.tapout_default_config.restype = None
+        lib.tapout_default_config.argtypes = [C.POINTER(TapoutConfig), i32, i32, i32]
+        lib.tapout_create.argtypes = [C.POINTER(vp), C.POINTER(TapoutConfig)]
+        lib.tapout_destroy.argtypes = [vp]
+        lib.tapout_last_error.restype = C.c_char_p
+        lib.tapout_last_error.argtypes = [vp]
+        lib.tapout_bandit_select.argtypes = [vp, i32, vp, vp, vp, vp]
+        lib.tapout_draft_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 14
+        lib.tapout_verify.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 15
+        lib.tapout_bandit_update.argtypes = [vp, i32] + [vp] * 6
+        lib.tapout_bandit_get_state.argtypes = [vp] * 4
+        lib.tapout_bandit_set_state.argtypes = [vp] * 4
+        lib.tapout_set_option.argtypes = [vp, C.c_char_p, i32]
+        _lib = lib
+    return _lib
+
+
+def default_config(max_batch: int, max_k: int, vocab: int) -> TapoutConfig:
+    cfg = TapoutConfig()
+    load_library().tapout_default_config(C.byref(cfg), max_batch, max_k, vocab)
+    return cfg
+
+
+def _ptr(t, dtype=None, shape=None, name="tensor"):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name}: expected {dtype}, got {t.dtype}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: expected shape {tuple(shape)}, got {tuple(t.shape)}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    return t.data_ptr()
+
+
+def _logits(t, name) -> TapoutLogits:
+    if t.dim() != 3 or not t.is_cuda:
+        raise ValueError(f"{name} logits must be a 3-d GPU tensor")
+    if t.shape[2] > 1 and t.stride(2) != 1:
+        raise ValueError(f"{name} logits: the vocabulary axis must be contiguous")
+    if t.dtype == torch.float32:
+        dt = F32
+    elif t.dtype == torch.bfloat16:
+        dt = BF16
+    else:
+        raise ValueError(f"{name} logits: dtype {t.dtype} is not supported (float32 / bfloat16)")
+    return TapoutLogits(t.data_ptr(), dt, t.stride(0), t.stride(1))
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+class Tapout:
+    """One libtapout context (scratch memory + bandit state) on one GPU."""
+
+    def __init__(self, max_batch: int, max_k: int, vocab: int, *, device: int = 0, policy: int = UCB1,
+                 rules=(RULE_SVIP, RULE_MAXCONF, RULE_MARGIN), thresholds=(0.6, 0.8, 0.2),
+                 alpha: float = 0.5, shared_bandit: bool = False):
+        self._lib = load_library()
+        cfg = default_config(max_batch, max_k, vocab)
+        cfg.device = device
+        cfg.policy = policy
+        cfg.n_arms = len(rules)
+        for i, (r, h) in enumerate(zip(rules, thresholds)):
+            cfg.rule[i], cfg.threshold[i] = r, h
+        cfg.alpha = alpha
+        cfg.n_bandits = 1 if shared_bandit else max_batch
+        self.cfg = cfg
+        self.device = torch.device("cuda", device)
+        self._ctx = C.c_void_p()
+        st = self._lib.tapout_create(C.byref(self._ctx), C.byref(cfg))
+        if st != 0:
+            raise TapoutError(st, self._lib.tapout_last_error(None).decode())
+
+    def close(self):
+        if getattr(self, "_ctx", None) is not None and self._ctx.value:
+            self._lib.tapout_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    __del__ = close
+
+    def _check(self, st):
+        if st != 0:
+            raise TapoutError(st, self._lib.tapout_last_error(self._ctx).decode())
+
+    def set_option(self, name: str, value: int):
+        self._check(self._lib.tapout_set_option(self._ctx, name.encode(), int(value)))
+
+    # -- tapout_bandit_select ------------------------------------------------
+    def bandit_select(self, B: int, u_ts=None, arm_out=None, flags=None, stream=None):
+        A = self.cfg.n_arms
+        if arm_out is None:
+            arm_out = torch.empty(B, dtype=torch.int32, device=self.device)
+        self._check(self._lib.tapout_bandit_select(
+            self._ctx, B, _ptr(u_ts, torch.float32, (B, A, TS_UNIFORMS_PER_ARM), "u_ts"),
+            _ptr(arm_out, torch.int32, (B,), "arm_out"), _ptr(flags, torch.int32, (B,), "flags"), _stream(stream)))
+        return arm_out
+
+    # -- tapout_draft_stats --------------------------------------------------
+    def draft_stats(self, draft, draft_tok=None, k_len=None, arm=None, out=None, stream=None):
+        """Returns / fills a dict: lse, entropy, p_top1, p_top2, margin, top1_id, logq_tok, n_stop, stop_fired, flags."""
+        B, K, V = draft.shape
+        if out is None:
+            out = self.alloc_draft_outputs(B, K)
+        f32, i32 = torch.float32, torch.int32
+        lg = _logits(draft, "draft")
+        self._check(self._lib.tapout_draft_stats(
+            self._ctx, C.byref(lg), B, K, V,
+            _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(k_len, i32, (B,), "k_len"), _ptr(arm, i32, (B,), "arm"),
+            _ptr(out.get("lse"), f32, (B, K), "lse"), _ptr(out.get("entropy"), f32, (B, K), "entropy"),
+            _ptr(out.get("p_top1"), f32, (B, K), "p_top1"), _ptr(out.get("p_top2"), f32, (B, K), "p_top2"),
+            _ptr(out.get("margin"), f32, (B, K), "margin"), _ptr(out.get("top1_id"), i32, (B, K), "top1_id"),
+            _ptr(out.get("logq_tok"), f32, (B, K), "logq_tok") if draft_tok is not None else None,
+            _ptr(out.get("n_stop"), i32, (B,), "n_stop") if arm is not None else None,
+            _ptr(out.get("stop_fired"), torch.uint8, (B, K), "stop_fired") if arm is not None else None,
+            _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream)))
+        return out
+
+    def alloc_draft_outputs(self, B, K):
+        d = self.device
+        f = lambda: torch.full((B, K), float("nan"), dtype=torch.float32, device=d)
+        return dict(lse=f(), entropy=f(), p_top1=f(), p_top2=f(), margin=f(), logq_tok=f(),
+                    top1_id=torch.full((B, K), -1, dtype=torch.int32, device=d),
+                    n_stop=torch.zeros(B, dtype=torch.int32, device=d),
+                    stop_fired=torch.zeros((B, K), dtype=torch.uint8, device=d),
+                    flags=torch.zeros(B, dtype=torch.int32, device=d))
+
+    # -- tapout_verify -------------------------------------------------------
+    def verify(self, target, draft, draft_lse, logq_tok, draft_tok, n_draft, u_accept, u_sample,
+               greedy=None, out=None, stream=None):
+        """Returns / fills a dict: accept_len, out_tok, n_out, target_lse, logp_tok, target_top1, flags."""
+        B, K1, V = target.shape
+        K = K1 - 1
+        if tuple(draft.shape) != (B, K, V):
+            raise ValueError(f"draft logits must be {(B, K, V)}, got {tuple(draft.shape)}")
+        if out is None:
+            out = self.alloc_verify_outputs(B, K)
+        f32, i32 = torch.float32, torch.int32
+        tl, dl = _logits(target, "target"), _logits(draft, "draft")
+        self._check(self._lib.tapout_verify(
+            self._ctx, C.byref(tl), C.byref(dl), B, K, V,
+            _ptr(draft_lse, f32, (B, K), "draft_lse"), _ptr(logq_tok, f32, (B, K), "logq_tok"),
+            _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(n_draft, i32, (B,), "n_draft"),
+            _ptr(greedy, torch.uint8, (B,), "greedy"),
+            _ptr(u_accept, f32, (B, K), "u_accept"), _ptr(u_sample, f32, (B,), "u_sample"),
+            _ptr(out["accept_len"], i32, (B,), "accept_len"), _ptr(out["out_tok"], i32, (B, K + 1), "out_tok"),
+            _ptr(out["n_out"], i32, (B,), "n_out"),
+            _ptr(out.get("target_lse"), f32, (B, K + 1), "target_lse"), _ptr(out.get("logp_tok"), f32, (B, K), "logp_tok"),
+            _ptr(out.get("target_top1"), i32, (B, K + 1), "target_top1"),
+            _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream)))
+        return out
+
+    def alloc_verify_outputs(self, B, K):
+        d = self.device
+        return dict(accept_len=torch.zeros(B, dtype=torch.int32, device=d),
+                    out_tok=torch.full((B, K + 1), -1, dtype=torch.int32, device=d),
+                    n_out=torch.zeros(B, dtype=torch.int32, device=d),
+                    target_lse=torch.full((B, K + 1), float("nan"), dtype=torch.float32, device=d),
+                    logp_tok=torch.full((B, K), float("nan"), dtype=torch.float32, device=d),
+                    target_top1=torch.full((B, K + 1), -1, dtype=torch.int32, device=d),
+                    flags=torch.zeros(B, dtype=torch.int32, device=d))
+
+    # -- tapout_bandit_update ------------------------------------------------
+    def bandit_update(self, arm, accept_len, n_draft, gamma, active=None, stream=None):
+        B = arm.shape[0]
+        i32 = torch.int32
+        self._check(self._lib.tapout_bandit_update(
+            self._ctx, B, _ptr(arm, i32, (B,), "arm"), _ptr(accept_len, i32, (B,), "accept_len"),
+            _ptr(n_draft, i32, (B,), "n_draft"), _ptr(gamma, i32, (B,), "gamma"),
+            _ptr(active, torch.uint8, (B,), "active"), _stream(stream)))
+
+    # -- state read-out / restore (host arrays) ------------------------------
+    def bandit_get_state(self, stream=None):
+        import numpy as np
+        n = (self.cfg.n_bandits, self.cfg.n_arms)
+        s, c = np.zeros(n, np.float64), np.zeros(n, np.int64)
+        self._check(self._lib.tapout_bandit_get_state(self._ctx, s.ctypes.data, c.ctypes.data, _stream(stream)))
+        return s, c
+
+    def bandit_set_state(self, sum_r, count, stream=None):
+        import numpy as np
+        n = (self.cfg.n_bandits, self.cfg.n_arms)
+        s = np.ascontiguousarray(sum_r, np.float64).reshape(n)
+        c = np.ascontiguousarray(count, np.int64).reshape(n)
+        self._check(self._lib.tapout_bandit_set_state(self._ctx, s.ctypes.data, c.ctypes.data, _stream(stream)))

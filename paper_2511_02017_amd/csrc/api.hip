@@ -1,0 +1,334 @@
+// C ABI of libtapout: argument validation, scratch ownership, launch sequencing.
+// Every entry point validates on the host, then only enqueues kernels.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.h"
+
+using namespace tapout;
+
+struct tapout_ctx {
+    tapout_config cfg;
+    Partial *part = nullptr;      size_t part_cap = 0;       // slice partials of the pass in flight
+    double *part1 = nullptr, *part2 = nullptr;                // residual sampler slice sums
+    SampleJob *jobs = nullptr;
+    uint32_t *flags_ws = nullptr;
+    double *sum_r = nullptr;      int64_t *count = nullptr;   // bandit state [n_bandits, n_arms]
+    int wgs_target = 4096;        // workgroups a streaming launch aims for
+    int min_slice = 4096;         // smallest slice (elements) a row is cut into
+    int sample_wgs = 2048;        // workgroups the sampler passes aim for
+    char err[256] = {0};
+};
+
+namespace {
+
+constexpr int kMaxWgsTarget = 1 << 16;
+constexpr int kMaxSampleSplit = 64;
+thread_local char g_create_err[256] = {0};
+
+tapout_status fail(tapout_ctx *ctx, tapout_status st, const char *fmt, ...)
+{
+    char *dst = ctx ? ctx->err : g_create_err;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 256, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+tapout_status hip_fail(tapout_ctx *ctx, hipError_t e, const char *what)
+{
+    return fail(ctx, TAPOUT_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+struct DeviceGuard {
+    int prev = -1; bool changed = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) changed = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() { if (changed) (void)hipSetDevice(prev); }
+};
+
+int choose_nsplit(const tapout_ctx *ctx, int64_t rows, int V)
+{
+    int64_t want = (ctx->wgs_target + rows - 1) / rows;
+    int64_t by_size = V / ctx->min_slice;
+    if (by_size < 1) by_size = 1;
+    if (want > by_size) want = by_size;
+    if (want < 1) want = 1;
+    return (int)want;
+}
+
+int choose_sample_nsplit(const tapout_ctx *ctx, int B, int V)
+{
+    int want = (ctx->sample_wgs + B - 1) / B;
+    int by_size = V / 2048;
+    if (by_size < 1) by_size = 1;
+    if (want > by_size) want = by_size;
+    if (want > kMaxSampleSplit) want = kMaxSampleSplit;
+    if (want < 1) want = 1;
+    return want;
+}
+
+const char *check_logits(const tapout_logits *l, const char *name, int V, int rows_k, char *buf)
+{
+    if (!l || !l->ptr) { snprintf(buf, 128, "%s logits pointer is NULL", name); return buf; }
+    if (l->dtype != TAPOUT_F32 && l->dtype != TAPOUT_BF16) { snprintf(buf, 128, "%s logits: unknown dtype %d", name, l->dtype); return buf; }
+    int esz = l->dtype == TAPOUT_F32 ? 4 : 2;
+    if ((uintptr_t)l->ptr % esz) { snprintf(buf, 128, "%s logits pointer is not element-aligned", name); return buf; }
+    if (l->stride_b < 0 || l->stride_k < 0) { snprintf(buf, 128, "%s logits: negative stride", name); return buf; }
+    (void)V; (void)rows_k;
+    return nullptr;
+}
+
+tapout_status check_shape(tapout_ctx *ctx, int B, int K, int V)
+{
+    if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (K < 1 || K > ctx->cfg.max_k) return fail(ctx, TAPOUT_EINVAL, "K = %d outside [1, max_k = %d]", K, ctx->cfg.max_k);
+    if (V < 1 || V > ctx->cfg.vocab) return fail(ctx, TAPOUT_EINVAL, "V = %d outside [1, vocab = %d]", V, ctx->cfg.vocab);
+    return TAPOUT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+void tapout_default_config(tapout_config *cfg, int32_t max_batch, int32_t max_k, int32_t vocab)
+{
+    if (!cfg) return;
+    memset(cfg, 0, sizeof *cfg);
+    cfg->device = 0;
+    cfg->max_batch = max_batch; cfg->max_k = max_k; cfg->vocab = vocab;
+    cfg->n_arms = 3;
+    cfg->rule[0] = TAPOUT_RULE_SVIP;    cfg->threshold[0] = 0.6f;
+    cfg->rule[1] = TAPOUT_RULE_MAXCONF; cfg->threshold[1] = 0.8f;
+    cfg->rule[2] = TAPOUT_RULE_MARGIN;  cfg->threshold[2] = 0.2f;
+    cfg->policy = TAPOUT_UCB1;
+    cfg->n_bandits = max_batch;
+    cfg->alpha = 0.5;
+}
+
+tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
+{
+    if (!out) return fail(nullptr, TAPOUT_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!cfg) return fail(nullptr, TAPOUT_EINVAL, "cfg is NULL");
+    if (cfg->max_batch < 1 || cfg->max_k < 1 || cfg->vocab < 1)
+        return fail(nullptr, TAPOUT_EINVAL, "max_batch, max_k and vocab must be positive");
+    if (cfg->max_k > 4096) return fail(nullptr, TAPOUT_EINVAL, "max_k = %d exceeds 4096", cfg->max_k);
+    if ((int64_t)cfg->max_batch * (cfg->max_k + 1) > (int64_t)1 << 26)
+        return fail(nullptr, TAPOUT_EINVAL, "max_batch * (max_k + 1) exceeds 2^26 rows");
+    if (cfg->n_arms < 1 || cfg->n_arms > TAPOUT_MAX_ARMS) return fail(nullptr, TAPOUT_EINVAL, "n_arms = %d outside [1, %d]", cfg->n_arms, TAPOUT_MAX_ARMS);
+    for (int a = 0; a < cfg->n_arms; ++a) {
+        if (cfg->rule[a] < TAPOUT_RULE_SVIP || cfg->rule[a] > TAPOUT_RULE_MARGIN)
+            return fail(nullptr, TAPOUT_EUNSUPPORTED, "arm %d: rule %d is not implemented", a, cfg->rule[a]);
+        if (!(cfg->threshold[a] == cfg->threshold[a])) return fail(nullptr, TAPOUT_EINVAL, "arm %d: threshold is NaN", a);
+    }
+    if (cfg->policy != TAPOUT_UCB1 && cfg->policy != TAPOUT_TS_BETA) return fail(nullptr, TAPOUT_EUNSUPPORTED, "policy %d is not implemented", cfg->policy);
+    if (cfg->n_bandits != 1 && cfg->n_bandits != cfg->max_batch) return fail(nullptr, TAPOUT_EINVAL, "n_bandits must be 1 or max_batch");
+    if (!(cfg->alpha >= 0.0 && cfg->alpha <= 1.0)) return fail(nullptr, TAPOUT_EINVAL, "alpha outside [0, 1]");
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev)
+        return fail(nullptr, TAPOUT_EHIP, "device %d not available (%d HIP devices)", cfg->device, ndev);
+
+    tapout_ctx *c = new (std::nothrow) tapout_ctx;
+    if (!c) return fail(nullptr, TAPOUT_ENOMEM, "host allocation failed");
+    c->cfg = *cfg;
+    DeviceGuard guard(cfg->device);
+    const size_t rows = (size_t)cfg->max_batch * (cfg->max_k + 1);
+    c->part_cap = rows + kMaxWgsTarget;
+    const size_t nstate = (size_t)cfg->n_bandits * cfg->n_arms;
+    bool ok = hipMalloc(&c->part, c->part_cap * sizeof(Partial)) == hipSuccess
+           && hipMalloc(&c->part1, (size_t)cfg->max_batch * kMaxSampleSplit * 2 * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->part2, (size_t)cfg->max_batch * kMaxSampleSplit * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->jobs, (size_t)cfg->max_batch * sizeof(SampleJob)) == hipSuccess
+           && hipMalloc(&c->flags_ws, (size_t)cfg->max_batch * sizeof(uint32_t)) == hipSuccess
+           && hipMalloc(&c->sum_r, nstate * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->count, nstate * sizeof(int64_t)) == hipSuccess
+           && hipMemset(c->sum_r, 0, nstate * sizeof(double)) == hipSuccess
+           && hipMemset(c->count, 0, nstate * sizeof(int64_t)) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        tapout_destroy(c);
+        return fail(nullptr, TAPOUT_ENOMEM, "device allocation failed");
+    }
+    *out = c;
+    return TAPOUT_OK;
+}
+
+tapout_status tapout_destroy(tapout_ctx *ctx)
+{
+    if (!ctx) return TAPOUT_OK;
+    DeviceGuard guard(ctx->cfg.device);
+    (void)hipFree(ctx->part); (void)hipFree(ctx->part1); (void)hipFree(ctx->part2);
+    (void)hipFree(ctx->jobs); (void)hipFree(ctx->flags_ws);
+    (void)hipFree(ctx->sum_r); (void)hipFree(ctx->count);
+    delete ctx;
+    return TAPOUT_OK;
+}
+
+const char *tapout_last_error(const tapout_ctx *ctx) { return ctx ? ctx->err : g_create_err; }
+
+tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value)
+{
+    if (!ctx || !name) return TAPOUT_EINVAL;
+    if (!strcmp(name, "wgs_target")) {
+        if (value < 1 || value > kMaxWgsTarget) return fail(ctx, TAPOUT_EINVAL, "wgs_target outside [1, %d]", kMaxWgsTarget);
+        ctx->wgs_target = value;
+    } else if (!strcmp(name, "min_slice")) {
+        if (value < 256) return fail(ctx, TAPOUT_EINVAL, "min_slice below 256 elements");
+        ctx->min_slice = value;
+    } else if (!strcmp(name, "sample_wgs")) {
+        if (value < 1 || value > kMaxWgsTarget) return fail(ctx, TAPOUT_EINVAL, "sample_wgs outside [1, %d]", kMaxWgsTarget);
+        ctx->sample_wgs = value;
+    } else return fail(ctx, TAPOUT_EINVAL, "unknown option '%s'", name);
+    return TAPOUT_OK;
+}
+
+tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const float *u_ts,
+                                   int32_t *arm_out, uint32_t *flags, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (!arm_out) return fail(ctx, TAPOUT_EINVAL, "arm_out is NULL");
+    if (ctx->cfg.policy == TAPOUT_TS_BETA && !u_ts) return fail(ctx, TAPOUT_EINVAL, "Thompson Sampling needs u_ts");
+    if (B == 0) return TAPOUT_OK;
+    DeviceGuard guard(ctx->cfg.device);
+    BanditArgs a{ctx->cfg.policy, ctx->cfg.n_bandits, ctx->cfg.n_arms, B, ctx->cfg.alpha, ctx->sum_r, ctx->count};
+    hipError_t e = launch_bandit_select(a, u_ts, arm_out, flags, (hipStream_t)stream);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_select launch");
+}
+
+tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *arm,
+                                   const int32_t *accept_len, const int32_t *n_draft,
+                                   const int32_t *gamma, const uint8_t *active, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (!arm || !accept_len || !n_draft || !gamma) return fail(ctx, TAPOUT_EINVAL, "arm, accept_len, n_draft and gamma are required");
+    if (B == 0) return TAPOUT_OK;
+    DeviceGuard guard(ctx->cfg.device);
+    BanditArgs a{ctx->cfg.policy, ctx->cfg.n_bandits, ctx->cfg.n_arms, B, ctx->cfg.alpha, ctx->sum_r, ctx->count};
+    hipError_t e = launch_bandit_update(a, arm, accept_len, n_draft, gamma, active, (hipStream_t)stream);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_update launch");
+}
+
+tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
+                                 int32_t B, int32_t K, int32_t V,
+                                 const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
+                                 int32_t *top1_id, float *logq_tok,
+                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    tapout_status s = check_shape(ctx, B, K, V);
+    if (s != TAPOUT_OK) return s;
+    if (B == 0) return TAPOUT_OK;
+    char buf[128];
+    if (const char *m = check_logits(draft, "draft", V, K, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
+    if (arm && !n_stop && !stop_fired) return fail(ctx, TAPOUT_EINVAL, "arm given but neither n_stop nor stop_fired");
+    DeviceGuard guard(ctx->cfg.device);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t rows = (int64_t)B * K;
+    const int nsplit = choose_nsplit(ctx, rows, V);
+    if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
+
+    RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, (int32_t)rows, k_len, 0, ctx->part};
+    hipError_t e = launch_row_reduce(r, draft->dtype, true, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "draft row_reduce launch");
+
+    DraftFinalArgs f{};
+    f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
+    f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = ctx->part;
+    f.draft_tok = draft_tok; f.k_len = k_len; f.arm = arm;
+    f.n_arms = ctx->cfg.n_arms;
+    for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) { f.rule[a] = ctx->cfg.rule[a]; f.threshold[a] = ctx->cfg.threshold[a]; }
+    f.lse = lse; f.entropy = entropy; f.p_top1 = p_top1; f.p_top2 = p_top2; f.margin = margin; f.logq_tok = logq_tok;
+    f.top1_id = top1_id; f.n_stop = n_stop; f.stop_fired = stop_fired; f.flags = flags;
+    e = launch_draft_finalize(f, st);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft_finalize launch");
+}
+
+tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const tapout_logits *draft,
+                            int32_t B, int32_t K, int32_t V,
+                            const float *draft_lse, const float *logq_tok,
+                            const int32_t *draft_tok, const int32_t *n_draft, const uint8_t *greedy,
+                            const float *u_accept, const float *u_sample,
+                            int32_t *accept_len, int32_t *out_tok, int32_t *n_out,
+                            float *target_lse, float *logp_tok, int32_t *target_top1,
+                            uint32_t *flags, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    tapout_status s = check_shape(ctx, B, K, V);
+    if (s != TAPOUT_OK) return s;
+    if (B == 0) return TAPOUT_OK;
+    char buf[128];
+    if (const char *m = check_logits(target, "target", V, K + 1, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
+    if (const char *m = check_logits(draft, "draft", V, K, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
+    if (!draft_lse || !logq_tok || !draft_tok || !n_draft || !u_accept || !u_sample)
+        return fail(ctx, TAPOUT_EINVAL, "draft_lse, logq_tok, draft_tok, n_draft, u_accept and u_sample are required");
+    if (!accept_len || !out_tok || !n_out) return fail(ctx, TAPOUT_EINVAL, "accept_len, out_tok and n_out are required");
+    DeviceGuard guard(ctx->cfg.device);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t rows = (int64_t)B * (K + 1);
+    const int nsplit = choose_nsplit(ctx, rows, V);
+    if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
+
+    RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, (int32_t)rows, n_draft, 1, ctx->part};
+    hipError_t e = launch_row_reduce(r, target->dtype, false, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "target row_reduce launch");
+
+    VerifyFinalArgs f{};
+    f.tbase = target->ptr; f.t_dtype = target->dtype; f.t_stride_b = target->stride_b; f.t_stride_k = target->stride_k;
+    f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = ctx->part;
+    f.draft_lse = draft_lse; f.logq_tok = logq_tok; f.draft_tok = draft_tok; f.n_draft = n_draft; f.greedy = greedy;
+    f.u_accept = u_accept;
+    f.accept_len = accept_len; f.out_tok = out_tok; f.n_out = n_out;
+    f.target_lse = target_lse; f.logp_tok = logp_tok; f.target_top1 = target_top1; f.flags = flags;
+    f.flags_ws = ctx->flags_ws; f.jobs = ctx->jobs;
+    e = launch_verify_finalize(f, st);
+    if (e != hipSuccess) return hip_fail(ctx, e, "verify_finalize launch");
+
+    SampleArgs sa{};
+    sa.tbase = target->ptr; sa.t_dtype = target->dtype; sa.t_stride_b = target->stride_b; sa.t_stride_k = target->stride_k;
+    sa.dbase = draft->ptr; sa.d_dtype = draft->dtype; sa.d_stride_b = draft->stride_b; sa.d_stride_k = draft->stride_k;
+    sa.B = B; sa.K = K; sa.V = V; sa.nsplit = choose_sample_nsplit(ctx, B, V);
+    sa.jobs = ctx->jobs; sa.u_sample = u_sample; sa.part1 = ctx->part1; sa.part2 = ctx->part2;
+    sa.out_tok = out_tok; sa.flags = flags; sa.flags_ws = ctx->flags_ws;
+    e = launch_sample(sa, st);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "sample launch");
+}
+
+tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, int64_t *count, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (!sum_r || !count) return fail(ctx, TAPOUT_EINVAL, "sum_r and count are required");
+    DeviceGuard guard(ctx->cfg.device);
+    const size_t n = (size_t)ctx->cfg.n_bandits * ctx->cfg.n_arms;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(sum_r, ctx->sum_r, n * sizeof(double), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(count, ctx->count, n * sizeof(int64_t), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_get_state");
+}
+
+tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *sum_r, const int64_t *count, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (!sum_r || !count) return fail(ctx, TAPOUT_EINVAL, "sum_r and count are required");
+    const size_t n = (size_t)ctx->cfg.n_bandits * ctx->cfg.n_arms;
+    for (size_t i = 0; i < n; ++i)
+        if (count[i] < 0 || !(sum_r[i] >= 0.0) || sum_r[i] > (double)count[i])
+            return fail(ctx, TAPOUT_EINVAL, "state entry %zu: need count >= 0 and 0 <= sum_r <= count", i);
+    DeviceGuard guard(ctx->cfg.device);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipMemcpyAsync(ctx->sum_r, sum_r, n * sizeof(double), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(ctx->count, count, n * sizeof(int64_t), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_set_state");
+}
+
+}  // extern "C"

@@ -1,0 +1,219 @@
+// Internal declarations shared by the translation units of libtapout (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tapout.h"
+
+namespace tapout {
+
+constexpr int kBlock = 256;          // threads per workgroup of the streaming kernels (4 wavefronts)
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.44269504088896340736f;   // binary32 nearest to log2(e); also used (widened) by the finalisers
+constexpr double kLn2 = 0.693147180559945309417232121458;
+
+// Partial statistics of one (row, split) slice, written by row_reduce and
+// merged by the finalisers.  Sums are kept in the base-2 domain relative to an
+// integer reference R = ceil(v1 * log2 e):  S = sum 2^(x*log2e - R),
+// T = sum 2^(x*log2e - R) * (x*log2e - R).  Changing the reference by an
+// integer is an exact power-of-two scaling, so merging loses nothing.
+struct Partial {
+    float v1;        // slice maximum (NaN entries ignored), -inf for an empty slice
+    float S;
+    float T;         // draft rows only
+    float v2;        // second largest value of the slice counting duplicates (draft rows only)
+    int32_t cand;    // element index at which an 8- (bf16) / 4- (f32) element window holding the first maximum starts
+    int32_t pad[3];
+};
+static_assert(sizeof(Partial) == 32, "Partial is one 32-byte record");
+
+// Final-token job of one sequence, produced by the verify finaliser and
+// consumed by the residual sampler.
+struct SampleJob {
+    int32_t kind;    // 0: nothing to sample (greedy / flagged: token already written), 1: residual max(0,p-q), 2: target row only
+    int32_t row;     // m: target row (and draft row for kind 1) to sample from
+    float ref_p;     // exponent reference of the target row (its maximum)
+    float ref_q;     // exponent reference of the draft row (its lse)
+};
+
+__host__ __device__ inline float ref_of_max(float v1)
+{
+    // integer-valued reference >= v1*log2e; 0 for a slice without finite maximum
+    return (v1 == -INFINITY) ? 0.0f : ceilf(v1 * kLog2e);
+}
+
+struct RowReduceArgs {
+    const void *base;
+    int64_t stride_b, stride_k;   // elements
+    int32_t V;
+    int32_t KK;                   // rows per sequence in this tensor (K for draft, K+1 for target)
+    int32_t nsplit;               // workgroups per row
+    int32_t n_rows;               // B * KK
+    const int32_t *len;           // draft: k_len (or NULL); target: n_draft
+    int32_t len_mode;             // 0: row k active iff k < len[b] (NULL: all); 1: iff k <= clamp(len[b], 1, KK-1)
+    Partial *out;                 // [n_rows, nsplit]
+};
+
+struct Ctx;
+
+// launchers (each returns hipGetLastError() after enqueueing)
+hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st);
+
+struct DraftFinalArgs {
+    const void *base; int32_t dtype; int64_t stride_b, stride_k;
+    int32_t B, K, V, nsplit;
+    const Partial *part;
+    const int32_t *draft_tok, *k_len, *arm;
+    int32_t n_arms; int32_t rule[TAPOUT_MAX_ARMS]; float threshold[TAPOUT_MAX_ARMS];
+    float *lse, *entropy, *p_top1, *p_top2, *margin, *logq_tok;
+    int32_t *top1_id, *n_stop; uint8_t *stop_fired; uint32_t *flags;
+};
+hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st);
+
+struct VerifyFinalArgs {
+    const void *tbase; int32_t t_dtype; int64_t t_stride_b, t_stride_k;
+    int32_t B, K, V, nsplit;
+    const Partial *part;
+    const float *draft_lse, *logq_tok; const int32_t *draft_tok, *n_draft; const uint8_t *greedy;
+    const float *u_accept;
+    int32_t *accept_len, *out_tok, *n_out;
+    float *target_lse, *logp_tok; int32_t *target_top1; uint32_t *flags;
+    uint32_t *flags_ws;           // internal copy of the flags (always present)
+    SampleJob *jobs;
+};
+hipError_t launch_verify_finalize(const VerifyFinalArgs &a, hipStream_t st);
+
+struct SampleArgs {
+    const void *tbase; int32_t t_dtype; int64_t t_stride_b, t_stride_k;
+    const void *dbase; int32_t d_dtype; int64_t d_stride_b, d_stride_k;
+    int32_t B, K, V, nsplit;
+    const SampleJob *jobs;
+    const float *u_sample;
+    double *part1;                // [B, nsplit, 2]  sum e_p, sum e_q of each slice
+    double *part2;                // [B, nsplit]     weight of each slice
+    int32_t *out_tok;             // [B, K+1]
+    uint32_t *flags, *flags_ws;
+};
+hipError_t launch_sample(const SampleArgs &a, hipStream_t st);
+
+struct BanditArgs {
+    int32_t policy, n_bandits, n_arms, B;
+    double alpha;
+    double *sum_r; int64_t *count;
+};
+hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st);
+hipError_t launch_bandit_update(const BanditArgs &a, const int32_t *arm, const int32_t *accept_len,
+                                const int32_t *n_draft, const int32_t *gamma, const uint8_t *active, hipStream_t st);
+
+// ---- device helpers --------------------------------------------------------
+#ifdef __HIPCC__
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT> struct Elem;
+template <> struct Elem<TAPOUT_F32>  { static constexpr int size = 4, vec = 4; };
+template <> struct Elem<TAPOUT_BF16> { static constexpr int size = 2, vec = 8; };
+
+__device__ inline float bf16_to_float(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+template <int DT>
+__device__ inline float load_elem(const void *row, int64_t j)
+{
+    if constexpr (DT == TAPOUT_F32) return ((const float *)row)[j];
+    else return bf16_to_float(((const uint16_t *)row)[j]);
+}
+
+__device__ inline float load_elem_rt(const void *row, int dtype, int64_t j)
+{
+    return dtype == TAPOUT_F32 ? ((const float *)row)[j] : bf16_to_float(((const uint16_t *)row)[j]);
+}
+
+// Split a row into an unaligned head, 16-byte vectors and a tail.
+template <int DT>
+__device__ inline void row_geometry(const void *row, int32_t V, int &head, int &nvec, int &tail)
+{
+    constexpr int VEC = Elem<DT>::vec;
+    int mis = (int)(((uintptr_t)row & 15u) / Elem<DT>::size);
+    head = (VEC - mis) % VEC;
+    if (head > V) head = V;
+    nvec = (V - head) / VEC;
+    tail = V - head - nvec * VEC;
+}
+
+template <int DT>
+__device__ inline void unpack(const u32x4 &w, float (&x)[Elem<DT>::vec])
+{
+    if constexpr (DT == TAPOUT_F32) {
+        x[0] = __uint_as_float(w.x); x[1] = __uint_as_float(w.y);
+        x[2] = __uint_as_float(w.z); x[3] = __uint_as_float(w.w);
+    } else {
+        x[0] = __uint_as_float(w.x << 16); x[1] = __uint_as_float(w.x & 0xffff0000u);
+        x[2] = __uint_as_float(w.y << 16); x[3] = __uint_as_float(w.y & 0xffff0000u);
+        x[4] = __uint_as_float(w.z << 16); x[5] = __uint_as_float(w.z & 0xffff0000u);
+        x[6] = __uint_as_float(w.w << 16); x[7] = __uint_as_float(w.w & 0xffff0000u);
+    }
+}
+
+__device__ inline const void *row_address(const void *base, int dtype, int64_t stride_b, int64_t stride_k, int b, int k)
+{
+    int64_t off = (int64_t)b * stride_b + (int64_t)k * stride_k;
+    return (const char *)base + off * (dtype == TAPOUT_F32 ? 4 : 2);
+}
+
+// Merged statistics of all slices of one row, in double.
+struct RowTotal {
+    float M;          // row maximum
+    double R;         // integer reference of M
+    double S, T;      // base-2 sums relative to R
+    float v2;
+    int32_t cand;
+    bool bad;
+};
+
+__device__ inline RowTotal merge_partials(const Partial *p, int nsplit)
+{
+    RowTotal r;
+    float M = -INFINITY;
+    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[s].v1);
+    r.M = M;
+    r.R = (double)ref_of_max(M);
+    double S = 0.0, T = 0.0;
+    float v2 = -INFINITY;
+    int32_t cand = 0x7fffffff;
+    bool seen_max = false;
+    for (int s = 0; s < nsplit; ++s) {
+        float v1 = p[s].v1;
+        if (v1 == -INFINITY && !(p[s].S != p[s].S)) continue;    // empty slice (a NaN sum still has to poison the row)
+        double d = r.R - (double)ref_of_max(v1);                  // >= 0, integer
+        double sc = exp2(-d);
+        double Si = (double)p[s].S, Ti = (double)p[s].T;
+        S += Si * sc;
+        T += (Ti - d * Si) * sc;
+        // second largest of the union, duplicates counted
+        if (v1 == M) {
+            if (seen_max) v2 = M; else seen_max = true;
+            if (p[s].cand < cand) cand = p[s].cand;
+        } else {
+            v2 = fmaxf(v2, v1);
+        }
+        v2 = fmaxf(v2, p[s].v2);
+    }
+    r.S = S; r.T = T; r.v2 = v2; r.cand = cand;
+    r.bad = !(S > 0.0) || !(S < INFINITY) || M == -INFINITY || M == INFINITY;
+    return r;
+}
+
+// First index j in [cand, cand + window) with x_j == M (the lowest argmax index of the row).
+__device__ inline int32_t resolve_argmax(const void *row, int dtype, int32_t V, int32_t cand, float M)
+{
+    int window = dtype == TAPOUT_F32 ? 4 : 8;
+    if (cand < 0 || cand >= V) return 0;
+    for (int i = 0; i < window && cand + i < V; ++i)
+        if (load_elem_rt(row, dtype, cand + i) == M) return cand + i;
+    return cand;
+}
+
+#endif  // __HIPCC__
+
+}  // namespace tapout

@@ -1,0 +1,323 @@
+"""GPU parity: libtapout (through its C ABI) against the CPU oracle, element by
+element, on the same seeded inputs.  Tolerances are defined in parity_util."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle as orc
+from paper_2511_02017_amd import binding, synth
+from tests import parity_util as pu
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def announce(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def make(w, rounds=(0,), **kw):
+    gen = synth.RoundGenerator(w, DEV)
+    tp = binding.Tapout(w.B, w.K, w.V, **kw)
+    return gen, tp, [gen.round(r) for r in rounds]
+
+
+def random_arms(B, seed=0):
+    g = torch.Generator().manual_seed(seed)
+    return torch.randint(0, 3, (B,), generator=g, dtype=torch.int32).to(DEV)
+
+
+# ---- the five workloads, at sizes the oracle finishes in seconds ---------------
+
+@pytest.mark.parametrize("name,kw", [
+    ("tiny", {}),
+    ("small", {}),
+    ("llama3", dict(B=16)),
+    ("zipf", dict(B=12)),
+    ("ragged", dict(B=12)),
+])
+def test_workload_parity_full_k(name, kw):
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    announce(f"full-K {w}")
+    gen, tp, rounds = make(w, rounds=(0, 1))
+    total = dict(stop_flagged=0, accept_flagged=0, icdf_flagged=0, sequences=0)
+    for rnd in rounds:
+        c = pu.check_round(tp, rnd)
+        for k in total:
+            total[k] += c[k]
+    announce(f"{name}: near-tie counts {total}")
+    assert total["accept_flagged"] + total["icdf_flagged"] <= max(2, total["sequences"] // 50)
+
+
+@pytest.mark.parametrize("name,kw", [("tiny", {}), ("small", {}), ("llama3", dict(B=16)), ("ragged", dict(B=8))])
+def test_workload_parity_truncated(name, kw):
+    """Algorithm 1 as written: n_draft = stop position of the selected arm."""
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    announce(f"truncate {w}")
+    gen, tp, rounds = make(w, rounds=(2,))
+    arm = random_arms(w.B, seed=w.index)
+    c = pu.check_round(tp, rounds[0], arm=arm)
+    announce(f"{name}: near-tie counts {c}")
+
+
+def test_peaked_rows_separate_the_rules():
+    # low-entropy rows: the three rules give different stop positions, none of them trivial
+    w = synth.scaled(synth.WORKLOADS["llama3"], B=24, V=32000, sigma_draft=4.5)
+    gen, tp, rounds = make(w, rounds=(0,))
+    seen = set()
+    for a in range(3):
+        arm = torch.full((w.B,), a, dtype=torch.int32, device=DEV)
+        pu.check_round(tp, rounds[0], arm=arm)
+        ds = tp.draft_stats(rounds[0]["draft"], draft_tok=rounds[0]["draft_tok"], arm=arm)
+        seen.add(tuple(ds["n_stop"].cpu().tolist()))
+    assert len(seen) == 3
+
+
+# ---- shapes: tails, misalignment, strides, tiny vocabularies --------------------
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [1, 2, 3, 7, 8, 9, 63, 1000, 4097, 12345, 32001])
+def test_odd_vocab_sizes_and_misaligned_rows(V, dtype):
+    announce(f"odd V={V} {dtype}")
+    B, K = 3, 4
+    g = torch.Generator(device=DEV).manual_seed(V)
+    # rows carved out of a wider buffer at an odd offset: every row start is misaligned differently
+    wide_d = (torch.randn(B, K, V + 13, generator=g, device=DEV) * 3).to(dtype)
+    wide_t = (torch.randn(B, K + 1, V + 13, generator=g, device=DEV) * 3).to(dtype)
+    draft, target = wide_d[:, :, 5:5 + V], wide_t[:, :, 3:3 + V]
+    tok = torch.randint(0, V, (B, K), generator=g, device=DEV, dtype=torch.int32)
+    rnd = dict(draft=draft, target=target, draft_tok=tok,
+               u_accept=torch.rand(B, K, generator=g, device=DEV), u_sample=torch.rand(B, generator=g, device=DEV),
+               k_len=torch.full((B,), K, dtype=torch.int32, device=DEV), greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
+    tp = binding.Tapout(B, K, V)
+    pu.check_round(tp, rnd)
+    pu.check_round(tp, rnd, arm=random_arms(B))
+
+
+def test_slice_counts_do_not_change_decisions():
+    w = synth.scaled(synth.WORKLOADS["small"], B=6)
+    gen, tp, rounds = make(w)
+    ref = None
+    for wgs, min_slice in ((1, 4096), (64, 256), (4096, 256), (65536, 256), (4096, 1 << 20)):
+        tp.set_option("wgs_target", wgs)
+        tp.set_option("min_slice", min_slice)
+        tp.set_option("sample_wgs", max(1, wgs // 2))
+        pu.check_round(tp, rounds[0])
+        ds, vf, _ = pu.gpu_round(tp, rounds[0])
+        ints = (ds["top1_id"].cpu(), vf["accept_len"].cpu(), vf["out_tok"].cpu())
+        if ref is not None:
+            assert all(torch.equal(a, b) for a, b in zip(ints, ref))
+        ref = ints
+
+
+def test_bit_identical_reruns():
+    w = synth.scaled(synth.WORKLOADS["llama3"], B=8)
+    gen, tp, rounds = make(w)
+    a = pu.gpu_round(tp, rounds[0], arm=random_arms(w.B))
+    b = pu.gpu_round(tp, rounds[0], arm=random_arms(w.B))
+    for x, y in ((a[0], b[0]), (a[1], b[1])):
+        for k in x:
+            assert torch.equal(x[k].cpu().view(torch.int32) if x[k].dtype == torch.float32 else x[k].cpu(),
+                               y[k].cpu().view(torch.int32) if y[k].dtype == torch.float32 else y[k].cpu()), k
+
+
+# ---- degenerate rows --------------------------------------------------------------
+
+def degenerate_round(dtype):
+    B, K, V = 8, 3, 5000
+    g = torch.Generator(device=DEV).manual_seed(77)
+    d = (torch.randn(B, K, V, generator=g, device=DEV) * 2).to(dtype)
+    t = (torch.randn(B, K + 1, V, generator=g, device=DEV) * 2).to(dtype)
+    d[0] = 0.5                                   # uniform rows: H = ln V, every rule fires at once
+    t[0] = 0.5
+    d[1, :, 100:] = float("-inf")                # masked vocabulary
+    t[1, :, 50:] = float("-inf")
+    d[2, :, 7] = 40.0                            # one-hot-like rows: H ~ 0, p_top1 ~ 1
+    t[2, :, 7] = 40.0
+    d[3, :, 11] = 9.0; d[3, :, 4000] = 9.0       # exact tie at the top: margin 0, lowest index wins
+    t[4] = d.new_tensor(0.0).expand(K + 1, V)    # flat target against a random draft
+    t[5, :K] = d[5]                              # p == q: everything accepted, bonus from row K
+    d[6, :, :] = -1e4; d[6, :, V - 1] = 0.0      # maximum at the last element
+    t[6, :, :] = -1e4; t[6, :, 0] = 0.0
+    tok = torch.randint(0, V, (B, K), generator=g, device=DEV, dtype=torch.int32)
+    tok[1] = torch.randint(0, 50, (K,), generator=g, device=DEV, dtype=torch.int32)
+    tok[2] = 7
+    tok[6] = V - 1
+    return dict(draft=d, target=t, draft_tok=tok,
+                u_accept=torch.rand(B, K, generator=g, device=DEV), u_sample=torch.rand(B, generator=g, device=DEV),
+                k_len=torch.full((B,), K, dtype=torch.int32, device=DEV),
+                greedy=torch.tensor([0, 0, 0, 0, 0, 0, 0, 1], dtype=torch.uint8, device=DEV))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_degenerate_rows(dtype):
+    rnd = degenerate_round(dtype)
+    B, K, V = rnd["draft"].shape
+    tp = binding.Tapout(B, K, V)
+    pu.check_round(tp, rnd)
+    for a in range(3):
+        pu.check_round(tp, rnd, arm=torch.full((B,), a, dtype=torch.int32, device=DEV))
+    ds, vf, _ = pu.gpu_round(tp, rnd)
+    assert float(ds["margin"][3, 0]) == 0.0 and int(ds["top1_id"][3, 0]) == 11
+    assert int(vf["accept_len"][5]) == K
+    assert abs(float(ds["entropy"][0, 0]) - np.log(V)) < 1e-4
+    assert not ds["flags"].any() and not vf["flags"].any()
+
+
+def test_bad_inputs_set_flags_and_fall_back():
+    rnd = degenerate_round(torch.float32)
+    B, K, V = rnd["draft"].shape
+    rnd["draft"][0, 1, 17] = float("nan")        # NaN in a draft row
+    rnd["target"][1, 0, 3] = float("nan")        # NaN in a target row
+    rnd["target"][2, 2, :] = float("-inf")       # target row without finite maximum
+    rnd["draft_tok"][3, 0] = V                   # token out of range
+    rnd["draft_tok"][4, 2] = -1
+    n_draft = torch.full((B,), K, dtype=torch.int32, device=DEV)
+    n_draft[5] = 0
+    n_draft[6] = K + 1
+    tp = binding.Tapout(B, K, V)
+    gds = tp.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"])
+    gvf = tp.verify(rnd["target"], rnd["draft"], gds["lse"], gds["logq_tok"], rnd["draft_tok"], n_draft,
+                    rnd["u_accept"], rnd["u_sample"], greedy=rnd["greedy"])
+    torch.cuda.synchronize()
+    ods, ovf, _ = pu.oracle_round(rnd, n_draft=n_draft)
+    assert gds["flags"].cpu().numpy().astype(np.uint32).tolist() == ods["flags"].tolist()
+    assert ods["flags"].tolist()[:5] == [orc.FLAG_BAD_ROW, 0, 0, orc.FLAG_BAD_TOKEN, orc.FLAG_BAD_TOKEN]
+    assert gvf["flags"].cpu().numpy().astype(np.uint32).tolist() == ovf["flags"].tolist()
+    assert ovf["flags"].tolist()[1:7] == [orc.FLAG_BAD_ROW, orc.FLAG_BAD_ROW, orc.FLAG_BAD_TOKEN, orc.FLAG_BAD_TOKEN,
+                                          orc.FLAG_BAD_NDRAFT, orc.FLAG_BAD_NDRAFT]
+    assert gvf["accept_len"].cpu().tolist() == ovf["accept_len"].tolist()
+    assert gvf["out_tok"].cpu().tolist() == ovf["out_tok"].tolist()
+    assert gvf["n_out"].cpu().tolist() == ovf["n_out"].tolist()
+    assert np.isnan(gds["entropy"][0, 1].item()) and np.isnan(gds["logq_tok"][3, 0].item())
+
+
+# ---- full benchmark shapes: sampled sequences, launch configuration of bench.py ----
+
+@pytest.mark.parametrize("name,n_seq", [("llama3", 12), ("zipf", 6), ("ragged", 4)])
+def test_full_size_sampled_sequences(name, n_seq):
+    w = synth.WORKLOADS[name]
+    announce(f"full size {w}")
+    gen, tp, rounds = make(w, rounds=(3,))
+    rnd = rounds[0]
+    g = torch.Generator().manual_seed(w.index)
+    seqs = torch.randperm(w.B, generator=g)[:n_seq].sort().values.tolist()
+    c = pu.check_round(tp, rnd, seqs=seqs)
+    announce(f"{name} full size, sequences {seqs}: near-tie counts {c}")
+    # properties that hold for every sequence at any size
+    ds, vf, nd = pu.gpu_round(tp, rnd)
+    m, n_out, out = vf["accept_len"].cpu(), vf["n_out"].cpu(), vf["out_tok"].cpu()
+    k_len, tok = rnd["k_len"].cpu(), rnd["draft_tok"].cpu()
+    assert ((0 <= m) & (m <= k_len)).all() and (n_out == m + 1).all()
+    pos = torch.arange(w.K + 1)[None]
+    assert (out[pos > m[:, None]] == -1).all()
+    assert ((out >= 0) & (out < w.V))[pos <= m[:, None]].all()
+    assert (out[:, :w.K][pos[:, :w.K] < m[:, None]] == tok[pos[:, :w.K] < m[:, None]]).all()
+    live = pos[:, :w.K] < k_len[:, None]
+    H, p1, p2, mg = (ds[k].cpu() for k in ("entropy", "p_top1", "p_top2", "margin"))
+    assert (H[live] >= 0).all() and (H[live] <= np.log(w.V) + 1e-4).all()
+    assert (p1[live] >= p2[live]).all() and (p1[live] <= 1.0).all() and (mg[live] >= 0).all()
+    assert (p1[live] >= torch.exp(-H[live]) * (1 - 1e-5)).all()          # H >= -ln p_max
+    # the accept decisions are a function of the returned log-probabilities and the uniforms
+    lp, lq, ua = vf["logp_tok"].cpu().double(), ds["logq_tok"].cpu().double(), rnd["u_accept"].cpu().double()
+    acc = ua < torch.exp(lp - lq)
+    greedy = rnd["greedy"].cpu().bool()
+    acc = torch.where(greedy[:, None], tok.long() == vf["target_top1"].cpu()[:, :w.K].long(), acc) & live
+    first_rej = torch.where(acc, torch.full_like(pos[:, :w.K], w.K + 1), pos[:, :w.K]).min(1).values
+    assert (torch.minimum(first_rej, k_len.long()) == m).all()
+
+
+# ---- bandit -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("policy", [binding.UCB1, binding.TS_BETA])
+@pytest.mark.parametrize("shared", [False, True])
+def test_bandit_trajectory_matches_oracle(policy, shared):
+    B, K, A, rounds = 37, 8, 3, 300
+    tp = binding.Tapout(B, K, 1000, policy=policy, shared_bandit=shared)
+    ob = orc.Bandit(policy, 1 if shared else B, A)
+    g = torch.Generator().manual_seed(5)
+    for r in range(rounds):
+        u = torch.rand(B, A, 48, generator=g)
+        if r % 50 == 7:
+            u[:, :, ::3] = 0.0                                           # zero uniforms hit the 2^-25 substitution
+        arm = tp.bandit_select(B, u_ts=u.to(DEV) if policy == binding.TS_BETA else None)
+        o_arm, _ = ob.select(B, u.numpy())
+        assert arm.cpu().tolist() == o_arm.tolist(), f"round {r}"
+        gamma = torch.randint(1, K + 1, (B,), generator=g, dtype=torch.int32)
+        n = (torch.rand(B, generator=g) * gamma).floor().to(torch.int32) + 1
+        m = (torch.rand(B, generator=g) * (n + 1) * (0.4 + 0.2 * arm.cpu())).floor().clamp(max=n).to(torch.int32)
+        active = (torch.rand(B, generator=g) < 0.9).to(torch.uint8)
+        tp.bandit_update(arm, m.to(DEV), n.to(DEV), gamma.to(DEV), active=active.to(DEV))
+        ob.update(o_arm, m.numpy(), n.numpy(), gamma.numpy(), active=active.numpy())
+    s, c = tp.bandit_get_state()
+    assert (c == ob.count).all()
+    assert (s == ob.sum_r).all()                                         # same fp64 operations in the same order
+    # restore round trip
+    tp2 = binding.Tapout(B, K, 1000, policy=policy, shared_bandit=shared)
+    tp2.bandit_set_state(s, c)
+    u = torch.rand(B, A, 48, generator=g)
+    a1 = tp.bandit_select(B, u_ts=u.to(DEV) if policy == binding.TS_BETA else None)
+    a2 = tp2.bandit_select(B, u_ts=u.to(DEV) if policy == binding.TS_BETA else None)
+    assert torch.equal(a1, a2)
+
+
+@pytest.mark.parametrize("name", ["tiny", "small"])
+def test_closed_loop_rounds(name):
+    """Algorithm 1 end to end over many rounds: select -> draft_stats -> verify -> update, bandit in the loop."""
+    w = synth.WORKLOADS[name]
+    w = synth.scaled(w, sigma_draft=6.0) if name == "tiny" else synth.scaled(w, B=8, sigma_draft=7.0)
+    n_rounds = 24 if name == "tiny" else 10
+    policy = binding.UCB1
+    gen = synth.RoundGenerator(w, DEV)
+    tp = binding.Tapout(w.B, w.K, w.V, policy=policy)
+    ob = orc.Bandit(policy, w.B, 3)
+    flagged = 0
+    for r in range(n_rounds):
+        rnd = gen.round(r)
+        arm = tp.bandit_select(w.B)
+        o_arm, _ = ob.select(w.B)
+        assert arm.cpu().tolist() == o_arm.tolist(), f"round {r}"
+        gds, gvf, g_nd = pu.gpu_round(tp, rnd, arm=arm)
+        ods, ovf, o_nd = pu.oracle_round(rnd, arm=arm)
+        gvf = dict(gvf); gvf["n_draft_used"] = g_nd
+        c = pu.compare_round(gds, gvf, ods, ovf, rnd["k_len"].cpu().numpy(), o_nd)
+        flagged += c["stop_flagged"] + c["accept_flagged"]
+        tp.bandit_update(arm, gvf["accept_len"], g_nd, rnd["k_len"])
+        # the oracle's bandit follows the GPU's integer decisions so that a near-tie flip cannot cascade
+        ob.update(o_arm, gvf["accept_len"].cpu().numpy(), g_nd.cpu().numpy(), rnd["k_len"].cpu().numpy())
+    s, c = tp.bandit_get_state()
+    assert (c == ob.count).all() and (s == ob.sum_r).all()
+    assert flagged <= 2
+
+
+# ---- boundary error handling --------------------------------------------------------
+
+def test_argument_errors_leave_outputs_untouched():
+    B, K, V = 4, 3, 100
+    tp = binding.Tapout(B, K, V)
+    d = torch.zeros(B, K, V, device=DEV)
+    out = tp.alloc_draft_outputs(B, K)
+    before = {k: v.clone() for k, v in out.items()}
+    with pytest.raises(binding.TapoutError, match="EINVAL"):
+        tp.draft_stats(torch.zeros(B + 1, K, V, device=DEV))
+    with pytest.raises(binding.TapoutError, match="EINVAL"):
+        tp.draft_stats(torch.zeros(B, K + 1, V, device=DEV))
+    with pytest.raises(binding.TapoutError, match="EINVAL"):
+        tp.draft_stats(torch.zeros(B, K, V + 1, device=DEV))
+    with pytest.raises(ValueError):
+        tp.draft_stats(torch.zeros(B, K, V, device=DEV, dtype=torch.float16))
+    with pytest.raises(ValueError):
+        tp.draft_stats(torch.zeros(B, K, 2 * V, device=DEV)[:, :, ::2])
+    with pytest.raises(binding.TapoutError, match="required"):
+        tp.bandit_update(torch.zeros(B, dtype=torch.int32, device=DEV), None, None, None)
+    with pytest.raises(binding.TapoutError):
+        binding.Tapout(B, K, V, rules=(7,), thresholds=(0.1,))
+    with pytest.raises(binding.TapoutError):
+        binding.Tapout(0, K, V)
+    torch.cuda.synchronize()
+    for k in out:
+        a, b = out[k].cpu(), before[k].cpu()
+        assert torch.equal(torch.nan_to_num(a.float(), nan=-7.0), torch.nan_to_num(b.float(), nan=-7.0))
+    # B = 0 is a valid empty call
+    tp.draft_stats(d[:0])
+    tp.bandit_select(0)

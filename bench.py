@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the TapOut logits path on one MI355X.
+
+One "step" is one decode round of the whole hot path over one batch of
+synthetic logits already resident in HBM:
+    tapout_bandit_select -> tapout_draft_stats -> tapout_verify -> tapout_bandit_update
+The default workload is the Llama-3-vocabulary configuration (V = 128256,
+B = 64, K = 8, bfloat16) on which the headline metric (verified draft tokens/s
+at a 128k vocabulary) is quoted.  Inputs rotate through a ring of pre-generated
+rounds larger than the 256 MB Infinity Cache, so no step finds its logits cached.
+
+Prints ONE JSON line; see the design doc for the definition of every field.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--workload", default="llama3", choices=["tiny", "small", "llama3", "zipf", "ragged"])
+    ap.add_argument("--mode", default="full", choices=["full", "truncate"],
+                    help="full: verify all K drafted tokens (stop signals still computed); truncate: verify up to the stop position")
+    ap.add_argument("--ring", type=int, default=0, help="pre-generated rounds to rotate through (0: enough for > 1 GB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences of one round the oracle is timed on (0: auto)")
+    ap.add_argument("--profile-all", action="store_true", help="time every kernel with events (perturbs the step time slightly)")
+    ap.add_argument("--opt", action="append", default=[], help="library tuning option name=value")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path needs no exchange between GPUs; see DESIGN.md, "
+              "'How the path would shard'); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2511_02017_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    esz = {torch.float32: 4, torch.bfloat16: 2}
+    round_bytes = w.V * (w.B * w.K * esz[w.draft_dtype] + w.B * (w.K + 1) * esz[w.target_dtype])
+    ring_n = args.ring or max(2, min(8, -(-(1 << 30) // round_bytes)))
+    gen = synth.RoundGenerator(w, dev)
+    ring = [gen.round(r) for r in range(ring_n)]
+    policy = binding.UCB1 if w.policy == "ucb1" else binding.TS_BETA
+    tp = binding.Tapout(w.B, w.K, w.V, policy=policy)
+    for o in args.opt:
+        k, v = o.split("=")
+        tp.set_option(k, int(v))
+    truncate = args.mode == "truncate"
+    prepared = [tp.prepare_round(r, truncate, u_ts=r["u_ts"] if policy == binding.TS_BETA else None) for r in ring]
+    stream = torch.cuda.current_stream()
+    sh = stream.cuda_stream
+
+    def run(n, first=0):
+        for i in range(n):
+            prepared[(first + i) % ring_n][0](sh)
+
+    kinds = binding.PROFILE_KINDS if args.profile_all else ("draft_reduce", "target_reduce")
+    run(args.warmup)
+    torch.cuda.synchronize()
+    tp.profile_enable(kinds, args.steps)
+    for k in kinds:
+        tp.profile_read(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(args.steps, first=args.warmup)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = {k: tp.profile_read(k) for k in kinds}
+    tp.profile_enable((), 0)
+    elapsed = t1 - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # work actually done in the timed steps (integer outputs of the last pass over each ring slot)
+    n_draft_ring = [p[1]["n_draft"].cpu().long() for p in prepared]
+    k_len_ring = [r["k_len"].cpu().long() for r in ring]
+    acc_ring = [p[1]["verify"]["accept_len"].cpu().long() for p in prepared]
+    slots = [(args.warmup + i) % ring_n for i in range(args.steps)]
+    verified = sum(int(n_draft_ring[s].sum()) for s in slots)
+    emitted = sum(int(acc_ring[s].sum()) + w.B for s in slots)
+    draft_rows = sum(int(k_len_ring[s].sum()) for s in slots)
+    target_rows = sum(int(n_draft_ring[s].sum()) + w.B for s in slots)
+    ed, et = esz[w.draft_dtype], esz[w.target_dtype]
+    stream_bytes = w.V * (draft_rows * ed + target_rows * et)          # every logit of a live row once
+
+    def roof(kind, nbytes):
+        ms, n = prof[kind]
+        if n == 0:
+            return None
+        avg_us = ms / n * 1e3
+        gbs = nbytes / n / (avg_us * 1e-6) / 1e9
+        return dict(kernel=kind, bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(gbs / HBM_PEAK_GBS, 4), avg_us=round(avg_us, 2), launches=n,
+                    bytes_per_launch=nbytes // n, traffic=None)
+
+    r_target = roof("target_reduce", w.V * target_rows * et)
+    r_draft = roof("draft_reduce", w.V * draft_rows * ed)
+    both_ms = prof["target_reduce"][0] + prof["draft_reduce"][0]
+    out = {
+        "metric": "verified draft tokens/sec and achieved HBM GB/s (% of peak) at vocab 128k",
+        "value": round(verified / elapsed, 1),
+        "unit": "verified draft tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",                               # arithmetic type of the streaming path (fp64 in the final-token sampler and bandit)
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: V={w.V} B={w.B} K={w.K} draft={str(w.draft_dtype)[6:]} target={str(w.target_dtype)[6:]}",
+                   "mode": "full-K (n_draft = K)" if not truncate else "truncate (n_draft = stop position)",
+                   "policy": w.policy, "ring_rounds": ring_n, "ring_bytes": ring_n * round_bytes},
+        "emitted_tokens_per_s": round(emitted / elapsed, 1),
+        "rows_per_s": round((draft_rows + target_rows) / elapsed, 1),
+        "whole_round_GBps": round(stream_bytes / elapsed / 1e9, 1),
+        "whole_round_frac_of_hbm_peak": round(stream_bytes / elapsed / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": r_target,
+        "roofline_draft_reduce": r_draft,
+        "streaming_kernels_GBps": round(stream_bytes / (both_ms * 1e-3) / 1e9, 1) if both_ms else None,
+    }
+    if args.profile_all:
+        out["kernel_avg_us"] = {k: round(prof[k][0] / max(1, prof[k][1]) * 1e3, 2) for k in kinds}
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, ring[0], truncate, args.cpu_seqs)
+    print(json.dumps(out))
+
+
+def cpu_baseline(w, rnd, truncate, n_seq):
+    """The CPU oracle, as it stands, on a bounded sample of the same round (whole sequences), all host cores."""
+    import numpy as np
+    from oracle import oracle as orc
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
+    if n_seq <= 0:
+        # about 1e9 element visits keep the leg within roughly 10-30 s on 16 cores
+        per_seq = w.V * (2 * w.K + 1) * 3.5
+        n_seq = int(max(1, min(w.B, 1.2e9 // per_seq)))
+    seqs = list(range(n_seq))
+    draft = orc.as_logits(rnd["draft"][seqs].cpu())
+    target = orc.as_logits(rnd["target"][seqs].cpu())
+    tok = rnd["draft_tok"][seqs].cpu().numpy()
+    k_len = rnd["k_len"][seqs].cpu().numpy()
+    greedy = rnd["greedy"][seqs].cpu().numpy()
+    ua, us = rnd["u_accept"][seqs].cpu().numpy(), rnd["u_sample"][seqs].cpu().numpy()
+    bandit = orc.Bandit(orc.POLICY_UCB1 if w.policy == "ucb1" else orc.POLICY_TS_BETA, n_seq, w.n_arms)
+    u_ts = rnd["u_ts"][seqs].cpu().numpy()
+    t0 = time.perf_counter()
+    arm, _ = bandit.select(n_seq, u_ts)
+    ds = orc.draft_stats(draft, draft_tok=tok, k_len=k_len, arm=arm, nthreads=cores)
+    nd = ds["n_stop"] if truncate else k_len
+    vf = orc.verify(target, draft, ds["logq_tok"], tok, nd, ua, us, greedy=greedy, nthreads=cores)
+    bandit.update(arm, vf["accept_len"], nd, k_len)
+    dt = time.perf_counter() - t0
+    return {"value": round(float(np.sum(nd)) / dt, 1), "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{n_seq} of {w.B} sequences of one round ({int(np.sum(nd))} drafted tokens), {dt:.1f} s"}
+
+
+if __name__ == "__main__":
+    main()

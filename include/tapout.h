@@ -238,6 +238,31 @@ TAPOUT_API tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *
  */
 TAPOUT_API tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value);
 
+/*
+ * Kernel timing for benchmarks (host).  tapout_profile_enable makes the
+ * library bracket each launch of the selected kernels with a pair of HIP events
+ * on the caller's stream (kind_mask: bit k = kernel k below; at most
+ * max_records launches per kernel between two reads; 0 switches timing off and
+ * releases the events).  tapout_profile_read synchronises `stream`, returns the
+ * summed elapsed time and the number of launches recorded for one kernel since
+ * the last read, and rewinds that kernel's records.  No device memory is
+ * involved; timing is off by default.
+ */
+enum {
+    TAPOUT_PROFILE_SELECT = 0,          /* bandit select                                  */
+    TAPOUT_PROFILE_DRAFT_REDUCE = 1,    /* streaming pass over the draft logits           */
+    TAPOUT_PROFILE_DRAFT_FINALIZE = 2,  /* signals + stop scan                            */
+    TAPOUT_PROFILE_TARGET_REDUCE = 3,   /* streaming pass over the target logits          */
+    TAPOUT_PROFILE_VERIFY_FINALIZE = 4, /* accept tests + first rejection                 */
+    TAPOUT_PROFILE_SAMPLE_PASS1 = 5,    /* final token: normalisers                       */
+    TAPOUT_PROFILE_SAMPLE_PASS2 = 6,    /* final token: slice weights                     */
+    TAPOUT_PROFILE_SAMPLE_PASS3 = 7,    /* final token: locate                            */
+    TAPOUT_PROFILE_UPDATE = 8,          /* bandit update                                  */
+    TAPOUT_PROFILE_KINDS = 9
+};
+TAPOUT_API tapout_status tapout_profile_enable(tapout_ctx *ctx, uint32_t kind_mask, int32_t max_records);
+TAPOUT_API tapout_status tapout_profile_read(tapout_ctx *ctx, int32_t kind, double *total_ms, int32_t *launches, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,11 @@ STATUS = {0: "TAPOUT_OK", 1: "TAPOUT_EINVAL", 2: "TAPOUT_EUNSUPPORTED", 3: "TAPO
 
 EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_last_error",
            "tapout_bandit_select", "tapout_draft_stats", "tapout_verify", "tapout_bandit_update",
-           "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_set_option")
+           "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_set_option",
+           "tapout_profile_enable", "tapout_profile_read")
+
+PROFILE_KINDS = ("select", "draft_reduce", "draft_finalize", "target_reduce", "verify_finalize",
+                 "sample_pass1", "sample_pass2", "sample_pass3", "update")
 
 
 class TapoutConfig(C.Structure):
@@ -67,6 +71,8 @@ def load_library():
         lib.tapout_bandit_get_state.argtypes = [vp] * 4
         lib.tapout_bandit_set_state.argtypes = [vp] * 4
         lib.tapout_set_option.argtypes = [vp, C.c_char_p, i32]
+        lib.tapout_profile_enable.argtypes = [vp, C.c_uint32, i32]
+        lib.tapout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32), vp]
         _lib = lib
     return _lib
 
@@ -145,6 +151,54 @@ class Tapout:
 
     def set_option(self, name: str, value: int):
         self._check(self._lib.tapout_set_option(self._ctx, name.encode(), int(value)))
+
+    # -- kernel timing ---------------------------------------------------------
+    def profile_enable(self, kinds=(), max_records: int = 0):
+        mask = 0
+        for k in kinds:
+            mask |= 1 << PROFILE_KINDS.index(k)
+        self._check(self._lib.tapout_profile_enable(self._ctx, mask, int(max_records)))
+
+    def profile_read(self, kind: str, stream=None):
+        """(total milliseconds, launches) recorded for one kernel since the last read."""
+        ms, n = C.c_double(0), C.c_int32(0)
+        self._check(self._lib.tapout_profile_read(self._ctx, PROFILE_KINDS.index(kind), C.byref(ms), C.byref(n), _stream(stream)))
+        return ms.value, n.value
+
+    # -- one decode round with the arguments marshalled once ---------------------
+    def prepare_round(self, rnd: dict, truncate: bool, u_ts=None):
+        """Pre-marshals the four calls of one round (Algorithm 1) on fixed tensors and returns
+        (launch, outputs): launch(stream_handle) enqueues select -> draft_stats -> verify -> update.
+        truncate=True verifies the tokens up to the stop position, False all k_len drafted tokens."""
+        draft, target, tok = rnd["draft"], rnd["target"], rnd["draft_tok"]
+        B, K, V = draft.shape
+        f32, i32 = torch.float32, torch.int32
+        do, vo = self.alloc_draft_outputs(B, K), self.alloc_verify_outputs(B, K)
+        arm = torch.zeros(B, dtype=i32, device=self.device)
+        n_draft = do["n_stop"] if truncate else rnd["k_len"]
+        dl, tl = _logits(draft, "draft"), _logits(target, "target")
+        keep = (dl, tl, do, vo, arm, rnd, u_ts)
+        lib, ctx = self._lib, self._ctx
+        p = lambda t: C.c_void_p(t.data_ptr()) if t is not None else None
+        a_sel = (ctx, B, p(u_ts), p(arm), None)
+        a_ds = (ctx, C.byref(dl), B, K, V, p(tok), p(rnd["k_len"]), p(arm), p(do["lse"]), p(do["entropy"]),
+                p(do["p_top1"]), p(do["p_top2"]), p(do["margin"]), p(do["top1_id"]), p(do["logq_tok"]),
+                p(do["n_stop"]), p(do["stop_fired"]), p(do["flags"]))
+        a_vf = (ctx, C.byref(tl), C.byref(dl), B, K, V, p(do["lse"]), p(do["logq_tok"]), p(tok), p(n_draft),
+                p(rnd.get("greedy")), p(rnd["u_accept"]), p(rnd["u_sample"]), p(vo["accept_len"]), p(vo["out_tok"]),
+                p(vo["n_out"]), p(vo["target_lse"]), p(vo["logp_tok"]), p(vo["target_top1"]), p(vo["flags"]))
+        a_up = (ctx, B, p(arm), p(vo["accept_len"]), p(n_draft), p(rnd["k_len"]), None)
+
+        def launch(stream_handle):
+            st = lib.tapout_bandit_select(*a_sel, stream_handle)
+            st = st or lib.tapout_draft_stats(*a_ds, stream_handle)
+            st = st or lib.tapout_verify(*a_vf, stream_handle)
+            st = st or lib.tapout_bandit_update(*a_up, stream_handle)
+            if st:
+                self._check(st)
+
+        launch._keep = keep
+        return launch, dict(arm=arm, n_draft=n_draft, draft=do, verify=vo)
 
     # -- tapout_bandit_select ------------------------------------------------
     def bandit_select(self, B: int, u_ts=None, arm_out=None, flags=None, stream=None):

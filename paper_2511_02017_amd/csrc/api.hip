@@ -5,6 +5,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "common.h"
 
@@ -20,6 +21,11 @@ struct tapout_ctx {
     int wgs_target = 4096;        // workgroups a streaming launch aims for
     int min_slice = 4096;         // smallest slice (elements) a row is cut into
     int sample_wgs = 2048;        // workgroups the sampler passes aim for
+    // optional kernel timing (tapout_profile_*): event pairs around the launches of selected kernels
+    uint32_t prof_mask = 0;
+    int prof_cap = 0;
+    std::vector<hipEvent_t> prof_start[TAPOUT_PROFILE_KINDS], prof_stop[TAPOUT_PROFILE_KINDS];
+    int prof_used[TAPOUT_PROFILE_KINDS] = {0};
     char err[256] = {0};
 };
 
@@ -82,6 +88,32 @@ const char *check_logits(const tapout_logits *l, const char *name, int V, int ro
     if (l->stride_b < 0 || l->stride_k < 0) { snprintf(buf, 128, "%s logits: negative stride", name); return buf; }
     (void)V; (void)rows_k;
     return nullptr;
+}
+
+// Enqueue one kernel; when timing of `kind` is on, bracket it with an event pair on the same stream.
+template <class F>
+hipError_t timed(tapout_ctx *ctx, int kind, hipStream_t st, F launch)
+{
+    const bool on = (ctx->prof_mask >> kind) & 1u && ctx->prof_used[kind] < ctx->prof_cap;
+    if (!on) return launch();
+    const int i = ctx->prof_used[kind];
+    hipError_t e = hipEventRecord(ctx->prof_start[kind][i], st);
+    if (e != hipSuccess) return e;
+    e = launch();
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(ctx->prof_stop[kind][i], st);
+    if (e == hipSuccess) ctx->prof_used[kind] = i + 1;
+    return e;
+}
+
+void profile_release(tapout_ctx *ctx)
+{
+    for (int k = 0; k < TAPOUT_PROFILE_KINDS; ++k) {
+        for (hipEvent_t ev : ctx->prof_start[k]) (void)hipEventDestroy(ev);
+        for (hipEvent_t ev : ctx->prof_stop[k]) (void)hipEventDestroy(ev);
+        ctx->prof_start[k].clear(); ctx->prof_stop[k].clear(); ctx->prof_used[k] = 0;
+    }
+    ctx->prof_mask = 0; ctx->prof_cap = 0;
 }
 
 tapout_status check_shape(tapout_ctx *ctx, int B, int K, int V)
@@ -163,6 +195,7 @@ tapout_status tapout_destroy(tapout_ctx *ctx)
 {
     if (!ctx) return TAPOUT_OK;
     DeviceGuard guard(ctx->cfg.device);
+    profile_release(ctx);
     (void)hipFree(ctx->part); (void)hipFree(ctx->part1); (void)hipFree(ctx->part2);
     (void)hipFree(ctx->jobs); (void)hipFree(ctx->flags_ws);
     (void)hipFree(ctx->sum_r); (void)hipFree(ctx->count);
@@ -193,12 +226,13 @@ tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const float *u_ts
 {
     if (!ctx) return TAPOUT_EINVAL;
     if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (B == 0) return TAPOUT_OK;
     if (!arm_out) return fail(ctx, TAPOUT_EINVAL, "arm_out is NULL");
     if (ctx->cfg.policy == TAPOUT_TS_BETA && !u_ts) return fail(ctx, TAPOUT_EINVAL, "Thompson Sampling needs u_ts");
-    if (B == 0) return TAPOUT_OK;
     DeviceGuard guard(ctx->cfg.device);
     BanditArgs a{ctx->cfg.policy, ctx->cfg.n_bandits, ctx->cfg.n_arms, B, ctx->cfg.alpha, ctx->sum_r, ctx->count};
-    hipError_t e = launch_bandit_select(a, u_ts, arm_out, flags, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_SELECT, st, [&] { return launch_bandit_select(a, u_ts, arm_out, flags, st); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_select launch");
 }
 
@@ -208,11 +242,12 @@ tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *ar
 {
     if (!ctx) return TAPOUT_EINVAL;
     if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
-    if (!arm || !accept_len || !n_draft || !gamma) return fail(ctx, TAPOUT_EINVAL, "arm, accept_len, n_draft and gamma are required");
     if (B == 0) return TAPOUT_OK;
+    if (!arm || !accept_len || !n_draft || !gamma) return fail(ctx, TAPOUT_EINVAL, "arm, accept_len, n_draft and gamma are required");
     DeviceGuard guard(ctx->cfg.device);
     BanditArgs a{ctx->cfg.policy, ctx->cfg.n_bandits, ctx->cfg.n_arms, B, ctx->cfg.alpha, ctx->sum_r, ctx->count};
-    hipError_t e = launch_bandit_update(a, arm, accept_len, n_draft, gamma, active, (hipStream_t)stream);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_UPDATE, st, [&] { return launch_bandit_update(a, arm, accept_len, n_draft, gamma, active, st); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_update launch");
 }
 
@@ -237,7 +272,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, (int32_t)rows, k_len, 0, ctx->part};
-    hipError_t e = launch_row_reduce(r, draft->dtype, true, st);
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_REDUCE, st, [&] { return launch_row_reduce(r, draft->dtype, true, st); });
     if (e != hipSuccess) return hip_fail(ctx, e, "draft row_reduce launch");
 
     DraftFinalArgs f{};
@@ -248,7 +283,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) { f.rule[a] = ctx->cfg.rule[a]; f.threshold[a] = ctx->cfg.threshold[a]; }
     f.lse = lse; f.entropy = entropy; f.p_top1 = p_top1; f.p_top2 = p_top2; f.margin = margin; f.logq_tok = logq_tok;
     f.top1_id = top1_id; f.n_stop = n_stop; f.stop_fired = stop_fired; f.flags = flags;
-    e = launch_draft_finalize(f, st);
+    e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, st, [&] { return launch_draft_finalize(f, st); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft_finalize launch");
 }
 
@@ -278,7 +313,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, (int32_t)rows, n_draft, 1, ctx->part};
-    hipError_t e = launch_row_reduce(r, target->dtype, false, st);
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_REDUCE, st, [&] { return launch_row_reduce(r, target->dtype, false, st); });
     if (e != hipSuccess) return hip_fail(ctx, e, "target row_reduce launch");
 
     VerifyFinalArgs f{};
@@ -289,7 +324,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     f.accept_len = accept_len; f.out_tok = out_tok; f.n_out = n_out;
     f.target_lse = target_lse; f.logp_tok = logp_tok; f.target_top1 = target_top1; f.flags = flags;
     f.flags_ws = ctx->flags_ws; f.jobs = ctx->jobs;
-    e = launch_verify_finalize(f, st);
+    e = timed(ctx, TAPOUT_PROFILE_VERIFY_FINALIZE, st, [&] { return launch_verify_finalize(f, st); });
     if (e != hipSuccess) return hip_fail(ctx, e, "verify_finalize launch");
 
     SampleArgs sa{};
@@ -298,8 +333,52 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     sa.B = B; sa.K = K; sa.V = V; sa.nsplit = choose_sample_nsplit(ctx, B, V);
     sa.jobs = ctx->jobs; sa.u_sample = u_sample; sa.part1 = ctx->part1; sa.part2 = ctx->part2;
     sa.out_tok = out_tok; sa.flags = flags; sa.flags_ws = ctx->flags_ws;
-    e = launch_sample(sa, st);
+    for (int pass = 1; pass <= 3 && e == hipSuccess; ++pass)
+        e = timed(ctx, TAPOUT_PROFILE_SAMPLE_PASS1 + pass - 1, st, [&] { return launch_sample(sa, pass, st); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "sample launch");
+}
+
+tapout_status tapout_profile_enable(tapout_ctx *ctx, uint32_t kind_mask, int32_t max_records)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (max_records < 0 || max_records > (1 << 20)) return fail(ctx, TAPOUT_EINVAL, "max_records outside [0, 2^20]");
+    if (kind_mask >> TAPOUT_PROFILE_KINDS) return fail(ctx, TAPOUT_EINVAL, "kind_mask names an unknown kernel");
+    DeviceGuard guard(ctx->cfg.device);
+    profile_release(ctx);
+    if (!kind_mask || !max_records) return TAPOUT_OK;
+    for (int k = 0; k < TAPOUT_PROFILE_KINDS; ++k) {
+        if (!((kind_mask >> k) & 1u)) continue;
+        for (int i = 0; i < max_records; ++i) {
+            hipEvent_t a = nullptr, b = nullptr;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+                if (a) (void)hipEventDestroy(a);
+                profile_release(ctx);
+                return fail(ctx, TAPOUT_EHIP, "hipEventCreate failed");
+            }
+            ctx->prof_start[k].push_back(a); ctx->prof_stop[k].push_back(b);
+        }
+    }
+    ctx->prof_mask = kind_mask; ctx->prof_cap = max_records;
+    return TAPOUT_OK;
+}
+
+tapout_status tapout_profile_read(tapout_ctx *ctx, int32_t kind, double *total_ms, int32_t *launches, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (kind < 0 || kind >= TAPOUT_PROFILE_KINDS || !total_ms || !launches) return fail(ctx, TAPOUT_EINVAL, "bad kind or NULL output");
+    DeviceGuard guard(ctx->cfg.device);
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(ctx, e, "profile_read sync");
+    double sum = 0.0;
+    for (int i = 0; i < ctx->prof_used[kind]; ++i) {
+        float ms = 0.0f;
+        e = hipEventElapsedTime(&ms, ctx->prof_start[kind][i], ctx->prof_stop[kind][i]);
+        if (e != hipSuccess) return hip_fail(ctx, e, "hipEventElapsedTime");
+        sum += ms;
+    }
+    *total_ms = sum; *launches = ctx->prof_used[kind];
+    ctx->prof_used[kind] = 0;
+    return TAPOUT_OK;
 }
 
 tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, int64_t *count, void *stream)

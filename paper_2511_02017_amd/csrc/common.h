@@ -95,7 +95,7 @@ struct SampleArgs {
     int32_t *out_tok;             // [B, K+1]
     uint32_t *flags, *flags_ws;
 };
-hipError_t launch_sample(const SampleArgs &a, hipStream_t st);
+hipError_t launch_sample(const SampleArgs &a, int pass /*1..3*/, hipStream_t st);
 
 struct BanditArgs {
     int32_t policy, n_bandits, n_arms, B;

@@ -22,20 +22,6 @@ namespace {
 
 constexpr int kSampleBlock = 256;
 
-struct RowView {
-    const char *p;
-    int head, nvec, tail;
-};
-
-template <int DT>
-__device__ inline RowView view_row(const void *base, int64_t stride_b, int64_t stride_k, int b, int k, int V)
-{
-    RowView r;
-    r.p = (const char *)base + ((int64_t)b * stride_b + (int64_t)k * stride_k) * Elem<DT>::size;
-    row_geometry<DT>(r.p, V, r.head, r.nvec, r.tail);
-    return r;
-}
-
 __device__ inline double wave_sum_d(double v)
 {
 #pragma unroll
@@ -275,22 +261,22 @@ __global__ __launch_bounds__(kSampleBlock) void sample_pass3(SampleArgs a)
 }
 
 template <int TD, int DD>
-hipError_t launch_typed(const SampleArgs &a, hipStream_t st)
+hipError_t launch_typed(const SampleArgs &a, int pass, hipStream_t st)
 {
     dim3 grid12(a.nsplit, a.B), block(kSampleBlock);
-    hipLaunchKernelGGL((sample_pass1<TD, DD>), grid12, block, 0, st, a);
-    hipLaunchKernelGGL((sample_pass2<TD, DD>), grid12, block, 0, st, a);
-    hipLaunchKernelGGL((sample_pass3<TD, DD>), dim3(a.B), block, 0, st, a);
+    if (pass == 1) hipLaunchKernelGGL((sample_pass1<TD, DD>), grid12, block, 0, st, a);
+    else if (pass == 2) hipLaunchKernelGGL((sample_pass2<TD, DD>), grid12, block, 0, st, a);
+    else hipLaunchKernelGGL((sample_pass3<TD, DD>), dim3(a.B), block, 0, st, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_sample(const SampleArgs &a, hipStream_t st)
+hipError_t launch_sample(const SampleArgs &a, int pass, hipStream_t st)
 {
     if (a.t_dtype == TAPOUT_F32)
-        return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_F32, TAPOUT_F32>(a, st) : launch_typed<TAPOUT_F32, TAPOUT_BF16>(a, st);
-    return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_BF16, TAPOUT_F32>(a, st) : launch_typed<TAPOUT_BF16, TAPOUT_BF16>(a, st);
+        return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_F32, TAPOUT_F32>(a, pass, st) : launch_typed<TAPOUT_F32, TAPOUT_BF16>(a, pass, st);
+    return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_BF16, TAPOUT_F32>(a, pass, st) : launch_typed<TAPOUT_BF16, TAPOUT_BF16>(a, pass, st);
 }
 
 }  // namespace tapout

@@ -74,7 +74,7 @@ def main():
         for i in range(n):
             prepared[(first + i) % ring_n][0](sh)
 
-    kinds = binding.PROFILE_KINDS if args.profile_all else ("draft_reduce", "target_reduce")
+    kinds = binding.PROFILE_KINDS if args.profile_all else ("draft_pass", "target_pass")
     run(args.warmup)
     torch.cuda.synchronize()
     tp.profile_enable(kinds, args.steps)
@@ -112,9 +112,9 @@ def main():
                     frac=round(gbs / HBM_PEAK_GBS, 4), avg_us=round(avg_us, 2), launches=n,
                     bytes_per_launch=nbytes // n, traffic=None)
 
-    r_target = roof("target_reduce", w.V * target_rows * et)
-    r_draft = roof("draft_reduce", w.V * draft_rows * ed)
-    both_ms = prof["target_reduce"][0] + prof["draft_reduce"][0]
+    r_target = roof("target_pass", w.V * target_rows * et)
+    r_draft = roof("draft_pass", w.V * draft_rows * ed)
+    both_ms = prof["target_pass"][0] + prof["draft_pass"][0]
     out = {
         "metric": "verified draft tokens/sec and achieved HBM GB/s (% of peak) at vocab 128k",
         "value": round(verified / elapsed, 1),

@@ -232,7 +232,6 @@ TAPOUT_API tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *
  *   "wgs_target"  workgroups a streaming launch aims for (rows are cut into
  *                 slices until the launch has about this many), default 4096
  *   "min_slice"   smallest slice of a row, in elements, default 4096
- *   "sample_wgs"  workgroups the final-token passes aim for, default 2048
  * Results do not depend on these values except through the rounding of the
  * binary32 partial sums.
  */
@@ -249,16 +248,15 @@ TAPOUT_API tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, in
  * involved; timing is off by default.
  */
 enum {
-    TAPOUT_PROFILE_SELECT = 0,          /* bandit select                                  */
-    TAPOUT_PROFILE_DRAFT_REDUCE = 1,    /* streaming pass over the draft logits           */
-    TAPOUT_PROFILE_DRAFT_FINALIZE = 2,  /* signals + stop scan                            */
-    TAPOUT_PROFILE_TARGET_REDUCE = 3,   /* streaming pass over the target logits          */
-    TAPOUT_PROFILE_VERIFY_FINALIZE = 4, /* accept tests + first rejection                 */
-    TAPOUT_PROFILE_SAMPLE_PASS1 = 5,    /* final token: normalisers                       */
-    TAPOUT_PROFILE_SAMPLE_PASS2 = 6,    /* final token: slice weights                     */
-    TAPOUT_PROFILE_SAMPLE_PASS3 = 7,    /* final token: locate                            */
-    TAPOUT_PROFILE_UPDATE = 8,          /* bandit update                                  */
-    TAPOUT_PROFILE_KINDS = 9
+    TAPOUT_PROFILE_SELECT = 0,          /* bandit select                                            */
+    TAPOUT_PROFILE_DRAFT_PASS = 1,      /* streaming pass over the draft logits                     */
+    TAPOUT_PROFILE_DRAFT_FINALIZE = 2,  /* signals + stop scan                                      */
+    TAPOUT_PROFILE_TARGET_PASS = 3,     /* streaming pass over the target logits                    */
+    TAPOUT_PROFILE_VERIFY_PASS1 = 4,    /* accept tests, first rejection; final token: normalisers  */
+    TAPOUT_PROFILE_VERIFY_PASS2 = 5,    /* final token: slice weights                               */
+    TAPOUT_PROFILE_VERIFY_PASS3 = 6,    /* final token: locate                                      */
+    TAPOUT_PROFILE_UPDATE = 7,          /* bandit update                                            */
+    TAPOUT_PROFILE_KINDS = 8
 };
 TAPOUT_API tapout_status tapout_profile_enable(tapout_ctx *ctx, uint32_t kind_mask, int32_t max_records);
 TAPOUT_API tapout_status tapout_profile_read(tapout_ctx *ctx, int32_t kind, double *total_ms, int32_t *launches, void *stream);

@@ -27,8 +27,7 @@ EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_l
            "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
-PROFILE_KINDS = ("select", "draft_reduce", "draft_finalize", "target_reduce", "verify_finalize",
-                 "sample_pass1", "sample_pass2", "sample_pass3", "update")
+PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_pass1", "verify_pass2", "verify_pass3", "update")
 
 
 class TapoutConfig(C.Structure):

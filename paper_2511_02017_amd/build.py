@@ -15,7 +15,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(PKG, "libtapout.so")
-SOURCES = ["row_reduce.hip", "finalize.hip", "sample.hip", "bandit.hip", "api.hip"]
+SOURCES = ["row_reduce.hip", "finalize.hip", "verify.hip", "bandit.hip", "api.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -17,10 +17,11 @@ struct tapout_ctx {
     double *part1 = nullptr, *part2 = nullptr;                // residual sampler slice sums
     SampleJob *jobs = nullptr;
     uint32_t *flags_ws = nullptr;
+    double *exp_table = nullptr;                               // 2^(k/256), k = 0..255, for the final-token passes
+    int nsl_max = 0;                                           // final-token slices per row at cfg.vocab
     double *sum_r = nullptr;      int64_t *count = nullptr;   // bandit state [n_bandits, n_arms]
     int wgs_target = 4096;        // workgroups a streaming launch aims for
     int min_slice = 4096;         // smallest slice (elements) a row is cut into
-    int sample_wgs = 2048;        // workgroups the sampler passes aim for
     // optional kernel timing (tapout_profile_*): event pairs around the launches of selected kernels
     uint32_t prof_mask = 0;
     int prof_cap = 0;
@@ -32,7 +33,6 @@ struct tapout_ctx {
 namespace {
 
 constexpr int kMaxWgsTarget = 1 << 16;
-constexpr int kMaxSampleSplit = 64;
 thread_local char g_create_err[256] = {0};
 
 tapout_status fail(tapout_ctx *ctx, tapout_status st, const char *fmt, ...)
@@ -64,19 +64,9 @@ int choose_nsplit(const tapout_ctx *ctx, int64_t rows, int V)
     int64_t by_size = V / ctx->min_slice;
     if (by_size < 1) by_size = 1;
     if (want > by_size) want = by_size;
+    if (want > kStageCap) want = kStageCap;      // an epilogue stages whole rows of partials in LDS
     if (want < 1) want = 1;
     return (int)want;
-}
-
-int choose_sample_nsplit(const tapout_ctx *ctx, int B, int V)
-{
-    int want = (ctx->sample_wgs + B - 1) / B;
-    int by_size = V / 2048;
-    if (by_size < 1) by_size = 1;
-    if (want > by_size) want = by_size;
-    if (want > kMaxSampleSplit) want = kMaxSampleSplit;
-    if (want < 1) want = 1;
-    return want;
 }
 
 const char *check_logits(const tapout_logits *l, const char *name, int V, int rows_k, char *buf)
@@ -173,9 +163,14 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     const size_t rows = (size_t)cfg->max_batch * (cfg->max_k + 1);
     c->part_cap = rows + kMaxWgsTarget;
     const size_t nstate = (size_t)cfg->n_bandits * cfg->n_arms;
+    c->nsl_max = (cfg->vocab + kSampleSlice - 1) / kSampleSlice;
+    double table[256];
+    for (int k = 0; k < 256; ++k) table[k] = std::exp2((double)k / 256.0);
     bool ok = hipMalloc(&c->part, c->part_cap * sizeof(Partial)) == hipSuccess
-           && hipMalloc(&c->part1, (size_t)cfg->max_batch * kMaxSampleSplit * 2 * sizeof(double)) == hipSuccess
-           && hipMalloc(&c->part2, (size_t)cfg->max_batch * kMaxSampleSplit * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->part1, (size_t)cfg->max_batch * c->nsl_max * 2 * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->part2, (size_t)cfg->max_batch * c->nsl_max * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->exp_table, sizeof table) == hipSuccess
+           && hipMemcpy(c->exp_table, table, sizeof table, hipMemcpyHostToDevice) == hipSuccess
            && hipMalloc(&c->jobs, (size_t)cfg->max_batch * sizeof(SampleJob)) == hipSuccess
            && hipMalloc(&c->flags_ws, (size_t)cfg->max_batch * sizeof(uint32_t)) == hipSuccess
            && hipMalloc(&c->sum_r, nstate * sizeof(double)) == hipSuccess
@@ -198,6 +193,7 @@ tapout_status tapout_destroy(tapout_ctx *ctx)
     profile_release(ctx);
     (void)hipFree(ctx->part); (void)hipFree(ctx->part1); (void)hipFree(ctx->part2);
     (void)hipFree(ctx->jobs); (void)hipFree(ctx->flags_ws);
+    (void)hipFree(ctx->exp_table);
     (void)hipFree(ctx->sum_r); (void)hipFree(ctx->count);
     delete ctx;
     return TAPOUT_OK;
@@ -214,9 +210,6 @@ tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value
     } else if (!strcmp(name, "min_slice")) {
         if (value < 256) return fail(ctx, TAPOUT_EINVAL, "min_slice below 256 elements");
         ctx->min_slice = value;
-    } else if (!strcmp(name, "sample_wgs")) {
-        if (value < 1 || value > kMaxWgsTarget) return fail(ctx, TAPOUT_EINVAL, "sample_wgs outside [1, %d]", kMaxWgsTarget);
-        ctx->sample_wgs = value;
     } else return fail(ctx, TAPOUT_EINVAL, "unknown option '%s'", name);
     return TAPOUT_OK;
 }
@@ -272,9 +265,8 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, (int32_t)rows, k_len, 0, ctx->part};
-    hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_REDUCE, st, [&] { return launch_row_reduce(r, draft->dtype, true, st); });
-    if (e != hipSuccess) return hip_fail(ctx, e, "draft row_reduce launch");
-
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, st, [&] { return launch_row_reduce(r, draft->dtype, true, st); });
+    if (e != hipSuccess) return hip_fail(ctx, e, "draft pass launch");
     DraftFinalArgs f{};
     f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
     f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = ctx->part;
@@ -284,7 +276,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     f.lse = lse; f.entropy = entropy; f.p_top1 = p_top1; f.p_top2 = p_top2; f.margin = margin; f.logq_tok = logq_tok;
     f.top1_id = top1_id; f.n_stop = n_stop; f.stop_fired = stop_fired; f.flags = flags;
     e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, st, [&] { return launch_draft_finalize(f, st); });
-    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft_finalize launch");
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft finalize launch");
 }
 
 tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const tapout_logits *draft,
@@ -313,29 +305,23 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, (int32_t)rows, n_draft, 1, ctx->part};
-    hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_REDUCE, st, [&] { return launch_row_reduce(r, target->dtype, false, st); });
-    if (e != hipSuccess) return hip_fail(ctx, e, "target row_reduce launch");
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_PASS, st, [&] { return launch_row_reduce(r, target->dtype, false, st); });
+    if (e != hipSuccess) return hip_fail(ctx, e, "target pass launch");
 
-    VerifyFinalArgs f{};
-    f.tbase = target->ptr; f.t_dtype = target->dtype; f.t_stride_b = target->stride_b; f.t_stride_k = target->stride_k;
-    f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = ctx->part;
-    f.draft_lse = draft_lse; f.logq_tok = logq_tok; f.draft_tok = draft_tok; f.n_draft = n_draft; f.greedy = greedy;
-    f.u_accept = u_accept;
-    f.accept_len = accept_len; f.out_tok = out_tok; f.n_out = n_out;
-    f.target_lse = target_lse; f.logp_tok = logp_tok; f.target_top1 = target_top1; f.flags = flags;
-    f.flags_ws = ctx->flags_ws; f.jobs = ctx->jobs;
-    e = timed(ctx, TAPOUT_PROFILE_VERIFY_FINALIZE, st, [&] { return launch_verify_finalize(f, st); });
-    if (e != hipSuccess) return hip_fail(ctx, e, "verify_finalize launch");
-
-    SampleArgs sa{};
-    sa.tbase = target->ptr; sa.t_dtype = target->dtype; sa.t_stride_b = target->stride_b; sa.t_stride_k = target->stride_k;
-    sa.dbase = draft->ptr; sa.d_dtype = draft->dtype; sa.d_stride_b = draft->stride_b; sa.d_stride_k = draft->stride_k;
-    sa.B = B; sa.K = K; sa.V = V; sa.nsplit = choose_sample_nsplit(ctx, B, V);
-    sa.jobs = ctx->jobs; sa.u_sample = u_sample; sa.part1 = ctx->part1; sa.part2 = ctx->part2;
-    sa.out_tok = out_tok; sa.flags = flags; sa.flags_ws = ctx->flags_ws;
+    VerifyArgs va{};
+    va.tbase = target->ptr; va.t_dtype = target->dtype; va.t_stride_b = target->stride_b; va.t_stride_k = target->stride_k;
+    va.dbase = draft->ptr; va.d_dtype = draft->dtype; va.d_stride_b = draft->stride_b; va.d_stride_k = draft->stride_k;
+    va.B = B; va.K = K; va.V = V; va.nsplit = nsplit; va.nsl = (V + kSampleSlice - 1) / kSampleSlice;
+    va.part = ctx->part;
+    va.draft_lse = draft_lse; va.logq_tok = logq_tok; va.draft_tok = draft_tok; va.n_draft = n_draft; va.greedy = greedy;
+    va.u_accept = u_accept; va.u_sample = u_sample;
+    va.accept_len = accept_len; va.out_tok = out_tok; va.n_out = n_out;
+    va.target_lse = target_lse; va.logp_tok = logp_tok; va.target_top1 = target_top1; va.flags = flags;
+    va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
+    va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
     for (int pass = 1; pass <= 3 && e == hipSuccess; ++pass)
-        e = timed(ctx, TAPOUT_PROFILE_SAMPLE_PASS1 + pass - 1, st, [&] { return launch_sample(sa, pass, st); });
-    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "sample launch");
+        e = timed(ctx, TAPOUT_PROFILE_VERIFY_PASS1 + pass - 1, st, [&] { return launch_verify(va, pass, st); });
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "verify launch");
 }
 
 tapout_status tapout_profile_enable(tapout_ctx *ctx, uint32_t kind_mask, int32_t max_records)

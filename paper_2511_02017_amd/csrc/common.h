@@ -54,10 +54,7 @@ struct RowReduceArgs {
     int32_t len_mode;             // 0: row k active iff k < len[b] (NULL: all); 1: iff k <= clamp(len[b], 1, KK-1)
     Partial *out;                 // [n_rows, nsplit]
 };
-
-struct Ctx;
-
-// launchers (each returns hipGetLastError() after enqueueing)
+// Streaming pass: one Partial per (row, slice).  Returns hipGetLastError() after enqueueing.
 hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st);
 
 struct DraftFinalArgs {
@@ -71,31 +68,29 @@ struct DraftFinalArgs {
 };
 hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st);
 
-struct VerifyFinalArgs {
+// Verification + final token.  Kernel 1 merges the target partials of its sequence, takes the
+// accept decisions (every workgroup of the sequence redundantly; slice 0 writes the outputs) and
+// then sums its slice of exp(t - ref_p), exp(d - ref_q); kernel 2 forms the slice weights of the
+// residual; kernel 3 locates the token.
+struct VerifyArgs {
     const void *tbase; int32_t t_dtype; int64_t t_stride_b, t_stride_k;
-    int32_t B, K, V, nsplit;
+    const void *dbase; int32_t d_dtype; int64_t d_stride_b, d_stride_k;
+    int32_t B, K, V, nsplit;      // nsplit: slices per row of the streaming pass
+    int32_t nsl;                  // slices per row of the final-token passes (kSampleSlice elements each)
     const Partial *part;
     const float *draft_lse, *logq_tok; const int32_t *draft_tok, *n_draft; const uint8_t *greedy;
-    const float *u_accept;
+    const float *u_accept, *u_sample;
     int32_t *accept_len, *out_tok, *n_out;
     float *target_lse, *logp_tok; int32_t *target_top1; uint32_t *flags;
     uint32_t *flags_ws;           // internal copy of the flags (always present)
-    SampleJob *jobs;
+    SampleJob *jobs;              // [B]
+    double *part1;                // [B, nsl, 2]  sum e_p, sum e_q of each slice
+    double *part2;                // [B, nsl]     weight of each slice
+    const double *exp_table;      // 2^(k/256), k = 0..255
 };
-hipError_t launch_verify_finalize(const VerifyFinalArgs &a, hipStream_t st);
+hipError_t launch_verify(const VerifyArgs &a, int pass /*1..3*/, hipStream_t st);
 
-struct SampleArgs {
-    const void *tbase; int32_t t_dtype; int64_t t_stride_b, t_stride_k;
-    const void *dbase; int32_t d_dtype; int64_t d_stride_b, d_stride_k;
-    int32_t B, K, V, nsplit;
-    const SampleJob *jobs;
-    const float *u_sample;
-    double *part1;                // [B, nsplit, 2]  sum e_p, sum e_q of each slice
-    double *part2;                // [B, nsplit]     weight of each slice
-    int32_t *out_tok;             // [B, K+1]
-    uint32_t *flags, *flags_ws;
-};
-hipError_t launch_sample(const SampleArgs &a, int pass /*1..3*/, hipStream_t st);
+constexpr int kSampleSlice = 2048;   // elements per slice of the final-token passes (256 threads x 8)
 
 struct BanditArgs {
     int32_t policy, n_bandits, n_arms, B;
@@ -161,6 +156,19 @@ __device__ inline const void *row_address(const void *base, int dtype, int64_t s
     return (const char *)base + off * (dtype == TAPOUT_F32 ? 4 : 2);
 }
 
+constexpr int kStageCap = 256;     // partials staged in LDS at a time by an epilogue (8 KB)
+constexpr int kScanCap = 4096;     // largest K: one stop / accept decision byte per draft position fits LDS
+
+// All threads of the workgroup copy `count` partials (count <= kStageCap) into LDS; the loads of
+// all threads are in flight together, so the copy costs one memory round trip.
+__device__ inline void stage_partials(Partial *sh, const Partial *src, int count)
+{
+    const u32x4 *s = (const u32x4 *)src;
+    u32x4 *d = (u32x4 *)sh;
+    for (int i = threadIdx.x; i < 2 * count; i += blockDim.x) d[i] = s[i];
+    __syncthreads();
+}
+
 // Merged statistics of all slices of one row, in double.
 struct RowTotal {
     float M;          // row maximum
@@ -171,7 +179,7 @@ struct RowTotal {
     bool bad;
 };
 
-__device__ inline RowTotal merge_partials(const Partial *p, int nsplit)
+__device__ inline RowTotal merge_partials(const Partial *p /* LDS */, int nsplit)
 {
     RowTotal r;
     float M = -INFINITY;
@@ -184,12 +192,12 @@ __device__ inline RowTotal merge_partials(const Partial *p, int nsplit)
     bool seen_max = false;
     for (int s = 0; s < nsplit; ++s) {
         float v1 = p[s].v1;
-        if (v1 == -INFINITY && !(p[s].S != p[s].S)) continue;    // empty slice (a NaN sum still has to poison the row)
+        if (v1 == -INFINITY && !(p[s].S != p[s].S)) continue;     // empty slice (a NaN sum still has to poison the row)
         double d = r.R - (double)ref_of_max(v1);                  // >= 0, integer
-        double sc = exp2(-d);
+        int di = d > 4000.0 ? 4000 : (int)d;                      // 2^-4000 underflows to 0 as it should
         double Si = (double)p[s].S, Ti = (double)p[s].T;
-        S += Si * sc;
-        T += (Ti - d * Si) * sc;
+        S += ldexp(Si, -di);                                      // exact power-of-two scaling
+        T += ldexp(Ti - d * Si, -di);
         // second largest of the union, duplicates counted
         if (v1 == M) {
             if (seen_max) v2 = M; else seen_max = true;
@@ -207,11 +215,18 @@ __device__ inline RowTotal merge_partials(const Partial *p, int nsplit)
 // First index j in [cand, cand + window) with x_j == M (the lowest argmax index of the row).
 __device__ inline int32_t resolve_argmax(const void *row, int dtype, int32_t V, int32_t cand, float M)
 {
-    int window = dtype == TAPOUT_F32 ? 4 : 8;
     if (cand < 0 || cand >= V) return 0;
-    for (int i = 0; i < window && cand + i < V; ++i)
-        if (load_elem_rt(row, dtype, cand + i) == M) return cand + i;
-    return cand;
+    const int window = dtype == TAPOUT_F32 ? 4 : 8;
+    // all loads first (independent, one memory round trip), then the first match
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+        x[i] = (i < window && cand + i < V) ? load_elem_rt(row, dtype, cand + i) : NAN;
+    int32_t hit = cand;
+#pragma unroll
+    for (int i = 7; i >= 0; --i)
+        if (x[i] == M) hit = cand + i;
+    return hit;
 }
 
 #endif  // __HIPCC__

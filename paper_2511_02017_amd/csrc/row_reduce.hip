@@ -1,19 +1,27 @@
-// Streaming reduction of logits rows: the one pass over the vocabulary that
-// feeds every signal of Table 1 / Appendix A.1 (entropy, top-1 probability,
+// Streaming pass over logits rows: the one read of the vocabulary that feeds
+// every signal of Table 1 / Appendix A.1 (entropy, top-1 probability,
 // top-1/top-2 margin) and the normalisers the verification step needs.
 //
 // One launch covers all rows of a [B, KK, V] tensor.  A row is cut into
 // `nsplit` slices of whole 16-byte vectors; one 256-thread workgroup reduces
 // one slice to a 32-byte Partial.  Every element is loaded exactly once, with
-// 16-byte loads that are contiguous across the wavefront.
+// 16-byte non-temporal loads that are contiguous across the wavefront; the
+// loads of the next batch are issued before the current batch is folded.
 //
 // Per thread the softmax sums are kept online in the base-2 domain against an
-// integer reference R = ceil(max * log2 e): y = fma(x, log2e, -R) has a single
+// integer reference R >= max * log2 e: y = fma(x, log2e, -R) has a single
 // rounding, 2^y comes from the hardware exp2, and moving to a larger reference
 // is an exact ldexp.  Top-2 values are tracked with max3 / med3 on pairs
 // (second largest of {v1, a, b, v2} = max(med3(v1, a, b), v2) while v2 <= v1).
 // Only the 16-byte window in which the thread's maximum first appeared is
 // remembered; the exact argmax index is recovered later from that window.
+//
+// Wavefront reductions use DPP row operations (no LDS traffic).  The partials
+// are merged per sequence by a second, small launch (finalize.hip for draft
+// rows, the head of the final-token kernel in sample.hip for target rows): a
+// "last workgroup finishes the sequence" scheme was measured and lost, because
+// on this chip every cross-workgroup hand-over costs a memory round trip of
+// about 3 us under streaming load and four of them chain up.
 #include "common.h"
 
 namespace tapout {
@@ -72,57 +80,109 @@ struct ThreadState {
     }
 };
 
+// ---- wavefront reductions with DPP -------------------------------------------
+// quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141,
+// row_mirror = 0x140: after the four steps every lane of a 16-lane row holds the
+// row's result; the four rows are then combined through readlane.
+template <int CTRL>
+__device__ inline float dpp_f(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+template <int CTRL>
+__device__ inline int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
+__device__ inline float lane_f(float v, int lane) { return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane)); }
+
 __device__ inline float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-    return v;
+    v = fmaxf(v, dpp_f<0xB1>(v)); v = fmaxf(v, dpp_f<0x4E>(v));
+    v = fmaxf(v, dpp_f<0x141>(v)); v = fmaxf(v, dpp_f<0x140>(v));
+    return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
 }
 __device__ inline float wave_sum(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
+    v += dpp_f<0xB1>(v); v += dpp_f<0x4E>(v); v += dpp_f<0x141>(v); v += dpp_f<0x140>(v);
+    return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
 }
 __device__ inline int wave_min_i(int v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, kWave));
-    return v;
+    v = min(v, dpp_i<0xB1>(v)); v = min(v, dpp_i<0x4E>(v)); v = min(v, dpp_i<0x141>(v)); v = min(v, dpp_i<0x140>(v));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
-// second largest of the union of two (largest, second) pairs, duplicates counted
+// (largest, second largest counting duplicates) of the union of two such pairs
+__device__ inline void top2_merge(float &a1, float &a2, float b1, float b2)
+{
+    a2 = max3(fminf(a1, b1), a2, b2);
+    a1 = fmaxf(a1, b1);
+}
 __device__ inline void wave_top2(float &a1, float &a2)
 {
+    top2_merge(a1, a2, dpp_f<0xB1>(a1), dpp_f<0xB1>(a2));
+    top2_merge(a1, a2, dpp_f<0x4E>(a1), dpp_f<0x4E>(a2));
+    top2_merge(a1, a2, dpp_f<0x141>(a1), dpp_f<0x141>(a2));
+    top2_merge(a1, a2, dpp_f<0x140>(a1), dpp_f<0x140>(a2));
+    float r1 = lane_f(a1, 0), r2 = lane_f(a2, 0);
+    top2_merge(r1, r2, lane_f(a1, 16), lane_f(a2, 16));
+    top2_merge(r1, r2, lane_f(a1, 32), lane_f(a2, 32));
+    top2_merge(r1, r2, lane_f(a1, 48), lane_f(a2, 48));
+    a1 = r1; a2 = r2;
+}
+
+template <int DT> struct NegInfVec;
+template <> struct NegInfVec<TAPOUT_F32>  { static constexpr uint32_t word = 0xff800000u; };
+template <> struct NegInfVec<TAPOUT_BF16> { static constexpr uint32_t word = 0xff80ff80u; };
+
+template <int DT, int U>
+__device__ inline void load_batch(u32x4 (&w)[U], const u32x4 *vp, int i, int end)
+{
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        float b1 = __shfl_xor(a1, o, kWave), b2 = __shfl_xor(a2, o, kWave);
-        a2 = max3(fminf(a1, b1), a2, b2);
-        a1 = fmaxf(a1, b1);
+    for (int u = 0; u < U; ++u) {
+        const int idx = i + u * kBlock;
+        if (idx < end) w[u] = __builtin_nontemporal_load(vp + idx);
+        else { const uint32_t ni = NegInfVec<DT>::word; w[u] = u32x4{ni, ni, ni, ni}; }   // -inf padding folds to nothing
+    }
+}
+
+template <int DT, bool FULL, int U>
+__device__ inline void fold_batch(ThreadState<FULL> &st, const u32x4 (&w)[U], int i, int head)
+{
+    constexpr int VEC = Elem<DT>::vec;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        float x[VEC];
+        unpack<DT>(w[u], x);
+        st.template fold<VEC>(x, head + (i + u * kBlock) * VEC);
     }
 }
 
 template <int DT, bool FULL>
-__global__ __launch_bounds__(kBlock) void row_reduce_kernel(RowReduceArgs a)
+__global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
 {
     constexpr int VEC = Elem<DT>::vec;
-    constexpr int UNROLL = 4;
+    constexpr int U = 4;
+    __shared__ float sh_f[4][kBlock / kWave];
+    __shared__ int sh_i[kBlock / kWave];
+
     const int split = blockIdx.x % a.nsplit;
     const int row = blockIdx.x / a.nsplit;
     const int b = row / a.KK, k = row % a.KK;
-    if (a.len_mode == 0) {
-        if (a.len && k >= a.len[b]) return;
+    const int tid = threadIdx.x;
+    int n_active;                                   // rows of sequence b this pass reads
+    if constexpr (FULL) {
+        n_active = a.len ? a.len[b] : a.KK;
+        n_active = n_active > a.KK ? a.KK : (n_active < 0 ? 0 : n_active);
     } else {
         int n = a.len[b];
-        n = n < 1 ? 1 : (n > a.KK - 1 ? a.KK - 1 : n);
-        if (k > n) return;
+        n_active = (n < 1 ? 1 : (n > a.KK - 1 ? a.KK - 1 : n)) + 1;
     }
+    if (k >= n_active) return;
     const char *rowp = (const char *)a.base + ((int64_t)b * a.stride_b + (int64_t)k * a.stride_k) * Elem<DT>::size;
     int head, nvec, tail;
     row_geometry<DT>(rowp, a.V, head, nvec, tail);
     const u32x4 *vp = (const u32x4 *)(rowp + (int64_t)head * Elem<DT>::size);
     const int per = (nvec + a.nsplit - 1) / a.nsplit;
     const int v0 = min(split * per, nvec), v1e = min(v0 + per, nvec);
-    const int tid = threadIdx.x;
 
     ThreadState<FULL> st;
     // unaligned head (first slice) and tail (last slice): one element per thread
@@ -130,23 +190,21 @@ __global__ __launch_bounds__(kBlock) void row_reduce_kernel(RowReduceArgs a)
         float x[1] = { load_elem<DT>(rowp, tid) };
         st.template fold<1>(x, tid);
     }
-    int i = v0 + tid;
-    for (; i + (UNROLL - 1) * kBlock < v1e; i += UNROLL * kBlock) {
-        u32x4 w[UNROLL];
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) w[u] = __builtin_nontemporal_load(vp + i + u * kBlock);
-#pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
-            float x[VEC];
-            unpack<DT>(w[u], x);
-            st.template fold<VEC>(x, head + (i + u * kBlock) * VEC);
+    {
+        // ping-pong over batches of U vectors per thread; the other buffer's loads are in flight while one is folded
+        const int nbatch = (v1e - v0 + U * kBlock - 1) / (U * kBlock);
+        u32x4 wa[U], wb[U];
+        int i = v0 + tid;
+        if (nbatch > 0) load_batch<DT, U>(wa, vp, i, v1e);
+        int bi = 0;
+        for (; bi + 2 <= nbatch; bi += 2) {
+            load_batch<DT, U>(wb, vp, i + U * kBlock, v1e);
+            fold_batch<DT, FULL, U>(st, wa, i, head);
+            if (bi + 2 < nbatch) load_batch<DT, U>(wa, vp, i + 2 * U * kBlock, v1e);
+            fold_batch<DT, FULL, U>(st, wb, i + U * kBlock, head);
+            i += 2 * U * kBlock;
         }
-    }
-    for (; i < v1e; i += kBlock) {
-        u32x4 w = __builtin_nontemporal_load(vp + i);
-        float x[VEC];
-        unpack<DT>(w, x);
-        st.template fold<VEC>(x, head + i * VEC);
+        if (bi < nbatch) fold_batch<DT, FULL, U>(st, wa, i, head);
     }
     if (split == a.nsplit - 1 && tid < tail) {
         int32_t j = head + nvec * VEC + tid;
@@ -155,8 +213,6 @@ __global__ __launch_bounds__(kBlock) void row_reduce_kernel(RowReduceArgs a)
     }
 
     // ---- workgroup reduction ----
-    __shared__ float sh_f[4][kBlock / kWave];
-    __shared__ int sh_i[kBlock / kWave];
     const int wave = tid / kWave, lane = tid % kWave;
     float wm = wave_max(st.v1);
     if (lane == 0) sh_f[0][wave] = wm;
@@ -185,10 +241,7 @@ __global__ __launch_bounds__(kBlock) void row_reduce_kernel(RowReduceArgs a)
         p.T = (sh_f[1][0] + sh_f[1][1]) + (sh_f[1][2] + sh_f[1][3]);
         float b1 = sh_f[2][0], b2 = sh_f[3][0];
 #pragma unroll
-        for (int w = 1; w < kBlock / kWave; ++w) {
-            b2 = max3(fminf(b1, sh_f[2][w]), b2, sh_f[3][w]);
-            b1 = fmaxf(b1, sh_f[2][w]);
-        }
+        for (int w = 1; w < kBlock / kWave; ++w) top2_merge(b1, b2, sh_f[2][w], sh_f[3][w]);
         p.v2 = b2;
         p.cand = min(min(sh_i[0], sh_i[1]), min(sh_i[2], sh_i[3]));
         p.pad[0] = p.pad[1] = p.pad[2] = 0;
@@ -196,19 +249,20 @@ __global__ __launch_bounds__(kBlock) void row_reduce_kernel(RowReduceArgs a)
     }
 }
 
+template <int DT, bool FULL>
+hipError_t launch(const RowReduceArgs &a, hipStream_t st)
+{
+    dim3 grid((unsigned)((int64_t)a.n_rows * a.nsplit)), block(kBlock);
+    hipLaunchKernelGGL((stream_pass_kernel<DT, FULL>), grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
 }  // namespace
 
 hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st)
 {
-    dim3 grid((unsigned)((int64_t)a.n_rows * a.nsplit)), block(kBlock);
-    if (dtype == TAPOUT_F32) {
-        if (full) hipLaunchKernelGGL((row_reduce_kernel<TAPOUT_F32, true>), grid, block, 0, st, a);
-        else      hipLaunchKernelGGL((row_reduce_kernel<TAPOUT_F32, false>), grid, block, 0, st, a);
-    } else {
-        if (full) hipLaunchKernelGGL((row_reduce_kernel<TAPOUT_BF16, true>), grid, block, 0, st, a);
-        else      hipLaunchKernelGGL((row_reduce_kernel<TAPOUT_BF16, false>), grid, block, 0, st, a);
-    }
-    return hipGetLastError();
+    if (dtype == TAPOUT_F32) return full ? launch<TAPOUT_F32, true>(a, st) : launch<TAPOUT_F32, false>(a, st);
+    return full ? launch<TAPOUT_BF16, true>(a, st) : launch<TAPOUT_BF16, false>(a, st);
 }
 
 }  // namespace tapout

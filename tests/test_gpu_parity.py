@@ -101,7 +101,6 @@ def test_slice_counts_do_not_change_decisions():
     for wgs, min_slice in ((1, 4096), (64, 256), (4096, 256), (65536, 256), (4096, 1 << 20)):
         tp.set_option("wgs_target", wgs)
         tp.set_option("min_slice", min_slice)
-        tp.set_option("sample_wgs", max(1, wgs // 2))
         pu.check_round(tp, rounds[0])
         ds, vf, _ = pu.gpu_round(tp, rounds[0])
         ints = (ds["top1_id"].cpu(), vf["accept_len"].cpu(), vf["out_tok"].cpu())

@@ -27,7 +27,7 @@ EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_l
            "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
-PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_pass1", "verify_pass2", "verify_pass3", "update")
+PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_head", "verify_pass1", "verify_pass2", "verify_pass3", "update")
 
 
 class TapoutConfig(C.Structure):
@@ -138,9 +138,10 @@ class Tapout:
             raise TapoutError(st, self._lib.tapout_last_error(None).decode())
 
     def close(self):
-        if getattr(self, "_ctx", None) is not None and self._ctx.value:
-            self._lib.tapout_destroy(self._ctx)
-            self._ctx = C.c_void_p()
+        ctx = getattr(self, "_ctx", None)
+        if ctx is not None and ctx.value:
+            self._lib.tapout_destroy(ctx)
+            self._ctx = None
 
     __del__ = close
 

@@ -319,8 +319,8 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     va.target_lse = target_lse; va.logp_tok = logp_tok; va.target_top1 = target_top1; va.flags = flags;
     va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
     va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
-    for (int pass = 1; pass <= 3 && e == hipSuccess; ++pass)
-        e = timed(ctx, TAPOUT_PROFILE_VERIFY_PASS1 + pass - 1, st, [&] { return launch_verify(va, pass, st); });
+    for (int pass = 0; pass <= 3 && e == hipSuccess; ++pass)
+        e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, st, [&] { return launch_verify(va, pass, st); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "verify launch");
 }
 

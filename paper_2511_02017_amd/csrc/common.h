@@ -88,9 +88,9 @@ struct VerifyArgs {
     double *part2;                // [B, nsl]     weight of each slice
     const double *exp_table;      // 2^(k/256), k = 0..255
 };
-hipError_t launch_verify(const VerifyArgs &a, int pass /*1..3*/, hipStream_t st);
+hipError_t launch_verify(const VerifyArgs &a, int pass /*0 = head, 1..3*/, hipStream_t st);
 
-constexpr int kSampleSlice = 2048;   // elements per slice of the final-token passes (256 threads x 8)
+constexpr int kSampleSlice = 4096;   // elements per slice of the final-token passes
 
 struct BanditArgs {
     int32_t policy, n_bandits, n_arms, B;

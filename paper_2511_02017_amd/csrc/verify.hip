@@ -1,18 +1,18 @@
 // Verification of the drafted tokens and the final token (Algorithm 1, lines
 // 10-11; "verify" = speculative sampling as in the works the paper cites).
 //
-// After the streaming pass over the target rows (row_reduce.hip) three small
+// After the streaming pass over the target rows (row_reduce.hip) four small
 // launches finish the job:
 //
-//   pass 1  head: every workgroup of a sequence merges the target partials,
-//           forms log p(tok), takes the accept decisions u < p(tok)/q(tok) and
-//           finds the first rejection m (slice 0 writes the outputs); then it
-//           sums its slice of e_p = exp(t - ref_p), e_q = exp(d - ref_q) of
-//           the row pair (m, m) the final token is drawn from
+//   head    one workgroup per sequence merges the target partials, forms
+//           log p(tok), takes the accept decisions u < p(tok)/q(tok), finds the
+//           first rejection m, emits the accepted tokens and describes the draw
+//           of the final token (row pair (m, m), or target row n alone)
+//   pass 1  slice sums of e_p = exp(t - ref_p), e_q = exp(d - ref_q)  -> normalisers
 //   pass 2  slice sums of w = max(0, e_p/S_p - e_q/S_q)   (or e_p/S_p: bonus token)
-//   pass 3  one workgroup per sequence: scan the slice sums, then a block scan
-//           inside the slice that contains u * Z: token = smallest j whose
-//           inclusive prefix sum exceeds u * Z
+//   pass 3  one workgroup per sequence: scan the slice sums, then a scan inside
+//           the slice that contains u * Z: token = smallest j whose inclusive
+//           prefix sum exceeds u * Z
 //
 // Passes 1-3 are double precision.  With ~1e5 CDF cell edges in [0,1) a binary32
 // evaluation would move an edge across u for about one draw in a hundred; in
@@ -29,8 +29,9 @@ namespace tapout {
 namespace {
 
 constexpr int kVBlock = 256;
-constexpr int kPer = 8;                       // consecutive elements per thread: kSampleSlice = kVBlock * kPer
-static_assert(kVBlock * kPer == kSampleSlice, "slice = one 8-element run per thread");
+constexpr int kPer = 8;                       // elements per 16-byte (bf16) / 32-byte (f32) run
+constexpr int kRuns = 2;                      // runs per thread and slice in passes 1 and 2
+static_assert(kVBlock * kPer * kRuns == kSampleSlice, "slice = kRuns 8-element runs per thread");
 
 // ---- double-precision helpers ---------------------------------------------------
 __device__ inline double exp_tab(double y, const double *T)
@@ -53,34 +54,16 @@ __device__ inline double wave_sum_d(double v)
     return v;
 }
 
-// Sum over the workgroup in a fixed order (same result in every workgroup that sums the same values).
-__device__ inline double block_sum_d(double v, double *sh4)
+// Sums of two values over the workgroup in a fixed order, one barrier.  sh8 must not be in use by a
+// previous call that other wavefronts may still be reading.
+__device__ inline void block_sum2_d(double &v1, double &v2, double *sh8)
 {
-    v = wave_sum_d(v);
+    v1 = wave_sum_d(v1); v2 = wave_sum_d(v2);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) { sh8[wave] = v1; sh8[4 + wave] = v2; }
     __syncthreads();
-    if ((threadIdx.x & (kWave - 1)) == 0) sh4[threadIdx.x / kWave] = v;
-    __syncthreads();
-    return (sh4[0] + sh4[1]) + (sh4[2] + sh4[3]);
-}
-
-// Inclusive scan over the workgroup of one double per thread; returns the exclusive prefix of this
-// thread, the workgroup total through *total.
-__device__ inline double block_excl_scan_d(double v, double *sh4, double *total)
-{
-    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    double inc = v;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        double up = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += up;
-    }
-    __syncthreads();
-    if (lane == kWave - 1) sh4[wave] = inc;
-    __syncthreads();
-    double base = 0.0;
-    for (int w2 = 0; w2 < wave; ++w2) base += sh4[w2];
-    *total = ((sh4[0] + sh4[1]) + sh4[2]) + sh4[3];
-    return base + (inc - v);
+    v1 = (sh8[0] + sh8[1]) + (sh8[2] + sh8[3]);
+    v2 = (sh8[4] + sh8[5]) + (sh8[6] + sh8[7]);
 }
 
 // Eight consecutive elements j .. j+7 of a row, exact in binary32; -inf beyond V.
@@ -108,27 +91,6 @@ struct Weights {
     int kind;          // 1 residual max(0, p - q), 2 target row only
     double ref_p, ref_q, inv_Sp, inv_Sq;
 };
-
-// The eight weights of this thread in slice `s` (elements s*kSampleSlice + tid*8 ..).
-template <int TD, int DD>
-__device__ inline void thread_weights(const Weights &w, const char *trow, bool t_al, const char *drow, bool d_al,
-                                      int s, int V, const double *T, double (&wv)[kPer])
-{
-    const int j = s * kSampleSlice + threadIdx.x * kPer;
-    float xt[kPer], xd[kPer];
-    load8<TD>(trow, t_al, j, V, xt);
-    if (w.kind == 1) load8<DD>(drow, d_al, j, V, xd);
-#pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-        double p = exp_tab((double)xt[i] - w.ref_p, T) * w.inv_Sp;
-        if (w.kind == 1) {
-            double q = exp_tab((double)xd[i] - w.ref_q, T) * w.inv_Sq;
-            p = p - q;
-            p = p > 0.0 ? p : 0.0;
-        }
-        wv[i] = p;
-    }
-}
 
 __device__ inline void load_table(double *shT, const double *T)
 {
@@ -275,52 +237,68 @@ __device__ inline Rows job_rows(const VerifyArgs &a, int b, const SampleJob &job
     return r;
 }
 
-// ---- pass 1 ----------------------------------------------------------------------
-template <int TD, int DD>
-__global__ __launch_bounds__(kVBlock) void verify_pass1(VerifyArgs a)
+// ---- head kernel: one workgroup per sequence ------------------------------------------
+__global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
 {
     __shared__ Partial sh_part[kStageCap];
     __shared__ uint8_t sh_dec[kScanCap];
     __shared__ uint32_t sh_flags;
     __shared__ int32_t sh_bcast[8];
+    verify_head(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast);
+}
+
+// ---- pass 1: slice sums of e_p, e_q ------------------------------------------------------
+// A slice is kSampleSlice = 4096 elements: thread t owns the 8-element runs t and t + 256 of it.
+template <int TD, int DD>
+__global__ __launch_bounds__(kVBlock) void verify_pass1(VerifyArgs a)
+{
     __shared__ double shT[256];
-    __shared__ double sh4[4];
+    __shared__ double sh8[8];
     const int b = blockIdx.y, s = blockIdx.x;
-    const SampleJob job = verify_head(a, b, s == 0, sh_part, sh_dec, &sh_flags, sh_bcast);
+    const SampleJob job = a.jobs[b];
     if (job.kind == 0) return;
-    load_table(shT, a.exp_table);
     const Rows r = job_rows<TD, DD>(a, b, job);
-    const int j = s * kSampleSlice + threadIdx.x * kPer;
+    float xt[kRuns][kPer], xd[kRuns][kPer];
+#pragma unroll
+    for (int g = 0; g < kRuns; ++g) {
+        const int j = s * kSampleSlice + (g * kVBlock + threadIdx.x) * kPer;
+        load8<TD>(r.trow, r.t_al, j, a.V, xt[g]);
+        if (job.kind == 1) load8<DD>(r.drow, r.d_al, j, a.V, xd[g]);
+    }
+    load_table(shT, a.exp_table);
     const double ref_p = (double)job.ref_p, ref_q = (double)job.ref_q;
-    float xt[kPer], xd[kPer];
-    load8<TD>(r.trow, r.t_al, j, a.V, xt);
-    if (job.kind == 1) load8<DD>(r.drow, r.d_al, j, a.V, xd);
     double sp = 0.0, sq = 0.0;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-        sp += exp_tab((double)xt[i] - ref_p, shT);
-        if (job.kind == 1) sq += exp_tab((double)xd[i] - ref_q, shT);
-    }
-    sp = block_sum_d(sp, sh4);
-    sq = block_sum_d(sq, sh4);
+    for (int g = 0; g < kRuns; ++g)
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            sp += exp_tab((double)xt[g][i] - ref_p, shT);
+            if (job.kind == 1) sq += exp_tab((double)xd[g][i] - ref_q, shT);
+        }
+    block_sum2_d(sp, sq, sh8);
     if (threadIdx.x == 0) {
         a.part1[((int64_t)b * a.nsl + s) * 2 + 0] = sp;
         a.part1[((int64_t)b * a.nsl + s) * 2 + 1] = sq;
     }
 }
 
-// Normalisers of the sequence from the slice sums of pass 1: every workgroup adds the same numbers
-// in the same order.  A draft row whose sum is not a positive finite number cannot be resampled
-// from: the draw then comes from the target row alone.
-__device__ inline Weights make_weights(const VerifyArgs &a, const SampleJob &job, int b, double *sh4, bool *draft_bad)
+// Normalisers of the sequence from the slice sums of pass 1, computed by the first wavefront in a
+// fixed order (every workgroup of the sequence gets bit-identical values) and handed to the other
+// wavefronts through LDS.  A draft row whose sum is not a positive finite number cannot be
+// resampled from: the draw then comes from the target row alone.
+__device__ inline Weights make_weights(const VerifyArgs &a, const SampleJob &job, int b, double *sh2, bool *draft_bad)
 {
-    double sp = 0.0, sq = 0.0;
-    for (int s = threadIdx.x; s < a.nsl; s += blockDim.x) {
-        sp += a.part1[((int64_t)b * a.nsl + s) * 2 + 0];
-        sq += a.part1[((int64_t)b * a.nsl + s) * 2 + 1];
+    if (threadIdx.x < kWave) {
+        double sp = 0.0, sq = 0.0;
+        for (int s = threadIdx.x; s < a.nsl; s += kWave) {
+            sp += a.part1[((int64_t)b * a.nsl + s) * 2 + 0];
+            sq += a.part1[((int64_t)b * a.nsl + s) * 2 + 1];
+        }
+        sp = wave_sum_d(sp); sq = wave_sum_d(sq);
+        if (threadIdx.x == 0) { sh2[0] = sp; sh2[1] = sq; }
     }
-    const double Sp = block_sum_d(sp, sh4);
-    const double Sq = block_sum_d(sq, sh4);
+    __syncthreads();
+    const double Sp = sh2[0], Sq = sh2[1];
     Weights w;
     w.kind = job.kind;
     w.ref_p = (double)job.ref_p; w.ref_q = (double)job.ref_q;
@@ -334,56 +312,126 @@ __device__ inline Weights make_weights(const VerifyArgs &a, const SampleJob &job
     return w;
 }
 
-// ---- pass 2 ----------------------------------------------------------------------
+template <int TD, int DD>
+__device__ inline double weight_of(const Weights &w, float xt, float xd, const double *T)
+{
+    double p = exp_tab((double)xt - w.ref_p, T) * w.inv_Sp;
+    if (w.kind == 1) {
+        const double q = exp_tab((double)xd - w.ref_q, T) * w.inv_Sq;
+        p -= q;
+        p = p > 0.0 ? p : 0.0;
+    }
+    return p;
+}
+
+// ---- pass 2: slice weights ---------------------------------------------------------------
 template <int TD, int DD>
 __global__ __launch_bounds__(kVBlock) void verify_pass2(VerifyArgs a)
 {
     __shared__ double shT[256];
-    __shared__ double sh4[4];
+    __shared__ double sh8[8];
+    __shared__ double sh2[2];
     const int b = blockIdx.y, s = blockIdx.x;
     const SampleJob job = a.jobs[b];
     if (job.kind == 0) return;
-    load_table(shT, a.exp_table);
-    bool draft_bad;
-    const Weights w = make_weights(a, job, b, sh4, &draft_bad);
     const Rows r = job_rows<TD, DD>(a, b, job);
-    double wv[kPer];
-    thread_weights<TD, DD>(w, r.trow, r.t_al, r.drow, r.d_al, s, a.V, shT, wv);
-    double z = 0.0;
+    float xt[kRuns][kPer], xd[kRuns][kPer];
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) z += wv[i];
-    z = block_sum_d(z, sh4);
+    for (int g = 0; g < kRuns; ++g) {
+        const int j = s * kSampleSlice + (g * kVBlock + threadIdx.x) * kPer;
+        load8<TD>(r.trow, r.t_al, j, a.V, xt[g]);
+        if (job.kind == 1) load8<DD>(r.drow, r.d_al, j, a.V, xd[g]);
+        else {
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) xd[g][i] = 0.0f;
+        }
+    }
+    for (int i = threadIdx.x; i < 256; i += blockDim.x) shT[i] = a.exp_table[i];
+    bool draft_bad;
+    const Weights w = make_weights(a, job, b, sh2, &draft_bad);      // its barrier also publishes the table
+    double z = 0.0, unused = 0.0;
+#pragma unroll
+    for (int g = 0; g < kRuns; ++g)
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) z += weight_of<TD, DD>(w, xt[g][i], xd[g][i], shT);
+    block_sum2_d(z, unused, sh8);
     if (threadIdx.x == 0) a.part2[(int64_t)b * a.nsl + s] = z;
 }
 
-// ---- pass 3 ----------------------------------------------------------------------
-// Locate inside slice s: first element whose running sum (starting at `cum`) exceeds `target`.
-// Returns the element index or -1; *last_pos collects the largest index with positive weight seen.
-template <int TD, int DD>
-__device__ inline int locate_in_slice(const Weights &w, const Rows &r, int s, int V, const double *shT,
-                                      double cum, double target, double *sh4, int *sh_hit, int *last_pos, double *slice_total)
+// ---- pass 3: locate, one workgroup per sequence ------------------------------------------------
+constexpr int kThreadPer = kSampleSlice / kVBlock;     // 16 consecutive elements per thread inside the located slice
+
+// Exclusive scan of one double per thread over the workgroup (thread order); *total = sum.  One barrier;
+// sh4 must not be in use by a previous call that other wavefronts may still be reading.
+__device__ inline double block_excl_scan_d(double v, double *sh4, double *total)
 {
-    double wv[kPer];
-    thread_weights<TD, DD>(w, r.trow, r.t_al, r.drow, r.d_al, s, V, shT, wv);
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    double inc = v;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        double up = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += up;
+    }
+    if (lane == kWave - 1) sh4[wave] = inc;
+    __syncthreads();
+    double base = 0.0;
+#pragma unroll
+    for (int w2 = 0; w2 < kVBlock / kWave; ++w2) base += (w2 < wave) ? sh4[w2] : 0.0;
+    *total = ((sh4[0] + sh4[1]) + sh4[2]) + sh4[3];
+    return base + (inc - v);
+}
+
+// Weights of the 16 consecutive elements this thread owns in slice s.
+template <int TD, int DD>
+__device__ inline void thread_weights(const Weights &w, const Rows &r, int s, int V, const double *T, double (&wv)[kThreadPer])
+{
+    const int j0 = s * kSampleSlice + threadIdx.x * kThreadPer;
+#pragma unroll
+    for (int g = 0; g < kThreadPer / kPer; ++g) {
+        float xt[kPer], xd[kPer];
+        load8<TD>(r.trow, r.t_al, j0 + g * kPer, V, xt);
+        if (w.kind == 1) load8<DD>(r.drow, r.d_al, j0 + g * kPer, V, xd);
+        else {
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) xd[i] = 0.0f;
+        }
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) wv[g * kPer + i] = weight_of<TD, DD>(w, xt[i], xd[i], T);
+    }
+}
+
+struct LocateShared {
+    double scan[2][4];      // alternating buffers of block_excl_scan_d
+    int hit, last;
+};
+
+// First element of slice s whose running sum (starting at cum) exceeds target, or -1.
+// sh->last collects the largest index with positive weight seen; *slice_total: the slice's weight as scanned.
+// `phase` alternates between calls so that consecutive scans use different LDS buffers.
+template <int TD, int DD>
+__device__ inline int locate_in_slice(const Weights &w, const Rows &r, int s, int V, const double *T,
+                                      double cum, double target, LocateShared *sh, int phase, double *slice_total)
+{
+    double wv[kThreadPer];
+    thread_weights<TD, DD>(w, r, s, V, T, wv);
     double sum = 0.0;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) sum += wv[i];
-    const double excl = block_excl_scan_d(sum, sh4, slice_total);
-    if (threadIdx.x == 0) *sh_hit = 0x7fffffff;
-    __syncthreads();
-    const int j0 = s * kSampleSlice + threadIdx.x * kPer;
+    for (int i = 0; i < kThreadPer; ++i) sum += wv[i];
+    if (threadIdx.x == 0) sh->hit = 0x7fffffff;
+    const double excl = block_excl_scan_d(sum, sh->scan[phase & 1], slice_total);     // barrier: also publishes hit
+    const int j0 = s * kSampleSlice + threadIdx.x * kThreadPer;
     double c = cum + excl;
     int hit = 0x7fffffff, lp = -1;
 #pragma unroll
-    for (int i = 0; i < kPer; ++i) {
+    for (int i = 0; i < kThreadPer; ++i) {
         c += wv[i];
         if (wv[i] > 0.0) lp = j0 + i;
         if (hit == 0x7fffffff && j0 + i < V && c > target) hit = j0 + i;
     }
-    if (hit != 0x7fffffff) atomicMin(sh_hit, hit);
-    if (lp >= 0) atomicMax(last_pos, lp);
+    if (hit != 0x7fffffff) atomicMin(&sh->hit, hit);
+    if (lp >= 0) atomicMax(&sh->last, lp);
     __syncthreads();
-    const int h = *sh_hit;
+    const int h = sh->hit;
     __syncthreads();
     return h == 0x7fffffff ? -1 : h;
 }
@@ -392,91 +440,98 @@ template <int TD, int DD>
 __global__ __launch_bounds__(kVBlock) void verify_pass3(VerifyArgs a)
 {
     __shared__ double shT[256];
-    __shared__ double sh4[4];
-    __shared__ int sh_hit, sh_last, sh_slice;
+    __shared__ double sh2[2];
+    __shared__ double sh_cum[2];
+    __shared__ int sh_slice;
+    __shared__ LocateShared shl;
     const int b = blockIdx.x;
+    const int tid = threadIdx.x;
     const SampleJob job = a.jobs[b];
     if (job.kind == 0) return;
-    load_table(shT, a.exp_table);
-    bool draft_bad;
-    Weights w = make_weights(a, job, b, sh4, &draft_bad);
-    const Rows r = job_rows<TD, DD>(a, b, job);
-    if (threadIdx.x == 0) { sh_last = -1; sh_slice = 0x7fffffff; }
-    __syncthreads();
-    const double u = (double)a.u_sample[b];
+    const float u32v = a.u_sample[b];
     double *zs = a.part2 + (int64_t)b * a.nsl;
+    const double z_mine = tid < a.nsl ? zs[tid] : 0.0;               // the first 256 slice sums, one per thread
+    for (int i = tid; i < 256; i += kVBlock) shT[i] = a.exp_table[i];
+    if (tid == 0) { shl.last = -1; sh_slice = 0x7fffffff; }
+    bool draft_bad;
+    Weights w = make_weights(a, job, b, sh2, &draft_bad);            // its barrier also publishes the table and the inits
+    const Rows r = job_rows<TD, DD>(a, b, job);
+    const double u = (double)u32v;
+    int phase = 0;
 
-    // total weight (fixed order), then the slice that holds u * Z
-    double zt = 0.0;
-    for (int s = threadIdx.x; s < a.nsl; s += blockDim.x) zt += zs[s];
-    double Z = block_sum_d(zt, sh4);
+    // slice whose inclusive prefix (slice order) first exceeds u * Z
+    double Z, cum_at = 0.0;
+    int s_found = -1;
+    if (a.nsl <= kVBlock) {
+        double tot;
+        const double excl = block_excl_scan_d(z_mine, shl.scan[phase++ & 1], &tot);
+        Z = tot;
+        if (tid < a.nsl && Z > 0.0 && excl + z_mine > u * Z) atomicMin(&sh_slice, tid);
+        __syncthreads();
+        s_found = sh_slice == 0x7fffffff ? -1 : sh_slice;
+        if (tid == s_found) sh_cum[0] = excl;
+        __syncthreads();
+        if (s_found >= 0) cum_at = sh_cum[0];
+    } else {
+        // very large vocabularies: the first thread walks the slice sums
+        if (tid == 0) {
+            double tot = 0.0;
+            for (int s = 0; s < a.nsl; ++s) tot += zs[s];
+            double c = 0.0; int sf = -1;
+            if (tot > 0.0)
+                for (int s = 0; s < a.nsl; ++s) { if (c + zs[s] > u * tot) { sf = s; break; } c += zs[s]; }
+            sh_cum[0] = tot; sh_cum[1] = c; sh_slice = sf;
+        }
+        __syncthreads();
+        Z = sh_cum[0]; cum_at = sh_cum[1]; s_found = sh_slice;
+        __syncthreads();
+    }
     if (!(Z > 0.0) && w.kind == 1) {
         // the residual vanished (p == q up to rounding): draw from the target row itself
         w.kind = 2;
-        __syncthreads();
+        double c = 0.0; int sf = -1; double cat = 0.0;
+        double tot = 0.0;
         for (int s = 0; s < a.nsl; ++s) {
-            double wv[kPer];
-            thread_weights<TD, DD>(w, r.trow, r.t_al, r.drow, r.d_al, s, a.V, shT, wv);
-            double z = 0.0;
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) z += wv[i];
-            z = block_sum_d(z, sh4);
-            if (threadIdx.x == 0) zs[s] = z;
+            double st;
+            locate_in_slice<TD, DD>(w, r, s, a.V, shT, 0.0, INFINITY, &shl, phase++, &st);
+            if (tid == 0) zs[s] = st;
+            tot += st;
         }
         __threadfence_block();
         __syncthreads();
-        zt = 0.0;
-        for (int s = threadIdx.x; s < a.nsl; s += blockDim.x) zt += zs[s];
-        Z = block_sum_d(zt, sh4);
+        Z = tot;
+        if (Z > 0.0)
+            for (int s = 0; s < a.nsl; ++s) { const double v = zs[s]; if (c + v > u * Z) { sf = s; cat = c; break; } c += v; }
+        s_found = sf; cum_at = cat;
+        if (tid == 0) shl.last = -1;
+        __syncthreads();
     }
     int token = -1;
     if (Z > 0.0) {
         const double target = u * Z;
-        // prefix over the slice sums, 256 slices at a time
-        double carry = 0.0, cum_at = 0.0;
-        int s_found = -1;
-        for (int s0 = 0; s0 < a.nsl && s_found < 0; s0 += kVBlock) {
-            const int s = s0 + threadIdx.x;
-            const double v = s < a.nsl ? zs[s] : 0.0;
-            double tot;
-            const double excl = block_excl_scan_d(v, sh4, &tot);
-            if (s < a.nsl && carry + excl + v > target) atomicMin(&sh_slice, s);
-            __syncthreads();
-            const int sf = sh_slice;
-            if (sf != 0x7fffffff) {
-                s_found = sf;
-                // every thread needs the prefix in front of slice sf: the owning thread publishes it
-                if (s == sf) sh4[0] = carry + excl;
-                __syncthreads();
-                cum_at = sh4[0];
-                __syncthreads();
-            }
-            carry += tot;
-        }
         // slice sums and the in-slice scan round differently: if the crossing is not inside the chosen
         // slice, continue into the following ones
         if (s_found >= 0) {
             double cum = cum_at;
             for (int s = s_found; s < a.nsl && token < 0; ++s) {
                 double slice_total;
-                token = locate_in_slice<TD, DD>(w, r, s, a.V, shT, cum, target, sh4, &sh_hit, &sh_last, &slice_total);
+                token = locate_in_slice<TD, DD>(w, r, s, a.V, shT, cum, target, &shl, phase++, &slice_total);
                 cum += slice_total;
             }
         }
         if (token < 0) {
             // rounding left no crossing: the largest index with positive weight
-            __syncthreads();
-            if (sh_last < 0) {
+            if (shl.last < 0) {
+                __syncthreads();
                 for (int s = 0; s < a.nsl; ++s) {
                     double slice_total;
-                    locate_in_slice<TD, DD>(w, r, s, a.V, shT, 0.0, INFINITY, sh4, &sh_hit, &sh_last, &slice_total);
+                    locate_in_slice<TD, DD>(w, r, s, a.V, shT, 0.0, INFINITY, &shl, phase++, &slice_total);
                 }
-                __syncthreads();
             }
-            token = sh_last;
+            token = shl.last;
         }
     }
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
         if (token < 0) token = 0;
         a.out_tok[(int64_t)b * (a.K + 1) + job.row] = token;
         if (draft_bad) {
@@ -501,6 +556,10 @@ hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st)
 
 hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st)
 {
+    if (pass == 0) {
+        hipLaunchKernelGGL(verify_head_kernel, dim3(a.B), dim3(kVBlock), 0, st, a);
+        return hipGetLastError();
+    }
     if (a.t_dtype == TAPOUT_F32)
         return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_F32, TAPOUT_F32>(a, pass, st) : launch_typed<TAPOUT_F32, TAPOUT_BF16>(a, pass, st);
     return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_BF16, TAPOUT_F32>(a, pass, st) : launch_typed<TAPOUT_BF16, TAPOUT_BF16>(a, pass, st);

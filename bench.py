@@ -34,9 +34,12 @@ def parse():
                     help="full: verify all K drafted tokens (stop signals still computed); truncate: verify up to the stop position")
     ap.add_argument("--ring", type=int, default=0, help="pre-generated rounds to rotate through (0: enough for > 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seqs", type=int, default=0, help="sequences of one round the oracle is timed on (0: auto)")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="wall-time budget of the CPU-oracle leg")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel with events (perturbs the step time slightly)")
     ap.add_argument("--opt", action="append", default=[], help="library tuning option name=value")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run 8 plain device copies of 512 MiB (torch copy_): a kernel of known traffic that scales "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     return ap.parse_args()
 
 
@@ -102,15 +105,30 @@ def main():
     ed, et = esz[w.draft_dtype], esz[w.target_dtype]
     stream_bytes = w.V * (draft_rows * ed + target_rows * et)          # every logit of a live row once
 
+    def measured_traffic(kernel_name):
+        """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, copy-kernel calibrated) from the committed rocprofv3 --pmc summary."""
+        path = os.path.join(ROOT, "profiles", f"stream_pass_{w.name}_hbm_traffic.txt")
+        if not os.path.exists(path):
+            return None
+        total, seen = 0.0, 0
+        for line in open(path):
+            if kernel_name in line and "MB per launch" in line:
+                total += float(line.split("->")[1].split("MB per launch")[0]) * 1e6
+                seen += 1
+        return int(total) if seen == 2 else None
+
+    kernel_of = {"target_pass": f"stream_pass_kernel<{1 if w.target_dtype == torch.bfloat16 else 0}, false>",
+                 "draft_pass": f"stream_pass_kernel<{1 if w.draft_dtype == torch.bfloat16 else 0}, true>"}
+
     def roof(kind, nbytes):
         ms, n = prof[kind]
         if n == 0:
             return None
         avg_us = ms / n * 1e3
         gbs = nbytes / n / (avg_us * 1e-6) / 1e9
-        return dict(kernel=kind, bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+        return dict(kernel=kernel_of[kind], bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(gbs / HBM_PEAK_GBS, 4), avg_us=round(avg_us, 2), launches=n,
-                    bytes_per_launch=nbytes // n, traffic=None)
+                    bytes_per_launch=nbytes // n, traffic=measured_traffic(kernel_of[kind]) if not truncate else None)
 
     r_target = roof("target_pass", w.V * target_rows * et)
     r_draft = roof("draft_pass", w.V * draft_rows * ed)
@@ -138,38 +156,47 @@ def main():
     if args.profile_all:
         out["kernel_avg_us"] = {k: round(prof[k][0] / max(1, prof[k][1]) * 1e3, 2) for k in kinds}
 
+    if args.copy_calibration:
+        src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(8):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read_per_copy": src.numel(), "bytes_written_per_copy": src.numel(), "copies": 8}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, ring[0], truncate, args.cpu_seqs)
+        out["cpu_baseline"] = cpu_baseline(w, ring, truncate, args.cpu_seconds)
     print(json.dumps(out))
 
 
-def cpu_baseline(w, rnd, truncate, n_seq):
-    """The CPU oracle, as it stands, on a bounded sample of the same round (whole sequences), all host cores."""
+def cpu_baseline(w, ring, truncate, budget_s):
+    """The CPU oracle, as it stands, on whole rounds of the same workload (cycling through the
+    pre-generated ring) until about `budget_s` seconds of wall time are spent; all host cores."""
     import numpy as np
     from oracle import oracle as orc
     cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")))
-    if n_seq <= 0:
-        # about 1e9 element visits keep the leg within roughly 10-30 s on 16 cores
-        per_seq = w.V * (2 * w.K + 1) * 3.5
-        n_seq = int(max(1, min(w.B, 1.2e9 // per_seq)))
-    seqs = list(range(n_seq))
-    draft = orc.as_logits(rnd["draft"][seqs].cpu())
-    target = orc.as_logits(rnd["target"][seqs].cpu())
-    tok = rnd["draft_tok"][seqs].cpu().numpy()
-    k_len = rnd["k_len"][seqs].cpu().numpy()
-    greedy = rnd["greedy"][seqs].cpu().numpy()
-    ua, us = rnd["u_accept"][seqs].cpu().numpy(), rnd["u_sample"][seqs].cpu().numpy()
-    bandit = orc.Bandit(orc.POLICY_UCB1 if w.policy == "ucb1" else orc.POLICY_TS_BETA, n_seq, w.n_arms)
-    u_ts = rnd["u_ts"][seqs].cpu().numpy()
+    host = []
+    for rnd in ring:
+        host.append(dict(draft=orc.as_logits(rnd["draft"].cpu()), target=orc.as_logits(rnd["target"].cpu()),
+                         tok=rnd["draft_tok"].cpu().numpy(), k_len=rnd["k_len"].cpu().numpy(),
+                         greedy=rnd["greedy"].cpu().numpy(), ua=rnd["u_accept"].cpu().numpy(),
+                         us=rnd["u_sample"].cpu().numpy(), u_ts=rnd["u_ts"].cpu().numpy()))
+    bandit = orc.Bandit(orc.POLICY_UCB1 if w.policy == "ucb1" else orc.POLICY_TS_BETA, w.B, w.n_arms)
+    tokens, rounds = 0, 0
     t0 = time.perf_counter()
-    arm, _ = bandit.select(n_seq, u_ts)
-    ds = orc.draft_stats(draft, draft_tok=tok, k_len=k_len, arm=arm, nthreads=cores)
-    nd = ds["n_stop"] if truncate else k_len
-    vf = orc.verify(target, draft, ds["logq_tok"], tok, nd, ua, us, greedy=greedy, nthreads=cores)
-    bandit.update(arm, vf["accept_len"], nd, k_len)
-    dt = time.perf_counter() - t0
-    return {"value": round(float(np.sum(nd)) / dt, 1), "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"{n_seq} of {w.B} sequences of one round ({int(np.sum(nd))} drafted tokens), {dt:.1f} s"}
+    while True:
+        h = host[rounds % len(host)]
+        arm, _ = bandit.select(w.B, h["u_ts"])
+        ds = orc.draft_stats(h["draft"], draft_tok=h["tok"], k_len=h["k_len"], arm=arm, nthreads=cores)
+        nd = ds["n_stop"] if truncate else h["k_len"]
+        vf = orc.verify(h["target"], h["draft"], ds["logq_tok"], h["tok"], nd, h["ua"], h["us"], greedy=h["greedy"], nthreads=cores)
+        bandit.update(arm, vf["accept_len"], nd, h["k_len"])
+        tokens += int(np.sum(nd))
+        rounds += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s:
+            break
+    return {"value": round(tokens / dt, 1), "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"{rounds} whole rounds of the workload ({tokens} drafted tokens) in {dt:.1f} s"}
 
 
 if __name__ == "__main__":

@@ -239,10 +239,10 @@ TAPOUT_API tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, in
 
 /*
  * Kernel timing for benchmarks (host).  tapout_profile_enable makes the
- * library bracket each launch of the selected kernels with a pair of HIP events
- * on the caller's stream (kind_mask: bit k = kernel k below; at most
- * max_records launches per kernel between two reads; 0 switches timing off and
- * releases the events).  tapout_profile_read synchronises `stream`, returns the
+ * library attach a pair of HIP events to each launch of the selected kernels;
+ * the runtime stamps them with the begin and end of the kernel's execution
+ * (kind_mask: bit k = kernel k below; at most max_records launches per kernel
+ * between two reads; 0 switches timing off and releases the events).  tapout_profile_read synchronises `stream`, returns the
  * summed elapsed time and the number of launches recorded for one kernel since
  * the last read, and rewinds that kernel's records.  No device memory is
  * involved; timing is off by default.

@@ -80,18 +80,15 @@ const char *check_logits(const tapout_logits *l, const char *name, int V, int ro
     return nullptr;
 }
 
-// Enqueue one kernel; when timing of `kind` is on, bracket it with an event pair on the same stream.
+// Enqueue one kernel; when timing of `kind` is on, hand the launcher an event pair that the
+// runtime stamps with the begin and end of the kernel's execution.
 template <class F>
-hipError_t timed(tapout_ctx *ctx, int kind, hipStream_t st, F launch)
+hipError_t timed(tapout_ctx *ctx, int kind, F launch)
 {
     const bool on = (ctx->prof_mask >> kind) & 1u && ctx->prof_used[kind] < ctx->prof_cap;
-    if (!on) return launch();
+    if (!on) return launch(Timing{});
     const int i = ctx->prof_used[kind];
-    hipError_t e = hipEventRecord(ctx->prof_start[kind][i], st);
-    if (e != hipSuccess) return e;
-    e = launch();
-    if (e != hipSuccess) return e;
-    e = hipEventRecord(ctx->prof_stop[kind][i], st);
+    hipError_t e = launch(Timing{ctx->prof_start[kind][i], ctx->prof_stop[kind][i]});
     if (e == hipSuccess) ctx->prof_used[kind] = i + 1;
     return e;
 }
@@ -225,7 +222,7 @@ tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const float *u_ts
     DeviceGuard guard(ctx->cfg.device);
     BanditArgs a{ctx->cfg.policy, ctx->cfg.n_bandits, ctx->cfg.n_arms, B, ctx->cfg.alpha, ctx->sum_r, ctx->count};
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = timed(ctx, TAPOUT_PROFILE_SELECT, st, [&] { return launch_bandit_select(a, u_ts, arm_out, flags, st); });
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_SELECT, [&](Timing tm) { return launch_bandit_select(a, u_ts, arm_out, flags, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_select launch");
 }
 
@@ -240,7 +237,7 @@ tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *ar
     DeviceGuard guard(ctx->cfg.device);
     BanditArgs a{ctx->cfg.policy, ctx->cfg.n_bandits, ctx->cfg.n_arms, B, ctx->cfg.alpha, ctx->sum_r, ctx->count};
     hipStream_t st = (hipStream_t)stream;
-    hipError_t e = timed(ctx, TAPOUT_PROFILE_UPDATE, st, [&] { return launch_bandit_update(a, arm, accept_len, n_draft, gamma, active, st); });
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_UPDATE, [&](Timing tm) { return launch_bandit_update(a, arm, accept_len, n_draft, gamma, active, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_update launch");
 }
 
@@ -265,7 +262,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, (int32_t)rows, k_len, 0, ctx->part};
-    hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, st, [&] { return launch_row_reduce(r, draft->dtype, true, st); });
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, [&](Timing tm) { return launch_row_reduce(r, draft->dtype, true, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "draft pass launch");
     DraftFinalArgs f{};
     f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
@@ -275,7 +272,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) { f.rule[a] = ctx->cfg.rule[a]; f.threshold[a] = ctx->cfg.threshold[a]; }
     f.lse = lse; f.entropy = entropy; f.p_top1 = p_top1; f.p_top2 = p_top2; f.margin = margin; f.logq_tok = logq_tok;
     f.top1_id = top1_id; f.n_stop = n_stop; f.stop_fired = stop_fired; f.flags = flags;
-    e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, st, [&] { return launch_draft_finalize(f, st); });
+    e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, [&](Timing tm) { return launch_draft_finalize(f, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft finalize launch");
 }
 
@@ -305,7 +302,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, (int32_t)rows, n_draft, 1, ctx->part};
-    hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_PASS, st, [&] { return launch_row_reduce(r, target->dtype, false, st); });
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_PASS, [&](Timing tm) { return launch_row_reduce(r, target->dtype, false, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "target pass launch");
 
     VerifyArgs va{};
@@ -320,7 +317,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
     va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
     for (int pass = 0; pass <= 3 && e == hipSuccess; ++pass)
-        e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, st, [&] { return launch_verify(va, pass, st); });
+        e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, [&](Timing tm) { return launch_verify(va, pass, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "verify launch");
 }
 

@@ -115,19 +115,19 @@ __global__ void bandit_update_kernel(BanditArgs a, const int32_t *arm, const int
 
 }  // namespace
 
-hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st)
+hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm)
 {
     const int block = 64;
-    hipLaunchKernelGGL(bandit_select_kernel, dim3((a.B + block - 1) / block), dim3(block), 0, st, a, u_ts, arm_out, flags);
+    launch_kernel(bandit_select_kernel, dim3((a.B + block - 1) / block), dim3(block), st, tm, a, u_ts, arm_out, flags);
     return hipGetLastError();
 }
 
 hipError_t launch_bandit_update(const BanditArgs &a, const int32_t *arm, const int32_t *accept_len,
-                                const int32_t *n_draft, const int32_t *gamma, const uint8_t *active, hipStream_t st)
+                                const int32_t *n_draft, const int32_t *gamma, const uint8_t *active, hipStream_t st, Timing tm)
 {
     const int block = 64;
     int grid = a.n_bandits == 1 ? 1 : (a.B + block - 1) / block;
-    hipLaunchKernelGGL(bandit_update_kernel, dim3(grid), dim3(block), 0, st, a, arm, accept_len, n_draft, gamma, active);
+    launch_kernel(bandit_update_kernel, dim3(grid), dim3(block), st, tm, a, arm, accept_len, n_draft, gamma, active);
     return hipGetLastError();
 }
 

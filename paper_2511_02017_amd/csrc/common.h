@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "tapout.h"
@@ -43,6 +44,12 @@ __host__ __device__ inline float ref_of_max(float v1)
     return (v1 == -INFINITY) ? 0.0f : ceilf(v1 * kLog2e);
 }
 
+// Optional timing of one launch: when both events are set the kernel is launched through
+// hipExtLaunchKernelGGL, which stamps them with the begin / end of the kernel's execution itself.
+struct Timing {
+    hipEvent_t start = nullptr, stop = nullptr;
+};
+
 struct RowReduceArgs {
     const void *base;
     int64_t stride_b, stride_k;   // elements
@@ -55,7 +62,7 @@ struct RowReduceArgs {
     Partial *out;                 // [n_rows, nsplit]
 };
 // Streaming pass: one Partial per (row, slice).  Returns hipGetLastError() after enqueueing.
-hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st);
+hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st, Timing tm);
 
 struct DraftFinalArgs {
     const void *base; int32_t dtype; int64_t stride_b, stride_k;
@@ -66,7 +73,7 @@ struct DraftFinalArgs {
     float *lse, *entropy, *p_top1, *p_top2, *margin, *logq_tok;
     int32_t *top1_id, *n_stop; uint8_t *stop_fired; uint32_t *flags;
 };
-hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st);
+hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st, Timing tm);
 
 // Verification + final token.  Kernel 1 merges the target partials of its sequence, takes the
 // accept decisions (every workgroup of the sequence redundantly; slice 0 writes the outputs) and
@@ -88,7 +95,7 @@ struct VerifyArgs {
     double *part2;                // [B, nsl]     weight of each slice
     const double *exp_table;      // 2^(k/256), k = 0..255
 };
-hipError_t launch_verify(const VerifyArgs &a, int pass /*0 = head, 1..3*/, hipStream_t st);
+hipError_t launch_verify(const VerifyArgs &a, int pass /*0 = head, 1..3*/, hipStream_t st, Timing tm);
 
 constexpr int kSampleSlice = 4096;   // elements per slice of the final-token passes
 
@@ -97,12 +104,19 @@ struct BanditArgs {
     double alpha;
     double *sum_r; int64_t *count;
 };
-hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st);
+hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm);
 hipError_t launch_bandit_update(const BanditArgs &a, const int32_t *arm, const int32_t *accept_len,
-                                const int32_t *n_draft, const int32_t *gamma, const uint8_t *active, hipStream_t st);
+                                const int32_t *n_draft, const int32_t *gamma, const uint8_t *active, hipStream_t st, Timing tm);
 
 // ---- device helpers --------------------------------------------------------
 #ifdef __HIPCC__
+
+template <class F, class... Args>
+inline void launch_kernel(F kernel, dim3 grid, dim3 block, hipStream_t st, Timing tm, Args... args)
+{
+    if (tm.start && tm.stop) hipExtLaunchKernelGGL(kernel, grid, block, 0, st, tm.start, tm.stop, 0, args...);
+    else hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+}
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 

@@ -66,20 +66,11 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
                 f |= TAPOUT_FLAG_BAD_ROW;
                 lse = H = p1 = p2 = mg = NAN;
             } else {
-#ifdef TAPOUT_EXP_FLOATMATH
-                double l2S = (double)__log2f((float)r.S);
-#else
                 double l2S = log2(r.S);
-#endif
                 lse_d = (r.R + l2S) * kLn2;
                 double Hd = (l2S - r.T / r.S) * kLn2;
-#ifdef TAPOUT_EXP_FLOATMATH
-                double p1d = (double)exp2f((float)((double)r.M * (double)kLog2e - r.R)) / r.S;
-                double p2d = (a.V > 1) ? (double)exp2f((float)((double)r.v2 * (double)kLog2e - r.R)) / r.S : 0.0;
-#else
                 double p1d = exp2((double)r.M * (double)kLog2e - r.R) / r.S;
                 double p2d = (a.V > 1) ? exp2((double)r.v2 * (double)kLog2e - r.R) / r.S : 0.0;
-#endif
                 lse = (float)lse_d; H = (float)(Hd > 0.0 ? Hd : 0.0);
                 p1 = (float)p1d; p2 = (float)p2d; mg = (float)(p1d - p2d);
             }
@@ -122,9 +113,9 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
 
 }  // namespace
 
-hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st)
+hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st, Timing tm)
 {
-    hipLaunchKernelGGL(draft_finalize_kernel, dim3(a.B), dim3(kFinalBlock), 0, st, a);
+    launch_kernel(draft_finalize_kernel, dim3(a.B), dim3(kFinalBlock), st, tm, a);
     return hipGetLastError();
 }
 

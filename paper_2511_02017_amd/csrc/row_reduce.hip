@@ -250,19 +250,19 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
 }
 
 template <int DT, bool FULL>
-hipError_t launch(const RowReduceArgs &a, hipStream_t st)
+hipError_t launch(const RowReduceArgs &a, hipStream_t st, Timing tm)
 {
     dim3 grid((unsigned)((int64_t)a.n_rows * a.nsplit)), block(kBlock);
-    hipLaunchKernelGGL((stream_pass_kernel<DT, FULL>), grid, block, 0, st, a);
+    launch_kernel(stream_pass_kernel<DT, FULL>, grid, block, st, tm, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st)
+hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st, Timing tm)
 {
-    if (dtype == TAPOUT_F32) return full ? launch<TAPOUT_F32, true>(a, st) : launch<TAPOUT_F32, false>(a, st);
-    return full ? launch<TAPOUT_BF16, true>(a, st) : launch<TAPOUT_BF16, false>(a, st);
+    if (dtype == TAPOUT_F32) return full ? launch<TAPOUT_F32, true>(a, st, tm) : launch<TAPOUT_F32, false>(a, st, tm);
+    return full ? launch<TAPOUT_BF16, true>(a, st, tm) : launch<TAPOUT_BF16, false>(a, st, tm);
 }
 
 }  // namespace tapout

@@ -543,26 +543,26 @@ __global__ __launch_bounds__(kVBlock) void verify_pass3(VerifyArgs a)
 }
 
 template <int TD, int DD>
-hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st)
+hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {
     dim3 grid12(a.nsl, a.B), block(kVBlock);
-    if (pass == 1) hipLaunchKernelGGL((verify_pass1<TD, DD>), grid12, block, 0, st, a);
-    else if (pass == 2) hipLaunchKernelGGL((verify_pass2<TD, DD>), grid12, block, 0, st, a);
-    else hipLaunchKernelGGL((verify_pass3<TD, DD>), dim3(a.B), block, 0, st, a);
+    if (pass == 1) launch_kernel(verify_pass1<TD, DD>, grid12, block, st, tm, a);
+    else if (pass == 2) launch_kernel(verify_pass2<TD, DD>, grid12, block, st, tm, a);
+    else launch_kernel(verify_pass3<TD, DD>, dim3(a.B), block, st, tm, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st)
+hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {
     if (pass == 0) {
-        hipLaunchKernelGGL(verify_head_kernel, dim3(a.B), dim3(kVBlock), 0, st, a);
+        launch_kernel(verify_head_kernel, dim3(a.B), dim3(kVBlock), st, tm, a);
         return hipGetLastError();
     }
     if (a.t_dtype == TAPOUT_F32)
-        return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_F32, TAPOUT_F32>(a, pass, st) : launch_typed<TAPOUT_F32, TAPOUT_BF16>(a, pass, st);
-    return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_BF16, TAPOUT_F32>(a, pass, st) : launch_typed<TAPOUT_BF16, TAPOUT_BF16>(a, pass, st);
+        return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_F32, TAPOUT_F32>(a, pass, st, tm) : launch_typed<TAPOUT_F32, TAPOUT_BF16>(a, pass, st, tm);
+    return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_BF16, TAPOUT_F32>(a, pass, st, tm) : launch_typed<TAPOUT_BF16, TAPOUT_BF16>(a, pass, st, tm);
 }
 
 }  // namespace tapout

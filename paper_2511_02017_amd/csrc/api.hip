@@ -58,6 +58,15 @@ struct DeviceGuard {
     ~DeviceGuard() { if (changed) (void)hipSetDevice(prev); }
 };
 
+// Vectors per slice: a multiple of 64 (whole 1 KB wavefront loads) such that nsplit slices cover a row
+// whatever its alignment (an unaligned row has at most one vector more than an aligned one).
+int slice_vectors(int V, int dtype, int nsplit)
+{
+    const int vec = dtype == TAPOUT_F32 ? 4 : 8;
+    const int nvec = (V + vec - 1) / vec + 1;
+    return (((nvec + nsplit - 1) / nsplit) + 63) & ~63;
+}
+
 int choose_nsplit(const tapout_ctx *ctx, int64_t rows, int V)
 {
     int64_t want = (ctx->wgs_target + rows - 1) / rows;
@@ -138,6 +147,7 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     if (cfg->max_batch < 1 || cfg->max_k < 1 || cfg->vocab < 1)
         return fail(nullptr, TAPOUT_EINVAL, "max_batch, max_k and vocab must be positive");
     if (cfg->max_k > 4096) return fail(nullptr, TAPOUT_EINVAL, "max_k = %d exceeds 4096", cfg->max_k);
+    if (cfg->max_batch > 65535) return fail(nullptr, TAPOUT_EINVAL, "max_batch = %d exceeds 65535", cfg->max_batch);
     if ((int64_t)cfg->max_batch * (cfg->max_k + 1) > (int64_t)1 << 26)
         return fail(nullptr, TAPOUT_EINVAL, "max_batch * (max_k + 1) exceeds 2^26 rows");
     if (cfg->n_arms < 1 || cfg->n_arms > TAPOUT_MAX_ARMS) return fail(nullptr, TAPOUT_EINVAL, "n_arms = %d outside [1, %d]", cfg->n_arms, TAPOUT_MAX_ARMS);
@@ -261,7 +271,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     const int nsplit = choose_nsplit(ctx, rows, V);
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
-    RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, (int32_t)rows, k_len, 0, ctx->part};
+    RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, slice_vectors(V, draft->dtype, nsplit), (int32_t)rows, k_len, 0, ctx->part};
     hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, [&](Timing tm) { return launch_row_reduce(r, draft->dtype, true, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "draft pass launch");
     DraftFinalArgs f{};
@@ -301,7 +311,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     const int nsplit = choose_nsplit(ctx, rows, V);
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
-    RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, (int32_t)rows, n_draft, 1, ctx->part};
+    RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, slice_vectors(V, target->dtype, nsplit), (int32_t)rows, n_draft, 1, ctx->part};
     hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_PASS, [&](Timing tm) { return launch_row_reduce(r, target->dtype, false, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "target pass launch");
 

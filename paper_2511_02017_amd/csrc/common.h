@@ -56,6 +56,7 @@ struct RowReduceArgs {
     int32_t V;
     int32_t KK;                   // rows per sequence in this tensor (K for draft, K+1 for target)
     int32_t nsplit;               // workgroups per row
+    int32_t per;                  // 16-byte vectors per slice (multiple of 64; nsplit * per covers any row)
     int32_t n_rows;               // B * KK
     const int32_t *len;           // draft: k_len (or NULL); target: n_draft
     int32_t len_mode;             // 0: row k active iff k < len[b] (NULL: all); 1: iff k <= clamp(len[b], 1, KK-1)

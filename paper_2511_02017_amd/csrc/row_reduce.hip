@@ -5,8 +5,9 @@
 // One launch covers all rows of a [B, KK, V] tensor.  A row is cut into
 // `nsplit` slices of whole 16-byte vectors; one 256-thread workgroup reduces
 // one slice to a 32-byte Partial.  Every element is loaded exactly once, with
-// 16-byte non-temporal loads that are contiguous across the wavefront; the
-// loads of the next batch are issued before the current batch is folded.
+// 16-byte non-temporal loads that are contiguous across the wavefront, two
+// (draft) or four (target) vectors per thread in flight; eight wavefronts per
+// SIMD hide the latency (explicit double buffering was measured: no gain).
 //
 // Per thread the softmax sums are kept online in the base-2 domain against an
 // integer reference R >= max * log2 e: y = fma(x, log2e, -R) has a single
@@ -160,13 +161,15 @@ template <int DT, bool FULL>
 __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
 {
     constexpr int VEC = Elem<DT>::vec;
-    constexpr int U = 4;
+    // vectors in flight per thread: the draft pass carries more live state per element (second
+    // maximum, entropy sum), so it takes the shallower batch to stay at full occupancy
+    constexpr int U = FULL ? 2 : 4;
     __shared__ float sh_f[4][kBlock / kWave];
     __shared__ int sh_i[kBlock / kWave];
 
-    const int split = blockIdx.x % a.nsplit;
-    const int row = blockIdx.x / a.nsplit;
-    const int b = row / a.KK, k = row % a.KK;
+    // grid = (slice, row of the sequence, sequence): no index arithmetic ahead of the first load
+    const int split = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
+    const int row = b * a.KK + k;
     const int tid = threadIdx.x;
     int n_active;                                   // rows of sequence b this pass reads
     if constexpr (FULL) {
@@ -181,8 +184,9 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
     int head, nvec, tail;
     row_geometry<DT>(rowp, a.V, head, nvec, tail);
     const u32x4 *vp = (const u32x4 *)(rowp + (int64_t)head * Elem<DT>::size);
-    const int per = (nvec + a.nsplit - 1) / a.nsplit;
-    const int v0 = min(split * per, nvec), v1e = min(v0 + per, nvec);
+    // a.per: vectors per slice, chosen on the host as a multiple of 64 (whole 1 KB wavefront loads, so
+    // slices of aligned rows start on cache-line boundaries) with nsplit * per >= the vectors of any row
+    const int v0 = min(split * a.per, nvec), v1e = min(v0 + a.per, nvec);
 
     ThreadState<FULL> st;
     // unaligned head (first slice) and tail (last slice): one element per thread
@@ -191,20 +195,13 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
         st.template fold<1>(x, tid);
     }
     {
-        // ping-pong over batches of U vectors per thread; the other buffer's loads are in flight while one is folded
         const int nbatch = (v1e - v0 + U * kBlock - 1) / (U * kBlock);
-        u32x4 wa[U], wb[U];
         int i = v0 + tid;
-        if (nbatch > 0) load_batch<DT, U>(wa, vp, i, v1e);
-        int bi = 0;
-        for (; bi + 2 <= nbatch; bi += 2) {
-            load_batch<DT, U>(wb, vp, i + U * kBlock, v1e);
-            fold_batch<DT, FULL, U>(st, wa, i, head);
-            if (bi + 2 < nbatch) load_batch<DT, U>(wa, vp, i + 2 * U * kBlock, v1e);
-            fold_batch<DT, FULL, U>(st, wb, i + U * kBlock, head);
-            i += 2 * U * kBlock;
+        for (int bi = 0; bi < nbatch; ++bi, i += U * kBlock) {
+            u32x4 w[U];
+            load_batch<DT, U>(w, vp, i, v1e);
+            fold_batch<DT, FULL, U>(st, w, i, head);
         }
-        if (bi < nbatch) fold_batch<DT, FULL, U>(st, wa, i, head);
     }
     if (split == a.nsplit - 1 && tid < tail) {
         int32_t j = head + nvec * VEC + tid;
@@ -252,7 +249,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
 template <int DT, bool FULL>
 hipError_t launch(const RowReduceArgs &a, hipStream_t st, Timing tm)
 {
-    dim3 grid((unsigned)((int64_t)a.n_rows * a.nsplit)), block(kBlock);
+    dim3 grid((unsigned)a.nsplit, (unsigned)a.KK, (unsigned)(a.n_rows / a.KK)), block(kBlock);
     launch_kernel(stream_pass_kernel<DT, FULL>, grid, block, st, tm, a);
     return hipGetLastError();
 }

@@ -253,11 +253,10 @@ enum {
     TAPOUT_PROFILE_DRAFT_FINALIZE = 2,  /* signals + stop scan                                      */
     TAPOUT_PROFILE_TARGET_PASS = 3,     /* streaming pass over the target logits                    */
     TAPOUT_PROFILE_VERIFY_HEAD = 4,     /* accept tests, first rejection, emitted prefix            */
-    TAPOUT_PROFILE_VERIFY_PASS1 = 5,    /* final token: normalisers                                 */
-    TAPOUT_PROFILE_VERIFY_PASS2 = 6,    /* final token: slice weights                               */
-    TAPOUT_PROFILE_VERIFY_PASS3 = 7,    /* final token: locate                                      */
-    TAPOUT_PROFILE_UPDATE = 8,          /* bandit update                                            */
-    TAPOUT_PROFILE_KINDS = 9
+    TAPOUT_PROFILE_VERIFY_SLICES = 5,   /* final token: slice sums of the row pair                  */
+    TAPOUT_PROFILE_VERIFY_LOCATE = 6,   /* final token: normalisers, slice, token                   */
+    TAPOUT_PROFILE_UPDATE = 7,          /* bandit update                                            */
+    TAPOUT_PROFILE_KINDS = 8
 };
 TAPOUT_API tapout_status tapout_profile_enable(tapout_ctx *ctx, uint32_t kind_mask, int32_t max_records);
 TAPOUT_API tapout_status tapout_profile_read(tapout_ctx *ctx, int32_t kind, double *total_ms, int32_t *launches, void *stream);

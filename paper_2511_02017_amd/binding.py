@@ -27,7 +27,7 @@ EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_l
            "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
-PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_head", "verify_pass1", "verify_pass2", "verify_pass3", "update")
+PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_head", "verify_slices", "verify_locate", "update")
 
 
 class TapoutConfig(C.Structure):

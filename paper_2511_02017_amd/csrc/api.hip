@@ -174,7 +174,7 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     double table[256];
     for (int k = 0; k < 256; ++k) table[k] = std::exp2((double)k / 256.0);
     bool ok = hipMalloc(&c->part, c->part_cap * sizeof(Partial)) == hipSuccess
-           && hipMalloc(&c->part1, (size_t)cfg->max_batch * c->nsl_max * 2 * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->part1, (size_t)cfg->max_batch * c->nsl_max * 5 * sizeof(double)) == hipSuccess
            && hipMalloc(&c->part2, (size_t)cfg->max_batch * c->nsl_max * sizeof(double)) == hipSuccess
            && hipMalloc(&c->exp_table, sizeof table) == hipSuccess
            && hipMemcpy(c->exp_table, table, sizeof table, hipMemcpyHostToDevice) == hipSuccess
@@ -326,7 +326,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     va.target_lse = target_lse; va.logp_tok = logp_tok; va.target_top1 = target_top1; va.flags = flags;
     va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
     va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
-    for (int pass = 0; pass <= 3 && e == hipSuccess; ++pass)
+    for (int pass = 0; pass <= 2 && e == hipSuccess; ++pass)
         e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, [&](Timing tm) { return launch_verify(va, pass, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "verify launch");
 }

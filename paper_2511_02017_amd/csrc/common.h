@@ -36,6 +36,7 @@ struct SampleJob {
     int32_t row;     // m: target row (and draft row for kind 1) to sample from
     float ref_p;     // exponent reference of the target row (its maximum)
     float ref_q;     // exponent reference of the draft row (its lse)
+    double lam;      // binary32-grade estimate of S_p / S_q in those references (kind 1)
 };
 
 __host__ __device__ inline float ref_of_max(float v1)
@@ -92,11 +93,11 @@ struct VerifyArgs {
     float *target_lse, *logp_tok; int32_t *target_top1; uint32_t *flags;
     uint32_t *flags_ws;           // internal copy of the flags (always present)
     SampleJob *jobs;              // [B]
-    double *part1;                // [B, nsl, 2]  sum e_p, sum e_q of each slice
-    double *part2;                // [B, nsl]     weight of each slice
+    double *part1;                // [B, nsl, 5]  A, B, R~, D, U of each slice
+    double *part2;                // [B, nsl]     exact weight of each slice (slow path)
     const double *exp_table;      // 2^(k/256), k = 0..255
 };
-hipError_t launch_verify(const VerifyArgs &a, int pass /*0 = head, 1..3*/, hipStream_t st, Timing tm);
+hipError_t launch_verify(const VerifyArgs &a, int pass /*0 head, 1 slices, 2 locate*/, hipStream_t st, Timing tm);
 
 constexpr int kSampleSlice = 4096;   // elements per slice of the final-token passes
 

@@ -1,27 +1,36 @@
 // Verification of the drafted tokens and the final token (Algorithm 1, lines
 // 10-11; "verify" = speculative sampling as in the works the paper cites).
 //
-// After the streaming pass over the target rows (row_reduce.hip) four small
+// After the streaming pass over the target rows (row_reduce.hip) three small
 // launches finish the job:
 //
 //   head    one workgroup per sequence merges the target partials, forms
 //           log p(tok), takes the accept decisions u < p(tok)/q(tok), finds the
 //           first rejection m, emits the accepted tokens and describes the draw
 //           of the final token (row pair (m, m), or target row n alone)
-//   pass 1  slice sums of e_p = exp(t - ref_p), e_q = exp(d - ref_q)  -> normalisers
-//   pass 2  slice sums of w = max(0, e_p/S_p - e_q/S_q)   (or e_p/S_p: bonus token)
-//   pass 3  one workgroup per sequence: scan the slice sums, then a scan inside
-//           the slice that contains u * Z: token = smallest j whose inclusive
-//           prefix sum exceeds u * Z
+//   slices  per 4096-element slice of the row pair, in double: A = sum a_j,
+//           B = sum b_j (a = exp(t - ref_p), b = exp(d - ref_q)) and, with the
+//           head's binary32-grade estimate L~ of L = S_p / S_q:
+//           R~ = sum max(0, a_j - L~ b_j), D = sum of b_j over a_j > L~ b_j,
+//           U = sum of b_j over |a_j - L~ b_j| <= eta L~ b_j
+//   locate  one workgroup per sequence: exact L = sum A / sum B; the slice
+//           weights of the residual max(0, a - L b) are R~ - (L - L~) D, exact
+//           except for elements whose sign flips between L~ and L, all of which
+//           are counted in U: the error is at most |L - L~| * sum U.  If that
+//           bound is below 2e-10 of the total weight (it typically is 1e-12)
+//           the slice holding u * Z is found from those sums and the token by
+//           an exact scan inside it; otherwise the slice sums are recomputed
+//           exactly first (slow path).
 //
-// Passes 1-3 are double precision.  With ~1e5 CDF cell edges in [0,1) a binary32
-// evaluation would move an edge across u for about one draw in a hundred; in
-// double the chance is ~1e-11, so the token agrees with a sequential fp64
-// evaluation.  Only one row pair per sequence is touched (2/(2K+1) of the
-// round's logits).  exp() is evaluated as 2^(n/256) * (1 + r + r^2/2 + r^3/6),
-// |r| <= ln2/512, with a 256-entry table in LDS: relative error < 2e-13, far
-// inside what the 1e-9 decision margin needs, at a third of the instructions of
-// a correctly rounded exp.
+// token = smallest j whose inclusive prefix sum exceeds u * Z.  Everything is
+// double precision: with ~1e5 CDF cell edges in [0,1) a binary32 evaluation
+// would move an edge across u for about one draw in a hundred; in double the
+// chance is ~1e-10, so the token agrees with a sequential fp64 evaluation.
+// Only one row pair per sequence is touched (2/(2K+1) of the round's logits),
+// with two exponentials per element.  exp() is 2^(n/256) * (1 + r + r^2/2 +
+// r^3/6), |r| <= ln2/512, with a 256-entry table in LDS: relative error
+// < 2e-13, far inside what the 1e-9 decision margin needs, at a third of the
+// instructions of a correctly rounded exp.
 #include "common.h"
 
 namespace tapout {
@@ -34,36 +43,37 @@ constexpr int kRuns = 2;                      // runs per thread and slice in pa
 static_assert(kVBlock * kPer * kRuns == kSampleSlice, "slice = kRuns 8-element runs per thread");
 
 // ---- double-precision helpers ---------------------------------------------------
-__device__ inline double exp_tab(double y, const double *T)
+constexpr double kExpC = 369.3299304675746;            // 256 / ln 2
+constexpr double kExpC1 = 0.0027076061740622863;       // ln2/256
+constexpr double kExpC2 = kExpC1 * kExpC1 / 2.0;
+constexpr double kExpC3 = kExpC1 * kExpC1 * kExpC1 / 6.0;
+constexpr double kMagic = 6755399441055744.0;          // 1.5 * 2^52: adding it rounds to an integer held in the low mantissa bits
+
+// exp(x - ref) for x <= ref + small.  neg_ref_c = -ref * 256/ln2; lo = ref - 700 as binary32: inputs
+// below it (masked -inf logits, NaN) are treated as ref - 700, i.e. as weight 1e-304.
+__device__ inline double exp_fast(float x, double neg_ref_c, float lo, const double *T)
 {
-    // y <= ~0 in all uses; anything below -745 is 0 in double anyway
-    y = fmax(y, -800.0);
-    const double t = y * 369.3299304675746;                 // 256 / ln 2
-    const double n = rint(t);
-    const double r = fma(n, -0.0027076061740622863, y);      // y - n * ln2/256
-    const int ni = (int)n;
+    const double xd = (double)fmaxf(x, lo);
+    const double t = fma(xd, kExpC, neg_ref_c);          // (x - ref) * 256/ln2
+    const double tm = t + kMagic;
+    const int ni = __double2loint(tm);                   // round(t) in two's complement
+    const double rs = t - (tm - kMagic);                 // remainder in units of ln2/256, |rs| <= 1/2
+    const double q = rs * fma(rs, fma(rs, kExpC3, kExpC2), kExpC1);
     const double tk = T[ni & 255];
-    const double q = r * fma(r, fma(r, 1.0 / 6.0, 0.5), 1.0);
-    return ldexp(fma(tk, q, tk), ni >> 8);
+    const double e = fma(tk, q, tk);                     // in [1, 2): scale by 2^(ni >> 8) through the exponent field
+    return __hiloint2double(__double2hiint(e) + (int)((uint32_t)(ni >> 8) << 20), __double2loint(e));
 }
+
+struct ExpRef {
+    double neg_ref_c; float lo;
+    __device__ inline void set(double ref) { neg_ref_c = -ref * kExpC; lo = (float)(ref - 700.0); }
+};
 
 __device__ inline double wave_sum_d(double v)
 {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
     return v;
-}
-
-// Sums of two values over the workgroup in a fixed order, one barrier.  sh8 must not be in use by a
-// previous call that other wavefronts may still be reading.
-__device__ inline void block_sum2_d(double &v1, double &v2, double *sh8)
-{
-    v1 = wave_sum_d(v1); v2 = wave_sum_d(v2);
-    const int wave = threadIdx.x / kWave;
-    if ((threadIdx.x & (kWave - 1)) == 0) { sh8[wave] = v1; sh8[4 + wave] = v2; }
-    __syncthreads();
-    v1 = (sh8[0] + sh8[1]) + (sh8[2] + sh8[3]);
-    v2 = (sh8[4] + sh8[5]) + (sh8[6] + sh8[7]);
 }
 
 // Eight consecutive elements j .. j+7 of a row, exact in binary32; -inf beyond V.
@@ -87,23 +97,12 @@ __device__ inline void load8(const char *rowp, bool aligned, int j, int V, float
     }
 }
 
-struct Weights {
-    int kind;          // 1 residual max(0, p - q), 2 target row only
-    double ref_p, ref_q, inv_Sp, inv_Sq;
-};
-
-__device__ inline void load_table(double *shT, const double *T)
-{
-    for (int i = threadIdx.x; i < 256; i += blockDim.x) shT[i] = T[i];
-    __syncthreads();
-}
-
 // ---- head: accept decisions of one sequence -----------------------------------------
 // Called by all threads of a workgroup.  Returns the sequence's job (identical in every
 // workgroup of the sequence); with `writer` also writes the sequence's outputs.
 // Accept decisions exist for rows k < n <= K <= kScanCap, so the LDS byte buffer always holds them.
 __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
-                                        Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast)
+                                        Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast, double *sh_lse)
 {
     const int K = a.K;
     int n = a.n_draft[b];
@@ -111,11 +110,11 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     if (n < 1 || n > K) { f0 |= TAPOUT_FLAG_BAD_NDRAFT; n = n < 1 ? 1 : K; }
     const bool greedy = a.greedy ? a.greedy[b] != 0 : false;
     SampleJob job;
-    job.kind = 0; job.row = 0; job.ref_p = 0.0f; job.ref_q = 0.0f;
+    job.kind = 0; job.row = 0; job.ref_p = 0.0f; job.ref_q = 0.0f; job.lam = 0.0;
     if (greedy && !writer) return job;           // greedy sequences have nothing to sample
     if (threadIdx.x == 0) { *sh_flags = f0; sh_bcast[4] = 0; }
     const bool need_top1 = writer || greedy;
-    int last_k = -1; float last_M = 0.0f; int32_t last_top1 = 0;     // the last row this thread merged
+    int last_k = -1; float last_M = 0.0f; int32_t last_top1 = 0; double last_lse = 0.0;     // the last row this thread merged
     const int rows_per_stage = kStageCap / a.nsplit;
     for (int k0 = 0; k0 <= n; k0 += rows_per_stage) {
         const int k1 = min(n + 1, k0 + rows_per_stage);
@@ -165,7 +164,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 if (writer && a.logp_tok) a.logp_tok[i] = lp;
                 sh_dec[k] = acc ? 1 : 0;
             }
-            last_k = k; last_M = r.M; last_top1 = top1;
+            last_k = k; last_M = r.M; last_top1 = top1; last_lse = lse_d;
             if (f) atomicOr(sh_flags, f);
         }
     }
@@ -185,16 +184,17 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     const bool flagged = sh_bcast[1] != 0;
     const uint32_t f = (uint32_t)sh_bcast[2];
     // maximum and argmax of row m: from the thread that merged it, if it still holds them
-    if (last_k == m) { sh_bcast[4] = 1; sh_bcast[5] = __float_as_int(last_M); sh_bcast[6] = last_top1; }
+    if (last_k == m) { sh_bcast[4] = 1; sh_bcast[5] = __float_as_int(last_M); sh_bcast[6] = last_top1; *sh_lse = last_lse; }
     __syncthreads();
-    float Mm; int32_t top1m;
+    float Mm; int32_t top1m; double lse_m;
     if (sh_bcast[4]) {
-        Mm = __int_as_float(sh_bcast[5]); top1m = sh_bcast[6];
+        Mm = __int_as_float(sh_bcast[5]); top1m = sh_bcast[6]; lse_m = *sh_lse;
     } else {                                     // more rows than threads: merge row m once more
         __syncthreads();
         stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + m) * a.nsplit, a.nsplit);
         RowTotal r = merge_partials(sh_part, a.nsplit);
         Mm = r.M;
+        lse_m = (r.R + log2(r.S)) * kLn2;
         top1m = need_top1 ? resolve_argmax(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, m), a.t_dtype, a.V, r.cand, r.M) : 0;
     }
     if (!flagged && !greedy) {
@@ -202,6 +202,9 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         job.row = m;
         job.ref_p = Mm;                          // exponent references: the target row's maximum, the draft row's lse
         job.ref_q = m < n ? a.draft_lse[(int64_t)b * K + m] : 0.0f;
+        // binary32-grade estimate of S_p / S_q in these references (S_q = sum exp(d - lse_q) = 1): lets the
+        // slice pass form the residual before the exact normalisers exist
+        job.lam = exp(lse_m - (double)Mm);
     }
     if (writer) {
         const int32_t final_tok = (flagged || greedy) ? top1m : -1;   // sampled sequences: written by pass 3
@@ -244,16 +247,20 @@ __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
     __shared__ uint8_t sh_dec[kScanCap];
     __shared__ uint32_t sh_flags;
     __shared__ int32_t sh_bcast[8];
-    verify_head(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast);
+    __shared__ double sh_lse;
+    verify_head(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse);
 }
 
-// ---- pass 1: slice sums of e_p, e_q ------------------------------------------------------
+// ---- slice kernel -----------------------------------------------------------------------
 // A slice is kSampleSlice = 4096 elements: thread t owns the 8-element runs t and t + 256 of it.
+constexpr double kEta = 1.0e-5;        // half-width (relative) of the band around L~ whose elements are counted in U
+constexpr int kSliceVals = 5;          // A, B, R~, D, U
+
 template <int TD, int DD>
-__global__ __launch_bounds__(kVBlock) void verify_pass1(VerifyArgs a)
+__global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
 {
     __shared__ double shT[256];
-    __shared__ double sh8[8];
+    __shared__ double sh_red[kSliceVals][kVBlock / kWave];
     const int b = blockIdx.y, s = blockIdx.x;
     const SampleJob job = a.jobs[b];
     if (job.kind == 0) return;
@@ -265,101 +272,46 @@ __global__ __launch_bounds__(kVBlock) void verify_pass1(VerifyArgs a)
         load8<TD>(r.trow, r.t_al, j, a.V, xt[g]);
         if (job.kind == 1) load8<DD>(r.drow, r.d_al, j, a.V, xd[g]);
     }
-    load_table(shT, a.exp_table);
-    const double ref_p = (double)job.ref_p, ref_q = (double)job.ref_q;
-    double sp = 0.0, sq = 0.0;
+    for (int i = threadIdx.x; i < 256; i += kVBlock) shT[i] = a.exp_table[i];
+    __syncthreads();
+    ExpRef rp, rq;
+    rp.set((double)job.ref_p); rq.set((double)job.ref_q);
+    const double lam = job.lam, band = kEta * job.lam;
+    double A = 0.0, Bs = 0.0, R = 0.0, D = 0.0, U = 0.0;
 #pragma unroll
     for (int g = 0; g < kRuns; ++g)
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
-            sp += exp_tab((double)xt[g][i] - ref_p, shT);
-            if (job.kind == 1) sq += exp_tab((double)xd[g][i] - ref_q, shT);
+            const double av = exp_fast(xt[g][i], rp.neg_ref_c, rp.lo, shT);
+            A += av;
+            if (job.kind == 1) {
+                const double bv = exp_fast(xd[g][i], rq.neg_ref_c, rq.lo, shT);
+                const double diff = fma(-lam, bv, av);
+                Bs += bv;
+                R += diff > 0.0 ? diff : 0.0;
+                D += diff > 0.0 ? bv : 0.0;
+                U += fabs(diff) <= band * bv ? bv : 0.0;
+            }
         }
-    block_sum2_d(sp, sq, sh8);
-    if (threadIdx.x == 0) {
-        a.part1[((int64_t)b * a.nsl + s) * 2 + 0] = sp;
-        a.part1[((int64_t)b * a.nsl + s) * 2 + 1] = sq;
-    }
-}
-
-// Normalisers of the sequence from the slice sums of pass 1, computed by the first wavefront in a
-// fixed order (every workgroup of the sequence gets bit-identical values) and handed to the other
-// wavefronts through LDS.  A draft row whose sum is not a positive finite number cannot be
-// resampled from: the draw then comes from the target row alone.
-__device__ inline Weights make_weights(const VerifyArgs &a, const SampleJob &job, int b, double *sh2, bool *draft_bad)
-{
-    if (threadIdx.x < kWave) {
-        double sp = 0.0, sq = 0.0;
-        for (int s = threadIdx.x; s < a.nsl; s += kWave) {
-            sp += a.part1[((int64_t)b * a.nsl + s) * 2 + 0];
-            sq += a.part1[((int64_t)b * a.nsl + s) * 2 + 1];
-        }
-        sp = wave_sum_d(sp); sq = wave_sum_d(sq);
-        if (threadIdx.x == 0) { sh2[0] = sp; sh2[1] = sq; }
-    }
+    A = wave_sum_d(A);
+    if (job.kind == 1) { Bs = wave_sum_d(Bs); R = wave_sum_d(R); D = wave_sum_d(D); U = wave_sum_d(U); }
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) { sh_red[0][wave] = A; sh_red[1][wave] = Bs; sh_red[2][wave] = R; sh_red[3][wave] = D; sh_red[4][wave] = U; }
     __syncthreads();
-    const double Sp = sh2[0], Sq = sh2[1];
-    Weights w;
-    w.kind = job.kind;
-    w.ref_p = (double)job.ref_p; w.ref_q = (double)job.ref_q;
-    w.inv_Sp = 1.0 / Sp;
-    w.inv_Sq = 1.0 / Sq;
-    *draft_bad = false;
-    if (job.kind == 1 && (!(Sq > 0.0) || !(Sq < INFINITY))) {
-        w.kind = 2;
-        *draft_bad = true;
+    if (threadIdx.x < kSliceVals) {
+        const double *v = sh_red[threadIdx.x];
+        a.part1[((int64_t)b * a.nsl + s) * kSliceVals + threadIdx.x] = (v[0] + v[1]) + (v[2] + v[3]);
     }
-    return w;
 }
 
-template <int TD, int DD>
-__device__ inline double weight_of(const Weights &w, float xt, float xd, const double *T)
-{
-    double p = exp_tab((double)xt - w.ref_p, T) * w.inv_Sp;
-    if (w.kind == 1) {
-        const double q = exp_tab((double)xd - w.ref_q, T) * w.inv_Sq;
-        p -= q;
-        p = p > 0.0 ? p : 0.0;
-    }
-    return p;
-}
+// ---- locate kernel: one workgroup per sequence --------------------------------------------
+constexpr int kThreadPer = kSampleSlice / kVBlock;     // 16 consecutive elements per thread inside a slice
 
-// ---- pass 2: slice weights ---------------------------------------------------------------
-template <int TD, int DD>
-__global__ __launch_bounds__(kVBlock) void verify_pass2(VerifyArgs a)
-{
-    __shared__ double shT[256];
-    __shared__ double sh8[8];
-    __shared__ double sh2[2];
-    const int b = blockIdx.y, s = blockIdx.x;
-    const SampleJob job = a.jobs[b];
-    if (job.kind == 0) return;
-    const Rows r = job_rows<TD, DD>(a, b, job);
-    float xt[kRuns][kPer], xd[kRuns][kPer];
-#pragma unroll
-    for (int g = 0; g < kRuns; ++g) {
-        const int j = s * kSampleSlice + (g * kVBlock + threadIdx.x) * kPer;
-        load8<TD>(r.trow, r.t_al, j, a.V, xt[g]);
-        if (job.kind == 1) load8<DD>(r.drow, r.d_al, j, a.V, xd[g]);
-        else {
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) xd[g][i] = 0.0f;
-        }
-    }
-    for (int i = threadIdx.x; i < 256; i += blockDim.x) shT[i] = a.exp_table[i];
-    bool draft_bad;
-    const Weights w = make_weights(a, job, b, sh2, &draft_bad);      // its barrier also publishes the table
-    double z = 0.0, unused = 0.0;
-#pragma unroll
-    for (int g = 0; g < kRuns; ++g)
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) z += weight_of<TD, DD>(w, xt[g][i], xd[g][i], shT);
-    block_sum2_d(z, unused, sh8);
-    if (threadIdx.x == 0) a.part2[(int64_t)b * a.nsl + s] = z;
-}
-
-// ---- pass 3: locate, one workgroup per sequence ------------------------------------------------
-constexpr int kThreadPer = kSampleSlice / kVBlock;     // 16 consecutive elements per thread inside the located slice
+struct Weights {
+    int kind;          // 1 residual max(0, a - L b), 2 target row only (a)
+    double lam;        // exact S_p / S_q
+    ExpRef rp, rq;
+};
 
 // Exclusive scan of one double per thread over the workgroup (thread order); *total = sum.  One barrier;
 // sh4 must not be in use by a previous call that other wavefronts may still be reading.
@@ -391,18 +343,23 @@ __device__ inline void thread_weights(const Weights &w, const Rows &r, int s, in
         float xt[kPer], xd[kPer];
         load8<TD>(r.trow, r.t_al, j0 + g * kPer, V, xt);
         if (w.kind == 1) load8<DD>(r.drow, r.d_al, j0 + g * kPer, V, xd);
-        else {
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) xd[i] = 0.0f;
+        for (int i = 0; i < kPer; ++i) {
+            double v = exp_fast(xt[i], w.rp.neg_ref_c, w.rp.lo, T);
+            if (w.kind == 1) {
+                v = fma(-w.lam, exp_fast(xd[i], w.rq.neg_ref_c, w.rq.lo, T), v);
+                v = v > 0.0 ? v : 0.0;
+            }
+            // masked (-inf) logits carry a stand-in weight of ~1e-304: exactly zero for the scan
+            wv[g * kPer + i] = (j0 + g * kPer + i < V && v > 1.0e-290) ? v : 0.0;
         }
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) wv[g * kPer + i] = weight_of<TD, DD>(w, xt[i], xd[i], T);
     }
 }
 
 struct LocateShared {
     double scan[2][4];      // alternating buffers of block_excl_scan_d
-    int hit, last;
+    double bc[4];           // broadcasts
+    int hit, last, slice;
 };
 
 // First element of slice s whose running sum (starting at cum) exceeds target, or -1.
@@ -437,78 +394,119 @@ __device__ inline int locate_in_slice(const Weights &w, const Rows &r, int s, in
 }
 
 template <int TD, int DD>
-__global__ __launch_bounds__(kVBlock) void verify_pass3(VerifyArgs a)
+__global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
 {
     __shared__ double shT[256];
-    __shared__ double sh2[2];
-    __shared__ double sh_cum[2];
-    __shared__ int sh_slice;
+    __shared__ double sh_red[kSliceVals][kVBlock / kWave];
     __shared__ LocateShared shl;
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
     const SampleJob job = a.jobs[b];
     if (job.kind == 0) return;
     const float u32v = a.u_sample[b];
-    double *zs = a.part2 + (int64_t)b * a.nsl;
-    const double z_mine = tid < a.nsl ? zs[tid] : 0.0;               // the first 256 slice sums, one per thread
+    const double *ps = a.part1 + (int64_t)b * a.nsl * kSliceVals;
+    double *zs = a.part2 + (int64_t)b * a.nsl;                       // exact slice weights (slow path only)
     for (int i = tid; i < 256; i += kVBlock) shT[i] = a.exp_table[i];
-    if (tid == 0) { shl.last = -1; sh_slice = 0x7fffffff; }
-    bool draft_bad;
-    Weights w = make_weights(a, job, b, sh2, &draft_bad);            // its barrier also publishes the table and the inits
+    if (tid == 0) { shl.last = -1; shl.slice = 0x7fffffff; }
+
+    // totals of the five slice quantities, fixed order
+    double tot[kSliceVals];
+    {
+        double acc[kSliceVals] = {0.0, 0.0, 0.0, 0.0, 0.0};
+        for (int s = tid; s < a.nsl; s += kVBlock)
+#pragma unroll
+            for (int q = 0; q < kSliceVals; ++q) acc[q] += ps[s * kSliceVals + q];
+#pragma unroll
+        for (int q = 0; q < kSliceVals; ++q) acc[q] = wave_sum_d(acc[q]);
+        if ((tid & (kWave - 1)) == 0)
+#pragma unroll
+            for (int q = 0; q < kSliceVals; ++q) sh_red[q][tid / kWave] = acc[q];
+        __syncthreads();                                               // also publishes the table and the inits
+#pragma unroll
+        for (int q = 0; q < kSliceVals; ++q) tot[q] = (sh_red[q][0] + sh_red[q][1]) + (sh_red[q][2] + sh_red[q][3]);
+    }
+    const double Sp = tot[0], Sq = tot[1];
+    Weights w;
+    w.kind = job.kind;
+    w.rp.set((double)job.ref_p); w.rq.set((double)job.ref_q);
+    bool draft_bad = false;
+    if (job.kind == 1 && (!(Sq > 0.0) || !(Sq < INFINITY))) {          // NaN / empty draft row: draw from the target row alone
+        w.kind = 2;
+        draft_bad = true;
+    }
+    w.lam = w.kind == 1 ? Sp / Sq : 0.0;
+    const double delta = w.lam - job.lam;
     const Rows r = job_rows<TD, DD>(a, b, job);
     const double u = (double)u32v;
     int phase = 0;
 
-    // slice whose inclusive prefix (slice order) first exceeds u * Z
-    double Z, cum_at = 0.0;
-    int s_found = -1;
-    if (a.nsl <= kVBlock) {
-        double tot;
-        const double excl = block_excl_scan_d(z_mine, shl.scan[phase++ & 1], &tot);
-        Z = tot;
-        if (tid < a.nsl && Z > 0.0 && excl + z_mine > u * Z) atomicMin(&sh_slice, tid);
-        __syncthreads();
-        s_found = sh_slice == 0x7fffffff ? -1 : sh_slice;
-        if (tid == s_found) sh_cum[0] = excl;
-        __syncthreads();
-        if (s_found >= 0) cum_at = sh_cum[0];
-    } else {
-        // very large vocabularies: the first thread walks the slice sums
-        if (tid == 0) {
-            double tot = 0.0;
-            for (int s = 0; s < a.nsl; ++s) tot += zs[s];
-            double c = 0.0; int sf = -1;
-            if (tot > 0.0)
-                for (int s = 0; s < a.nsl; ++s) { if (c + zs[s] > u * tot) { sf = s; break; } c += zs[s]; }
-            sh_cum[0] = tot; sh_cum[1] = c; sh_slice = sf;
+    // slice weights: target row alone -> A_s; residual -> R~_s - delta D_s if the bound on the sign flips allows
+    double Z = w.kind == 2 ? Sp : tot[2] - delta * tot[3];
+    bool exact_sums = false;
+    if (w.kind == 1) {
+        const bool certified = fabs(delta) <= kEta * job.lam && Z > 0.0 && fabs(delta) * tot[4] <= 2.0e-10 * Z;
+        if (!certified) {
+            // slow path: exact slice weights with the exact L (also the p == q case: then Z may vanish)
+            double ztot = 0.0;
+            for (int s = 0; s < a.nsl; ++s) {
+                double st;
+                locate_in_slice<TD, DD>(w, r, s, a.V, shT, 0.0, INFINITY, &shl, phase++, &st);
+                if (tid == 0) zs[s] = st;
+                ztot += st;
+            }
+            Z = ztot;
+            if (!(Z > 0.0)) {
+                // the residual vanished (p == q up to rounding): draw from the target row itself
+                w.kind = 2;
+                ztot = 0.0;
+                for (int s = 0; s < a.nsl; ++s) {
+                    double st;
+                    locate_in_slice<TD, DD>(w, r, s, a.V, shT, 0.0, INFINITY, &shl, phase++, &st);
+                    if (tid == 0) zs[s] = st;
+                    ztot += st;
+                }
+                Z = ztot;
+            }
+            exact_sums = true;
+            if (tid == 0) shl.last = -1;
+            __threadfence_block();
+            __syncthreads();
         }
-        __syncthreads();
-        Z = sh_cum[0]; cum_at = sh_cum[1]; s_found = sh_slice;
-        __syncthreads();
     }
-    if (!(Z > 0.0) && w.kind == 1) {
-        // the residual vanished (p == q up to rounding): draw from the target row itself
-        w.kind = 2;
-        double c = 0.0; int sf = -1; double cat = 0.0;
-        double tot = 0.0;
-        for (int s = 0; s < a.nsl; ++s) {
-            double st;
-            locate_in_slice<TD, DD>(w, r, s, a.V, shT, 0.0, INFINITY, &shl, phase++, &st);
-            if (tid == 0) zs[s] = st;
-            tot += st;
-        }
-        __threadfence_block();
-        __syncthreads();
-        Z = tot;
-        if (Z > 0.0)
-            for (int s = 0; s < a.nsl; ++s) { const double v = zs[s]; if (c + v > u * Z) { sf = s; cat = c; break; } c += v; }
-        s_found = sf; cum_at = cat;
-        if (tid == 0) shl.last = -1;
-        __syncthreads();
-    }
+    auto slice_weight = [&](int s) -> double {
+        if (exact_sums) return zs[s];
+        if (w.kind == 2) return ps[s * kSliceVals + 0];
+        const double v = ps[s * kSliceVals + 2] - delta * ps[s * kSliceVals + 3];
+        return v > 0.0 ? v : 0.0;
+    };
+
     int token = -1;
     if (Z > 0.0) {
         const double target = u * Z;
+        // slice whose inclusive prefix (slice order) first exceeds the target
+        double cum_at = 0.0;
+        int s_found = -1;
+        if (a.nsl <= kVBlock) {
+            const double z_mine = tid < a.nsl ? slice_weight(tid) : 0.0;
+            double ztot;
+            const double excl = block_excl_scan_d(z_mine, shl.scan[phase++ & 1], &ztot);
+            if (tid < a.nsl && excl + z_mine > target) atomicMin(&shl.slice, tid);
+            __syncthreads();
+            s_found = shl.slice == 0x7fffffff ? -1 : shl.slice;
+            if (tid == s_found) shl.bc[0] = excl;
+            __syncthreads();
+            if (s_found >= 0) cum_at = shl.bc[0];
+        } else {
+            // very large vocabularies: the first thread walks the slice weights
+            if (tid == 0) {
+                double c = 0.0; int sf = -1;
+                for (int s = 0; s < a.nsl; ++s) { const double v = slice_weight(s); if (c + v > target) { sf = s; break; } c += v; }
+                shl.bc[0] = c; shl.slice = sf;
+            }
+            __syncthreads();
+            cum_at = shl.bc[0]; s_found = shl.slice;
+            __syncthreads();
+        }
         // slice sums and the in-slice scan round differently: if the crossing is not inside the chosen
         // slice, continue into the following ones
         if (s_found >= 0) {
@@ -546,9 +544,8 @@ template <int TD, int DD>
 hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {
     dim3 grid12(a.nsl, a.B), block(kVBlock);
-    if (pass == 1) launch_kernel(verify_pass1<TD, DD>, grid12, block, st, tm, a);
-    else if (pass == 2) launch_kernel(verify_pass2<TD, DD>, grid12, block, st, tm, a);
-    else launch_kernel(verify_pass3<TD, DD>, dim3(a.B), block, st, tm, a);
+    if (pass == 1) launch_kernel(verify_slices<TD, DD>, grid12, block, st, tm, a);
+    else launch_kernel(verify_locate<TD, DD>, dim3(a.B), block, st, tm, a);
     return hipGetLastError();
 }
 

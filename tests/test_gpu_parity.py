@@ -163,6 +163,36 @@ def test_degenerate_rows(dtype):
     assert not ds["flags"].any() and not vf["flags"].any()
 
 
+@pytest.mark.parametrize("boost", [8.0, 1e-2, 1e-4])
+def test_residual_with_tied_probability_ratios(boost):
+    """target = draft except for a few boosted tokens: p/q is the same number for almost every token.  With a
+    large boost the ratio is clearly below 1 there (fast path); with a tiny boost it sits inside the band in
+    which the sign of p - q cannot be decided from binary32-grade normalisers, which must send the sampler
+    down its exact path.  The drafted tokens avoid the boosted ones and u_accept is ~1, so position 0 is
+    rejected and the final token is a residual draw."""
+    B, K, V = 6, 3, 40000
+    g = torch.Generator(device=DEV).manual_seed(int(boost * 1e5) + 1)
+    d = (torch.randn(B, K, V, generator=g, device=DEV) * 2).float()
+    t = torch.cat([d, torch.randn(B, 1, V, generator=g, device=DEV) * 2], 1).clone()
+    hot = torch.randint(0, V, (B, 5), generator=g, device=DEV)
+    for b in range(B):
+        t[b, :, hot[b]] += boost
+    tok = torch.randint(0, V, (B, K), generator=g, device=DEV, dtype=torch.int32)
+    for b in range(B):
+        clash = (tok[b][:, None] == hot[b][None, :]).any(1)
+        tok[b][clash] = (tok[b][clash] + 7) % V
+    rnd = dict(draft=d, target=t, draft_tok=tok,
+               u_accept=torch.full((B, K), 1.0 - 2.0 ** -24, device=DEV), u_sample=torch.rand(B, generator=g, device=DEV),
+               k_len=torch.full((B,), K, dtype=torch.int32, device=DEV), greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
+    tp = binding.Tapout(B, K, V)
+    c = pu.check_round(tp, rnd)
+    ds, vf, _ = pu.gpu_round(tp, rnd)
+    ok = vf["accept_len"].cpu() == 0
+    assert ok.sum() >= B - c["accept_flagged"]                       # rejected at once unless the accept test itself was a near tie
+    final = vf["out_tok"][:, 0].cpu()
+    assert all(int(final[b]) in hot[b].cpu().tolist() for b in range(B) if ok[b])   # the residual lives on the boosted tokens
+
+
 def test_bad_inputs_set_flags_and_fall_back():
     rnd = degenerate_round(torch.float32)
     B, K, V = rnd["draft"].shape

@@ -35,25 +35,30 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     __shared__ uint32_t sh_flags;
     const int b = blockIdx.x;
     const int K = a.K;
+    const int rows_per_stage = kStageCap / a.nsplit;          // nsplit <= kStageCap is guaranteed by the host
+    const bool want_tok = a.draft_tok && a.logq_tok;
+    // Everything whose address does not depend on k_len is requested before k_len is looked at, so that the
+    // first memory round trip carries k_len, the arm, the tokens and the partials together.  (Rows beyond
+    // k_len hold stale partials and unused tokens: read, never used.)
+    int32_t tok0 = -1;
+    if (want_tok && (int)threadIdx.x < K) tok0 = a.draft_tok[(int64_t)b * K + threadIdx.x];
+    stage_partials(sh_part, a.part + (int64_t)b * K * a.nsplit, min(K, rows_per_stage) * a.nsplit);
     int kb = a.k_len ? a.k_len[b] : K;
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
     const int arm = a.arm ? a.arm[b] : -1;
     const bool arm_ok = arm >= 0 && arm < a.n_arms;
     if (threadIdx.x == 0) sh_flags = 0;
-    const int rows_per_stage = kStageCap / a.nsplit;          // nsplit <= kStageCap is guaranteed by the host
     for (int k0 = 0; k0 < kb; k0 += rows_per_stage) {
         const int k1 = min(kb, k0 + rows_per_stage);
-        // loads that do not depend on the partials go out first: the drafted token and its logit
         const int kmine = k0 + threadIdx.x;                   // first (usually only) row of this thread in the stage
-        int32_t tok0 = -1;
         float xtok0 = 0.0f;
-        if (kmine < k1 && a.draft_tok && a.logq_tok) {
-            tok0 = a.draft_tok[(int64_t)b * K + kmine];
-            if (tok0 >= 0 && tok0 < a.V)
-                xtok0 = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, kmine), a.dtype, tok0);
+        if (k0 > 0) {                                         // further stages (K > rows_per_stage): load late
+            tok0 = (want_tok && kmine < k1) ? a.draft_tok[(int64_t)b * K + kmine] : -1;
+            __syncthreads();
+            stage_partials(sh_part, a.part + ((int64_t)b * K + k0) * a.nsplit, (k1 - k0) * a.nsplit);
         }
-        __syncthreads();
-        stage_partials(sh_part, a.part + ((int64_t)b * K + k0) * a.nsplit, (k1 - k0) * a.nsplit);
+        if (want_tok && kmine < k1 && tok0 >= 0 && tok0 < a.V)
+            xtok0 = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, kmine), a.dtype, tok0);
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t i = (int64_t)b * K + k;
             const void *row = row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);

@@ -69,10 +69,35 @@ struct ExpRef {
     __device__ inline void set(double ref) { neg_ref_c = -ref * kExpC; lo = (float)(ref - 700.0); }
 };
 
+// ---- wavefront reductions and scans of doubles with DPP (no LDS round trips) ---------------
+// quad_perm [1,0,3,2] = 0xB1, quad_perm [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140,
+// row_shr:n = 0x110 + n (lanes without a source inside their 16-lane row read 0).
+template <int CTRL>
+__device__ inline double dpp_d(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xf, 0xf, true);
+    return __hiloint2double(hi, lo);
+}
+__device__ inline double lane_d(double v, int lane)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane), __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+// Sum over the 64 lanes, same value in every lane, fixed order.
 __device__ inline double wave_sum_d(double v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    v += dpp_d<0xB1>(v); v += dpp_d<0x4E>(v); v += dpp_d<0x141>(v); v += dpp_d<0x140>(v);
+    return (lane_d(v, 0) + lane_d(v, 16)) + (lane_d(v, 32) + lane_d(v, 48));
+}
+// Inclusive prefix sum over the 64 lanes (lane order); *total = sum of all lanes.
+__device__ inline double wave_incl_scan_d(double v, double *total)
+{
+    v += dpp_d<0x111>(v); v += dpp_d<0x112>(v); v += dpp_d<0x114>(v); v += dpp_d<0x118>(v);   // inside each 16-lane row
+    const double t0 = lane_d(v, 15), t1 = lane_d(v, 31), t2 = lane_d(v, 47), t3 = lane_d(v, 63);
+    const int rowid = (threadIdx.x & (kWave - 1)) >> 4;
+    const double t01 = t0 + t1, t012 = t01 + t2;
+    v += rowid == 0 ? 0.0 : (rowid == 1 ? t0 : (rowid == 2 ? t01 : t012));
+    *total = t012 + t3;
     return v;
 }
 
@@ -105,33 +130,43 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                                         Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast, double *sh_lse)
 {
     const int K = a.K;
+    const int rows_per_stage = kStageCap / a.nsplit;
+    // Everything whose address does not depend on n_draft is requested before n_draft is looked at, so that
+    // the first memory round trip carries n_draft, the tokens, the uniforms and the partials together.
+    // (Rows beyond n_draft hold stale partials and unused tokens: read, never used.)
+    int32_t tok0 = -1;
+    float u0 = 0.0f, lq0 = 0.0f;
+    if ((int)threadIdx.x < K) {
+        const int64_t i = (int64_t)b * K + threadIdx.x;
+        tok0 = a.draft_tok[i];
+        u0 = a.u_accept[i];
+        lq0 = a.logq_tok[i];
+    }
+    stage_partials(sh_part, a.part + (int64_t)b * (K + 1) * a.nsplit, min(K + 1, rows_per_stage) * a.nsplit);
     int n = a.n_draft[b];
     uint32_t f0 = 0;
     if (n < 1 || n > K) { f0 |= TAPOUT_FLAG_BAD_NDRAFT; n = n < 1 ? 1 : K; }
     const bool greedy = a.greedy ? a.greedy[b] != 0 : false;
     SampleJob job;
     job.kind = 0; job.row = 0; job.ref_p = 0.0f; job.ref_q = 0.0f; job.lam = 0.0;
-    if (greedy && !writer) return job;           // greedy sequences have nothing to sample
     if (threadIdx.x == 0) { *sh_flags = f0; sh_bcast[4] = 0; }
     const bool need_top1 = writer || greedy;
     int last_k = -1; float last_M = 0.0f; int32_t last_top1 = 0; double last_lse = 0.0;     // the last row this thread merged
-    const int rows_per_stage = kStageCap / a.nsplit;
     for (int k0 = 0; k0 <= n; k0 += rows_per_stage) {
         const int k1 = min(n + 1, k0 + rows_per_stage);
-        // loads that do not depend on the partials go out first
         const int kmine = k0 + threadIdx.x;
-        int32_t tok0 = -1;
-        float xtok0 = 0.0f, u0 = 0.0f, lq0 = 0.0f;
-        if (kmine < k1 && kmine < n) {
-            const int64_t i = (int64_t)b * K + kmine;
-            tok0 = a.draft_tok[i];
-            u0 = a.u_accept[i];
-            lq0 = a.logq_tok[i];
-            if (tok0 >= 0 && tok0 < a.V)
-                xtok0 = load_elem_rt(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, kmine), a.t_dtype, tok0);
+        float xtok0 = 0.0f;
+        if (k0 > 0) {                               // further stages (K + 1 > rows_per_stage): load late
+            tok0 = -1;
+            if (kmine < k1 && kmine < n) {
+                const int64_t i = (int64_t)b * K + kmine;
+                tok0 = a.draft_tok[i]; u0 = a.u_accept[i]; lq0 = a.logq_tok[i];
+            }
+            __syncthreads();
+            stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + k0) * a.nsplit, (k1 - k0) * a.nsplit);
         }
-        __syncthreads();
-        stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + k0) * a.nsplit, (k1 - k0) * a.nsplit);
+        if (kmine < k1 && kmine < n && tok0 >= 0 && tok0 < a.V)
+            xtok0 = load_elem_rt(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, kmine), a.t_dtype, tok0);
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t it = (int64_t)b * (K + 1) + k;
             const void *row = row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, k);
@@ -318,13 +353,9 @@ struct Weights {
 __device__ inline double block_excl_scan_d(double v, double *sh4, double *total)
 {
     const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
-    double inc = v;
-#pragma unroll
-    for (int o = 1; o < kWave; o <<= 1) {
-        double up = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += up;
-    }
-    if (lane == kWave - 1) sh4[wave] = inc;
+    double wtot;
+    const double inc = wave_incl_scan_d(v, &wtot);
+    if (lane == 0) sh4[wave] = wtot;
     __syncthreads();
     double base = 0.0;
 #pragma unroll
@@ -359,23 +390,35 @@ __device__ inline void thread_weights(const Weights &w, const Rows &r, int s, in
 struct LocateShared {
     double scan[2][4];      // alternating buffers of block_excl_scan_d
     double bc[4];           // broadcasts
-    int hit, last, slice;
+    int hits[2][4];         // alternating per-wavefront results of locate_in_slice
+    int last, slice;
 };
 
+__device__ inline int wave_min_i32(int v)
+{
+    v = min(v, __builtin_amdgcn_update_dpp(0x7fffffff, v, 0xB1, 0xf, 0xf, false));
+    v = min(v, __builtin_amdgcn_update_dpp(0x7fffffff, v, 0x4E, 0xf, 0xf, false));
+    v = min(v, __builtin_amdgcn_update_dpp(0x7fffffff, v, 0x141, 0xf, 0xf, false));
+    v = min(v, __builtin_amdgcn_update_dpp(0x7fffffff, v, 0x140, 0xf, 0xf, false));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+
 // First element of slice s whose running sum (starting at cum) exceeds target, or -1.
-// sh->last collects the largest index with positive weight seen; *slice_total: the slice's weight as scanned.
-// `phase` alternates between calls so that consecutive scans use different LDS buffers.
+// With track_last, sh->last collects the largest index with positive weight seen (fallback only).
+// *slice_total: the slice's weight as scanned.  `phase` alternates between calls so that consecutive
+// scans use different LDS buffers.
 template <int TD, int DD>
 __device__ inline int locate_in_slice(const Weights &w, const Rows &r, int s, int V, const double *T,
-                                      double cum, double target, LocateShared *sh, int phase, double *slice_total)
+                                      double cum, double target, LocateShared *sh, int phase, double *slice_total,
+                                      bool track_last = false)
 {
     double wv[kThreadPer];
     thread_weights<TD, DD>(w, r, s, V, T, wv);
     double sum = 0.0;
 #pragma unroll
     for (int i = 0; i < kThreadPer; ++i) sum += wv[i];
-    if (threadIdx.x == 0) sh->hit = 0x7fffffff;
-    const double excl = block_excl_scan_d(sum, sh->scan[phase & 1], slice_total);     // barrier: also publishes hit
+    const double excl = block_excl_scan_d(sum, sh->scan[phase & 1], slice_total);
     const int j0 = s * kSampleSlice + threadIdx.x * kThreadPer;
     double c = cum + excl;
     int hit = 0x7fffffff, lp = -1;
@@ -385,11 +428,17 @@ __device__ inline int locate_in_slice(const Weights &w, const Rows &r, int s, in
         if (wv[i] > 0.0) lp = j0 + i;
         if (hit == 0x7fffffff && j0 + i < V && c > target) hit = j0 + i;
     }
-    if (hit != 0x7fffffff) atomicMin(&sh->hit, hit);
-    if (lp >= 0) atomicMax(&sh->last, lp);
+    // one LDS word per wavefront instead of one atomic per thread
+    hit = wave_min_i32(hit);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) sh->hits[phase & 1][wave] = hit;
+    if (track_last) {
+        const int neg = wave_min_i32(-lp);                         // max of lp
+        if ((threadIdx.x & (kWave - 1)) == 0 && -neg >= 0) atomicMax(&sh->last, -neg);
+    }
     __syncthreads();
-    const int h = sh->hit;
-    __syncthreads();
+    const int *hh = sh->hits[phase & 1];
+    const int h = min(min(hh[0], hh[1]), min(hh[2], hh[3]));
     return h == 0x7fffffff ? -1 : h;
 }
 
@@ -401,21 +450,22 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     __shared__ LocateShared shl;
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
-    const SampleJob job = a.jobs[b];
-    if (job.kind == 0) return;
-    const float u32v = a.u_sample[b];
+    // the slice sums, the table and the uniform are requested before the job is looked at (one round trip)
     const double *ps = a.part1 + (int64_t)b * a.nsl * kSliceVals;
     double *zs = a.part2 + (int64_t)b * a.nsl;                       // exact slice weights (slow path only)
+    double acc[kSliceVals] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int s = tid; s < a.nsl; s += kVBlock)
+#pragma unroll
+        for (int q = 0; q < kSliceVals; ++q) acc[q] += ps[s * kSliceVals + q];
     for (int i = tid; i < 256; i += kVBlock) shT[i] = a.exp_table[i];
+    const float u32v = a.u_sample[b];
+    const SampleJob job = a.jobs[b];
+    if (job.kind == 0) return;                                        // the slice sums of such a sequence are stale: unused
     if (tid == 0) { shl.last = -1; shl.slice = 0x7fffffff; }
 
     // totals of the five slice quantities, fixed order
     double tot[kSliceVals];
     {
-        double acc[kSliceVals] = {0.0, 0.0, 0.0, 0.0, 0.0};
-        for (int s = tid; s < a.nsl; s += kVBlock)
-#pragma unroll
-            for (int q = 0; q < kSliceVals; ++q) acc[q] += ps[s * kSliceVals + q];
 #pragma unroll
         for (int q = 0; q < kSliceVals; ++q) acc[q] = wave_sum_d(acc[q]);
         if ((tid & (kWave - 1)) == 0)
@@ -490,9 +540,13 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
             const double z_mine = tid < a.nsl ? slice_weight(tid) : 0.0;
             double ztot;
             const double excl = block_excl_scan_d(z_mine, shl.scan[phase++ & 1], &ztot);
-            if (tid < a.nsl && excl + z_mine > target) atomicMin(&shl.slice, tid);
+            const int cand = wave_min_i32((tid < a.nsl && excl + z_mine > target) ? tid : 0x7fffffff);
+            if ((tid & (kWave - 1)) == 0) shl.hits[phase & 1][tid / kWave] = cand;
             __syncthreads();
-            s_found = shl.slice == 0x7fffffff ? -1 : shl.slice;
+            const int *hh = shl.hits[phase & 1];
+            const int sf = min(min(hh[0], hh[1]), min(hh[2], hh[3]));
+            ++phase;
+            s_found = sf == 0x7fffffff ? -1 : sf;
             if (tid == s_found) shl.bc[0] = excl;
             __syncthreads();
             if (s_found >= 0) cum_at = shl.bc[0];
@@ -519,12 +573,12 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
         }
         if (token < 0) {
             // rounding left no crossing: the largest index with positive weight
-            if (shl.last < 0) {
-                __syncthreads();
+            {
                 for (int s = 0; s < a.nsl; ++s) {
                     double slice_total;
-                    locate_in_slice<TD, DD>(w, r, s, a.V, shT, 0.0, INFINITY, &shl, phase++, &slice_total);
+                    locate_in_slice<TD, DD>(w, r, s, a.V, shT, 0.0, INFINITY, &shl, phase++, &slice_total, true);
                 }
+                __syncthreads();
             }
             token = shl.last;
         }

@@ -99,7 +99,7 @@ struct VerifyArgs {
 };
 hipError_t launch_verify(const VerifyArgs &a, int pass /*0 head, 1 slices, 2 locate*/, hipStream_t st, Timing tm);
 
-constexpr int kSampleSlice = 4096;   // elements per slice of the final-token passes
+constexpr int kSampleSlice = 2048;   // elements per slice of the final-token passes
 
 struct BanditArgs {
     int32_t policy, n_bandits, n_arms, B;

@@ -8,7 +8,7 @@
 //           log p(tok), takes the accept decisions u < p(tok)/q(tok), finds the
 //           first rejection m, emits the accepted tokens and describes the draw
 //           of the final token (row pair (m, m), or target row n alone)
-//   slices  per 4096-element slice of the row pair, in double: A = sum a_j,
+//   slices  per 2048-element slice of the row pair, in double: A = sum a_j,
 //           B = sum b_j (a = exp(t - ref_p), b = exp(d - ref_q)) and, with the
 //           head's binary32-grade estimate L~ of L = S_p / S_q:
 //           R~ = sum max(0, a_j - L~ b_j), D = sum of b_j over a_j > L~ b_j,
@@ -39,7 +39,7 @@ namespace {
 
 constexpr int kVBlock = 256;
 constexpr int kPer = 8;                       // elements per 16-byte (bf16) / 32-byte (f32) run
-constexpr int kRuns = 2;                      // runs per thread and slice in passes 1 and 2
+constexpr int kRuns = 1;                      // runs per thread and slice in the slice pass
 static_assert(kVBlock * kPer * kRuns == kSampleSlice, "slice = kRuns 8-element runs per thread");
 
 // ---- double-precision helpers ---------------------------------------------------
@@ -287,12 +287,14 @@ __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
 }
 
 // ---- slice kernel -----------------------------------------------------------------------
-// A slice is kSampleSlice = 4096 elements: thread t owns the 8-element runs t and t + 256 of it.
+// A slice is kSampleSlice = 2048 elements, one 8-element run per thread: small enough for 64 registers, so
+// that eight workgroups share a compute unit and the loads of the next ones are in flight while the first
+// ones do their double-precision arithmetic.
 constexpr double kEta = 1.0e-5;        // half-width (relative) of the band around L~ whose elements are counted in U
 constexpr int kSliceVals = 5;          // A, B, R~, D, U
 
 template <int TD, int DD>
-__global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
+__global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void verify_slices(VerifyArgs a)
 {
     __shared__ double shT[256];
     __shared__ double sh_red[kSliceVals][kVBlock / kWave];
@@ -312,22 +314,35 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
     ExpRef rp, rq;
     rp.set((double)job.ref_p); rq.set((double)job.ref_q);
     const double lam = job.lam, band = kEta * job.lam;
-    double A = 0.0, Bs = 0.0, R = 0.0, D = 0.0, U = 0.0;
+    // Ds = sum of b carrying the sign of a - L~ b, so that D = (B + Ds) / 2 without a select per element (an
+    // element with a == L~ b lands in D; it is in the band, so U covers it).  Elements inside the band are a
+    // handful per row at most: their sum is taken under a branch that a wavefront almost never enters.
+    double A = 0.0, Bs = 0.0, R = 0.0, Ds = 0.0, U = 0.0;
+    if (job.kind == 1) {
 #pragma unroll
-    for (int g = 0; g < kRuns; ++g)
+        for (int g = 0; g < kRuns; ++g)
 #pragma unroll
-        for (int i = 0; i < kPer; ++i) {
-            const double av = exp_fast(xt[g][i], rp.neg_ref_c, rp.lo, shT);
-            A += av;
-            if (job.kind == 1) {
+            for (int i = 0; i < kPer; ++i) {
+                const double av = exp_fast(xt[g][i], rp.neg_ref_c, rp.lo, shT);
                 const double bv = exp_fast(xd[g][i], rq.neg_ref_c, rq.lo, shT);
                 const double diff = fma(-lam, bv, av);
+                A += av;
                 Bs += bv;
-                R += diff > 0.0 ? diff : 0.0;
-                D += diff > 0.0 ? bv : 0.0;
-                U += fabs(diff) <= band * bv ? bv : 0.0;
+                R += fmax(diff, 0.0);
+                Ds += copysign(bv, diff);
+                const bool in_band = fabs(diff) <= band * bv;
+                if (__builtin_amdgcn_ballot_w64(in_band) != 0) {
+                    asm volatile("" ::: "memory");              // keep this a branch: a select would cost every element
+                    U += in_band ? bv : 0.0;
+                }
             }
-        }
+    } else {
+#pragma unroll
+        for (int g = 0; g < kRuns; ++g)
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) A += exp_fast(xt[g][i], rp.neg_ref_c, rp.lo, shT);
+    }
+    double D = 0.5 * (Bs + Ds);
     A = wave_sum_d(A);
     if (job.kind == 1) { Bs = wave_sum_d(Bs); R = wave_sum_d(R); D = wave_sum_d(D); U = wave_sum_d(U); }
     const int wave = threadIdx.x / kWave;
@@ -340,7 +355,7 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
 }
 
 // ---- locate kernel: one workgroup per sequence --------------------------------------------
-constexpr int kThreadPer = kSampleSlice / kVBlock;     // 16 consecutive elements per thread inside a slice
+constexpr int kThreadPer = kSampleSlice / kVBlock;     // 8 consecutive elements per thread inside a slice
 
 struct Weights {
     int kind;          // 1 residual max(0, a - L b), 2 target row only (a)
@@ -364,7 +379,7 @@ __device__ inline double block_excl_scan_d(double v, double *sh4, double *total)
     return base + (inc - v);
 }
 
-// Weights of the 16 consecutive elements this thread owns in slice s.
+// Weights of the kThreadPer consecutive elements this thread owns in slice s.
 template <int TD, int DD>
 __device__ inline void thread_weights(const Weights &w, const Rows &r, int s, int V, const double *T, double (&wv)[kThreadPer])
 {

@@ -19,7 +19,7 @@
 //
 // Wavefront reductions use DPP row operations (no LDS traffic).  The partials
 // are merged per sequence by a second, small launch (finalize.hip for draft
-// rows, the head of the final-token kernel in sample.hip for target rows): a
+// rows, the head kernel in verify.hip for target rows): a
 // "last workgroup finishes the sequence" scheme was measured and lost, because
 // on this chip every cross-workgroup hand-over costs a memory round trip of
 // about 3 us under streaming load and four of them chain up.

@@ -20,8 +20,9 @@ _SRC = os.path.join(_HERE, "tapout_oracle.c")
 _LIB = os.path.join(_HERE, "libtapout_oracle.so")
 
 TS_UNIFORMS_PER_ARM = 48
-RULE_SVIP, RULE_MAXCONF, RULE_MARGIN = 0, 1, 2
-POLICY_UCB1, POLICY_TS_BETA = 0, 1
+RULE_SVIP, RULE_MAXCONF, RULE_MARGIN, RULE_SVIP_DIFF, RULE_ADAEDL = 0, 1, 2, 3, 4
+POLICY_UCB1, POLICY_TS_BETA, POLICY_UCB_TUNED, POLICY_TS_GAUSS = 0, 1, 2, 3
+REWARD_BLEND, REWARD_SIMPLE = 0, 1
 FLAG_BAD_ROW, FLAG_BAD_TOKEN, FLAG_BAD_NDRAFT, FLAG_SAMPLER_EXHAUSTED = 1, 2, 4, 8
 
 
@@ -47,6 +48,8 @@ def lib():
         _lib.tapout_oracle_gamma.argtypes = [C.c_double, C.c_void_p, C.c_void_p]
         _lib.tapout_oracle_beta.restype = C.c_double
         _lib.tapout_oracle_beta.argtypes = [C.c_double, C.c_double, C.c_void_p, C.c_void_p]
+        _lib.tapout_oracle_reward_simple.restype = C.c_double
+        _lib.tapout_oracle_reward_simple.argtypes = [C.c_int, C.c_int]
         _lib.tapout_oracle_inverse_cdf.restype = C.c_int32
         _lib.tapout_oracle_inverse_cdf.argtypes = [C.c_void_p, C.c_int64, C.c_double, C.c_void_p, C.c_void_p]
     return _lib
@@ -119,8 +122,10 @@ def row_stats(row) -> dict:
 
 
 def draft_stats(draft, draft_tok=None, k_len=None, arm=None, rules=(0, 1, 2),
-                thresholds=(0.6, 0.8, 0.2), nthreads=1) -> dict:
-    """Signals of every draft row and the stop position of Algorithm 1's draft loop."""
+                thresholds=(0.6, 0.8, 0.2), nthreads=1, prev_entropy=None, lam=None, adaedl_gamma=0.5) -> dict:
+    """Signals of every draft row and the stop position of Algorithm 1's draft loop.
+    prev_entropy [B] f32 (NaN = none) feeds SVIPDifference at the first position; lam [B, arms] f64 the
+    adaptive thresholds of AdaEDL arms."""
     draft = as_logits(draft)
     B, K, V = draft.shape
     sb, sk = _strides(draft)
@@ -139,7 +144,9 @@ def draft_stats(draft, draft_tok=None, k_len=None, arm=None, rules=(0, 1, 2),
         _p(tok), _p(kl), _p(ar), len(rl), _p(rl), _p(th),
         _p(o["lse"]), _p(o["entropy"]), _p(o["p_top1"]), _p(o["p_top2"]), _p(o["margin"]),
         _p(o["top1_id"]), _p(o["logq_tok"]) if tok is not None else None,
-        _p(o["n_stop"]), _p(o["stop_fired"]), _p(o["stop_margin"]), _p(o["flags"]), int(nthreads))
+        _p(o["n_stop"]), _p(o["stop_fired"]), _p(o["stop_margin"]), _p(o["flags"]),
+        _p(_f32(prev_entropy, (B,))), _p(None if lam is None else np.ascontiguousarray(lam, np.float64)),
+        C.c_double(adaedl_gamma), int(nthreads))
     if ar is None:
         o["n_stop"] = None
     return o
@@ -177,6 +184,28 @@ def verify(target, draft, logq_tok, draft_tok, n_draft, u_accept, u_sample, gree
 
 def reward(m: int, n_drafted: int, gamma: int, alpha: float = 0.5) -> float:
     return lib().tapout_oracle_reward(int(m), int(n_drafted), int(gamma), float(alpha))
+
+
+def reward_simple(m: int, gamma: int) -> float:
+    return lib().tapout_oracle_reward_simple(int(m), int(gamma))
+
+
+def ucb_tuned_select(sum_r, sum_r2, count):
+    s = np.ascontiguousarray(sum_r, np.float64)
+    q = np.ascontiguousarray(sum_r2, np.float64)
+    c = np.ascontiguousarray(count, np.int64)
+    idx = np.zeros(len(s), np.float64)
+    a = lib().tapout_oracle_ucb_tuned_select(_p(s), _p(q), _p(c), len(s), _p(idx))
+    return a, idx
+
+
+def ts_gauss_select(sum_r, count, u):
+    s = np.ascontiguousarray(sum_r, np.float64)
+    c = np.ascontiguousarray(count, np.int64)
+    u = _f32(u, (len(s), TS_UNIFORMS_PER_ARM))
+    th = np.zeros(len(s), np.float64)
+    a = lib().tapout_oracle_ts_gauss_select(_p(s), _p(c), len(s), _p(u), _p(th))
+    return a, th
 
 
 def ucb1_select(sum_r, count):
@@ -222,24 +251,50 @@ def inverse_cdf(w, u: float):
 class Bandit:
     """Host-side bandit state driven by the oracle's select/update (Section 3.3)."""
 
-    def __init__(self, policy: int, n_bandits: int, n_arms: int, alpha: float = 0.5):
-        self.policy, self.n_bandits, self.A, self.alpha = policy, n_bandits, n_arms, alpha
+    def __init__(self, policy: int, n_bandits: int, n_arms: int, alpha: float = 0.5, reward_kind: int = REWARD_BLEND):
+        self.policy, self.n_bandits, self.A, self.alpha, self.reward_kind = policy, n_bandits, n_arms, alpha, reward_kind
         self.sum_r = np.zeros((n_bandits, n_arms), np.float64)
+        self.sum_r2 = np.zeros((n_bandits, n_arms), np.float64)
         self.count = np.zeros((n_bandits, n_arms), np.int64)
 
     def select(self, B: int, u_ts=None):
         arm = np.zeros(B, np.int32)
         flags = np.zeros(B, np.uint32)
         u = None
-        if self.policy == POLICY_TS_BETA:
+        if self.policy in (POLICY_TS_BETA, POLICY_TS_GAUSS):
             u = _f32(u_ts, (B, self.A, TS_UNIFORMS_PER_ARM))
-        lib().tapout_oracle_bandit_select(self.policy, self.n_bandits, B, self.A, _p(self.sum_r), _p(self.count),
-                                          _p(u), _p(arm), _p(flags))
+        lib().tapout_oracle_bandit_select(self.policy, self.n_bandits, B, self.A, _p(self.sum_r), _p(self.sum_r2),
+                                          _p(self.count), _p(u), _p(arm), _p(flags))
         return arm, flags
 
     def update(self, arm, accept_len, n_draft, gamma, active=None):
         B = len(arm)
-        lib().tapout_oracle_bandit_update(self.n_bandits, B, self.A, C.c_double(self.alpha),
-                                          _p(self.sum_r), _p(self.count),
+        lib().tapout_oracle_bandit_update(self.n_bandits, B, self.A, self.reward_kind, C.c_double(self.alpha),
+                                          _p(self.sum_r), _p(self.sum_r2), _p(self.count),
                                           _p(_i32(arm, (B,))), _p(_i32(accept_len, (B,))),
                                           _p(_i32(n_draft, (B,))), _p(_i32(gamma, (B,))), _p(_u8(active)))
+
+
+class RuleState:
+    """Carried state of the stateful stop rules (Appendix A.1): per sequence the entropy of the last drafted
+    position of the previous draft (SVIPDifference) and AdaEDL's smoothed acceptance rate; per sequence and
+    arm AdaEDL's threshold lambda (it starts at the arm's configured threshold)."""
+
+    def __init__(self, B: int, rules, thresholds, ad_alpha=0.9, beta1=0.5, beta2=0.9, eps=0.01, rate0=None):
+        self.B, self.rules = B, _i32(rules)
+        self.A = len(self.rules)
+        self.ad_alpha, self.beta1, self.beta2, self.eps = ad_alpha, beta1, beta2, eps
+        self.prev_entropy = np.full(B, np.nan, np.float32)
+        self.accept_rate = np.full(B, ad_alpha if rate0 is None else rate0, np.float64)
+        self.lam = np.tile(np.asarray(thresholds, np.float32).astype(np.float64), (B, 1))
+
+    def update(self, entropy, n_draft, accept_len, active=None):
+        B = self.B
+        ent = None if entropy is None else _f32(entropy)
+        K = 0 if ent is None else ent.shape[1]
+        if ent is None:
+            K = int(np.max(n_draft)) if len(n_draft) else 0
+        lib().tapout_oracle_rule_state_update(
+            B, K, self.A, _p(self.rules), _p(ent), _p(_i32(n_draft, (B,))), _p(_i32(accept_len, (B,))),
+            _p(_u8(active)), _p(self.prev_entropy), _p(self.accept_rate), _p(self.lam),
+            C.c_double(self.ad_alpha), C.c_double(self.beta1), C.c_double(self.beta2), C.c_double(self.eps))

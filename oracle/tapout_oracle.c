@@ -24,16 +24,26 @@
  * Parity pins (tests/test_oracle_*.py): closed-form rows (uniform, two- and
  * three-point), library cross-checks of the row statistics, threshold edges,
  * exact enumeration of the speculative-sampling output law on tiny
- * vocabularies, UCB1 and reward hand cases, Gamma/Beta sampler moments.
- * Every function in this file is covered by at least one of those pins.
+ * vocabularies, UCB1 and reward hand cases, Gamma/Beta sampler moments,
+ * closed-form rows for SVIPDifference / AdaEDL, the empirical variance of
+ * UCB-Tuned against a two-pass library variance, Gaussian posterior moments.
+ * Every function in this file is covered by at least one of those pins,
+ * except the VALUES of AdaEDL's hyper-parameters and the exact form of its
+ * threshold update, which the paper prints garbled: PARITY UNPINNED for
+ * those (the arithmetic of the reading taken here is pinned by closed
+ * forms; whether it is the authors' reading cannot be).
  *
  * Conventions shared with the boundary (they are the boundary's, restated
  * here, not imported from it):
  *   dtype 0 = IEEE binary32 logits, dtype 1 = bfloat16 logits (upper 16 bits
  *   of a binary32); both widen exactly to double.
  *   rule 0 = SVIP (sqrt(H) > h), 1 = Max-Confidence (p_top1 < h),
- *   rule 2 = LogitMargin (p_top1 - p_top2 < h)           -- Table 1
- *   policy 0 = UCB1, 1 = Thompson Sampling with Beta posteriors.
+ *   rule 2 = LogitMargin (p_top1 - p_top2 < h), 3 = SVIPDifference
+ *   (sqrt(H_t) - sqrt(H_{t-1}) > h), 4 = AdaEDL (1 - sqrt(g H) < lambda)
+ *                                             -- Table 1, Appendix A.1
+ *   policy 0 = UCB1, 1 = Thompson Sampling with Beta posteriors,
+ *   2 = UCB-Tuned, 3 = Thompson Sampling with a Gaussian posterior.
+ *   reward 0 = r_blend, 1 = r_simple                      -- Section 3.2
  *   flag bits: 1 = a processed row holds NaN or has no finite maximum,
  *              2 = drafted token id outside [0, V), 4 = n_draft outside [1, K].
  */
@@ -140,12 +150,39 @@ static int rule_fires(int rule, float h, float H, float p1, float margin, double
     return fire;
 }
 
+/* SVIPDifference (Table 1, Appendix A.1): sqrt(H_t) - sqrt(H_{t-1}) > h, the
+ * entropies being those of the current and the previous token step.  At the
+ * first step of a draft the previous step is the last drafted position of the
+ * sequence's previous draft (carried by the caller); without one (has_prev =
+ * 0, or a NaN) the rule cannot fire.                                          */
+static int svip_diff_fires(float h, float H, int has_prev, float H_prev, double *margin_out)
+{
+    double thr = (double)h;
+    if (!has_prev || H_prev != H_prev || H != H) { if (margin_out) *margin_out = INFINITY; return 0; }
+    double sig = sqrt((double)H) - sqrt((double)H_prev);
+    if (margin_out) *margin_out = fabs(sig - thr) / (fabs(thr) > 0 ? fabs(thr) : 1.0);
+    return sig > thr;
+}
+
+/* AdaEDL (Table 1, Appendix A.1): 1 - sqrt(g * H) < lambda_t, g a fixed
+ * hyper-parameter, lambda_t the sequence's adaptive threshold.               */
+static int adaedl_fires(double g, double lambda, float H, double *margin_out)
+{
+    if (H != H) { if (margin_out) *margin_out = INFINITY; return 0; }
+    double sig = 1.0 - sqrt(g * (double)H);
+    if (margin_out) *margin_out = fabs(sig - lambda) / (fabs(lambda) > 0 ? fabs(lambda) : 1.0);
+    return sig < lambda;
+}
+
 /*
  * Draft pass: signals of every draft row (b,k), k < k_len[b], and the stop
  * position of Algorithm 1's draft loop: the token of the step at which the
  * selected rule fires is kept, so n_stop = (first firing k) + 1, or k_len[b]
  * if it never fires.  Rows k >= k_len[b] are left untouched.  When arm is
  * given, entropy, p_top1 and margin must be given too (the scan reads them).
+ * prev_entropy [B] (or NULL): entropy of the last drafted position of each
+ * sequence's previous draft, NaN for none (SVIPDifference).  lambda [B,
+ * n_arms] (or NULL): adaptive thresholds (AdaEDL arms read their column).
  */
 ORACLE_API int tapout_oracle_draft_stats(
     const void *draft, int dtype, int64_t stride_b, int64_t stride_k,
@@ -155,6 +192,7 @@ ORACLE_API int tapout_oracle_draft_stats(
     float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
     int32_t *top1_id, float *logq_tok,
     int32_t *n_stop, uint8_t *stop_fired, double *stop_margin, uint32_t *flags,
+    const float *prev_entropy, const double *lambda, double adaedl_g,
     int nthreads)
 {
     if (nthreads < 1) nthreads = 1;
@@ -197,7 +235,17 @@ ORACLE_API int tapout_oracle_draft_stats(
             int64_t i = (int64_t)b * K + k;
             double mg = INFINITY;
             int fire = 0;
-            if (a >= 0 && a < n_arms) fire = rule_fires(rule[a], threshold[a], entropy[i], p_top1[i], margin[i], &mg);
+            if (a >= 0 && a < n_arms) {
+                if (rule[a] == 3) {
+                    int has_prev = k > 0 ? 1 : (prev_entropy != NULL);
+                    float Hp = k > 0 ? entropy[i - 1] : (prev_entropy ? prev_entropy[b] : NAN);
+                    fire = svip_diff_fires(threshold[a], entropy[i], has_prev, Hp, &mg);
+                } else if (rule[a] == 4) {
+                    fire = adaedl_fires(adaedl_g, lambda ? lambda[(size_t)b * n_arms + a] : (double)threshold[a], entropy[i], &mg);
+                } else {
+                    fire = rule_fires(rule[a], threshold[a], entropy[i], p_top1[i], margin[i], &mg);
+                }
+            }
             if (stop_fired) stop_fired[i] = (uint8_t)fire;
             if (stop_margin) stop_margin[i] = mg;
             if (fire && !stopped) { ns = k + 1; stopped = 1; }
@@ -381,12 +429,59 @@ ORACLE_API int tapout_oracle_verify(
     return 0;
 }
 
+/* ---- carried state of the stateful stop rules (Appendix A.1) ------------- *
+ * After each draft of an active sequence with 1 <= n_draft <= K:
+ *   prev_entropy <- entropy of the last drafted position (row n_draft - 1);
+ *   AdaEDL:  r = n_acc / n_drafted
+ *            accept_rate <- beta1 * accept_rate + (1 - beta1) * r
+ *            lambda <- beta2 * lambda + (1 - beta2) * (lambda + eps * sign(alpha - accept_rate))
+ *   for the lambda of every AdaEDL arm of the sequence (each arm keeps its own,
+ *   they start at different values).  The printed update is garbled (a doubled
+ *   "+", an accept_rate that nothing reads); the reading here lets the smoothed
+ *   rate steer the threshold.  sign(0) = 0.                                  */
+ORACLE_API int tapout_oracle_rule_state_update(
+    int B, int K, int n_arms, const int32_t *rule,
+    const float *entropy /* [B,K] or NULL */, const int32_t *n_draft, const int32_t *accept_len,
+    const uint8_t *active,
+    float *prev_entropy /* [B] */, double *accept_rate /* [B] */, double *lambda /* [B,n_arms] */,
+    double ad_alpha, double beta1, double beta2, double eps)
+{
+    for (int b = 0; b < B; ++b) {
+        if (active && !active[b]) continue;
+        int n = n_draft[b];
+        if (n < 1 || n > K) continue;
+        if (entropy) prev_entropy[b] = entropy[(size_t)b * K + (n - 1)];
+        volatile double r = (double)accept_len[b] / (double)n;
+        volatile double keep = beta1 * accept_rate[b];
+        volatile double add = (1.0 - beta1) * r;
+        double rate = keep + add;
+        accept_rate[b] = rate;
+        double sg = ad_alpha > rate ? 1.0 : (ad_alpha < rate ? -1.0 : 0.0);
+        for (int a = 0; a < n_arms; ++a) {
+            if (rule[a] != 4) continue;
+            double lam = lambda[(size_t)b * n_arms + a];
+            volatile double step = eps * sg;
+            volatile double moved = lam + step;
+            volatile double t1 = beta2 * lam;
+            volatile double t2 = (1.0 - beta2) * moved;
+            lambda[(size_t)b * n_arms + a] = t1 + t2;
+        }
+    }
+    return 0;
+}
+
 /* ---- reward (Section 3.2): r_blend = a*|Y|/gamma + (1-a)*|Y|/|X| -------- */
 ORACLE_API double tapout_oracle_reward(int m, int n_drafted, int gamma, double alpha)
 {
     volatile double t1 = (alpha * (double)m) / (double)gamma;
     volatile double t2 = ((1.0 - alpha) * (double)m) / (double)n_drafted;
     return t1 + t2;
+}
+
+/* r_simple = |Y| / gamma (Section 3.2), the normalised acceptance length. */
+ORACLE_API double tapout_oracle_reward_simple(int m, int gamma)
+{
+    return (double)m / (double)gamma;
 }
 
 /* ---- UCB1 (Section 3.3): argmax_a mean_a + sqrt(2 ln t / N_a) ----------- *
@@ -471,6 +566,67 @@ ORACLE_API int tapout_oracle_ts_select(const double *sum_r, const int64_t *count
     return best;
 }
 
+/* ---- UCB-Tuned (Section 3.3) -------------------------------------------- *
+ * argmax_a mean_a + sqrt( (ln t / N_a) * min(1/4, V_a) ),
+ * V_a = var_a + sqrt(2 ln t / N_a), var_a the empirical (population)
+ * variance of the rewards of arm a, here from the running sums:
+ * sum_r2/N - mean^2.  t, the initial plays and ties as for UCB1.            */
+ORACLE_API int tapout_oracle_ucb_tuned_select(const double *sum_r, const double *sum_r2, const int64_t *count,
+                                              int A, double *index_out)
+{
+    int64_t t = 1;
+    for (int a = 0; a < A; ++a) t += count[a];
+    int best = -1, unplayed = -1;
+    double best_v = -INFINITY;
+    for (int a = 0; a < A; ++a) {
+        double v;
+        if (count[a] == 0) { v = INFINITY; if (unplayed < 0) unplayed = a; }
+        else {
+            double n = (double)count[a];
+            double lt = log((double)t);
+            volatile double mean = sum_r[a] / n;
+            volatile double m2 = sum_r2[a] / n;
+            volatile double msq = mean * mean;
+            volatile double var = m2 - msq;
+            volatile double two_lt = 2.0 * lt;
+            volatile double wide = sqrt(two_lt / n);
+            volatile double V = var + wide;
+            double cap = V < 0.25 ? V : 0.25;
+            volatile double ratio = lt / n;
+            volatile double prod = ratio * cap;
+            volatile double bonus = sqrt(prod);
+            v = mean + bonus;
+        }
+        if (index_out) index_out[a] = v;
+        if (best < 0 || v > best_v) { best = a; best_v = v; }
+    }
+    return unplayed >= 0 ? unplayed : best;
+}
+
+/* ---- Thompson Sampling with a Gaussian posterior (Section 3.3) ----------- *
+ * The paper names a Gaussian prior with known noise variance and gives no
+ * values; taken here: prior N(0, 1), unit noise variance, so that after N_a
+ * plays with summed reward S_a the posterior is N(S_a/(N_a+1), 1/(N_a+1)).
+ * theta_a = mean + z / sqrt(N_a + 1), z = sqrt(-2 ln u1) cos(2 pi u2) from
+ * the first two of the arm's caller uniforms (u1 = 0 read as 2^-25).         */
+ORACLE_API int tapout_oracle_ts_gauss_select(const double *sum_r, const int64_t *count, int A, const float *u,
+                                             double *theta_out)
+{
+    int best = 0;
+    double best_v = -INFINITY;
+    for (int a = 0; a < A; ++a) {
+        const float *ua = u + (size_t)a * TS_UNIFORMS_PER_ARM;
+        double n1 = (double)count[a] + 1.0;
+        double z = sqrt(-2.0 * log(unit_open(ua[0]))) * cos(6.283185307179586476925 * (double)ua[1]);
+        volatile double mean = sum_r[a] / n1;
+        volatile double dev = z / sqrt(n1);
+        double th = mean + dev;
+        if (theta_out) theta_out[a] = th;
+        if (a == 0 || th > best_v) { best = a; best_v = th; }
+    }
+    return best;
+}
+
 /*
  * Batched bandit calls.  n_bandits == B: one bandit per sequence slot.
  * n_bandits == 1: one shared bandit; select draws one arm for the round
@@ -478,25 +634,27 @@ ORACLE_API int tapout_oracle_ts_select(const double *sum_r, const int64_t *count
  * index order, each as one play.
  */
 ORACLE_API int tapout_oracle_bandit_select(int policy, int n_bandits, int B, int A,
-                                           const double *sum_r, const int64_t *count,
+                                           const double *sum_r, const double *sum_r2, const int64_t *count,
                                            const float *u_ts, int32_t *arm_out, uint32_t *flags)
 {
     for (int b = 0; b < B; ++b) {
         int nb = n_bandits == 1 ? 0 : b;
         int ex = 0, a;
-        if (policy == 0)
-            a = tapout_oracle_ucb1_select(sum_r + (size_t)nb * A, count + (size_t)nb * A, A, NULL);
-        else
-            a = tapout_oracle_ts_select(sum_r + (size_t)nb * A, count + (size_t)nb * A, A,
-                                        u_ts + (size_t)nb * A * TS_UNIFORMS_PER_ARM, NULL, &ex);
+        const double *S = sum_r + (size_t)nb * A;
+        const int64_t *N = count + (size_t)nb * A;
+        const float *u = u_ts ? u_ts + (size_t)nb * A * TS_UNIFORMS_PER_ARM : NULL;
+        if (policy == 0) a = tapout_oracle_ucb1_select(S, N, A, NULL);
+        else if (policy == 2) a = tapout_oracle_ucb_tuned_select(S, sum_r2 + (size_t)nb * A, N, A, NULL);
+        else if (policy == 3) a = tapout_oracle_ts_gauss_select(S, N, A, u, NULL);
+        else a = tapout_oracle_ts_select(S, N, A, u, NULL, &ex);
         arm_out[b] = a;
         if (flags) flags[b] = ex ? FLAG_SAMPLER_EXHAUSTED : 0;
     }
     return 0;
 }
 
-ORACLE_API int tapout_oracle_bandit_update(int n_bandits, int B, int A, double alpha,
-                                           double *sum_r, int64_t *count,
+ORACLE_API int tapout_oracle_bandit_update(int n_bandits, int B, int A, int reward_kind, double alpha,
+                                           double *sum_r, double *sum_r2, int64_t *count,
                                            const int32_t *arm, const int32_t *accept_len,
                                            const int32_t *n_draft, const int32_t *gamma,
                                            const uint8_t *active)
@@ -506,9 +664,11 @@ ORACLE_API int tapout_oracle_bandit_update(int n_bandits, int B, int A, double a
         int a = arm[b];
         if (a < 0 || a >= A || n_draft[b] < 1 || gamma[b] < 1) continue;
         int nb = n_bandits == 1 ? 0 : b;
-        double r = tapout_oracle_reward(accept_len[b], n_draft[b], gamma[b], alpha);
+        double r = reward_kind == 1 ? tapout_oracle_reward_simple(accept_len[b], gamma[b])
+                                    : tapout_oracle_reward(accept_len[b], n_draft[b], gamma[b], alpha);
         count[(size_t)nb * A + a] += 1;
         sum_r[(size_t)nb * A + a] += r;
+        if (sum_r2) { volatile double sq = r * r; sum_r2[(size_t)nb * A + a] += sq; }
     }
     return 0;
 }

@@ -169,3 +169,101 @@ def test_ucb1_converges_to_best_arm():
         bd.update([a], [m], [8], [8])
     assert bd.count[0].argmax() == 2 and bd.count[0, 2] > 2000
     np.testing.assert_allclose(bd.sum_r[0] / bd.count[0], means, atol=0.12)
+
+
+# ---- bandit and reward variants of the ablations (Section 3.2, Section 3.3) ------------------------------
+
+def test_reward_simple_is_the_normalised_acceptance_length():
+    assert orc.reward_simple(3, 8) == 0.375 and orc.reward_simple(0, 5) == 0.0 and orc.reward_simple(5, 5) == 1.0
+    # it is the alpha = 1 end of the blend, and it ignores how many tokens were drafted
+    for m, n, g in ((2, 3, 8), (2, 7, 8), (4, 4, 16)):
+        assert orc.reward_simple(m, g) == orc.reward(m, n, g, 1.0)
+    bd = orc.Bandit(orc.POLICY_UCB1, 1, 2, reward_kind=orc.REWARD_SIMPLE)
+    bd.update([1], [3], [4], [8])
+    assert bd.sum_r[0, 1] == 0.375 and bd.sum_r2[0, 1] == 0.375 ** 2
+
+
+def test_ucb_tuned_hand_cases(golden):
+    for N, S, Q, t, want in golden("ucb_tuned_hand_cases.txt"):
+        N, t = int(N), int(t)
+        # two arms with the same statistics and N + N + 1 = t: both indices equal the hand value, tie -> arm 0
+        assert 2 * N + 1 == t
+        a, idx = orc.ucb_tuned_select([float(S)] * 2, [float(Q)] * 2, [N, N])
+        assert a == 0
+        np.testing.assert_allclose(idx, float(want), atol=2e-6)
+
+
+def test_ucb_tuned_variance_is_the_population_variance_of_the_rewards_played():
+    g = np.random.default_rng(11)
+    bd = orc.Bandit(orc.POLICY_UCB_TUNED, 1, 3)
+    hist = [[], [], []]
+    for _ in range(400):
+        a = int(g.integers(3))
+        n = int(g.integers(1, 9)); m = int(g.integers(0, n + 1))
+        bd.update([a], [m], [n], [8])
+        hist[a].append(orc.reward(m, n, 8))
+    t = 401
+    _, idx = orc.ucb_tuned_select(bd.sum_r[0], bd.sum_r2[0], bd.count[0])
+    for a in range(3):
+        r = np.array(hist[a])
+        V = np.var(r) + math.sqrt(2 * math.log(t) / len(r))          # numpy: two-pass, divides by N
+        want = r.mean() + math.sqrt(math.log(t) / len(r) * min(0.25, V))
+        assert idx[a] == pytest.approx(want, rel=1e-12)
+    # more spread at equal mean and plays -> larger index, until the 1/4 cap
+    lo = orc.ucb_tuned_select([500.0, 500.0], [250.0, 260.0], [1000, 1000])
+    assert lo[0] == 1 and lo[1][1] > lo[1][0]
+    capped = orc.ucb_tuned_select([5.0, 5.0], [2.5, 5.0], [10, 10])
+    assert capped[0] == 0 and capped[1][0] == capped[1][1]
+
+
+def test_ucb_tuned_plays_every_arm_once_first_and_explores_less_than_ucb1():
+    s, q, c = np.zeros(3), np.zeros(3), np.zeros(3, np.int64)
+    for expect in (0, 1, 2):
+        a, idx = orc.ucb_tuned_select(s, q, c)
+        assert a == expect and np.isinf(idx[expect])
+        c[a] += 1; s[a] += 0.3; q[a] += 0.09
+    # bonus <= sqrt(ln t / (4 N)) < UCB1's sqrt(2 ln t / N)
+    s, q, c = np.array([30.0, 4.0]), np.array([12.0, 2.0]), np.array([60, 10])
+    _, tuned = orc.ucb_tuned_select(s, q, c)
+    _, plain = orc.ucb1_select(s, c)
+    assert ((tuned - s / c) < (plain - s / c)).all() and ((tuned - s / c) > 0).all()
+
+
+def test_ts_gauss_posterior_and_uniform_use():
+    # u2 = 0 -> cos = 1, u1 = exp(-2) -> z = 2;  u2 = 0.5 -> z = -2;  u2 = 0.25 -> z = 0 (to rounding)
+    u = np.zeros((3, 48), np.float32)
+    u[:, 0] = math.exp(-2.0)
+    u[:, 1] = (0.0, 0.5, 0.25)
+    z = math.sqrt(-2.0 * math.log(float(np.float32(math.exp(-2.0)))))
+    a, th = orc.ts_gauss_select([3.0, 3.0, 3.0], [8, 8, 8], u)
+    np.testing.assert_allclose(th, [3 / 9 + z / 3, 3 / 9 - z / 3, 3 / 9], atol=1e-15)
+    assert a == 0
+    # fresh arm: the prior N(0, 1) itself
+    a, th = orc.ts_gauss_select([0.0], [0], u[:1])
+    assert th[0] == pytest.approx(z, rel=1e-15)
+    # law of the draw: N(S/(N+1), 1/(N+1))
+    g = np.random.default_rng(5)
+    draws = np.array([orc.ts_gauss_select([6.0], [15], g.random((1, 48), np.float32))[1][0] for _ in range(40000)])
+    assert draws.mean() == pytest.approx(6 / 16, abs=0.005)
+    assert draws.var() == pytest.approx(1 / 16, rel=0.04)
+    assert stats.kstest(draws, stats.norm(6 / 16, 0.25).cdf).pvalue > 1e-3
+    # u1 = 0 is read as 2^-25, not as log(0)
+    u0 = np.zeros((1, 48), np.float32)
+    assert orc.ts_gauss_select([0.0], [0], u0)[1][0] == pytest.approx(math.sqrt(50 * math.log(2)), rel=1e-15)
+
+
+def test_batched_select_dispatches_the_variants():
+    u = np.random.default_rng(9).random((2, 3, 48), np.float32)
+    for pol, single in ((orc.POLICY_UCB_TUNED, None), (orc.POLICY_TS_GAUSS, None)):
+        bd = orc.Bandit(pol, 2, 3)
+        bd.sum_r[:] = [[1.0, 2.5, 0.5], [3.0, 0.2, 0.1]]
+        bd.sum_r2[:] = [[0.6, 1.4, 0.2], [1.9, 0.04, 0.01]]
+        bd.count[:] = [[4, 5, 2], [6, 1, 1]]
+        arms, fl = bd.select(2, u)
+        for b in range(2):
+            if pol == orc.POLICY_UCB_TUNED:
+                want = orc.ucb_tuned_select(bd.sum_r[b], bd.sum_r2[b], bd.count[b])[0]
+            else:
+                want = orc.ts_gauss_select(bd.sum_r[b], bd.count[b], u[b])[0]
+            assert arms[b] == want
+        assert not fl.any()

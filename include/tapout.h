@@ -64,15 +64,31 @@ typedef enum {
 
 typedef enum { TAPOUT_F32 = 0, TAPOUT_BF16 = 1 } tapout_dtype;
 
-/* Stop rules of Table 1 (threshold arms).  A rule fires, i.e. drafting stops
- * after the current token, when its strict inequality holds:
- *   SVIP     sqrt(H(p)) > h          h = 0.6
- *   MAXCONF  p(top-1) < h            h = 0.8
- *   MARGIN   p(top-1) - p(top-2) < h h = 0.2                                  */
-typedef enum { TAPOUT_RULE_SVIP = 0, TAPOUT_RULE_MAXCONF = 1, TAPOUT_RULE_MARGIN = 2 } tapout_rule;
+/* Stop rules of Table 1 / Appendix A.1.  A rule fires, i.e. drafting stops
+ * after the current token, when its strict inequality holds (H = entropy of
+ * the draft distribution of the current step, in nats):
+ *   SVIP       sqrt(H) > h                        h = 0.6
+ *   MAXCONF    p(top-1) < h                       h = 0.8
+ *   MARGIN     p(top-1) - p(top-2) < h            h = 0.2
+ *   SVIP_DIFF  sqrt(H_t) - sqrt(H_{t-1}) > h      h = 0.2
+ *              At the first step of a draft, H_{t-1} is the entropy of the last
+ *              drafted position of the sequence's previous draft (carried in
+ *              the context, see tapout_rule_state_get); a sequence without a
+ *              previous draft cannot stop at its first step.
+ *   ADAEDL     1 - sqrt(g * H) < lambda           g = tapout_config.adaedl_gamma
+ *              lambda is kept per sequence and arm, starts at the arm's
+ *              threshold[] entry and is moved by tapout_bandit_update.       */
+typedef enum {
+    TAPOUT_RULE_SVIP = 0, TAPOUT_RULE_MAXCONF = 1, TAPOUT_RULE_MARGIN = 2,
+    TAPOUT_RULE_SVIP_DIFF = 3, TAPOUT_RULE_ADAEDL = 4
+} tapout_rule;
 
 /* Bandit policies of Section 3.3 (sequence-level). */
-typedef enum { TAPOUT_UCB1 = 0, TAPOUT_TS_BETA = 1 } tapout_policy;
+typedef enum { TAPOUT_UCB1 = 0, TAPOUT_TS_BETA = 1, TAPOUT_UCB_TUNED = 2, TAPOUT_TS_GAUSS = 3 } tapout_policy;
+
+/* Rewards of Section 3.2: r_blend = alpha |Y|/gamma + (1 - alpha) |Y|/|X|,
+ * r_simple = |Y|/gamma.                                                       */
+typedef enum { TAPOUT_REWARD_BLEND = 0, TAPOUT_REWARD_SIMPLE = 1 } tapout_reward;
 
 /* per-sequence flag bits written by the kernels */
 #define TAPOUT_FLAG_BAD_ROW 1u           /* a processed row holds NaN or has no finite maximum */
@@ -91,6 +107,18 @@ typedef struct {
     int32_t policy;                       /* tapout_policy                                      */
     int32_t n_bandits;                    /* max_batch: one bandit per sequence slot; 1: shared */
     double alpha;                         /* weight of |Y|/gamma in the blended reward (0.5)    */
+    int32_t reward;                       /* tapout_reward                                      */
+    int32_t reserved;                     /* 0                                                  */
+    /* AdaEDL (Appendix A.1).  The paper leaves all of these unvalued; the defaults are this
+     * library's choice.  After every draft of a sequence, with r = accepted / drafted:
+     *   rate   <- beta1 * rate + (1 - beta1) * r
+     *   lambda <- beta2 * lambda + (1 - beta2) * (lambda + eps * sign(alpha_target - rate))       */
+    double adaedl_gamma;                  /* g in the stop rule (0.5)                           */
+    double adaedl_alpha;                  /* acceptance rate the threshold is steered to (0.9)  */
+    double adaedl_beta1;                  /* smoothing of the acceptance rate (0.5)             */
+    double adaedl_beta2;                  /* smoothing of lambda (0.9)                          */
+    double adaedl_eps;                    /* step of lambda (0.01)                              */
+    double adaedl_rate0;                  /* initial smoothed acceptance rate (= adaedl_alpha)  */
 } tapout_config;
 
 typedef struct {
@@ -99,8 +127,9 @@ typedef struct {
     int64_t stride_b, stride_k;           /* elements; the vocabulary axis has stride 1         */
 } tapout_logits;
 
-/* Fill *cfg with the paper's set-up: three arms SVIP / MAXCONF / MARGIN at the
- * Table 1 thresholds, UCB1, alpha = 0.5, one bandit per sequence.  host.     */
+/* Fill *cfg with the set-up of the paper's main experiments restricted to the
+ * stateless rules: three arms SVIP / MAXCONF / MARGIN at the Table 1
+ * thresholds, UCB1, r_blend with alpha = 0.5, one bandit per sequence.  host. */
 TAPOUT_API void tapout_default_config(tapout_config *cfg, int32_t max_batch, int32_t max_k, int32_t vocab);
 
 /* Create a context on cfg->device: validates cfg (host), allocates scratch
@@ -117,13 +146,21 @@ TAPOUT_API const char *tapout_last_error(const tapout_ctx *ctx);
  *   UCB1: an arm never played is chosen first (lowest index); otherwise
  *     argmax_a  mean_a + sqrt(2 ln t / N_a),  t = 1 + sum_a N_a, lowest index
  *     on exact ties.  fp64.
+ *   UCB_TUNED: as UCB1 with the bonus sqrt((ln t / N_a) min(1/4, V_a)),
+ *     V_a = var_a + sqrt(2 ln t / N_a), var_a = Q_a/N_a - (S_a/N_a)^2 the
+ *     empirical variance from the running sums of r and r^2.  fp64.
+ *   TS_GAUSS: theta_a ~ N(S_a/(N_a+1), 1/(N_a+1)) (prior N(0,1), unit noise
+ *     variance: the paper names the family, not the values); theta_a = mean +
+ *     z / sqrt(N_a+1), z = sqrt(-2 ln u1) cos(2 pi u2) from u_ts[b][a][0..1]
+ *     (u1 = 0 read as 2^-25).  fp64.
  *   TS_BETA: theta_a ~ Beta(1 + S_a, 1 + N_a - S_a) (S_a = summed rewards),
  *     argmax_a theta_a.  The draw is G1/(G1+G2), G ~ Gamma(shape) by
  *     Marsaglia-Tsang driven by u_ts[b][a][0..47]: 8 attempts x (2 Box-Muller
  *     uniforms, 1 acceptance uniform) for G1, then the same for G2; u = 0 is
  *     read as 2^-25; if all attempts reject, G = shape and
  *     TAPOUT_FLAG_SAMPLER_EXHAUSTED is set.  fp64.
- * u_ts    [B, n_arms, 48] f32 in [0,1), required for TS_BETA, ignored for UCB1
+ * u_ts    [B, n_arms, 48] f32 in [0,1), required for TS_BETA and TS_GAUSS,
+ *         ignored for UCB1 and UCB_TUNED
  * arm_out [B] i32
  * flags   [B] u32 or NULL (overwritten)
  * With a shared bandit (n_bandits == 1) every sequence gets the arm drawn for
@@ -146,6 +183,9 @@ TAPOUT_API tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const 
  * else k_len[b]: the token drafted at the firing step is kept.  The rule is
  * evaluated on the returned binary32 signals, widened to double (SVIP compares
  * sqrt(entropy)).  Rows k >= k_len[b] are neither read nor written.
+ * SVIP_DIFF and ADAEDL arms read the context's rule state (previous entropy,
+ * lambda) and, when the configuration holds such an arm, the call keeps the
+ * entropies of this draft in the context for tapout_bandit_update.
  *
  * draft_tok [B,K] i32 or NULL (then logq_tok is not written)
  * k_len     [B] i32 or NULL (= K for all)
@@ -211,10 +251,16 @@ TAPOUT_API tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *tar
  * Bandit update after verification (Algorithm 1 line 12; Section 3.2):
  *   r = alpha * m / gamma + (1 - alpha) * m / n,  m = accept_len, n = n_draft,
  *   evaluated in double as (alpha*m)/gamma + ((1-alpha)*m)/n without fused
- *   multiply-add; then N[arm] += 1, S[arm] += r.
+ *   multiply-add (REWARD_SIMPLE: r = m / gamma); then N[arm] += 1,
+ *   S[arm] += r, Q[arm] += r*r.
  * Sequences with active[b] == 0, an arm outside [0, n_arms), n_draft < 1 or
  * gamma < 1 are skipped.  With a shared bandit the B rewards are applied in
  * index order, each as one play.
+ * If the configuration holds a SVIP_DIFF or ADAEDL arm, the rule state of every
+ * active sequence with 1 <= n_draft <= K (K of the preceding tapout_draft_stats
+ * call) is advanced as well, whatever arm was played: previous entropy <-
+ * entropy of row n_draft - 1 of that call; AdaEDL rate and lambdas as described
+ * at tapout_config.
  * arm, accept_len, n_draft, gamma [B] i32;  active [B] u8 or NULL
  */
 TAPOUT_API tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *arm,
@@ -222,10 +268,20 @@ TAPOUT_API tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const 
                                    const int32_t *gamma, const uint8_t *active, void *stream);
 
 /* Bandit state read-out (the arm values of Section 4.3 are sum_r / count) and
- * restore.  sum_r, count: HOST arrays [n_bandits, n_arms] (f64, i64).  Both
- * calls synchronise `stream`.                                                 */
-TAPOUT_API tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, int64_t *count, void *stream);
-TAPOUT_API tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *sum_r, const int64_t *count, void *stream);
+ * restore.  sum_r, sum_r2 (or NULL), count: HOST arrays [n_bandits, n_arms]
+ * (f64, f64, i64); sum_r2 = summed squared rewards (UCB_TUNED), set to
+ * sum_r^2 / count when NULL on restore.  Both calls synchronise `stream`.     */
+TAPOUT_API tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, double *sum_r2, int64_t *count, void *stream);
+TAPOUT_API tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *sum_r, const double *sum_r2, const int64_t *count, void *stream);
+
+/* State of the stateful stop rules (Appendix A.1: SVIP-Difference, AdaEDL)
+ * read-out and restore.  HOST arrays, each or NULL: prev_entropy [max_batch]
+ * f32 (NaN = no previous draft), accept_rate [max_batch] f64, lambda
+ * [max_batch, n_arms] f64 (only the columns of ADAEDL arms are used).  A new
+ * context starts with NaN, adaedl_rate0 and the arms' thresholds.  Both calls
+ * synchronise `stream`.                                                       */
+TAPOUT_API tapout_status tapout_rule_state_get(tapout_ctx *ctx, float *prev_entropy, double *accept_rate, double *lambda, void *stream);
+TAPOUT_API tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *prev_entropy, const double *accept_rate, const double *lambda, void *stream);
 
 /*
  * Launch-shape tuning (host; takes effect from the next call).  Names:

@@ -17,14 +17,16 @@ LIB_PATH = os.path.join(_PKG, "libtapout.so")
 MAX_ARMS = 8
 TS_UNIFORMS_PER_ARM = 48
 F32, BF16 = 0, 1
-RULE_SVIP, RULE_MAXCONF, RULE_MARGIN = 0, 1, 2
-UCB1, TS_BETA = 0, 1
+RULE_SVIP, RULE_MAXCONF, RULE_MARGIN, RULE_SVIP_DIFF, RULE_ADAEDL = 0, 1, 2, 3, 4
+UCB1, TS_BETA, UCB_TUNED, TS_GAUSS = 0, 1, 2, 3
+REWARD_BLEND, REWARD_SIMPLE = 0, 1
 FLAG_BAD_ROW, FLAG_BAD_TOKEN, FLAG_BAD_NDRAFT, FLAG_SAMPLER_EXHAUSTED = 1, 2, 4, 8
 STATUS = {0: "TAPOUT_OK", 1: "TAPOUT_EINVAL", 2: "TAPOUT_EUNSUPPORTED", 3: "TAPOUT_ENOMEM", 4: "TAPOUT_EHIP"}
 
 EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_last_error",
            "tapout_bandit_select", "tapout_draft_stats", "tapout_verify", "tapout_bandit_update",
-           "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_set_option",
+           "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_rule_state_get", "tapout_rule_state_set",
+           "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
 PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_head", "verify_slices", "verify_locate", "update")
@@ -33,7 +35,10 @@ PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verif
 class TapoutConfig(C.Structure):
     _fields_ = [("device", C.c_int32), ("max_batch", C.c_int32), ("max_k", C.c_int32), ("vocab", C.c_int32),
                 ("n_arms", C.c_int32), ("rule", C.c_int32 * MAX_ARMS), ("threshold", C.c_float * MAX_ARMS),
-                ("policy", C.c_int32), ("n_bandits", C.c_int32), ("alpha", C.c_double)]
+                ("policy", C.c_int32), ("n_bandits", C.c_int32), ("alpha", C.c_double),
+                ("reward", C.c_int32), ("reserved", C.c_int32),
+                ("adaedl_gamma", C.c_double), ("adaedl_alpha", C.c_double), ("adaedl_beta1", C.c_double),
+                ("adaedl_beta2", C.c_double), ("adaedl_eps", C.c_double), ("adaedl_rate0", C.c_double)]
 
 
 class TapoutLogits(C.Structure):
@@ -67,8 +72,10 @@ def load_library():
         lib.tapout_draft_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 14
         lib.tapout_verify.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 15
         lib.tapout_bandit_update.argtypes = [vp, i32] + [vp] * 6
-        lib.tapout_bandit_get_state.argtypes = [vp] * 4
-        lib.tapout_bandit_set_state.argtypes = [vp] * 4
+        lib.tapout_bandit_get_state.argtypes = [vp] * 5
+        lib.tapout_bandit_set_state.argtypes = [vp] * 5
+        lib.tapout_rule_state_get.argtypes = [vp] * 5
+        lib.tapout_rule_state_set.argtypes = [vp] * 5
         lib.tapout_set_option.argtypes = [vp, C.c_char_p, i32]
         lib.tapout_profile_enable.argtypes = [vp, C.c_uint32, i32]
         lib.tapout_profile_read.argtypes = [vp, i32, C.POINTER(C.c_double), C.POINTER(i32), vp]
@@ -120,15 +127,19 @@ class Tapout:
 
     def __init__(self, max_batch: int, max_k: int, vocab: int, *, device: int = 0, policy: int = UCB1,
                  rules=(RULE_SVIP, RULE_MAXCONF, RULE_MARGIN), thresholds=(0.6, 0.8, 0.2),
-                 alpha: float = 0.5, shared_bandit: bool = False):
+                 alpha: float = 0.5, shared_bandit: bool = False, reward: int = REWARD_BLEND, adaedl: dict | None = None):
+        """adaedl: optional dict with any of gamma, alpha, beta1, beta2, eps, rate0 (tapout_config.adaedl_*)."""
         self._lib = load_library()
         cfg = default_config(max_batch, max_k, vocab)
         cfg.device = device
         cfg.policy = policy
         cfg.n_arms = len(rules)
-        for i, (r, h) in enumerate(zip(rules, thresholds)):
+        for i, (r, h) in enumerate(list(zip(rules, thresholds))[:MAX_ARMS]):       # more arms: tapout_create rejects n_arms
             cfg.rule[i], cfg.threshold[i] = r, h
         cfg.alpha = alpha
+        cfg.reward = reward
+        for k, v in (adaedl or {}).items():
+            setattr(cfg, "adaedl_" + k, float(v))
         cfg.n_bandits = 1 if shared_bandit else max_batch
         self.cfg = cfg
         self.device = torch.device("cuda", device)
@@ -284,16 +295,36 @@ class Tapout:
             _ptr(active, torch.uint8, (B,), "active"), _stream(stream)))
 
     # -- state read-out / restore (host arrays) ------------------------------
-    def bandit_get_state(self, stream=None):
+    def bandit_get_state(self, stream=None, moments: bool = False):
+        """(sum_r, count) or, with moments=True, (sum_r, sum_r2, count) as numpy arrays [n_bandits, n_arms]."""
         import numpy as np
         n = (self.cfg.n_bandits, self.cfg.n_arms)
-        s, c = np.zeros(n, np.float64), np.zeros(n, np.int64)
-        self._check(self._lib.tapout_bandit_get_state(self._ctx, s.ctypes.data, c.ctypes.data, _stream(stream)))
-        return s, c
+        s, q, c = np.zeros(n, np.float64), np.zeros(n, np.float64), np.zeros(n, np.int64)
+        self._check(self._lib.tapout_bandit_get_state(self._ctx, s.ctypes.data, q.ctypes.data, c.ctypes.data, _stream(stream)))
+        return (s, q, c) if moments else (s, c)
 
-    def bandit_set_state(self, sum_r, count, stream=None):
+    def bandit_set_state(self, sum_r, count, sum_r2=None, stream=None):
         import numpy as np
         n = (self.cfg.n_bandits, self.cfg.n_arms)
         s = np.ascontiguousarray(sum_r, np.float64).reshape(n)
         c = np.ascontiguousarray(count, np.int64).reshape(n)
-        self._check(self._lib.tapout_bandit_set_state(self._ctx, s.ctypes.data, c.ctypes.data, _stream(stream)))
+        q = None if sum_r2 is None else np.ascontiguousarray(sum_r2, np.float64).reshape(n)
+        self._check(self._lib.tapout_bandit_set_state(self._ctx, s.ctypes.data, None if q is None else q.ctypes.data,
+                                                      c.ctypes.data, _stream(stream)))
+
+    def rule_state_get(self, stream=None):
+        """dict(prev_entropy [max_batch] f32, accept_rate [max_batch] f64, lam [max_batch, n_arms] f64), numpy."""
+        import numpy as np
+        nb, A = self.cfg.max_batch, self.cfg.n_arms
+        pe, ar, lam = np.zeros(nb, np.float32), np.zeros(nb, np.float64), np.zeros((nb, A), np.float64)
+        self._check(self._lib.tapout_rule_state_get(self._ctx, pe.ctypes.data, ar.ctypes.data, lam.ctypes.data, _stream(stream)))
+        return dict(prev_entropy=pe, accept_rate=ar, lam=lam)
+
+    def rule_state_set(self, prev_entropy=None, accept_rate=None, lam=None, stream=None):
+        import numpy as np
+        nb, A = self.cfg.max_batch, self.cfg.n_arms
+        pe = None if prev_entropy is None else np.ascontiguousarray(prev_entropy, np.float32).reshape(nb)
+        ar = None if accept_rate is None else np.ascontiguousarray(accept_rate, np.float64).reshape(nb)
+        lm = None if lam is None else np.ascontiguousarray(lam, np.float64).reshape(nb, A)
+        d = lambda x: None if x is None else x.ctypes.data
+        self._check(self._lib.tapout_rule_state_set(self._ctx, d(pe), d(ar), d(lm), _stream(stream)))

@@ -19,7 +19,13 @@ struct tapout_ctx {
     uint32_t *flags_ws = nullptr;
     double *exp_table = nullptr;                               // 2^(k/256), k = 0..255, for the final-token passes
     int nsl_max = 0;                                           // final-token slices per row at cfg.vocab
-    double *sum_r = nullptr;      int64_t *count = nullptr;   // bandit state [n_bandits, n_arms]
+    double *sum_r = nullptr, *sum_r2 = nullptr; int64_t *count = nullptr;   // bandit state [n_bandits, n_arms]
+    // state of the stateful stop rules (allocated only when an arm needs it)
+    bool stateful = false;
+    float *prev_entropy = nullptr;                             // [max_batch]
+    double *accept_rate = nullptr, *lambda = nullptr;          // [max_batch], [max_batch, n_arms]
+    float *round_entropy = nullptr;                            // [max_batch, max_k] entropies of the last draft_stats call
+    int round_K = 0;                                           // its K (0: no draft_stats call yet)
     int wgs_target = 4096;        // workgroups a streaming launch aims for
     int min_slice = 4096;         // smallest slice (elements) a row is cut into
     // optional kernel timing (tapout_profile_*): event pairs around the launches of selected kernels
@@ -112,6 +118,22 @@ void profile_release(tapout_ctx *ctx)
     ctx->prof_mask = 0; ctx->prof_cap = 0;
 }
 
+BanditArgs bandit_args(const tapout_ctx *ctx, int B)
+{
+    BanditArgs a{};
+    a.policy = ctx->cfg.policy; a.n_bandits = ctx->cfg.n_bandits; a.n_arms = ctx->cfg.n_arms; a.B = B;
+    a.reward = ctx->cfg.reward; a.alpha = ctx->cfg.alpha;
+    a.sum_r = ctx->sum_r; a.sum_r2 = ctx->sum_r2; a.count = ctx->count;
+    for (int j = 0; j < TAPOUT_MAX_ARMS; ++j) a.rule[j] = ctx->cfg.rule[j];
+    if (ctx->stateful) {
+        a.prev_entropy = ctx->prev_entropy; a.accept_rate = ctx->accept_rate; a.lambda = ctx->lambda;
+        a.round_entropy = ctx->round_entropy; a.round_K = ctx->round_K;
+        a.ad_alpha = ctx->cfg.adaedl_alpha; a.ad_beta1 = ctx->cfg.adaedl_beta1; a.ad_beta2 = ctx->cfg.adaedl_beta2;
+        a.ad_eps = ctx->cfg.adaedl_eps;
+    }
+    return a;
+}
+
 tapout_status check_shape(tapout_ctx *ctx, int B, int K, int V)
 {
     if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
@@ -137,6 +159,9 @@ void tapout_default_config(tapout_config *cfg, int32_t max_batch, int32_t max_k,
     cfg->policy = TAPOUT_UCB1;
     cfg->n_bandits = max_batch;
     cfg->alpha = 0.5;
+    cfg->reward = TAPOUT_REWARD_BLEND;
+    cfg->adaedl_gamma = 0.5; cfg->adaedl_alpha = 0.9; cfg->adaedl_beta1 = 0.5; cfg->adaedl_beta2 = 0.9;
+    cfg->adaedl_eps = 0.01; cfg->adaedl_rate0 = 0.9;
 }
 
 tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
@@ -151,12 +176,23 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     if ((int64_t)cfg->max_batch * (cfg->max_k + 1) > (int64_t)1 << 26)
         return fail(nullptr, TAPOUT_EINVAL, "max_batch * (max_k + 1) exceeds 2^26 rows");
     if (cfg->n_arms < 1 || cfg->n_arms > TAPOUT_MAX_ARMS) return fail(nullptr, TAPOUT_EINVAL, "n_arms = %d outside [1, %d]", cfg->n_arms, TAPOUT_MAX_ARMS);
+    bool stateful = false, adaedl = false;
     for (int a = 0; a < cfg->n_arms; ++a) {
-        if (cfg->rule[a] < TAPOUT_RULE_SVIP || cfg->rule[a] > TAPOUT_RULE_MARGIN)
+        if (cfg->rule[a] < TAPOUT_RULE_SVIP || cfg->rule[a] > TAPOUT_RULE_ADAEDL)
             return fail(nullptr, TAPOUT_EUNSUPPORTED, "arm %d: rule %d is not implemented", a, cfg->rule[a]);
         if (!(cfg->threshold[a] == cfg->threshold[a])) return fail(nullptr, TAPOUT_EINVAL, "arm %d: threshold is NaN", a);
+        if (cfg->rule[a] == TAPOUT_RULE_SVIP_DIFF || cfg->rule[a] == TAPOUT_RULE_ADAEDL) stateful = true;
+        if (cfg->rule[a] == TAPOUT_RULE_ADAEDL) adaedl = true;
     }
-    if (cfg->policy != TAPOUT_UCB1 && cfg->policy != TAPOUT_TS_BETA) return fail(nullptr, TAPOUT_EUNSUPPORTED, "policy %d is not implemented", cfg->policy);
+    if (cfg->policy < TAPOUT_UCB1 || cfg->policy > TAPOUT_TS_GAUSS) return fail(nullptr, TAPOUT_EUNSUPPORTED, "policy %d is not implemented", cfg->policy);
+    if (cfg->reward != TAPOUT_REWARD_BLEND && cfg->reward != TAPOUT_REWARD_SIMPLE) return fail(nullptr, TAPOUT_EUNSUPPORTED, "reward %d is not implemented", cfg->reward);
+    if (adaedl) {
+        if (!(cfg->adaedl_gamma >= 0.0) || !(cfg->adaedl_gamma < INFINITY)) return fail(nullptr, TAPOUT_EINVAL, "adaedl_gamma must be finite and >= 0");
+        if (!(cfg->adaedl_beta1 >= 0.0 && cfg->adaedl_beta1 <= 1.0) || !(cfg->adaedl_beta2 >= 0.0 && cfg->adaedl_beta2 <= 1.0))
+            return fail(nullptr, TAPOUT_EINVAL, "adaedl_beta1 and adaedl_beta2 must lie in [0, 1]");
+        if (!(cfg->adaedl_alpha == cfg->adaedl_alpha) || !(cfg->adaedl_eps == cfg->adaedl_eps) || !(cfg->adaedl_rate0 == cfg->adaedl_rate0))
+            return fail(nullptr, TAPOUT_EINVAL, "adaedl_alpha, adaedl_eps and adaedl_rate0 must not be NaN");
+    }
     if (cfg->n_bandits != 1 && cfg->n_bandits != cfg->max_batch) return fail(nullptr, TAPOUT_EINVAL, "n_bandits must be 1 or max_batch");
     if (!(cfg->alpha >= 0.0 && cfg->alpha <= 1.0)) return fail(nullptr, TAPOUT_EINVAL, "alpha outside [0, 1]");
     int ndev = 0;
@@ -181,9 +217,26 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
            && hipMalloc(&c->jobs, (size_t)cfg->max_batch * sizeof(SampleJob)) == hipSuccess
            && hipMalloc(&c->flags_ws, (size_t)cfg->max_batch * sizeof(uint32_t)) == hipSuccess
            && hipMalloc(&c->sum_r, nstate * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->sum_r2, nstate * sizeof(double)) == hipSuccess
            && hipMalloc(&c->count, nstate * sizeof(int64_t)) == hipSuccess
            && hipMemset(c->sum_r, 0, nstate * sizeof(double)) == hipSuccess
+           && hipMemset(c->sum_r2, 0, nstate * sizeof(double)) == hipSuccess
            && hipMemset(c->count, 0, nstate * sizeof(int64_t)) == hipSuccess;
+    c->stateful = stateful;
+    if (ok && stateful) {
+        const size_t nb = (size_t)cfg->max_batch;
+        std::vector<float> pe(nb, NAN);
+        std::vector<double> ar(nb, cfg->adaedl_rate0), lam(nb * cfg->n_arms);
+        for (size_t b = 0; b < nb; ++b)
+            for (int a = 0; a < cfg->n_arms; ++a) lam[b * cfg->n_arms + a] = (double)cfg->threshold[a];
+        ok = hipMalloc(&c->prev_entropy, nb * sizeof(float)) == hipSuccess
+          && hipMalloc(&c->accept_rate, nb * sizeof(double)) == hipSuccess
+          && hipMalloc(&c->lambda, nb * cfg->n_arms * sizeof(double)) == hipSuccess
+          && hipMalloc(&c->round_entropy, nb * cfg->max_k * sizeof(float)) == hipSuccess
+          && hipMemcpy(c->prev_entropy, pe.data(), nb * sizeof(float), hipMemcpyHostToDevice) == hipSuccess
+          && hipMemcpy(c->accept_rate, ar.data(), nb * sizeof(double), hipMemcpyHostToDevice) == hipSuccess
+          && hipMemcpy(c->lambda, lam.data(), nb * cfg->n_arms * sizeof(double), hipMemcpyHostToDevice) == hipSuccess;
+    }
     if (!ok) {
         (void)hipGetLastError();
         tapout_destroy(c);
@@ -201,7 +254,8 @@ tapout_status tapout_destroy(tapout_ctx *ctx)
     (void)hipFree(ctx->part); (void)hipFree(ctx->part1); (void)hipFree(ctx->part2);
     (void)hipFree(ctx->jobs); (void)hipFree(ctx->flags_ws);
     (void)hipFree(ctx->exp_table);
-    (void)hipFree(ctx->sum_r); (void)hipFree(ctx->count);
+    (void)hipFree(ctx->sum_r); (void)hipFree(ctx->sum_r2); (void)hipFree(ctx->count);
+    (void)hipFree(ctx->prev_entropy); (void)hipFree(ctx->accept_rate); (void)hipFree(ctx->lambda); (void)hipFree(ctx->round_entropy);
     delete ctx;
     return TAPOUT_OK;
 }
@@ -228,9 +282,9 @@ tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const float *u_ts
     if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
     if (B == 0) return TAPOUT_OK;
     if (!arm_out) return fail(ctx, TAPOUT_EINVAL, "arm_out is NULL");
-    if (ctx->cfg.policy == TAPOUT_TS_BETA && !u_ts) return fail(ctx, TAPOUT_EINVAL, "Thompson Sampling needs u_ts");
+    if ((ctx->cfg.policy == TAPOUT_TS_BETA || ctx->cfg.policy == TAPOUT_TS_GAUSS) && !u_ts) return fail(ctx, TAPOUT_EINVAL, "Thompson Sampling needs u_ts");
     DeviceGuard guard(ctx->cfg.device);
-    BanditArgs a{ctx->cfg.policy, ctx->cfg.n_bandits, ctx->cfg.n_arms, B, ctx->cfg.alpha, ctx->sum_r, ctx->count};
+    BanditArgs a = bandit_args(ctx, B);
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = timed(ctx, TAPOUT_PROFILE_SELECT, [&](Timing tm) { return launch_bandit_select(a, u_ts, arm_out, flags, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_select launch");
@@ -245,7 +299,7 @@ tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *ar
     if (B == 0) return TAPOUT_OK;
     if (!arm || !accept_len || !n_draft || !gamma) return fail(ctx, TAPOUT_EINVAL, "arm, accept_len, n_draft and gamma are required");
     DeviceGuard guard(ctx->cfg.device);
-    BanditArgs a{ctx->cfg.policy, ctx->cfg.n_bandits, ctx->cfg.n_arms, B, ctx->cfg.alpha, ctx->sum_r, ctx->count};
+    BanditArgs a = bandit_args(ctx, B);
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = timed(ctx, TAPOUT_PROFILE_UPDATE, [&](Timing tm) { return launch_bandit_update(a, arm, accept_len, n_draft, gamma, active, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_update launch");
@@ -282,6 +336,11 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) { f.rule[a] = ctx->cfg.rule[a]; f.threshold[a] = ctx->cfg.threshold[a]; }
     f.lse = lse; f.entropy = entropy; f.p_top1 = p_top1; f.p_top2 = p_top2; f.margin = margin; f.logq_tok = logq_tok;
     f.top1_id = top1_id; f.n_stop = n_stop; f.stop_fired = stop_fired; f.flags = flags;
+    if (ctx->stateful) {
+        f.prev_entropy = ctx->prev_entropy; f.lambda = ctx->lambda; f.adaedl_gamma = ctx->cfg.adaedl_gamma;
+        f.round_entropy = ctx->round_entropy;
+        ctx->round_K = K;
+    }
     e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, [&](Timing tm) { return launch_draft_finalize(f, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft finalize launch");
 }
@@ -374,7 +433,7 @@ tapout_status tapout_profile_read(tapout_ctx *ctx, int32_t kind, double *total_m
     return TAPOUT_OK;
 }
 
-tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, int64_t *count, void *stream)
+tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, double *sum_r2, int64_t *count, void *stream)
 {
     if (!ctx) return TAPOUT_EINVAL;
     if (!sum_r || !count) return fail(ctx, TAPOUT_EINVAL, "sum_r and count are required");
@@ -382,25 +441,72 @@ tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, int64_t *c
     const size_t n = (size_t)ctx->cfg.n_bandits * ctx->cfg.n_arms;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = hipMemcpyAsync(sum_r, ctx->sum_r, n * sizeof(double), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess && sum_r2) e = hipMemcpyAsync(sum_r2, ctx->sum_r2, n * sizeof(double), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipMemcpyAsync(count, ctx->count, n * sizeof(int64_t), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_get_state");
 }
 
-tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *sum_r, const int64_t *count, void *stream)
+tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *sum_r, const double *sum_r2, const int64_t *count, void *stream)
 {
     if (!ctx) return TAPOUT_EINVAL;
     if (!sum_r || !count) return fail(ctx, TAPOUT_EINVAL, "sum_r and count are required");
     const size_t n = (size_t)ctx->cfg.n_bandits * ctx->cfg.n_arms;
-    for (size_t i = 0; i < n; ++i)
+    for (size_t i = 0; i < n; ++i) {
         if (count[i] < 0 || !(sum_r[i] >= 0.0) || sum_r[i] > (double)count[i])
             return fail(ctx, TAPOUT_EINVAL, "state entry %zu: need count >= 0 and 0 <= sum_r <= count", i);
+        if (sum_r2 && (!(sum_r2[i] >= 0.0) || sum_r2[i] > (double)count[i]))
+            return fail(ctx, TAPOUT_EINVAL, "state entry %zu: need 0 <= sum_r2 <= count", i);
+    }
+    std::vector<double> q;
+    if (!sum_r2) {                                   // all plays of an arm taken to have had its mean reward
+        q.resize(n);
+        for (size_t i = 0; i < n; ++i) q[i] = count[i] > 0 ? sum_r[i] * sum_r[i] / (double)count[i] : 0.0;
+        sum_r2 = q.data();
+    }
     DeviceGuard guard(ctx->cfg.device);
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = hipMemcpyAsync(ctx->sum_r, sum_r, n * sizeof(double), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(ctx->sum_r2, sum_r2, n * sizeof(double), hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipMemcpyAsync(ctx->count, count, n * sizeof(int64_t), hipMemcpyHostToDevice, st);
     if (e == hipSuccess) e = hipStreamSynchronize(st);
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_set_state");
+}
+
+tapout_status tapout_rule_state_get(tapout_ctx *ctx, float *prev_entropy, double *accept_rate, double *lambda, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (!ctx->stateful) return fail(ctx, TAPOUT_EINVAL, "the configuration has no SVIP_DIFF or ADAEDL arm: no rule state");
+    DeviceGuard guard(ctx->cfg.device);
+    const size_t nb = (size_t)ctx->cfg.max_batch;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    if (prev_entropy) e = hipMemcpyAsync(prev_entropy, ctx->prev_entropy, nb * sizeof(float), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess && accept_rate) e = hipMemcpyAsync(accept_rate, ctx->accept_rate, nb * sizeof(double), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess && lambda) e = hipMemcpyAsync(lambda, ctx->lambda, nb * ctx->cfg.n_arms * sizeof(double), hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "rule_state_get");
+}
+
+tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *prev_entropy, const double *accept_rate, const double *lambda, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (!ctx->stateful) return fail(ctx, TAPOUT_EINVAL, "the configuration has no SVIP_DIFF or ADAEDL arm: no rule state");
+    const size_t nb = (size_t)ctx->cfg.max_batch;
+    if (accept_rate)
+        for (size_t i = 0; i < nb; ++i)
+            if (!(accept_rate[i] == accept_rate[i])) return fail(ctx, TAPOUT_EINVAL, "accept_rate[%zu] is NaN", i);
+    if (lambda)
+        for (size_t i = 0; i < nb * ctx->cfg.n_arms; ++i)
+            if (!(lambda[i] == lambda[i])) return fail(ctx, TAPOUT_EINVAL, "lambda[%zu] is NaN", i);
+    DeviceGuard guard(ctx->cfg.device);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    if (prev_entropy) e = hipMemcpyAsync(ctx->prev_entropy, prev_entropy, nb * sizeof(float), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess && accept_rate) e = hipMemcpyAsync(ctx->accept_rate, accept_rate, nb * sizeof(double), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess && lambda) e = hipMemcpyAsync(ctx->lambda, lambda, nb * ctx->cfg.n_arms * sizeof(double), hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipStreamSynchronize(st);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "rule_state_set");
 }
 
 }  // extern "C"

@@ -1,7 +1,11 @@
-// Sequence-level bandit over the stop rules (Section 3.3) and the blended
-// reward (Section 3.2).  State: per bandit and arm the number of plays N and
-// the summed reward S, in double / int64.  One thread per sequence; the work
-// is O(B * arms) and never touches the vocabulary.
+// Sequence-level bandit over the stop rules (Section 3.3: UCB1, UCB-Tuned,
+// Thompson Sampling with Beta or Gaussian posteriors) and the rewards of
+// Section 3.2.  State: per bandit and arm the number of plays N, the summed
+// reward S and the summed squared reward Q, in int64 / double.  The update also
+// advances the carried state of the stateful stop rules of Appendix A.1
+// (SVIP-Difference's previous entropy, AdaEDL's acceptance rate and thresholds).
+// One thread per sequence; the work is O(B * arms) and never touches the
+// vocabulary.
 //
 // This file is compiled without floating-point contraction: every product,
 // quotient and sum below is a separately rounded IEEE double operation.
@@ -51,6 +55,42 @@ __device__ inline int ucb1_arm(const double *S, const int64_t *N, int A)
     return best;
 }
 
+// UCB-Tuned: bonus sqrt((ln t / N) min(1/4, V)), V = var + sqrt(2 ln t / N), var = Q/N - mean^2.
+__device__ inline int ucb_tuned_arm(const double *S, const double *Q, const int64_t *N, int A)
+{
+    int64_t t = 1;
+    for (int a = 0; a < A; ++a) t += N[a];
+    const double lt = log((double)t);
+    int best = 0;
+    double best_v = -INFINITY;
+    for (int a = 0; a < A; ++a) {
+        if (N[a] == 0) return a;
+        const double n = (double)N[a];
+        const double mean = S[a] / n;
+        const double var = Q[a] / n - mean * mean;
+        const double V = var + sqrt((2.0 * lt) / n);
+        const double cap = V < 0.25 ? V : 0.25;
+        const double v = mean + sqrt((lt / n) * cap);
+        if (a == 0 || v > best_v) { best = a; best_v = v; }
+    }
+    return best;
+}
+
+// Gaussian posterior N(S/(N+1), 1/(N+1)); one Box-Muller normal from the arm's first two uniforms.
+__device__ inline int ts_gauss_arm(const double *S, const int64_t *N, int A, const float *u)
+{
+    int best = 0;
+    double best_v = -INFINITY;
+    for (int a = 0; a < A; ++a) {
+        const float *ua = u + (size_t)a * TAPOUT_TS_UNIFORMS_PER_ARM;
+        const double n1 = (double)N[a] + 1.0;
+        const double z = sqrt(-2.0 * log(unit_open(ua[0]))) * cos(6.283185307179586476925 * (double)ua[1]);
+        const double th = S[a] / n1 + z / sqrt(n1);
+        if (a == 0 || th > best_v) { best = a; best_v = th; }
+    }
+    return best;
+}
+
 __device__ inline int ts_arm(const double *S, const int64_t *N, int A, const float *u, bool *exhausted)
 {
     int best = 0;
@@ -76,17 +116,38 @@ __global__ void bandit_select_kernel(BanditArgs a, const float *u_ts, int32_t *a
     const int64_t *N = a.count + (size_t)nb * a.n_arms;
     bool ex = false;
     int arm;
+    const float *u = u_ts ? u_ts + (size_t)nb * a.n_arms * TAPOUT_TS_UNIFORMS_PER_ARM : nullptr;
     if (a.policy == TAPOUT_UCB1) arm = ucb1_arm(S, N, a.n_arms);
-    else arm = ts_arm(S, N, a.n_arms, u_ts + (size_t)nb * a.n_arms * TAPOUT_TS_UNIFORMS_PER_ARM, &ex);
+    else if (a.policy == TAPOUT_UCB_TUNED) arm = ucb_tuned_arm(S, a.sum_r2 + (size_t)nb * a.n_arms, N, a.n_arms);
+    else if (a.policy == TAPOUT_TS_GAUSS) arm = ts_gauss_arm(S, N, a.n_arms, u);
+    else arm = ts_arm(S, N, a.n_arms, u, &ex);
     arm_out[b] = arm;
     if (flags) flags[b] = ex ? TAPOUT_FLAG_SAMPLER_EXHAUSTED : 0u;
 }
 
 __device__ inline void apply_reward(const BanditArgs &a, int nb, int arm, int m, int n, int g)
 {
-    double r = (a.alpha * (double)m) / (double)g + ((1.0 - a.alpha) * (double)m) / (double)n;
+    const double r = a.reward == TAPOUT_REWARD_SIMPLE
+                         ? (double)m / (double)g
+                         : (a.alpha * (double)m) / (double)g + ((1.0 - a.alpha) * (double)m) / (double)n;
     a.count[(size_t)nb * a.n_arms + arm] += 1;
     a.sum_r[(size_t)nb * a.n_arms + arm] += r;
+    a.sum_r2[(size_t)nb * a.n_arms + arm] += r * r;
+}
+
+// Carried state of the stateful stop rules after one draft of sequence b (Appendix A.1).
+__device__ inline void advance_rule_state(const BanditArgs &a, int b, int m, int n)
+{
+    if (a.round_K > 0) a.prev_entropy[b] = a.round_entropy[(int64_t)b * a.round_K + (n - 1)];
+    const double r = (double)m / (double)n;
+    const double rate = a.ad_beta1 * a.accept_rate[b] + (1.0 - a.ad_beta1) * r;
+    a.accept_rate[b] = rate;
+    const double sg = a.ad_alpha > rate ? 1.0 : (a.ad_alpha < rate ? -1.0 : 0.0);
+    for (int j = 0; j < a.n_arms; ++j) {
+        if (a.rule[j] != TAPOUT_RULE_ADAEDL) continue;
+        const double lam = a.lambda[(int64_t)b * a.n_arms + j];
+        a.lambda[(int64_t)b * a.n_arms + j] = a.ad_beta2 * lam + (1.0 - a.ad_beta2) * (lam + a.ad_eps * sg);
+    }
 }
 
 __device__ inline bool playable(const BanditArgs &a, int b, const int32_t *arm, const int32_t *n_draft,
@@ -99,18 +160,20 @@ __device__ inline bool playable(const BanditArgs &a, int b, const int32_t *arm, 
 __global__ void bandit_update_kernel(BanditArgs a, const int32_t *arm, const int32_t *accept_len,
                                      const int32_t *n_draft, const int32_t *gamma, const uint8_t *active)
 {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (a.n_bandits == 1) {
         // shared bandit: the B plays are applied in index order by one thread
-        if (blockIdx.x == 0 && threadIdx.x == 0)
-            for (int b = 0; b < a.B; ++b)
-                if (playable(a, b, arm, n_draft, gamma, active))
-                    apply_reward(a, 0, arm[b], accept_len[b], n_draft[b], gamma[b]);
-        return;
-    }
-    const int b = blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= a.B) return;
-    if (playable(a, b, arm, n_draft, gamma, active))
+        if (b == 0)
+            for (int i = 0; i < a.B; ++i)
+                if (playable(a, i, arm, n_draft, gamma, active))
+                    apply_reward(a, 0, arm[i], accept_len[i], n_draft[i], gamma[i]);
+    } else if (b < a.B && playable(a, b, arm, n_draft, gamma, active)) {
         apply_reward(a, b, arm[b], accept_len[b], n_draft[b], gamma[b]);
+    }
+    if (a.accept_rate && b < a.B && !(active && !active[b])) {
+        const int n = n_draft[b];
+        if (n >= 1 && (a.round_K == 0 || n <= a.round_K)) advance_rule_state(a, b, accept_len[b], n);
+    }
 }
 
 }  // namespace
@@ -126,7 +189,7 @@ hipError_t launch_bandit_update(const BanditArgs &a, const int32_t *arm, const i
                                 const int32_t *n_draft, const int32_t *gamma, const uint8_t *active, hipStream_t st, Timing tm)
 {
     const int block = 64;
-    int grid = a.n_bandits == 1 ? 1 : (a.B + block - 1) / block;
+    int grid = (a.n_bandits == 1 && !a.accept_rate) ? 1 : (a.B + block - 1) / block;
     launch_kernel(bandit_update_kernel, dim3(grid), dim3(block), st, tm, a, arm, accept_len, n_draft, gamma, active);
     return hipGetLastError();
 }

@@ -74,13 +74,17 @@ struct DraftFinalArgs {
     int32_t n_arms; int32_t rule[TAPOUT_MAX_ARMS]; float threshold[TAPOUT_MAX_ARMS];
     float *lse, *entropy, *p_top1, *p_top2, *margin, *logq_tok;
     int32_t *top1_id, *n_stop; uint8_t *stop_fired; uint32_t *flags;
+    // stateful rules (SVIP-Difference, AdaEDL); all NULL when the configuration has no such arm
+    const float *prev_entropy;    // [B] entropy of the last drafted position of the previous draft, NaN = none
+    const double *lambda;         // [B, n_arms] AdaEDL thresholds
+    double adaedl_gamma;
+    float *round_entropy;         // [B, K] entropies of this draft, kept for the state update
 };
 hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st, Timing tm);
 
-// Verification + final token.  Kernel 1 merges the target partials of its sequence, takes the
-// accept decisions (every workgroup of the sequence redundantly; slice 0 writes the outputs) and
-// then sums its slice of exp(t - ref_p), exp(d - ref_q); kernel 2 forms the slice weights of the
-// residual; kernel 3 locates the token.
+// Verification + final token: the head kernel merges the target partials of each sequence, takes the
+// accept decisions and describes the final-token draw (SampleJob); the slice kernel sums the row pair
+// per slice; the locate kernel finds the token.
 struct VerifyArgs {
     const void *tbase; int32_t t_dtype; int64_t t_stride_b, t_stride_k;
     const void *dbase; int32_t d_dtype; int64_t d_stride_b, d_stride_k;
@@ -103,8 +107,14 @@ constexpr int kSampleSlice = 2048;   // elements per slice of the final-token pa
 
 struct BanditArgs {
     int32_t policy, n_bandits, n_arms, B;
+    int32_t reward;               // tapout_reward
     double alpha;
-    double *sum_r; int64_t *count;
+    double *sum_r, *sum_r2; int64_t *count;
+    // stateful stop rules (all NULL when the configuration has no such arm)
+    int32_t rule[TAPOUT_MAX_ARMS];
+    float *prev_entropy; double *accept_rate; double *lambda;
+    const float *round_entropy; int32_t round_K;      // entropies of the last draft_stats call, [B, round_K]; round_K = 0: none
+    double ad_alpha, ad_beta1, ad_beta2, ad_eps;
 };
 hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm);
 hipError_t launch_bandit_update(const BanditArgs &a, const int32_t *arm, const int32_t *accept_len,

@@ -9,7 +9,10 @@
 // few: the partials are staged through LDS by all threads at once, the token
 // gather and the argmax window are loaded before the fp64 math that does not
 // need them, and every row decides "fires / does not fire" for itself so that
-// the sequential part is a scan over bytes in LDS.
+// the sequential part is a scan over bytes in LDS.  The two rules that look at
+// more than the current row's signals (SVIP-Difference: previous row's entropy;
+// AdaEDL: the sequence's adaptive threshold) decide in a second sweep, after all
+// entropies of the sequence are in LDS.
 #include "common.h"
 
 namespace tapout {
@@ -28,10 +31,25 @@ __device__ inline bool rule_fires(int rule, float h, float H, float p1, float ma
     }
 }
 
+// SVIP-Difference (Table 1): sqrt(H_t) - sqrt(H_{t-1}) > h; no previous entropy (NaN) or a bad row: no stop.
+__device__ inline bool svip_diff_fires(float h, float H, float H_prev)
+{
+    if (H != H || H_prev != H_prev) return false;
+    return sqrt((double)H) - sqrt((double)H_prev) > (double)h;
+}
+
+// AdaEDL (Table 1): 1 - sqrt(g H) < lambda.
+__device__ inline bool adaedl_fires(double g, double lambda, float H)
+{
+    if (H != H) return false;
+    return 1.0 - sqrt(g * (double)H) < lambda;
+}
+
 __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalArgs a)
 {
     __shared__ Partial sh_part[kStageCap];
     __shared__ uint8_t sh_dec[kScanCap];
+    __shared__ float sh_H[kScanCap];                           // entropies of the sequence (stateful rules only)
     __shared__ uint32_t sh_flags;
     const int b = blockIdx.x;
     const int K = a.K;
@@ -47,6 +65,12 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
     const int arm = a.arm ? a.arm[b] : -1;
     const bool arm_ok = arm >= 0 && arm < a.n_arms;
+    const int rule_b = arm_ok ? a.rule[arm] : -1;
+    const bool late = rule_b == TAPOUT_RULE_SVIP_DIFF || rule_b == TAPOUT_RULE_ADAEDL;     // uniform over the workgroup
+    float H_carry = NAN;
+    double lam_b = 0.0;
+    if (late && rule_b == TAPOUT_RULE_SVIP_DIFF && a.prev_entropy) H_carry = a.prev_entropy[b];
+    if (late && rule_b == TAPOUT_RULE_ADAEDL) lam_b = a.lambda ? a.lambda[(int64_t)b * a.n_arms + arm] : (double)a.threshold[arm];
     if (threadIdx.x == 0) sh_flags = 0;
     for (int k0 = 0; k0 < kb; k0 += rows_per_stage) {
         const int k1 = min(kb, k0 + rows_per_stage);
@@ -95,15 +119,31 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
                 if (t < 0 || t >= a.V) { f |= TAPOUT_FLAG_BAD_TOKEN; a.logq_tok[i] = NAN; }
                 else a.logq_tok[i] = (float)((double)xt - lse_d);
             }
+            if (a.round_entropy) a.round_entropy[i] = H;
             if (a.arm) {
-                const bool fire = arm_ok && rule_fires(a.rule[arm], a.threshold[arm], H, p1, mg);
-                if (a.stop_fired) a.stop_fired[i] = fire ? 1 : 0;
-                sh_dec[k] = fire ? 1 : 0;                      // k < K <= kScanCap
+                if (late) {
+                    sh_H[k] = H;                               // decided below, once every row's entropy is known
+                } else {
+                    const bool fire = arm_ok && rule_fires(a.rule[arm], a.threshold[arm], H, p1, mg);
+                    if (a.stop_fired) a.stop_fired[i] = fire ? 1 : 0;
+                    sh_dec[k] = fire ? 1 : 0;                  // k < K <= kScanCap
+                }
             }
             if (f) atomicOr(&sh_flags, f);
         }
     }
     __syncthreads();                       // orders the LDS / scratch writes above before the scan
+    if (late) {
+        for (int k = threadIdx.x; k < kb; k += blockDim.x) {
+            const float H = sh_H[k];
+            const bool fire = rule_b == TAPOUT_RULE_SVIP_DIFF
+                                  ? svip_diff_fires(a.threshold[arm], H, k > 0 ? sh_H[k - 1] : H_carry)
+                                  : adaedl_fires(a.adaedl_gamma, lam_b, H);
+            if (a.stop_fired) a.stop_fired[(int64_t)b * K + k] = fire ? 1 : 0;
+            sh_dec[k] = fire ? 1 : 0;
+        }
+        __syncthreads();
+    }
     if (threadIdx.x == 0) {
         if (a.flags) a.flags[b] = sh_flags;
         if (a.arm && a.n_stop) {

@@ -59,8 +59,10 @@ def assert_stats_close(name, gpu, ref, mask=None, tau=TAU):
                            f" gpu={gpu[bad][0]!r} ref={ref[bad][0]!r}")
 
 
-def oracle_round(rnd, arm=None, n_draft=None, rules=(0, 1, 2), thresholds=(0.6, 0.8, 0.2), nthreads=16, seqs=None):
-    """Oracle on host copies of a round.  seqs: optional index list (subset of sequences)."""
+def oracle_round(rnd, arm=None, n_draft=None, rules=(0, 1, 2), thresholds=(0.6, 0.8, 0.2), nthreads=16, seqs=None,
+                 prev_entropy=None, lam=None, adaedl_gamma=0.5):
+    """Oracle on host copies of a round.  seqs: optional index list (subset of sequences).
+    prev_entropy / lam / adaedl_gamma: carried state of the stateful stop rules (oracle.RuleState)."""
     pick = (lambda t: t) if seqs is None else (lambda t: t[seqs])
     draft = host_logits(pick(rnd["draft"]))
     target = host_logits(pick(rnd["target"]))
@@ -68,7 +70,8 @@ def oracle_round(rnd, arm=None, n_draft=None, rules=(0, 1, 2), thresholds=(0.6, 
     k_len = pick(rnd["k_len"]).cpu().numpy()
     greedy = pick(rnd["greedy"]).cpu().numpy()
     arm_h = None if arm is None else pick(arm).cpu().numpy()
-    ds = orc.draft_stats(draft, draft_tok=tok, k_len=k_len, arm=arm_h, rules=rules, thresholds=thresholds, nthreads=nthreads)
+    ds = orc.draft_stats(draft, draft_tok=tok, k_len=k_len, arm=arm_h, rules=rules, thresholds=thresholds, nthreads=nthreads,
+                         prev_entropy=prev_entropy, lam=lam, adaedl_gamma=adaedl_gamma)
     if n_draft is None:
         nd = ds["n_stop"] if arm is not None else k_len
     else:

@@ -1,5 +1,7 @@
 """GPU parity: libtapout (through its C ABI) against the CPU oracle, element by
 element, on the same seeded inputs.  Tolerances are defined in parity_util."""
+import math
+
 import numpy as np
 import pytest
 import torch
@@ -258,18 +260,21 @@ def test_full_size_sampled_sequences(name, n_seq):
 
 # ---- bandit -----------------------------------------------------------------------
 
-@pytest.mark.parametrize("policy", [binding.UCB1, binding.TS_BETA])
+@pytest.mark.parametrize("policy,reward", [(binding.UCB1, binding.REWARD_BLEND), (binding.TS_BETA, binding.REWARD_BLEND),
+                                           (binding.UCB_TUNED, binding.REWARD_BLEND), (binding.TS_GAUSS, binding.REWARD_BLEND),
+                                           (binding.UCB1, binding.REWARD_SIMPLE), (binding.UCB_TUNED, binding.REWARD_SIMPLE)])
 @pytest.mark.parametrize("shared", [False, True])
-def test_bandit_trajectory_matches_oracle(policy, shared):
+def test_bandit_trajectory_matches_oracle(policy, reward, shared):
     B, K, A, rounds = 37, 8, 3, 300
-    tp = binding.Tapout(B, K, 1000, policy=policy, shared_bandit=shared)
-    ob = orc.Bandit(policy, 1 if shared else B, A)
+    tp = binding.Tapout(B, K, 1000, policy=policy, shared_bandit=shared, reward=reward)
+    ob = orc.Bandit(policy, 1 if shared else B, A, reward_kind=reward)
+    needs_u = policy in (binding.TS_BETA, binding.TS_GAUSS)
     g = torch.Generator().manual_seed(5)
     for r in range(rounds):
         u = torch.rand(B, A, 48, generator=g)
         if r % 50 == 7:
             u[:, :, ::3] = 0.0                                           # zero uniforms hit the 2^-25 substitution
-        arm = tp.bandit_select(B, u_ts=u.to(DEV) if policy == binding.TS_BETA else None)
+        arm = tp.bandit_select(B, u_ts=u.to(DEV) if needs_u else None)
         o_arm, _ = ob.select(B, u.numpy())
         assert arm.cpu().tolist() == o_arm.tolist(), f"round {r}"
         gamma = torch.randint(1, K + 1, (B,), generator=g, dtype=torch.int32)
@@ -278,16 +283,20 @@ def test_bandit_trajectory_matches_oracle(policy, shared):
         active = (torch.rand(B, generator=g) < 0.9).to(torch.uint8)
         tp.bandit_update(arm, m.to(DEV), n.to(DEV), gamma.to(DEV), active=active.to(DEV))
         ob.update(o_arm, m.numpy(), n.numpy(), gamma.numpy(), active=active.numpy())
-    s, c = tp.bandit_get_state()
+    s, q, c = tp.bandit_get_state(moments=True)
     assert (c == ob.count).all()
-    assert (s == ob.sum_r).all()                                         # same fp64 operations in the same order
+    assert (s == ob.sum_r).all() and (q == ob.sum_r2).all()              # same fp64 operations in the same order
     # restore round trip
-    tp2 = binding.Tapout(B, K, 1000, policy=policy, shared_bandit=shared)
-    tp2.bandit_set_state(s, c)
+    tp2 = binding.Tapout(B, K, 1000, policy=policy, shared_bandit=shared, reward=reward)
+    tp2.bandit_set_state(s, c, sum_r2=q)
     u = torch.rand(B, A, 48, generator=g)
-    a1 = tp.bandit_select(B, u_ts=u.to(DEV) if policy == binding.TS_BETA else None)
-    a2 = tp2.bandit_select(B, u_ts=u.to(DEV) if policy == binding.TS_BETA else None)
+    a1 = tp.bandit_select(B, u_ts=u.to(DEV) if needs_u else None)
+    a2 = tp2.bandit_select(B, u_ts=u.to(DEV) if needs_u else None)
     assert torch.equal(a1, a2)
+    # without the second moments the restored bandit takes every play of an arm to have had its mean reward
+    tp2.bandit_set_state(s, c)
+    _, q2, _ = tp2.bandit_get_state(moments=True)
+    np.testing.assert_allclose(q2, np.where(c > 0, s * s / np.maximum(c, 1), 0.0), rtol=1e-15)
 
 
 @pytest.mark.parametrize("name", ["tiny", "small"])
@@ -317,6 +326,123 @@ def test_closed_loop_rounds(name):
     s, c = tp.bandit_get_state()
     assert (c == ob.count).all() and (s == ob.sum_r).all()
     assert flagged <= 2
+
+
+FIVE_RULES = (binding.RULE_SVIP, binding.RULE_MAXCONF, binding.RULE_MARGIN, binding.RULE_SVIP_DIFF, binding.RULE_ADAEDL)
+FIVE_THRESHOLDS = (0.6, 0.8, 0.2, 0.2, 0.4)
+
+
+@pytest.mark.parametrize("name,shared", [("small", False), ("small", True), ("llama3", False)])
+def test_stateful_rules_closed_loop(name, shared):
+    """The paper's full pool of five arms (Table 1): SVIP-Difference and AdaEDL carry state from draft to draft
+    (previous entropy; smoothed acceptance rate and threshold), so the loop is compared round by round,
+    decisions and state."""
+    w = synth.WORKLOADS[name]
+    w = synth.scaled(w, B=8, sigma_draft=7.0) if name == "small" else synth.scaled(w, B=6, V=20000)
+    ad = dict(gamma=0.5, alpha=0.6, beta1=0.5, beta2=0.9, eps=0.05, rate0=0.6)
+    tp = binding.Tapout(w.B, w.K, w.V, rules=FIVE_RULES, thresholds=FIVE_THRESHOLDS, shared_bandit=shared, adaedl=ad)
+    ob = orc.Bandit(orc.POLICY_UCB1, 1 if shared else w.B, 5)
+    st = orc.RuleState(w.B, FIVE_RULES, FIVE_THRESHOLDS, ad_alpha=ad["alpha"], beta1=ad["beta1"], beta2=ad["beta2"],
+                       eps=ad["eps"], rate0=ad["rate0"])
+    gen = synth.RoundGenerator(w, DEV)
+    g0 = tp.rule_state_get()
+    assert np.isnan(g0["prev_entropy"]).all() and (g0["accept_rate"] == 0.6).all()
+    assert (g0["lam"] == np.float32(FIVE_THRESHOLDS).astype(np.float64)[None, :]).all()
+    flagged, fired_by_rule = 0, np.zeros(5, int)
+    for r in range(14):
+        rnd = gen.round(r)
+        arm = tp.bandit_select(w.B)
+        o_arm, _ = ob.select(w.B)
+        assert arm.cpu().tolist() == o_arm.tolist(), f"round {r}"
+        if r >= 10:                                               # late rounds: force the two stateful arms
+            arm = torch.full_like(arm, 3 + (r & 1)); o_arm = arm.cpu().numpy()
+        gds, gvf, g_nd = pu.gpu_round(tp, rnd, arm=arm)
+        ods, ovf, o_nd = pu.oracle_round(rnd, arm=arm, rules=FIVE_RULES, thresholds=FIVE_THRESHOLDS,
+                                         prev_entropy=st.prev_entropy, lam=st.lam, adaedl_gamma=ad["gamma"])
+        gvf = dict(gvf); gvf["n_draft_used"] = g_nd
+        c = pu.compare_round(gds, gvf, ods, ovf, rnd["k_len"].cpu().numpy(), o_nd)
+        flagged += c["stop_flagged"] + c["accept_flagged"]
+        for b in range(w.B):
+            if ods["stop_fired"][b, ods["n_stop"][b] - 1]:
+                fired_by_rule[FIVE_RULES[int(o_arm[b])]] += 1
+        tp.bandit_update(arm, gvf["accept_len"], g_nd, rnd["k_len"])
+        # the oracle's state follows the GPU's integer decisions so that a near-tie flip cannot cascade
+        ob.update(o_arm, gvf["accept_len"].cpu().numpy(), g_nd.cpu().numpy(), rnd["k_len"].cpu().numpy())
+        st.update(ods["entropy"], g_nd.cpu().numpy(), gvf["accept_len"].cpu().numpy())
+        gs = tp.rule_state_get()
+        pu.assert_stats_close("entropy", gs["prev_entropy"], st.prev_entropy)
+        assert (gs["accept_rate"] == st.accept_rate).all(), f"round {r}"
+        assert (gs["lam"] == st.lam).all(), f"round {r}"
+    s, c = tp.bandit_get_state()
+    assert (c == ob.count).all() and (s == ob.sum_r).all()
+    assert flagged <= 2
+    assert fired_by_rule[3] > 0 and fired_by_rule[4] > 0, fired_by_rule       # both stateful rules actually stopped drafts
+    assert len(np.unique(st.lam[:, 4])) > 1 or st.lam[0, 4] != np.float32(0.4)  # and the AdaEDL threshold moved
+    # restore: a fresh context given the state continues identically
+    tp2 = binding.Tapout(w.B, w.K, w.V, rules=FIVE_RULES, thresholds=FIVE_THRESHOLDS, shared_bandit=shared, adaedl=ad)
+    tp2.rule_state_set(**tp.rule_state_get())
+    rnd = gen.round(99)
+    arm = torch.full((w.B,), 3, dtype=torch.int32, device=DEV)
+    arm[::2] = 4
+    d1 = tp.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arm)
+    d2 = tp2.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arm)
+    assert torch.equal(d1["n_stop"], d2["n_stop"]) and torch.equal(d1["stop_fired"], d2["stop_fired"])
+
+
+def test_stateful_rules_on_closed_form_rows():
+    """Rows uniform over n tokens (entropy ln n): the decisions are known in closed form (Table 1)."""
+    V, sizes = 5000, [[2, 3, 4, 8], [8, 4, 3, 2], [3, 4, 8, 16]]
+    x = torch.full((3, 4, V), float("-inf"))
+    for b, row in enumerate(sizes):
+        for k, n in enumerate(row):
+            x[b, k, 100 * k + b: 100 * k + b + n] = 0.75
+    for dt in (torch.float32, torch.bfloat16):
+        tp = binding.Tapout(3, 4, V, rules=(binding.RULE_SVIP_DIFF, binding.RULE_ADAEDL), thresholds=(0.2, 0.3))
+        xd = x.to(dt).to(DEV)
+        arm = torch.zeros(3, dtype=torch.int32, device=DEV)
+        o = tp.draft_stats(xd, arm=arm)
+        assert o["stop_fired"].cpu().tolist() == [[0, 1, 0, 1], [0, 0, 0, 0], [0, 0, 1, 1]]
+        assert o["n_stop"].cpu().tolist() == [2, 4, 3]
+        # carried entropies: 0.3 makes the first step of sequence 0 a jump of 0.2848; NaN means no history
+        tp.rule_state_set(prev_entropy=[0.3, float("nan"), 0.9])
+        o = tp.draft_stats(xd, arm=arm)
+        assert o["stop_fired"].cpu()[:, 0].tolist() == [1, 0, 0] and o["n_stop"].cpu().tolist() == [1, 4, 3]
+        # AdaEDL, g = 0.5: 1 - sqrt(0.5 ln n) = 0.4113, 0.2588, 0.1674, -0.0197 for n = 2, 3, 4, 8
+        o = tp.draft_stats(xd, arm=arm + 1)
+        assert o["stop_fired"].cpu().tolist() == [[0, 1, 1, 1], [1, 1, 1, 0], [1, 1, 1, 1]]
+        lam = np.zeros((3, 2)); lam[:, 1] = (0.1, 0.42, -1.0)
+        tp.rule_state_set(lam=lam)
+        o = tp.draft_stats(xd, arm=arm + 1)
+        assert o["stop_fired"].cpu().tolist() == [[0, 0, 0, 1], [1, 1, 1, 1], [0, 0, 0, 0]]
+        # the update takes the entropy of the last drafted row and moves lambda by (1 - beta2) eps
+        n_draft = torch.tensor([2, 4, 1], dtype=torch.int32, device=DEV)
+        acc = torch.tensor([2, 0, 1], dtype=torch.int32, device=DEV)
+        tp.bandit_update(arm + 1, acc, n_draft, torch.full_like(n_draft, 4), active=torch.tensor([1, 1, 0], dtype=torch.uint8, device=DEV))
+        st = tp.rule_state_get()
+        np.testing.assert_allclose(st["prev_entropy"][:2], [math.log(3), math.log(2)], rtol=1e-5)
+        assert st["prev_entropy"][2] == np.float32(0.9)                          # inactive: untouched
+        assert st["accept_rate"].tolist() == [0.5 * 0.9 + 0.5 * 1.0, 0.5 * 0.9 + 0.5 * 0.0, 0.9]
+        np.testing.assert_allclose(st["lam"][:, 1], [0.1 - 0.001, 0.42 + 0.001, -1.0], atol=1e-15)
+
+
+def test_several_thresholds_per_rule():
+    """Arm lists with several thresholds per rule (the paper's "more arms" ablation, Appendix A.2)."""
+    w = synth.scaled(synth.WORKLOADS["llama3"], B=16, V=12000)
+    rules = (0, 0, 0, 1, 1, 2, 2, 3)
+    thresholds = (0.2, 0.4, 0.6, 0.5, 0.8, 0.1, 0.2, 0.1)
+    tp = binding.Tapout(w.B, w.K, w.V, rules=rules, thresholds=thresholds)
+    rnd = synth.RoundGenerator(w, DEV).round(3)
+    arm = (torch.arange(w.B, dtype=torch.int32) % 8).to(DEV)
+    gds = tp.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arm)
+    ods, _, _ = pu.oracle_round(rnd, arm=arm, rules=rules, thresholds=thresholds)
+    near = (ods["stop_margin"] <= pu.TAU).any(1)
+    assert near.sum() <= 1
+    assert (gds["n_stop"].cpu().numpy()[~near] == ods["n_stop"][~near]).all()
+    assert len(set(ods["n_stop"].tolist())) > 1
+    with pytest.raises(binding.TapoutError):
+        binding.Tapout(4, 4, 100, rules=(0,) * 9, thresholds=(0.5,) * 9)
+    with pytest.raises(binding.TapoutError):
+        binding.Tapout(4, 4, 100, rules=(5,), thresholds=(0.5,))
 
 
 # ---- boundary error handling --------------------------------------------------------

@@ -32,6 +32,9 @@ def parse():
     ap.add_argument("--workload", default="llama3", choices=["tiny", "small", "llama3", "zipf", "ragged"])
     ap.add_argument("--mode", default="full", choices=["full", "truncate"],
                     help="full: verify all K drafted tokens (stop signals still computed); truncate: verify up to the stop position")
+    ap.add_argument("--arms", default="three", choices=["three", "five"],
+                    help="three: SVIP / Max-Confidence / LogitMargin (the default pool); five: plus SVIPDifference and AdaEDL (Table 1)")
+    ap.add_argument("--policy", default=None, choices=["ucb1", "ts", "ucb_tuned", "ts_gauss"], help="bandit policy (default: the workload's)")
     ap.add_argument("--ring", type=int, default=0, help="pre-generated rounds to rotate through (0: enough for > 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="wall-time budget of the CPU-oracle leg")
@@ -63,13 +66,23 @@ def main():
     ring_n = args.ring or max(2, min(8, -(-(1 << 30) // round_bytes)))
     gen = synth.RoundGenerator(w, dev)
     ring = [gen.round(r) for r in range(ring_n)]
-    policy = binding.UCB1 if w.policy == "ucb1" else binding.TS_BETA
-    tp = binding.Tapout(w.B, w.K, w.V, policy=policy)
+    pol_name = args.policy or w.policy
+    policy = {"ucb1": binding.UCB1, "ts": binding.TS_BETA, "ucb_tuned": binding.UCB_TUNED, "ts_gauss": binding.TS_GAUSS}[pol_name]
+    needs_u = policy in (binding.TS_BETA, binding.TS_GAUSS)
+    rules, thresholds = (0, 1, 2), (0.6, 0.8, 0.2)
+    if args.arms == "five":
+        rules, thresholds = (0, 1, 2, 3, 4), (0.6, 0.8, 0.2, 0.2, 0.4)
+    n_arms = len(rules)
+    tp = binding.Tapout(w.B, w.K, w.V, policy=policy, rules=rules, thresholds=thresholds)
     for o in args.opt:
         k, v = o.split("=")
         tp.set_option(k, int(v))
     truncate = args.mode == "truncate"
-    prepared = [tp.prepare_round(r, truncate, u_ts=r["u_ts"] if policy == binding.TS_BETA else None) for r in ring]
+    u_ts_ring = [None] * ring_n
+    if needs_u:            # uniforms of the Thompson draws, [B, arms, 48]; the generator's are sized for three arms
+        g = torch.Generator(device=dev).manual_seed(20251102)
+        u_ts_ring = [r["u_ts"] if n_arms == w.n_arms else torch.rand(w.B, n_arms, 48, device=dev, generator=g) for r in ring]
+    prepared = [tp.prepare_round(r, truncate, u_ts=u) for r, u in zip(ring, u_ts_ring)]
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
 
@@ -144,7 +157,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: V={w.V} B={w.B} K={w.K} draft={str(w.draft_dtype)[6:]} target={str(w.target_dtype)[6:]}",
                    "mode": "full-K (n_draft = K)" if not truncate else "truncate (n_draft = stop position)",
-                   "policy": w.policy, "ring_rounds": ring_n, "ring_bytes": ring_n * round_bytes},
+                   "policy": pol_name, "arms": args.arms, "ring_rounds": ring_n, "ring_bytes": ring_n * round_bytes},
         "emitted_tokens_per_s": round(emitted / elapsed, 1),
         "rows_per_s": round((draft_rows + target_rows) / elapsed, 1),
         "whole_round_GBps": round(stream_bytes / elapsed / 1e9, 1),
@@ -164,11 +177,12 @@ def main():
         torch.cuda.synchronize()
         out["copy_calibration"] = {"bytes_read_per_copy": src.numel(), "bytes_written_per_copy": src.numel(), "copies": 8}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, ring, truncate, args.cpu_seconds)
+        out["cpu_baseline"] = cpu_baseline(w, ring, truncate, args.cpu_seconds, policy, rules, thresholds,
+                                           [None if u is None else u.cpu().numpy() for u in u_ts_ring])
     print(json.dumps(out))
 
 
-def cpu_baseline(w, ring, truncate, budget_s):
+def cpu_baseline(w, ring, truncate, budget_s, policy, rules, thresholds, u_ts_ring):
     """The CPU oracle, as it stands, on whole rounds of the same workload (cycling through the
     pre-generated ring) until about `budget_s` seconds of wall time are spent; all host cores."""
     import numpy as np
@@ -179,17 +193,20 @@ def cpu_baseline(w, ring, truncate, budget_s):
         host.append(dict(draft=orc.as_logits(rnd["draft"].cpu()), target=orc.as_logits(rnd["target"].cpu()),
                          tok=rnd["draft_tok"].cpu().numpy(), k_len=rnd["k_len"].cpu().numpy(),
                          greedy=rnd["greedy"].cpu().numpy(), ua=rnd["u_accept"].cpu().numpy(),
-                         us=rnd["u_sample"].cpu().numpy(), u_ts=rnd["u_ts"].cpu().numpy()))
-    bandit = orc.Bandit(orc.POLICY_UCB1 if w.policy == "ucb1" else orc.POLICY_TS_BETA, w.B, w.n_arms)
+                         us=rnd["u_sample"].cpu().numpy(), u_ts=u_ts_ring[len(host)]))
+    bandit = orc.Bandit(policy, w.B, len(rules))              # the policy codes of the oracle and of the boundary coincide
+    state = orc.RuleState(w.B, rules, thresholds)
     tokens, rounds = 0, 0
     t0 = time.perf_counter()
     while True:
         h = host[rounds % len(host)]
         arm, _ = bandit.select(w.B, h["u_ts"])
-        ds = orc.draft_stats(h["draft"], draft_tok=h["tok"], k_len=h["k_len"], arm=arm, nthreads=cores)
+        ds = orc.draft_stats(h["draft"], draft_tok=h["tok"], k_len=h["k_len"], arm=arm, rules=rules, thresholds=thresholds,
+                             prev_entropy=state.prev_entropy, lam=state.lam, nthreads=cores)
         nd = ds["n_stop"] if truncate else h["k_len"]
         vf = orc.verify(h["target"], h["draft"], ds["logq_tok"], h["tok"], nd, h["ua"], h["us"], greedy=h["greedy"], nthreads=cores)
         bandit.update(arm, vf["accept_len"], nd, h["k_len"])
+        state.update(ds["entropy"], nd, vf["accept_len"])
         tokens += int(np.sum(nd))
         rounds += 1
         dt = time.perf_counter() - t0

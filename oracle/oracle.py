@@ -122,16 +122,17 @@ def row_stats(row) -> dict:
 
 
 def draft_stats(draft, draft_tok=None, k_len=None, arm=None, rules=(0, 1, 2),
-                thresholds=(0.6, 0.8, 0.2), nthreads=1, prev_entropy=None, lam=None, adaedl_gamma=0.5) -> dict:
+                thresholds=(0.6, 0.8, 0.2), nthreads=1, prev_entropy=None, lam=None, adaedl_gamma=0.5,
+                token_level=False) -> dict:
     """Signals of every draft row and the stop position of Algorithm 1's draft loop.
     prev_entropy [B] f32 (NaN = none) feeds SVIPDifference at the first position; lam [B, arms] f64 the
-    adaptive thresholds of AdaEDL arms."""
+    adaptive thresholds of AdaEDL arms.  token_level: arm is [B, K], one arm per draft position (Section 3.1)."""
     draft = as_logits(draft)
     B, K, V = draft.shape
     sb, sk = _strides(draft)
     tok = _i32(draft_tok, (B, K))
     kl = _i32(k_len, (B,))
-    ar = _i32(arm, (B,))
+    ar = _i32(arm, (B, K) if token_level else (B,))
     rl = _i32(rules)
     th = _f32(thresholds)
     f = lambda: np.full((B, K), np.nan, np.float32)
@@ -146,7 +147,7 @@ def draft_stats(draft, draft_tok=None, k_len=None, arm=None, rules=(0, 1, 2),
         _p(o["top1_id"]), _p(o["logq_tok"]) if tok is not None else None,
         _p(o["n_stop"]), _p(o["stop_fired"]), _p(o["stop_margin"]), _p(o["flags"]),
         _p(_f32(prev_entropy, (B,))), _p(None if lam is None else np.ascontiguousarray(lam, np.float64)),
-        C.c_double(adaedl_gamma), int(nthreads))
+        C.c_double(adaedl_gamma), K if token_level else 0, int(nthreads))
     if ar is None:
         o["n_stop"] = None
     return o
@@ -249,29 +250,33 @@ def inverse_cdf(w, u: float):
 
 
 class Bandit:
-    """Host-side bandit state driven by the oracle's select/update (Section 3.3)."""
+    """Host-side bandit state driven by the oracle's select/update (Section 3.3).  positions > 1: token-level
+    bandits, one per draft position (Section 3.1), state [n_bandits, positions, arms], binary rewards."""
 
-    def __init__(self, policy: int, n_bandits: int, n_arms: int, alpha: float = 0.5, reward_kind: int = REWARD_BLEND):
+    def __init__(self, policy: int, n_bandits: int, n_arms: int, alpha: float = 0.5, reward_kind: int = REWARD_BLEND,
+                 positions: int = 1):
         self.policy, self.n_bandits, self.A, self.alpha, self.reward_kind = policy, n_bandits, n_arms, alpha, reward_kind
-        self.sum_r = np.zeros((n_bandits, n_arms), np.float64)
-        self.sum_r2 = np.zeros((n_bandits, n_arms), np.float64)
-        self.count = np.zeros((n_bandits, n_arms), np.int64)
+        self.P = positions
+        shape = (n_bandits, n_arms) if positions == 1 else (n_bandits, positions, n_arms)
+        self.sum_r = np.zeros(shape, np.float64)
+        self.sum_r2 = np.zeros(shape, np.float64)
+        self.count = np.zeros(shape, np.int64)
 
     def select(self, B: int, u_ts=None):
-        arm = np.zeros(B, np.int32)
+        arm = np.zeros(B if self.P == 1 else (B, self.P), np.int32)
         flags = np.zeros(B, np.uint32)
         u = None
         if self.policy in (POLICY_TS_BETA, POLICY_TS_GAUSS):
-            u = _f32(u_ts, (B, self.A, TS_UNIFORMS_PER_ARM))
-        lib().tapout_oracle_bandit_select(self.policy, self.n_bandits, B, self.A, _p(self.sum_r), _p(self.sum_r2),
+            u = _f32(u_ts, (B, self.A, TS_UNIFORMS_PER_ARM) if self.P == 1 else (B, self.P, self.A, TS_UNIFORMS_PER_ARM))
+        lib().tapout_oracle_bandit_select(self.policy, self.n_bandits, B, self.A, self.P, _p(self.sum_r), _p(self.sum_r2),
                                           _p(self.count), _p(u), _p(arm), _p(flags))
         return arm, flags
 
     def update(self, arm, accept_len, n_draft, gamma, active=None):
         B = len(arm)
-        lib().tapout_oracle_bandit_update(self.n_bandits, B, self.A, self.reward_kind, C.c_double(self.alpha),
+        lib().tapout_oracle_bandit_update(self.n_bandits, B, self.A, self.P, self.reward_kind, C.c_double(self.alpha),
                                           _p(self.sum_r), _p(self.sum_r2), _p(self.count),
-                                          _p(_i32(arm, (B,))), _p(_i32(accept_len, (B,))),
+                                          _p(_i32(arm, (B,) if self.P == 1 else (B, self.P))), _p(_i32(accept_len, (B,))),
                                           _p(_i32(n_draft, (B,))), _p(_i32(gamma, (B,))), _p(_u8(active)))
 
 

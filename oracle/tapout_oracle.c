@@ -183,6 +183,9 @@ static int adaedl_fires(double g, double lambda, float H, double *margin_out)
  * prev_entropy [B] (or NULL): entropy of the last drafted position of each
  * sequence's previous draft, NaN for none (SVIPDifference).  lambda [B,
  * n_arms] (or NULL): adaptive thresholds (AdaEDL arms read their column).
+ * arm_stride = 0: sequence-level bandit, arm[b] decides at every step;
+ * arm_stride > 0: token-level bandits (Section 3.1), the arm of step k is
+ * arm[b * arm_stride + k].
  */
 ORACLE_API int tapout_oracle_draft_stats(
     const void *draft, int dtype, int64_t stride_b, int64_t stride_k,
@@ -193,7 +196,7 @@ ORACLE_API int tapout_oracle_draft_stats(
     int32_t *top1_id, float *logq_tok,
     int32_t *n_stop, uint8_t *stop_fired, double *stop_margin, uint32_t *flags,
     const float *prev_entropy, const double *lambda, double adaedl_g,
-    int nthreads)
+    int arm_stride, int nthreads)
 {
     if (nthreads < 1) nthreads = 1;
     if (flags) memset(flags, 0, (size_t)B * sizeof *flags);
@@ -228,10 +231,10 @@ ORACLE_API int tapout_oracle_draft_stats(
     for (int b = 0; b < B; ++b) {
         int kb = k_len ? k_len[b] : K;
         if (kb > K) kb = K;
-        int a = arm[b];
         int ns = kb;
         int stopped = 0;
         for (int k = 0; k < kb; ++k) {
+            int a = arm_stride > 0 ? arm[(size_t)b * arm_stride + k] : arm[b];
             int64_t i = (int64_t)b * K + k;
             double mg = INFINITY;
             int fire = 0;
@@ -632,28 +635,39 @@ ORACLE_API int tapout_oracle_ts_gauss_select(const double *sum_r, const int64_t 
  * n_bandits == 1: one shared bandit; select draws one arm for the round
  * (from the first sequence's uniforms) and update applies the B rewards in
  * index order, each as one play.
+ *
+ * positions = 1: sequence-level bandits.  positions = P > 1: token-level
+ * bandits (Section 3.1: every position of the drafting sequence is itself a
+ * bandit): state [n_bandits, P, A], arms [B, P], uniforms [B, P, A, 48].
+ * The token-level reward (Section 3.2) is 1 for an accepted token and 0 for a
+ * rejected one: position k < m = accept_len is an accepted play of its arm,
+ * position m (if m < n_draft) a rejected one; later positions were never
+ * evaluated by the target model and are not played.
  */
-ORACLE_API int tapout_oracle_bandit_select(int policy, int n_bandits, int B, int A,
+ORACLE_API int tapout_oracle_bandit_select(int policy, int n_bandits, int B, int A, int positions,
                                            const double *sum_r, const double *sum_r2, const int64_t *count,
                                            const float *u_ts, int32_t *arm_out, uint32_t *flags)
 {
     for (int b = 0; b < B; ++b) {
-        int nb = n_bandits == 1 ? 0 : b;
-        int ex = 0, a;
-        const double *S = sum_r + (size_t)nb * A;
-        const int64_t *N = count + (size_t)nb * A;
-        const float *u = u_ts ? u_ts + (size_t)nb * A * TS_UNIFORMS_PER_ARM : NULL;
-        if (policy == 0) a = tapout_oracle_ucb1_select(S, N, A, NULL);
-        else if (policy == 2) a = tapout_oracle_ucb_tuned_select(S, sum_r2 + (size_t)nb * A, N, A, NULL);
-        else if (policy == 3) a = tapout_oracle_ts_gauss_select(S, N, A, u, NULL);
-        else a = tapout_oracle_ts_select(S, N, A, u, NULL, &ex);
-        arm_out[b] = a;
-        if (flags) flags[b] = ex ? FLAG_SAMPLER_EXHAUSTED : 0;
+        if (flags) flags[b] = 0;
+        for (int k = 0; k < positions; ++k) {
+            size_t nb = ((size_t)(n_bandits == 1 ? 0 : b) * positions + k) * A;
+            int ex = 0, a;
+            const double *S = sum_r + nb;
+            const int64_t *N = count + nb;
+            const float *u = u_ts ? u_ts + nb * TS_UNIFORMS_PER_ARM : NULL;
+            if (policy == 0) a = tapout_oracle_ucb1_select(S, N, A, NULL);
+            else if (policy == 2) a = tapout_oracle_ucb_tuned_select(S, sum_r2 + nb, N, A, NULL);
+            else if (policy == 3) a = tapout_oracle_ts_gauss_select(S, N, A, u, NULL);
+            else a = tapout_oracle_ts_select(S, N, A, u, NULL, &ex);
+            arm_out[(size_t)b * positions + k] = a;
+            if (flags && ex) flags[b] |= FLAG_SAMPLER_EXHAUSTED;
+        }
     }
     return 0;
 }
 
-ORACLE_API int tapout_oracle_bandit_update(int n_bandits, int B, int A, int reward_kind, double alpha,
+ORACLE_API int tapout_oracle_bandit_update(int n_bandits, int B, int A, int positions, int reward_kind, double alpha,
                                            double *sum_r, double *sum_r2, int64_t *count,
                                            const int32_t *arm, const int32_t *accept_len,
                                            const int32_t *n_draft, const int32_t *gamma,
@@ -661,14 +675,28 @@ ORACLE_API int tapout_oracle_bandit_update(int n_bandits, int B, int A, int rewa
 {
     for (int b = 0; b < B; ++b) {
         if (active && !active[b]) continue;
-        int a = arm[b];
-        if (a < 0 || a >= A || n_draft[b] < 1 || gamma[b] < 1) continue;
+        if (n_draft[b] < 1 || gamma[b] < 1) continue;
         int nb = n_bandits == 1 ? 0 : b;
-        double r = reward_kind == 1 ? tapout_oracle_reward_simple(accept_len[b], gamma[b])
-                                    : tapout_oracle_reward(accept_len[b], n_draft[b], gamma[b], alpha);
-        count[(size_t)nb * A + a] += 1;
-        sum_r[(size_t)nb * A + a] += r;
-        if (sum_r2) { volatile double sq = r * r; sum_r2[(size_t)nb * A + a] += sq; }
+        if (positions == 1) {
+            int a = arm[b];
+            if (a < 0 || a >= A) continue;
+            double r = reward_kind == 1 ? tapout_oracle_reward_simple(accept_len[b], gamma[b])
+                                        : tapout_oracle_reward(accept_len[b], n_draft[b], gamma[b], alpha);
+            count[(size_t)nb * A + a] += 1;
+            sum_r[(size_t)nb * A + a] += r;
+            if (sum_r2) { volatile double sq = r * r; sum_r2[(size_t)nb * A + a] += sq; }
+            continue;
+        }
+        int m = accept_len[b], n = n_draft[b] < positions ? n_draft[b] : positions;
+        for (int k = 0; k < n && k <= m; ++k) {
+            int a = arm[(size_t)b * positions + k];
+            if (a < 0 || a >= A) continue;
+            size_t i = ((size_t)nb * positions + k) * A + a;
+            double r = k < m ? 1.0 : 0.0;
+            count[i] += 1;
+            sum_r[i] += r;
+            if (sum_r2) sum_r2[i] += r;
+        }
     }
     return 0;
 }

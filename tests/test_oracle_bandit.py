@@ -267,3 +267,74 @@ def test_batched_select_dispatches_the_variants():
                 want = orc.ts_gauss_select(bd.sum_r[b], bd.count[b], u[b])[0]
             assert arms[b] == want
         assert not fl.any()
+
+
+# ---- token-level bandits (Section 3.1: every draft position is its own bandit; Section 3.2: binary reward) -----
+
+def test_token_level_update_plays_only_the_positions_the_target_evaluated():
+    bd = orc.Bandit(orc.POLICY_UCB1, n_bandits=2, n_arms=2, positions=4)
+    arms = np.array([[0, 1, 1, 0], [1, 1, 0, 0]], np.int32)
+    # sequence 0: 4 drafted, 2 accepted -> positions 0, 1 rewarded 1, position 2 (first rejection) rewarded 0, position 3 unplayed
+    # sequence 1: 3 drafted, all accepted -> positions 0..2 rewarded 1, position 3 was never drafted
+    bd.update(arms, [2, 3], [4, 3], [4, 4])
+    assert bd.count[0].tolist() == [[1, 0], [0, 1], [0, 1], [0, 0]]
+    assert bd.sum_r[0].tolist() == [[1, 0], [0, 1], [0, 0], [0, 0]]
+    assert bd.count[1].tolist() == [[0, 1], [0, 1], [1, 0], [0, 0]]
+    assert bd.sum_r[1].tolist() == [[0, 1], [0, 1], [1, 0], [0, 0]]
+    assert (bd.sum_r2 == bd.sum_r).all()                       # r in {0, 1}
+    # nothing accepted: only position 0 is played, with reward 0; an inactive sequence is skipped
+    bd.update(arms, [0, 1], [2, 2], [4, 4], active=[1, 0])
+    assert bd.count[0].tolist() == [[2, 0], [0, 1], [0, 1], [0, 0]] and bd.sum_r[0, 0, 0] == 1.0
+    assert bd.count[1].sum() == 3
+    # shared bandit: the plays of all sequences land in the one table, position by position
+    sh = orc.Bandit(orc.POLICY_UCB1, n_bandits=1, n_arms=2, positions=3)
+    sh.update(np.array([[0, 0, 0], [0, 1, 1], [1, 1, 1]], np.int32), [3, 1, 0], [3, 3, 2], [3, 3, 3])
+    assert sh.count[0].tolist() == [[2, 1], [1, 1], [1, 0]]
+    assert sh.sum_r[0].tolist() == [[2, 0], [1, 0], [1, 0]]
+
+
+def test_token_level_select_is_the_single_bandit_rule_per_position():
+    g = np.random.default_rng(21)
+    for pol in (orc.POLICY_UCB1, orc.POLICY_TS_BETA):
+        bd = orc.Bandit(pol, n_bandits=3, n_arms=3, positions=5)
+        bd.count[:] = g.integers(0, 6, bd.count.shape)
+        bd.sum_r[:] = np.minimum(bd.count, g.integers(0, 6, bd.count.shape))          # integer successes <= plays
+        u = g.random((3, 5, 3, 48), np.float32)
+        arms, fl = bd.select(3, u)
+        assert arms.shape == (3, 5) and not fl.any()
+        for b in range(3):
+            for k in range(5):
+                if pol == orc.POLICY_UCB1:
+                    want = orc.ucb1_select(bd.sum_r[b, k], bd.count[b, k])[0]
+                else:                                                             # Beta(1 + successes, 1 + failures)
+                    want, th, _ = orc.ts_select(bd.sum_r[b, k], bd.count[b, k], u[b, k])
+                    for a in range(3):
+                        assert th[a] == orc.beta_draw(1 + bd.sum_r[b, k, a], 1 + bd.count[b, k, a] - bd.sum_r[b, k, a], u[b, k, a])[0]
+                assert arms[b, k] == want
+    # shared: every sequence gets the arms drawn for sequence 0
+    sh = orc.Bandit(orc.POLICY_TS_BETA, n_bandits=1, n_arms=3, positions=5)
+    arms, _ = sh.select(3, u)
+    assert (arms == arms[0]).all()
+
+
+def test_token_level_stop_scan_uses_the_arm_of_each_position():
+    # rows uniform over n tokens: sqrt(H) = sqrt(ln n); p_top1 = 1/n; margin 0 for n >= 2
+    V = 32
+    x = np.full((1, 4, V), -np.inf, np.float32)
+    for k, n in enumerate((1, 1, 2, 8)):
+        x[0, k, :n] = 0.0
+    rules, th = [orc.RULE_SVIP, orc.RULE_MAXCONF, orc.RULE_MARGIN], [0.6, 0.8, 0.2]
+    # SVIP fires on rows 2, 3 (0.83, 1.44 > 0.6); Max-Confidence on rows 2, 3 (0.5, 0.125 < 0.8); LogitMargin on rows
+    # 2, 3 (margin 0) but not on one-hot rows (margin 1)
+    for arms, fired in (([0, 0, 0, 0], [0, 0, 1, 1]), ([2, 1, 0, 2], [0, 0, 1, 1]), ([1, 1, 1, 1], [0, 0, 1, 1])):
+        o = orc.draft_stats(x, arm=np.array([arms]), rules=rules, thresholds=th, token_level=True)
+        assert o["stop_fired"][0].tolist() == fired and o["n_stop"][0] == 3
+    # thresholds that make the per-position arm matter: SVIP at 1.0 fires on row 3 only, Max-Confidence at 0.3 on row 3 only,
+    # LogitMargin at 0.2 on rows 2 and 3
+    th2 = [1.0, 0.3, 0.2]
+    o = orc.draft_stats(x, arm=np.array([[0, 0, 0, 0]]), rules=rules, thresholds=th2, token_level=True)
+    assert o["stop_fired"][0].tolist() == [0, 0, 0, 1] and o["n_stop"][0] == 4
+    o = orc.draft_stats(x, arm=np.array([[0, 0, 2, 0]]), rules=rules, thresholds=th2, token_level=True)
+    assert o["stop_fired"][0].tolist() == [0, 0, 1, 1] and o["n_stop"][0] == 3
+    o = orc.draft_stats(x, arm=np.array([[2, 2, 1, 1]]), rules=rules, thresholds=th2, token_level=True)
+    assert o["stop_fired"][0].tolist() == [0, 0, 0, 1] and o["n_stop"][0] == 4

@@ -90,6 +90,16 @@ typedef enum { TAPOUT_UCB1 = 0, TAPOUT_TS_BETA = 1, TAPOUT_UCB_TUNED = 2, TAPOUT
  * r_simple = |Y|/gamma.                                                       */
 typedef enum { TAPOUT_REWARD_BLEND = 0, TAPOUT_REWARD_SIMPLE = 1 } tapout_reward;
 
+/* Action granularity of Section 3.1.  SEQUENCE: one bandit decides the stop
+ * rule of a whole drafting session.  TOKEN: every draft position is a bandit of
+ * its own (max_k of them per bandit slot); its reward (Section 3.2) is 1 if the
+ * token drafted at that position is accepted and 0 if it is the first rejected
+ * one; positions after the first rejection are not played.  In TOKEN mode the
+ * arm arrays of all calls are [B, max_k] (row stride max_k whatever K is),
+ * u_ts is [B, max_k, n_arms, 48], the bandit state is [n_bandits, max_k,
+ * n_arms], and tapout_config.reward is ignored.                               */
+typedef enum { TAPOUT_SEQUENCE_LEVEL = 0, TAPOUT_TOKEN_LEVEL = 1 } tapout_granularity;
+
 /* per-sequence flag bits written by the kernels */
 #define TAPOUT_FLAG_BAD_ROW 1u           /* a processed row holds NaN or has no finite maximum */
 #define TAPOUT_FLAG_BAD_TOKEN 2u         /* drafted token id outside [0, V)                    */
@@ -108,7 +118,7 @@ typedef struct {
     int32_t n_bandits;                    /* max_batch: one bandit per sequence slot; 1: shared */
     double alpha;                         /* weight of |Y|/gamma in the blended reward (0.5)    */
     int32_t reward;                       /* tapout_reward                                      */
-    int32_t reserved;                     /* 0                                                  */
+    int32_t granularity;                  /* tapout_granularity                                 */
     /* AdaEDL (Appendix A.1).  The paper leaves all of these unvalued; the defaults are this
      * library's choice.  After every draft of a sequence, with r = accepted / drafted:
      *   rate   <- beta1 * rate + (1 - beta1) * r
@@ -164,7 +174,8 @@ TAPOUT_API const char *tapout_last_error(const tapout_ctx *ctx);
  * arm_out [B] i32
  * flags   [B] u32 or NULL (overwritten)
  * With a shared bandit (n_bandits == 1) every sequence gets the arm drawn for
- * sequence 0.
+ * sequence 0.  TOKEN_LEVEL: one draw per position, arm_out [B, max_k], u_ts
+ * [B, max_k, n_arms, 48]; flags[b] ORs the positions.
  */
 TAPOUT_API tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const float *u_ts,
                                    int32_t *arm_out, uint32_t *flags, void *stream);
@@ -189,7 +200,8 @@ TAPOUT_API tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const 
  *
  * draft_tok [B,K] i32 or NULL (then logq_tok is not written)
  * k_len     [B] i32 or NULL (= K for all)
- * arm       [B] i32 or NULL (then n_stop / stop_fired are not written)
+ * arm       [B] i32 ([B, max_k] for TOKEN_LEVEL: step k is decided by the rule
+ *           of arm[b, k]) or NULL (then n_stop / stop_fired are not written)
  * lse, entropy, p_top1, p_top2, margin, logq_tok [B,K] f32, each or NULL
  * top1_id   [B,K] i32 or NULL
  * n_stop    [B] i32 or NULL;  stop_fired [B,K] u8 or NULL
@@ -261,6 +273,9 @@ TAPOUT_API tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *tar
  * call) is advanced as well, whatever arm was played: previous entropy <-
  * entropy of row n_draft - 1 of that call; AdaEDL rate and lambdas as described
  * at tapout_config.
+ * TOKEN_LEVEL: arm is [B, max_k]; for k < min(n_draft, max_k): position k < m
+ * plays arm[b,k] with reward 1, position m (if m < n_draft) with reward 0, later
+ * positions are not played; gamma is only checked (>= 1).
  * arm, accept_len, n_draft, gamma [B] i32;  active [B] u8 or NULL
  */
 TAPOUT_API tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *arm,
@@ -269,7 +284,7 @@ TAPOUT_API tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const 
 
 /* Bandit state read-out (the arm values of Section 4.3 are sum_r / count) and
  * restore.  sum_r, sum_r2 (or NULL), count: HOST arrays [n_bandits, n_arms]
- * (f64, f64, i64); sum_r2 = summed squared rewards (UCB_TUNED), set to
+ * ([n_bandits, max_k, n_arms] for TOKEN_LEVEL) (f64, f64, i64); sum_r2 = summed squared rewards (UCB_TUNED), set to
  * sum_r^2 / count when NULL on restore.  Both calls synchronise `stream`.     */
 TAPOUT_API tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, double *sum_r2, int64_t *count, void *stream);
 TAPOUT_API tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *sum_r, const double *sum_r2, const int64_t *count, void *stream);

@@ -20,6 +20,7 @@ F32, BF16 = 0, 1
 RULE_SVIP, RULE_MAXCONF, RULE_MARGIN, RULE_SVIP_DIFF, RULE_ADAEDL = 0, 1, 2, 3, 4
 UCB1, TS_BETA, UCB_TUNED, TS_GAUSS = 0, 1, 2, 3
 REWARD_BLEND, REWARD_SIMPLE = 0, 1
+SEQUENCE_LEVEL, TOKEN_LEVEL = 0, 1
 FLAG_BAD_ROW, FLAG_BAD_TOKEN, FLAG_BAD_NDRAFT, FLAG_SAMPLER_EXHAUSTED = 1, 2, 4, 8
 STATUS = {0: "TAPOUT_OK", 1: "TAPOUT_EINVAL", 2: "TAPOUT_EUNSUPPORTED", 3: "TAPOUT_ENOMEM", 4: "TAPOUT_EHIP"}
 
@@ -36,7 +37,7 @@ class TapoutConfig(C.Structure):
     _fields_ = [("device", C.c_int32), ("max_batch", C.c_int32), ("max_k", C.c_int32), ("vocab", C.c_int32),
                 ("n_arms", C.c_int32), ("rule", C.c_int32 * MAX_ARMS), ("threshold", C.c_float * MAX_ARMS),
                 ("policy", C.c_int32), ("n_bandits", C.c_int32), ("alpha", C.c_double),
-                ("reward", C.c_int32), ("reserved", C.c_int32),
+                ("reward", C.c_int32), ("granularity", C.c_int32),
                 ("adaedl_gamma", C.c_double), ("adaedl_alpha", C.c_double), ("adaedl_beta1", C.c_double),
                 ("adaedl_beta2", C.c_double), ("adaedl_eps", C.c_double), ("adaedl_rate0", C.c_double)]
 
@@ -127,7 +128,8 @@ class Tapout:
 
     def __init__(self, max_batch: int, max_k: int, vocab: int, *, device: int = 0, policy: int = UCB1,
                  rules=(RULE_SVIP, RULE_MAXCONF, RULE_MARGIN), thresholds=(0.6, 0.8, 0.2),
-                 alpha: float = 0.5, shared_bandit: bool = False, reward: int = REWARD_BLEND, adaedl: dict | None = None):
+                 alpha: float = 0.5, shared_bandit: bool = False, reward: int = REWARD_BLEND, adaedl: dict | None = None,
+                 token_level: bool = False):
         """adaedl: optional dict with any of gamma, alpha, beta1, beta2, eps, rate0 (tapout_config.adaedl_*)."""
         self._lib = load_library()
         cfg = default_config(max_batch, max_k, vocab)
@@ -138,10 +140,12 @@ class Tapout:
             cfg.rule[i], cfg.threshold[i] = r, h
         cfg.alpha = alpha
         cfg.reward = reward
+        cfg.granularity = TOKEN_LEVEL if token_level else SEQUENCE_LEVEL
         for k, v in (adaedl or {}).items():
             setattr(cfg, "adaedl_" + k, float(v))
         cfg.n_bandits = 1 if shared_bandit else max_batch
         self.cfg = cfg
+        self.positions = max_k if token_level else 1           # bandits per slot; arm arrays are [B, max_k] when > 1
         self.device = torch.device("cuda", device)
         self._ctx = C.c_void_p()
         st = self._lib.tapout_create(C.byref(self._ctx), C.byref(cfg))
@@ -213,12 +217,14 @@ class Tapout:
 
     # -- tapout_bandit_select ------------------------------------------------
     def bandit_select(self, B: int, u_ts=None, arm_out=None, flags=None, stream=None):
-        A = self.cfg.n_arms
+        A, P = self.cfg.n_arms, self.positions
+        ashape = (B,) if P == 1 else (B, P)
+        ushape = (B, A, TS_UNIFORMS_PER_ARM) if P == 1 else (B, P, A, TS_UNIFORMS_PER_ARM)
         if arm_out is None:
-            arm_out = torch.empty(B, dtype=torch.int32, device=self.device)
+            arm_out = torch.empty(ashape, dtype=torch.int32, device=self.device)
         self._check(self._lib.tapout_bandit_select(
-            self._ctx, B, _ptr(u_ts, torch.float32, (B, A, TS_UNIFORMS_PER_ARM), "u_ts"),
-            _ptr(arm_out, torch.int32, (B,), "arm_out"), _ptr(flags, torch.int32, (B,), "flags"), _stream(stream)))
+            self._ctx, B, _ptr(u_ts, torch.float32, ushape, "u_ts"),
+            _ptr(arm_out, torch.int32, ashape, "arm_out"), _ptr(flags, torch.int32, (B,), "flags"), _stream(stream)))
         return arm_out
 
     # -- tapout_draft_stats --------------------------------------------------
@@ -231,7 +237,8 @@ class Tapout:
         lg = _logits(draft, "draft")
         self._check(self._lib.tapout_draft_stats(
             self._ctx, C.byref(lg), B, K, V,
-            _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(k_len, i32, (B,), "k_len"), _ptr(arm, i32, (B,), "arm"),
+            _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(k_len, i32, (B,), "k_len"),
+            _ptr(arm, i32, (B,) if self.positions == 1 else (B, self.positions), "arm"),
             _ptr(out.get("lse"), f32, (B, K), "lse"), _ptr(out.get("entropy"), f32, (B, K), "entropy"),
             _ptr(out.get("p_top1"), f32, (B, K), "p_top1"), _ptr(out.get("p_top2"), f32, (B, K), "p_top2"),
             _ptr(out.get("margin"), f32, (B, K), "margin"), _ptr(out.get("top1_id"), i32, (B, K), "top1_id"),
@@ -290,22 +297,28 @@ class Tapout:
         B = arm.shape[0]
         i32 = torch.int32
         self._check(self._lib.tapout_bandit_update(
-            self._ctx, B, _ptr(arm, i32, (B,), "arm"), _ptr(accept_len, i32, (B,), "accept_len"),
+            self._ctx, B, _ptr(arm, i32, (B,) if self.positions == 1 else (B, self.positions), "arm"),
+            _ptr(accept_len, i32, (B,), "accept_len"),
             _ptr(n_draft, i32, (B,), "n_draft"), _ptr(gamma, i32, (B,), "gamma"),
             _ptr(active, torch.uint8, (B,), "active"), _stream(stream)))
 
     # -- state read-out / restore (host arrays) ------------------------------
+    def _state_shape(self):
+        c = self.cfg
+        return (c.n_bandits, c.n_arms) if self.positions == 1 else (c.n_bandits, self.positions, c.n_arms)
+
     def bandit_get_state(self, stream=None, moments: bool = False):
-        """(sum_r, count) or, with moments=True, (sum_r, sum_r2, count) as numpy arrays [n_bandits, n_arms]."""
+        """(sum_r, count) or, with moments=True, (sum_r, sum_r2, count) as numpy arrays [n_bandits, n_arms]
+        ([n_bandits, max_k, n_arms] for token-level bandits)."""
         import numpy as np
-        n = (self.cfg.n_bandits, self.cfg.n_arms)
+        n = self._state_shape()
         s, q, c = np.zeros(n, np.float64), np.zeros(n, np.float64), np.zeros(n, np.int64)
         self._check(self._lib.tapout_bandit_get_state(self._ctx, s.ctypes.data, q.ctypes.data, c.ctypes.data, _stream(stream)))
         return (s, q, c) if moments else (s, c)
 
     def bandit_set_state(self, sum_r, count, sum_r2=None, stream=None):
         import numpy as np
-        n = (self.cfg.n_bandits, self.cfg.n_arms)
+        n = self._state_shape()
         s = np.ascontiguousarray(sum_r, np.float64).reshape(n)
         c = np.ascontiguousarray(count, np.int64).reshape(n)
         q = None if sum_r2 is None else np.ascontiguousarray(sum_r2, np.float64).reshape(n)

@@ -26,6 +26,7 @@ struct tapout_ctx {
     double *accept_rate = nullptr, *lambda = nullptr;          // [max_batch], [max_batch, n_arms]
     float *round_entropy = nullptr;                            // [max_batch, max_k] entropies of the last draft_stats call
     int round_K = 0;                                           // its K (0: no draft_stats call yet)
+    int positions = 1;                                         // bandits per slot: 1, or max_k for token-level bandits
     int wgs_target = 4096;        // workgroups a streaming launch aims for
     int min_slice = 4096;         // smallest slice (elements) a row is cut into
     // optional kernel timing (tapout_profile_*): event pairs around the launches of selected kernels
@@ -122,6 +123,7 @@ BanditArgs bandit_args(const tapout_ctx *ctx, int B)
 {
     BanditArgs a{};
     a.policy = ctx->cfg.policy; a.n_bandits = ctx->cfg.n_bandits; a.n_arms = ctx->cfg.n_arms; a.B = B;
+    a.positions = ctx->positions;
     a.reward = ctx->cfg.reward; a.alpha = ctx->cfg.alpha;
     a.sum_r = ctx->sum_r; a.sum_r2 = ctx->sum_r2; a.count = ctx->count;
     for (int j = 0; j < TAPOUT_MAX_ARMS; ++j) a.rule[j] = ctx->cfg.rule[j];
@@ -160,6 +162,7 @@ void tapout_default_config(tapout_config *cfg, int32_t max_batch, int32_t max_k,
     cfg->n_bandits = max_batch;
     cfg->alpha = 0.5;
     cfg->reward = TAPOUT_REWARD_BLEND;
+    cfg->granularity = TAPOUT_SEQUENCE_LEVEL;
     cfg->adaedl_gamma = 0.5; cfg->adaedl_alpha = 0.9; cfg->adaedl_beta1 = 0.5; cfg->adaedl_beta2 = 0.9;
     cfg->adaedl_eps = 0.01; cfg->adaedl_rate0 = 0.9;
 }
@@ -185,6 +188,8 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
         if (cfg->rule[a] == TAPOUT_RULE_ADAEDL) adaedl = true;
     }
     if (cfg->policy < TAPOUT_UCB1 || cfg->policy > TAPOUT_TS_GAUSS) return fail(nullptr, TAPOUT_EUNSUPPORTED, "policy %d is not implemented", cfg->policy);
+    if (cfg->granularity != TAPOUT_SEQUENCE_LEVEL && cfg->granularity != TAPOUT_TOKEN_LEVEL)
+        return fail(nullptr, TAPOUT_EUNSUPPORTED, "granularity %d is not implemented", cfg->granularity);
     if (cfg->reward != TAPOUT_REWARD_BLEND && cfg->reward != TAPOUT_REWARD_SIMPLE) return fail(nullptr, TAPOUT_EUNSUPPORTED, "reward %d is not implemented", cfg->reward);
     if (adaedl) {
         if (!(cfg->adaedl_gamma >= 0.0) || !(cfg->adaedl_gamma < INFINITY)) return fail(nullptr, TAPOUT_EINVAL, "adaedl_gamma must be finite and >= 0");
@@ -205,7 +210,8 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     DeviceGuard guard(cfg->device);
     const size_t rows = (size_t)cfg->max_batch * (cfg->max_k + 1);
     c->part_cap = rows + kMaxWgsTarget;
-    const size_t nstate = (size_t)cfg->n_bandits * cfg->n_arms;
+    c->positions = cfg->granularity == TAPOUT_TOKEN_LEVEL ? cfg->max_k : 1;
+    const size_t nstate = (size_t)cfg->n_bandits * c->positions * cfg->n_arms;
     c->nsl_max = (cfg->vocab + kSampleSlice - 1) / kSampleSlice;
     double table[256];
     for (int k = 0; k < 256; ++k) table[k] = std::exp2((double)k / 256.0);
@@ -332,6 +338,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
     f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = ctx->part;
     f.draft_tok = draft_tok; f.k_len = k_len; f.arm = arm;
+    f.arm_stride = ctx->positions > 1 ? ctx->cfg.max_k : 0;
     f.n_arms = ctx->cfg.n_arms;
     for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) { f.rule[a] = ctx->cfg.rule[a]; f.threshold[a] = ctx->cfg.threshold[a]; }
     f.lse = lse; f.entropy = entropy; f.p_top1 = p_top1; f.p_top2 = p_top2; f.margin = margin; f.logq_tok = logq_tok;
@@ -438,7 +445,7 @@ tapout_status tapout_bandit_get_state(tapout_ctx *ctx, double *sum_r, double *su
     if (!ctx) return TAPOUT_EINVAL;
     if (!sum_r || !count) return fail(ctx, TAPOUT_EINVAL, "sum_r and count are required");
     DeviceGuard guard(ctx->cfg.device);
-    const size_t n = (size_t)ctx->cfg.n_bandits * ctx->cfg.n_arms;
+    const size_t n = (size_t)ctx->cfg.n_bandits * ctx->positions * ctx->cfg.n_arms;
     hipStream_t st = (hipStream_t)stream;
     hipError_t e = hipMemcpyAsync(sum_r, ctx->sum_r, n * sizeof(double), hipMemcpyDeviceToHost, st);
     if (e == hipSuccess && sum_r2) e = hipMemcpyAsync(sum_r2, ctx->sum_r2, n * sizeof(double), hipMemcpyDeviceToHost, st);
@@ -451,7 +458,7 @@ tapout_status tapout_bandit_set_state(tapout_ctx *ctx, const double *sum_r, cons
 {
     if (!ctx) return TAPOUT_EINVAL;
     if (!sum_r || !count) return fail(ctx, TAPOUT_EINVAL, "sum_r and count are required");
-    const size_t n = (size_t)ctx->cfg.n_bandits * ctx->cfg.n_arms;
+    const size_t n = (size_t)ctx->cfg.n_bandits * ctx->positions * ctx->cfg.n_arms;
     for (size_t i = 0; i < n; ++i) {
         if (count[i] < 0 || !(sum_r[i] >= 0.0) || sum_r[i] > (double)count[i])
             return fail(ctx, TAPOUT_EINVAL, "state entry %zu: need count >= 0 and 0 <= sum_r <= count", i);

@@ -107,22 +107,45 @@ __device__ inline int ts_arm(const double *S, const int64_t *N, int A, const flo
     return best;
 }
 
+__device__ inline int select_arm(const BanditArgs &a, size_t nb, const float *u_ts, bool *ex)
+{
+    const double *S = a.sum_r + nb;
+    const int64_t *N = a.count + nb;
+    const float *u = u_ts ? u_ts + nb * TAPOUT_TS_UNIFORMS_PER_ARM : nullptr;
+    if (a.policy == TAPOUT_UCB1) return ucb1_arm(S, N, a.n_arms);
+    if (a.policy == TAPOUT_UCB_TUNED) return ucb_tuned_arm(S, a.sum_r2 + nb, N, a.n_arms);
+    if (a.policy == TAPOUT_TS_GAUSS) return ts_gauss_arm(S, N, a.n_arms, u);
+    return ts_arm(S, N, a.n_arms, u, ex);
+}
+
+// Sequence-level bandit: one thread per sequence.
 __global__ void bandit_select_kernel(BanditArgs a, const float *u_ts, int32_t *arm_out, uint32_t *flags)
 {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= a.B) return;
-    const int nb = a.n_bandits == 1 ? 0 : b;
-    const double *S = a.sum_r + (size_t)nb * a.n_arms;
-    const int64_t *N = a.count + (size_t)nb * a.n_arms;
     bool ex = false;
-    int arm;
-    const float *u = u_ts ? u_ts + (size_t)nb * a.n_arms * TAPOUT_TS_UNIFORMS_PER_ARM : nullptr;
-    if (a.policy == TAPOUT_UCB1) arm = ucb1_arm(S, N, a.n_arms);
-    else if (a.policy == TAPOUT_UCB_TUNED) arm = ucb_tuned_arm(S, a.sum_r2 + (size_t)nb * a.n_arms, N, a.n_arms);
-    else if (a.policy == TAPOUT_TS_GAUSS) arm = ts_gauss_arm(S, N, a.n_arms, u);
-    else arm = ts_arm(S, N, a.n_arms, u, &ex);
-    arm_out[b] = arm;
+    arm_out[b] = select_arm(a, (size_t)(a.n_bandits == 1 ? 0 : b) * a.n_arms, u_ts, &ex);
     if (flags) flags[b] = ex ? TAPOUT_FLAG_SAMPLER_EXHAUSTED : 0u;
+}
+
+// Token-level bandits: one workgroup per sequence, its threads take the positions; the sequence's flag word
+// is the OR over its positions.
+__global__ void bandit_select_token_kernel(BanditArgs a, const float *u_ts, int32_t *arm_out, uint32_t *flags)
+{
+    __shared__ uint32_t sh_flag;
+    const int b = blockIdx.x;
+    if (threadIdx.x == 0) sh_flag = 0;
+    __syncthreads();
+    bool any = false;
+    for (int k = threadIdx.x; k < a.positions; k += blockDim.x) {
+        bool ex = false;
+        const size_t nb = ((size_t)(a.n_bandits == 1 ? 0 : b) * a.positions + k) * a.n_arms;
+        arm_out[(size_t)b * a.positions + k] = select_arm(a, nb, u_ts, &ex);
+        any |= ex;
+    }
+    if (any) atomicOr(&sh_flag, TAPOUT_FLAG_SAMPLER_EXHAUSTED);
+    __syncthreads();
+    if (threadIdx.x == 0 && flags) flags[b] = sh_flag;
 }
 
 __device__ inline void apply_reward(const BanditArgs &a, int nb, int arm, int m, int n, int g)
@@ -133,6 +156,22 @@ __device__ inline void apply_reward(const BanditArgs &a, int nb, int arm, int m,
     a.count[(size_t)nb * a.n_arms + arm] += 1;
     a.sum_r[(size_t)nb * a.n_arms + arm] += r;
     a.sum_r2[(size_t)nb * a.n_arms + arm] += r * r;
+}
+
+// Token-level bandits (Section 3.1 / 3.2): position k < m is an accepted play (reward 1) of the arm chosen
+// there, position m < n the rejected one (reward 0); later positions were never evaluated.
+__device__ inline void apply_token_rewards(const BanditArgs &a, int nb, const int32_t *arm_b, int m, int n)
+{
+    if (n > a.positions) n = a.positions;
+    for (int k = 0; k < n && k <= m; ++k) {
+        const int arm = arm_b[k];
+        if (arm < 0 || arm >= a.n_arms) continue;
+        const size_t i = ((size_t)nb * a.positions + k) * a.n_arms + arm;
+        const double r = k < m ? 1.0 : 0.0;
+        a.count[i] += 1;
+        a.sum_r[i] += r;
+        a.sum_r2[i] += r;
+    }
 }
 
 // Carried state of the stateful stop rules after one draft of sequence b (Appendix A.1).
@@ -154,7 +193,15 @@ __device__ inline bool playable(const BanditArgs &a, int b, const int32_t *arm, 
                                 const int32_t *gamma, const uint8_t *active)
 {
     if (active && !active[b]) return false;
-    return arm[b] >= 0 && arm[b] < a.n_arms && n_draft[b] >= 1 && gamma[b] >= 1;
+    if (n_draft[b] < 1 || gamma[b] < 1) return false;
+    return a.positions > 1 || (arm[b] >= 0 && arm[b] < a.n_arms);           // token-level arms are checked per position
+}
+
+__device__ inline void play(const BanditArgs &a, int nb, int b, const int32_t *arm, const int32_t *accept_len,
+                            const int32_t *n_draft, const int32_t *gamma)
+{
+    if (a.positions > 1) apply_token_rewards(a, nb, arm + (size_t)b * a.positions, accept_len[b], n_draft[b]);
+    else apply_reward(a, nb, arm[b], accept_len[b], n_draft[b], gamma[b]);
 }
 
 __global__ void bandit_update_kernel(BanditArgs a, const int32_t *arm, const int32_t *accept_len,
@@ -165,10 +212,9 @@ __global__ void bandit_update_kernel(BanditArgs a, const int32_t *arm, const int
         // shared bandit: the B plays are applied in index order by one thread
         if (b == 0)
             for (int i = 0; i < a.B; ++i)
-                if (playable(a, i, arm, n_draft, gamma, active))
-                    apply_reward(a, 0, arm[i], accept_len[i], n_draft[i], gamma[i]);
+                if (playable(a, i, arm, n_draft, gamma, active)) play(a, 0, i, arm, accept_len, n_draft, gamma);
     } else if (b < a.B && playable(a, b, arm, n_draft, gamma, active)) {
-        apply_reward(a, b, arm[b], accept_len[b], n_draft[b], gamma[b]);
+        play(a, b, b, arm, accept_len, n_draft, gamma);
     }
     if (a.accept_rate && b < a.B && !(active && !active[b])) {
         const int n = n_draft[b];
@@ -181,7 +227,8 @@ __global__ void bandit_update_kernel(BanditArgs a, const int32_t *arm, const int
 hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm)
 {
     const int block = 64;
-    launch_kernel(bandit_select_kernel, dim3((a.B + block - 1) / block), dim3(block), st, tm, a, u_ts, arm_out, flags);
+    if (a.positions > 1) launch_kernel(bandit_select_token_kernel, dim3(a.B), dim3(block), st, tm, a, u_ts, arm_out, flags);
+    else launch_kernel(bandit_select_kernel, dim3((a.B + block - 1) / block), dim3(block), st, tm, a, u_ts, arm_out, flags);
     return hipGetLastError();
 }
 

@@ -71,6 +71,7 @@ struct DraftFinalArgs {
     int32_t B, K, V, nsplit;
     const Partial *part;
     const int32_t *draft_tok, *k_len, *arm;
+    int32_t arm_stride;           // 0: arm[b] decides every step; > 0 (token-level bandits): step k uses arm[b * arm_stride + k]
     int32_t n_arms; int32_t rule[TAPOUT_MAX_ARMS]; float threshold[TAPOUT_MAX_ARMS];
     float *lse, *entropy, *p_top1, *p_top2, *margin, *logq_tok;
     int32_t *top1_id, *n_stop; uint8_t *stop_fired; uint32_t *flags;
@@ -107,6 +108,7 @@ constexpr int kSampleSlice = 2048;   // elements per slice of the final-token pa
 
 struct BanditArgs {
     int32_t policy, n_bandits, n_arms, B;
+    int32_t positions;            // bandits per slot: 1 (sequence-level) or max_k (token-level, one per draft position)
     int32_t reward;               // tapout_reward
     double alpha;
     double *sum_r, *sum_r2; int64_t *count;

@@ -63,14 +63,16 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     stage_partials(sh_part, a.part + (int64_t)b * K * a.nsplit, min(K, rows_per_stage) * a.nsplit);
     int kb = a.k_len ? a.k_len[b] : K;
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
-    const int arm = a.arm ? a.arm[b] : -1;
+    // sequence-level bandit: one arm for all steps; token-level bandits: the arm of step k is arm[b, k]
+    const bool tok_mode = a.arm_stride > 0;
+    const int arm = (a.arm && !tok_mode) ? a.arm[b] : -1;
     const bool arm_ok = arm >= 0 && arm < a.n_arms;
     const int rule_b = arm_ok ? a.rule[arm] : -1;
-    const bool late = rule_b == TAPOUT_RULE_SVIP_DIFF || rule_b == TAPOUT_RULE_ADAEDL;     // uniform over the workgroup
+    // rows whose rule looks beyond their own signals are decided in a second sweep (uniform over the workgroup)
+    const bool sweep = tok_mode ? (a.round_entropy != nullptr)
+                                : (rule_b == TAPOUT_RULE_SVIP_DIFF || rule_b == TAPOUT_RULE_ADAEDL);
     float H_carry = NAN;
-    double lam_b = 0.0;
-    if (late && rule_b == TAPOUT_RULE_SVIP_DIFF && a.prev_entropy) H_carry = a.prev_entropy[b];
-    if (late && rule_b == TAPOUT_RULE_ADAEDL) lam_b = a.lambda ? a.lambda[(int64_t)b * a.n_arms + arm] : (double)a.threshold[arm];
+    if (sweep && a.prev_entropy) H_carry = a.prev_entropy[b];
     if (threadIdx.x == 0) sh_flags = 0;
     for (int k0 = 0; k0 < kb; k0 += rows_per_stage) {
         const int k1 = min(kb, k0 + rows_per_stage);
@@ -121,10 +123,14 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
             }
             if (a.round_entropy) a.round_entropy[i] = H;
             if (a.arm) {
-                if (late) {
-                    sh_H[k] = H;                               // decided below, once every row's entropy is known
+                const int arm_k = tok_mode ? a.arm[(int64_t)b * a.arm_stride + k] : arm;
+                const bool ok_k = arm_k >= 0 && arm_k < a.n_arms;
+                const int rule_k = ok_k ? a.rule[arm_k] : -1;
+                if (sweep) sh_H[k] = H;
+                if (rule_k == TAPOUT_RULE_SVIP_DIFF || rule_k == TAPOUT_RULE_ADAEDL) {
+                    sh_dec[k] = 2;                             // decided below, once every row's entropy is known
                 } else {
-                    const bool fire = arm_ok && rule_fires(a.rule[arm], a.threshold[arm], H, p1, mg);
+                    const bool fire = ok_k && rule_fires(rule_k, a.threshold[arm_k], H, p1, mg);
                     if (a.stop_fired) a.stop_fired[i] = fire ? 1 : 0;
                     sh_dec[k] = fire ? 1 : 0;                  // k < K <= kScanCap
                 }
@@ -133,12 +139,18 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
         }
     }
     __syncthreads();                       // orders the LDS / scratch writes above before the scan
-    if (late) {
+    if (sweep) {
         for (int k = threadIdx.x; k < kb; k += blockDim.x) {
+            if (sh_dec[k] != 2) continue;
+            const int arm_k = tok_mode ? a.arm[(int64_t)b * a.arm_stride + k] : arm;      // in range: checked when it was marked
             const float H = sh_H[k];
-            const bool fire = rule_b == TAPOUT_RULE_SVIP_DIFF
-                                  ? svip_diff_fires(a.threshold[arm], H, k > 0 ? sh_H[k - 1] : H_carry)
-                                  : adaedl_fires(a.adaedl_gamma, lam_b, H);
+            bool fire;
+            if (a.rule[arm_k] == TAPOUT_RULE_SVIP_DIFF) {
+                fire = svip_diff_fires(a.threshold[arm_k], H, k > 0 ? sh_H[k - 1] : H_carry);
+            } else {
+                const double lam = a.lambda ? a.lambda[(int64_t)b * a.n_arms + arm_k] : (double)a.threshold[arm_k];
+                fire = adaedl_fires(a.adaedl_gamma, lam, H);
+            }
             if (a.stop_fired) a.stop_fired[(int64_t)b * K + k] = fire ? 1 : 0;
             sh_dec[k] = fire ? 1 : 0;
         }

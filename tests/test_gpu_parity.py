@@ -445,6 +445,81 @@ def test_several_thresholds_per_rule():
         binding.Tapout(4, 4, 100, rules=(5,), thresholds=(0.5,))
 
 
+@pytest.mark.parametrize("policy", [binding.UCB1, binding.TS_BETA])
+@pytest.mark.parametrize("shared", [False, True])
+def test_token_level_bandit_trajectory_matches_oracle(policy, shared):
+    """One bandit per draft position, binary rewards up to the first rejection (Sections 3.1, 3.2)."""
+    B, K, A, rounds = 21, 6, 3, 200
+    tp = binding.Tapout(B, K, 1000, policy=policy, shared_bandit=shared, token_level=True)
+    ob = orc.Bandit(policy, 1 if shared else B, A, positions=K)
+    g = torch.Generator().manual_seed(17)
+    for r in range(rounds):
+        u = torch.rand(B, K, A, 48, generator=g)
+        if r % 40 == 3:
+            u[:, :, :, ::3] = 0.0
+        fl = torch.full((B,), 7, dtype=torch.int32, device=DEV)
+        arm = tp.bandit_select(B, u_ts=u.to(DEV) if policy == binding.TS_BETA else None, flags=fl)
+        o_arm, o_fl = ob.select(B, u.numpy())
+        assert arm.shape == (B, K) and (arm.cpu().numpy() == o_arm).all(), f"round {r}"
+        assert (fl.cpu().numpy().astype(np.uint32) == o_fl).all()
+        n = torch.randint(1, K + 1, (B,), generator=g, dtype=torch.int32)
+        m = (torch.rand(B, generator=g) * (n + 1)).floor().clamp(max=n).to(torch.int32)
+        active = (torch.rand(B, generator=g) < 0.9).to(torch.uint8)
+        gamma = torch.full((B,), K, dtype=torch.int32)
+        tp.bandit_update(arm, m.to(DEV), n.to(DEV), gamma.to(DEV), active=active.to(DEV))
+        ob.update(o_arm, m.numpy(), n.numpy(), gamma.numpy(), active=active.numpy())
+    s, q, c = tp.bandit_get_state(moments=True)
+    assert s.shape == ob.sum_r.shape
+    assert (c == ob.count).all() and (s == ob.sum_r).all() and (q == ob.sum_r2).all()
+    assert c[:, K - 1].sum() < c[:, 0].sum()                            # late positions are played less often
+    tp2 = binding.Tapout(B, K, 1000, policy=policy, shared_bandit=shared, token_level=True)
+    tp2.bandit_set_state(s, c, sum_r2=q)
+    u = torch.rand(B, K, A, 48, generator=g).to(DEV)
+    assert torch.equal(tp.bandit_select(B, u_ts=u if policy == binding.TS_BETA else None),
+                       tp2.bandit_select(B, u_ts=u if policy == binding.TS_BETA else None))
+
+
+def test_token_level_closed_loop():
+    """Algorithm 1 with token-level bandits over the five-arm pool: the rule of step k is the arm of position k."""
+    w = synth.scaled(synth.WORKLOADS["llama3"], B=6, V=20000)
+    tp = binding.Tapout(w.B, w.K, w.V, rules=FIVE_RULES, thresholds=FIVE_THRESHOLDS, token_level=True)
+    ob = orc.Bandit(orc.POLICY_UCB1, w.B, 5, positions=w.K)
+    st = orc.RuleState(w.B, FIVE_RULES, FIVE_THRESHOLDS)
+    gen = synth.RoundGenerator(w, DEV)
+    flagged, n_stops = 0, set()
+    for r in range(12):
+        rnd = gen.round(r)
+        arm = tp.bandit_select(w.B)
+        o_arm, _ = ob.select(w.B)
+        assert (arm.cpu().numpy() == o_arm).all(), f"round {r}"
+        if r >= 7:                                               # mixed arms along the draft, every rule somewhere
+            arm = ((torch.arange(w.B)[:, None] + torch.arange(w.K)[None, :] + r) % 5).to(torch.int32).to(DEV)
+            o_arm = arm.cpu().numpy()
+        gds = tp.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arm)
+        g_nd = gds["n_stop"]
+        gvf = tp.verify(rnd["target"], rnd["draft"], gds["lse"], gds["logq_tok"], rnd["draft_tok"], g_nd,
+                        rnd["u_accept"], rnd["u_sample"], greedy=rnd["greedy"])
+        ods = orc.draft_stats(pu.host_logits(rnd["draft"]), draft_tok=rnd["draft_tok"].cpu().numpy(), k_len=rnd["k_len"].cpu().numpy(),
+                              arm=o_arm, rules=FIVE_RULES, thresholds=FIVE_THRESHOLDS, prev_entropy=st.prev_entropy, lam=st.lam,
+                              token_level=True, nthreads=16)
+        ovf = orc.verify(pu.host_logits(rnd["target"]), pu.host_logits(rnd["draft"]), ods["logq_tok"], rnd["draft_tok"].cpu().numpy(),
+                         ods["n_stop"], rnd["u_accept"].cpu().numpy(), rnd["u_sample"].cpu().numpy(),
+                         greedy=rnd["greedy"].cpu().numpy(), nthreads=16)
+        gvf = dict(gvf); gvf["n_draft_used"] = g_nd
+        c = pu.compare_round(gds, gvf, ods, ovf, rnd["k_len"].cpu().numpy(), ods["n_stop"])
+        flagged += c["stop_flagged"] + c["accept_flagged"]
+        n_stops |= set(ods["n_stop"].tolist())
+        tp.bandit_update(arm, gvf["accept_len"], g_nd, rnd["k_len"])
+        ob.update(o_arm, gvf["accept_len"].cpu().numpy(), g_nd.cpu().numpy(), rnd["k_len"].cpu().numpy())
+        st.update(ods["entropy"], g_nd.cpu().numpy(), gvf["accept_len"].cpu().numpy())
+        gs = tp.rule_state_get()
+        pu.assert_stats_close("entropy", gs["prev_entropy"], st.prev_entropy)
+        assert (gs["accept_rate"] == st.accept_rate).all() and (gs["lam"] == st.lam).all()
+    s, c = tp.bandit_get_state()
+    assert (c == ob.count).all() and (s == ob.sum_r).all()
+    assert flagged <= 2 and len(n_stops) >= 3
+
+
 # ---- boundary error handling --------------------------------------------------------
 
 def test_argument_errors_leave_outputs_untouched():

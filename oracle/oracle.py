@@ -153,6 +153,18 @@ def draft_stats(draft, draft_tok=None, k_len=None, arm=None, rules=(0, 1, 2),
     return o
 
 
+def draft_sample(draft, u_draft, k_len=None, nthreads=1) -> dict:
+    """Draft tokens drawn from softmax(draft row) by inverse CDF at the caller's uniforms (Algorithm 1)."""
+    draft = as_logits(draft)
+    B, K, V = draft.shape
+    sb, sk = _strides(draft)
+    o = dict(tok=np.full((B, K), -1, np.int32), icdf_margin=np.full((B, K), np.inf, np.float64), flags=np.zeros(B, np.uint32))
+    lib().tapout_oracle_draft_sample(_p(draft), _dtype_code(draft), C.c_int64(sb), C.c_int64(sk), B, K, C.c_int64(V),
+                                     _p(_i32(k_len, (B,))), _p(_f32(u_draft, (B, K))), _p(o["tok"]), _p(o["icdf_margin"]),
+                                     _p(o["flags"]), int(nthreads))
+    return o
+
+
 def verify(target, draft, logq_tok, draft_tok, n_draft, u_accept, u_sample, greedy=None, nthreads=1) -> dict:
     """Speculative-sampling verification and final token of every sequence."""
     target = as_logits(target)

@@ -321,6 +321,49 @@ ORACLE_API int32_t tapout_oracle_inverse_cdf(const double *w, int64_t V, double 
 }
 
 /*
+ * Draft-token sampling (Algorithm 1: x_i ~ M_q(prefix + X)): the token of every
+ * live draft row (b,k), k < k_len[b], is the inverse CDF of softmax(row) at the
+ * caller's uniform u_draft[b,k], with the conventions of the final token
+ * (smallest j whose inclusive prefix sum exceeds u * Z; index-order sums in
+ * double).  A row holding NaN or without a finite maximum gives token -1 and
+ * sets the bad-row flag of its sequence.  Rows k >= k_len[b] are untouched.
+ */
+ORACLE_API int tapout_oracle_draft_sample(
+    const void *draft, int dtype, int64_t stride_b, int64_t stride_k,
+    int B, int K, int64_t V, const int32_t *k_len, const float *u_draft,
+    int32_t *tok_out, double *icdf_margin, uint32_t *flags, int nthreads)
+{
+    if (nthreads < 1) nthreads = 1;
+    if (flags) memset(flags, 0, (size_t)B * sizeof *flags);
+#pragma omp parallel for collapse(2) schedule(dynamic, 1) num_threads(nthreads)
+    for (int b = 0; b < B; ++b)
+        for (int k = 0; k < K; ++k) {
+            int kb = k_len ? k_len[b] : K;
+            if (kb > K) kb = K;
+            if (k >= kb) continue;
+            int64_t i = (int64_t)b * K + k;
+            resid_ctx c;
+            row_stats_t r;
+            c.t_row = row_ptr(draft, dtype, stride_b, stride_k, b, k);
+            c.t_dtype = dtype;
+            row_stats(c.t_row, dtype, V, &r);
+            double mg = INFINITY, Z = 0.0;
+            if (r.bad) {
+                tok_out[i] = -1;
+                if (flags) {
+#pragma omp atomic
+                    flags[b] |= FLAG_BAD_ROW;
+                }
+            } else {
+                c.Mp = r.M; c.Sp = r.S;
+                tok_out[i] = inverse_cdf(w_target, &c, V, (double)u_draft[i], &Z, &mg);
+            }
+            if (icdf_margin) icdf_margin[i] = mg;
+        }
+    return 0;
+}
+
+/*
  * Verification of the n_draft[b] drafted tokens of each sequence and the
  * final token (Algorithm 1: verify, then sample the final token from the
  * target at prefix + Y).

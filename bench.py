@@ -35,6 +35,8 @@ def parse():
     ap.add_argument("--arms", default="three", choices=["three", "five"],
                     help="three: SVIP / Max-Confidence / LogitMargin (the default pool); five: plus SVIPDifference and AdaEDL (Table 1)")
     ap.add_argument("--policy", default=None, choices=["ucb1", "ts", "ucb_tuned", "ts_gauss"], help="bandit policy (default: the workload's)")
+    ap.add_argument("--sample-draft", action="store_true",
+                    help="let tapout_draft_stats draw the draft tokens (inverse CDF at caller uniforms) instead of reading them")
     ap.add_argument("--ring", type=int, default=0, help="pre-generated rounds to rotate through (0: enough for > 1 GB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="wall-time budget of the CPU-oracle leg")
@@ -82,7 +84,11 @@ def main():
     if needs_u:            # uniforms of the Thompson draws, [B, arms, 48]; the generator's are sized for three arms
         g = torch.Generator(device=dev).manual_seed(20251102)
         u_ts_ring = [r["u_ts"] if n_arms == w.n_arms else torch.rand(w.B, n_arms, 48, device=dev, generator=g) for r in ring]
-    prepared = [tp.prepare_round(r, truncate, u_ts=u) for r, u in zip(ring, u_ts_ring)]
+    u_draft_ring = [None] * ring_n
+    if args.sample_draft:
+        g = torch.Generator(device=dev).manual_seed(20251103)
+        u_draft_ring = [torch.rand(w.B, w.K, device=dev, generator=g) for _ in ring]
+    prepared = [tp.prepare_round(r, truncate, u_ts=u, u_draft=ud) for r, u, ud in zip(ring, u_ts_ring, u_draft_ring)]
     stream = torch.cuda.current_stream()
     sh = stream.cuda_stream
 
@@ -157,7 +163,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: V={w.V} B={w.B} K={w.K} draft={str(w.draft_dtype)[6:]} target={str(w.target_dtype)[6:]}",
                    "mode": "full-K (n_draft = K)" if not truncate else "truncate (n_draft = stop position)",
-                   "policy": pol_name, "arms": args.arms, "ring_rounds": ring_n, "ring_bytes": ring_n * round_bytes},
+                   "policy": pol_name, "arms": args.arms, "draft_tokens": "sampled by the library" if args.sample_draft else "given", "ring_rounds": ring_n, "ring_bytes": ring_n * round_bytes},
         "emitted_tokens_per_s": round(emitted / elapsed, 1),
         "rows_per_s": round((draft_rows + target_rows) / elapsed, 1),
         "whole_round_GBps": round(stream_bytes / elapsed / 1e9, 1),
@@ -176,7 +182,7 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         out["copy_calibration"] = {"bytes_read_per_copy": src.numel(), "bytes_written_per_copy": src.numel(), "copies": 8}
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.sample_draft:
         out["cpu_baseline"] = cpu_baseline(w, ring, truncate, args.cpu_seconds, policy, rules, thresholds,
                                            [None if u is None else u.cpu().numpy() for u in u_ts_ring])
     print(json.dumps(out))

@@ -198,7 +198,17 @@ TAPOUT_API tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const 
  * lambda) and, when the configuration holds such an arm, the call keeps the
  * entropies of this draft in the context for tapout_bandit_update.
  *
- * draft_tok [B,K] i32 or NULL (then logq_tok is not written)
+ * Draft-token sampling (Algorithm 1, "sample x_i from the draft model"): with
+ * u_draft given, the token of every live row is drawn first, as the inverse CDF
+ * of softmax(row) at u_draft[b,k] with the conventions of the final token of
+ * tapout_verify (smallest j whose inclusive prefix sum exceeds u * total, in
+ * double), written to sampled_tok, and logq_tok refers to it.  A bad row gets
+ * token -1 (BAD_ROW and BAD_TOKEN are both flagged).
+ *
+ * draft_tok [B,K] i32 or NULL (then logq_tok is not written, unless u_draft is
+ *           given); draft_tok and u_draft exclude each other
+ * u_draft   [B,K] f32 in [0,1) or NULL;  sampled_tok [B,K] i32, required with
+ *           u_draft (rows k >= k_len[b] untouched)
  * k_len     [B] i32 or NULL (= K for all)
  * arm       [B] i32 ([B, max_k] for TOKEN_LEVEL: step k is decided by the rule
  *           of arm[b, k]) or NULL (then n_stop / stop_fired are not written)
@@ -212,8 +222,9 @@ TAPOUT_API tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const 
 TAPOUT_API tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
                                  int32_t B, int32_t K, int32_t V,
                                  const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 const float *u_draft,
                                  float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
-                                 int32_t *top1_id, float *logq_tok,
+                                 int32_t *top1_id, float *logq_tok, int32_t *sampled_tok,
                                  int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream);
 
 /*
@@ -327,7 +338,10 @@ enum {
     TAPOUT_PROFILE_VERIFY_SLICES = 5,   /* final token: slice sums of the row pair                  */
     TAPOUT_PROFILE_VERIFY_LOCATE = 6,   /* final token: normalisers, slice, token                   */
     TAPOUT_PROFILE_UPDATE = 7,          /* bandit update                                            */
-    TAPOUT_PROFILE_KINDS = 8
+    TAPOUT_PROFILE_SAMPLE_HEAD = 8,     /* draft-token sampling: one job per draft row              */
+    TAPOUT_PROFILE_SAMPLE_SLICES = 9,   /* draft-token sampling: slice sums of every draft row      */
+    TAPOUT_PROFILE_SAMPLE_LOCATE = 10,  /* draft-token sampling: slice, token                       */
+    TAPOUT_PROFILE_KINDS = 11
 };
 TAPOUT_API tapout_status tapout_profile_enable(tapout_ctx *ctx, uint32_t kind_mask, int32_t max_records);
 TAPOUT_API tapout_status tapout_profile_read(tapout_ctx *ctx, int32_t kind, double *total_ms, int32_t *launches, void *stream);

@@ -30,7 +30,8 @@ EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_l
            "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
-PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_head", "verify_slices", "verify_locate", "update")
+PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_head", "verify_slices", "verify_locate", "update",
+                 "sample_head", "sample_slices", "sample_locate")
 
 
 class TapoutConfig(C.Structure):
@@ -70,7 +71,7 @@ def load_library():
         lib.tapout_last_error.restype = C.c_char_p
         lib.tapout_last_error.argtypes = [vp]
         lib.tapout_bandit_select.argtypes = [vp, i32, vp, vp, vp, vp]
-        lib.tapout_draft_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 14
+        lib.tapout_draft_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 16
         lib.tapout_verify.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 15
         lib.tapout_bandit_update.argtypes = [vp, i32] + [vp] * 6
         lib.tapout_bandit_get_state.argtypes = [vp] * 5
@@ -181,23 +182,28 @@ class Tapout:
         return ms.value, n.value
 
     # -- one decode round with the arguments marshalled once ---------------------
-    def prepare_round(self, rnd: dict, truncate: bool, u_ts=None):
+    def prepare_round(self, rnd: dict, truncate: bool, u_ts=None, u_draft=None):
         """Pre-marshals the four calls of one round (Algorithm 1) on fixed tensors and returns
         (launch, outputs): launch(stream_handle) enqueues select -> draft_stats -> verify -> update.
-        truncate=True verifies the tokens up to the stop position, False all k_len drafted tokens."""
+        truncate=True verifies the tokens up to the stop position, False all k_len drafted tokens.
+        u_draft [B, K]: the library draws the draft tokens itself instead of reading rnd["draft_tok"]."""
         draft, target, tok = rnd["draft"], rnd["target"], rnd["draft_tok"]
         B, K, V = draft.shape
         f32, i32 = torch.float32, torch.int32
         do, vo = self.alloc_draft_outputs(B, K), self.alloc_verify_outputs(B, K)
-        arm = torch.zeros(B, dtype=i32, device=self.device)
+        arm = torch.zeros(B if self.positions == 1 else (B, self.positions), dtype=i32, device=self.device)
         n_draft = do["n_stop"] if truncate else rnd["k_len"]
+        if u_draft is not None:
+            do["sampled_tok"] = torch.full((B, K), -1, dtype=i32, device=self.device)
+            tok = do["sampled_tok"]
         dl, tl = _logits(draft, "draft"), _logits(target, "target")
-        keep = (dl, tl, do, vo, arm, rnd, u_ts)
+        keep = (dl, tl, do, vo, arm, rnd, u_ts, u_draft)
         lib, ctx = self._lib, self._ctx
         p = lambda t: C.c_void_p(t.data_ptr()) if t is not None else None
         a_sel = (ctx, B, p(u_ts), p(arm), None)
-        a_ds = (ctx, C.byref(dl), B, K, V, p(tok), p(rnd["k_len"]), p(arm), p(do["lse"]), p(do["entropy"]),
-                p(do["p_top1"]), p(do["p_top2"]), p(do["margin"]), p(do["top1_id"]), p(do["logq_tok"]),
+        a_ds = (ctx, C.byref(dl), B, K, V, None if u_draft is not None else p(tok), p(rnd["k_len"]), p(arm), p(u_draft),
+                p(do["lse"]), p(do["entropy"]),
+                p(do["p_top1"]), p(do["p_top2"]), p(do["margin"]), p(do["top1_id"]), p(do["logq_tok"]), p(do.get("sampled_tok")),
                 p(do["n_stop"]), p(do["stop_fired"]), p(do["flags"]))
         a_vf = (ctx, C.byref(tl), C.byref(dl), B, K, V, p(do["lse"]), p(do["logq_tok"]), p(tok), p(n_draft),
                 p(rnd.get("greedy")), p(rnd["u_accept"]), p(rnd["u_sample"]), p(vo["accept_len"]), p(vo["out_tok"]),
@@ -228,21 +234,26 @@ class Tapout:
         return arm_out
 
     # -- tapout_draft_stats --------------------------------------------------
-    def draft_stats(self, draft, draft_tok=None, k_len=None, arm=None, out=None, stream=None):
-        """Returns / fills a dict: lse, entropy, p_top1, p_top2, margin, top1_id, logq_tok, n_stop, stop_fired, flags."""
+    def draft_stats(self, draft, draft_tok=None, k_len=None, arm=None, u_draft=None, out=None, stream=None):
+        """Returns / fills a dict: lse, entropy, p_top1, p_top2, margin, top1_id, logq_tok, n_stop, stop_fired, flags.
+        With u_draft [B, K] the draft tokens are drawn by the library (out["sampled_tok"]) and logq_tok refers to them."""
         B, K, V = draft.shape
         if out is None:
             out = self.alloc_draft_outputs(B, K)
+        if u_draft is not None and "sampled_tok" not in out:
+            out["sampled_tok"] = torch.full((B, K), -1, dtype=torch.int32, device=self.device)
         f32, i32 = torch.float32, torch.int32
         lg = _logits(draft, "draft")
         self._check(self._lib.tapout_draft_stats(
             self._ctx, C.byref(lg), B, K, V,
             _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(k_len, i32, (B,), "k_len"),
             _ptr(arm, i32, (B,) if self.positions == 1 else (B, self.positions), "arm"),
+            _ptr(u_draft, f32, (B, K), "u_draft"),
             _ptr(out.get("lse"), f32, (B, K), "lse"), _ptr(out.get("entropy"), f32, (B, K), "entropy"),
             _ptr(out.get("p_top1"), f32, (B, K), "p_top1"), _ptr(out.get("p_top2"), f32, (B, K), "p_top2"),
             _ptr(out.get("margin"), f32, (B, K), "margin"), _ptr(out.get("top1_id"), i32, (B, K), "top1_id"),
-            _ptr(out.get("logq_tok"), f32, (B, K), "logq_tok") if draft_tok is not None else None,
+            _ptr(out.get("logq_tok"), f32, (B, K), "logq_tok") if (draft_tok is not None or u_draft is not None) else None,
+            _ptr(out.get("sampled_tok"), i32, (B, K), "sampled_tok") if u_draft is not None else None,
             _ptr(out.get("n_stop"), i32, (B,), "n_stop") if arm is not None else None,
             _ptr(out.get("stop_fired"), torch.uint8, (B, K), "stop_fired") if arm is not None else None,
             _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream)))

@@ -213,14 +213,16 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     c->positions = cfg->granularity == TAPOUT_TOKEN_LEVEL ? cfg->max_k : 1;
     const size_t nstate = (size_t)cfg->n_bandits * c->positions * cfg->n_arms;
     c->nsl_max = (cfg->vocab + kSampleSlice - 1) / kSampleSlice;
+    // final-token jobs: one per sequence (verification) or one per draft row (draft-token sampling)
+    const size_t njobs = (size_t)cfg->max_batch * cfg->max_k;
     double table[256];
     for (int k = 0; k < 256; ++k) table[k] = std::exp2((double)k / 256.0);
     bool ok = hipMalloc(&c->part, c->part_cap * sizeof(Partial)) == hipSuccess
-           && hipMalloc(&c->part1, (size_t)cfg->max_batch * c->nsl_max * 5 * sizeof(double)) == hipSuccess
-           && hipMalloc(&c->part2, (size_t)cfg->max_batch * c->nsl_max * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->part1, njobs * c->nsl_max * 5 * sizeof(double)) == hipSuccess
+           && hipMalloc(&c->part2, njobs * c->nsl_max * sizeof(double)) == hipSuccess
            && hipMalloc(&c->exp_table, sizeof table) == hipSuccess
            && hipMemcpy(c->exp_table, table, sizeof table, hipMemcpyHostToDevice) == hipSuccess
-           && hipMalloc(&c->jobs, (size_t)cfg->max_batch * sizeof(SampleJob)) == hipSuccess
+           && hipMalloc(&c->jobs, njobs * sizeof(SampleJob)) == hipSuccess
            && hipMalloc(&c->flags_ws, (size_t)cfg->max_batch * sizeof(uint32_t)) == hipSuccess
            && hipMalloc(&c->sum_r, nstate * sizeof(double)) == hipSuccess
            && hipMalloc(&c->sum_r2, nstate * sizeof(double)) == hipSuccess
@@ -314,8 +316,9 @@ tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *ar
 tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
                                  int32_t B, int32_t K, int32_t V,
                                  const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 const float *u_draft,
                                  float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
-                                 int32_t *top1_id, float *logq_tok,
+                                 int32_t *top1_id, float *logq_tok, int32_t *sampled_tok,
                                  int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream)
 {
     if (!ctx) return TAPOUT_EINVAL;
@@ -325,6 +328,8 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     char buf[128];
     if (const char *m = check_logits(draft, "draft", V, K, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
     if (arm && !n_stop && !stop_fired) return fail(ctx, TAPOUT_EINVAL, "arm given but neither n_stop nor stop_fired");
+    if (u_draft && draft_tok) return fail(ctx, TAPOUT_EINVAL, "draft_tok and u_draft exclude each other");
+    if (u_draft && !sampled_tok) return fail(ctx, TAPOUT_EINVAL, "u_draft given but sampled_tok is NULL");
     DeviceGuard guard(ctx->cfg.device);
     hipStream_t st = (hipStream_t)stream;
     const int64_t rows = (int64_t)B * K;
@@ -334,6 +339,22 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, slice_vectors(V, draft->dtype, nsplit), (int32_t)rows, k_len, 0, ctx->part};
     hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, [&](Timing tm) { return launch_row_reduce(r, draft->dtype, true, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "draft pass launch");
+    if (u_draft) {
+        // draw the tokens first (one final-token job per draft row), so that the finaliser can form log q(tok)
+        VerifyArgs va{};
+        va.tbase = draft->ptr; va.t_dtype = draft->dtype; va.t_stride_b = draft->stride_b; va.t_stride_k = draft->stride_k;
+        va.dbase = draft->ptr; va.d_dtype = draft->dtype; va.d_stride_b = draft->stride_b; va.d_stride_k = draft->stride_k;
+        va.B = B; va.K = K; va.V = V; va.nsplit = nsplit; va.nsl = (V + kSampleSlice - 1) / kSampleSlice;
+        va.jps = K; va.n_jobs = (int32_t)rows;
+        va.part = ctx->part; va.n_draft = k_len; va.u_sample = u_draft; va.tok_direct = sampled_tok;
+        va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
+        va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
+        e = timed(ctx, TAPOUT_PROFILE_SAMPLE_HEAD, [&](Timing tm) { return launch_sample_head(va, st, tm); });
+        for (int pass = 1; pass <= 2 && e == hipSuccess; ++pass)
+            e = timed(ctx, TAPOUT_PROFILE_SAMPLE_SLICES + pass - 1, [&](Timing tm) { return launch_verify(va, pass, st, tm); });
+        if (e != hipSuccess) return hip_fail(ctx, e, "draft sampling launch");
+        draft_tok = sampled_tok;
+    }
     DraftFinalArgs f{};
     f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
     f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = ctx->part;
@@ -385,6 +406,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     va.tbase = target->ptr; va.t_dtype = target->dtype; va.t_stride_b = target->stride_b; va.t_stride_k = target->stride_k;
     va.dbase = draft->ptr; va.d_dtype = draft->dtype; va.d_stride_b = draft->stride_b; va.d_stride_k = draft->stride_k;
     va.B = B; va.K = K; va.V = V; va.nsplit = nsplit; va.nsl = (V + kSampleSlice - 1) / kSampleSlice;
+    va.jps = 1; va.n_jobs = B;
     va.part = ctx->part;
     va.draft_lse = draft_lse; va.logq_tok = logq_tok; va.draft_tok = draft_tok; va.n_draft = n_draft; va.greedy = greedy;
     va.u_accept = u_accept; va.u_sample = u_sample;

@@ -91,6 +91,11 @@ struct VerifyArgs {
     const void *dbase; int32_t d_dtype; int64_t d_stride_b, d_stride_k;
     int32_t B, K, V, nsplit;      // nsplit: slices per row of the streaming pass
     int32_t nsl;                  // slices per row of the final-token passes (kSampleSlice elements each)
+    // The slice and locate kernels work on "jobs": one per sequence for verification (jps = 1, job j belongs to
+    // sequence j), one per draft row for draft-token sampling (jps = K, job j = row j % K of sequence j / K).
+    // jobs, part1, part2 and u_sample are indexed by job; the rows of a job are rows job.row of its sequence.
+    int32_t jps, n_jobs;
+    int32_t *tok_direct;          // draft-token sampling: token of job j goes to tok_direct[j] instead of out_tok
     const Partial *part;
     const float *draft_lse, *logq_tok; const int32_t *draft_tok, *n_draft; const uint8_t *greedy;
     const float *u_accept, *u_sample;
@@ -103,6 +108,12 @@ struct VerifyArgs {
     const double *exp_table;      // 2^(k/256), k = 0..255
 };
 hipError_t launch_verify(const VerifyArgs &a, int pass /*0 head, 1 slices, 2 locate*/, hipStream_t st, Timing tm);
+
+// Draft-token sampling (Algorithm 1, the sampling step of the draft loop): one job per live draft row with the
+// row's maximum as exponent reference; bad live rows get token -1 at once.  The slice and locate kernels of
+// the final token then draw the tokens.  Arguments as VerifyArgs with the draft tensor in the target slots:
+// tbase/t_* = draft logits, part = draft partials [B*K, nsplit], n_draft = k_len (or NULL), jps = K.
+hipError_t launch_sample_head(const VerifyArgs &a, hipStream_t st, Timing tm);
 
 constexpr int kSampleSlice = 2048;   // elements per slice of the final-token passes
 

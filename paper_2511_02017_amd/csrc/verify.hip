@@ -298,8 +298,10 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
 {
     __shared__ double shT[256];
     __shared__ double sh_red[kSliceVals][kVBlock / kWave];
-    const int b = blockIdx.y, s = blockIdx.x;
-    const SampleJob job = a.jobs[b];
+    const int j = blockIdx.z * gridDim.y + blockIdx.y, s = blockIdx.x;
+    if (j >= a.n_jobs) return;
+    const int b = j / a.jps;
+    const SampleJob job = a.jobs[j];
     if (job.kind == 0) return;
     const Rows r = job_rows<TD, DD>(a, b, job);
     float xt[kRuns][kPer], xd[kRuns][kPer];
@@ -350,7 +352,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
     __syncthreads();
     if (threadIdx.x < kSliceVals) {
         const double *v = sh_red[threadIdx.x];
-        a.part1[((int64_t)b * a.nsl + s) * kSliceVals + threadIdx.x] = (v[0] + v[1]) + (v[2] + v[3]);
+        a.part1[((int64_t)j * a.nsl + s) * kSliceVals + threadIdx.x] = (v[0] + v[1]) + (v[2] + v[3]);
     }
 }
 
@@ -463,18 +465,19 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     __shared__ double shT[256];
     __shared__ double sh_red[kSliceVals][kVBlock / kWave];
     __shared__ LocateShared shl;
-    const int b = blockIdx.x;
+    const int j = blockIdx.x;                                        // job; its sequence is b
+    const int b = j / a.jps;
     const int tid = threadIdx.x;
     // the slice sums, the table and the uniform are requested before the job is looked at (one round trip)
-    const double *ps = a.part1 + (int64_t)b * a.nsl * kSliceVals;
-    double *zs = a.part2 + (int64_t)b * a.nsl;                       // exact slice weights (slow path only)
+    const double *ps = a.part1 + (int64_t)j * a.nsl * kSliceVals;
+    double *zs = a.part2 + (int64_t)j * a.nsl;                       // exact slice weights (slow path only)
     double acc[kSliceVals] = {0.0, 0.0, 0.0, 0.0, 0.0};
     for (int s = tid; s < a.nsl; s += kVBlock)
 #pragma unroll
         for (int q = 0; q < kSliceVals; ++q) acc[q] += ps[s * kSliceVals + q];
     for (int i = tid; i < 256; i += kVBlock) shT[i] = a.exp_table[i];
-    const float u32v = a.u_sample[b];
-    const SampleJob job = a.jobs[b];
+    const float u32v = a.u_sample[j];
+    const SampleJob job = a.jobs[j];
     if (job.kind == 0) return;                                        // the slice sums of such a sequence are stale: unused
     if (tid == 0) { shl.last = -1; shl.slice = 0x7fffffff; }
 
@@ -600,7 +603,8 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     }
     if (tid == 0) {
         if (token < 0) token = 0;
-        a.out_tok[(int64_t)b * (a.K + 1) + job.row] = token;
+        if (a.tok_direct) a.tok_direct[j] = token;
+        else a.out_tok[(int64_t)b * (a.K + 1) + job.row] = token;
         if (draft_bad) {
             uint32_t f = a.flags_ws[b] | TAPOUT_FLAG_BAD_ROW;
             a.flags_ws[b] = f;
@@ -609,16 +613,45 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     }
 }
 
+// ---- draft-token sampling: one job per draft row --------------------------------------------
+// One thread per row (b, k): merges the row's slice partials straight from memory (a few dozen bytes) for
+// the maximum, the exponent reference of the draw.
+__global__ __launch_bounds__(kVBlock) void sample_head_kernel(VerifyArgs a)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= a.n_jobs) return;
+    const int b = j / a.K, k = j - b * a.K;
+    int kb = a.n_draft ? a.n_draft[b] : a.K;
+    kb = kb > a.K ? a.K : kb;
+    SampleJob job;
+    job.kind = 0; job.row = k; job.ref_p = 0.0f; job.ref_q = 0.0f; job.lam = 0.0;
+    if (k < kb) {
+        const RowTotal r = merge_partials(a.part + (int64_t)j * a.nsplit, a.nsplit);     // same bad-row rule as the finaliser
+        const bool bad = r.bad;
+        const float M = r.M;
+        if (bad) a.tok_direct[j] = -1;           // NaN in the row or no finite maximum: nothing to draw from
+        else { job.kind = 2; job.ref_p = M; }
+    }
+    a.jobs[j] = job;
+}
+
 template <int TD, int DD>
 hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {
-    dim3 grid12(a.nsl, a.B), block(kVBlock);
+    const unsigned gy = a.n_jobs < 65535 ? a.n_jobs : 65535, gz = (a.n_jobs + gy - 1) / gy;
+    dim3 grid12(a.nsl, gy, gz), block(kVBlock);
     if (pass == 1) launch_kernel(verify_slices<TD, DD>, grid12, block, st, tm, a);
-    else launch_kernel(verify_locate<TD, DD>, dim3(a.B), block, st, tm, a);
+    else launch_kernel(verify_locate<TD, DD>, dim3(a.n_jobs), block, st, tm, a);
     return hipGetLastError();
 }
 
 }  // namespace
+
+hipError_t launch_sample_head(const VerifyArgs &a, hipStream_t st, Timing tm)
+{
+    launch_kernel(sample_head_kernel, dim3((a.n_jobs + kVBlock - 1) / kVBlock), dim3(kVBlock), st, tm, a);
+    return hipGetLastError();
+}
 
 hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {

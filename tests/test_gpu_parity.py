@@ -520,6 +520,66 @@ def test_token_level_closed_loop():
     assert flagged <= 2 and len(n_stops) >= 3
 
 
+# ---- draft-token sampling inside tapout_draft_stats ---------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny", "small", "ragged"])
+def test_draft_token_sampling_matches_oracle(name):
+    w = synth.WORKLOADS[name]
+    if name == "small":
+        w = synth.scaled(w, B=8)
+    if name == "ragged":
+        w = synth.scaled(w, B=6, V=70001)                         # odd V: ragged last slice, misaligned rows
+    rnd = synth.RoundGenerator(w, DEV).round(2)
+    tp = binding.Tapout(w.B, w.K, w.V)
+    g = torch.Generator().manual_seed(77)
+    u = torch.rand(w.B, w.K, generator=g)
+    u[0, 0] = 0.0
+    u[-1, -1] = float(np.nextafter(np.float32(1.0), np.float32(0.0)))
+    arm = (torch.arange(w.B, dtype=torch.int32) % 3).to(DEV)
+    gds = tp.draft_stats(rnd["draft"], k_len=rnd["k_len"], arm=arm, u_draft=u.to(DEV))
+    k_len = rnd["k_len"].cpu().numpy()
+    live = np.arange(w.K)[None, :] < k_len[:, None]
+    osm = orc.draft_sample(pu.host_logits(rnd["draft"]), u.numpy(), k_len=k_len, nthreads=16)
+    g_tok = gds["sampled_tok"].cpu().numpy()
+    near = osm["icdf_margin"] <= pu.TAU_S
+    assert near.sum() <= 1
+    assert (g_tok[live & ~near] == osm["tok"][live & ~near]).all()
+    assert (g_tok[~live] == -1).all()                               # rows beyond k_len untouched
+    # log q of the sampled token and everything else as with caller-supplied tokens
+    ods = orc.draft_stats(pu.host_logits(rnd["draft"]), draft_tok=np.where(live, g_tok, 0), k_len=k_len, arm=arm.cpu().numpy(), nthreads=16)
+    for key in pu.STAT_KEYS:
+        pu.assert_stats_close(key, gds[key].cpu().numpy(), ods[key], live)
+    gd2 = tp.draft_stats(rnd["draft"], draft_tok=gds["sampled_tok"].clamp(min=0), k_len=rnd["k_len"], arm=arm)
+    assert torch.equal(gd2["n_stop"], gds["n_stop"])
+    assert torch.equal(gd2["logq_tok"][torch.from_numpy(live).to(DEV)], gds["logq_tok"][torch.from_numpy(live).to(DEV)])
+
+
+def test_draft_token_sampling_law_edges_and_bad_rows():
+    V = 6000
+    x = torch.full((3, 2, V), float("-inf"))
+    x[0, :, 1000:1010] = 1.5                                        # uniform over 10 tokens: token = 1000 + floor(10 u)
+    x[1, 0, :] = torch.randn(V) * 2; x[1, 1, :] = x[1, 0, :]
+    x[2, 0, :] = 0.0; x[2, 0, 17] = float("nan")                    # bad row
+    x[2, 1, :] = float("-inf")                                      # no finite maximum
+    tp = binding.Tapout(3, 2, V)
+    for dt in (torch.float32, torch.bfloat16):
+        u = torch.tensor([[0.31, 0.99], [0.0, 0.999999], [0.5, 0.5]])
+        o = tp.draft_stats(x.to(dt).to(DEV), u_draft=u.to(DEV))
+        tok = o["sampled_tok"].cpu()
+        assert tok[0].tolist() == [1003, 1009]
+        row = x[1, 0].to(dt).double()
+        p = torch.softmax(row, 0)
+        c = torch.cumsum(p, 0)
+        assert tok[1, 0] == int((c > 0).nonzero()[0])               # u = 0: the first token with positive mass
+        assert abs(float(c[tok[1, 1]]) - 0.999999) < 1e-3 and float(c[tok[1, 1]]) > 0.999998
+        assert tok[2].tolist() == [-1, -1]
+        fl = o["flags"].cpu().tolist()
+        assert fl[0] == 0 and fl[1] == 0 and fl[2] == (binding.FLAG_BAD_ROW | binding.FLAG_BAD_TOKEN)
+        assert torch.isnan(o["logq_tok"][2]).all()
+    with pytest.raises(binding.TapoutError):
+        tp.draft_stats(x.to(DEV), draft_tok=torch.zeros(3, 2, dtype=torch.int32, device=DEV), u_draft=u.to(DEV))
+
+
 # ---- boundary error handling --------------------------------------------------------
 
 def test_argument_errors_leave_outputs_untouched():

@@ -49,7 +49,7 @@ def test_create_rejects_bad_config_on_the_host():
         assert st in (1, 2) and ctx.value is None
         assert word in lib.tapout_last_error(None).decode()
     assert lib.tapout_create(None, None) == 1
-    assert lib.tapout_draft_stats(None, None, 1, 1, 1, *([None] * 14)) == 1
+    assert lib.tapout_draft_stats(None, None, 1, 1, 1, *([None] * 16)) == 1
 
 
 def test_synthetic_workloads_have_the_stated_shapes():

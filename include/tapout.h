@@ -313,6 +313,9 @@ TAPOUT_API tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *pre
  * Launch-shape tuning (host; takes effect from the next call).  Names:
  *   "wgs_target"  workgroups a streaming launch aims for (rows are cut into
  *                 slices until the launch has about this many), default 4096
+ *   "slice_bytes" slice size aimed for when the rows alone already give that
+ *                 many workgroups (long rows are still cut), default 65536,
+ *                 at least 16384
  *   "min_slice"   smallest slice of a row, in elements, default 4096
  * Results do not depend on these values except through the rounding of the
  * binary32 partial sums.

@@ -29,6 +29,7 @@ struct tapout_ctx {
     int positions = 1;                                         // bandits per slot: 1, or max_k for token-level bandits
     int wgs_target = 4096;        // workgroups a streaming launch aims for
     int min_slice = 4096;         // smallest slice (elements) a row is cut into
+    int slice_bytes = 65536;      // slice size aimed for when the rows alone give enough workgroups
     // optional kernel timing (tapout_profile_*): event pairs around the launches of selected kernels
     uint32_t prof_mask = 0;
     int prof_cap = 0;
@@ -40,6 +41,7 @@ struct tapout_ctx {
 namespace {
 
 constexpr int kMaxWgsTarget = 1 << 16;
+constexpr int kMinSliceBytes = 16384;            // lower limit of the "slice_bytes" option (sizes the partial buffer)
 thread_local char g_create_err[256] = {0};
 
 tapout_status fail(tapout_ctx *ctx, tapout_status st, const char *fmt, ...)
@@ -74,9 +76,16 @@ int slice_vectors(int V, int dtype, int nsplit)
     return (((nvec + nsplit - 1) / nsplit) + 63) & ~63;
 }
 
-int choose_nsplit(const tapout_ctx *ctx, int64_t rows, int V)
+// Slices per row: enough for about wgs_target workgroups per launch when rows are few, and slices of about
+// slice_bytes when rows are many (a launch ends ragged by about half the duration of one workgroup, so
+// workgroups that stream a whole long row cost several percent of the launch); never below min_slice
+// elements per slice, which no longer amortises a workgroup's fixed cost.
+int choose_nsplit(const tapout_ctx *ctx, int64_t rows, int V, int dtype)
 {
+    const int64_t row_bytes = (int64_t)V * (dtype == TAPOUT_F32 ? 4 : 2);
     int64_t want = (ctx->wgs_target + rows - 1) / rows;
+    const int64_t by_bytes = row_bytes / ctx->slice_bytes;
+    if (want < by_bytes) want = by_bytes;
     int64_t by_size = V / ctx->min_slice;
     if (by_size < 1) by_size = 1;
     if (want > by_size) want = by_size;
@@ -209,7 +218,9 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     c->cfg = *cfg;
     DeviceGuard guard(cfg->device);
     const size_t rows = (size_t)cfg->max_batch * (cfg->max_k + 1);
-    c->part_cap = rows + kMaxWgsTarget;
+    int64_t by_bytes_max = (int64_t)cfg->vocab * 4 / kMinSliceBytes;
+    by_bytes_max = by_bytes_max < 1 ? 1 : (by_bytes_max > kStageCap ? kStageCap : by_bytes_max);
+    c->part_cap = rows * (size_t)by_bytes_max + kMaxWgsTarget;   // rows * nsplit under either rule of choose_nsplit
     c->positions = cfg->granularity == TAPOUT_TOKEN_LEVEL ? cfg->max_k : 1;
     const size_t nstate = (size_t)cfg->n_bandits * c->positions * cfg->n_arms;
     c->nsl_max = (cfg->vocab + kSampleSlice - 1) / kSampleSlice;
@@ -276,6 +287,9 @@ tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value
     if (!strcmp(name, "wgs_target")) {
         if (value < 1 || value > kMaxWgsTarget) return fail(ctx, TAPOUT_EINVAL, "wgs_target outside [1, %d]", kMaxWgsTarget);
         ctx->wgs_target = value;
+    } else if (!strcmp(name, "slice_bytes")) {
+        if (value < kMinSliceBytes) return fail(ctx, TAPOUT_EINVAL, "slice_bytes below %d", kMinSliceBytes);
+        ctx->slice_bytes = value;
     } else if (!strcmp(name, "min_slice")) {
         if (value < 256) return fail(ctx, TAPOUT_EINVAL, "min_slice below 256 elements");
         ctx->min_slice = value;
@@ -333,7 +347,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     DeviceGuard guard(ctx->cfg.device);
     hipStream_t st = (hipStream_t)stream;
     const int64_t rows = (int64_t)B * K;
-    const int nsplit = choose_nsplit(ctx, rows, V);
+    const int nsplit = choose_nsplit(ctx, rows, V, draft->dtype);
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, slice_vectors(V, draft->dtype, nsplit), (int32_t)rows, k_len, 0, ctx->part};
@@ -395,7 +409,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     DeviceGuard guard(ctx->cfg.device);
     hipStream_t st = (hipStream_t)stream;
     const int64_t rows = (int64_t)B * (K + 1);
-    const int nsplit = choose_nsplit(ctx, rows, V);
+    const int nsplit = choose_nsplit(ctx, rows, V, target->dtype);
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, slice_vectors(V, target->dtype, nsplit), (int32_t)rows, n_draft, 1, ctx->part};

@@ -15,7 +15,7 @@ struct tapout_ctx {
     tapout_config cfg;
     Partial *part = nullptr;      size_t part_cap = 0;       // slice partials of the pass in flight
     double *part1 = nullptr, *part2 = nullptr;                // residual sampler slice sums
-    SampleJob *jobs = nullptr;
+    JobRecord *jobs = nullptr;                                 // per final-token job: what to draw from, and its band list
     uint32_t *flags_ws = nullptr;
     double *exp_table = nullptr;                               // 2^(k/256), k = 0..255, for the final-token passes
     int nsl_max = 0;                                           // final-token slices per row at cfg.vocab
@@ -233,7 +233,7 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
            && hipMalloc(&c->part2, njobs * c->nsl_max * sizeof(double)) == hipSuccess
            && hipMalloc(&c->exp_table, sizeof table) == hipSuccess
            && hipMemcpy(c->exp_table, table, sizeof table, hipMemcpyHostToDevice) == hipSuccess
-           && hipMalloc(&c->jobs, njobs * sizeof(SampleJob)) == hipSuccess
+           && hipMalloc(&c->jobs, njobs * sizeof(JobRecord)) == hipSuccess
            && hipMalloc(&c->flags_ws, (size_t)cfg->max_batch * sizeof(uint32_t)) == hipSuccess
            && hipMalloc(&c->sum_r, nstate * sizeof(double)) == hipSuccess
            && hipMalloc(&c->sum_r2, nstate * sizeof(double)) == hipSuccess

@@ -39,6 +39,20 @@ struct SampleJob {
     double lam;      // binary32-grade estimate of S_p / S_q in those references (kind 1)
 };
 
+
+constexpr int kBandCap = 32;         // band elements per job the locate kernel settles one by one; more: exact slow path
+
+// The job as it lies in memory, together with the list of elements of its row pair whose sign of a - L b is
+// open until L is exact (appended by the slice kernel, read by the locate kernel).  One record, so that the
+// locate kernel finds everything about its job in two neighbouring cache lines of one page.
+struct JobRecord {
+    SampleJob job;
+    int32_t band_cnt;              // appended so far; entries beyond kBandCap are dropped (the count still grows)
+    int32_t pad;
+    int32_t band_idx[kBandCap];    // element indices, any order
+};
+static_assert(sizeof(JobRecord) == 160, "job record layout");
+
 __host__ __device__ inline float ref_of_max(float v1)
 {
     // integer-valued reference >= v1*log2e; 0 for a slice without finite maximum
@@ -102,8 +116,8 @@ struct VerifyArgs {
     int32_t *accept_len, *out_tok, *n_out;
     float *target_lse, *logp_tok; int32_t *target_top1; uint32_t *flags;
     uint32_t *flags_ws;           // internal copy of the flags (always present)
-    SampleJob *jobs;              // [B]
-    double *part1;                // [B, nsl, 5]  A, B, R~, D, U of each slice
+    JobRecord *jobs;              // [jobs]
+    double *part1;                // [jobs, nsl, 5]  A, B, R~, D, U of each slice
     double *part2;                // [B, nsl]     exact weight of each slice (slow path)
     const double *exp_table;      // 2^(k/256), k = 0..255
 };

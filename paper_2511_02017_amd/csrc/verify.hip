@@ -12,15 +12,23 @@
 //           B = sum b_j (a = exp(t - ref_p), b = exp(d - ref_q)) and, with the
 //           head's binary32-grade estimate L~ of L = S_p / S_q:
 //           R~ = sum max(0, a_j - L~ b_j), D = sum of b_j over a_j > L~ b_j,
-//           U = sum of b_j over |a_j - L~ b_j| <= eta L~ b_j
+//           U = sum of b_j over the band |a_j - L~ b_j| <= eta L~ b_j; the
+//           indices of the band elements (a handful: the band is 1e-5 wide) go
+//           to a short per-sequence list
 //   locate  one workgroup per sequence: exact L = sum A / sum B; the slice
-//           weights of the residual max(0, a - L b) are R~ - (L - L~) D, exact
-//           except for elements whose sign flips between L~ and L, all of which
-//           are counted in U: the error is at most |L - L~| * sum U.  If that
-//           bound is below 2e-10 of the total weight (it typically is 1e-12)
-//           the slice holding u * Z is found from those sums and the token by
-//           an exact scan inside it; otherwise the slice sums are recomputed
-//           exactly first (slow path).
+//           weights of the residual max(0, a - L b) are R~ - (L - L~) D, which
+//           is exact for every element whose sign of a - L b is the same at L~
+//           and at L; an element can change sign only inside the band (given
+//           |L - L~| <= eta L~, which is checked), where it is off by at most
+//           |L - L~| b_j: in total at most |L - L~| * sum U.  If that bound is
+//           below 2e-10 of the total weight (typically it is 1e-12) the sums
+//           are used as they are.  If a heavy token sits in the band, the
+//           listed elements are evaluated one by one with the exact L and
+//           their slices corrected.  Then the slice holding u * Z is found
+//           from the slice weights and the token by an exact scan inside it.
+//           If the list overflowed (ratios tied inside the band, p == q), L~ is
+//           off or Z vanishes, the slice weights are recomputed exactly first
+//           (slow path).
 //
 // token = smallest j whose inclusive prefix sum exceeds u * Z.  Everything is
 // double precision: with ~1e5 CDF cell edges in [0,1) a binary32 evaluation
@@ -246,7 +254,8 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         if (threadIdx.x == 0) {
             a.accept_len[b] = m;
             a.n_out[b] = m + 1;
-            a.jobs[b] = job;
+            a.jobs[b].job = job;
+            a.jobs[b].band_cnt = 0;                  // the slice kernel appends to the sequence's band list
             a.flags_ws[b] = f;
             if (a.flags) a.flags[b] = f;
         }
@@ -290,7 +299,7 @@ __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
 // A slice is kSampleSlice = 2048 elements, one 8-element run per thread: small enough for 64 registers, so
 // that eight workgroups share a compute unit and the loads of the next ones are in flight while the first
 // ones do their double-precision arithmetic.
-constexpr double kEta = 1.0e-5;        // half-width (relative) of the band around L~ whose elements are counted in U
+constexpr double kEta = 1.0e-5;        // half-width (relative) of the band around L~ in which a sign may be wrong
 constexpr int kSliceVals = 5;          // A, B, R~, D, U
 
 template <int TD, int DD>
@@ -301,7 +310,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
     const int j = blockIdx.z * gridDim.y + blockIdx.y, s = blockIdx.x;
     if (j >= a.n_jobs) return;
     const int b = j / a.jps;
-    const SampleJob job = a.jobs[j];
+    const SampleJob job = a.jobs[j].job;
     if (job.kind == 0) return;
     const Rows r = job_rows<TD, DD>(a, b, job);
     float xt[kRuns][kPer], xd[kRuns][kPer];
@@ -318,7 +327,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
     const double lam = job.lam, band = kEta * job.lam;
     // Ds = sum of b carrying the sign of a - L~ b, so that D = (B + Ds) / 2 without a select per element (an
     // element with a == L~ b lands in D; it is in the band, so U covers it).  Elements inside the band are a
-    // handful per row at most: their sum is taken under a branch that a wavefront almost never enters.
+    // handful per row at most: their sum and their list are kept under a branch a wavefront almost never enters.
     double A = 0.0, Bs = 0.0, R = 0.0, Ds = 0.0, U = 0.0;
     if (job.kind == 1) {
 #pragma unroll
@@ -335,7 +344,12 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
                 const bool in_band = fabs(diff) <= band * bv;
                 if (__builtin_amdgcn_ballot_w64(in_band) != 0) {
                     asm volatile("" ::: "memory");              // keep this a branch: a select would cost every element
-                    U += in_band ? bv : 0.0;
+                    if (in_band) {
+                        U += bv;
+                        const int pos = atomicAdd(&a.jobs[j].band_cnt, 1);
+                        if (pos < kBandCap)
+                            a.jobs[j].band_idx[pos] = s * kSampleSlice + (g * kVBlock + (int)threadIdx.x) * kPer + i;
+                    }
                 }
             }
     } else {
@@ -409,6 +423,8 @@ struct LocateShared {
     double bc[4];           // broadcasts
     int hits[2][4];         // alternating per-wavefront results of locate_in_slice
     int last, slice;
+    int band_key[kBandCap];     // band elements of the sequence, sorted by index ...
+    double band_val[kBandCap];  // ... and their residual weights with the exact L
 };
 
 __device__ inline int wave_min_i32(int v)
@@ -459,6 +475,38 @@ __device__ inline int locate_in_slice(const Weights &w, const Rows &r, int s, in
     return h == 0x7fffffff ? -1 : h;
 }
 
+// Band elements of a sequence (see the slice kernel).  Each listed element is evaluated with the exact L; what it
+// contributed to the slice sums under L~ (recomputed here with the slice kernel's own arithmetic, hence the same
+// number) is taken back: correction = max(0, a - L b) - (max(0, a - L~ b) - delta [a > L~ b] b).  The list is
+// sorted by index, so that sums over it do not depend on the order in which the slice kernel's workgroups
+// appended.  Leaves the sorted (index, correction) pairs in sh and returns their total.  Whole workgroup.
+template <int TD, int DD>
+__device__ __noinline__ double settle_band(const Weights &w, const Rows &r, int V, const double *T,
+                                           double lam_est, double delta, int n_band, int band_i, LocateShared *sh)
+{
+    const int tid = threadIdx.x;
+    double wv = 0.0;
+    if (tid < n_band && band_i < V) {
+        const double av = exp_fast(load_elem<TD>(r.trow, band_i), w.rp.neg_ref_c, w.rp.lo, T);
+        const double bv = exp_fast(load_elem<DD>(r.drow, band_i), w.rq.neg_ref_c, w.rq.lo, T);
+        const double v = fma(-w.lam, bv, av);
+        const double exact = v > 1.0e-290 ? v : 0.0;           // same rule as thread_weights (masked logits weigh nothing)
+        const double dt = fma(-lam_est, bv, av);
+        wv = exact - (fmax(dt, 0.0) - delta * (dt >= 0.0 ? bv : 0.0));
+    }
+    if (tid < kBandCap) { sh->band_key[tid] = tid < n_band ? band_i : 0x7fffffff; sh->band_val[tid] = wv; }
+    __syncthreads();
+    int rank = 0;
+    if (tid < n_band)
+        for (int q = 0; q < n_band; ++q) rank += sh->band_key[q] < band_i ? 1 : 0;     // indices are distinct
+    __syncthreads();
+    if (tid < n_band) { sh->band_key[rank] = band_i; sh->band_val[rank] = wv; }
+    __syncthreads();
+    double total = 0.0;
+    for (int q = 0; q < n_band; ++q) total += sh->band_val[q];
+    return total;
+}
+
 template <int TD, int DD>
 __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
 {
@@ -471,14 +519,26 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     // the slice sums, the table and the uniform are requested before the job is looked at (one round trip)
     const double *ps = a.part1 + (int64_t)j * a.nsl * kSliceVals;
     double *zs = a.part2 + (int64_t)j * a.nsl;                       // exact slice weights (slow path only)
+    // First all loads that do not depend on each other, then their uses: written so that no wait separates the
+    // requests (the first slice of each thread without a loop; 256 threads fetch the 256 table entries).
+    static_assert(kVBlock == 256, "one table entry per thread");
     double acc[kSliceVals] = {0.0, 0.0, 0.0, 0.0, 0.0};
-    for (int s = tid; s < a.nsl; s += kVBlock)
+    const bool has_first = tid < a.nsl;
+    const double *pf = ps + (has_first ? tid : 0) * kSliceVals;
+    const double f0 = pf[0], f1 = pf[1], f2 = pf[2], f3 = pf[3], f4 = pf[4];     // slot 0 always exists: harmless when unused
+    const double tv = a.exp_table[tid];
+    const float u32v = a.u_sample[j];
+    const int band_n = a.jobs[j].band_cnt;
+    const int band_i = a.jobs[j].band_idx[tid & (kBandCap - 1)];                                  // stale beyond band_n: unused
+    const SampleJob job = a.jobs[j].job;
+    // the compiler would otherwise sink these loads below the early exit and pay a second round trip for them
+    asm volatile("" :: "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(f4), "v"(tv), "v"(u32v), "v"(band_n), "v"(band_i));
+    shT[tid] = tv;
+    if (job.kind == 0) return;                                        // the slice sums of such a sequence are stale: unused
+    if (has_first) { acc[0] = f0; acc[1] = f1; acc[2] = f2; acc[3] = f3; acc[4] = f4; }
+    for (int s = tid + kVBlock; s < a.nsl; s += kVBlock)              // vocabularies beyond 256 slices
 #pragma unroll
         for (int q = 0; q < kSliceVals; ++q) acc[q] += ps[s * kSliceVals + q];
-    for (int i = tid; i < 256; i += kVBlock) shT[i] = a.exp_table[i];
-    const float u32v = a.u_sample[j];
-    const SampleJob job = a.jobs[j];
-    if (job.kind == 0) return;                                        // the slice sums of such a sequence are stale: unused
     if (tid == 0) { shl.last = -1; shl.slice = 0x7fffffff; }
 
     // totals of the five slice quantities, fixed order
@@ -508,12 +568,21 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     const double u = (double)u32v;
     int phase = 0;
 
-    // slice weights: target row alone -> A_s; residual -> R~_s - delta D_s if the bound on the sign flips allows
+    // slice weights: target row alone -> A_s; residual -> R~_s - delta D_s if the bound on the sign flips allows,
+    // else with the listed band elements corrected one by one
     double Z = w.kind == 2 ? Sp : tot[2] - delta * tot[3];
     bool exact_sums = false;
+    int n_band = 0;
     if (w.kind == 1) {
-        const bool certified = fabs(delta) <= kEta * job.lam && Z > 0.0 && fabs(delta) * tot[4] <= 2.0e-10 * Z;
+        const bool close = fabs(delta) <= kEta * job.lam;
+        bool certified = close && Z > 0.0 && fabs(delta) * tot[4] <= 2.0e-10 * Z;
+        if (!certified && close && band_n <= kBandCap) {
+            n_band = band_n;
+            Z += settle_band<TD, DD>(w, r, a.V, shT, job.lam, delta, band_n, band_i, &shl);
+            certified = Z > 0.0;
+        }
         if (!certified) {
+            n_band = 0;
             // slow path: exact slice weights with the exact L (also the p == q case: then Z may vanish)
             double ztot = 0.0;
             for (int s = 0; s < a.nsl; ++s) {
@@ -544,8 +613,11 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     auto slice_weight = [&](int s) -> double {
         if (exact_sums) return zs[s];
         if (w.kind == 2) return ps[s * kSliceVals + 0];
-        const double v = ps[s * kSliceVals + 2] - delta * ps[s * kSliceVals + 3];
-        return v > 0.0 ? v : 0.0;
+        double v = ps[s * kSliceVals + 2] - delta * ps[s * kSliceVals + 3];
+        v = v > 0.0 ? v : 0.0;
+        for (int q = 0; q < n_band; ++q)
+            if (shl.band_key[q] / kSampleSlice == s) v += shl.band_val[q];
+        return v;
     };
 
     int token = -1;
@@ -632,7 +704,8 @@ __global__ __launch_bounds__(kVBlock) void sample_head_kernel(VerifyArgs a)
         if (bad) a.tok_direct[j] = -1;           // NaN in the row or no finite maximum: nothing to draw from
         else { job.kind = 2; job.ref_p = M; }
     }
-    a.jobs[j] = job;
+    a.jobs[j].job = job;
+    a.jobs[j].band_cnt = 0;
 }
 
 template <int TD, int DD>

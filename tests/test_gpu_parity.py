@@ -195,6 +195,38 @@ def test_residual_with_tied_probability_ratios(boost):
     assert all(int(final[b]) in hot[b].cpu().tolist() for b in range(B) if ok[b])   # the residual lives on the boosted tokens
 
 
+def test_residual_with_a_few_tokens_where_p_equals_q():
+    """A few heavy tokens with p = q to within 1e-6: the sign of p - q there cannot be taken from binary32-grade
+    normalisers; the sampler has to settle exactly these tokens with the exact normalisers (and only them)."""
+    B, K, V = 5, 2, 30000
+    g = torch.Generator().manual_seed(41)
+    d = (torch.randn(B, K, V, generator=g) * 2).float()
+    t = torch.cat([d + torch.randn(B, K, V, generator=g), torch.randn(B, 1, V, generator=g) * 2], 1).float()
+    hot = torch.randint(0, V, (B, 4), generator=g)
+    for b in range(B):
+        d[b, 0, hot[b]] = d[b, 0].max() + torch.tensor([2.0, 1.5, 1.0, 0.5])        # heavy under q
+        # p_h = q_h on the hot set H:  e^{t_h} = q_h R_p / (1 - Q_H),  R_p = sum of e^{t_j} over j outside H, Q_H = sum_H q_h
+        q = torch.softmax(d[b, 0].double(), 0)
+        mask = torch.ones(V, dtype=torch.bool); mask[hot[b]] = False
+        ln_rp = torch.logsumexp(t[b, 0].double()[mask], 0)
+        t[b, 0, hot[b]] = (q[hot[b]].log() + ln_rp - torch.log1p(-q[hot[b]].sum())).float()
+        p = torch.softmax(t[b, 0].double(), 0); q = torch.softmax(d[b, 0].double(), 0)
+        rel = ((p - q) / q)[hot[b]].abs()
+        assert (rel < 5e-6).all() and (q[hot[b]] > 1e-3).all()
+    tok = torch.randint(0, V, (B, K), generator=g, dtype=torch.int32)
+    for b in range(B):
+        clash = (tok[b][:, None] == hot[b][None, :]).any(1)
+        tok[b][clash] = (tok[b][clash] + 11) % V
+    rnd = dict(draft=d.to(DEV), target=t.to(DEV), draft_tok=tok.to(DEV),
+               u_accept=torch.full((B, K), 1.0 - 2.0 ** -24, device=DEV), u_sample=torch.rand(B, generator=g).to(DEV),
+               k_len=torch.full((B,), K, dtype=torch.int32, device=DEV), greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
+    tp = binding.Tapout(B, K, V)
+    c = pu.check_round(tp, rnd)
+    assert c["icdf_flagged"] <= 1
+    _, vf, _ = pu.gpu_round(tp, rnd)
+    assert (vf["accept_len"].cpu() == 0).sum() >= B - c["accept_flagged"] - 1
+
+
 def test_bad_inputs_set_flags_and_fall_back():
     rnd = degenerate_round(torch.float32)
     B, K, V = rnd["draft"].shape

@@ -222,6 +222,40 @@ __device__ inline void stage_partials(Partial *sh, const Partial *src, int count
     __syncthreads();
 }
 
+// The same copy in two steps for a 256-thread workgroup, so that a caller can put other independent loads
+// into the same memory round trip: stage_issue requests (at most two 16-byte words per thread, count <=
+// kStageCap), stage_commit stores to LDS and synchronises.
+struct StageRegs { u32x4 w0, w1; };
+__device__ inline StageRegs stage_issue(const Partial *src, int count)
+{
+    const u32x4 *s = (const u32x4 *)src;
+    StageRegs r;
+    r.w0 = r.w1 = u32x4{0u, 0u, 0u, 0u};
+    const int i = threadIdx.x;
+    if (i < 2 * count) r.w0 = s[i];
+    if (i + 256 < 2 * count) r.w1 = s[i + 256];
+    return r;
+}
+__device__ inline void stage_commit(Partial *sh, const StageRegs &r, int count)
+{
+    u32x4 *d = (u32x4 *)sh;
+    const int i = threadIdx.x;
+    if (i < 2 * count) d[i] = r.w0;
+    if (i + 256 < 2 * count) d[i + 256] = r.w1;
+    __syncthreads();
+}
+
+// v[i] for a small array that lives in scalar registers (kernel arguments): selects instead of a load from
+// the argument buffer, which would be one more memory round trip.
+template <class T>
+__device__ inline T pick8(const T (&v)[TAPOUT_MAX_ARMS], int i)
+{
+    T r = v[0];
+#pragma unroll
+    for (int q = 1; q < TAPOUT_MAX_ARMS; ++q) r = (i == q) ? v[q] : r;
+    return r;
+}
+
 // Merged statistics of all slices of one row, in double.
 struct RowTotal {
     float M;          // row maximum
@@ -270,11 +304,24 @@ __device__ inline int32_t resolve_argmax(const void *row, int dtype, int32_t V, 
 {
     if (cand < 0 || cand >= V) return 0;
     const int window = dtype == TAPOUT_F32 ? 4 : 8;
-    // all loads first (independent, one memory round trip), then the first match
+    const int esz = dtype == TAPOUT_F32 ? 4 : 2;
+    const char *p = (const char *)row + (int64_t)cand * esz;
     float x[8];
+    if ((((uintptr_t)p) & 15u) == 0 && cand + window <= V) {
+        // the usual case: the window is one of the 16-byte vectors the streaming pass loaded; one load
+        const u32x4 w = *(const u32x4 *)p;
+        const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-        x[i] = (i < window && cand + i < V) ? load_elem_rt(row, dtype, cand + i) : NAN;
+        for (int i = 0; i < 4; ++i) {
+            if (dtype == TAPOUT_F32) { x[i] = __uint_as_float(ww[i]); x[4 + i] = NAN; }
+            else { x[2 * i] = __uint_as_float(ww[i] << 16); x[2 * i + 1] = __uint_as_float(ww[i] & 0xffff0000u); }
+        }
+    } else {
+        // unaligned head / tail elements of a row
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            x[i] = (i < window && cand + i < V) ? load_elem_rt(row, dtype, cand + i) : NAN;
+    }
     int32_t hit = cand;
 #pragma unroll
     for (int i = 7; i >= 0; --i)

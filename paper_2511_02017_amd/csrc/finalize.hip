@@ -55,36 +55,45 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     const int K = a.K;
     const int rows_per_stage = kStageCap / a.nsplit;          // nsplit <= kStageCap is guaranteed by the host
     const bool want_tok = a.draft_tok && a.logq_tok;
-    // Everything whose address does not depend on k_len is requested before k_len is looked at, so that the
-    // first memory round trip carries k_len, the arm, the tokens and the partials together.  (Rows beyond
-    // k_len hold stale partials and unused tokens: read, never used.)
+    static_assert(kFinalBlock == 256, "stage_issue / stage_commit assume 256 threads");
+    // First memory round trip: k_len, the arm, the carried entropy, the drafted tokens and the partials, all
+    // requested before anything is waited for.  (Rows beyond k_len hold stale partials and unused tokens:
+    // read, never used.)  The empty asm keeps the compiler from sinking the small loads below the barrier.
+    const bool tok_mode = a.arm_stride > 0;
+    int kb = a.k_len ? a.k_len[b] : K;
+    const int arm = (a.arm && !tok_mode) ? a.arm[b] : -1;     // sequence-level bandit: one arm for all steps
+    float H_carry = a.prev_entropy ? a.prev_entropy[b] : NAN;
     int32_t tok0 = -1;
     if (want_tok && (int)threadIdx.x < K) tok0 = a.draft_tok[(int64_t)b * K + threadIdx.x];
-    stage_partials(sh_part, a.part + (int64_t)b * K * a.nsplit, min(K, rows_per_stage) * a.nsplit);
-    int kb = a.k_len ? a.k_len[b] : K;
+    const int count0 = min(K, rows_per_stage) * a.nsplit;
+    const StageRegs st0 = stage_issue(a.part + (int64_t)b * K * a.nsplit, count0);
+    asm volatile("" :: "v"(kb), "v"(arm), "v"(H_carry), "v"(tok0), "v"(st0.w0), "v"(st0.w1));
+    // Second round trip: the logit of the drafted token (its address needs the token, not k_len: rows up to K
+    // exist), in flight while the partials go through LDS and are merged.
+    float xtok_first = 0.0f;
+    if (want_tok && (int)threadIdx.x < K && tok0 >= 0 && tok0 < a.V)
+        xtok_first = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, threadIdx.x), a.dtype, tok0);
+    stage_commit(sh_part, st0, count0);
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
-    // sequence-level bandit: one arm for all steps; token-level bandits: the arm of step k is arm[b, k]
-    const bool tok_mode = a.arm_stride > 0;
-    const int arm = (a.arm && !tok_mode) ? a.arm[b] : -1;
     const bool arm_ok = arm >= 0 && arm < a.n_arms;
-    const int rule_b = arm_ok ? a.rule[arm] : -1;
-    // rows whose rule looks beyond their own signals are decided in a second sweep (uniform over the workgroup)
+    const int rule_b = arm_ok ? pick8(a.rule, arm) : -1;
+    // rows whose rule looks beyond their own signals are decided in a second sweep (uniform over the workgroup);
+    // token-level bandits: the arm of step k is arm[b, k]
     const bool sweep = tok_mode ? (a.round_entropy != nullptr)
                                 : (rule_b == TAPOUT_RULE_SVIP_DIFF || rule_b == TAPOUT_RULE_ADAEDL);
-    float H_carry = NAN;
-    if (sweep && a.prev_entropy) H_carry = a.prev_entropy[b];
     if (threadIdx.x == 0) sh_flags = 0;
     for (int k0 = 0; k0 < kb; k0 += rows_per_stage) {
         const int k1 = min(kb, k0 + rows_per_stage);
         const int kmine = k0 + threadIdx.x;                   // first (usually only) row of this thread in the stage
-        float xtok0 = 0.0f;
+        float xtok0 = xtok_first;
         if (k0 > 0) {                                         // further stages (K > rows_per_stage): load late
             tok0 = (want_tok && kmine < k1) ? a.draft_tok[(int64_t)b * K + kmine] : -1;
             __syncthreads();
             stage_partials(sh_part, a.part + ((int64_t)b * K + k0) * a.nsplit, (k1 - k0) * a.nsplit);
+            xtok0 = 0.0f;
+            if (want_tok && kmine < k1 && tok0 >= 0 && tok0 < a.V)
+                xtok0 = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, kmine), a.dtype, tok0);
         }
-        if (want_tok && kmine < k1 && tok0 >= 0 && tok0 < a.V)
-            xtok0 = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, kmine), a.dtype, tok0);
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t i = (int64_t)b * K + k;
             const void *row = row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
@@ -125,12 +134,12 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
             if (a.arm) {
                 const int arm_k = tok_mode ? a.arm[(int64_t)b * a.arm_stride + k] : arm;
                 const bool ok_k = arm_k >= 0 && arm_k < a.n_arms;
-                const int rule_k = ok_k ? a.rule[arm_k] : -1;
+                const int rule_k = ok_k ? pick8(a.rule, arm_k) : -1;
                 if (sweep) sh_H[k] = H;
                 if (rule_k == TAPOUT_RULE_SVIP_DIFF || rule_k == TAPOUT_RULE_ADAEDL) {
                     sh_dec[k] = 2;                             // decided below, once every row's entropy is known
                 } else {
-                    const bool fire = ok_k && rule_fires(rule_k, a.threshold[arm_k], H, p1, mg);
+                    const bool fire = ok_k && rule_fires(rule_k, pick8(a.threshold, arm_k), H, p1, mg);
                     if (a.stop_fired) a.stop_fired[i] = fire ? 1 : 0;
                     sh_dec[k] = fire ? 1 : 0;                  // k < K <= kScanCap
                 }
@@ -145,10 +154,10 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
             const int arm_k = tok_mode ? a.arm[(int64_t)b * a.arm_stride + k] : arm;      // in range: checked when it was marked
             const float H = sh_H[k];
             bool fire;
-            if (a.rule[arm_k] == TAPOUT_RULE_SVIP_DIFF) {
-                fire = svip_diff_fires(a.threshold[arm_k], H, k > 0 ? sh_H[k - 1] : H_carry);
+            if (pick8(a.rule, arm_k) == TAPOUT_RULE_SVIP_DIFF) {
+                fire = svip_diff_fires(pick8(a.threshold, arm_k), H, k > 0 ? sh_H[k - 1] : H_carry);
             } else {
-                const double lam = a.lambda ? a.lambda[(int64_t)b * a.n_arms + arm_k] : (double)a.threshold[arm_k];
+                const double lam = a.lambda ? a.lambda[(int64_t)b * a.n_arms + arm_k] : (double)pick8(a.threshold, arm_k);
                 fire = adaedl_fires(a.adaedl_gamma, lam, H);
             }
             if (a.stop_fired) a.stop_fired[(int64_t)b * K + k] = fire ? 1 : 0;

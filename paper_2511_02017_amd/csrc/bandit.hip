@@ -128,6 +128,47 @@ __global__ void bandit_select_kernel(BanditArgs a, const float *u_ts, int32_t *a
     if (flags) flags[b] = ex ? TAPOUT_FLAG_SAMPLER_EXHAUSTED : 0u;
 }
 
+// Sequence-level Thompson Sampling with Beta posteriors, lane-parallel: the Marsaglia-Tsang loops of the 2 * arms
+// Gamma variates of a sequence are long serial chains of double-precision log / sqrt / cos, so each gets a lane
+// of its own (16 lanes per sequence: lane = 2 * arm + variate), the pair is combined with one lane exchange and
+// the argmax runs over the sequence's 16 lanes.  Same operations per variate as the one-thread version, hence
+// the same bits.
+__global__ __launch_bounds__(64) void bandit_select_ts_kernel(BanditArgs a, const float *u_ts, int32_t *arm_out, uint32_t *flags)
+{
+    static_assert(TAPOUT_MAX_ARMS * 2 == 16, "16 lanes per sequence");
+    const int lane16 = threadIdx.x & 15;
+    const int b = blockIdx.x * 4 + (threadIdx.x >> 4);
+    const int arm = lane16 >> 1, which = lane16 & 1;
+    const bool live = b < a.B && arm < a.n_arms;
+    double g = 1.0;
+    bool ex = false;
+    if (live) {
+        const size_t nb = (size_t)(a.n_bandits == 1 ? 0 : b) * a.n_arms;
+        const double S = a.sum_r[nb + arm], N = (double)a.count[nb + arm];
+        const double shape = which == 0 ? 1.0 + S : 1.0 + (N - S);
+        const float *ua = u_ts + (nb + arm) * TAPOUT_TS_UNIFORMS_PER_ARM + which * kAttempts * 3;
+        g = gamma_draw(shape, ua, &ex);
+    }
+    // theta = g1 / (g1 + g2) on the even lane of each pair
+    const double other = __shfl_xor(g, 1);
+    double th = (live && which == 0) ? g / (g + other) : -INFINITY;
+    int best = (live && which == 0) ? arm : 0x7fffffff;
+    uint32_t exm = ex ? 1u : 0u;
+    // argmax over the 16 lanes of the sequence; ties go to the lowest arm (the one-thread loop keeps the first maximum)
+#pragma unroll
+    for (int d = 2; d < 16; d <<= 1) {
+        const double oth = __shfl_xor(th, d);
+        const int ob = __shfl_xor(best, d);
+        if (oth > th || (oth == th && ob < best)) { th = oth; best = ob; }
+    }
+#pragma unroll
+    for (int d = 1; d < 16; d <<= 1) exm |= __shfl_xor(exm, d);
+    if (b < a.B && lane16 == 0) {
+        arm_out[b] = best == 0x7fffffff ? 0 : best;
+        if (flags) flags[b] = exm ? TAPOUT_FLAG_SAMPLER_EXHAUSTED : 0u;
+    }
+}
+
 // Token-level bandits: one workgroup per sequence, its threads take the positions; the sequence's flag word
 // is the OR over its positions.
 __global__ void bandit_select_token_kernel(BanditArgs a, const float *u_ts, int32_t *arm_out, uint32_t *flags)
@@ -228,6 +269,7 @@ hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t 
 {
     const int block = 64;
     if (a.positions > 1) launch_kernel(bandit_select_token_kernel, dim3(a.B), dim3(block), st, tm, a, u_ts, arm_out, flags);
+    else if (a.policy == TAPOUT_TS_BETA) launch_kernel(bandit_select_ts_kernel, dim3((a.B + 3) / 4), dim3(64), st, tm, a, u_ts, arm_out, flags);
     else launch_kernel(bandit_select_kernel, dim3((a.B + block - 1) / block), dim3(block), st, tm, a, u_ts, arm_out, flags);
     return hipGetLastError();
 }

@@ -47,8 +47,8 @@ namespace {
 
 constexpr int kVBlock = 256;
 constexpr int kPer = 8;                       // elements per 16-byte (bf16) / 32-byte (f32) run
-constexpr int kRuns = 1;                      // runs per thread and slice in the slice pass
-static_assert(kVBlock * kPer * kRuns == kSampleSlice, "slice = kRuns 8-element runs per thread");
+
+
 
 // ---- double-precision helpers ---------------------------------------------------
 constexpr double kExpC = 369.3299304675746;            // 256 / ln 2
@@ -296,32 +296,41 @@ __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
 }
 
 // ---- slice kernel -----------------------------------------------------------------------
-// A slice is kSampleSlice = 2048 elements, one 8-element run per thread: small enough for 64 registers, so
-// that eight workgroups share a compute unit and the loads of the next ones are in flight while the first
-// ones do their double-precision arithmetic.
+// A slice is kSampleSlice = 2048 elements.
 constexpr double kEta = 1.0e-5;        // half-width (relative) of the band around L~ in which a sign may be wrong
 constexpr int kSliceVals = 5;          // A, B, R~, D, U
 
+constexpr int kWavesPerWG = kVBlock / kWave;                    // 4 slices per workgroup, one per wavefront
+constexpr int kChunks = kSampleSlice / (kWave * kPer);          // a wavefront takes its slice in 4 chunks of 512 elements
+
+// One wavefront per slice, four slices per workgroup.  A wavefront streams its slice in chunks of one 8-element
+// run per lane and requests the next chunk before it does the arithmetic of the current one, so that after the
+// first chunk the memory latency hides behind the double-precision work; its five sums need no LDS and no
+// barrier.  (One slice per workgroup with all loads up front was latency bound: job record, then rows, then
+// arithmetic, 8.7 us per workgroup with at most eight of them per compute unit.)
 template <int TD, int DD>
-__global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8))) void verify_slices(VerifyArgs a)
+__global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
 {
     __shared__ double shT[256];
-    __shared__ double sh_red[kSliceVals][kVBlock / kWave];
-    const int j = blockIdx.z * gridDim.y + blockIdx.y, s = blockIdx.x;
+    const int j = blockIdx.z * gridDim.y + blockIdx.y;
     if (j >= a.n_jobs) return;
     const int b = j / a.jps;
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    const int s = blockIdx.x * kWavesPerWG + wave;
     const SampleJob job = a.jobs[j].job;
     if (job.kind == 0) return;
     const Rows r = job_rows<TD, DD>(a, b, job);
-    float xt[kRuns][kPer], xd[kRuns][kPer];
-#pragma unroll
-    for (int g = 0; g < kRuns; ++g) {
-        const int j = s * kSampleSlice + (g * kVBlock + threadIdx.x) * kPer;
-        load8<TD>(r.trow, r.t_al, j, a.V, xt[g]);
-        if (job.kind == 1) load8<DD>(r.drow, r.d_al, j, a.V, xd[g]);
+    const bool live = s < a.nsl;
+    const bool resid = job.kind == 1;
+    const int base = s * kSampleSlice + lane * kPer;
+    float ct[kPer], cd[kPer];
+    if (live) {
+        load8<TD>(r.trow, r.t_al, base, a.V, ct);
+        if (resid) load8<DD>(r.drow, r.d_al, base, a.V, cd);
     }
     for (int i = threadIdx.x; i < 256; i += kVBlock) shT[i] = a.exp_table[i];
     __syncthreads();
+    if (!live) return;
     ExpRef rp, rq;
     rp.set((double)job.ref_p); rq.set((double)job.ref_q);
     const double lam = job.lam, band = kEta * job.lam;
@@ -329,13 +338,19 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
     // element with a == L~ b lands in D; it is in the band, so U covers it).  Elements inside the band are a
     // handful per row at most: their sum and their list are kept under a branch a wavefront almost never enters.
     double A = 0.0, Bs = 0.0, R = 0.0, Ds = 0.0, U = 0.0;
-    if (job.kind == 1) {
 #pragma unroll
-        for (int g = 0; g < kRuns; ++g)
+    for (int c = 0; c < kChunks; ++c) {
+        float nt[kPer], nd[kPer];
+        if (c + 1 < kChunks) {
+            const int jn = base + (c + 1) * kWave * kPer;
+            load8<TD>(r.trow, r.t_al, jn, a.V, nt);
+            if (resid) load8<DD>(r.drow, r.d_al, jn, a.V, nd);
+        }
+        if (resid) {
 #pragma unroll
             for (int i = 0; i < kPer; ++i) {
-                const double av = exp_fast(xt[g][i], rp.neg_ref_c, rp.lo, shT);
-                const double bv = exp_fast(xd[g][i], rq.neg_ref_c, rq.lo, shT);
+                const double av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT);
+                const double bv = exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT);
                 const double diff = fma(-lam, bv, av);
                 A += av;
                 Bs += bv;
@@ -347,26 +362,25 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(8, 8)))
                     if (in_band) {
                         U += bv;
                         const int pos = atomicAdd(&a.jobs[j].band_cnt, 1);
-                        if (pos < kBandCap)
-                            a.jobs[j].band_idx[pos] = s * kSampleSlice + (g * kVBlock + (int)threadIdx.x) * kPer + i;
+                        if (pos < kBandCap) a.jobs[j].band_idx[pos] = base + c * kWave * kPer + i;
                     }
                 }
             }
-    } else {
+        } else {
 #pragma unroll
-        for (int g = 0; g < kRuns; ++g)
+            for (int i = 0; i < kPer; ++i) A += exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT);
+        }
+        if (c + 1 < kChunks) {
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) A += exp_fast(xt[g][i], rp.neg_ref_c, rp.lo, shT);
+            for (int i = 0; i < kPer; ++i) { ct[i] = nt[i]; cd[i] = nd[i]; }
+        }
     }
     double D = 0.5 * (Bs + Ds);
     A = wave_sum_d(A);
-    if (job.kind == 1) { Bs = wave_sum_d(Bs); R = wave_sum_d(R); D = wave_sum_d(D); U = wave_sum_d(U); }
-    const int wave = threadIdx.x / kWave;
-    if ((threadIdx.x & (kWave - 1)) == 0) { sh_red[0][wave] = A; sh_red[1][wave] = Bs; sh_red[2][wave] = R; sh_red[3][wave] = D; sh_red[4][wave] = U; }
-    __syncthreads();
-    if (threadIdx.x < kSliceVals) {
-        const double *v = sh_red[threadIdx.x];
-        a.part1[((int64_t)j * a.nsl + s) * kSliceVals + threadIdx.x] = (v[0] + v[1]) + (v[2] + v[3]);
+    if (resid) { Bs = wave_sum_d(Bs); R = wave_sum_d(R); D = wave_sum_d(D); U = wave_sum_d(U); }
+    if (lane == 0) {
+        double *o = a.part1 + ((int64_t)j * a.nsl + s) * kSliceVals;
+        o[0] = A; o[1] = Bs; o[2] = R; o[3] = D; o[4] = U;
     }
 }
 
@@ -712,7 +726,7 @@ template <int TD, int DD>
 hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {
     const unsigned gy = a.n_jobs < 65535 ? a.n_jobs : 65535, gz = (a.n_jobs + gy - 1) / gy;
-    dim3 grid12(a.nsl, gy, gz), block(kVBlock);
+    dim3 grid12((a.nsl + kWavesPerWG - 1) / kWavesPerWG, gy, gz), block(kVBlock);
     if (pass == 1) launch_kernel(verify_slices<TD, DD>, grid12, block, st, tm, a);
     else launch_kernel(verify_locate<TD, DD>, dim3(a.n_jobs), block, st, tm, a);
     return hipGetLastError();

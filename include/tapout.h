@@ -271,6 +271,56 @@ TAPOUT_API tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *tar
                             uint32_t *flags, void *stream);
 
 /*
+ * Vocabulary-sharded operation (the lm_head is tensor-parallel and this GPU holds
+ * columns [vocab_offset, vocab_offset + Vs) of every row).  tapout_shard_stats
+ * reduces the local slice of every live row to one 32-byte record; the caller
+ * exchanges the records of all G shards (an all-gather of 32 bytes per row and
+ * GPU) and hands them, shard-major, to tapout_draft_stats_sharded, which returns
+ * what tapout_draft_stats returns for the unsplit rows.  Records combine with
+ * the associative rule the library uses between the slices of a row.
+ *   max     largest logit of the slice (-inf for a fully masked slice)
+ *   sum     sum_j 2^(x_j log2(e) - R), R = ceil(max log2(e)) (0 if max = -inf)
+ *   ent     sum_j 2^(x_j log2(e) - R) (x_j log2(e) - R)
+ *   second  second largest logit of the slice, duplicates counted
+ *   argmax  GLOBAL index (vocab_offset + local) of the first maximum
+ *   x_tok   logit of the row's drafted token if its id lies in this slice,
+ *           else NaN
+ */
+typedef struct {
+    float max, sum, ent, second;
+    int32_t argmax;
+    float x_tok;
+    int32_t reserved[2];
+} tapout_shard_stat;
+
+/*
+ * shard     [B, KK, Vs] logits of this GPU's vocabulary slice
+ * len       [B] i32 or NULL;  rows_mode 0: rows k < len[b] are live (draft rows,
+ *           len = k_len, NULL = all); 1: rows k <= len[b] (target rows, len =
+ *           n_draft, required)
+ * tok       [B, KK - rows_mode] i32 GLOBAL token ids or NULL (x_tok = NaN)
+ * out       [B * KK] records; rows that are not live are left untouched
+ */
+TAPOUT_API tapout_status tapout_shard_stats(tapout_ctx *ctx, const tapout_logits *shard,
+                                 int32_t B, int32_t KK, int32_t Vs, int32_t vocab_offset,
+                                 const int32_t *len, int32_t rows_mode, const int32_t *tok,
+                                 tapout_shard_stat *out, void *stream);
+
+/*
+ * stats     [G, B * K] records of the G shards (shard g of row (b,k) at
+ *           stats[g * B * K + b * K + k]), 1 <= G <= 256
+ * V         size of the whole vocabulary (token ids are checked against it)
+ * Everything else as tapout_draft_stats, which this call equals on the unsplit
+ * rows up to the rounding of the binary32 records; u_draft is not supported.
+ */
+TAPOUT_API tapout_status tapout_draft_stats_sharded(tapout_ctx *ctx, const tapout_shard_stat *stats, int32_t G,
+                                 int32_t B, int32_t K, int32_t V,
+                                 const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
+                                 int32_t *top1_id, float *logq_tok,
+                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream);
+
+/*
  * Bandit update after verification (Algorithm 1 line 12; Section 3.2):
  *   r = alpha * m / gamma + (1 - alpha) * m / n,  m = accept_len, n = n_draft,
  *   evaluated in double as (alpha*m)/gamma + ((1-alpha)*m)/n without fused

@@ -27,6 +27,7 @@ STATUS = {0: "TAPOUT_OK", 1: "TAPOUT_EINVAL", 2: "TAPOUT_EUNSUPPORTED", 3: "TAPO
 EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_last_error",
            "tapout_bandit_select", "tapout_draft_stats", "tapout_verify", "tapout_bandit_update",
            "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_rule_state_get", "tapout_rule_state_set",
+           "tapout_shard_stats", "tapout_draft_stats_sharded",
            "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
@@ -72,6 +73,8 @@ def load_library():
         lib.tapout_last_error.argtypes = [vp]
         lib.tapout_bandit_select.argtypes = [vp, i32, vp, vp, vp, vp]
         lib.tapout_draft_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 16
+        lib.tapout_shard_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32, i32, vp, i32, vp, vp, vp]
+        lib.tapout_draft_stats_sharded.argtypes = [vp, vp, i32, i32, i32, i32] + [vp] * 14
         lib.tapout_verify.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 15
         lib.tapout_bandit_update.argtypes = [vp, i32] + [vp] * 6
         lib.tapout_bandit_get_state.argtypes = [vp] * 5
@@ -254,6 +257,37 @@ class Tapout:
             _ptr(out.get("margin"), f32, (B, K), "margin"), _ptr(out.get("top1_id"), i32, (B, K), "top1_id"),
             _ptr(out.get("logq_tok"), f32, (B, K), "logq_tok") if (draft_tok is not None or u_draft is not None) else None,
             _ptr(out.get("sampled_tok"), i32, (B, K), "sampled_tok") if u_draft is not None else None,
+            _ptr(out.get("n_stop"), i32, (B,), "n_stop") if arm is not None else None,
+            _ptr(out.get("stop_fired"), torch.uint8, (B, K), "stop_fired") if arm is not None else None,
+            _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream)))
+        return out
+
+    # -- vocabulary shards -----------------------------------------------------
+    def shard_stats(self, shard, vocab_offset: int, length=None, rows_mode: int = 0, tok=None, out=None, stream=None):
+        """One 32-byte record per row of a vocabulary shard [B, KK, Vs]; returns an int32 tensor [B*KK, 8] (raw records)."""
+        B, KK, Vs = shard.shape
+        if out is None:
+            out = torch.zeros((B * KK, 8), dtype=torch.int32, device=self.device)
+        lg = _logits(shard, "shard")
+        self._check(self._lib.tapout_shard_stats(
+            self._ctx, C.byref(lg), B, KK, Vs, int(vocab_offset), _ptr(length, torch.int32, (B,), "len"), int(rows_mode),
+            _ptr(tok, torch.int32, (B, KK - rows_mode), "tok"), _ptr(out, torch.int32, (B * KK, 8), "out"), _stream(stream)))
+        return out
+
+    def draft_stats_sharded(self, stats, B: int, K: int, V: int, draft_tok=None, k_len=None, arm=None, out=None, stream=None):
+        """stats: int32 tensor [G, B*K, 8] of shard records.  Returns the dict tapout_draft_stats returns."""
+        G = stats.shape[0]
+        if out is None:
+            out = self.alloc_draft_outputs(B, K)
+        f32, i32 = torch.float32, torch.int32
+        self._check(self._lib.tapout_draft_stats_sharded(
+            self._ctx, _ptr(stats, i32, (G, B * K, 8), "stats"), G, B, K, V,
+            _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(k_len, i32, (B,), "k_len"),
+            _ptr(arm, i32, (B,) if self.positions == 1 else (B, self.positions), "arm"),
+            _ptr(out.get("lse"), f32, (B, K), "lse"), _ptr(out.get("entropy"), f32, (B, K), "entropy"),
+            _ptr(out.get("p_top1"), f32, (B, K), "p_top1"), _ptr(out.get("p_top2"), f32, (B, K), "p_top2"),
+            _ptr(out.get("margin"), f32, (B, K), "margin"), _ptr(out.get("top1_id"), i32, (B, K), "top1_id"),
+            _ptr(out.get("logq_tok"), f32, (B, K), "logq_tok") if draft_tok is not None else None,
             _ptr(out.get("n_stop"), i32, (B,), "n_stop") if arm is not None else None,
             _ptr(out.get("stop_fired"), torch.uint8, (B, K), "stop_fired") if arm is not None else None,
             _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream)))

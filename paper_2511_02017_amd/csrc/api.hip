@@ -387,6 +387,73 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft finalize launch");
 }
 
+tapout_status tapout_shard_stats(tapout_ctx *ctx, const tapout_logits *shard,
+                                 int32_t B, int32_t KK, int32_t Vs, int32_t vocab_offset,
+                                 const int32_t *len, int32_t rows_mode, const int32_t *tok,
+                                 tapout_shard_stat *out, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (rows_mode != 0 && rows_mode != 1) return fail(ctx, TAPOUT_EINVAL, "rows_mode must be 0 (draft rows) or 1 (target rows)");
+    if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (KK < 1 + rows_mode || KK > ctx->cfg.max_k + rows_mode) return fail(ctx, TAPOUT_EINVAL, "KK = %d outside [%d, %d]", KK, 1 + rows_mode, ctx->cfg.max_k + rows_mode);
+    if (Vs < 1 || Vs > ctx->cfg.vocab) return fail(ctx, TAPOUT_EINVAL, "Vs = %d outside [1, vocab = %d]", Vs, ctx->cfg.vocab);
+    if (vocab_offset < 0 || (int64_t)vocab_offset + Vs > INT32_MAX) return fail(ctx, TAPOUT_EINVAL, "vocab_offset out of range");
+    if (B == 0) return TAPOUT_OK;
+    char buf[128];
+    if (const char *m = check_logits(shard, "shard", Vs, KK, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
+    if (!out) return fail(ctx, TAPOUT_EINVAL, "out is NULL");
+    if (rows_mode == 1 && !len) return fail(ctx, TAPOUT_EINVAL, "rows_mode 1 needs len (n_draft)");
+    DeviceGuard guard(ctx->cfg.device);
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t rows = (int64_t)B * KK;
+    const int nsplit = choose_nsplit(ctx, rows, Vs, shard->dtype);
+    if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
+    RowReduceArgs r{shard->ptr, shard->stride_b, shard->stride_k, Vs, KK, nsplit, slice_vectors(Vs, shard->dtype, nsplit), (int32_t)rows, len, rows_mode, ctx->part};
+    // the draft pass also tracks the second maximum and the entropy sum; target rows need neither, but a record has one layout
+    hipError_t e = timed(ctx, rows_mode ? TAPOUT_PROFILE_TARGET_PASS : TAPOUT_PROFILE_DRAFT_PASS,
+                         [&](Timing tm) { return launch_row_reduce(r, shard->dtype, true, st, tm); });
+    if (e != hipSuccess) return hip_fail(ctx, e, "shard pass launch");
+    ShardMergeArgs m{shard->ptr, shard->dtype, shard->stride_b, shard->stride_k, B, KK, Vs, nsplit, vocab_offset, rows_mode,
+                     ctx->part, len, tok, (Partial *)out};
+    e = launch_shard_merge(m, st, Timing{});
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "shard merge launch");
+}
+
+tapout_status tapout_draft_stats_sharded(tapout_ctx *ctx, const tapout_shard_stat *stats, int32_t G,
+                                 int32_t B, int32_t K, int32_t V,
+                                 const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
+                                 int32_t *top1_id, float *logq_tok,
+                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (K < 1 || K > ctx->cfg.max_k) return fail(ctx, TAPOUT_EINVAL, "K = %d outside [1, max_k = %d]", K, ctx->cfg.max_k);
+    if (V < 1) return fail(ctx, TAPOUT_EINVAL, "V = %d must be positive", V);
+    if (G < 1 || G > kStageCap) return fail(ctx, TAPOUT_EINVAL, "G = %d outside [1, %d]", G, kStageCap);
+    if (B == 0) return TAPOUT_OK;
+    if (!stats) return fail(ctx, TAPOUT_EINVAL, "stats is NULL");
+    if (arm && !n_stop && !stop_fired) return fail(ctx, TAPOUT_EINVAL, "arm given but neither n_stop nor stop_fired");
+    DeviceGuard guard(ctx->cfg.device);
+    hipStream_t st = (hipStream_t)stream;
+    DraftFinalArgs f{};
+    f.base = nullptr; f.dtype = TAPOUT_F32;
+    f.B = B; f.K = K; f.V = V; f.nsplit = G; f.shards = G; f.part = (const Partial *)stats;
+    f.draft_tok = draft_tok; f.k_len = k_len; f.arm = arm;
+    f.arm_stride = ctx->positions > 1 ? ctx->cfg.max_k : 0;
+    f.n_arms = ctx->cfg.n_arms;
+    for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) { f.rule[a] = ctx->cfg.rule[a]; f.threshold[a] = ctx->cfg.threshold[a]; }
+    f.lse = lse; f.entropy = entropy; f.p_top1 = p_top1; f.p_top2 = p_top2; f.margin = margin; f.logq_tok = logq_tok;
+    f.top1_id = top1_id; f.n_stop = n_stop; f.stop_fired = stop_fired; f.flags = flags;
+    if (ctx->stateful) {
+        f.prev_entropy = ctx->prev_entropy; f.lambda = ctx->lambda; f.adaedl_gamma = ctx->cfg.adaedl_gamma;
+        f.round_entropy = ctx->round_entropy;
+        ctx->round_K = K;
+    }
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, [&](Timing tm) { return launch_draft_finalize(f, st, tm); });
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "sharded draft finalize launch");
+}
+
 tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const tapout_logits *draft,
                             int32_t B, int32_t K, int32_t V,
                             const float *draft_lse, const float *logq_tok,

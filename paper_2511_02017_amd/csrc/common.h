@@ -25,9 +25,10 @@ struct Partial {
     float T;         // draft rows only
     float v2;        // second largest value of the slice counting duplicates (draft rows only)
     int32_t cand;    // element index at which an 8- (bf16) / 4- (f32) element window holding the first maximum starts
-    int32_t pad[3];
+    int32_t pad[3];  // a record of a vocabulary shard (tapout_shard_stat, same layout) carries the bits of x_tok in pad[0]
 };
 static_assert(sizeof(Partial) == 32, "Partial is one 32-byte record");
+static_assert(sizeof(tapout_shard_stat) == sizeof(Partial), "shard records are staged and merged as partials");
 
 // Final-token job of one sequence, produced by the verify finaliser and
 // consumed by the residual sampler.
@@ -94,8 +95,21 @@ struct DraftFinalArgs {
     const double *lambda;         // [B, n_arms] AdaEDL thresholds
     double adaedl_gamma;
     float *round_entropy;         // [B, K] entropies of this draft, kept for the state update
+    // vocabulary-sharded input: part holds the records of `shards` vocabulary shards, shard-major [shards, B*K], instead
+    // of slice partials [B*K, nsplit] (then nsplit = shards; the argmax of a record is exact and global, the logit of
+    // the drafted token travels in the record, and base is not used)
+    int32_t shards;
 };
 hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st, Timing tm);
+
+// One record per live row of a vocabulary shard from its slice partials (see tapout_shard_stats).
+struct ShardMergeArgs {
+    const void *base; int32_t dtype; int64_t stride_b, stride_k;
+    int32_t B, KK, Vs, nsplit, vocab_offset, rows_mode;
+    const Partial *part; const int32_t *len, *tok;
+    Partial *out;
+};
+hipError_t launch_shard_merge(const ShardMergeArgs &a, hipStream_t st, Timing tm);
 
 // Verification + final token: the head kernel merges the target partials of each sequence, takes the
 // accept decisions and describes the final-token draw (SampleJob); the slice kernel sums the row pair
@@ -243,6 +257,19 @@ __device__ inline void stage_commit(Partial *sh, const StageRegs &r, int count)
     if (i < 2 * count) d[i] = r.w0;
     if (i + 256 < 2 * count) d[i + 256] = r.w1;
     __syncthreads();
+}
+
+// The same for records of vocabulary shards: src is shard-major [shards, rows_total]; the `count` = rows * shards
+// records of rows row0 .. land in LDS row-major ([row][shard]), where merge_partials expects the slices of a row.
+__device__ inline StageRegs stage_issue_shards(const Partial *src, int64_t rows_total, int64_t row0, int shards, int count)
+{
+    StageRegs r;
+    r.w0 = r.w1 = u32x4{0u, 0u, 0u, 0u};
+    const u32x4 *s = (const u32x4 *)src;
+    const int i = threadIdx.x;                                 // 16-byte word i of the LDS image: record i/2, half i%2
+    if (i < 2 * count) { const int rec = i >> 1; r.w0 = s[2 * ((int64_t)(rec % shards) * rows_total + row0 + rec / shards) + (i & 1)]; }
+    if (i + 256 < 2 * count) { const int rec = (i + 256) >> 1; r.w1 = s[2 * ((int64_t)(rec % shards) * rows_total + row0 + rec / shards) + (i & 1)]; }
+    return r;
 }
 
 // v[i] for a small array that lives in scalar registers (kernel arguments): selects instead of a load from

@@ -45,6 +45,7 @@ __device__ inline bool adaedl_fires(double g, double lambda, float H)
     return 1.0 - sqrt(g * (double)H) < lambda;
 }
 
+template <bool SHARDED>
 __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalArgs a)
 {
     __shared__ Partial sh_part[kStageCap];
@@ -66,13 +67,16 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     int32_t tok0 = -1;
     if (want_tok && (int)threadIdx.x < K) tok0 = a.draft_tok[(int64_t)b * K + threadIdx.x];
     const int count0 = min(K, rows_per_stage) * a.nsplit;
-    const StageRegs st0 = stage_issue(a.part + (int64_t)b * K * a.nsplit, count0);
+    StageRegs st0;
+    if constexpr (SHARDED) st0 = stage_issue_shards(a.part, (int64_t)a.B * K, (int64_t)b * K, a.nsplit, count0);
+    else st0 = stage_issue(a.part + (int64_t)b * K * a.nsplit, count0);
     asm volatile("" :: "v"(kb), "v"(arm), "v"(H_carry), "v"(tok0), "v"(st0.w0), "v"(st0.w1));
     // Second round trip: the logit of the drafted token (its address needs the token, not k_len: rows up to K
     // exist), in flight while the partials go through LDS and are merged.
     float xtok_first = 0.0f;
-    if (want_tok && (int)threadIdx.x < K && tok0 >= 0 && tok0 < a.V)
-        xtok_first = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, threadIdx.x), a.dtype, tok0);
+    if constexpr (!SHARDED)
+        if (want_tok && (int)threadIdx.x < K && tok0 >= 0 && tok0 < a.V)
+            xtok_first = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, threadIdx.x), a.dtype, tok0);
     stage_commit(sh_part, st0, count0);
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
     const bool arm_ok = arm >= 0 && arm < a.n_arms;
@@ -89,16 +93,24 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
         if (k0 > 0) {                                         // further stages (K > rows_per_stage): load late
             tok0 = (want_tok && kmine < k1) ? a.draft_tok[(int64_t)b * K + kmine] : -1;
             __syncthreads();
-            stage_partials(sh_part, a.part + ((int64_t)b * K + k0) * a.nsplit, (k1 - k0) * a.nsplit);
+            if constexpr (SHARDED) {
+                stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * K, (int64_t)b * K + k0, a.nsplit, (k1 - k0) * a.nsplit),
+                             (k1 - k0) * a.nsplit);
+            } else {
+                stage_partials(sh_part, a.part + ((int64_t)b * K + k0) * a.nsplit, (k1 - k0) * a.nsplit);
+            }
             xtok0 = 0.0f;
-            if (want_tok && kmine < k1 && tok0 >= 0 && tok0 < a.V)
-                xtok0 = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, kmine), a.dtype, tok0);
+            if constexpr (!SHARDED)
+                if (want_tok && kmine < k1 && tok0 >= 0 && tok0 < a.V)
+                    xtok0 = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, kmine), a.dtype, tok0);
         }
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t i = (int64_t)b * K + k;
-            const void *row = row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
+            const void *row = SHARDED ? nullptr : row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
             RowTotal r = merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
-            const int32_t top1 = a.top1_id ? resolve_argmax(row, a.dtype, a.V, r.cand, r.M) : 0;   // loads overlap the math below
+            int32_t top1 = 0;
+            if constexpr (SHARDED) top1 = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;             // a shard's argmax is exact and global
+            else top1 = a.top1_id ? resolve_argmax(row, a.dtype, a.V, r.cand, r.M) : 0;            // loads overlap the math below
             uint32_t f = 0;
             float lse, H, p1, p2, mg;
             double lse_d = NAN;
@@ -123,8 +135,15 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
             if (a.draft_tok && a.logq_tok) {
                 int32_t t = tok0;
                 float xt = xtok0;
-                if (k != kmine) {                              // more rows than threads: load late
-                    t = a.draft_tok[i];
+                if (k != kmine) t = a.draft_tok[i];            // more rows than threads: load late
+                if constexpr (SHARDED) {
+                    // the shard that owns the token sent its logit; the others sent NaN
+                    xt = NAN;
+                    for (int g = 0; g < a.nsplit; ++g) {
+                        const float v = __int_as_float(sh_part[(k - k0) * a.nsplit + g].pad[0]);
+                        if (v == v) xt = v;
+                    }
+                } else if (k != kmine) {
                     if (t >= 0 && t < a.V) xt = load_elem_rt(row, a.dtype, t);
                 }
                 if (t < 0 || t >= a.V) { f |= TAPOUT_FLAG_BAD_TOKEN; a.logq_tok[i] = NAN; }
@@ -177,11 +196,52 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     }
 }
 
+
+// ---- vocabulary shards -----------------------------------------------------------------------
+// One thread per row of the shard: merges the row's slice partials (a few dozen bytes, straight from memory)
+// into one record with the exact global argmax and, if this shard owns it, the logit of the drafted token.
+__global__ __launch_bounds__(kFinalBlock) void shard_merge_kernel(ShardMergeArgs a)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.B * a.KK) return;
+    const int b = i / a.KK, k = i - b * a.KK;
+    int n_live;
+    if (a.rows_mode == 0) {
+        n_live = a.len ? a.len[b] : a.KK;
+        n_live = n_live > a.KK ? a.KK : n_live;
+    } else {
+        const int n = a.len[b];
+        n_live = (n < 1 ? 1 : (n > a.KK - 1 ? a.KK - 1 : n)) + 1;
+    }
+    if (k >= n_live) return;
+    const void *row = row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
+    const RowTotal r = merge_partials(a.part + (int64_t)i * a.nsplit, a.nsplit);
+    Partial o;
+    o.v1 = r.M; o.S = (float)r.S; o.T = (float)r.T; o.v2 = r.v2;
+    o.cand = a.vocab_offset + resolve_argmax(row, a.dtype, a.Vs, r.cand, r.M);
+    float xt = NAN;
+    const int KT = a.KK - a.rows_mode;                       // tokens per sequence (the last target row has none)
+    if (a.tok && k < KT) {
+        const int t = a.tok[(int64_t)b * KT + k] - a.vocab_offset;
+        if (t >= 0 && t < a.Vs) xt = load_elem_rt(row, a.dtype, t);
+    }
+    o.pad[0] = __float_as_int(xt); o.pad[1] = o.pad[2] = 0;
+    a.out[i] = o;
+}
+
 }  // namespace
 
 hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st, Timing tm)
 {
-    launch_kernel(draft_finalize_kernel, dim3(a.B), dim3(kFinalBlock), st, tm, a);
+    if (a.shards > 0) launch_kernel(draft_finalize_kernel<true>, dim3(a.B), dim3(kFinalBlock), st, tm, a);
+    else launch_kernel(draft_finalize_kernel<false>, dim3(a.B), dim3(kFinalBlock), st, tm, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_shard_merge(const ShardMergeArgs &a, hipStream_t st, Timing tm)
+{
+    const int n = a.B * a.KK;
+    launch_kernel(shard_merge_kernel, dim3((n + kFinalBlock - 1) / kFinalBlock), dim3(kFinalBlock), st, tm, a);
     return hipGetLastError();
 }
 

@@ -51,7 +51,8 @@ def assert_stats_close(name, gpu, ref, mask=None, tau=TAU):
     floor = 1.0 if name in LOG_KEYS else (0.1 if name in ("entropy", "margin") else 1e-3)
     both_nan = np.isnan(gpu) & np.isnan(ref)
     same_inf = np.isinf(ref) & (gpu == ref)
-    err = np.abs(gpu - ref)
+    with np.errstate(invalid="ignore"):
+        err = np.abs(gpu - ref)                              # inf - inf: covered by same_inf
     scale = np.maximum(np.abs(ref), floor)
     bad = ~both_nan & ~same_inf & ~(err <= tau * scale)
     assert not bad.any(), (f"{name}: {bad.sum()} of {bad.size} outside tolerance; worst "

@@ -612,6 +612,71 @@ def test_draft_token_sampling_law_edges_and_bad_rows():
         tp.draft_stats(x.to(DEV), draft_tok=torch.zeros(3, 2, dtype=torch.int32, device=DEV), u_draft=u.to(DEV))
 
 
+# ---- vocabulary-sharded entry points --------------------------------------------------------------
+
+@pytest.mark.parametrize("name,G", [("small", 4), ("ragged", 3), ("llama3", 8)])
+def test_vocabulary_sharded_draft_stats_match_oracle(name, G):
+    """Each "GPU" reduces its column slice of every row to one 32-byte record; the merged records must give what the
+    oracle computes on the unsplit rows (signals, argmax, log q(tok), stop position)."""
+    w = synth.WORKLOADS[name]
+    w = {"small": synth.scaled(w, B=8), "ragged": synth.scaled(w, B=6, V=70001), "llama3": synth.scaled(w, B=4)}[name]
+    rnd = synth.RoundGenerator(w, DEV).round(1)
+    B, K, V = w.B, w.K, w.V
+    tp = binding.Tapout(B, K, V)
+    edges = [round(g * V / G) for g in range(G + 1)]
+    if name == "ragged":
+        edges[1] += 3                                                      # shards of unequal, odd sizes
+    recs = []
+    for g in range(G):
+        sl = rnd["draft"][:, :, edges[g]:edges[g + 1]]                    # a strided view: rows keep the full-row stride
+        recs.append(tp.shard_stats(sl, edges[g], length=rnd["k_len"], rows_mode=0, tok=rnd["draft_tok"]).clone())
+    stats = torch.stack(recs)
+    arm = (torch.arange(B, dtype=torch.int32) % 3).to(DEV)
+    gds = tp.draft_stats_sharded(stats, B, K, V, draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arm)
+    ods, _, _ = pu.oracle_round(rnd, arm=arm)
+    k_len = rnd["k_len"].cpu().numpy()
+    live = np.arange(K)[None, :] < k_len[:, None]
+    for key in pu.STAT_KEYS:
+        pu.assert_stats_close(key, gds[key].cpu().numpy(), ods[key], live)
+    assert (gds["top1_id"].cpu().numpy()[live] == ods["top1_id"][live]).all()
+    near = ((ods["stop_margin"] <= pu.TAU) & live).any(1)
+    assert near.sum() <= 1
+    assert (gds["n_stop"].cpu().numpy()[~near] == ods["n_stop"][~near]).all()
+    assert (gds["flags"].cpu().numpy().astype(np.uint32) == ods["flags"]).all()
+    # and the unsplit library call agrees with the sharded one to rounding
+    one = tp.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arm)
+    for key in pu.STAT_KEYS:
+        pu.assert_stats_close(key, gds[key].cpu().numpy(), one[key].cpu().numpy(), live, tau=2e-6)
+
+
+def test_vocabulary_shard_records_edge_cases():
+    B, K, V, G = 2, 2, 4000, 4
+    x = torch.randn(B, K, V) * 2
+    x[0, 0, 1000:2000] = float("-inf")                                    # a fully masked shard
+    x[0, 1, :] = 3.0                                                      # all equal: argmax 0, second = max
+    x[1, 0, 2500] = float("nan")                                          # NaN in one shard poisons the row
+    x[1, 1, 3999] = 50.0                                                  # maximum in the last column of the last shard
+    tok = torch.tensor([[1500, 3999], [10, 3999]], dtype=torch.int32)
+    tp = binding.Tapout(B, K, V)
+    xd = x.to(DEV)
+    recs = torch.stack([tp.shard_stats(xd[:, :, g * 1000:(g + 1) * 1000], g * 1000, tok=tok.to(DEV)).clone() for g in range(G)])
+    r = recs.cpu().view(G, B, K, 8)
+    assert r[1, 0, 0, 0].view(torch.float32) == float("-inf") and r[1, 0, 0, 1].view(torch.float32) == 0.0
+    assert not torch.isnan(r[1, 0, 0, 5].view(torch.float32))             # the masked shard still owns token 1500 (its logit is -inf)
+    assert torch.isnan(r[0, 0, 0, 5].view(torch.float32))                 # shard 0 does not
+    o = tp.draft_stats_sharded(recs, B, K, V, draft_tok=tok.to(DEV))
+    ods = orc.draft_stats(x.numpy(), draft_tok=tok.numpy())
+    live = np.ones((B, K), bool)
+    for key in pu.STAT_KEYS:
+        pu.assert_stats_close(key, o[key].cpu().numpy(), ods[key], live)
+    assert o["top1_id"].cpu().tolist() == ods["top1_id"].tolist() and o["top1_id"][1, 1] == 3999 and o["top1_id"][0, 1] == 0
+    assert (o["flags"].cpu().numpy().astype(np.uint32) == ods["flags"]).all() and o["flags"][1] == binding.FLAG_BAD_ROW
+    with pytest.raises(binding.TapoutError):
+        tp.shard_stats(xd[:, :, :1000], -1)
+    with pytest.raises(binding.TapoutError):
+        tp.shard_stats(torch.zeros(B, 1, 10, device=DEV), 0, rows_mode=1)
+
+
 # ---- boundary error handling --------------------------------------------------------
 
 def test_argument_errors_leave_outputs_untouched():

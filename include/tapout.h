@@ -321,6 +321,25 @@ TAPOUT_API tapout_status tapout_draft_stats_sharded(tapout_ctx *ctx, const tapou
                                  int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream);
 
 /*
+ * Acceptance step of tapout_verify from shard records of the target rows
+ * (tapout_shard_stats with rows_mode = 1, tok = draft_tok, len = n_draft,
+ * exchanged as for the draft side).  Writes what tapout_verify writes, except
+ * the final token of a sampled sequence: its draw needs the exact normalisers
+ * of one row pair over the whole vocabulary, a second, smaller exchange that
+ * this library does not do yet; out_tok[b, accept_len[b]] is -1 for such a
+ * sequence (greedy and flagged sequences get their token, the argmax of the
+ * merged records).
+ * stats     [G, B * (K + 1)] records, shard-major; V the whole vocabulary
+ */
+TAPOUT_API tapout_status tapout_verify_accept_sharded(tapout_ctx *ctx, const tapout_shard_stat *stats, int32_t G,
+                                 int32_t B, int32_t K, int32_t V,
+                                 const float *logq_tok, const int32_t *draft_tok, const int32_t *n_draft,
+                                 const uint8_t *greedy, const float *u_accept,
+                                 int32_t *accept_len, int32_t *out_tok, int32_t *n_out,
+                                 float *target_lse, float *logp_tok, int32_t *target_top1,
+                                 uint32_t *flags, void *stream);
+
+/*
  * Bandit update after verification (Algorithm 1 line 12; Section 3.2):
  *   r = alpha * m / gamma + (1 - alpha) * m / n,  m = accept_len, n = n_draft,
  *   evaluated in double as (alpha*m)/gamma + ((1-alpha)*m)/n without fused

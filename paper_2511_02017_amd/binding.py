@@ -27,7 +27,7 @@ STATUS = {0: "TAPOUT_OK", 1: "TAPOUT_EINVAL", 2: "TAPOUT_EUNSUPPORTED", 3: "TAPO
 EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_last_error",
            "tapout_bandit_select", "tapout_draft_stats", "tapout_verify", "tapout_bandit_update",
            "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_rule_state_get", "tapout_rule_state_set",
-           "tapout_shard_stats", "tapout_draft_stats_sharded",
+           "tapout_shard_stats", "tapout_draft_stats_sharded", "tapout_verify_accept_sharded",
            "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
@@ -75,6 +75,7 @@ def load_library():
         lib.tapout_draft_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 16
         lib.tapout_shard_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32, i32, vp, i32, vp, vp, vp]
         lib.tapout_draft_stats_sharded.argtypes = [vp, vp, i32, i32, i32, i32] + [vp] * 14
+        lib.tapout_verify_accept_sharded.argtypes = [vp, vp, i32, i32, i32, i32] + [vp] * 13
         lib.tapout_verify.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 15
         lib.tapout_bandit_update.argtypes = [vp, i32] + [vp] * 6
         lib.tapout_bandit_get_state.argtypes = [vp] * 5
@@ -290,6 +291,25 @@ class Tapout:
             _ptr(out.get("logq_tok"), f32, (B, K), "logq_tok") if draft_tok is not None else None,
             _ptr(out.get("n_stop"), i32, (B,), "n_stop") if arm is not None else None,
             _ptr(out.get("stop_fired"), torch.uint8, (B, K), "stop_fired") if arm is not None else None,
+            _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream)))
+        return out
+
+    def verify_accept_sharded(self, stats, B: int, K: int, V: int, logq_tok, draft_tok, n_draft, u_accept, greedy=None,
+                              out=None, stream=None):
+        """stats: int32 tensor [G, B*(K+1), 8] of target-row shard records.  Fills the dict tapout_verify fills; the final
+        token of a sampled sequence is left at -1."""
+        G = stats.shape[0]
+        if out is None:
+            out = self.alloc_verify_outputs(B, K)
+        f32, i32 = torch.float32, torch.int32
+        self._check(self._lib.tapout_verify_accept_sharded(
+            self._ctx, _ptr(stats, i32, (G, B * (K + 1), 8), "stats"), G, B, K, V,
+            _ptr(logq_tok, f32, (B, K), "logq_tok"), _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(n_draft, i32, (B,), "n_draft"),
+            _ptr(greedy, torch.uint8, (B,), "greedy"), _ptr(u_accept, f32, (B, K), "u_accept"),
+            _ptr(out["accept_len"], i32, (B,), "accept_len"), _ptr(out["out_tok"], i32, (B, K + 1), "out_tok"),
+            _ptr(out["n_out"], i32, (B,), "n_out"),
+            _ptr(out.get("target_lse"), f32, (B, K + 1), "target_lse"), _ptr(out.get("logp_tok"), f32, (B, K), "logp_tok"),
+            _ptr(out.get("target_top1"), i32, (B, K + 1), "target_top1"),
             _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream)))
         return out
 

@@ -454,6 +454,34 @@ tapout_status tapout_draft_stats_sharded(tapout_ctx *ctx, const tapout_shard_sta
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "sharded draft finalize launch");
 }
 
+tapout_status tapout_verify_accept_sharded(tapout_ctx *ctx, const tapout_shard_stat *stats, int32_t G,
+                                 int32_t B, int32_t K, int32_t V,
+                                 const float *logq_tok, const int32_t *draft_tok, const int32_t *n_draft,
+                                 const uint8_t *greedy, const float *u_accept,
+                                 int32_t *accept_len, int32_t *out_tok, int32_t *n_out,
+                                 float *target_lse, float *logp_tok, int32_t *target_top1,
+                                 uint32_t *flags, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (K < 1 || K > ctx->cfg.max_k) return fail(ctx, TAPOUT_EINVAL, "K = %d outside [1, max_k = %d]", K, ctx->cfg.max_k);
+    if (V < 1) return fail(ctx, TAPOUT_EINVAL, "V = %d must be positive", V);
+    if (G < 1 || G > kStageCap) return fail(ctx, TAPOUT_EINVAL, "G = %d outside [1, %d]", G, kStageCap);
+    if (B == 0) return TAPOUT_OK;
+    if (!stats || !logq_tok || !draft_tok || !n_draft || !u_accept) return fail(ctx, TAPOUT_EINVAL, "stats, logq_tok, draft_tok, n_draft and u_accept are required");
+    if (!accept_len || !out_tok || !n_out) return fail(ctx, TAPOUT_EINVAL, "accept_len, out_tok and n_out are required");
+    DeviceGuard guard(ctx->cfg.device);
+    hipStream_t st = (hipStream_t)stream;
+    VerifyArgs va{};
+    va.B = B; va.K = K; va.V = V; va.nsplit = G; va.shards = G; va.jps = 1; va.n_jobs = B;
+    va.part = (const Partial *)stats;
+    va.logq_tok = logq_tok; va.draft_tok = draft_tok; va.n_draft = n_draft; va.greedy = greedy; va.u_accept = u_accept;
+    va.accept_len = accept_len; va.out_tok = out_tok; va.n_out = n_out;
+    va.target_lse = target_lse; va.logp_tok = logp_tok; va.target_top1 = target_top1; va.flags = flags;
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD, [&](Timing tm) { return launch_verify(va, 0, st, tm); });
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "sharded verify head launch");
+}
+
 tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const tapout_logits *draft,
                             int32_t B, int32_t K, int32_t V,
                             const float *draft_lse, const float *logq_tok,

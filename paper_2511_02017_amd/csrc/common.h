@@ -124,6 +124,7 @@ struct VerifyArgs {
     // jobs, part1, part2 and u_sample are indexed by job; the rows of a job are rows job.row of its sequence.
     int32_t jps, n_jobs;
     int32_t *tok_direct;          // draft-token sampling: token of job j goes to tok_direct[j] instead of out_tok
+    int32_t shards;               // > 0: part holds records of vocabulary shards, shard-major [shards, B*(K+1)] (head kernel only)
     const Partial *part;
     const float *draft_lse, *logq_tok; const int32_t *draft_tok, *n_draft; const uint8_t *greedy;
     const float *u_accept, *u_sample;

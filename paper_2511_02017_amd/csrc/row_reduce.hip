@@ -172,10 +172,10 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
     const int row = b * a.KK + k;
     const int tid = threadIdx.x;
     int n_active;                                   // rows of sequence b this pass reads
-    if constexpr (FULL) {
+    if (a.len_mode == 0) {                          // draft rows: k < k_len[b]
         n_active = a.len ? a.len[b] : a.KK;
         n_active = n_active > a.KK ? a.KK : (n_active < 0 ? 0 : n_active);
-    } else {
+    } else {                                        // target rows: k <= n_draft[b]
         int n = a.len[b];
         n_active = (n < 1 ? 1 : (n > a.KK - 1 ? a.KK - 1 : n)) + 1;
     }

@@ -134,6 +134,7 @@ __device__ inline void load8(const char *rowp, bool aligned, int j, int V, float
 // Called by all threads of a workgroup.  Returns the sequence's job (identical in every
 // workgroup of the sequence); with `writer` also writes the sequence's outputs.
 // Accept decisions exist for rows k < n <= K <= kScanCap, so the LDS byte buffer always holds them.
+template <bool SHARDED>
 __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                                         Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast, double *sh_lse)
 {
@@ -150,7 +151,12 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         u0 = a.u_accept[i];
         lq0 = a.logq_tok[i];
     }
-    stage_partials(sh_part, a.part + (int64_t)b * (K + 1) * a.nsplit, min(K + 1, rows_per_stage) * a.nsplit);
+    if constexpr (SHARDED) {
+        const int c0 = min(K + 1, rows_per_stage) * a.nsplit;
+        stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1), a.nsplit, c0), c0);
+    } else {
+        stage_partials(sh_part, a.part + (int64_t)b * (K + 1) * a.nsplit, min(K + 1, rows_per_stage) * a.nsplit);
+    }
     int n = a.n_draft[b];
     uint32_t f0 = 0;
     if (n < 1 || n > K) { f0 |= TAPOUT_FLAG_BAD_NDRAFT; n = n < 1 ? 1 : K; }
@@ -171,15 +177,23 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 tok0 = a.draft_tok[i]; u0 = a.u_accept[i]; lq0 = a.logq_tok[i];
             }
             __syncthreads();
-            stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + k0) * a.nsplit, (k1 - k0) * a.nsplit);
+            if constexpr (SHARDED) {
+                const int c1 = (k1 - k0) * a.nsplit;
+                stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1) + k0, a.nsplit, c1), c1);
+            } else {
+                stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + k0) * a.nsplit, (k1 - k0) * a.nsplit);
+            }
         }
-        if (kmine < k1 && kmine < n && tok0 >= 0 && tok0 < a.V)
-            xtok0 = load_elem_rt(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, kmine), a.t_dtype, tok0);
+        if constexpr (!SHARDED)
+            if (kmine < k1 && kmine < n && tok0 >= 0 && tok0 < a.V)
+                xtok0 = load_elem_rt(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, kmine), a.t_dtype, tok0);
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t it = (int64_t)b * (K + 1) + k;
-            const void *row = row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, k);
+            const void *row = SHARDED ? nullptr : row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, k);
             RowTotal r = merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
-            const int32_t top1 = need_top1 ? resolve_argmax(row, a.t_dtype, a.V, r.cand, r.M) : 0;   // loads overlap the math below
+            int32_t top1 = 0;
+            if constexpr (SHARDED) top1 = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;                // a shard's argmax is exact and global
+            else top1 = need_top1 ? resolve_argmax(row, a.t_dtype, a.V, r.cand, r.M) : 0;             // loads overlap the math below
             uint32_t f = 0;
             double lse_d = NAN;
             if (r.bad) f |= TAPOUT_FLAG_BAD_ROW;
@@ -194,7 +208,15 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 float xt = xtok0, u = u0, lq = lq0;
                 if (k != kmine) {                              // more rows than threads: load late
                     t = a.draft_tok[i]; u = a.u_accept[i]; lq = a.logq_tok[i];
-                    if (t >= 0 && t < a.V) xt = load_elem_rt(row, a.t_dtype, t);
+                    if constexpr (!SHARDED)
+                        if (t >= 0 && t < a.V) xt = load_elem_rt(row, a.t_dtype, t);
+                }
+                if constexpr (SHARDED) {                       // the shard that owns the token sent its logit, the others NaN
+                    xt = NAN;
+                    for (int g = 0; g < a.nsplit; ++g) {
+                        const float v = __int_as_float(sh_part[(k - k0) * a.nsplit + g].pad[0]);
+                        if (v == v) xt = v;
+                    }
                 }
                 bool acc = false;
                 float lp = NAN;
@@ -234,17 +256,19 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         Mm = __int_as_float(sh_bcast[5]); top1m = sh_bcast[6]; lse_m = *sh_lse;
     } else {                                     // more rows than threads: merge row m once more
         __syncthreads();
-        stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + m) * a.nsplit, a.nsplit);
+        if constexpr (SHARDED) stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1) + m, a.nsplit, a.nsplit), a.nsplit);
+        else stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + m) * a.nsplit, a.nsplit);
         RowTotal r = merge_partials(sh_part, a.nsplit);
         Mm = r.M;
         lse_m = (r.R + log2(r.S)) * kLn2;
-        top1m = need_top1 ? resolve_argmax(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, m), a.t_dtype, a.V, r.cand, r.M) : 0;
+        if constexpr (SHARDED) top1m = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;
+        else top1m = need_top1 ? resolve_argmax(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, m), a.t_dtype, a.V, r.cand, r.M) : 0;
     }
     if (!flagged && !greedy) {
         job.kind = m < n ? 1 : 2;
         job.row = m;
         job.ref_p = Mm;                          // exponent references: the target row's maximum, the draft row's lse
-        job.ref_q = m < n ? a.draft_lse[(int64_t)b * K + m] : 0.0f;
+        job.ref_q = (m < n && a.draft_lse) ? a.draft_lse[(int64_t)b * K + m] : 0.0f;
         // binary32-grade estimate of S_p / S_q in these references (S_q = sum exp(d - lse_q) = 1): lets the
         // slice pass form the residual before the exact normalisers exist
         job.lam = exp(lse_m - (double)Mm);
@@ -254,9 +278,11 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         if (threadIdx.x == 0) {
             a.accept_len[b] = m;
             a.n_out[b] = m + 1;
-            a.jobs[b].job = job;
-            a.jobs[b].band_cnt = 0;                  // the slice kernel appends to the sequence's band list
-            a.flags_ws[b] = f;
+            if constexpr (!SHARDED) {
+                a.jobs[b].job = job;
+                a.jobs[b].band_cnt = 0;              // the slice kernel appends to the sequence's band list
+                a.flags_ws[b] = f;
+            }
             if (a.flags) a.flags[b] = f;
         }
         int32_t *o = a.out_tok + (int64_t)b * (K + 1);
@@ -285,6 +311,7 @@ __device__ inline Rows job_rows(const VerifyArgs &a, int b, const SampleJob &job
 }
 
 // ---- head kernel: one workgroup per sequence ------------------------------------------
+template <bool SHARDED>
 __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
 {
     __shared__ Partial sh_part[kStageCap];
@@ -292,7 +319,7 @@ __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
     __shared__ uint32_t sh_flags;
     __shared__ int32_t sh_bcast[8];
     __shared__ double sh_lse;
-    verify_head(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse);
+    verify_head<SHARDED>(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse);
 }
 
 // ---- slice kernel -----------------------------------------------------------------------
@@ -743,7 +770,8 @@ hipError_t launch_sample_head(const VerifyArgs &a, hipStream_t st, Timing tm)
 hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {
     if (pass == 0) {
-        launch_kernel(verify_head_kernel, dim3(a.B), dim3(kVBlock), st, tm, a);
+        if (a.shards > 0) launch_kernel(verify_head_kernel<true>, dim3(a.B), dim3(kVBlock), st, tm, a);
+        else launch_kernel(verify_head_kernel<false>, dim3(a.B), dim3(kVBlock), st, tm, a);
         return hipGetLastError();
     }
     if (a.t_dtype == TAPOUT_F32)

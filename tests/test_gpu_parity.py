@@ -649,6 +649,45 @@ def test_vocabulary_sharded_draft_stats_match_oracle(name, G):
         pu.assert_stats_close(key, gds[key].cpu().numpy(), one[key].cpu().numpy(), live, tau=2e-6)
 
 
+@pytest.mark.parametrize("name,G", [("small", 4), ("ragged", 3)])
+def test_vocabulary_sharded_accept_step_matches_oracle(name, G):
+    """Target rows through shard records: log p(tok), accept decisions, accepted prefix, greedy final tokens."""
+    w = synth.WORKLOADS[name]
+    w = synth.scaled(w, B=8) if name == "small" else synth.scaled(w, B=8, V=70001)
+    rnd = synth.RoundGenerator(w, DEV).round(2)
+    B, K, V = w.B, w.K, w.V
+    tp = binding.Tapout(B, K, V)
+    ods, ovf, nd = pu.oracle_round(rnd)                                   # full-K: n_draft = k_len
+    n_draft = rnd["k_len"]
+    edges = [round(g * V / G) for g in range(G + 1)]
+    recs = torch.stack([tp.shard_stats(rnd["target"][:, :, edges[g]:edges[g + 1]], edges[g], length=n_draft, rows_mode=1,
+                                       tok=rnd["draft_tok"]).clone() for g in range(G)])
+    gds = tp.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"])
+    gvf = tp.verify_accept_sharded(recs, B, K, V, gds["logq_tok"], rnd["draft_tok"], n_draft, rnd["u_accept"], greedy=rnd["greedy"])
+    used = np.arange(K)[None, :] < nd[:, None]
+    near = ((ovf["accept_margin"] <= pu.TAU) & used).any(1)
+    assert near.sum() <= 1
+    ok = ~near
+    g_len = gvf["accept_len"].cpu().numpy()
+    assert (g_len[ok] == ovf["accept_len"][ok]).all()
+    rows = np.arange(K + 1)[None, :] <= nd[:, None]
+    pu.assert_stats_close("target_lse", gvf["target_lse"].cpu().numpy(), ovf["target_lse"], rows)
+    pu.assert_stats_close("logp_tok", gvf["logp_tok"].cpu().numpy(), ovf["logp_tok"], used)
+    assert (gvf["target_top1"].cpu().numpy()[rows] == ovf["target_top1"][rows]).all()
+    g_out = gvf["out_tok"].cpu().numpy()
+    greedy = rnd["greedy"].cpu().numpy().astype(bool)
+    for b in np.nonzero(ok)[0]:
+        m = ovf["accept_len"][b]
+        assert (g_out[b, :m] == ovf["out_tok"][b, :m]).all()
+        assert g_out[b, m] == (ovf["out_tok"][b, m] if greedy[b] else -1)       # sampled sequences: final token not drawn here
+        assert (g_out[b, m + 1:] == -1).all()
+    assert (gvf["n_out"].cpu().numpy()[ok] == ovf["n_out"][ok]).all()
+    # the unsplit call takes the same decisions
+    one = tp.verify(rnd["target"], rnd["draft"], gds["lse"], gds["logq_tok"], rnd["draft_tok"], n_draft, rnd["u_accept"],
+                    rnd["u_sample"], greedy=rnd["greedy"])
+    assert (one["accept_len"].cpu().numpy()[ok] == g_len[ok]).all()
+
+
 def test_vocabulary_shard_records_edge_cases():
     B, K, V, G = 2, 2, 4000, 4
     x = torch.randn(B, K, V) * 2

@@ -227,6 +227,72 @@ def test_residual_with_a_few_tokens_where_p_equals_q():
     assert (vf["accept_len"].cpu() == 0).sum() >= B - c["accept_flagged"] - 1
 
 
+def random_round(B, K, V, dtype, seed, sigma=2.5, k_len=None):
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    d = (torch.randn(B, K, V, generator=g, device=DEV) * sigma).to(dtype)
+    t = torch.cat([d.float() + torch.randn(B, K, V, generator=g, device=DEV), torch.randn(B, 1, V, generator=g, device=DEV) * sigma], 1).to(dtype)
+    gum = -torch.log(-torch.log(torch.rand(B, K, V, generator=g, device=DEV).clamp_min(1e-20)))
+    tok = (d.float() + gum).argmax(-1).to(torch.int32)
+    kl = torch.full((B,), K, dtype=torch.int32, device=DEV) if k_len is None else torch.tensor(k_len, dtype=torch.int32, device=DEV)
+    return dict(draft=d, target=t, draft_tok=tok, u_accept=torch.rand(B, K, generator=g, device=DEV),
+                u_sample=torch.rand(B, generator=g, device=DEV), k_len=kl, greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
+
+
+@pytest.mark.parametrize("K,V,dtype", [(300, 600, torch.float32), (700, 20000, torch.bfloat16), (4096, 50, torch.bfloat16)])
+def test_long_drafts(K, V, dtype):
+    """More draft positions than a workgroup has threads, and more rows than one LDS stage of partials holds: the
+    per-sequence kernels walk them in stages.  K = 4096 is the largest K a context accepts."""
+    B = 2 if K < 4096 else 1
+    rnd = random_round(B, K, V, dtype, seed=K, sigma=1.0, k_len=[K, K - 37][:B])
+    tp = binding.Tapout(B, K, V)
+    arm = torch.tensor([1, 2][:B], dtype=torch.int32, device=DEV)
+    c = pu.check_round(tp, rnd)                                          # full K: accept decisions far into the draft
+    assert c["accept_flagged"] + c["icdf_flagged"] <= 1
+    c = pu.check_round(tp, rnd, arm=arm)                                 # stop scan over K positions
+    assert c["stop_flagged"] <= 1
+    # a draft that equals the target is accepted to the end: accept_len = n_draft, bonus token from the last target row
+    same = dict(rnd); same["target"] = torch.cat([rnd["draft"], rnd["target"][:, K:]], 1).contiguous()
+    ds, vf, nd = pu.gpu_round(tp, same)
+    assert torch.equal(vf["accept_len"], same["k_len"]) and torch.equal(vf["n_out"], same["k_len"] + 1)
+    pu.check_round(tp, same)
+    # the five-arm pool with carried state and token-level arms over a long draft
+    tp5 = binding.Tapout(B, K, V, rules=FIVE_RULES, thresholds=FIVE_THRESHOLDS, token_level=True)
+    arms = ((torch.arange(B)[:, None] * 3 + torch.arange(K)[None, :]) % 5).to(torch.int32).to(DEV)
+    tp5.rule_state_set(prev_entropy=[1.0, float("nan")][:B] if B > 1 else [1.0])
+    gds = tp5.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arms)
+    st = orc.RuleState(B, FIVE_RULES, FIVE_THRESHOLDS)
+    st.prev_entropy[:] = [1.0, np.nan][:B]
+    ods = orc.draft_stats(pu.host_logits(rnd["draft"]), draft_tok=rnd["draft_tok"].cpu().numpy(), k_len=rnd["k_len"].cpu().numpy(),
+                          arm=arms.cpu().numpy(), rules=FIVE_RULES, thresholds=FIVE_THRESHOLDS, prev_entropy=st.prev_entropy, lam=st.lam,
+                          token_level=True, nthreads=16)
+    live = np.arange(K)[None, :] < rnd["k_len"].cpu().numpy()[:, None]
+    near = (ods["stop_margin"] <= pu.TAU) & live
+    assert near.sum() <= 2
+    assert (gds["stop_fired"].cpu().numpy()[live & ~near] == ods["stop_fired"][live & ~near]).all()
+    ok = ~near.any(1)
+    assert (gds["n_stop"].cpu().numpy()[ok] == ods["n_stop"][ok]).all()
+
+
+def test_vocabulary_beyond_256_final_token_slices():
+    """V = 600001 gives 293 slices of the final-token passes: more than the locate kernel's workgroup scan covers."""
+    B, K, V = 3, 2, 600001
+    rnd = random_round(B, K, V, torch.float32, seed=5, sigma=3.0)
+    rnd["u_accept"][:] = 1.0 - 2.0 ** -24                                 # reject at once: residual draws ...
+    rnd["u_accept"][2] = 0.0                                              # ... and one bonus-token draw from the last row
+    rnd["u_sample"][:] = torch.tensor([0.0001, 0.9999, 0.5], device=DEV)
+    tp = binding.Tapout(B, K, V)
+    c = pu.check_round(tp, rnd)
+    assert c["icdf_flagged"] <= 1
+    ds, vf, _ = pu.gpu_round(tp, rnd)
+    assert vf["accept_len"].cpu().tolist()[2] == K
+    # draft-token sampling walks the same kernels with one job per row
+    u = torch.rand(B, K, generator=torch.Generator().manual_seed(3))
+    o = tp.draft_stats(rnd["draft"], u_draft=u.to(DEV))
+    osm = orc.draft_sample(pu.host_logits(rnd["draft"]), u.numpy(), nthreads=16)
+    near = osm["icdf_margin"] <= pu.TAU_S
+    assert (o["sampled_tok"].cpu().numpy()[~near] == osm["tok"][~near]).all()
+
+
 def test_bad_inputs_set_flags_and_fall_back():
     rnd = degenerate_round(torch.float32)
     B, K, V = rnd["draft"].shape

@@ -42,7 +42,12 @@ def test_create_rejects_bad_config_on_the_host():
                          (lambda c: setattr(c, "max_batch", 0), "positive"),
                          (lambda c: setattr(c, "alpha", 1.5), "alpha"),
                          (lambda c: setattr(c, "n_bandits", 3), "n_bandits"),
-                         (lambda c: setattr(c, "policy", 9), "policy")):
+                         (lambda c: setattr(c, "policy", 9), "policy"),
+                         (lambda c: setattr(c, "reward", 2), "reward"),
+                         (lambda c: setattr(c, "granularity", 2), "granularity"),
+                         (lambda c: c.rule.__setitem__(1, 5), "rule"),
+                         (lambda c: (c.rule.__setitem__(0, binding.RULE_ADAEDL), setattr(c, "adaedl_beta1", 1.5)), "adaedl_beta1"),
+                         (lambda c: setattr(c, "max_k", 5000), "max_k")):
         cfg = binding.default_config(4, 8, 1000)
         mutate(cfg)
         st = lib.tapout_create(ctypes.byref(ctx), ctypes.byref(cfg))

@@ -75,7 +75,7 @@ def main():
     if args.arms == "five":
         rules, thresholds = (0, 1, 2, 3, 4), (0.6, 0.8, 0.2, 0.2, 0.4)
     n_arms = len(rules)
-    tp = binding.Tapout(w.B, w.K, w.V, policy=policy, rules=rules, thresholds=thresholds)
+    tp = binding.Tapout(w.B, w.K, w.V, policy=policy, rules=rules, thresholds=thresholds, draft_sampling=args.sample_draft)
     for o in args.opt:
         k, v = o.split("=")
         tp.set_option(k, int(v))

@@ -129,6 +129,10 @@ typedef struct {
     double adaedl_beta2;                  /* smoothing of lambda (0.9)                          */
     double adaedl_eps;                    /* step of lambda (0.01)                              */
     double adaedl_rate0;                  /* initial smoothed acceptance rate (= adaedl_alpha)  */
+    int32_t draft_sampling;               /* 1: tapout_draft_stats may draw the draft tokens    */
+                                          /* (u_draft); sizes the final-token scratch for one   */
+                                          /* job per draft row instead of one per sequence      */
+    int32_t reserved;                     /* 0                                                  */
 } tapout_config;
 
 typedef struct {
@@ -203,7 +207,8 @@ TAPOUT_API tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const 
  * of softmax(row) at u_draft[b,k] with the conventions of the final token of
  * tapout_verify (smallest j whose inclusive prefix sum exceeds u * total, in
  * double), written to sampled_tok, and logq_tok refers to it.  A bad row gets
- * token -1 (BAD_ROW and BAD_TOKEN are both flagged).
+ * token -1 (BAD_ROW and BAD_TOKEN are both flagged).  Needs a context created
+ * with tapout_config.draft_sampling = 1.
  *
  * draft_tok [B,K] i32 or NULL (then logq_tok is not written, unless u_draft is
  *           given); draft_tok and u_draft exclude each other

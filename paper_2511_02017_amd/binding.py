@@ -41,7 +41,8 @@ class TapoutConfig(C.Structure):
                 ("policy", C.c_int32), ("n_bandits", C.c_int32), ("alpha", C.c_double),
                 ("reward", C.c_int32), ("granularity", C.c_int32),
                 ("adaedl_gamma", C.c_double), ("adaedl_alpha", C.c_double), ("adaedl_beta1", C.c_double),
-                ("adaedl_beta2", C.c_double), ("adaedl_eps", C.c_double), ("adaedl_rate0", C.c_double)]
+                ("adaedl_beta2", C.c_double), ("adaedl_eps", C.c_double), ("adaedl_rate0", C.c_double),
+                ("draft_sampling", C.c_int32), ("reserved", C.c_int32)]
 
 
 class TapoutLogits(C.Structure):
@@ -134,7 +135,7 @@ class Tapout:
     def __init__(self, max_batch: int, max_k: int, vocab: int, *, device: int = 0, policy: int = UCB1,
                  rules=(RULE_SVIP, RULE_MAXCONF, RULE_MARGIN), thresholds=(0.6, 0.8, 0.2),
                  alpha: float = 0.5, shared_bandit: bool = False, reward: int = REWARD_BLEND, adaedl: dict | None = None,
-                 token_level: bool = False):
+                 token_level: bool = False, draft_sampling: bool = False):
         """adaedl: optional dict with any of gamma, alpha, beta1, beta2, eps, rate0 (tapout_config.adaedl_*)."""
         self._lib = load_library()
         cfg = default_config(max_batch, max_k, vocab)
@@ -146,6 +147,7 @@ class Tapout:
         cfg.alpha = alpha
         cfg.reward = reward
         cfg.granularity = TOKEN_LEVEL if token_level else SEQUENCE_LEVEL
+        cfg.draft_sampling = 1 if draft_sampling else 0
         for k, v in (adaedl or {}).items():
             setattr(cfg, "adaedl_" + k, float(v))
         cfg.n_bandits = 1 if shared_bandit else max_batch

@@ -199,6 +199,7 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     if (cfg->policy < TAPOUT_UCB1 || cfg->policy > TAPOUT_TS_GAUSS) return fail(nullptr, TAPOUT_EUNSUPPORTED, "policy %d is not implemented", cfg->policy);
     if (cfg->granularity != TAPOUT_SEQUENCE_LEVEL && cfg->granularity != TAPOUT_TOKEN_LEVEL)
         return fail(nullptr, TAPOUT_EUNSUPPORTED, "granularity %d is not implemented", cfg->granularity);
+    if (cfg->draft_sampling != 0 && cfg->draft_sampling != 1) return fail(nullptr, TAPOUT_EINVAL, "draft_sampling must be 0 or 1");
     if (cfg->reward != TAPOUT_REWARD_BLEND && cfg->reward != TAPOUT_REWARD_SIMPLE) return fail(nullptr, TAPOUT_EUNSUPPORTED, "reward %d is not implemented", cfg->reward);
     if (adaedl) {
         if (!(cfg->adaedl_gamma >= 0.0) || !(cfg->adaedl_gamma < INFINITY)) return fail(nullptr, TAPOUT_EINVAL, "adaedl_gamma must be finite and >= 0");
@@ -225,7 +226,7 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     const size_t nstate = (size_t)cfg->n_bandits * c->positions * cfg->n_arms;
     c->nsl_max = (cfg->vocab + kSampleSlice - 1) / kSampleSlice;
     // final-token jobs: one per sequence (verification) or one per draft row (draft-token sampling)
-    const size_t njobs = (size_t)cfg->max_batch * cfg->max_k;
+    const size_t njobs = (size_t)cfg->max_batch * (cfg->draft_sampling ? cfg->max_k : 1);
     double table[256];
     for (int k = 0; k < 256; ++k) table[k] = std::exp2((double)k / 256.0);
     bool ok = hipMalloc(&c->part, c->part_cap * sizeof(Partial)) == hipSuccess
@@ -344,6 +345,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     if (arm && !n_stop && !stop_fired) return fail(ctx, TAPOUT_EINVAL, "arm given but neither n_stop nor stop_fired");
     if (u_draft && draft_tok) return fail(ctx, TAPOUT_EINVAL, "draft_tok and u_draft exclude each other");
     if (u_draft && !sampled_tok) return fail(ctx, TAPOUT_EINVAL, "u_draft given but sampled_tok is NULL");
+    if (u_draft && !ctx->cfg.draft_sampling) return fail(ctx, TAPOUT_EINVAL, "u_draft needs a context created with draft_sampling = 1");
     DeviceGuard guard(ctx->cfg.device);
     hipStream_t st = (hipStream_t)stream;
     const int64_t rows = (int64_t)B * K;

@@ -280,7 +280,7 @@ def test_vocabulary_beyond_256_final_token_slices():
     rnd["u_accept"][:] = 1.0 - 2.0 ** -24                                 # reject at once: residual draws ...
     rnd["u_accept"][2] = 0.0                                              # ... and one bonus-token draw from the last row
     rnd["u_sample"][:] = torch.tensor([0.0001, 0.9999, 0.5], device=DEV)
-    tp = binding.Tapout(B, K, V)
+    tp = binding.Tapout(B, K, V, draft_sampling=True)
     c = pu.check_round(tp, rnd)
     assert c["icdf_flagged"] <= 1
     ds, vf, _ = pu.gpu_round(tp, rnd)
@@ -628,7 +628,7 @@ def test_draft_token_sampling_matches_oracle(name):
     if name == "ragged":
         w = synth.scaled(w, B=6, V=70001)                         # odd V: ragged last slice, misaligned rows
     rnd = synth.RoundGenerator(w, DEV).round(2)
-    tp = binding.Tapout(w.B, w.K, w.V)
+    tp = binding.Tapout(w.B, w.K, w.V, draft_sampling=True)
     g = torch.Generator().manual_seed(77)
     u = torch.rand(w.B, w.K, generator=g)
     u[0, 0] = 0.0
@@ -659,7 +659,9 @@ def test_draft_token_sampling_law_edges_and_bad_rows():
     x[1, 0, :] = torch.randn(V) * 2; x[1, 1, :] = x[1, 0, :]
     x[2, 0, :] = 0.0; x[2, 0, 17] = float("nan")                    # bad row
     x[2, 1, :] = float("-inf")                                      # no finite maximum
-    tp = binding.Tapout(3, 2, V)
+    tp = binding.Tapout(3, 2, V, draft_sampling=True)
+    with pytest.raises(binding.TapoutError):                        # a context without the scratch for it refuses
+        binding.Tapout(3, 2, V).draft_stats(x.to(DEV), u_draft=torch.zeros(3, 2, device=DEV))
     for dt in (torch.float32, torch.bfloat16):
         u = torch.tensor([[0.31, 0.99], [0.0, 0.999999], [0.5, 0.5]])
         o = tp.draft_stats(x.to(dt).to(DEV), u_draft=u.to(DEV))

@@ -329,20 +329,64 @@ TAPOUT_API tapout_status tapout_draft_stats_sharded(tapout_ctx *ctx, const tapou
  * Acceptance step of tapout_verify from shard records of the target rows
  * (tapout_shard_stats with rows_mode = 1, tok = draft_tok, len = n_draft,
  * exchanged as for the draft side).  Writes what tapout_verify writes, except
- * the final token of a sampled sequence: its draw needs the exact normalisers
- * of one row pair over the whole vocabulary, a second, smaller exchange that
- * this library does not do yet; out_tok[b, accept_len[b]] is -1 for such a
- * sequence (greedy and flagged sequences get their token, the argmax of the
- * merged records).
- * stats     [G, B * (K + 1)] records, shard-major; V the whole vocabulary
+ * the final token of a sampled sequence, for which out_tok[b, accept_len[b]]
+ * is -1 and final_jobs[b] describes the draw that the two calls below make
+ * (greedy and flagged sequences get their token, the argmax of the merged
+ * records, and a job of kind 0).
+ * stats      [G, B * (K + 1)] records, shard-major; V the whole vocabulary
+ * draft_lse  [B,K] f32 from tapout_draft_stats(_sharded), or NULL if final_jobs
+ *            is NULL
+ * final_jobs [B] or NULL
  */
+typedef struct {
+    int32_t kind;     /* 0 nothing to draw, 1 residual max(0, p - q) of row `row`, 2 target row `row` alone */
+    int32_t row;
+    float ref_p;      /* exponent reference of the target row: its maximum over the whole vocabulary        */
+    float ref_q;      /* exponent reference of the draft row: its lse                                       */
+    double lam_est;   /* binary32-grade estimate of sum exp(t - ref_p) / sum exp(d - ref_q)                 */
+} tapout_final_job;
+
 TAPOUT_API tapout_status tapout_verify_accept_sharded(tapout_ctx *ctx, const tapout_shard_stat *stats, int32_t G,
                                  int32_t B, int32_t K, int32_t V,
                                  const float *logq_tok, const int32_t *draft_tok, const int32_t *n_draft,
-                                 const uint8_t *greedy, const float *u_accept,
+                                 const uint8_t *greedy, const float *u_accept, const float *draft_lse,
                                  int32_t *accept_len, int32_t *out_tok, int32_t *n_out,
                                  float *target_lse, float *logp_tok, int32_t *target_top1,
-                                 uint32_t *flags, void *stream);
+                                 tapout_final_job *final_jobs, uint32_t *flags, void *stream);
+
+/*
+ * Final token of the sampled sequences over vocabulary shards, two calls with
+ * one exchange between them (and a second exchange in the rare case below).
+ *
+ * tapout_shard_final_sums: this shard's sums of the job's row pair, in double:
+ *   sums[b] = { A, B, R~, D, U } as defined for the unsplit path (A = sum of
+ *   exp(t - ref_p), B = sum of exp(d - ref_q), R~ / D / U with lam_est); the
+ *   per-slice sums stay in the context for the second call.
+ * The caller all-gathers sums to sums_all [G, B, 5] (shard-major).
+ *
+ * tapout_shard_final_token: every shard forms the exact normaliser ratio and
+ * the residual mass of every shard from sums_all, so all agree on the shard
+ * that holds u * Z; that shard locates the token in its slice and writes its
+ * GLOBAL id to tok_out[b], the others write -1.  If the sums cannot settle the
+ * masses to 2e-10 (a heavy token with p = q to 1e-5, p == q, ...), every shard
+ * instead writes its exact residual mass to exact_mass[b], sets need_exact[b]
+ * and tok_out[b] = -1; the caller all-gathers exact_mass to exact_all [G, B]
+ * and calls again with it (sequences that did not need it ignore it).
+ * Both calls must follow tapout_shard_final_sums on the same context with the
+ * same shards and jobs.
+ *
+ * target_shard [B,K+1,Vs], draft_shard [B,K,Vs]: this GPU's column slices
+ * jobs [B] from tapout_verify_accept_sharded;  g: this shard's index in 0..G-1
+ * u_sample [B] f32;  tok_out [B] i32;  exact_mass [B] f64;  need_exact [B] u8
+ */
+TAPOUT_API tapout_status tapout_shard_final_sums(tapout_ctx *ctx, const tapout_logits *target_shard, const tapout_logits *draft_shard,
+                                 int32_t B, int32_t K, int32_t Vs, const tapout_final_job *jobs,
+                                 double *sums, void *stream);
+TAPOUT_API tapout_status tapout_shard_final_token(tapout_ctx *ctx, const tapout_logits *target_shard, const tapout_logits *draft_shard,
+                                 int32_t B, int32_t K, int32_t Vs, int32_t vocab_offset, int32_t G, int32_t g,
+                                 const tapout_final_job *jobs, const double *sums_all, const double *exact_all,
+                                 const float *u_sample, int32_t *tok_out, double *exact_mass, uint8_t *need_exact,
+                                 void *stream);
 
 /*
  * Bandit update after verification (Algorithm 1 line 12; Section 3.2):

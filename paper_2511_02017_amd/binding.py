@@ -28,6 +28,7 @@ EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_l
            "tapout_bandit_select", "tapout_draft_stats", "tapout_verify", "tapout_bandit_update",
            "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_rule_state_get", "tapout_rule_state_set",
            "tapout_shard_stats", "tapout_draft_stats_sharded", "tapout_verify_accept_sharded",
+           "tapout_shard_final_sums", "tapout_shard_final_token",
            "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
@@ -76,7 +77,9 @@ def load_library():
         lib.tapout_draft_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 16
         lib.tapout_shard_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32, i32, vp, i32, vp, vp, vp]
         lib.tapout_draft_stats_sharded.argtypes = [vp, vp, i32, i32, i32, i32] + [vp] * 14
-        lib.tapout_verify_accept_sharded.argtypes = [vp, vp, i32, i32, i32, i32] + [vp] * 13
+        lib.tapout_verify_accept_sharded.argtypes = [vp, vp, i32, i32, i32, i32] + [vp] * 15
+        lib.tapout_shard_final_sums.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32, vp, vp, vp]
+        lib.tapout_shard_final_token.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32, i32, i32, i32] + [vp] * 8
         lib.tapout_verify.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 15
         lib.tapout_bandit_update.argtypes = [vp, i32] + [vp] * 6
         lib.tapout_bandit_get_state.argtypes = [vp] * 5
@@ -297,23 +300,53 @@ class Tapout:
         return out
 
     def verify_accept_sharded(self, stats, B: int, K: int, V: int, logq_tok, draft_tok, n_draft, u_accept, greedy=None,
-                              out=None, stream=None):
+                              draft_lse=None, out=None, stream=None):
         """stats: int32 tensor [G, B*(K+1), 8] of target-row shard records.  Fills the dict tapout_verify fills; the final
-        token of a sampled sequence is left at -1."""
+        token of a sampled sequence is left at -1 and described by out["final_jobs"] (uint8 [B, 24]) when draft_lse is given."""
         G = stats.shape[0]
         if out is None:
             out = self.alloc_verify_outputs(B, K)
+        if draft_lse is not None and "final_jobs" not in out:
+            out["final_jobs"] = torch.zeros((B, 24), dtype=torch.uint8, device=self.device)
         f32, i32 = torch.float32, torch.int32
         self._check(self._lib.tapout_verify_accept_sharded(
             self._ctx, _ptr(stats, i32, (G, B * (K + 1), 8), "stats"), G, B, K, V,
             _ptr(logq_tok, f32, (B, K), "logq_tok"), _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(n_draft, i32, (B,), "n_draft"),
-            _ptr(greedy, torch.uint8, (B,), "greedy"), _ptr(u_accept, f32, (B, K), "u_accept"),
+            _ptr(greedy, torch.uint8, (B,), "greedy"), _ptr(u_accept, f32, (B, K), "u_accept"), _ptr(draft_lse, f32, (B, K), "draft_lse"),
             _ptr(out["accept_len"], i32, (B,), "accept_len"), _ptr(out["out_tok"], i32, (B, K + 1), "out_tok"),
             _ptr(out["n_out"], i32, (B,), "n_out"),
             _ptr(out.get("target_lse"), f32, (B, K + 1), "target_lse"), _ptr(out.get("logp_tok"), f32, (B, K), "logp_tok"),
             _ptr(out.get("target_top1"), i32, (B, K + 1), "target_top1"),
+            _ptr(out.get("final_jobs"), torch.uint8, (B, 24), "final_jobs") if draft_lse is not None else None,
             _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream)))
         return out
+
+    def shard_final_sums(self, target_shard, draft_shard, jobs, stream=None):
+        """This shard's five double-precision sums per sequence for the final-token draw: float64 tensor [B, 5]."""
+        B, K1, Vs = target_shard.shape
+        sums = torch.zeros((B, 5), dtype=torch.float64, device=self.device)
+        tl, dl = _logits(target_shard, "target shard"), _logits(draft_shard, "draft shard")
+        self._check(self._lib.tapout_shard_final_sums(self._ctx, C.byref(tl), C.byref(dl), B, K1 - 1, Vs,
+                                                      _ptr(jobs, torch.uint8, (B, 24), "jobs"), _ptr(sums, torch.float64, (B, 5), "sums"),
+                                                      _stream(stream)))
+        return sums
+
+    def shard_final_token(self, target_shard, draft_shard, vocab_offset: int, G: int, g: int, jobs, sums_all, u_sample,
+                          exact_all=None, stream=None):
+        """(tok [B] int32: global id where this shard holds the draw, else -1; exact_mass [B] float64; need_exact [B] uint8)."""
+        B, K1, Vs = target_shard.shape
+        d = self.device
+        tok = torch.full((B,), -1, dtype=torch.int32, device=d)
+        mass = torch.zeros(B, dtype=torch.float64, device=d)
+        need = torch.zeros(B, dtype=torch.uint8, device=d)
+        tl, dl = _logits(target_shard, "target shard"), _logits(draft_shard, "draft shard")
+        self._check(self._lib.tapout_shard_final_token(
+            self._ctx, C.byref(tl), C.byref(dl), B, K1 - 1, Vs, int(vocab_offset), int(G), int(g),
+            _ptr(jobs, torch.uint8, (B, 24), "jobs"), _ptr(sums_all, torch.float64, (G, B, 5), "sums_all"),
+            _ptr(exact_all, torch.float64, (G, B), "exact_all"), _ptr(u_sample, torch.float32, (B,), "u_sample"),
+            _ptr(tok, torch.int32, (B,), "tok_out"), _ptr(mass, torch.float64, (B,), "exact_mass"),
+            _ptr(need, torch.uint8, (B,), "need_exact"), _stream(stream)))
+        return tok, mass, need
 
     def alloc_draft_outputs(self, B, K):
         d = self.device

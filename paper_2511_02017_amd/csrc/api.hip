@@ -459,10 +459,10 @@ tapout_status tapout_draft_stats_sharded(tapout_ctx *ctx, const tapout_shard_sta
 tapout_status tapout_verify_accept_sharded(tapout_ctx *ctx, const tapout_shard_stat *stats, int32_t G,
                                  int32_t B, int32_t K, int32_t V,
                                  const float *logq_tok, const int32_t *draft_tok, const int32_t *n_draft,
-                                 const uint8_t *greedy, const float *u_accept,
+                                 const uint8_t *greedy, const float *u_accept, const float *draft_lse,
                                  int32_t *accept_len, int32_t *out_tok, int32_t *n_out,
                                  float *target_lse, float *logp_tok, int32_t *target_top1,
-                                 uint32_t *flags, void *stream)
+                                 tapout_final_job *final_jobs, uint32_t *flags, void *stream)
 {
     if (!ctx) return TAPOUT_EINVAL;
     if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
@@ -471,6 +471,7 @@ tapout_status tapout_verify_accept_sharded(tapout_ctx *ctx, const tapout_shard_s
     if (G < 1 || G > kStageCap) return fail(ctx, TAPOUT_EINVAL, "G = %d outside [1, %d]", G, kStageCap);
     if (B == 0) return TAPOUT_OK;
     if (!stats || !logq_tok || !draft_tok || !n_draft || !u_accept) return fail(ctx, TAPOUT_EINVAL, "stats, logq_tok, draft_tok, n_draft and u_accept are required");
+    if (final_jobs && !draft_lse) return fail(ctx, TAPOUT_EINVAL, "final_jobs needs draft_lse");
     if (!accept_len || !out_tok || !n_out) return fail(ctx, TAPOUT_EINVAL, "accept_len, out_tok and n_out are required");
     DeviceGuard guard(ctx->cfg.device);
     hipStream_t st = (hipStream_t)stream;
@@ -478,10 +479,73 @@ tapout_status tapout_verify_accept_sharded(tapout_ctx *ctx, const tapout_shard_s
     va.B = B; va.K = K; va.V = V; va.nsplit = G; va.shards = G; va.jps = 1; va.n_jobs = B;
     va.part = (const Partial *)stats;
     va.logq_tok = logq_tok; va.draft_tok = draft_tok; va.n_draft = n_draft; va.greedy = greedy; va.u_accept = u_accept;
+    va.draft_lse = draft_lse; va.final_jobs = (SampleJob *)final_jobs;
     va.accept_len = accept_len; va.out_tok = out_tok; va.n_out = n_out;
     va.target_lse = target_lse; va.logp_tok = logp_tok; va.target_top1 = target_top1; va.flags = flags;
     hipError_t e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD, [&](Timing tm) { return launch_verify(va, 0, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "sharded verify head launch");
+}
+
+namespace {
+tapout_status shard_final_args(tapout_ctx *ctx, const tapout_logits *target_shard, const tapout_logits *draft_shard,
+                               int32_t B, int32_t K, int32_t Vs, const tapout_final_job *jobs, ShardFinalArgs *out)
+{
+    if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (K < 1 || K > ctx->cfg.max_k) return fail(ctx, TAPOUT_EINVAL, "K = %d outside [1, max_k = %d]", K, ctx->cfg.max_k);
+    if (Vs < 1 || Vs > ctx->cfg.vocab) return fail(ctx, TAPOUT_EINVAL, "Vs = %d outside [1, vocab = %d]", Vs, ctx->cfg.vocab);
+    if (B == 0) return TAPOUT_OK;
+    char buf[128];
+    if (const char *m = check_logits(target_shard, "target shard", Vs, K + 1, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
+    if (const char *m = check_logits(draft_shard, "draft shard", Vs, K, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
+    if (!jobs) return fail(ctx, TAPOUT_EINVAL, "jobs is NULL");
+    ShardFinalArgs a{};
+    VerifyArgs &va = a.v;
+    va.tbase = target_shard->ptr; va.t_dtype = target_shard->dtype; va.t_stride_b = target_shard->stride_b; va.t_stride_k = target_shard->stride_k;
+    va.dbase = draft_shard->ptr; va.d_dtype = draft_shard->dtype; va.d_stride_b = draft_shard->stride_b; va.d_stride_k = draft_shard->stride_k;
+    va.B = B; va.K = K; va.V = Vs; va.nsl = (Vs + kSampleSlice - 1) / kSampleSlice;
+    va.jps = 1; va.n_jobs = B;
+    va.jobs = ctx->jobs; va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
+    a.jobs_in = (const SampleJob *)jobs;
+    *out = a;
+    return TAPOUT_OK;
+}
+}  // namespace
+
+tapout_status tapout_shard_final_sums(tapout_ctx *ctx, const tapout_logits *target_shard, const tapout_logits *draft_shard,
+                                 int32_t B, int32_t K, int32_t Vs, const tapout_final_job *jobs,
+                                 double *sums, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    ShardFinalArgs a{};
+    tapout_status s = shard_final_args(ctx, target_shard, draft_shard, B, K, Vs, jobs, &a);
+    if (s != TAPOUT_OK || B == 0) return s;
+    if (!sums) return fail(ctx, TAPOUT_EINVAL, "sums is NULL");
+    DeviceGuard guard(ctx->cfg.device);
+    a.sums_out = sums;
+    hipError_t e = launch_shard_final_sums(a, (hipStream_t)stream);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "shard final sums launch");
+}
+
+tapout_status tapout_shard_final_token(tapout_ctx *ctx, const tapout_logits *target_shard, const tapout_logits *draft_shard,
+                                 int32_t B, int32_t K, int32_t Vs, int32_t vocab_offset, int32_t G, int32_t g,
+                                 const tapout_final_job *jobs, const double *sums_all, const double *exact_all,
+                                 const float *u_sample, int32_t *tok_out, double *exact_mass, uint8_t *need_exact,
+                                 void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    ShardFinalArgs a{};
+    tapout_status s = shard_final_args(ctx, target_shard, draft_shard, B, K, Vs, jobs, &a);
+    if (s != TAPOUT_OK || B == 0) return s;
+    if (G < 1 || g < 0 || g >= G) return fail(ctx, TAPOUT_EINVAL, "need 0 <= g < G, got g = %d, G = %d", g, G);
+    if (vocab_offset < 0 || (int64_t)vocab_offset + Vs > INT32_MAX) return fail(ctx, TAPOUT_EINVAL, "vocab_offset out of range");
+    if (!sums_all || !u_sample || !tok_out || !exact_mass || !need_exact)
+        return fail(ctx, TAPOUT_EINVAL, "sums_all, u_sample, tok_out, exact_mass and need_exact are required");
+    DeviceGuard guard(ctx->cfg.device);
+    a.v.u_sample = u_sample;
+    a.sums_all = sums_all; a.exact_all = exact_all; a.G = G; a.g = g; a.vocab_offset = vocab_offset;
+    a.tok_out = tok_out; a.exact_mass = exact_mass; a.need_exact = need_exact;
+    hipError_t e = launch_shard_final_token(a, (hipStream_t)stream);
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "shard final token launch");
 }
 
 tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const tapout_logits *draft,

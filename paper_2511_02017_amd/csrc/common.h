@@ -41,6 +41,8 @@ struct SampleJob {
 };
 
 
+static_assert(sizeof(tapout_final_job) == sizeof(SampleJob), "the public job record is the internal one");
+
 constexpr int kBandCap = 32;         // band elements per job the locate kernel settles one by one; more: exact slow path
 
 // The job as it lies in memory, together with the list of elements of its row pair whose sign of a - L b is
@@ -125,6 +127,7 @@ struct VerifyArgs {
     int32_t jps, n_jobs;
     int32_t *tok_direct;          // draft-token sampling: token of job j goes to tok_direct[j] instead of out_tok
     int32_t shards;               // > 0: part holds records of vocabulary shards, shard-major [shards, B*(K+1)] (head kernel only)
+    SampleJob *final_jobs;        // sharded head: the job of every sequence for the caller (or NULL)
     const Partial *part;
     const float *draft_lse, *logq_tok; const int32_t *draft_tok, *n_draft; const uint8_t *greedy;
     const float *u_accept, *u_sample;
@@ -143,6 +146,20 @@ hipError_t launch_verify(const VerifyArgs &a, int pass /*0 head, 1 slices, 2 loc
 // the final token then draw the tokens.  Arguments as VerifyArgs with the draft tensor in the target slots:
 // tbase/t_* = draft logits, part = draft partials [B*K, nsplit], n_draft = k_len (or NULL), jps = K.
 hipError_t launch_sample_head(const VerifyArgs &a, hipStream_t st, Timing tm);
+
+// Final token over vocabulary shards (see tapout_shard_final_sums / tapout_shard_final_token).  The VerifyArgs
+// describe this shard's column slices (V = its width, nsl = its slices, jobs / part1 / part2 of the context).
+struct ShardFinalArgs {
+    VerifyArgs v;
+    const SampleJob *jobs_in;     // [B] jobs as the caller holds them
+    double *sums_out;             // [B, 5]                       (sums)
+    const double *sums_all;       // [G, B, 5]                    (token)
+    const double *exact_all;      // [G, B] or NULL               (token)
+    int32_t G, g, vocab_offset;
+    int32_t *tok_out; double *exact_mass; uint8_t *need_exact;
+};
+hipError_t launch_shard_final_sums(const ShardFinalArgs &a, hipStream_t st);
+hipError_t launch_shard_final_token(const ShardFinalArgs &a, hipStream_t st);
 
 constexpr int kSampleSlice = 2048;   // elements per slice of the final-token passes
 

@@ -282,6 +282,8 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 a.jobs[b].job = job;
                 a.jobs[b].band_cnt = 0;              // the slice kernel appends to the sequence's band list
                 a.flags_ws[b] = f;
+            } else if (a.final_jobs) {
+                a.final_jobs[b] = job;
             }
             if (a.flags) a.flags[b] = f;
         }
@@ -749,6 +751,175 @@ __global__ __launch_bounds__(kVBlock) void sample_head_kernel(VerifyArgs a)
     a.jobs[j].band_cnt = 0;
 }
 
+// ---- final token over vocabulary shards ---------------------------------------------------------
+// Copies the caller's jobs into the context's job records (the slice kernel reads them there and appends band
+// elements, which the sharded path counts but does not use).
+__global__ void shard_jobs_kernel(ShardFinalArgs a)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= a.v.B) return;
+    a.v.jobs[b].job = a.jobs_in[b];
+    a.v.jobs[b].band_cnt = 0;
+}
+
+// This shard's five sums per sequence: the slice sums in slice order (fixed order, one thread per value).
+__global__ void shard_sums_kernel(ShardFinalArgs a)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.v.B * kSliceVals) return;
+    const int b = i / kSliceVals, q = i - b * kSliceVals;
+    double s = 0.0;
+    if (a.jobs_in[b].kind != 0 && (q == 0 || a.jobs_in[b].kind == 1)) {
+        const double *ps = a.v.part1 + (int64_t)b * a.v.nsl * kSliceVals;
+        for (int sl = 0; sl < a.v.nsl; ++sl) s += ps[sl * kSliceVals + q];
+    }
+    a.sums_out[i] = s;
+}
+
+// One workgroup per sequence.  Every shard runs this on the same sums_all, so all of them derive the same
+// normaliser ratio, the same masses and the same owner; only the owner scans its slices for the token.
+template <int TD, int DD>
+__global__ __launch_bounds__(kVBlock) void shard_locate(ShardFinalArgs a)
+{
+    __shared__ double shT[256];
+    __shared__ LocateShared shl;
+    const VerifyArgs &v = a.v;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const SampleJob job = a.jobs_in[b];
+    if (tid == 0) { a.tok_out[b] = -1; a.need_exact[b] = 0; a.exact_mass[b] = NAN; }
+    if (job.kind == 0) return;
+    shT[tid] = v.exp_table[tid];
+    if (tid == 0) { shl.last = -1; shl.slice = 0x7fffffff; }
+    __syncthreads();
+    // totals over all shards, shard order
+    double tot[kSliceVals] = {0.0, 0.0, 0.0, 0.0, 0.0};
+    for (int h = 0; h < a.G; ++h)
+#pragma unroll
+        for (int q = 0; q < kSliceVals; ++q) tot[q] += a.sums_all[((int64_t)h * v.B + b) * kSliceVals + q];
+    const double Sp = tot[0], Sq = tot[1];
+    Weights w;
+    w.kind = job.kind;
+    w.rp.set((double)job.ref_p); w.rq.set((double)job.ref_q);
+    if (job.kind == 1 && (!(Sq > 0.0) || !(Sq < INFINITY))) w.kind = 2;       // unusable draft row: draw from the target row alone
+    w.lam = w.kind == 1 ? Sp / Sq : 0.0;
+    const double delta = w.lam - job.lam;
+    const Rows r = job_rows<TD, DD>(v, b, job);
+    const double *ps = v.part1 + (int64_t)b * v.nsl * kSliceVals;
+    double *zs = v.part2 + (int64_t)b * v.nsl;
+    int phase = 0;
+    // mass of shard h under the current weights
+    bool exact = false;                       // masses and own slice weights are exact recomputations
+    auto shard_mass = [&](int h) -> double {
+        const double *sh = a.sums_all + ((int64_t)h * v.B + b) * kSliceVals;
+        if (w.kind == 2) return sh[0];
+        if (exact) return a.exact_all[(int64_t)h * v.B + b];
+        const double m = sh[2] - delta * sh[3];
+        return m > 0.0 ? m : 0.0;
+    };
+    double Z = w.kind == 2 ? Sp : tot[2] - delta * tot[3];
+    if (w.kind == 1) {
+        const bool certified = fabs(delta) <= kEta * job.lam && Z > 0.0 && fabs(delta) * tot[4] <= 2.0e-10 * Z;
+        if (!certified) {
+            // exact weights of this shard's slices with the exact ratio (every shard does this for its own slices)
+            double ztot = 0.0;
+            for (int s = 0; s < v.nsl; ++s) {
+                double st;
+                locate_in_slice<TD, DD>(w, r, s, v.V, shT, 0.0, INFINITY, &shl, phase++, &st);
+                if (tid == 0) zs[s] = st;
+                ztot += st;
+            }
+            __threadfence_block();
+            __syncthreads();
+            if (!a.exact_all) {                                                // first call: hand the exact mass to the caller
+                if (tid == 0) { a.exact_mass[b] = ztot; a.need_exact[b] = 1; }
+                return;
+            }
+            exact = true;
+            Z = 0.0;
+            for (int h = 0; h < a.G; ++h) Z += a.exact_all[(int64_t)h * v.B + b];
+            if (!(Z > 0.0)) {                                                   // p == q up to rounding: draw from the target row itself
+                w.kind = 2; exact = false; Z = Sp;
+            }
+        }
+    }
+    if (!(Z > 0.0)) {                                                           // nothing to draw from anywhere: the first shard answers token 0
+        if (tid == 0 && a.g == 0) a.tok_out[b] = a.vocab_offset;
+        return;
+    }
+    // owner: the first shard whose inclusive prefix of masses exceeds u * Z; the last one with mass if rounding leaves none
+    const double target = (double)v.u_sample[b] * Z;
+    double prefix = 0.0, mine_prefix = 0.0;
+    int owner = -1, last_pos = -1;
+    for (int h = 0; h < a.G; ++h) {
+        const double m = shard_mass(h);
+        if (h == a.g) mine_prefix = prefix;
+        if (m > 0.0) last_pos = h;
+        if (owner < 0 && prefix + m > target) owner = h;
+        prefix += m;
+    }
+    const bool fallback = owner < 0;
+    if (fallback) owner = last_pos;
+    if (owner != a.g) return;
+    auto slice_weight = [&](int s) -> double {
+        if (w.kind == 2) return ps[s * kSliceVals + 0];
+        if (exact) return zs[s];
+        const double x = ps[s * kSliceVals + 2] - delta * ps[s * kSliceVals + 3];
+        return x > 0.0 ? x : 0.0;
+    };
+    int token = -1;
+    if (!fallback) {
+        const double local = target - mine_prefix;
+        // the first thread walks the slice weights (a few hundred at most; this kernel is rare-path simple)
+        if (tid == 0) {
+            double c = 0.0; int sf = -1;
+            for (int s = 0; s < v.nsl; ++s) { const double x = slice_weight(s); if (c + x > local) { sf = s; break; } c += x; }
+            shl.bc[0] = c; shl.slice = sf;
+        }
+        __syncthreads();
+        double cum = shl.bc[0];
+        const int s_found = shl.slice;
+        __syncthreads();
+        if (s_found >= 0)
+            for (int s = s_found; s < v.nsl && token < 0; ++s) {
+                double slice_total;
+                token = locate_in_slice<TD, DD>(w, r, s, v.V, shT, cum, local, &shl, phase++, &slice_total);
+                cum += slice_total;
+            }
+    }
+    if (token < 0) {                                                            // rounding left no crossing: the last positive weight here
+        if (tid == 0) shl.last = -1;
+        __syncthreads();
+        for (int s = 0; s < v.nsl; ++s) {
+            double slice_total;
+            locate_in_slice<TD, DD>(w, r, s, v.V, shT, 0.0, INFINITY, &shl, phase++, &slice_total, true);
+        }
+        __syncthreads();
+        token = shl.last;
+    }
+    if (tid == 0) a.tok_out[b] = a.vocab_offset + (token < 0 ? 0 : token);
+}
+
+template <int TD, int DD>
+hipError_t launch_shard_typed(const ShardFinalArgs &a, int pass, hipStream_t st)
+{
+    if (pass == 0) {
+        hipLaunchKernelGGL(shard_jobs_kernel, dim3((a.v.B + 63) / 64), dim3(64), 0, st, a);
+        const unsigned gy = a.v.n_jobs < 65535 ? a.v.n_jobs : 65535, gz = (a.v.n_jobs + gy - 1) / gy;
+        hipLaunchKernelGGL((verify_slices<TD, DD>), dim3((a.v.nsl + kWavesPerWG - 1) / kWavesPerWG, gy, gz), dim3(kVBlock), 0, st, a.v);
+        hipLaunchKernelGGL(shard_sums_kernel, dim3((a.v.B * kSliceVals + 63) / 64), dim3(64), 0, st, a);
+    } else {
+        hipLaunchKernelGGL((shard_locate<TD, DD>), dim3(a.v.B), dim3(kVBlock), 0, st, a);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_shard_dispatch(const ShardFinalArgs &a, int pass, hipStream_t st)
+{
+    if (a.v.t_dtype == TAPOUT_F32)
+        return a.v.d_dtype == TAPOUT_F32 ? launch_shard_typed<TAPOUT_F32, TAPOUT_F32>(a, pass, st) : launch_shard_typed<TAPOUT_F32, TAPOUT_BF16>(a, pass, st);
+    return a.v.d_dtype == TAPOUT_F32 ? launch_shard_typed<TAPOUT_BF16, TAPOUT_F32>(a, pass, st) : launch_shard_typed<TAPOUT_BF16, TAPOUT_BF16>(a, pass, st);
+}
+
 template <int TD, int DD>
 hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {
@@ -760,6 +931,9 @@ hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm
 }
 
 }  // namespace
+
+hipError_t launch_shard_final_sums(const ShardFinalArgs &a, hipStream_t st) { return launch_shard_dispatch(a, 0, st); }
+hipError_t launch_shard_final_token(const ShardFinalArgs &a, hipStream_t st) { return launch_shard_dispatch(a, 1, st); }
 
 hipError_t launch_sample_head(const VerifyArgs &a, hipStream_t st, Timing tm)
 {

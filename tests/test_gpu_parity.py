@@ -756,6 +756,97 @@ def test_vocabulary_sharded_accept_step_matches_oracle(name, G):
     assert (one["accept_len"].cpu().numpy()[ok] == g_len[ok]).all()
 
 
+def sharded_round(rnd, G, V, edges=None):
+    """A whole verification over G emulated vocabulary shards (one context each, exchanges done with torch.stack).
+    Returns accept_len, out_tok and how many sequences needed the second (exact-mass) exchange."""
+    B, K = rnd["draft_tok"].shape
+    edges = edges or [round(g * V / G) for g in range(G + 1)]
+    tps = [binding.Tapout(B, K, edges[g + 1] - edges[g]) for g in range(G)]
+    dsl = [rnd["draft"][:, :, edges[g]:edges[g + 1]] for g in range(G)]
+    tsl = [rnd["target"][:, :, edges[g]:edges[g + 1]] for g in range(G)]
+    n_draft = rnd["k_len"]
+    drec = torch.stack([tps[g].shard_stats(dsl[g], edges[g], length=rnd["k_len"], tok=rnd["draft_tok"]).clone() for g in range(G)])
+    trec = torch.stack([tps[g].shard_stats(tsl[g], edges[g], length=n_draft, rows_mode=1, tok=rnd["draft_tok"]).clone() for g in range(G)])
+    gds = tps[0].draft_stats_sharded(drec, B, K, V, draft_tok=rnd["draft_tok"], k_len=rnd["k_len"])
+    gvf = tps[0].verify_accept_sharded(trec, B, K, V, gds["logq_tok"], rnd["draft_tok"], n_draft, rnd["u_accept"],
+                                       greedy=rnd["greedy"], draft_lse=gds["lse"])
+    jobs = gvf["final_jobs"]
+    sums_all = torch.stack([tps[g].shard_final_sums(tsl[g], dsl[g], jobs) for g in range(G)])
+    res = [tps[g].shard_final_token(tsl[g], dsl[g], edges[g], G, g, jobs, sums_all, rnd["u_sample"]) for g in range(G)]
+    need = torch.stack([r[2] for r in res])
+    assert (need == need[0]).all()                                   # every shard reaches the same verdict
+    n_second = int(need[0].sum())
+    if n_second:
+        exact_all = torch.stack([r[1] for r in res]).nan_to_num(0.0)
+        res = [tps[g].shard_final_token(tsl[g], dsl[g], edges[g], G, g, jobs, sums_all, rnd["u_sample"], exact_all=exact_all)
+               for g in range(G)]
+        assert not torch.stack([r[2] for r in res]).any()
+    toks = torch.stack([r[0] for r in res])                          # [G, B]: one shard answers, the others say -1
+    assert ((toks >= 0).sum(0) <= 1).all()
+    final = toks.max(0).values
+    out = gvf["out_tok"].clone()
+    m = gvf["accept_len"].long()
+    idx = torch.arange(B, device=out.device)
+    sampled = out[idx, m] < 0
+    assert torch.equal(sampled, final >= 0)
+    out[idx[sampled], m[sampled]] = final[sampled]
+    return gvf["accept_len"], out, n_second
+
+
+@pytest.mark.parametrize("name,G", [("small", 4), ("ragged", 3), ("llama3", 8)])
+def test_vocabulary_sharded_final_token_matches_oracle(name, G):
+    w = synth.WORKLOADS[name]
+    w = {"small": synth.scaled(w, B=8), "ragged": synth.scaled(w, B=8, V=70001), "llama3": synth.scaled(w, B=6)}[name]
+    rnd = synth.RoundGenerator(w, DEV).round(4)
+    acc, out, _ = sharded_round(rnd, G, w.V)
+    ods, ovf, nd = pu.oracle_round(rnd)
+    used = np.arange(w.K)[None, :] < nd[:, None]
+    ok = ~((ovf["accept_margin"] <= pu.TAU) & used).any(1) & ~(ovf["icdf_margin"] <= pu.TAU_S)
+    assert ok.sum() >= w.B - 1
+    assert (acc.cpu().numpy()[ok] == ovf["accept_len"][ok]).all()
+    assert (out.cpu().numpy()[ok] == ovf["out_tok"][ok]).all()
+
+
+def test_vocabulary_sharded_final_token_hard_cases():
+    """p = q on heavy tokens (the sums cannot settle the masses: second exchange), p == q everywhere (bonus-like draw
+    from the target row), and draws near the ends of the CDF."""
+    B, K, V, G = 5, 2, 30000, 4
+    g = torch.Generator().manual_seed(43)
+    d = (torch.randn(B, K, V, generator=g) * 2).float()
+    t = torch.cat([d + torch.randn(B, K, V, generator=g), torch.randn(B, 1, V, generator=g) * 2], 1).float()
+    hot = torch.randint(0, V, (B, 4), generator=g)
+    for b in range(3):                                               # sequences 0..2: heavy tokens with p_h = q_h
+        d[b, 0, hot[b]] = d[b, 0].max() + torch.tensor([2.0, 1.5, 1.0, 0.5])
+        q = torch.softmax(d[b, 0].double(), 0)
+        mask = torch.ones(V, dtype=torch.bool); mask[hot[b]] = False
+        ln_rp = torch.logsumexp(t[b, 0].double()[mask], 0)
+        t[b, 0, hot[b]] = (q[hot[b]].log() + ln_rp - torch.log1p(-q[hot[b]].sum())).float()
+    t[3, :K] = d[3]                                                  # p == q: accepted to the end, bonus token
+    tok = torch.randint(0, V, (B, K), generator=g, dtype=torch.int32)
+    for b in range(B):
+        clash = (tok[b][:, None] == hot[b][None, :]).any(1)
+        tok[b][clash] = (tok[b][clash] + 11) % V
+    ua = torch.full((B, K), 1.0 - 2.0 ** -24)
+    ua[3] = 0.5
+    rnd = dict(draft=d.to(DEV), target=t.to(DEV), draft_tok=tok.to(DEV), u_accept=ua.to(DEV),
+               u_sample=torch.tensor([0.3, 1e-4, 0.9999, 0.7, 0.5]).to(DEV),
+               k_len=torch.full((B,), K, dtype=torch.int32, device=DEV), greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
+    acc, out, n_second = sharded_round(rnd, G, V)
+    assert n_second >= 1                                             # the heavy p = q tokens forced the exact masses
+    ods, ovf, nd = pu.oracle_round(rnd)
+    used = np.arange(K)[None, :] < nd[:, None]
+    ok = ~((ovf["accept_margin"] <= pu.TAU) & used).any(1) & ~(ovf["icdf_margin"] <= pu.TAU_S)
+    # u_accept ~ 1 makes every drafted token with p >= q a near tie of the accept test: those sequences are not compared
+    assert ok[:3].any() and ok[3] and ok[4]
+    assert (acc.cpu().numpy()[ok] == ovf["accept_len"][ok]).all()
+    assert (out.cpu().numpy()[ok] == ovf["out_tok"][ok]).all()
+    assert acc[3] == K
+    # and the unsplit call agrees
+    tp = binding.Tapout(B, K, V)
+    _, vf, _ = pu.gpu_round(tp, rnd)
+    assert (vf["out_tok"].cpu().numpy()[ok] == out.cpu().numpy()[ok]).all()
+
+
 def test_vocabulary_shard_records_edge_cases():
     B, K, V, G = 2, 2, 4000, 4
     x = torch.randn(B, K, V) * 2

@@ -197,7 +197,9 @@ TAPOUT_API tapout_status tapout_bandit_select(tapout_ctx *ctx, int32_t B, const 
  * and per sequence n_stop = (first k at which the rule of arm[b] fires) + 1,
  * else k_len[b]: the token drafted at the firing step is kept.  The rule is
  * evaluated on the returned binary32 signals, widened to double (SVIP compares
- * sqrt(entropy)).  Rows k >= k_len[b] are neither read nor written.
+ * sqrt(entropy)).  Rows k >= k_len[b] are not streamed and their outputs are
+ * not written (the [B,K,V] tensor and draft_tok must still be addressable there:
+ * single elements of such rows may be read ahead of k_len and are discarded).
  * SVIP_DIFF and ADAEDL arms read the context's rule state (previous entropy,
  * lambda) and, when the configuration holds such an arm, the call keeps the
  * entropies of this draft in the context for tapout_bandit_update.

@@ -5,9 +5,10 @@
 // One launch covers all rows of a [B, KK, V] tensor.  A row is cut into
 // `nsplit` slices of whole 16-byte vectors; one 256-thread workgroup reduces
 // one slice to a 32-byte Partial.  Every element is loaded exactly once, with
-// 16-byte non-temporal loads that are contiguous across the wavefront, two
-// (draft) or four (target) vectors per thread in flight; eight wavefronts per
-// SIMD hide the latency (explicit double buffering was measured: no gain).
+// 16-byte non-temporal loads that are contiguous across the wavefront, four
+// vectors per thread in flight; six (draft) or eight (target) wavefronts per
+// SIMD hide the latency (explicit double buffering was measured: slower).
+// Batches that lie wholly inside the slice are loaded without bounds checks.
 //
 // Per thread the softmax sums are kept online in the base-2 domain against an
 // integer reference R >= max * log2 e: y = fma(x, log2e, -R) has a single
@@ -45,10 +46,24 @@ struct ThreadState {
     float t = 0.0f;         // sum 2^y * y (FULL only)
     int32_t cand = 0x7fffffff;
 
-    // Fold N values that start at element index `first` of the row; `first` is
-    // remembered as the argmax candidate when the running maximum grows.
+    // Raise the reference so that it covers the running maximum (rare after the first few vectors).
+    __device__ inline void cover_max()
+    {
+        if (v1 > xlim) {
+            float Rn = ceilf(v1 * kLog2e) + kHeadroom;
+            float d = Rn - R;
+            int di = (int)fminf(fmaxf(d, -1.0e9f), 1.0e9f);
+            if constexpr (FULL) t = ldexpf(t - d * s, -di);
+            s = ldexpf(s, -di);
+            R = Rn;
+            xlim = Rn * (1.0f / kLog2e);
+        }
+    }
+
+    // Maxima of N values that start at element index `first` of the row; `first` is remembered as the
+    // argmax candidate when the running maximum grows.
     template <int N>
-    __device__ inline void fold(const float (&x)[N], int32_t first)
+    __device__ inline void fold_max(const float (&x)[N], int32_t first)
     {
         float old = v1;
         if constexpr (N == 1) {
@@ -62,22 +77,41 @@ struct ThreadState {
             }
         }
         cand = v1 > old ? first : cand;
-        if (v1 > xlim) {                      // rare after the first few vectors
-            float Rn = ceilf(v1 * kLog2e) + kHeadroom;
-            float d = Rn - R;
-            int di = (int)fminf(fmaxf(d, -1.0e9f), 1.0e9f);
-            if constexpr (FULL) t = ldexpf(t - d * s, -di);
-            s = ldexpf(s, -di);
-            R = Rn;
-            xlim = Rn * (1.0f / kLog2e);
-        }
+    }
+
+    // Sums over N values the reference already covers.  The entropy sum of the group is formed without
+    // looking at the terms; a masked (-inf) logit gives 0 * -inf = NaN there, and only then the group is
+    // summed again with the exponent clamped (one comparison per group instead of one clamp per element).
+    template <int N>
+    __device__ inline void fold_sums(const float (&x)[N])
+    {
+        float tv = 0.0f;
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             float y = __builtin_fmaf(x[i], kLog2e, -R);
             float e = __builtin_amdgcn_exp2f(y);
             s += e;
-            if constexpr (FULL) t = __builtin_fmaf(e, fmaxf(y, -200.0f), t);   // clamp keeps 0 * -inf out of T for masked (-inf) logits
+            if constexpr (FULL) tv = __builtin_fmaf(e, y, tv);
         }
+        if constexpr (FULL) {
+            if (tv != tv) {
+                tv = 0.0f;
+#pragma unroll
+                for (int i = 0; i < N; ++i) {
+                    float y = __builtin_fmaf(x[i], kLog2e, -R);
+                    tv = __builtin_fmaf(__builtin_amdgcn_exp2f(y), fmaxf(y, -200.0f), tv);
+                }
+            }
+            t += tv;
+        }
+    }
+
+    template <int N>
+    __device__ inline void fold(const float (&x)[N], int32_t first)
+    {
+        fold_max<N>(x, first);
+        cover_max();
+        fold_sums<N>(x);
     }
 };
 
@@ -134,13 +168,13 @@ template <int DT> struct NegInfVec;
 template <> struct NegInfVec<TAPOUT_F32>  { static constexpr uint32_t word = 0xff800000u; };
 template <> struct NegInfVec<TAPOUT_BF16> { static constexpr uint32_t word = 0xff80ff80u; };
 
-template <int DT, int U>
+template <int DT, int U, bool CHECKED>
 __device__ inline void load_batch(u32x4 (&w)[U], const u32x4 *vp, int i, int end)
 {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int idx = i + u * kBlock;
-        if (idx < end) w[u] = __builtin_nontemporal_load(vp + idx);
+        if (!CHECKED || idx < end) w[u] = __builtin_nontemporal_load(vp + idx);
         else { const uint32_t ni = NegInfVec<DT>::word; w[u] = u32x4{ni, ni, ni, ni}; }   // -inf padding folds to nothing
     }
 }
@@ -161,9 +195,10 @@ template <int DT, bool FULL>
 __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
 {
     constexpr int VEC = Elem<DT>::vec;
-    // vectors in flight per thread: the draft pass carries more live state per element (second
-    // maximum, entropy sum), so it takes the shallower batch to stay at full occupancy
-    constexpr int U = FULL ? 2 : 4;
+    // vectors in flight per thread.  Four is best for both passes: for the draft pass that means 77 registers
+    // and six wavefronts per SIMD instead of eight, which still beats two vectors at full occupancy
+    // (measured; three, six and eight vectors and an explicit prefetch of the next batch are all slower).
+    constexpr int U = 4;
     __shared__ float sh_f[4][kBlock / kWave];
     __shared__ int sh_i[kBlock / kWave];
 
@@ -195,7 +230,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
         st.template fold<1>(x, tid);
     }
     {
-        const int nbatch = (v1e - v0 + U * kBlock - 1) / (U * kBlock);
+        const int nbatch = (v1e - v0 + U * kBlock - 1) / (U * kBlock), nfull = (v1e - v0) / (U * kBlock);
         int i = v0 + tid;
         // A compute unit issues the loads of its oldest wavefront first, so of the eight workgroups that share
         // it the ones dispatched first run ahead and the rest trail by up to a third of the launch; the chip
@@ -208,7 +243,8 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
             if (bi == q2) __builtin_amdgcn_s_setprio(1);
             if (bi == q3) __builtin_amdgcn_s_setprio(0);
             u32x4 w[U];
-            load_batch<DT, U>(w, vp, i, v1e);
+            if (bi < nfull) load_batch<DT, U, false>(w, vp, i, v1e);      // every vector of the batch lies inside the slice
+            else load_batch<DT, U, true>(w, vp, i, v1e);
             fold_batch<DT, FULL, U>(st, w, i, head);
         }
         __builtin_amdgcn_s_setprio(3);      // finish the reduction promptly: the slot is wanted by the next workgroup

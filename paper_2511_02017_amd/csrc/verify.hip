@@ -144,12 +144,13 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     // the first memory round trip carries n_draft, the tokens, the uniforms and the partials together.
     // (Rows beyond n_draft hold stale partials and unused tokens: read, never used.)
     int32_t tok0 = -1;
-    float u0 = 0.0f, lq0 = 0.0f;
+    float u0 = 0.0f, lq0 = 0.0f, dl0 = 0.0f;
     if ((int)threadIdx.x < K) {
         const int64_t i = (int64_t)b * K + threadIdx.x;
         tok0 = a.draft_tok[i];
         u0 = a.u_accept[i];
         lq0 = a.logq_tok[i];
+        if (a.draft_lse) dl0 = a.draft_lse[i];      // the final token's job wants it for row m: no dependent load later
     }
     if constexpr (SHARDED) {
         const int c0 = min(K + 1, rows_per_stage) * a.nsplit;
@@ -165,7 +166,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     job.kind = 0; job.row = 0; job.ref_p = 0.0f; job.ref_q = 0.0f; job.lam = 0.0;
     if (threadIdx.x == 0) { *sh_flags = f0; sh_bcast[4] = 0; }
     const bool need_top1 = writer || greedy;
-    int last_k = -1; float last_M = 0.0f; int32_t last_top1 = 0; double last_lse = 0.0;     // the last row this thread merged
+    int last_k = -1; float last_M = 0.0f, last_dl = 0.0f; int32_t last_top1 = 0; double last_lse = 0.0;   // the last row this thread merged
     for (int k0 = 0; k0 <= n; k0 += rows_per_stage) {
         const int k1 = min(n + 1, k0 + rows_per_stage);
         const int kmine = k0 + threadIdx.x;
@@ -175,6 +176,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
             if (kmine < k1 && kmine < n) {
                 const int64_t i = (int64_t)b * K + kmine;
                 tok0 = a.draft_tok[i]; u0 = a.u_accept[i]; lq0 = a.logq_tok[i];
+                if (a.draft_lse) dl0 = a.draft_lse[i];
             }
             __syncthreads();
             if constexpr (SHARDED) {
@@ -206,8 +208,10 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 const int64_t i = (int64_t)b * K + k;
                 int32_t t = tok0;
                 float xt = xtok0, u = u0, lq = lq0;
+                last_dl = dl0;
                 if (k != kmine) {                              // more rows than threads: load late
                     t = a.draft_tok[i]; u = a.u_accept[i]; lq = a.logq_tok[i];
+                    if (a.draft_lse) last_dl = a.draft_lse[i];
                     if constexpr (!SHARDED)
                         if (t >= 0 && t < a.V) xt = load_elem_rt(row, a.t_dtype, t);
                 }
@@ -249,11 +253,11 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     const bool flagged = sh_bcast[1] != 0;
     const uint32_t f = (uint32_t)sh_bcast[2];
     // maximum and argmax of row m: from the thread that merged it, if it still holds them
-    if (last_k == m) { sh_bcast[4] = 1; sh_bcast[5] = __float_as_int(last_M); sh_bcast[6] = last_top1; *sh_lse = last_lse; }
+    if (last_k == m) { sh_bcast[4] = 1; sh_bcast[5] = __float_as_int(last_M); sh_bcast[6] = last_top1; sh_bcast[7] = __float_as_int(last_dl); *sh_lse = last_lse; }
     __syncthreads();
-    float Mm; int32_t top1m; double lse_m;
+    float Mm, dl_m = 0.0f; int32_t top1m; double lse_m;
     if (sh_bcast[4]) {
-        Mm = __int_as_float(sh_bcast[5]); top1m = sh_bcast[6]; lse_m = *sh_lse;
+        Mm = __int_as_float(sh_bcast[5]); top1m = sh_bcast[6]; dl_m = __int_as_float(sh_bcast[7]); lse_m = *sh_lse;
     } else {                                     // more rows than threads: merge row m once more
         __syncthreads();
         if constexpr (SHARDED) stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1) + m, a.nsplit, a.nsplit), a.nsplit);
@@ -263,12 +267,13 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         lse_m = (r.R + log2(r.S)) * kLn2;
         if constexpr (SHARDED) top1m = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;
         else top1m = need_top1 ? resolve_argmax(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, m), a.t_dtype, a.V, r.cand, r.M) : 0;
+        if (m < n && a.draft_lse) dl_m = a.draft_lse[(int64_t)b * K + m];
     }
     if (!flagged && !greedy) {
         job.kind = m < n ? 1 : 2;
         job.row = m;
         job.ref_p = Mm;                          // exponent references: the target row's maximum, the draft row's lse
-        job.ref_q = (m < n && a.draft_lse) ? a.draft_lse[(int64_t)b * K + m] : 0.0f;
+        job.ref_q = (m < n && a.draft_lse) ? dl_m : 0.0f;
         // binary32-grade estimate of S_p / S_q in these references (S_q = sum exp(d - lse_q) = 1): lets the
         // slice pass form the residual before the exact normalisers exist
         job.lam = exp(lse_m - (double)Mm);

@@ -437,8 +437,13 @@ TAPOUT_API tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *pre
  *                 many workgroups (long rows are still cut), default 65536,
  *                 at least 16384
  *   "min_slice"   smallest slice of a row, in elements, default 4096
+ *   "fuse_head"   tapout_verify only: 1 = no launch of its own for the accept
+ *                 decisions, every workgroup of the final-token slice kernel
+ *                 takes them again for its sequence (pays while that kernel
+ *                 is a few workgroups per compute unit); 0 = separate launch;
+ *                 -1 (default) = decide per call from the launch size
  * Results do not depend on these values except through the rounding of the
- * binary32 partial sums.
+ * binary32 partial sums ("fuse_head": not at all).
  */
 TAPOUT_API tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value);
 

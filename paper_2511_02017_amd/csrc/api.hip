@@ -30,6 +30,7 @@ struct tapout_ctx {
     int wgs_target = 4096;        // workgroups a streaming launch aims for
     int min_slice = 4096;         // smallest slice (elements) a row is cut into
     int slice_bytes = 65536;      // slice size aimed for when the rows alone give enough workgroups
+    int fuse_head = -1;           // tapout_verify: accept decisions inside the slice kernel (1), in a launch of their own (0), by size (-1)
     // optional kernel timing (tapout_profile_*): event pairs around the launches of selected kernels
     uint32_t prof_mask = 0;
     int prof_cap = 0;
@@ -41,6 +42,7 @@ struct tapout_ctx {
 namespace {
 
 constexpr int kMaxWgsTarget = 1 << 16;
+constexpr int kFuseHeadMaxWgs = 2048;            // "fuse_head" = -1: fuse while the slice kernel has at most this many workgroups
 constexpr int kMinSliceBytes = 16384;            // lower limit of the "slice_bytes" option (sizes the partial buffer)
 thread_local char g_create_err[256] = {0};
 
@@ -294,6 +296,9 @@ tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value
     } else if (!strcmp(name, "min_slice")) {
         if (value < 256) return fail(ctx, TAPOUT_EINVAL, "min_slice below 256 elements");
         ctx->min_slice = value;
+    } else if (!strcmp(name, "fuse_head")) {
+        if (value < -1 || value > 1) return fail(ctx, TAPOUT_EINVAL, "fuse_head outside {-1, 0, 1}");
+        ctx->fuse_head = value;
     } else return fail(ctx, TAPOUT_EINVAL, "unknown option '%s'", name);
     return TAPOUT_OK;
 }
@@ -573,15 +578,23 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     const int nsplit = choose_nsplit(ctx, rows, V, target->dtype);
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
-    RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, slice_vectors(V, target->dtype, nsplit), (int32_t)rows, n_draft, 1, ctx->part};
+    // With few sequences the final-token slice kernel is a handful of workgroups per compute unit and its launch
+    // is latency: then the accept decisions are taken inside it (by every workgroup of a sequence again) and the
+    // head launch with its hand-over through memory goes away.  With many sequences that kernel is bound by
+    // arithmetic and the repeated head would add to it: separate launch.
+    const int nsl = (V + kSampleSlice - 1) / kSampleSlice;
+    const int64_t slice_wgs = (int64_t)B * ((nsl + 3) / 4);
+    const bool fused = ctx->fuse_head < 0 ? slice_wgs <= kFuseHeadMaxWgs : ctx->fuse_head == 1;
+    RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, slice_vectors(V, target->dtype, nsplit), (int32_t)rows, n_draft, 1, ctx->part,
+                    fused ? ctx->jobs : nullptr};
     hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_PASS, [&](Timing tm) { return launch_row_reduce(r, target->dtype, false, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "target pass launch");
 
     VerifyArgs va{};
     va.tbase = target->ptr; va.t_dtype = target->dtype; va.t_stride_b = target->stride_b; va.t_stride_k = target->stride_k;
     va.dbase = draft->ptr; va.d_dtype = draft->dtype; va.d_stride_b = draft->stride_b; va.d_stride_k = draft->stride_k;
-    va.B = B; va.K = K; va.V = V; va.nsplit = nsplit; va.nsl = (V + kSampleSlice - 1) / kSampleSlice;
-    va.jps = 1; va.n_jobs = B;
+    va.B = B; va.K = K; va.V = V; va.nsplit = nsplit; va.nsl = nsl;
+    va.jps = 1; va.n_jobs = B; va.fused_head = fused ? 1 : 0;
     va.part = ctx->part;
     va.draft_lse = draft_lse; va.logq_tok = logq_tok; va.draft_tok = draft_tok; va.n_draft = n_draft; va.greedy = greedy;
     va.u_accept = u_accept; va.u_sample = u_sample;
@@ -589,7 +602,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     va.target_lse = target_lse; va.logp_tok = logp_tok; va.target_top1 = target_top1; va.flags = flags;
     va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
     va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
-    for (int pass = 0; pass <= 2 && e == hipSuccess; ++pass)
+    for (int pass = fused ? 1 : 0; pass <= 2 && e == hipSuccess; ++pass)
         e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, [&](Timing tm) { return launch_verify(va, pass, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "verify launch");
 }

@@ -79,6 +79,7 @@ struct RowReduceArgs {
     const int32_t *len;           // draft: k_len (or NULL); target: n_draft
     int32_t len_mode;             // 0: row k active iff k < len[b] (NULL: all); 1: iff k <= clamp(len[b], 1, KK-1)
     Partial *out;                 // [n_rows, nsplit]
+    JobRecord *clear_jobs;        // NULL, or [B]: the first workgroup of sequence b empties the band list of its job record
 };
 // Streaming pass: one Partial per (row, slice).  Returns hipGetLastError() after enqueueing.
 hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st, Timing tm);
@@ -127,6 +128,7 @@ struct VerifyArgs {
     int32_t jps, n_jobs;
     int32_t *tok_direct;          // draft-token sampling: token of job j goes to tok_direct[j] instead of out_tok
     int32_t shards;               // > 0: part holds records of vocabulary shards, shard-major [shards, B*(K+1)] (head kernel only)
+    int32_t fused_head;           // 1: no head launch; every workgroup of the slice kernel works out its sequence's job itself
     SampleJob *final_jobs;        // sharded head: the job of every sequence for the caller (or NULL)
     const Partial *part;
     const float *draft_lse, *logq_tok; const int32_t *draft_tok, *n_draft; const uint8_t *greedy;

@@ -214,6 +214,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
         int n = a.len[b];
         n_active = (n < 1 ? 1 : (n > a.KK - 1 ? a.KK - 1 : n)) + 1;
     }
+    if (a.clear_jobs && split == 0 && k == 0 && tid == 0) a.clear_jobs[b].band_cnt = 0;
     if (k >= n_active) return;
     const char *rowp = (const char *)a.base + ((int64_t)b * a.stride_b + (int64_t)k * a.stride_k) * Elem<DT>::size;
     int head, nvec, tail;

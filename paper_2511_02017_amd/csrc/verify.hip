@@ -285,7 +285,9 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
             a.n_out[b] = m + 1;
             if constexpr (!SHARDED) {
                 a.jobs[b].job = job;
-                a.jobs[b].band_cnt = 0;              // the slice kernel appends to the sequence's band list
+                // the slice kernel appends to the sequence's band list; fused into that kernel, this workgroup
+                // cannot empty the list under the others' appends: the target pass has done it
+                if (!a.fused_head) a.jobs[b].band_cnt = 0;
                 a.flags_ws[b] = f;
             } else if (a.final_jobs) {
                 a.final_jobs[b] = job;
@@ -342,7 +344,7 @@ constexpr int kChunks = kSampleSlice / (kWave * kPer);          // a wavefront t
 // first chunk the memory latency hides behind the double-precision work; its five sums need no LDS and no
 // barrier.  (One slice per workgroup with all loads up front was latency bound: job record, then rows, then
 // arithmetic, 8.7 us per workgroup with at most eight of them per compute unit.)
-template <int TD, int DD>
+template <int TD, int DD, bool FUSED>
 __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
 {
     __shared__ double shT[256];
@@ -351,7 +353,20 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
     const int b = j / a.jps;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
     const int s = blockIdx.x * kWavesPerWG + wave;
-    const SampleJob job = a.jobs[j].job;
+    SampleJob job;
+    if constexpr (FUSED) {
+        // Small batches: a head launch of its own costs more (launch, hand-over of the job record through
+        // memory) than taking the accept decisions again in each of the sequence's workgroups.  All of them run
+        // the same code on the same inputs and reach the same job; the first one writes the sequence's outputs.
+        __shared__ Partial sh_part[kStageCap];
+        __shared__ uint8_t sh_dec[kScanCap];
+        __shared__ uint32_t sh_flags;
+        __shared__ int32_t sh_bcast[8];
+        __shared__ double sh_lse;
+        job = verify_head<false>(a, b, blockIdx.x == 0, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse);
+    } else {
+        job = a.jobs[j].job;
+    }
     if (job.kind == 0) return;
     const Rows r = job_rows<TD, DD>(a, b, job);
     const bool live = s < a.nsl;
@@ -910,7 +925,7 @@ hipError_t launch_shard_typed(const ShardFinalArgs &a, int pass, hipStream_t st)
     if (pass == 0) {
         hipLaunchKernelGGL(shard_jobs_kernel, dim3((a.v.B + 63) / 64), dim3(64), 0, st, a);
         const unsigned gy = a.v.n_jobs < 65535 ? a.v.n_jobs : 65535, gz = (a.v.n_jobs + gy - 1) / gy;
-        hipLaunchKernelGGL((verify_slices<TD, DD>), dim3((a.v.nsl + kWavesPerWG - 1) / kWavesPerWG, gy, gz), dim3(kVBlock), 0, st, a.v);
+        hipLaunchKernelGGL((verify_slices<TD, DD, false>), dim3((a.v.nsl + kWavesPerWG - 1) / kWavesPerWG, gy, gz), dim3(kVBlock), 0, st, a.v);
         hipLaunchKernelGGL(shard_sums_kernel, dim3((a.v.B * kSliceVals + 63) / 64), dim3(64), 0, st, a);
     } else {
         hipLaunchKernelGGL((shard_locate<TD, DD>), dim3(a.v.B), dim3(kVBlock), 0, st, a);
@@ -930,7 +945,10 @@ hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm
 {
     const unsigned gy = a.n_jobs < 65535 ? a.n_jobs : 65535, gz = (a.n_jobs + gy - 1) / gy;
     dim3 grid12((a.nsl + kWavesPerWG - 1) / kWavesPerWG, gy, gz), block(kVBlock);
-    if (pass == 1) launch_kernel(verify_slices<TD, DD>, grid12, block, st, tm, a);
+    if (pass == 1) {
+        if (a.fused_head) launch_kernel(verify_slices<TD, DD, true>, grid12, block, st, tm, a);
+        else launch_kernel(verify_slices<TD, DD, false>, grid12, block, st, tm, a);
+    }
     else launch_kernel(verify_locate<TD, DD>, dim3(a.n_jobs), block, st, tm, a);
     return hipGetLastError();
 }
@@ -949,6 +967,7 @@ hipError_t launch_sample_head(const VerifyArgs &a, hipStream_t st, Timing tm)
 hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
 {
     if (pass == 0) {
+        if (a.fused_head) return hipErrorInvalidValue;       // the slice kernel is the head then
         if (a.shards > 0) launch_kernel(verify_head_kernel<true>, dim3(a.B), dim3(kVBlock), st, tm, a);
         else launch_kernel(verify_head_kernel<false>, dim3(a.B), dim3(kVBlock), st, tm, a);
         return hipGetLastError();

@@ -18,10 +18,17 @@ def announce(msg):
     print(f"[case] {msg}", flush=True)
 
 
-def make(w, rounds=(0,), **kw):
+def make(w, rounds=(0,), fuse=None, **kw):
     gen = synth.RoundGenerator(w, DEV)
     tp = binding.Tapout(w.B, w.K, w.V, **kw)
+    if fuse is not None:
+        tp.set_option("fuse_head", fuse)
     return gen, tp, [gen.round(r) for r in rounds]
+
+
+# tapout_verify takes the accept decisions either in a launch of their own (0) or again in every workgroup of the
+# final-token slice kernel (1); left alone it picks by launch size, which at test sizes is always (1).
+FUSE = pytest.mark.parametrize("fuse", [0, 1])
 
 
 def random_arms(B, seed=0):
@@ -38,10 +45,11 @@ def random_arms(B, seed=0):
     ("zipf", dict(B=12)),
     ("ragged", dict(B=12)),
 ])
-def test_workload_parity_full_k(name, kw):
+@FUSE
+def test_workload_parity_full_k(name, kw, fuse):
     w = synth.scaled(synth.WORKLOADS[name], **kw)
-    announce(f"full-K {w}")
-    gen, tp, rounds = make(w, rounds=(0, 1))
+    announce(f"full-K {w} fuse_head={fuse}")
+    gen, tp, rounds = make(w, rounds=(0, 1), fuse=fuse)
     total = dict(stop_flagged=0, accept_flagged=0, icdf_flagged=0, sequences=0)
     for rnd in rounds:
         c = pu.check_round(tp, rnd)
@@ -52,11 +60,12 @@ def test_workload_parity_full_k(name, kw):
 
 
 @pytest.mark.parametrize("name,kw", [("tiny", {}), ("small", {}), ("llama3", dict(B=16)), ("ragged", dict(B=8))])
-def test_workload_parity_truncated(name, kw):
+@FUSE
+def test_workload_parity_truncated(name, kw, fuse):
     """Algorithm 1 as written: n_draft = stop position of the selected arm."""
     w = synth.scaled(synth.WORKLOADS[name], **kw)
-    announce(f"truncate {w}")
-    gen, tp, rounds = make(w, rounds=(2,))
+    announce(f"truncate {w} fuse_head={fuse}")
+    gen, tp, rounds = make(w, rounds=(2,), fuse=fuse)
     arm = random_arms(w.B, seed=w.index)
     c = pu.check_round(tp, rounds[0], arm=arm)
     announce(f"{name}: near-tie counts {c}")
@@ -122,6 +131,27 @@ def test_bit_identical_reruns():
                                y[k].cpu().view(torch.int32) if y[k].dtype == torch.float32 else y[k].cpu()), k
 
 
+def test_head_inside_the_slice_kernel_gives_the_same_bits():
+    """Both placements of the accept decisions run the same code: every output of tapout_verify is bit-identical,
+    also when the two alternate on one context (the band list of a job record is emptied by whoever appends next)."""
+    w = synth.scaled(synth.WORKLOADS["llama3"], B=24)
+    gen, tp, rounds = make(w, rounds=(0, 4))
+    bits = lambda t: t.cpu().view(torch.int32) if t.dtype == torch.float32 else t.cpu()
+    for rnd in rounds:
+        for arm in (None, random_arms(w.B, seed=5)):
+            outs = []
+            for fuse in (0, 1, 0, 1):
+                tp.set_option("fuse_head", fuse)
+                _, vf, _ = pu.gpu_round(tp, rnd, arm=arm)
+                outs.append({k: bits(v) for k, v in vf.items()})
+            for o in outs[1:]:
+                assert o.keys() == outs[0].keys()
+                for k in o:
+                    assert torch.equal(o[k], outs[0][k]), k
+    with pytest.raises(binding.TapoutError, match="fuse_head"):
+        tp.set_option("fuse_head", 2)
+
+
 # ---- degenerate rows --------------------------------------------------------------
 
 def degenerate_round(dtype):
@@ -151,10 +181,12 @@ def degenerate_round(dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
-def test_degenerate_rows(dtype):
+@FUSE
+def test_degenerate_rows(dtype, fuse):
     rnd = degenerate_round(dtype)
     B, K, V = rnd["draft"].shape
     tp = binding.Tapout(B, K, V)
+    tp.set_option("fuse_head", fuse)
     pu.check_round(tp, rnd)
     for a in range(3):
         pu.check_round(tp, rnd, arm=torch.full((B,), a, dtype=torch.int32, device=DEV))
@@ -239,12 +271,14 @@ def random_round(B, K, V, dtype, seed, sigma=2.5, k_len=None):
 
 
 @pytest.mark.parametrize("K,V,dtype", [(300, 600, torch.float32), (700, 20000, torch.bfloat16), (4096, 50, torch.bfloat16)])
-def test_long_drafts(K, V, dtype):
+@FUSE
+def test_long_drafts(K, V, dtype, fuse):
     """More draft positions than a workgroup has threads, and more rows than one LDS stage of partials holds: the
     per-sequence kernels walk them in stages.  K = 4096 is the largest K a context accepts."""
     B = 2 if K < 4096 else 1
     rnd = random_round(B, K, V, dtype, seed=K, sigma=1.0, k_len=[K, K - 37][:B])
     tp = binding.Tapout(B, K, V)
+    tp.set_option("fuse_head", fuse)
     arm = torch.tensor([1, 2][:B], dtype=torch.int32, device=DEV)
     c = pu.check_round(tp, rnd)                                          # full K: accept decisions far into the draft
     assert c["accept_flagged"] + c["icdf_flagged"] <= 1
@@ -293,7 +327,8 @@ def test_vocabulary_beyond_256_final_token_slices():
     assert (o["sampled_tok"].cpu().numpy()[~near] == osm["tok"][~near]).all()
 
 
-def test_bad_inputs_set_flags_and_fall_back():
+@FUSE
+def test_bad_inputs_set_flags_and_fall_back(fuse):
     rnd = degenerate_round(torch.float32)
     B, K, V = rnd["draft"].shape
     rnd["draft"][0, 1, 17] = float("nan")        # NaN in a draft row
@@ -305,6 +340,7 @@ def test_bad_inputs_set_flags_and_fall_back():
     n_draft[5] = 0
     n_draft[6] = K + 1
     tp = binding.Tapout(B, K, V)
+    tp.set_option("fuse_head", fuse)
     gds = tp.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"])
     gvf = tp.verify(rnd["target"], rnd["draft"], gds["lse"], gds["logq_tok"], rnd["draft_tok"], n_draft,
                     rnd["u_accept"], rnd["u_sample"], greedy=rnd["greedy"])

@@ -442,8 +442,11 @@ TAPOUT_API tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *pre
  *                 takes them again for its sequence (pays while that kernel
  *                 is a few workgroups per compute unit); 0 = separate launch;
  *                 -1 (default) = decide per call from the launch size
+ *   "profile_stride"  kernel timing (below) attaches events to every n-th
+ *                 launch of a selected kernel only, default 1: an event pair
+ *                 costs a few microseconds of the stream's time per launch
  * Results do not depend on these values except through the rounding of the
- * binary32 partial sums ("fuse_head": not at all).
+ * binary32 partial sums ("fuse_head", "profile_stride": not at all).
  */
 TAPOUT_API tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value);
 

@@ -36,6 +36,8 @@ struct tapout_ctx {
     int prof_cap = 0;
     std::vector<hipEvent_t> prof_start[TAPOUT_PROFILE_KINDS], prof_stop[TAPOUT_PROFILE_KINDS];
     int prof_used[TAPOUT_PROFILE_KINDS] = {0};
+    int prof_stride = 1;                                   // "profile_stride": events on every n-th launch of a kernel only
+    unsigned prof_tick[TAPOUT_PROFILE_KINDS] = {0};
     char err[256] = {0};
 };
 
@@ -112,7 +114,8 @@ const char *check_logits(const tapout_logits *l, const char *name, int V, int ro
 template <class F>
 hipError_t timed(tapout_ctx *ctx, int kind, F launch)
 {
-    const bool on = (ctx->prof_mask >> kind) & 1u && ctx->prof_used[kind] < ctx->prof_cap;
+    bool on = (ctx->prof_mask >> kind) & 1u && ctx->prof_used[kind] < ctx->prof_cap;
+    if (on && ctx->prof_stride > 1) on = ctx->prof_tick[kind]++ % ctx->prof_stride == 0;     // time one launch in prof_stride
     if (!on) return launch(Timing{});
     const int i = ctx->prof_used[kind];
     hipError_t e = launch(Timing{ctx->prof_start[kind][i], ctx->prof_stop[kind][i]});
@@ -125,7 +128,7 @@ void profile_release(tapout_ctx *ctx)
     for (int k = 0; k < TAPOUT_PROFILE_KINDS; ++k) {
         for (hipEvent_t ev : ctx->prof_start[k]) (void)hipEventDestroy(ev);
         for (hipEvent_t ev : ctx->prof_stop[k]) (void)hipEventDestroy(ev);
-        ctx->prof_start[k].clear(); ctx->prof_stop[k].clear(); ctx->prof_used[k] = 0;
+        ctx->prof_start[k].clear(); ctx->prof_stop[k].clear(); ctx->prof_used[k] = 0; ctx->prof_tick[k] = 0;
     }
     ctx->prof_mask = 0; ctx->prof_cap = 0;
 }
@@ -296,6 +299,9 @@ tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value
     } else if (!strcmp(name, "min_slice")) {
         if (value < 256) return fail(ctx, TAPOUT_EINVAL, "min_slice below 256 elements");
         ctx->min_slice = value;
+    } else if (!strcmp(name, "profile_stride")) {
+        if (value < 1) return fail(ctx, TAPOUT_EINVAL, "profile_stride below 1");
+        ctx->prof_stride = value;
     } else if (!strcmp(name, "fuse_head")) {
         if (value < -1 || value > 1) return fail(ctx, TAPOUT_EINVAL, "fuse_head outside {-1, 0, 1}");
         ctx->fuse_head = value;
@@ -647,6 +653,7 @@ tapout_status tapout_profile_read(tapout_ctx *ctx, int32_t kind, double *total_m
     }
     *total_ms = sum; *launches = ctx->prof_used[kind];
     ctx->prof_used[kind] = 0;
+    ctx->prof_tick[kind] = 0;
     return TAPOUT_OK;
 }
 

@@ -592,7 +592,7 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
     const int64_t slice_wgs = (int64_t)B * ((nsl + 3) / 4);
     const bool fused = ctx->fuse_head < 0 ? slice_wgs <= kFuseHeadMaxWgs : ctx->fuse_head == 1;
     RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, slice_vectors(V, target->dtype, nsplit), (int32_t)rows, n_draft, 1, ctx->part,
-                    fused ? ctx->jobs : nullptr};
+                    fused ? ctx->jobs : nullptr, draft_tok, K};     // the pass also picks up the logits of the drafted tokens
     hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_PASS, [&](Timing tm) { return launch_row_reduce(r, target->dtype, false, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "target pass launch");
 

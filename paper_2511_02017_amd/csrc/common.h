@@ -80,6 +80,8 @@ struct RowReduceArgs {
     int32_t len_mode;             // 0: row k active iff k < len[b] (NULL: all); 1: iff k <= clamp(len[b], 1, KK-1)
     Partial *out;                 // [n_rows, nsplit]
     JobRecord *clear_jobs;        // NULL, or [B]: the first workgroup of sequence b empties the band list of its job record
+    const int32_t *tok;           // NULL, or [B, tok_rows]: row k < tok_rows of sequence b has a token whose logit the
+    int32_t tok_rows;             //   slice holding it puts into its partial (pad[0]; NaN bits in all other partials)
 };
 // Streaming pass: one Partial per (row, slice).  Returns hipGetLastError() after enqueueing.
 hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st, Timing tm);
@@ -346,17 +348,133 @@ __device__ inline RowTotal merge_partials(const Partial *p /* LDS */, int nsplit
     return r;
 }
 
-// First index j in [cand, cand + window) with x_j == M (the lowest argmax index of the row).
-__device__ inline int32_t resolve_argmax(const void *row, int dtype, int32_t V, int32_t cand, float M)
+// ---- lane-parallel merge ------------------------------------------------------------------------
+// merge_partials walks the slices of a row one after the other: eight dependent LDS reads and rescalings, about
+// 1.4 us of a per-sequence kernel whose every other step is one memory round trip.  When the rows of a sequence
+// times the slice count rounded up to a power of two (P <= 16) fit one workgroup, thread t instead takes partial
+// (row t / P, slice t % P) straight from memory, and the P lanes of a row combine their records with DPP
+// exchanges in log2 P steps.  The combination is commutative, so both partners of an exchange, and in the end
+// all lanes of a group, hold the same bits; the first lane of the group puts the row's total into LDS.
+struct MergeElem {
+    float M;          // maximum (-inf: no finite element)
+    double S, T;      // base-2 sums relative to ref_of_max(M)
+    float v2;
+    int32_t cand;
+    float xt;         // logit of the row's token if this slice holds it, else NaN
+};
+struct RowSlot { RowTotal r; float xt; };
+
+__device__ inline bool merge_elem_empty(const MergeElem &e) { return e.M == -INFINITY && !(e.S != e.S); }
+
+__device__ inline MergeElem merge_pair(const MergeElem &a, const MergeElem &b)
+{
+    MergeElem o;
+    const bool ea = merge_elem_empty(a), eb = merge_elem_empty(b);
+    const float M = fmaxf(a.M, b.M);
+    const double R = (double)ref_of_max(M);
+    const double da = R - (double)ref_of_max(a.M), db = R - (double)ref_of_max(b.M);       // >= 0, integers
+    const int ia = da > 4000.0 ? 4000 : (int)da, ib = db > 4000.0 ? 4000 : (int)db;
+    // an empty side contributes exact zeros (its own sums are 0; 0 * d would be NaN for d = inf only, and d is finite)
+    const double Sa = ea ? 0.0 : ldexp(a.S, -ia), Sb = eb ? 0.0 : ldexp(b.S, -ib);
+    const double Ta = ea ? 0.0 : ldexp(a.T - da * a.S, -ia), Tb = eb ? 0.0 : ldexp(b.T - db * b.S, -ib);
+    o.M = M;
+    o.S = Sa + Sb;
+    o.T = Ta + Tb;
+    o.v2 = fmaxf(fmaxf(fminf(a.M, b.M), a.v2), b.v2);                        // second largest of the union, duplicates counted
+    o.cand = a.M == b.M ? min(a.cand, b.cand) : (a.M > b.M ? a.cand : b.cand);
+    o.xt = (a.xt == a.xt) ? a.xt : b.xt;                                     // at most one slice holds the token
+    return o;
+}
+
+template <int CTRL>
+__device__ inline MergeElem merge_elem_dpp(const MergeElem &e)
+{
+    auto mv = [](int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); };
+    MergeElem o;
+    o.M = __int_as_float(mv(__float_as_int(e.M)));
+    o.S = __hiloint2double(mv(__double2hiint(e.S)), mv(__double2loint(e.S)));
+    o.T = __hiloint2double(mv(__double2hiint(e.T)), mv(__double2loint(e.T)));
+    o.v2 = __int_as_float(mv(__float_as_int(e.v2)));
+    o.cand = mv(e.cand);
+    o.xt = __int_as_float(mv(__float_as_int(e.xt)));
+    return o;
+}
+
+// log2 of the group size P (1, 2, 4, 8 or 16) the lane-parallel merge would use for `rows` rows of `nsplit` slices,
+// or -1 if it does not apply (then the staged, sequential merge is used).
+__device__ inline int lane_merge_shift(int rows, int nsplit)
+{
+    if (nsplit > 16 || rows > 64) return -1;
+    const int sh = nsplit <= 1 ? 0 : 32 - __clz(nsplit - 1);
+    return (rows << sh) <= 256 ? sh : -1;
+}
+
+// Request this thread's partial: row `t >> sh`, slice `t & (P - 1)` of `rows` rows at `part` ([rows][nsplit]).
+// Threads without a partial get zeros.  (256-thread workgroups.)
+__device__ inline StageRegs lane_merge_issue(const Partial *part, int rows, int nsplit, int sh)
+{
+    StageRegs r;
+    r.w0 = r.w1 = u32x4{0u, 0u, 0u, 0u};
+    const int row = threadIdx.x >> sh, sl = threadIdx.x & ((1 << sh) - 1);
+    if (row < rows && sl < nsplit) {
+        const u32x4 *s = (const u32x4 *)(part + (int64_t)row * nsplit + sl);
+        r.w0 = s[0]; r.w1 = s[1];
+    }
+    return r;
+}
+
+// Combine and publish: sh_rows[row] for row < rows; ends with a barrier.
+__device__ inline void lane_merge_commit(RowSlot *sh_rows, const StageRegs &w, int rows, int nsplit, int sh)
+{
+    const int row = threadIdx.x >> sh, sl = threadIdx.x & ((1 << sh) - 1);
+    MergeElem e;
+    if (row < rows && sl < nsplit) {
+        e.M = __uint_as_float(w.w0.x); e.S = (double)__uint_as_float(w.w0.y); e.T = (double)__uint_as_float(w.w0.z);
+        e.v2 = __uint_as_float(w.w0.w); e.cand = (int32_t)w.w1.x; e.xt = __uint_as_float(w.w1.y);
+    } else {
+        e.M = -INFINITY; e.S = 0.0; e.T = 0.0; e.v2 = -INFINITY; e.cand = 0x7fffffff; e.xt = NAN;
+    }
+    if (merge_elem_empty(e)) { e.S = 0.0; e.T = 0.0; e.v2 = -INFINITY; e.cand = 0x7fffffff; }       // one image for every empty slice
+    // quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror: each pairs groups that already agree
+    if (sh >= 1) e = merge_pair(e, merge_elem_dpp<0xB1>(e));
+    if (sh >= 2) e = merge_pair(e, merge_elem_dpp<0x4E>(e));
+    if (sh >= 3) e = merge_pair(e, merge_elem_dpp<0x141>(e));
+    if (sh >= 4) e = merge_pair(e, merge_elem_dpp<0x140>(e));
+    if (row < rows && sl == 0) {
+        RowSlot o;
+        o.r.M = e.M; o.r.R = (double)ref_of_max(e.M); o.r.S = e.S; o.r.T = e.T; o.r.v2 = e.v2; o.r.cand = e.cand;
+        o.r.bad = !(e.S > 0.0) || !(e.S < INFINITY) || e.M == -INFINITY || e.M == INFINITY;
+        o.xt = e.xt;
+        sh_rows[row] = o;
+    }
+    __syncthreads();
+}
+
+// First index j in [cand, cand + window) with x_j == M (the lowest argmax index of the row), in two steps so
+// that a caller can put other work between the request and the use of the window.
+struct ArgmaxProbe { u32x4 w; bool loaded; };
+__device__ inline ArgmaxProbe argmax_issue(const void *row, int dtype, int32_t V, int32_t cand)
+{
+    ArgmaxProbe pr;
+    pr.w = u32x4{0u, 0u, 0u, 0u};
+    pr.loaded = false;
+    if (cand < 0 || cand >= V) return pr;
+    const int window = dtype == TAPOUT_F32 ? 4 : 8;
+    const char *p = (const char *)row + (int64_t)cand * (dtype == TAPOUT_F32 ? 4 : 2);
+    if ((((uintptr_t)p) & 15u) == 0 && cand + window <= V) {
+        // the usual case: the window is one of the 16-byte vectors the streaming pass loaded; one load
+        pr.w = *(const u32x4 *)p;
+        pr.loaded = true;
+    }
+    return pr;
+}
+__device__ inline int32_t argmax_finish(const ArgmaxProbe &pr, const void *row, int dtype, int32_t V, int32_t cand, float M)
 {
     if (cand < 0 || cand >= V) return 0;
     const int window = dtype == TAPOUT_F32 ? 4 : 8;
-    const int esz = dtype == TAPOUT_F32 ? 4 : 2;
-    const char *p = (const char *)row + (int64_t)cand * esz;
     float x[8];
-    if ((((uintptr_t)p) & 15u) == 0 && cand + window <= V) {
-        // the usual case: the window is one of the 16-byte vectors the streaming pass loaded; one load
-        const u32x4 w = *(const u32x4 *)p;
+    if (pr.loaded) {
+        const u32x4 w = pr.w;
         const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -374,6 +492,10 @@ __device__ inline int32_t resolve_argmax(const void *row, int dtype, int32_t V, 
     for (int i = 7; i >= 0; --i)
         if (x[i] == M) hit = cand + i;
     return hit;
+}
+__device__ inline int32_t resolve_argmax(const void *row, int dtype, int32_t V, int32_t cand, float M)
+{
+    return argmax_finish(argmax_issue(row, dtype, V, cand), row, dtype, V, cand, M);
 }
 
 #endif  // __HIPCC__

@@ -67,8 +67,13 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     int32_t tok0 = -1;
     if (want_tok && (int)threadIdx.x < K) tok0 = a.draft_tok[(int64_t)b * K + threadIdx.x];
     const int count0 = min(K, rows_per_stage) * a.nsplit;
+    // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
+    const int msh = SHARDED ? -1 : lane_merge_shift(K, a.nsplit);
+    RowSlot *sh_rows = (RowSlot *)sh_part;
+    static_assert(sizeof(RowSlot) * 64 <= sizeof(Partial) * kStageCap, "the row totals reuse the staging buffer");
     StageRegs st0;
     if constexpr (SHARDED) st0 = stage_issue_shards(a.part, (int64_t)a.B * K, (int64_t)b * K, a.nsplit, count0);
+    else if (msh >= 0) st0 = lane_merge_issue(a.part + (int64_t)b * K * a.nsplit, K, a.nsplit, msh);
     else st0 = stage_issue(a.part + (int64_t)b * K * a.nsplit, count0);
     asm volatile("" :: "v"(kb), "v"(arm), "v"(H_carry), "v"(tok0), "v"(st0.w0), "v"(st0.w1));
     // Second round trip: the logit of the drafted token (its address needs the token, not k_len: rows up to K
@@ -77,7 +82,8 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     if constexpr (!SHARDED)
         if (want_tok && (int)threadIdx.x < K && tok0 >= 0 && tok0 < a.V)
             xtok_first = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, threadIdx.x), a.dtype, tok0);
-    stage_commit(sh_part, st0, count0);
+    if (msh >= 0) lane_merge_commit(sh_rows, st0, K, a.nsplit, msh);
+    else stage_commit(sh_part, st0, count0);
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
     const bool arm_ok = arm >= 0 && arm < a.n_arms;
     const int rule_b = arm_ok ? pick8(a.rule, arm) : -1;
@@ -107,7 +113,7 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t i = (int64_t)b * K + k;
             const void *row = SHARDED ? nullptr : row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
-            RowTotal r = merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
+            const RowTotal r = msh >= 0 ? sh_rows[k].r : merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
             int32_t top1 = 0;
             if constexpr (SHARDED) top1 = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;             // a shard's argmax is exact and global
             else top1 = a.top1_id ? resolve_argmax(row, a.dtype, a.V, r.cand, r.M) : 0;            // loads overlap the math below

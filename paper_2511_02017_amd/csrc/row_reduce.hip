@@ -216,6 +216,15 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
     }
     if (a.clear_jobs && split == 0 && k == 0 && tid == 0) a.clear_jobs[b].band_cnt = 0;
     if (k >= n_active) return;
+    // The row's token, if it has one.  Requested as a vector load (the index carries a zero the compiler cannot
+    // see through): a scalar load from memory would hold up the first wait for the kernel arguments and with it
+    // the first logits; this one returns with the first batch.
+    int tk = -1;
+    if (a.tok && k < a.tok_rows) {
+        int zero;
+        asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
+        tk = a.tok[(int64_t)b * a.tok_rows + k + zero];
+    }
     const char *rowp = (const char *)a.base + ((int64_t)b * a.stride_b + (int64_t)k * a.stride_k) * Elem<DT>::size;
     int head, nvec, tail;
     row_geometry<DT>(rowp, a.V, head, nvec, tail);
@@ -288,7 +297,10 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
         for (int w = 1; w < kBlock / kWave; ++w) top2_merge(b1, b2, sh_f[2][w], sh_f[3][w]);
         p.v2 = b2;
         p.cand = min(min(sh_i[0], sh_i[1]), min(sh_i[2], sh_i[3]));
-        p.pad[0] = p.pad[1] = p.pad[2] = 0;
+        p.pad[0] = 0x7fc00000; p.pad[1] = p.pad[2] = 0;
+        // elements of this slice: [e0, e1); every index of the row lies in exactly one slice
+        const int e0 = split == 0 ? 0 : head + v0 * VEC, e1 = split == a.nsplit - 1 ? a.V : head + v1e * VEC;
+        if (tk >= e0 && tk < e1) p.pad[0] = __float_as_int(load_elem<DT>(rowp, tk));
         a.out[(int64_t)row * a.nsplit + split] = p;
     }
 }

@@ -145,6 +145,13 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     // (Rows beyond n_draft hold stale partials and unused tokens: read, never used.)
     int32_t tok0 = -1;
     float u0 = 0.0f, lq0 = 0.0f, dl0 = 0.0f;
+    // n_draft and greedy are requested here too, as vector loads (the index carries a zero the compiler cannot
+    // see through): a scalar load would share its counter with the loads of kernel arguments, and the first wait
+    // for one of those would wait for memory.  Their first use comes after the staging barrier.
+    int zero;
+    asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
+    int n = a.n_draft[b + zero];
+    uint8_t greedy_raw = a.greedy ? a.greedy[b + zero] : (uint8_t)0;
     if ((int)threadIdx.x < K) {
         const int64_t i = (int64_t)b * K + threadIdx.x;
         tok0 = a.draft_tok[i];
@@ -152,25 +159,31 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         lq0 = a.logq_tok[i];
         if (a.draft_lse) dl0 = a.draft_lse[i];      // the final token's job wants it for row m: no dependent load later
     }
+    // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
+    const int msh = SHARDED ? -1 : lane_merge_shift(K + 1, a.nsplit);
+    RowSlot *sh_rows = (RowSlot *)sh_part;
+    static_assert(sizeof(RowSlot) * 64 <= sizeof(Partial) * kStageCap, "the row totals reuse the staging buffer");
     if constexpr (SHARDED) {
         const int c0 = min(K + 1, rows_per_stage) * a.nsplit;
         stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1), a.nsplit, c0), c0);
+    } else if (msh >= 0) {
+        lane_merge_commit(sh_rows, lane_merge_issue(a.part + (int64_t)b * (K + 1) * a.nsplit, K + 1, a.nsplit, msh), K + 1, a.nsplit, msh);
     } else {
         stage_partials(sh_part, a.part + (int64_t)b * (K + 1) * a.nsplit, min(K + 1, rows_per_stage) * a.nsplit);
     }
-    int n = a.n_draft[b];
     uint32_t f0 = 0;
+    n = __builtin_amdgcn_readfirstlane(n);
     if (n < 1 || n > K) { f0 |= TAPOUT_FLAG_BAD_NDRAFT; n = n < 1 ? 1 : K; }
-    const bool greedy = a.greedy ? a.greedy[b] != 0 : false;
+    const bool greedy = __builtin_amdgcn_readfirstlane((int)greedy_raw) != 0;
     SampleJob job;
     job.kind = 0; job.row = 0; job.ref_p = 0.0f; job.ref_q = 0.0f; job.lam = 0.0;
     if (threadIdx.x == 0) { *sh_flags = f0; sh_bcast[4] = 0; }
     const bool need_top1 = writer || greedy;
     int last_k = -1; float last_M = 0.0f, last_dl = 0.0f; int32_t last_top1 = 0; double last_lse = 0.0;   // the last row this thread merged
+    bool acc_mine = false; uint32_t f_mine = 0;      // its accept decision and flags (used on the lane-merge path)
     for (int k0 = 0; k0 <= n; k0 += rows_per_stage) {
         const int k1 = min(n + 1, k0 + rows_per_stage);
         const int kmine = k0 + threadIdx.x;
-        float xtok0 = 0.0f;
         if (k0 > 0) {                               // further stages (K + 1 > rows_per_stage): load late
             tok0 = -1;
             if (kmine < k1 && kmine < n) {
@@ -186,20 +199,22 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + k0) * a.nsplit, (k1 - k0) * a.nsplit);
             }
         }
-        if constexpr (!SHARDED)
-            if (kmine < k1 && kmine < n && tok0 >= 0 && tok0 < a.V)
-                xtok0 = load_elem_rt(row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, kmine), a.t_dtype, tok0);
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t it = (int64_t)b * (K + 1) + k;
             const void *row = SHARDED ? nullptr : row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, k);
-            RowTotal r = merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
+            const RowTotal r = msh >= 0 ? sh_rows[k].r : merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
+            // the argmax window is requested here and looked at after the logarithm (greedy sequences need the
+            // argmax for their decisions, the others only for the outputs)
             int32_t top1 = 0;
+            ArgmaxProbe probe;
             if constexpr (SHARDED) top1 = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;                // a shard's argmax is exact and global
-            else top1 = need_top1 ? resolve_argmax(row, a.t_dtype, a.V, r.cand, r.M) : 0;             // loads overlap the math below
+            else if (need_top1) probe = argmax_issue(row, a.t_dtype, a.V, r.cand);
             uint32_t f = 0;
             double lse_d = NAN;
             if (r.bad) f |= TAPOUT_FLAG_BAD_ROW;
             else lse_d = (r.R + log2(r.S)) * kLn2;
+            if constexpr (!SHARDED)
+                if (need_top1) top1 = argmax_finish(probe, row, a.t_dtype, a.V, r.cand, r.M);
             if (writer) {
                 if (a.target_lse) a.target_lse[it] = (float)lse_d;
                 if (a.target_top1) a.target_top1[it] = top1;
@@ -207,21 +222,20 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
             if (k < n) {
                 const int64_t i = (int64_t)b * K + k;
                 int32_t t = tok0;
-                float xt = xtok0, u = u0, lq = lq0;
+                float u = u0, lq = lq0;
                 last_dl = dl0;
                 if (k != kmine) {                              // more rows than threads: load late
                     t = a.draft_tok[i]; u = a.u_accept[i]; lq = a.logq_tok[i];
                     if (a.draft_lse) last_dl = a.draft_lse[i];
-                    if constexpr (!SHARDED)
-                        if (t >= 0 && t < a.V) xt = load_elem_rt(row, a.t_dtype, t);
                 }
-                if constexpr (SHARDED) {                       // the shard that owns the token sent its logit, the others NaN
-                    xt = NAN;
+                // the slice (or vocabulary shard) that holds the token put its logit into its partial, the others NaN
+                float xt = NAN;
+                if (msh >= 0) xt = sh_rows[k].xt;
+                else
                     for (int g = 0; g < a.nsplit; ++g) {
                         const float v = __int_as_float(sh_part[(k - k0) * a.nsplit + g].pad[0]);
                         if (v == v) xt = v;
                     }
-                }
                 bool acc = false;
                 float lp = NAN;
                 if (t < 0 || t >= a.V) f |= TAPOUT_FLAG_BAD_TOKEN;
@@ -231,30 +245,56 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                     else acc = (double)u < exp((double)lp - (double)lq);
                 }
                 if (writer && a.logp_tok) a.logp_tok[i] = lp;
-                sh_dec[k] = acc ? 1 : 0;
+                acc_mine = acc;
+                if (msh < 0) sh_dec[k] = acc ? 1 : 0;
             }
             last_k = k; last_M = r.M; last_top1 = top1; last_lse = lse_d;
-            if (f) atomicOr(sh_flags, f);
+            f_mine = f;
+            if (msh < 0 && f) atomicOr(sh_flags, f);
         }
     }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const uint32_t f = *sh_flags;
-        const bool flagged = f & (TAPOUT_FLAG_BAD_NDRAFT | TAPOUT_FLAG_BAD_TOKEN | TAPOUT_FLAG_BAD_ROW);
-        int m = 0;
-        if (!flagged)
-            while (m < n && sh_dec[m] != 0) ++m;
-        sh_bcast[0] = m;
-        sh_bcast[1] = flagged ? 1 : 0;
-        sh_bcast[2] = (int32_t)f;
+    constexpr uint32_t kFatal = TAPOUT_FLAG_BAD_NDRAFT | TAPOUT_FLAG_BAD_TOKEN | TAPOUT_FLAG_BAD_ROW;
+    if (msh >= 0) {
+        // Lane-merge path: row k was thread k's, so the rows are lanes of the first wavefront.  Ballots give the
+        // first rejection and the flags, lane m hands over what the job needs of row m, one barrier publishes it.
+        if (threadIdx.x < kWave) {
+            const uint64_t acc_mask = __builtin_amdgcn_ballot_w64((int)threadIdx.x < n && acc_mine);
+            uint32_t fa = f0;
+            if (__builtin_amdgcn_ballot_w64((f_mine & TAPOUT_FLAG_BAD_TOKEN) != 0)) fa |= TAPOUT_FLAG_BAD_TOKEN;
+            if (__builtin_amdgcn_ballot_w64((f_mine & TAPOUT_FLAG_BAD_ROW) != 0)) fa |= TAPOUT_FLAG_BAD_ROW;
+            // first draft position that was not accepted, n if there is none (n <= 63 here)
+            const int mm = (fa & kFatal) ? 0 : __builtin_ctzll(~acc_mask | (1ull << n));
+            const int Mb = __builtin_amdgcn_readlane(__float_as_int(last_M), mm);
+            const int tb = __builtin_amdgcn_readlane(last_top1, mm);
+            const int db = __builtin_amdgcn_readlane(__float_as_int(last_dl), mm);
+            const int lh = __builtin_amdgcn_readlane(__double2hiint(last_lse), mm);
+            const int ll = __builtin_amdgcn_readlane(__double2loint(last_lse), mm);
+            if (threadIdx.x == 0) {
+                sh_bcast[0] = mm; sh_bcast[1] = (fa & kFatal) ? 1 : 0; sh_bcast[2] = (int32_t)fa;
+                sh_bcast[4] = 1; sh_bcast[5] = Mb; sh_bcast[6] = tb; sh_bcast[7] = db;
+                *sh_lse = __hiloint2double(lh, ll);
+            }
+        }
+        __syncthreads();
+    } else {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const uint32_t f = *sh_flags;
+            int m = 0;
+            if (!(f & kFatal))
+                while (m < n && sh_dec[m] != 0) ++m;
+            sh_bcast[0] = m;
+            sh_bcast[1] = (f & kFatal) ? 1 : 0;
+            sh_bcast[2] = (int32_t)f;
+        }
+        __syncthreads();
+        // maximum and argmax of row m: from the thread that merged it, if it still holds them
+        if (last_k == sh_bcast[0]) { sh_bcast[4] = 1; sh_bcast[5] = __float_as_int(last_M); sh_bcast[6] = last_top1; sh_bcast[7] = __float_as_int(last_dl); *sh_lse = last_lse; }
+        __syncthreads();
     }
-    __syncthreads();
     const int m = sh_bcast[0];                   // a flagged sequence has m = 0 and emits the argmax of row 0
     const bool flagged = sh_bcast[1] != 0;
     const uint32_t f = (uint32_t)sh_bcast[2];
-    // maximum and argmax of row m: from the thread that merged it, if it still holds them
-    if (last_k == m) { sh_bcast[4] = 1; sh_bcast[5] = __float_as_int(last_M); sh_bcast[6] = last_top1; sh_bcast[7] = __float_as_int(last_dl); *sh_lse = last_lse; }
-    __syncthreads();
     float Mm, dl_m = 0.0f; int32_t top1m; double lse_m;
     if (sh_bcast[4]) {
         Mm = __int_as_float(sh_bcast[5]); top1m = sh_bcast[6]; dl_m = __int_as_float(sh_bcast[7]); lse_m = *sh_lse;

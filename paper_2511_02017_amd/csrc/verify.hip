@@ -59,17 +59,23 @@ constexpr double kMagic = 6755399441055744.0;          // 1.5 * 2^52: adding it 
 
 // exp(x - ref) for x <= ref + small.  neg_ref_c = -ref * 256/ln2; lo = ref - 700 as binary32: inputs
 // below it (masked -inf logits, NaN) are treated as ref - 700, i.e. as weight 1e-304.
-__device__ inline double exp_fast(float x, double neg_ref_c, float lo, const double *T)
+// c2 is kExpC2 and top is +inf: a caller with many exponentials in a row keeps them in vector registers (an
+// instruction takes one scalar constant only, and the compiler would otherwise move c2 into a register before
+// every use; with a top it cannot see through, the clamp stays a med3, which unlike fmaxf needs no quieting of
+// its input first).
+__device__ inline double exp_fast(float x, double neg_ref_c, float lo, const double *T, double c2 = kExpC2, float top = INFINITY)
 {
-    const double xd = (double)fmaxf(x, lo);
+    const double xd = (double)__builtin_amdgcn_fmed3f(x, lo, top);      // max(x, lo) for numbers, lo for NaN
     const double t = fma(xd, kExpC, neg_ref_c);          // (x - ref) * 256/ln2
     const double tm = t + kMagic;
     const int ni = __double2loint(tm);                   // round(t) in two's complement
     const double rs = t - (tm - kMagic);                 // remainder in units of ln2/256, |rs| <= 1/2
-    const double q = rs * fma(rs, fma(rs, kExpC3, kExpC2), kExpC1);
+    const double q = rs * fma(rs, fma(rs, kExpC3, c2), kExpC1);
     const double tk = T[ni & 255];
     const double e = fma(tk, q, tk);                     // in [1, 2): scale by 2^(ni >> 8) through the exponent field
-    return __hiloint2double(__double2hiint(e) + (int)((uint32_t)(ni >> 8) << 20), __double2loint(e));
+    int hi;                                              // high word + ((ni >> 8) << 20), as mask and one shift-add
+    asm("v_lshl_add_u32 %0, %1, 12, %2" : "=v"(hi) : "v"(ni & (int)0xffffff00), "v"(__double2hiint(e)));
+    return __hiloint2double(hi, __double2loint(e));
 }
 
 struct ExpRef {
@@ -423,6 +429,9 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
     ExpRef rp, rq;
     rp.set((double)job.ref_p); rq.set((double)job.ref_q);
     const double lam = job.lam, band = kEta * job.lam;
+    double c2 = kExpC2;
+    float top = INFINITY;
+    asm volatile("" : "+v"(c2), "+v"(top));               // stay in vector registers through the loop
     // Ds = sum of b carrying the sign of a - L~ b, so that D = (B + Ds) / 2 without a select per element (an
     // element with a == L~ b lands in D; it is in the band, so U covers it).  Elements inside the band are a
     // handful per row at most: their sum and their list are kept under a branch a wavefront almost never enters.
@@ -438,8 +447,8 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
         if (resid) {
 #pragma unroll
             for (int i = 0; i < kPer; ++i) {
-                const double av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT);
-                const double bv = exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT);
+                const double av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
+                const double bv = exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT, c2, top);
                 const double diff = fma(-lam, bv, av);
                 A += av;
                 Bs += bv;
@@ -457,7 +466,7 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < kPer; ++i) A += exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT);
+            for (int i = 0; i < kPer; ++i) A += exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
         }
         if (c + 1 < kChunks) {
 #pragma unroll

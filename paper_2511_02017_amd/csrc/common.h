@@ -351,9 +351,9 @@ __device__ inline RowTotal merge_partials(const Partial *p /* LDS */, int nsplit
 // ---- lane-parallel merge ------------------------------------------------------------------------
 // merge_partials walks the slices of a row one after the other: eight dependent LDS reads and rescalings, about
 // 1.4 us of a per-sequence kernel whose every other step is one memory round trip.  When the rows of a sequence
-// times the slice count rounded up to a power of two (P <= 16) fit one workgroup, thread t instead takes partial
-// (row t / P, slice t % P) straight from memory, and the P lanes of a row combine their records with DPP
-// exchanges in log2 P steps.  The combination is commutative, so both partners of an exchange, and in the end
+// times the slice count rounded up to a power of two (P <= 16) fit two passes of one workgroup, thread t instead
+// takes partial (row t / P, slice t % P) straight from memory (and the partial 256 / P rows further on in the
+// second pass), and the P lanes of a row combine their records with DPP exchanges in log2 P steps.  The combination is commutative, so both partners of an exchange, and in the end
 // all lanes of a group, hold the same bits; the first lane of the group puts the row's total into LDS.
 struct MergeElem {
     float M;          // maximum (-inf: no finite element)
@@ -406,27 +406,32 @@ __device__ inline int lane_merge_shift(int rows, int nsplit)
 {
     if (nsplit > 16 || rows > 64) return -1;
     const int sh = nsplit <= 1 ? 0 : 32 - __clz(nsplit - 1);
-    return (rows << sh) <= 256 ? sh : -1;
+    return (rows << sh) <= 512 ? sh : -1;
 }
 
-// Request this thread's partial: row `t >> sh`, slice `t & (P - 1)` of `rows` rows at `part` ([rows][nsplit]).
-// Threads without a partial get zeros.  (256-thread workgroups.)
-__device__ inline StageRegs lane_merge_issue(const Partial *part, int rows, int nsplit, int sh)
+// Request this thread's partials: row `t >> sh` (first pass) and row `(t >> sh) + (256 >> sh)` (second pass),
+// slice `t & (P - 1)`, of `rows` rows at `part` ([rows][nsplit]).  Threads without a partial get zeros.
+// (256-thread workgroups.)
+struct LaneRegs { StageRegs p[2]; };
+__device__ inline LaneRegs lane_merge_issue(const Partial *part, int rows, int nsplit, int sh)
 {
-    StageRegs r;
-    r.w0 = r.w1 = u32x4{0u, 0u, 0u, 0u};
-    const int row = threadIdx.x >> sh, sl = threadIdx.x & ((1 << sh) - 1);
-    if (row < rows && sl < nsplit) {
-        const u32x4 *s = (const u32x4 *)(part + (int64_t)row * nsplit + sl);
-        r.w0 = s[0]; r.w1 = s[1];
+    LaneRegs r;
+    const int sl = threadIdx.x & ((1 << sh) - 1);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        r.p[q].w0 = r.p[q].w1 = u32x4{0u, 0u, 0u, 0u};
+        const int row = (threadIdx.x >> sh) + q * (256 >> sh);
+        if (row < rows && sl < nsplit) {
+            const u32x4 *s = (const u32x4 *)(part + (int64_t)row * nsplit + sl);
+            r.p[q].w0 = s[0]; r.p[q].w1 = s[1];
+        }
     }
     return r;
 }
 
-// Combine and publish: sh_rows[row] for row < rows; ends with a barrier.
-__device__ inline void lane_merge_commit(RowSlot *sh_rows, const StageRegs &w, int rows, int nsplit, int sh)
+__device__ inline void lane_merge_pass(RowSlot *sh_rows, const StageRegs &w, int row, int rows, int nsplit, int sh)
 {
-    const int row = threadIdx.x >> sh, sl = threadIdx.x & ((1 << sh) - 1);
+    const int sl = threadIdx.x & ((1 << sh) - 1);
     MergeElem e;
     if (row < rows && sl < nsplit) {
         e.M = __uint_as_float(w.w0.x); e.S = (double)__uint_as_float(w.w0.y); e.T = (double)__uint_as_float(w.w0.z);
@@ -447,6 +452,13 @@ __device__ inline void lane_merge_commit(RowSlot *sh_rows, const StageRegs &w, i
         o.xt = e.xt;
         sh_rows[row] = o;
     }
+}
+
+// Combine and publish: sh_rows[row] for row < rows; ends with a barrier.
+__device__ inline void lane_merge_commit(RowSlot *sh_rows, const LaneRegs &w, int rows, int nsplit, int sh)
+{
+    lane_merge_pass(sh_rows, w.p[0], threadIdx.x >> sh, rows, nsplit, sh);
+    if ((256 >> sh) < rows) lane_merge_pass(sh_rows, w.p[1], (threadIdx.x >> sh) + (256 >> sh), rows, nsplit, sh);   // uniform
     __syncthreads();
 }
 

@@ -72,17 +72,19 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     RowSlot *sh_rows = (RowSlot *)sh_part;
     static_assert(sizeof(RowSlot) * 64 <= sizeof(Partial) * kStageCap, "the row totals reuse the staging buffer");
     StageRegs st0;
+    LaneRegs ln0;
+    st0.w0 = st0.w1 = ln0.p[0].w0 = ln0.p[0].w1 = ln0.p[1].w0 = ln0.p[1].w1 = u32x4{0u, 0u, 0u, 0u};
     if constexpr (SHARDED) st0 = stage_issue_shards(a.part, (int64_t)a.B * K, (int64_t)b * K, a.nsplit, count0);
-    else if (msh >= 0) st0 = lane_merge_issue(a.part + (int64_t)b * K * a.nsplit, K, a.nsplit, msh);
+    else if (msh >= 0) ln0 = lane_merge_issue(a.part + (int64_t)b * K * a.nsplit, K, a.nsplit, msh);
     else st0 = stage_issue(a.part + (int64_t)b * K * a.nsplit, count0);
-    asm volatile("" :: "v"(kb), "v"(arm), "v"(H_carry), "v"(tok0), "v"(st0.w0), "v"(st0.w1));
+    asm volatile("" :: "v"(kb), "v"(arm), "v"(H_carry), "v"(tok0), "v"(st0.w0), "v"(st0.w1), "v"(ln0.p[0].w0), "v"(ln0.p[0].w1), "v"(ln0.p[1].w0), "v"(ln0.p[1].w1));
     // Second round trip: the logit of the drafted token (its address needs the token, not k_len: rows up to K
     // exist), in flight while the partials go through LDS and are merged.
     float xtok_first = 0.0f;
     if constexpr (!SHARDED)
         if (want_tok && (int)threadIdx.x < K && tok0 >= 0 && tok0 < a.V)
             xtok_first = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, threadIdx.x), a.dtype, tok0);
-    if (msh >= 0) lane_merge_commit(sh_rows, st0, K, a.nsplit, msh);
+    if (msh >= 0) lane_merge_commit(sh_rows, ln0, K, a.nsplit, msh);
     else stage_commit(sh_part, st0, count0);
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
     const bool arm_ok = arm >= 0 && arm < a.n_arms;

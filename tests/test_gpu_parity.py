@@ -109,7 +109,10 @@ def test_slice_counts_do_not_change_decisions():
     w = synth.scaled(synth.WORKLOADS["small"], B=6)
     gen, tp, rounds = make(w)
     ref = None
-    for wgs, min_slice in ((1, 4096), (64, 256), (4096, 256), (65536, 256), (4096, 1 << 20)):
+    # slices per row 1 .. 125: one to sixteen take the lane-parallel merge of the per-sequence kernels (groups of
+    # 1, 2, 4, 8, 16 lanes, also with empty lanes: 3, 5, 11 slices), more than sixteen the staged sequential one
+    for wgs, min_slice in ((1, 4096), (64, 256), (100, 256), (150, 256), (270, 256), (600, 256), (864, 256), (920, 256),
+                           (4096, 256), (65536, 256), (4096, 1 << 20)):
         tp.set_option("wgs_target", wgs)
         tp.set_option("min_slice", min_slice)
         pu.check_round(tp, rounds[0])

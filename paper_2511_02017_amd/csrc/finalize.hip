@@ -84,6 +84,7 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     if constexpr (!SHARDED)
         if (want_tok && (int)threadIdx.x < K && tok0 >= 0 && tok0 < a.V)
             xtok_first = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, threadIdx.x), a.dtype, tok0);
+    if (threadIdx.x == 0) sh_flags = 0;                       // ahead of the barrier in the commit: rows of other wavefronts OR into it
     if (msh >= 0) lane_merge_commit(sh_rows, ln0, K, a.nsplit, msh);
     else stage_commit(sh_part, st0, count0);
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     // token-level bandits: the arm of step k is arm[b, k]
     const bool sweep = tok_mode ? (a.round_entropy != nullptr)
                                 : (rule_b == TAPOUT_RULE_SVIP_DIFF || rule_b == TAPOUT_RULE_ADAEDL);
-    if (threadIdx.x == 0) sh_flags = 0;
+    bool fire_mine = false; uint32_t f_mine = 0;      // this thread's row: rule fired, flags (used on the lane-merge path)
     for (int k0 = 0; k0 < kb; k0 += rows_per_stage) {
         const int k1 = min(kb, k0 + rows_per_stage);
         const int kmine = k0 + threadIdx.x;                   // first (usually only) row of this thread in the stage
@@ -116,9 +117,11 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
             const int64_t i = (int64_t)b * K + k;
             const void *row = SHARDED ? nullptr : row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
             const RowTotal r = msh >= 0 ? sh_rows[k].r : merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
+            // the argmax window is requested here and looked at after the signals are formed
             int32_t top1 = 0;
+            ArgmaxProbe probe;
             if constexpr (SHARDED) top1 = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;             // a shard's argmax is exact and global
-            else top1 = a.top1_id ? resolve_argmax(row, a.dtype, a.V, r.cand, r.M) : 0;            // loads overlap the math below
+            else if (a.top1_id) probe = argmax_issue(row, a.dtype, a.V, r.cand);
             uint32_t f = 0;
             float lse, H, p1, p2, mg;
             double lse_d = NAN;
@@ -139,6 +142,8 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
             if (a.p_top1) a.p_top1[i] = p1;
             if (a.p_top2) a.p_top2[i] = p2;
             if (a.margin) a.margin[i] = mg;
+            if constexpr (!SHARDED)
+                if (a.top1_id) top1 = argmax_finish(probe, row, a.dtype, a.V, r.cand, r.M);
             if (a.top1_id) a.top1_id[i] = top1;
             if (a.draft_tok && a.logq_tok) {
                 int32_t t = tok0;
@@ -169,10 +174,27 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
                     const bool fire = ok_k && rule_fires(rule_k, pick8(a.threshold, arm_k), H, p1, mg);
                     if (a.stop_fired) a.stop_fired[i] = fire ? 1 : 0;
                     sh_dec[k] = fire ? 1 : 0;                  // k < K <= kScanCap
+                    fire_mine = fire;
                 }
             }
+            f_mine = f;
             if (f) atomicOr(&sh_flags, f);
         }
+    }
+    if (msh >= 0 && !sweep) {
+        // Lane-merge path without a second sweep: row k was thread k's, so the rows are lanes of the first wavefront
+        // and ballots give the stop position and the flags; no barrier, no scan through LDS.
+        if (threadIdx.x < kWave) {
+            const uint64_t fired = __builtin_amdgcn_ballot_w64((int)threadIdx.x < kb && fire_mine);
+            uint32_t fa = 0;
+            if (__builtin_amdgcn_ballot_w64((f_mine & TAPOUT_FLAG_BAD_ROW) != 0)) fa |= TAPOUT_FLAG_BAD_ROW;
+            if (__builtin_amdgcn_ballot_w64((f_mine & TAPOUT_FLAG_BAD_TOKEN) != 0)) fa |= TAPOUT_FLAG_BAD_TOKEN;
+            if (threadIdx.x == 0) {
+                if (a.flags) a.flags[b] = fa;
+                if (a.arm && a.n_stop) a.n_stop[b] = fired ? __builtin_ctzll(fired) + 1 : kb;
+            }
+        }
+        return;
     }
     __syncthreads();                       // orders the LDS / scratch writes above before the scan
     if (sweep) {

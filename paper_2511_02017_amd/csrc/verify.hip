@@ -165,6 +165,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         lq0 = a.logq_tok[i];
         if (a.draft_lse) dl0 = a.draft_lse[i];      // the final token's job wants it for row m: no dependent load later
     }
+    if (threadIdx.x == 0) { *sh_flags = 0; sh_bcast[4] = 0; }     // ahead of the staging barrier: rows of other wavefronts OR into the flags
     // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
     const int msh = SHARDED ? -1 : lane_merge_shift(K + 1, a.nsplit);
     RowSlot *sh_rows = (RowSlot *)sh_part;
@@ -183,7 +184,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     const bool greedy = __builtin_amdgcn_readfirstlane((int)greedy_raw) != 0;
     SampleJob job;
     job.kind = 0; job.row = 0; job.ref_p = 0.0f; job.ref_q = 0.0f; job.lam = 0.0;
-    if (threadIdx.x == 0) { *sh_flags = f0; sh_bcast[4] = 0; }
+    if (threadIdx.x == 0 && f0) atomicOr(sh_flags, f0);
     const bool need_top1 = writer || greedy;
     int last_k = -1; float last_M = 0.0f, last_dl = 0.0f; int32_t last_top1 = 0; double last_lse = 0.0;   // the last row this thread merged
     bool acc_mine = false; uint32_t f_mine = 0;      // its accept decision and flags (used on the lane-merge path)

@@ -17,7 +17,11 @@
  *   Asynchrony.  Calls enqueue kernels on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and return without waiting.  Calls on
  *     one context must be issued in stream order on one stream at a time: the
- *     context owns scratch memory that consecutive calls reuse.
+ *     context owns scratch memory that consecutive calls reuse.  The four
+ *     calls of a round (and the sharded variants) only launch kernels — no
+ *     allocation, no memset, no copy, no host synchronisation — so they can
+ *     be captured into a HIP graph and replayed; launch shapes are fixed at
+ *     capture time from the arguments and the context's options.
  *   Memory.  Device memory is allocated in tapout_create and released in
  *     tapout_destroy, never in between.
  *   Errors.  Every call returns a tapout_status.  Argument errors are found on

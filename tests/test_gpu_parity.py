@@ -134,6 +134,59 @@ def test_bit_identical_reruns():
                                y[k].cpu().view(torch.int32) if y[k].dtype == torch.float32 else y[k].cpu()), k
 
 
+@pytest.mark.parametrize("policy", [binding.UCB1, binding.TS_BETA])
+def test_rounds_replayed_from_hip_graphs_match_eager_rounds(policy):
+    """The four calls of a round capture into a HIP graph (they launch kernels only: no allocation, no memset, no
+    host synchronisation).  Nine rounds are run eagerly on one context and replayed from three captured graphs on
+    a second one, with eager work and synchronisations between the replays; every replay's outputs and the final
+    bandit state must carry the eager run's bits."""
+    w = synth.scaled(synth.WORKLOADS["llama3"], B=12)
+    gen = synth.RoundGenerator(w, DEV)
+    rounds = [gen.round(r) for r in range(3)]
+    bits = lambda t: t.cpu().view(torch.int32).clone() if t.dtype == torch.float32 else t.cpu().clone()
+    order = [0, 1, 2, 2, 0, 1, 1, 0, 2]
+
+    def context():
+        tp = binding.Tapout(w.B, w.K, w.V, policy=policy)
+        prep = [tp.prepare_round(r, truncate=True, u_ts=r["u_ts"] if policy == binding.TS_BETA else None) for r in rounds]
+        return tp, prep
+
+    def snapshot(outs):
+        d = {"arm": bits(outs["arm"])}
+        d.update({"d_" + k: bits(v) for k, v in outs["draft"].items()})
+        d.update({"v_" + k: bits(v) for k, v in outs["verify"].items()})
+        return d
+
+    tp_e, prep_e = context()
+    stream = torch.cuda.Stream()
+    expect = []
+    with torch.cuda.stream(stream):
+        for i in order:
+            prep_e[i][0](stream.cuda_stream)
+            stream.synchronize()
+            expect.append(snapshot(prep_e[i][1]))
+    state_e = tp_e.bandit_get_state()
+
+    tp_g, prep_g = context()
+    graphs = []
+    for launch, _ in prep_g:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            launch(torch.cuda.current_stream().cuda_stream)
+        graphs.append(g)
+    scratch = torch.zeros(1 << 20, device=DEV)
+    with torch.cuda.stream(stream):
+        for step, i in enumerate(order):
+            graphs[i].replay()
+            scratch.add_(1.0)                                  # the program's own eager work between replays
+            stream.synchronize()
+            got = snapshot(prep_g[i][1])
+            for k, v in expect[step].items():
+                assert torch.equal(got[k], v), (step, i, k)
+    for a, b in zip(tp_g.bandit_get_state(), state_e):
+        assert (a.view(np.int64) == b.view(np.int64)).all()
+
+
 def test_head_inside_the_slice_kernel_gives_the_same_bits():
     """Both placements of the accept decisions run the same code: every output of tapout_verify is bit-identical,
     also when the two alternate on one context (the band list of a job record is emptied by whoever appends next)."""

@@ -13,7 +13,10 @@
  * General rules
  *   Pointers.  Unless a parameter says "host", every array pointer is a DEVICE
  *     pointer into memory owned by the caller; the library never keeps it
- *     after the call returns.  "or NULL" marks optional arrays.
+ *     after the call returns.  "or NULL" marks optional arrays.  The output
+ *     arrays of a call must not overlap its input arrays or each other
+ *     (several workgroups read a sequence's inputs while one writes its
+ *     outputs).
  *   Asynchrony.  Calls enqueue kernels on `stream` (a hipStream_t passed as
  *     void*, NULL = the default stream) and return without waiting.  Calls on
  *     one context must be issued in stream order on one stream at a time: the

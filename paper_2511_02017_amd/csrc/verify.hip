@@ -446,6 +446,7 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
             if (resid) load8<DD>(r.drow, r.d_al, jn, a.V, nd);
         }
         if (resid) {
+            uint64_t any_band = 0;
 #pragma unroll
             for (int i = 0; i < kPer; ++i) {
                 const double av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
@@ -455,10 +456,19 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
                 Bs += bv;
                 R += fmax(diff, 0.0);
                 Ds += copysign(bv, diff);
-                const bool in_band = fabs(diff) <= band * bv;
-                if (__builtin_amdgcn_ballot_w64(in_band) != 0) {
-                    asm volatile("" ::: "memory");              // keep this a branch: a select would cost every element
-                    if (in_band) {
+                // band test: the comparison's lane mask is ORed up over the chunk in scalar registers; one branch
+                // per chunk instead of one per element (a branch on a fresh vector comparison stalls the wavefront)
+                any_band |= __builtin_amdgcn_ballot_w64(fabs(diff) <= band * bv);
+            }
+            if (any_band != 0) {
+                asm volatile("" ::: "memory");                  // keep this a branch: a select would cost every element
+                // almost never taken: form the chunk's exponentials again and treat its band elements one by one
+#pragma unroll 1
+                for (int i = 0; i < kPer; ++i) {
+                    const double av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
+                    const double bv = exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT, c2, top);
+                    const double diff = fma(-lam, bv, av);
+                    if (fabs(diff) <= band * bv) {
                         U += bv;
                         const int pos = atomicAdd(&a.jobs[j].band_cnt, 1);
                         if (pos < kBandCap) a.jobs[j].band_idx[pos] = base + c * kWave * kPer + i;

@@ -103,6 +103,17 @@ def test_odd_vocab_sizes_and_misaligned_rows(V, dtype):
     tp = binding.Tapout(B, K, V)
     pu.check_round(tp, rnd)
     pu.check_round(tp, rnd, arm=random_arms(B))
+    # the same rows cut into as many slices as the vocabulary allows (slices of 512 elements; the last ones of a row
+    # hold only its unaligned tail, or nothing), with tokens at the first and last index: the slice that holds a
+    # token's index hands its logit on
+    tp.set_option("min_slice", 256)
+    tp.set_option("wgs_target", 65536)
+    edge = dict(rnd)
+    edge["draft_tok"] = tok.clone()
+    edge["draft_tok"][:, 0] = 0
+    edge["draft_tok"][:, -1] = V - 1
+    pu.check_round(tp, edge)
+    pu.check_round(tp, edge, arm=random_arms(B))
 
 
 def test_slice_counts_do_not_change_decisions():

@@ -44,7 +44,10 @@ struct tapout_ctx {
 namespace {
 
 constexpr int kMaxWgsTarget = 1 << 16;
-constexpr int kFuseHeadMaxWgs = 2048;            // "fuse_head" = -1: fuse while the slice kernel has at most this many workgroups
+// "fuse_head" = -1: fuse while the slice kernel's workgroups are all resident at once (five per CU): a second round
+// of workgroups would pay the prologue a second time (measured at V = 128256: fused wins by 1.5-2.5 us up to 1280
+// workgroups and loses by 1-2 us from 1536 on)
+constexpr int kFuseHeadMaxWgs = 1280;
 constexpr int kMinSliceBytes = 16384;            // lower limit of the "slice_bytes" option (sizes the partial buffer)
 thread_local char g_create_err[256] = {0};
 

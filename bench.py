@@ -9,7 +9,11 @@ B = 64, K = 8, bfloat16) on which the headline metric (verified draft tokens/s
 at a 128k vocabulary) is quoted.  Inputs rotate through a ring of pre-generated
 rounds larger than the 256 MB Infinity Cache, so no step finds its logits cached.
 
-Prints ONE JSON line; see the design doc for the definition of every field.
+Prints ONE JSON line.  value = drafted tokens handed to verification (sum of n_draft over the timed steps) per
+second of wall time; roofline / roofline_draft_reduce = the two streaming launches (target / draft pass):
+algorithmic logit bytes per launch over the kernel's average duration, taken from event pairs the library puts on
+those launches inside the timed region, against the 8 TB/s HBM peak; traffic = HBM bytes per launch from the
+committed rocprofv3 counter summary; cpu_baseline = the CPU oracle on whole rounds of the same workload.
 """
 import argparse
 import json
@@ -53,8 +57,8 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path needs no exchange between GPUs; see DESIGN.md, "
-              "'How the path would shard'); --gpus must be 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (sequences are independent, so the path needs no exchange between "
+              "GPUs); --gpus must be 1", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2511_02017_amd import binding, synth

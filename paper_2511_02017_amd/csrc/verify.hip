@@ -750,7 +750,18 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
         double cum_at = 0.0;
         int s_found = -1;
         if (a.nsl <= kVBlock) {
-            const double z_mine = tid < a.nsl ? slice_weight(tid) : 0.0;
+            // this thread's slice is the one whose sums it fetched with the first round trip: no second look at memory
+            double z_mine = 0.0;
+            if (tid < a.nsl) {
+                if (exact_sums) z_mine = zs[tid];
+                else if (w.kind == 2) z_mine = f0;
+                else {
+                    z_mine = f2 - delta * f3;
+                    z_mine = z_mine > 0.0 ? z_mine : 0.0;
+                    for (int q = 0; q < n_band; ++q)
+                        if (shl.band_key[q] / kSampleSlice == tid) z_mine += shl.band_val[q];
+                }
+            }
             double ztot;
             const double excl = block_excl_scan_d(z_mine, shl.scan[phase++ & 1], &ztot);
             const int cand = wave_min_i32((tid < a.nsl && excl + z_mine > target) ? tid : 0x7fffffff);

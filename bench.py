@@ -46,6 +46,7 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="wall-time budget of the CPU-oracle leg")
     ap.add_argument("--profile-all", action="store_true", help="time every kernel with events (perturbs the step time slightly)")
     ap.add_argument("--opt", action="append", default=[], help="library tuning option name=value")
+    ap.add_argument("--no-read-reference", action="store_true", help="skip the plain PyTorch row-sum reference")
     ap.add_argument("--profile-stride", type=int, default=11,
                     help="time the streaming launches of one step in this many (event pairs perturb the step)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -190,6 +191,24 @@ def main():
     }
     if args.profile_all:
         out["kernel_avg_us"] = {k: round(prof[k][0] / max(1, prof[k][1]) * 1e3, 2) for k in kinds}
+    if not args.no_read_reference:
+        # A plain read-only streaming kernel on the same box and the same tensors, for scale: PyTorch's row sum of the
+        # draft logits of a round (one read of every element, one float per row out), after the timed region.
+        flat = [r["draft"].reshape(-1, w.V) for r in ring]
+        for i in range(4):
+            flat[i % ring_n].sum(dim=1, dtype=torch.float32)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 24
+        e0.record()
+        for i in range(reps):
+            flat[i % ring_n].sum(dim=1, dtype=torch.float32)
+        e1.record()
+        torch.cuda.synchronize()
+        ref_us = e0.elapsed_time(e1) / reps * 1e3
+        ref_gbs = flat[0].numel() * ed / (ref_us * 1e-6) / 1e9
+        out["read_only_reference"] = {"kernel": "torch.sum(dim=-1, dtype=float32) over the draft logits of one round",
+                                      "avg_us": round(ref_us, 2), "achieved": round(ref_gbs, 1), "unit": "GB/s",
+                                      "frac": round(ref_gbs / HBM_PEAK_GBS, 4)}
 
     if args.copy_calibration:
         src = torch.empty(512 << 20, dtype=torch.uint8, device=dev).random_(0, 255)

@@ -264,6 +264,36 @@ def test_degenerate_rows(dtype, fuse):
     assert not ds["flags"].any() and not vf["flags"].any()
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_scattered_masked_logits(dtype):
+    """A third of the vocabulary masked with -inf at random positions, differently in draft and target: nearly every
+    group of eight logits holds a masked one (the entropy sum then takes its clamped path), whole 16-byte vectors are
+    masked, drafted tokens can have target probability zero, and the residual lives on a thinned support."""
+    B, K, V = 5, 6, 40003
+    g = torch.Generator(device=DEV).manual_seed(77)
+    d = torch.randn(B, K, V, generator=g, device=DEV) * 2.5
+    t = d[:, :, :] + torch.randn(B, K, V, generator=g, device=DEV)
+    t = torch.cat([t, torch.randn(B, 1, V, generator=g, device=DEV) * 2.5], 1)
+    d[torch.rand(B, K, V, generator=g, device=DEV) < 0.33] = float("-inf")
+    t[torch.rand(B, K + 1, V, generator=g, device=DEV) < 0.33] = float("-inf")
+    d[0, 0, 4096:8192] = float("-inf")                                   # a whole slice masked
+    d, t = d.to(dtype), t.to(dtype)
+    tok = torch.multinomial(torch.softmax(d.float().reshape(B * K, V), -1), 1, generator=g).reshape(B, K).to(torch.int32)
+    rnd = dict(draft=d, target=t, draft_tok=tok,
+               u_accept=torch.rand(B, K, generator=g, device=DEV), u_sample=torch.rand(B, generator=g, device=DEV),
+               k_len=torch.full((B,), K, dtype=torch.int32, device=DEV), greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
+    tp = binding.Tapout(B, K, V)
+    for wgs, min_slice in ((4096, 4096), (65536, 256)):
+        tp.set_option("wgs_target", wgs)
+        tp.set_option("min_slice", min_slice)
+        c = pu.check_round(tp, rnd)
+        assert c["accept_flagged"] + c["icdf_flagged"] <= 1
+        pu.check_round(tp, rnd, arm=random_arms(B))
+    ds, vf, _ = pu.gpu_round(tp, rnd)
+    assert not ds["flags"].any() and not vf["flags"].any()
+    assert torch.isfinite(ds["entropy"]).all() and torch.isfinite(ds["logq_tok"]).all()
+
+
 @pytest.mark.parametrize("boost", [8.0, 1e-2, 1e-4])
 def test_residual_with_tied_probability_ratios(boost):
     """target = draft except for a few boosted tokens: p/q is the same number for almost every token.  With a

@@ -235,26 +235,33 @@ def cpu_baseline(w, ring, truncate, budget_s, policy, rules, thresholds, u_ts_ri
                          tok=rnd["draft_tok"].cpu().numpy(), k_len=rnd["k_len"].cpu().numpy(),
                          greedy=rnd["greedy"].cpu().numpy(), ua=rnd["u_accept"].cpu().numpy(),
                          us=rnd["u_sample"].cpu().numpy(), u_ts=u_ts_ring[len(host)]))
-    bandit = orc.Bandit(policy, w.B, len(rules))              # the policy codes of the oracle and of the boundary coincide
-    state = orc.RuleState(w.B, rules, thresholds)
-    tokens, rounds = 0, 0
-    t0 = time.perf_counter()
-    while True:
-        h = host[rounds % len(host)]
-        arm, _ = bandit.select(w.B, h["u_ts"])
-        ds = orc.draft_stats(h["draft"], draft_tok=h["tok"], k_len=h["k_len"], arm=arm, rules=rules, thresholds=thresholds,
-                             prev_entropy=state.prev_entropy, lam=state.lam, nthreads=cores)
-        nd = ds["n_stop"] if truncate else h["k_len"]
-        vf = orc.verify(h["target"], h["draft"], ds["logq_tok"], h["tok"], nd, h["ua"], h["us"], greedy=h["greedy"], nthreads=cores)
-        bandit.update(arm, vf["accept_len"], nd, h["k_len"])
-        state.update(ds["entropy"], nd, vf["accept_len"])
-        tokens += int(np.sum(nd))
-        rounds += 1
-        dt = time.perf_counter() - t0
-        if dt >= budget_s:
-            break
-    return {"value": round(tokens / dt, 1), "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"{rounds} whole rounds of the workload ({tokens} drafted tokens) in {dt:.1f} s"}
+    def run(nthreads, seconds):
+        bandit = orc.Bandit(policy, w.B, len(rules))          # the policy codes of the oracle and of the boundary coincide
+        state = orc.RuleState(w.B, rules, thresholds)
+        tokens, rounds = 0, 0
+        t0 = time.perf_counter()
+        while True:
+            h = host[rounds % len(host)]
+            arm, _ = bandit.select(w.B, h["u_ts"])
+            ds = orc.draft_stats(h["draft"], draft_tok=h["tok"], k_len=h["k_len"], arm=arm, rules=rules, thresholds=thresholds,
+                                 prev_entropy=state.prev_entropy, lam=state.lam, nthreads=nthreads)
+            nd = ds["n_stop"] if truncate else h["k_len"]
+            vf = orc.verify(h["target"], h["draft"], ds["logq_tok"], h["tok"], nd, h["ua"], h["us"], greedy=h["greedy"],
+                            nthreads=nthreads)
+            bandit.update(arm, vf["accept_len"], nd, h["k_len"])
+            state.update(ds["entropy"], nd, vf["accept_len"])
+            tokens += int(np.sum(nd))
+            rounds += 1
+            dt = time.perf_counter() - t0
+            if dt >= seconds:
+                return tokens, rounds, dt
+
+    tokens, rounds, dt = run(cores, budget_s)
+    out = {"value": round(tokens / dt, 1), "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
+           "sample": f"{rounds} whole rounds of the workload ({tokens} drafted tokens) in {dt:.1f} s"}
+    t1, r1, d1 = run(1, min(4.0, budget_s / 3))               # the same on one thread, a shorter sample (at least one round)
+    out["single_thread"] = {"value": round(t1 / d1, 1), "sample": f"{r1} whole rounds ({t1} drafted tokens) in {d1:.1f} s"}
+    return out
 
 
 if __name__ == "__main__":

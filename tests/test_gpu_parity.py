@@ -454,11 +454,12 @@ def test_bad_inputs_set_flags_and_fall_back(fuse):
     assert np.isnan(gds["entropy"][0, 1].item()) and np.isnan(gds["logq_tok"][3, 0].item())
 
 
-# ---- full benchmark shapes: sampled sequences, launch configuration of bench.py ----
+# ---- full benchmark shapes, launch configuration of bench.py: every sequence of a round against the oracle ----
 
-@pytest.mark.parametrize("name,n_seq", [("llama3", 12), ("zipf", 6), ("ragged", 4)])
-def test_full_size_sampled_sequences(name, n_seq):
+@pytest.mark.parametrize("name,n_seq", [("llama3", 64), ("zipf", 256), ("ragged", 512)])
+def test_full_size_rounds_every_sequence(name, n_seq):
     w = synth.WORKLOADS[name]
+    assert n_seq == w.B                     # the oracle takes a whole round of these sizes in a second or two on 16 threads
     announce(f"full size {w}")
     gen, tp, rounds = make(w, rounds=(3,))
     rnd = rounds[0]

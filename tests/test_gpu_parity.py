@@ -531,12 +531,14 @@ def test_bandit_trajectory_matches_oracle(policy, reward, shared):
     np.testing.assert_allclose(q2, np.where(c > 0, s * s / np.maximum(c, 1), 0.0), rtol=1e-15)
 
 
-@pytest.mark.parametrize("name", ["tiny", "small"])
+@pytest.mark.parametrize("name", ["tiny", "small", "llama3"])
 def test_closed_loop_rounds(name):
-    """Algorithm 1 end to end over many rounds: select -> draft_stats -> verify -> update, bandit in the loop."""
+    """Algorithm 1 end to end over many rounds: select -> draft_stats -> verify -> update, bandit in the loop
+    (llama3: the benchmark's own shape, all 64 sequences, stop rules truncating the drafts)."""
     w = synth.WORKLOADS[name]
-    w = synth.scaled(w, sigma_draft=6.0) if name == "tiny" else synth.scaled(w, B=8, sigma_draft=7.0)
-    n_rounds = 24 if name == "tiny" else 10
+    if name != "llama3":
+        w = synth.scaled(w, sigma_draft=6.0) if name == "tiny" else synth.scaled(w, B=8, sigma_draft=7.0)
+    n_rounds = {"tiny": 24, "small": 10, "llama3": 12}[name]
     policy = binding.UCB1
     gen = synth.RoundGenerator(w, DEV)
     tp = binding.Tapout(w.B, w.K, w.V, policy=policy)

@@ -1,6 +1,7 @@
 """GPU parity: libtapout (through its C ABI) against the CPU oracle, element by
 element, on the same seeded inputs.  Tolerances are defined in parity_util."""
 import math
+import os
 
 import numpy as np
 import pytest
@@ -292,6 +293,47 @@ def test_scattered_masked_logits(dtype):
     ds, vf, _ = pu.gpu_round(tp, rnd)
     assert not ds["flags"].any() and not vf["flags"].any()
     assert torch.isfinite(ds["entropy"]).all() and torch.isfinite(ds["logq_tok"]).all()
+
+
+@pytest.mark.parametrize("seed", list(range(int(os.environ.get("TAPOUT_RANDOM_CONFIGS", "96")))))
+def test_random_configurations(seed):
+    """Shapes, dtypes, strides, lengths, masks, decoding modes and launch options drawn at random (seeded): whatever
+    combination comes out must match the oracle."""
+    rs = np.random.RandomState(1000 + seed)
+    B, K = int(rs.randint(1, 10)), int(rs.randint(1, 13))
+    V = int(rs.choice([rs.randint(2, 600), rs.randint(600, 9000), rs.randint(9000, 70000)]))
+    dt_d, dt_t = (torch.float32, torch.bfloat16)[rs.randint(2)], (torch.float32, torch.bfloat16)[rs.randint(2)]
+    pad_d, pad_t, off_d, off_t = (int(x) for x in rs.randint(0, 11, 4))
+    sigma, noise = float(rs.uniform(0.5, 6.0)), float(rs.uniform(0.2, 2.5))
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    wide_d = torch.randn(B, K, V + pad_d + off_d, generator=g, device=DEV) * sigma
+    d32 = wide_d[:, :, off_d:off_d + V]
+    wide_t = torch.randn(B, K + 1, V + pad_t + off_t, generator=g, device=DEV) * noise
+    wide_t[:, :K, off_t:off_t + V] += d32
+    wide_t[:, K] *= sigma / noise
+    if rs.rand() < 0.4:                                                  # masked vocabulary tail or random holes
+        if rs.rand() < 0.5:
+            cut = int(rs.randint(1, V + 1))
+            wide_d[:, :, off_d + cut:] = float("-inf"); wide_t[:, :, off_t + cut:] = float("-inf")
+        else:
+            wide_d[torch.rand(wide_d.shape, generator=g, device=DEV) < 0.2] = float("-inf")
+    wide_d, wide_t = wide_d.to(dt_d), wide_t.to(dt_t)
+    draft, target = wide_d[:, :, off_d:off_d + V], wide_t[:, :, off_t:off_t + V]
+    q = torch.softmax(draft.float().reshape(B * K, V), -1)
+    tok = torch.multinomial(q, 1, generator=g).reshape(B, K).to(torch.int32)
+    greedy = torch.from_numpy((rs.rand(B) < 0.3).astype(np.uint8)).to(DEV)
+    tok = torch.where(greedy.bool()[:, None], draft.float().argmax(-1).to(torch.int32), tok)
+    k_len = torch.from_numpy(rs.randint(1, K + 1, B).astype(np.int32)).to(DEV)
+    rnd = dict(draft=draft, target=target, draft_tok=tok, u_accept=torch.rand(B, K, generator=g, device=DEV),
+               u_sample=torch.rand(B, generator=g, device=DEV), k_len=k_len, greedy=greedy)
+    tp = binding.Tapout(B, K, V)
+    tp.set_option("wgs_target", int(rs.choice([1, 64, 300, 4096, 65536])))
+    tp.set_option("min_slice", int(rs.choice([256, 1024, 4096])))
+    tp.set_option("fuse_head", int(rs.randint(-1, 2)))
+    announce(f"random configuration {seed}: B={B} K={K} V={V} {dt_d}/{dt_t} offsets {off_d}/{off_t} greedy={greedy.cpu().tolist()} k_len={k_len.cpu().tolist()}")
+    c = pu.check_round(tp, rnd)
+    c2 = pu.check_round(tp, rnd, arm=random_arms(B, seed=seed))
+    assert c["accept_flagged"] + c["icdf_flagged"] + c2["stop_flagged"] <= 2
 
 
 @pytest.mark.parametrize("boost", [8.0, 1e-2, 1e-4])

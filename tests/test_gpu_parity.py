@@ -985,6 +985,30 @@ def test_vocabulary_sharded_final_token_matches_oracle(name, G):
     assert (out.cpu().numpy()[ok] == ovf["out_tok"][ok]).all()
 
 
+@pytest.mark.parametrize("seed", list(range(int(os.environ.get("TAPOUT_RANDOM_SHARDINGS", "16")))))
+def test_random_shardings(seed):
+    """Random shapes cut into 2-8 vocabulary shards of uneven width (some a single column wide): the sharded path
+    must reproduce the oracle's decisions on the unsplit rows."""
+    rs = np.random.RandomState(5000 + seed)
+    B, K = int(rs.randint(1, 7)), int(rs.randint(1, 9))
+    V = int(rs.choice([rs.randint(16, 400), rs.randint(400, 9000), rs.randint(9000, 50000)]))
+    G = int(rs.randint(2, 9))
+    cuts = np.sort(rs.choice(np.arange(1, V), size=G - 1, replace=False))
+    edges = [0] + [int(c) for c in cuts] + [V]
+    dt = (torch.float32, torch.bfloat16)[rs.randint(2)]
+    rnd = random_round(B, K, V, dt, seed=seed, sigma=float(rs.uniform(1.0, 5.0)),
+                       k_len=[int(x) for x in rs.randint(1, K + 1, B)])
+    rnd["greedy"] = torch.from_numpy((rs.rand(B) < 0.25).astype(np.uint8)).to(DEV)
+    announce(f"random sharding {seed}: B={B} K={K} V={V} {dt} edges {edges}")
+    acc, out, _ = sharded_round(rnd, G, V, edges=edges)
+    ods, ovf, nd = pu.oracle_round(rnd)
+    used = np.arange(K)[None, :] < nd[:, None]
+    ok = ~((ovf["accept_margin"] <= pu.TAU) & used).any(1) & ~(ovf["icdf_margin"] <= pu.TAU_S)
+    assert ok.sum() >= B - 1
+    assert (acc.cpu().numpy()[ok] == ovf["accept_len"][ok]).all()
+    assert (out.cpu().numpy()[ok] == ovf["out_tok"][ok]).all()
+
+
 def test_vocabulary_sharded_final_token_hard_cases():
     """p = q on heavy tokens (the sums cannot settle the masses: second exchange), p == q everywhere (bonus-like draw
     from the target row), and draws near the ends of the CDF."""

@@ -894,6 +894,46 @@ def test_draft_token_sampling_matches_oracle(name):
     assert torch.equal(gd2["logq_tok"][torch.from_numpy(live).to(DEV)], gds["logq_tok"][torch.from_numpy(live).to(DEV)])
 
 
+@pytest.mark.parametrize("seed", list(range(int(os.environ.get("TAPOUT_RANDOM_SAMPLINGS", "12")))))
+def test_random_draft_token_sampling(seed):
+    """Draft tokens drawn by the library on random shapes, row offsets, lengths, masks and slice counts: the tokens
+    are the oracle's inverse-CDF draws, and the round that follows with them matches the oracle as well."""
+    rs = np.random.RandomState(7000 + seed)
+    B, K = int(rs.randint(1, 8)), int(rs.randint(1, 10))
+    V = int(rs.choice([rs.randint(2, 500), rs.randint(500, 9000), rs.randint(9000, 60000)]))
+    dt = (torch.float32, torch.bfloat16)[rs.randint(2)]
+    off = int(rs.randint(0, 9))
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    wide = torch.randn(B, K, V + off + 3, generator=g, device=DEV) * float(rs.uniform(1.0, 6.0))
+    if rs.rand() < 0.4:
+        wide[torch.rand(wide.shape, generator=g, device=DEV) < 0.3] = float("-inf")
+        wide[:, :, off] = 0.5                                             # every row keeps a finite logit
+    draft = wide.to(dt)[:, :, off:off + V]
+    target = torch.cat([draft.float() + torch.randn(B, K, V, generator=g, device=DEV), torch.randn(B, 1, V, generator=g, device=DEV)], 1).to(dt)
+    k_len = rs.randint(1, K + 1, B).astype(np.int32)
+    u = torch.rand(B, K, generator=g, device=DEV)
+    tp = binding.Tapout(B, K, V, draft_sampling=True)
+    tp.set_option("wgs_target", int(rs.choice([1, 64, 4096, 65536])))
+    tp.set_option("min_slice", int(rs.choice([256, 4096])))
+    announce(f"random sampling {seed}: B={B} K={K} V={V} {dt} offset {off} k_len={k_len.tolist()}")
+    kl = torch.from_numpy(k_len).to(DEV)
+    arm = random_arms(B, seed=seed)
+    gds = tp.draft_stats(draft, k_len=kl, arm=arm, u_draft=u)
+    live = np.arange(K)[None, :] < k_len[:, None]
+    osm = orc.draft_sample(pu.host_logits(draft), u.cpu().numpy(), k_len=k_len, nthreads=16)
+    g_tok = gds["sampled_tok"].cpu().numpy()
+    near = (osm["icdf_margin"] <= pu.TAU_S) & live
+    assert near.sum() <= 1
+    assert (g_tok[live & ~near] == osm["tok"][live & ~near]).all()
+    assert (g_tok[~live] == -1).all()
+    if not near.any():
+        rnd = dict(draft=draft, target=target, draft_tok=gds["sampled_tok"].clamp(min=0), k_len=kl,
+                   u_accept=torch.rand(B, K, generator=g, device=DEV), u_sample=torch.rand(B, generator=g, device=DEV),
+                   greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
+        tp2 = binding.Tapout(B, K, V)
+        pu.check_round(tp2, rnd, arm=arm)
+
+
 def test_draft_token_sampling_law_edges_and_bad_rows():
     V = 6000
     x = torch.full((3, 2, V), float("-inf"))

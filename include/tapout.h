@@ -129,7 +129,10 @@ typedef struct {
     /* AdaEDL (Appendix A.1).  The paper leaves all of these unvalued; the defaults are this
      * library's choice.  After every draft of a sequence, with r = accepted / drafted:
      *   rate   <- beta1 * rate + (1 - beta1) * r
-     *   lambda <- beta2 * lambda + (1 - beta2) * (lambda + eps * sign(alpha_target - rate))       */
+     *   lambda <- beta2 * lambda + (1 - beta2) * (lambda + eps * sign(alpha_target - s))
+     * with s = the new smoothed rate (adaedl_steer = 0, the default: the appendix defines the running
+     * average, and this reading is the one in which something reads it) or s = r, this draft's own
+     * rate (adaedl_steer = 1: the update as Appendix A.1 prints it, its doubled "+" dropped).          */
     double adaedl_gamma;                  /* g in the stop rule (0.5)                           */
     double adaedl_alpha;                  /* acceptance rate the threshold is steered to (0.9)  */
     double adaedl_beta1;                  /* smoothing of the acceptance rate (0.5)             */
@@ -139,7 +142,7 @@ typedef struct {
     int32_t draft_sampling;               /* 1: tapout_draft_stats may draw the draft tokens    */
                                           /* (u_draft); sizes the final-token scratch for one   */
                                           /* job per draft row instead of one per sequence      */
-    int32_t reserved;                     /* 0                                                  */
+    int32_t adaedl_steer;                 /* 0: lambda follows the smoothed rate; 1: r itself   */
 } tapout_config;
 
 typedef struct {

@@ -297,7 +297,10 @@ class RuleState:
     position of the previous draft (SVIPDifference) and AdaEDL's smoothed acceptance rate; per sequence and
     arm AdaEDL's threshold lambda (it starts at the arm's configured threshold)."""
 
-    def __init__(self, B: int, rules, thresholds, ad_alpha=0.9, beta1=0.5, beta2=0.9, eps=0.01, rate0=None):
+    def __init__(self, B: int, rules, thresholds, ad_alpha=0.9, beta1=0.5, beta2=0.9, eps=0.01, rate0=None, steer_raw=False):
+        """steer_raw: AdaEDL's threshold follows sign(alpha - r_t), this draft's own acceptance rate, as Appendix A.1
+        prints it; default: sign(alpha - smoothed rate)."""
+        self.steer_raw = bool(steer_raw)
         self.B, self.rules = B, _i32(rules)
         self.A = len(self.rules)
         self.ad_alpha, self.beta1, self.beta2, self.eps = ad_alpha, beta1, beta2, eps
@@ -314,4 +317,5 @@ class RuleState:
         lib().tapout_oracle_rule_state_update(
             B, K, self.A, _p(self.rules), _p(ent), _p(_i32(n_draft, (B,))), _p(_i32(accept_len, (B,))),
             _p(_u8(active)), _p(self.prev_entropy), _p(self.accept_rate), _p(self.lam),
-            C.c_double(self.ad_alpha), C.c_double(self.beta1), C.c_double(self.beta2), C.c_double(self.eps))
+            C.c_double(self.ad_alpha), C.c_double(self.beta1), C.c_double(self.beta2), C.c_double(self.eps),
+            int(self.steer_raw))

@@ -480,17 +480,22 @@ ORACLE_API int tapout_oracle_verify(
  *   prev_entropy <- entropy of the last drafted position (row n_draft - 1);
  *   AdaEDL:  r = n_acc / n_drafted
  *            accept_rate <- beta1 * accept_rate + (1 - beta1) * r
- *            lambda <- beta2 * lambda + (1 - beta2) * (lambda + eps * sign(alpha - accept_rate))
+ *            lambda <- beta2 * lambda + (1 - beta2) * (lambda + eps * sign(alpha - s))
  *   for the lambda of every AdaEDL arm of the sequence (each arm keeps its own,
  *   they start at different values).  The printed update is garbled (a doubled
- *   "+", an accept_rate that nothing reads); the reading here lets the smoothed
- *   rate steer the threshold.  sign(0) = 0.                                  */
+ *   "+", an accept_rate that nothing reads).  Two readings of s:
+ *     steer_raw = 0   s = the new smoothed accept_rate: the running average the
+ *                     appendix defines is what steers the threshold;
+ *     steer_raw = 1   s = r, this draft's own rate: the equation as printed
+ *                     with the doubled "+" dropped (accept_rate is then kept
+ *                     but read by nothing).
+ *   sign(0) = 0.                                                              */
 ORACLE_API int tapout_oracle_rule_state_update(
     int B, int K, int n_arms, const int32_t *rule,
     const float *entropy /* [B,K] or NULL */, const int32_t *n_draft, const int32_t *accept_len,
     const uint8_t *active,
     float *prev_entropy /* [B] */, double *accept_rate /* [B] */, double *lambda /* [B,n_arms] */,
-    double ad_alpha, double beta1, double beta2, double eps)
+    double ad_alpha, double beta1, double beta2, double eps, int steer_raw)
 {
     for (int b = 0; b < B; ++b) {
         if (active && !active[b]) continue;
@@ -502,7 +507,8 @@ ORACLE_API int tapout_oracle_rule_state_update(
         volatile double add = (1.0 - beta1) * r;
         double rate = keep + add;
         accept_rate[b] = rate;
-        double sg = ad_alpha > rate ? 1.0 : (ad_alpha < rate ? -1.0 : 0.0);
+        double s = steer_raw ? r : rate;
+        double sg = ad_alpha > s ? 1.0 : (ad_alpha < s ? -1.0 : 0.0);
         for (int a = 0; a < n_arms; ++a) {
             if (rule[a] != 4) continue;
             double lam = lambda[(size_t)b * n_arms + a];

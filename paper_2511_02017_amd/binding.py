@@ -43,7 +43,7 @@ class TapoutConfig(C.Structure):
                 ("reward", C.c_int32), ("granularity", C.c_int32),
                 ("adaedl_gamma", C.c_double), ("adaedl_alpha", C.c_double), ("adaedl_beta1", C.c_double),
                 ("adaedl_beta2", C.c_double), ("adaedl_eps", C.c_double), ("adaedl_rate0", C.c_double),
-                ("draft_sampling", C.c_int32), ("reserved", C.c_int32)]
+                ("draft_sampling", C.c_int32), ("adaedl_steer", C.c_int32)]
 
 
 class TapoutLogits(C.Structure):
@@ -139,7 +139,7 @@ class Tapout:
                  rules=(RULE_SVIP, RULE_MAXCONF, RULE_MARGIN), thresholds=(0.6, 0.8, 0.2),
                  alpha: float = 0.5, shared_bandit: bool = False, reward: int = REWARD_BLEND, adaedl: dict | None = None,
                  token_level: bool = False, draft_sampling: bool = False):
-        """adaedl: optional dict with any of gamma, alpha, beta1, beta2, eps, rate0 (tapout_config.adaedl_*)."""
+        """adaedl: optional dict with any of gamma, alpha, beta1, beta2, eps, rate0, steer (tapout_config.adaedl_*)."""
         self._lib = load_library()
         cfg = default_config(max_batch, max_k, vocab)
         cfg.device = device
@@ -152,7 +152,7 @@ class Tapout:
         cfg.granularity = TOKEN_LEVEL if token_level else SEQUENCE_LEVEL
         cfg.draft_sampling = 1 if draft_sampling else 0
         for k, v in (adaedl or {}).items():
-            setattr(cfg, "adaedl_" + k, float(v))
+            setattr(cfg, "adaedl_" + k, int(v) if k == "steer" else float(v))
         cfg.n_bandits = 1 if shared_bandit else max_batch
         self.cfg = cfg
         self.positions = max_k if token_level else 1           # bandits per slot; arm arrays are [B, max_k] when > 1

@@ -148,7 +148,7 @@ BanditArgs bandit_args(const tapout_ctx *ctx, int B)
         a.prev_entropy = ctx->prev_entropy; a.accept_rate = ctx->accept_rate; a.lambda = ctx->lambda;
         a.round_entropy = ctx->round_entropy; a.round_K = ctx->round_K;
         a.ad_alpha = ctx->cfg.adaedl_alpha; a.ad_beta1 = ctx->cfg.adaedl_beta1; a.ad_beta2 = ctx->cfg.adaedl_beta2;
-        a.ad_eps = ctx->cfg.adaedl_eps;
+        a.ad_eps = ctx->cfg.adaedl_eps; a.ad_steer = ctx->cfg.adaedl_steer;
     }
     return a;
 }
@@ -209,6 +209,7 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
         return fail(nullptr, TAPOUT_EUNSUPPORTED, "granularity %d is not implemented", cfg->granularity);
     if (cfg->draft_sampling != 0 && cfg->draft_sampling != 1) return fail(nullptr, TAPOUT_EINVAL, "draft_sampling must be 0 or 1");
     if (cfg->reward != TAPOUT_REWARD_BLEND && cfg->reward != TAPOUT_REWARD_SIMPLE) return fail(nullptr, TAPOUT_EUNSUPPORTED, "reward %d is not implemented", cfg->reward);
+    if (cfg->adaedl_steer != 0 && cfg->adaedl_steer != 1) return fail(nullptr, TAPOUT_EINVAL, "adaedl_steer must be 0 or 1");
     if (adaedl) {
         if (!(cfg->adaedl_gamma >= 0.0) || !(cfg->adaedl_gamma < INFINITY)) return fail(nullptr, TAPOUT_EINVAL, "adaedl_gamma must be finite and >= 0");
         if (!(cfg->adaedl_beta1 >= 0.0 && cfg->adaedl_beta1 <= 1.0) || !(cfg->adaedl_beta2 >= 0.0 && cfg->adaedl_beta2 <= 1.0))

@@ -222,7 +222,8 @@ __device__ inline void advance_rule_state(const BanditArgs &a, int b, int m, int
     const double r = (double)m / (double)n;
     const double rate = a.ad_beta1 * a.accept_rate[b] + (1.0 - a.ad_beta1) * r;
     a.accept_rate[b] = rate;
-    const double sg = a.ad_alpha > rate ? 1.0 : (a.ad_alpha < rate ? -1.0 : 0.0);
+    const double s = a.ad_steer ? r : rate;       // what steers the threshold: the smoothed rate, or r as printed
+    const double sg = a.ad_alpha > s ? 1.0 : (a.ad_alpha < s ? -1.0 : 0.0);
     for (int j = 0; j < a.n_arms; ++j) {
         if (a.rule[j] != TAPOUT_RULE_ADAEDL) continue;
         const double lam = a.lambda[(int64_t)b * a.n_arms + j];

@@ -178,6 +178,7 @@ struct BanditArgs {
     float *prev_entropy; double *accept_rate; double *lambda;
     const float *round_entropy; int32_t round_K;      // entropies of the last draft_stats call, [B, round_K]; round_K = 0: none
     double ad_alpha, ad_beta1, ad_beta2, ad_eps;
+    int32_t ad_steer;             // tapout_config.adaedl_steer
 };
 hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm);
 hipError_t launch_bandit_update(const BanditArgs &a, const int32_t *arm, const int32_t *accept_len,

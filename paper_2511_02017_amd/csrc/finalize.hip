@@ -54,7 +54,12 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     __shared__ uint32_t sh_flags;
     const int b = blockIdx.x;
     const int K = a.K;
-    const int rows_per_stage = kStageCap / a.nsplit;          // nsplit <= kStageCap is guaranteed by the host
+    // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
+    const int msh = SHARDED ? -1 : lane_merge_shift(K, a.nsplit);
+    // The lane-parallel merge leaves the totals of all K <= 64 rows in LDS at once and row k with thread k: it is one
+    // stage whatever the slice count.  The staged merge takes kStageCap partials at a time (nsplit <= kStageCap is
+    // guaranteed by the host).
+    const int rows_per_stage = msh >= 0 ? kWave : kStageCap / a.nsplit;
     const bool want_tok = a.draft_tok && a.logq_tok;
     static_assert(kFinalBlock == 256, "stage_issue / stage_commit assume 256 threads");
     // First memory round trip: k_len, the arm, the carried entropy, the drafted tokens and the partials, all
@@ -67,8 +72,6 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     int32_t tok0 = -1;
     if (want_tok && (int)threadIdx.x < K) tok0 = a.draft_tok[(int64_t)b * K + threadIdx.x];
     const int count0 = min(K, rows_per_stage) * a.nsplit;
-    // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
-    const int msh = SHARDED ? -1 : lane_merge_shift(K, a.nsplit);
     RowSlot *sh_rows = (RowSlot *)sh_part;
     static_assert(sizeof(RowSlot) * 64 <= sizeof(Partial) * kStageCap, "the row totals reuse the staging buffer");
     StageRegs st0;

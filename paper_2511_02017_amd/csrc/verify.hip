@@ -145,7 +145,11 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                                         Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast, double *sh_lse)
 {
     const int K = a.K;
-    const int rows_per_stage = kStageCap / a.nsplit;
+    // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
+    const int msh = SHARDED ? -1 : lane_merge_shift(K + 1, a.nsplit);
+    // The lane-parallel merge leaves the totals of all K + 1 <= 64 rows in LDS at once and row k with thread k: it is
+    // one stage whatever the slice count.  The staged merge takes kStageCap partials at a time.
+    const int rows_per_stage = msh >= 0 ? kWave : kStageCap / a.nsplit;
     // Everything whose address does not depend on n_draft is requested before n_draft is looked at, so that
     // the first memory round trip carries n_draft, the tokens, the uniforms and the partials together.
     // (Rows beyond n_draft hold stale partials and unused tokens: read, never used.)
@@ -166,8 +170,6 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         if (a.draft_lse) dl0 = a.draft_lse[i];      // the final token's job wants it for row m: no dependent load later
     }
     if (threadIdx.x == 0) { *sh_flags = 0; sh_bcast[4] = 0; }     // ahead of the staging barrier: rows of other wavefronts OR into the flags
-    // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
-    const int msh = SHARDED ? -1 : lane_merge_shift(K + 1, a.nsplit);
     RowSlot *sh_rows = (RowSlot *)sh_part;
     static_assert(sizeof(RowSlot) * 64 <= sizeof(Partial) * kStageCap, "the row totals reuse the staging buffer");
     if constexpr (SHARDED) {

@@ -70,6 +70,9 @@ def test_workload_parity_truncated(name, kw, fuse):
     arm = random_arms(w.B, seed=w.index)
     c = pu.check_round(tp, rounds[0], arm=arm)
     announce(f"{name}: near-tie counts {c}")
+    # a near tie needs a signal within 1e-5 (relative) of its threshold or a uniform within 1e-5 of p/q: about one
+    # decision in 1e5; a count beyond a couple means the flags are hiding mismatches
+    assert c["stop_flagged"] + c["accept_flagged"] + c["icdf_flagged"] <= max(2, c["sequences"] // 50)
 
 
 def test_peaked_rows_separate_the_rules():
@@ -336,6 +339,108 @@ def test_random_configurations(seed):
     assert c["accept_flagged"] + c["icdf_flagged"] + c2["stop_flagged"] <= 2
 
 
+def force_slices(tp, rows, P, min_slice=256):
+    """Launch options under which a pass over `rows` rows cuts every row into P slices (given V >= P * min_slice and
+    rows shorter than P * slice_bytes)."""
+    tp.set_option("min_slice", min_slice)
+    tp.set_option("wgs_target", min(65536, rows * P))
+
+
+def lane_round(B, K, V, dtype, seed, greedy_rows=(), sigma=3.0):
+    rnd = random_round(B, K, V, dtype, seed=seed, sigma=sigma)
+    g = torch.zeros(B, dtype=torch.uint8)
+    g[list(greedy_rows)] = 1
+    rnd["greedy"] = g.to(DEV)
+    tok = rnd["draft_tok"]
+    rnd["draft_tok"] = torch.where(rnd["greedy"].bool()[:, None], rnd["draft"].float().argmax(-1).to(torch.int32), tok)
+    return rnd
+
+
+@pytest.mark.parametrize("B,K,V,P", [
+    (16, 16, 128256, 0),      # default options: 16 slices per row, 17 target rows > 256 / 16
+    (8, 32, 65536, 0),        # default options, draft side: 16 slices, 32 rows
+    (16, 20, 70001, 0),
+    (3, 63, 4096, 8),         # 64 target rows x 8 slices = 512: the largest lane-merge shape
+    (3, 42, 3100, 12),        # 12 slices in groups of 16 lanes with empty lanes; 43 x 16 = 688 > 512 -> staged; draft 42 x 16 too
+    (5, 31, 4100, 16),        # 32 x 16 = 512 target rows on the lane path, second pass of every thread in use
+    (4, 40, 2100, 5),         # 5 slices in groups of 8: rows 32..40 come from the second pass
+    (2, 64, 1100, 4),         # K = 64: draft side on the lane path (64 x 4), target side (65 rows) staged
+    (6, 17, 9000, 15),
+])
+@FUSE
+def test_lane_merge_with_more_rows_than_one_stage_of_partials(B, K, V, P, fuse):
+    """Per-sequence epilogues on the lane-parallel merge when the sequence has more rows than a staging buffer of
+    256 partials holds at the slice count in use (K + 1 > 256 / slices): all rows are still one stage, row k stays
+    with thread k.  Full-K (accept decisions far into the draft), greedy and sampled sequences, every stop rule,
+    and flags raised at row 0."""
+    announce(f"lane merge B={B} K={K} V={V} P={P} fuse_head={fuse}")
+    rnd = lane_round(B, K, V, torch.bfloat16 if V > 60000 else torch.float32, seed=K * 1000 + P, greedy_rows=range(0, B, 3))
+    tp = binding.Tapout(B, K, V)
+    tp.set_option("fuse_head", fuse)
+    if P:
+        force_slices(tp, B * K, P)
+    c = pu.check_round(tp, rnd)
+    assert c["accept_flagged"] + c["icdf_flagged"] <= 1
+    # a draft equal to the target is accepted to the end: the decisions of rows beyond 256 / slices count
+    same = dict(rnd); same["target"] = torch.cat([rnd["draft"], rnd["target"][:, K:]], 1).contiguous()
+    _, vf, _ = pu.gpu_round(tp, same)
+    assert (vf["accept_len"] == K).all() and (vf["n_out"] == K + 1).all()
+    pu.check_round(tp, same)
+    # a sequence rejected only at its last position
+    late = dict(same); late["u_accept"] = same["u_accept"].clone(); late["target"] = same["target"].clone()
+    late["target"][:, K - 1] = rnd["target"][:, K - 1]
+    late["u_accept"][:, K - 1] = 1.0 - 2.0 ** -24
+    pu.check_round(tp, late)
+    for a in range(3):
+        c = pu.check_round(tp, rnd, arm=torch.full((B,), a, dtype=torch.int32, device=DEV))
+        assert c["stop_flagged"] <= 1
+    # bad inputs at row 0 and at the last row: the flags of every row reach the sequence's flag word
+    bad = {k: (v.clone() if torch.is_tensor(v) else v) for k, v in rnd.items()}
+    bad["draft_tok"][0, 0] = V                          # token out of range at row 0
+    if B > 1:
+        bad["target"][1, 0, 1] = float("nan")           # NaN in target row 0
+    if B > 2:
+        bad["draft"][2, K - 1, 0] = float("nan")        # NaN in the last draft row
+        bad["draft_tok"][2, K - 1] = -1
+    gds, gvf, _ = pu.gpu_round(tp, bad)
+    ods, ovf, _ = pu.oracle_round(bad)
+    assert gds["flags"].cpu().numpy().astype(np.uint32).tolist() == ods["flags"].tolist()
+    assert gvf["flags"].cpu().numpy().astype(np.uint32).tolist() == ovf["flags"].tolist()
+    assert ods["flags"][0] & orc.FLAG_BAD_TOKEN and ovf["flags"][0] & orc.FLAG_BAD_TOKEN
+    flagged = ovf["flags"] != 0
+    assert (gvf["accept_len"].cpu().numpy()[flagged] == ovf["accept_len"][flagged]).all()
+    assert (gvf["out_tok"].cpu().numpy()[flagged] == ovf["out_tok"][flagged]).all()
+
+
+@pytest.mark.parametrize("seed", list(range(int(os.environ.get("TAPOUT_RANDOM_LANE_SHAPES", "40")))))
+def test_random_lane_merge_shapes(seed):
+    """13 <= K <= 64 with 2 .. 16 slices per row forced through the launch options: every (group size, rows) pair of the
+    lane-parallel merge, including rows in (256 / slices, 512 / group] that take each thread's second pass, and the
+    shapes just beyond it that fall back to the staged merge."""
+    rs = np.random.RandomState(3000 + seed)
+    P = int(rs.randint(2, 17))
+    K = int(rs.randint(13, 65))
+    B = int(rs.randint(1, 5))
+    V = int(P * 256 + rs.randint(0, 3000))
+    dt = (torch.float32, torch.bfloat16)[rs.randint(2)]
+    rnd = lane_round(B, K, V, dt, seed=seed, greedy_rows=[b for b in range(B) if rs.rand() < 0.3], sigma=float(rs.uniform(1.5, 6.0)))
+    rnd["k_len"] = torch.from_numpy(np.where(rs.rand(B) < 0.5, K, rs.randint(1, K + 1, B)).astype(np.int32)).to(DEV)
+    if rs.rand() < 0.5:                                   # p == q on a prefix: accept decisions deep into the draft
+        keep = int(rs.randint(1, K + 1))
+        rnd["target"] = rnd["target"].clone()
+        rnd["target"][:, :keep] = rnd["draft"][:, :keep]
+    if rs.rand() < 0.3:
+        rnd["draft_tok"] = rnd["draft_tok"].clone()
+        rnd["draft_tok"][0, 0] = -1 if rs.rand() < 0.5 else V
+    tp = binding.Tapout(B, K, V)
+    force_slices(tp, B * K, P)
+    tp.set_option("fuse_head", int(rs.randint(-1, 2)))
+    announce(f"random lane shape {seed}: B={B} K={K} V={V} P={P} {dt} k_len={rnd['k_len'].cpu().tolist()} greedy={rnd['greedy'].cpu().tolist()}")
+    c = pu.check_round(tp, rnd)
+    c2 = pu.check_round(tp, rnd, arm=random_arms(B, seed=seed))
+    assert c["accept_flagged"] + c["icdf_flagged"] + c2["stop_flagged"] <= 2
+
+
 @pytest.mark.parametrize("boost", [8.0, 1e-2, 1e-4])
 def test_residual_with_tied_probability_ratios(boost):
     """target = draft except for a few boosted tokens: p/q is the same number for almost every token.  With a
@@ -509,6 +614,8 @@ def test_full_size_rounds_every_sequence(name, n_seq):
     seqs = torch.randperm(w.B, generator=g)[:n_seq].sort().values.tolist()
     c = pu.check_round(tp, rnd, seqs=seqs)
     announce(f"{name} full size, sequences {seqs}: near-tie counts {c}")
+    assert c["sequences"] == w.B
+    assert c["stop_flagged"] + c["accept_flagged"] + c["icdf_flagged"] <= max(2, w.B // 100)
     # properties that hold for every sequence at any size
     ds, vf, nd = pu.gpu_round(tp, rnd)
     m, n_out, out = vf["accept_len"].cpu(), vf["n_out"].cpu(), vf["out_tok"].cpu()
@@ -684,13 +791,15 @@ def test_random_closed_loops(seed):
     shared = bool(rs.rand() < 0.3)
     alpha = float(rs.choice([0.0, 0.25, 0.5, 1.0]))
     ad = dict(gamma=float(rs.uniform(0.3, 0.8)), alpha=float(rs.uniform(0.4, 0.9)), beta1=float(rs.uniform(0.2, 0.9)),
-              beta2=float(rs.uniform(0.5, 0.95)), eps=float(rs.uniform(0.005, 0.08)), rate0=float(rs.uniform(0.3, 0.9)))
+              beta2=float(rs.uniform(0.5, 0.95)), eps=float(rs.uniform(0.005, 0.08)), rate0=float(rs.uniform(0.3, 0.9)),
+              steer=int(seed & 1))                      # odd seeds: lambda follows r_t as Appendix A.1 prints the update
     announce(f"random loop {seed}: B={B} K={K} V={V} rules={rules} policy={policy} reward={reward} shared={shared} "
              f"alpha={alpha} token_level={token_level}")
     tp = binding.Tapout(B, K, V, policy=policy, rules=rules, thresholds=thresholds, alpha=alpha, shared_bandit=shared,
                         reward=reward, adaedl=ad, token_level=token_level)
     ob = orc.Bandit(policy, 1 if shared else B, n_arms, alpha=alpha, reward_kind=reward, positions=K if token_level else 1)
-    st = orc.RuleState(B, rules, thresholds, ad_alpha=ad["alpha"], beta1=ad["beta1"], beta2=ad["beta2"], eps=ad["eps"], rate0=ad["rate0"])
+    st = orc.RuleState(B, rules, thresholds, ad_alpha=ad["alpha"], beta1=ad["beta1"], beta2=ad["beta2"], eps=ad["eps"], rate0=ad["rate0"],
+                       steer_raw=bool(ad["steer"]))
     stateful = any(r in (binding.RULE_SVIP_DIFF, binding.RULE_ADAEDL) for r in rules)
     g = torch.Generator(device=DEV).manual_seed(seed)
     flagged = 0
@@ -763,6 +872,35 @@ def test_stateful_rules_on_closed_form_rows():
         assert st["prev_entropy"][2] == np.float32(0.9)                          # inactive: untouched
         assert st["accept_rate"].tolist() == [0.5 * 0.9 + 0.5 * 1.0, 0.5 * 0.9 + 0.5 * 0.0, 0.9]
         np.testing.assert_allclose(st["lam"][:, 1], [0.1 - 0.001, 0.42 + 0.001, -1.0], atol=1e-15)
+
+
+@pytest.mark.parametrize("steer", [0, 1])
+def test_adaedl_threshold_update_both_readings(steer, golden):
+    """The four drafts of tests/golden/adaedl_update_two_readings.txt through tapout_bandit_update: lambda steered by
+    the smoothed acceptance rate (default) or by the draft's own rate r_t (Appendix A.1 as printed), bit-equal to the
+    oracle's state and equal to the hand-worked values."""
+    rows = golden("adaedl_update_two_readings.txt")
+    B, K = 3, 5
+    ad = dict(alpha=0.87, beta1=0.5, beta2=0.9, eps=0.01, rate0=1.0, steer=steer)
+    rules, th = (binding.RULE_ADAEDL, binding.RULE_SVIP), (0.4, 0.6)
+    tp = binding.Tapout(B, K, 64, rules=rules, thresholds=th, adaedl=ad)
+    st = orc.RuleState(B, rules, th, ad_alpha=0.87, beta1=0.5, beta2=0.9, eps=0.01, rate0=1.0, steer_raw=bool(steer))
+    x = torch.randn(B, K, 64, generator=torch.Generator().manual_seed(1)).to(DEV)
+    arm = torch.zeros(B, dtype=torch.int32, device=DEV)
+    for row in rows:
+        n_acc, n_dr = int(row[0]), int(row[1])
+        ds = tp.draft_stats(x, arm=arm)
+        m = torch.tensor([n_acc, n_dr, 0], dtype=torch.int32, device=DEV)     # sequence 0 follows the fixture
+        n = torch.full((B,), n_dr, dtype=torch.int32, device=DEV)
+        tp.bandit_update(arm, m, n, torch.full((B,), K, dtype=torch.int32, device=DEV))
+        st.update(ds["entropy"].cpu().numpy(), n.cpu().numpy(), m.cpu().numpy())
+        gs = tp.rule_state_get()
+        assert (gs["lam"] == st.lam).all() and (gs["accept_rate"] == st.accept_rate).all()
+        assert gs["accept_rate"][0] == pytest.approx(float(row[3]), rel=1e-14)
+        assert gs["lam"][0, 0] == pytest.approx(float(row[7 - 2 * steer]) + (float(np.float32(0.4)) - 0.4), abs=1e-12)
+        assert (gs["lam"][:, 1] == np.float32(0.6)).all()                      # not an AdaEDL arm: never moved
+    with pytest.raises(binding.TapoutError, match="adaedl_steer"):
+        binding.Tapout(B, K, 64, rules=rules, thresholds=th, adaedl=dict(steer=2))
 
 
 def test_several_thresholds_per_rule():
@@ -932,6 +1070,30 @@ def test_random_draft_token_sampling(seed):
                    greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
         tp2 = binding.Tapout(B, K, V)
         pu.check_round(tp2, rnd, arm=arm)
+
+
+def test_draft_token_sampling_with_more_than_65535_rows():
+    """B * K = 65600 draft rows: one final-token job per row is more than one grid dimension holds, the slice kernel's
+    jobs spread over two of them."""
+    B, K, V = 4100, 16, 300
+    g = torch.Generator(device=DEV).manual_seed(11)
+    draft = torch.randn(B, K, V, generator=g, device=DEV) * 2.0
+    u = torch.rand(B, K, generator=g, device=DEV)
+    k_len = torch.randint(1, K + 1, (B,), generator=g, device=DEV, dtype=torch.int32)
+    k_len[-8:] = K                                                   # every job beyond the first 65535 is live
+    tp = binding.Tapout(B, K, V, draft_sampling=True)
+    o = tp.draft_stats(draft, k_len=k_len, u_draft=u)
+    torch.cuda.synchronize()
+    osm = orc.draft_sample(pu.host_logits(draft), u.cpu().numpy(), k_len=k_len.cpu().numpy(), nthreads=16)
+    live = np.arange(K)[None, :] < k_len.cpu().numpy()[:, None]
+    near = (osm["icdf_margin"] <= pu.TAU_S) & live
+    assert near.sum() <= 2
+    g_tok = o["sampled_tok"].cpu().numpy()
+    assert (g_tok[live & ~near] == osm["tok"][live & ~near]).all()
+    assert (g_tok[~live] == -1).all()
+    assert live.sum() > 30000 and live.reshape(-1)[65535:].sum() > 30         # jobs beyond the first grid dimension were live
+    ods = orc.draft_stats(pu.host_logits(draft), draft_tok=np.where(live, g_tok, 0), k_len=k_len.cpu().numpy(), nthreads=16)
+    pu.assert_stats_close("logq_tok", o["logq_tok"].cpu().numpy(), ods["logq_tok"], live & ~near)
 
 
 def test_draft_token_sampling_law_edges_and_bad_rows():

@@ -3,7 +3,8 @@
 The rows are uniform over n tokens with every other token masked, so their entropy is ln n in closed form and the
 expected decisions in tests/golden/ were worked out by hand from the paper's Table 1 / Appendix A.1 formulas.
 The VALUES of AdaEDL's hyper-parameters and the exact shape of its threshold update are not recoverable from the
-paper (printed garbled): those stay parity unpinned; what is pinned here is the arithmetic of the reading taken.
+paper (printed garbled): those stay parity unpinned; what is pinned here is the arithmetic of both readings the oracle
+offers (threshold steered by the smoothed acceptance rate, or by the draft's own rate as the equation is printed).
 """
 import math
 
@@ -124,3 +125,35 @@ def test_adaedl_state_follows_the_closed_forms():
     for t in range(1, 6):
         st.update(None, n_draft=[6], accept_len=[6])
         assert st.lam[0, 0] == pytest.approx(0.5 - t * 0.25 * 0.04, abs=1e-15)
+
+
+def test_adaedl_update_golden_both_readings(golden):
+    """Four drafts worked by hand (tests/golden/adaedl_update_two_readings.txt): the printed form steers lambda by
+    sign(alpha - r_t), the other reading by sign(alpha - smoothed rate); the two part ways at the first draft."""
+    rows = golden("adaedl_update_two_readings.txt")
+    for raw, sign_col, lam_col in ((True, 4, 5), (False, 6, 7)):
+        st = orc.RuleState(1, [orc.RULE_ADAEDL], [0.4], ad_alpha=0.87, beta1=0.5, beta2=0.9, eps=0.01, rate0=1.0, steer_raw=raw)
+        lam = float(np.float32(0.4))
+        for row in rows:
+            n_acc, n_dr = int(row[0]), int(row[1])
+            st.update(None, n_draft=[n_dr], accept_len=[n_acc])
+            assert n_acc / n_dr == pytest.approx(float(row[2]))
+            assert st.accept_rate[0] == pytest.approx(float(row[3]), rel=1e-14)     # the average is kept under both readings
+            lam += int(row[sign_col]) * (1 - 0.9) * 0.01
+            assert st.lam[0, 0] == pytest.approx(lam, abs=1e-15)
+            assert st.lam[0, 0] == pytest.approx(float(row[lam_col]) + (float(np.float32(0.4)) - 0.4), abs=1e-12)
+
+
+def test_adaedl_as_printed_ignores_the_running_average():
+    """Steered by r_t, lambda's path does not depend on where the smoothed rate starts or how it is smoothed."""
+    paths = []
+    for rate0, b1 in ((1.0, 0.5), (0.0, 0.9), (0.5, 0.0)):
+        st = orc.RuleState(1, [orc.RULE_ADAEDL], [0.3], ad_alpha=0.7, beta1=b1, beta2=0.8, eps=0.02, rate0=rate0, steer_raw=True)
+        path = []
+        for m, n in ((3, 4), (2, 4), (7, 10), (4, 4), (0, 3)):       # r = .75, .5, .7 (= alpha: no move), 1, 0
+            st.update(None, n_draft=[n], accept_len=[m])
+            path.append(st.lam[0, 0])
+        paths.append(path)
+    assert paths[0] == paths[1] == paths[2]
+    step, l0 = (1 - 0.8) * 0.02, float(np.float32(0.3))
+    np.testing.assert_allclose(paths[0], [l0 - step, l0, l0, l0 - step, l0], atol=1e-15)

@@ -161,7 +161,8 @@ TAPOUT_API void tapout_default_config(tapout_config *cfg, int32_t max_batch, int
 TAPOUT_API tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg);
 TAPOUT_API tapout_status tapout_destroy(tapout_ctx *ctx);
 /* Text of the last error on ctx (valid until the next call on ctx); with
- * ctx == NULL the text of the last failed tapout_create on this thread.      */
+ * ctx == NULL the text of the last failed tapout_create or context-free call
+ * (tapout_draft_stats_static) on this thread.                                 */
 TAPOUT_API const char *tapout_last_error(const tapout_ctx *ctx);
 
 /*
@@ -286,6 +287,38 @@ TAPOUT_API tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *tar
                             int32_t *accept_len, int32_t *out_tok, int32_t *n_out,
                             float *target_lse, float *logp_tok, int32_t *target_top1,
                             uint32_t *flags, void *stream);
+
+/*
+ * tapout_draft_stats for callers that cannot allocate device memory or hold a
+ * context: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  No context: the call computes the same signals and stop
+ * positions with the same kernels and the launch shape of a context with
+ * default options, and keeps the slice partials of its streaming pass in a
+ * fixed array in the library's device image (TAPOUT_STATIC_MAX_PARTIALS 32-byte
+ * records, 4 MiB per GPU, held until the process ends) on the CURRENT HIP
+ * device, whose logits and arrays the pointers must refer to.  It calls no
+ * allocating routine; the first call on a device looks the array's address up
+ * once.  Inputs with B * K * slices-per-row beyond the array (slices per row =
+ * max(ceil(4096 / (B K)), row bytes / 65536), at most V / 4096) are refused
+ * with TAPOUT_EINVAL before anything is launched.
+ *   All calls on one GPU share the array, which keeps the previous call's
+ *   records: calls that overlap in time on one GPU (different streams, or
+ *   different threads) race; issue them in stream order on one stream.
+ * Arguments as tapout_draft_stats, except:
+ *   no u_draft / sampled_tok (draft-token sampling needs a context);
+ *   n_arms, rule, threshold: HOST arrays [n_arms] describing the arm pool that
+ *     `arm` indexes (required with arm; only the rules that carry no state
+ *     between drafts: SVIP, MAXCONF, MARGIN; others: TAPOUT_EUNSUPPORTED);
+ *   arm is [B] (sequence-level).
+ * Errors are described by tapout_last_error(NULL) on the calling thread.
+ */
+#define TAPOUT_STATIC_MAX_PARTIALS 131072
+TAPOUT_API tapout_status tapout_draft_stats_static(const tapout_logits *draft, int32_t B, int32_t K, int32_t V,
+                                 const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 int32_t n_arms, const int32_t *rule, const float *threshold,
+                                 float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
+                                 int32_t *top1_id, float *logq_tok,
+                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream);
 
 /*
  * Vocabulary-sharded operation (the lm_head is tensor-parallel and this GPU holds

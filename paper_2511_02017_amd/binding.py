@@ -25,7 +25,7 @@ FLAG_BAD_ROW, FLAG_BAD_TOKEN, FLAG_BAD_NDRAFT, FLAG_SAMPLER_EXHAUSTED = 1, 2, 4,
 STATUS = {0: "TAPOUT_OK", 1: "TAPOUT_EINVAL", 2: "TAPOUT_EUNSUPPORTED", 3: "TAPOUT_ENOMEM", 4: "TAPOUT_EHIP"}
 
 EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_last_error",
-           "tapout_bandit_select", "tapout_draft_stats", "tapout_verify", "tapout_bandit_update",
+           "tapout_bandit_select", "tapout_draft_stats", "tapout_draft_stats_static", "tapout_verify", "tapout_bandit_update",
            "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_rule_state_get", "tapout_rule_state_set",
            "tapout_shard_stats", "tapout_draft_stats_sharded", "tapout_verify_accept_sharded",
            "tapout_shard_final_sums", "tapout_shard_final_token",
@@ -75,6 +75,7 @@ def load_library():
         lib.tapout_last_error.argtypes = [vp]
         lib.tapout_bandit_select.argtypes = [vp, i32, vp, vp, vp, vp]
         lib.tapout_draft_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 16
+        lib.tapout_draft_stats_static.argtypes = [C.POINTER(TapoutLogits), i32, i32, i32, vp, vp, vp, i32, vp, vp] + [vp] * 11
         lib.tapout_shard_stats.argtypes = [vp, C.POINTER(TapoutLogits), i32, i32, i32, i32, vp, i32, vp, vp, vp]
         lib.tapout_draft_stats_sharded.argtypes = [vp, vp, i32, i32, i32, i32] + [vp] * 14
         lib.tapout_verify_accept_sharded.argtypes = [vp, vp, i32, i32, i32, i32] + [vp] * 15
@@ -130,6 +131,42 @@ def _logits(t, name) -> TapoutLogits:
 def _stream(stream):
     s = torch.cuda.current_stream() if stream is None else stream
     return s.cuda_stream
+
+
+STATIC_MAX_PARTIALS = 131072
+
+
+def draft_stats_static(draft, draft_tok=None, k_len=None, arm=None, rules=(RULE_SVIP, RULE_MAXCONF, RULE_MARGIN),
+                       thresholds=(0.6, 0.8, 0.2), out=None, stream=None):
+    """tapout_draft_stats_static: the draft signals and stop positions without a context and without any allocation
+    inside the library (its scratch is a fixed array in the library's device image).  `out`: dict of output tensors as
+    Tapout.alloc_draft_outputs makes them (allocated here, by torch, when None).  Returns the dict."""
+    lib = load_library()
+    B, K, V = draft.shape
+    dev = draft.device
+    f32, i32 = torch.float32, torch.int32
+    if out is None:
+        f = lambda: torch.full((B, K), float("nan"), dtype=f32, device=dev)
+        out = dict(lse=f(), entropy=f(), p_top1=f(), p_top2=f(), margin=f(), logq_tok=f(),
+                   top1_id=torch.full((B, K), -1, dtype=i32, device=dev), n_stop=torch.zeros(B, dtype=i32, device=dev),
+                   stop_fired=torch.zeros((B, K), dtype=torch.uint8, device=dev), flags=torch.zeros(B, dtype=i32, device=dev))
+    lg = _logits(draft, "draft")
+    n = len(rules)
+    rule_h, th_h = (C.c_int32 * max(n, 1))(*rules), (C.c_float * max(n, 1))(*thresholds)
+    with torch.cuda.device(dev):
+        st = lib.tapout_draft_stats_static(
+            C.byref(lg), B, K, V, _ptr(draft_tok, i32, (B, K), "draft_tok"), _ptr(k_len, i32, (B,), "k_len"),
+            _ptr(arm, i32, (B,), "arm"), n, C.cast(rule_h, C.c_void_p), C.cast(th_h, C.c_void_p),
+            _ptr(out.get("lse"), f32, (B, K), "lse"), _ptr(out.get("entropy"), f32, (B, K), "entropy"),
+            _ptr(out.get("p_top1"), f32, (B, K), "p_top1"), _ptr(out.get("p_top2"), f32, (B, K), "p_top2"),
+            _ptr(out.get("margin"), f32, (B, K), "margin"), _ptr(out.get("top1_id"), i32, (B, K), "top1_id"),
+            _ptr(out.get("logq_tok"), f32, (B, K), "logq_tok") if draft_tok is not None else None,
+            _ptr(out.get("n_stop"), i32, (B,), "n_stop") if arm is not None else None,
+            _ptr(out.get("stop_fired"), torch.uint8, (B, K), "stop_fired") if arm is not None else None,
+            _ptr(out.get("flags"), i32, (B,), "flags"), _stream(stream))
+    if st != 0:
+        raise TapoutError(st, lib.tapout_last_error(None).decode())
+    return out
 
 
 class Tapout:

@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -40,6 +41,12 @@ struct tapout_ctx {
     unsigned prof_tick[TAPOUT_PROFILE_KINDS] = {0};
     char err[256] = {0};
 };
+
+// Scratch of tapout_draft_stats_static, the entry point that allocates nothing: its slice partials live here instead
+// of in context memory.  Every GPU the library runs on holds its own copy at its own address until the process ends.
+// In host code the name is only a handle for the symbol: the device address is looked up once per device
+// (static_scratch below) and that pointer is what kernels get.
+static __device__ __align__(256) unsigned char scratch[(size_t)TAPOUT_STATIC_MAX_PARTIALS * sizeof(Partial)];
 
 namespace {
 
@@ -87,18 +94,44 @@ int slice_vectors(int V, int dtype, int nsplit)
 // slice_bytes when rows are many (a launch ends ragged by about half the duration of one workgroup, so
 // workgroups that stream a whole long row cost several percent of the launch); never below min_slice
 // elements per slice, which no longer amortises a workgroup's fixed cost.
-int choose_nsplit(const tapout_ctx *ctx, int64_t rows, int V, int dtype)
+int choose_nsplit_for(int wgs_target, int min_slice, int slice_bytes, int64_t rows, int V, int dtype)
 {
     const int64_t row_bytes = (int64_t)V * (dtype == TAPOUT_F32 ? 4 : 2);
-    int64_t want = (ctx->wgs_target + rows - 1) / rows;
-    const int64_t by_bytes = row_bytes / ctx->slice_bytes;
+    int64_t want = (wgs_target + rows - 1) / rows;
+    const int64_t by_bytes = row_bytes / slice_bytes;
     if (want < by_bytes) want = by_bytes;
-    int64_t by_size = V / ctx->min_slice;
+    int64_t by_size = V / min_slice;
     if (by_size < 1) by_size = 1;
     if (want > by_size) want = by_size;
     if (want > kStageCap) want = kStageCap;      // an epilogue stages whole rows of partials in LDS
     if (want < 1) want = 1;
     return (int)want;
+}
+
+int choose_nsplit(const tapout_ctx *ctx, int64_t rows, int V, int dtype)
+{
+    return choose_nsplit_for(ctx->wgs_target, ctx->min_slice, ctx->slice_bytes, rows, V, dtype);
+}
+
+// ---- device address of the static scratch, per device ------------------------------------------------
+constexpr size_t kStaticPartials = TAPOUT_STATIC_MAX_PARTIALS;
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {nullptr};
+
+// Device address of `scratch` on the current device `dev`, or NULL (the HIP error is left in *err).
+Partial *static_scratch(int dev, hipError_t *err)
+{
+    *err = hipSuccess;
+    if (dev < 0 || dev >= kMaxDevices) { *err = hipErrorInvalidDevice; return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        *err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (*err != hipSuccess || !p) { if (*err == hipSuccess) *err = hipErrorInvalidSymbol; return nullptr; }
+        g_scratch_ptr[dev] = p;
+    }
+    return (Partial *)g_scratch_ptr[dev];
 }
 
 const char *check_logits(const tapout_logits *l, const char *name, int V, int rows_k, char *buf)
@@ -402,6 +435,58 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     }
     e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, [&](Timing tm) { return launch_draft_finalize(f, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft finalize launch");
+}
+
+tapout_status tapout_draft_stats_static(const tapout_logits *draft, int32_t B, int32_t K, int32_t V,
+                                 const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 int32_t n_arms, const int32_t *rule, const float *threshold,
+                                 float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
+                                 int32_t *top1_id, float *logq_tok,
+                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream)
+{
+    if (B < 0 || B > 65535) return fail(nullptr, TAPOUT_EINVAL, "B = %d outside [0, 65535]", B);
+    if (K < 1 || K > kScanCap) return fail(nullptr, TAPOUT_EINVAL, "K = %d outside [1, %d]", K, kScanCap);
+    if (V < 1) return fail(nullptr, TAPOUT_EINVAL, "V = %d must be positive", V);
+    if (B == 0) return TAPOUT_OK;
+    char buf[128];
+    if (const char *m = check_logits(draft, "draft", V, K, buf)) return fail(nullptr, TAPOUT_EINVAL, "%s", m);
+    if (arm) {
+        if (!n_stop && !stop_fired) return fail(nullptr, TAPOUT_EINVAL, "arm given but neither n_stop nor stop_fired");
+        if (n_arms < 1 || n_arms > TAPOUT_MAX_ARMS || !rule || !threshold)
+            return fail(nullptr, TAPOUT_EINVAL, "arm given: need 1 <= n_arms <= %d, rule and threshold", TAPOUT_MAX_ARMS);
+        for (int a = 0; a < n_arms; ++a) {
+            if (rule[a] != TAPOUT_RULE_SVIP && rule[a] != TAPOUT_RULE_MAXCONF && rule[a] != TAPOUT_RULE_MARGIN)
+                return fail(nullptr, TAPOUT_EUNSUPPORTED, "arm %d: rule %d carries state between drafts and needs a context", a, rule[a]);
+            if (!(threshold[a] == threshold[a])) return fail(nullptr, TAPOUT_EINVAL, "arm %d: threshold is NaN", a);
+        }
+    }
+    const int64_t rows = (int64_t)B * K;
+    const int nsplit = choose_nsplit_for(4096, 4096, 65536, rows, V, draft->dtype);       // the defaults of a context
+    if ((uint64_t)rows * (uint64_t)nsplit > kStaticPartials)
+        return fail(nullptr, TAPOUT_EINVAL, "B * K * slices = %lld x %d exceeds the static scratch of %zu slice partials",
+                    (long long)rows, nsplit, kStaticPartials);
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(nullptr, e, "hipGetDevice");
+    Partial *part = static_scratch(dev, &e);
+    if (!part) return hip_fail(nullptr, e, "hipGetSymbolAddress(scratch)");
+    hipStream_t st = (hipStream_t)stream;
+    RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, slice_vectors(V, draft->dtype, nsplit), (int32_t)rows, k_len, 0, part};
+    e = launch_row_reduce(r, draft->dtype, true, st, Timing{});
+    if (e != hipSuccess) return hip_fail(nullptr, e, "draft pass launch");
+    DraftFinalArgs f{};
+    f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
+    f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = part;
+    f.draft_tok = draft_tok; f.k_len = k_len; f.arm = arm;
+    f.n_arms = arm ? n_arms : 0;
+    for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) {
+        f.rule[a] = (arm && a < n_arms) ? rule[a] : TAPOUT_RULE_SVIP;
+        f.threshold[a] = (arm && a < n_arms) ? threshold[a] : 0.0f;
+    }
+    f.lse = lse; f.entropy = entropy; f.p_top1 = p_top1; f.p_top2 = p_top2; f.margin = margin; f.logq_tok = logq_tok;
+    f.top1_id = top1_id; f.n_stop = n_stop; f.stop_fired = stop_fired; f.flags = flags;
+    e = launch_draft_finalize(f, st, Timing{});
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(nullptr, e, "draft finalize launch");
 }
 
 tapout_status tapout_shard_stats(tapout_ctx *ctx, const tapout_logits *shard,

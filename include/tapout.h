@@ -329,8 +329,13 @@ TAPOUT_API tapout_status tapout_draft_stats_static(const tapout_logits *draft, i
  * what tapout_draft_stats returns for the unsplit rows.  Records combine with
  * the associative rule the library uses between the slices of a row.
  *   max     largest logit of the slice (-inf for a fully masked slice)
- *   sum     sum_j 2^(x_j log2(e) - R), R = ceil(max log2(e)) (0 if max = -inf)
- *   ent     sum_j 2^(x_j log2(e) - R) (x_j log2(e) - R)
+ *   sum     sum_j 2^(x_j log2(e) - R), R = ceil(max log2(e)) (0 if max = -inf),
+ *           over every element of the slice EXCEPT the first maximum (the one
+ *           at `argmax`): the entropy of a peaked row is made of small terms,
+ *           which a binary32 sum that also held the dominant one would round
+ *           away; whoever merges the records adds the maximum's own term
+ *           2^(max log2(e) - R) back in double
+ *   ent     sum_j 2^(x_j log2(e) - R) (x_j log2(e) - R), over the same elements
  *   second  second largest logit of the slice, duplicates counted
  *   argmax  GLOBAL index (vocab_offset + local) of the first maximum
  *   x_tok   logit of the row's drafted token if its id lies in this slice,

@@ -421,7 +421,7 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     }
     DraftFinalArgs f{};
     f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
-    f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = ctx->part;
+    f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.per = r.per; f.part = ctx->part;
     f.draft_tok = draft_tok; f.k_len = k_len; f.arm = arm;
     f.arm_stride = ctx->positions > 1 ? ctx->cfg.max_k : 0;
     f.n_arms = ctx->cfg.n_arms;
@@ -476,7 +476,7 @@ tapout_status tapout_draft_stats_static(const tapout_logits *draft, int32_t B, i
     if (e != hipSuccess) return hip_fail(nullptr, e, "draft pass launch");
     DraftFinalArgs f{};
     f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
-    f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.part = part;
+    f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.per = r.per; f.part = part;
     f.draft_tok = draft_tok; f.k_len = k_len; f.arm = arm;
     f.n_arms = arm ? n_arms : 0;
     for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) {
@@ -515,7 +515,7 @@ tapout_status tapout_shard_stats(tapout_ctx *ctx, const tapout_logits *shard,
     hipError_t e = timed(ctx, rows_mode ? TAPOUT_PROFILE_TARGET_PASS : TAPOUT_PROFILE_DRAFT_PASS,
                          [&](Timing tm) { return launch_row_reduce(r, shard->dtype, true, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "shard pass launch");
-    ShardMergeArgs m{shard->ptr, shard->dtype, shard->stride_b, shard->stride_k, B, KK, Vs, nsplit, vocab_offset, rows_mode,
+    ShardMergeArgs m{shard->ptr, shard->dtype, shard->stride_b, shard->stride_k, B, KK, Vs, nsplit, r.per, vocab_offset, rows_mode,
                      ctx->part, len, tok, (Partial *)out};
     e = launch_shard_merge(m, st, Timing{});
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "shard merge launch");

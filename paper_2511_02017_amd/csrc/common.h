@@ -10,6 +10,7 @@
 namespace tapout {
 
 constexpr int kBlock = 256;          // threads per workgroup of the streaming kernels (4 wavefronts)
+constexpr int kStreamU = 4;          // 16-byte vectors a thread of the streaming kernels has in flight (one batch)
 constexpr int kWave = 64;
 constexpr float kLog2e = 1.44269504088896340736f;   // binary32 nearest to log2(e); also used (widened) by the finalisers
 constexpr double kLn2 = 0.693147180559945309417232121458;
@@ -19,13 +20,17 @@ constexpr double kLn2 = 0.693147180559945309417232121458;
 // integer reference R = ceil(v1 * log2 e):  S = sum 2^(x*log2e - R),
 // T = sum 2^(x*log2e - R) * (x*log2e - R).  Changing the reference by an
 // integer is an exact power-of-two scaling, so merging loses nothing.
+// Target rows: S runs over the whole slice.  Draft rows: S and T leave out the batch of vectors in which the
+// slice's first maximum was met (see the streaming kernel); the epilogue adds that batch's elements back from the
+// logits, the first maximum itself as an exact term.  Shard records: S and T leave out the first maximum element only.
 struct Partial {
     float v1;        // slice maximum (NaN entries ignored), -inf for an empty slice
     float S;
     float T;         // draft rows only
     float v2;        // second largest value of the slice counting duplicates (draft rows only)
-    int32_t cand;    // element index at which an 8- (bf16) / 4- (f32) element window holding the first maximum starts
-    int32_t pad[3];  // a record of a vocabulary shard (tapout_shard_stat, same layout) carries the bits of x_tok in pad[0]
+    int32_t cand;    // element index at which the 8- (bf16) / 4- (f32) element vector holding the first maximum starts
+                     // (shard records: the global index of the first maximum itself)
+    int32_t pad[3];  // pad[0]: bits of the logit of the row's token if the slice / shard holds it, else NaN
 };
 static_assert(sizeof(Partial) == 32, "Partial is one 32-byte record");
 static_assert(sizeof(tapout_shard_stat) == sizeof(Partial), "shard records are staged and merged as partials");
@@ -89,6 +94,7 @@ hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipSt
 struct DraftFinalArgs {
     const void *base; int32_t dtype; int64_t stride_b, stride_k;
     int32_t B, K, V, nsplit;
+    int32_t per;                  // 16-byte vectors per slice of the streaming pass that wrote `part`
     const Partial *part;
     const int32_t *draft_tok, *k_len, *arm;
     int32_t arm_stride;           // 0: arm[b] decides every step; > 0 (token-level bandits): step k uses arm[b * arm_stride + k]
@@ -110,7 +116,7 @@ hipError_t launch_draft_finalize(const DraftFinalArgs &a, hipStream_t st, Timing
 // One record per live row of a vocabulary shard from its slice partials (see tapout_shard_stats).
 struct ShardMergeArgs {
     const void *base; int32_t dtype; int64_t stride_b, stride_k;
-    int32_t B, KK, Vs, nsplit, vocab_offset, rows_mode;
+    int32_t B, KK, Vs, nsplit, per, vocab_offset, rows_mode;
     const Partial *part; const int32_t *len, *tok;
     Partial *out;
 };
@@ -306,97 +312,265 @@ __device__ inline T pick8(const T (&v)[TAPOUT_MAX_ARMS], int i)
     return r;
 }
 
-// Merged statistics of all slices of one row, in double.
-struct RowTotal {
-    float M;          // row maximum
-    double R;         // integer reference of M
-    double S, T;      // base-2 sums relative to R
-    float v2;
-    int32_t cand;
-    bool bad;
-};
-
-__device__ inline RowTotal merge_partials(const Partial *p /* LDS */, int nsplit)
-{
-    RowTotal r;
-    float M = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) M = fmaxf(M, p[s].v1);
-    r.M = M;
-    r.R = (double)ref_of_max(M);
-    double S = 0.0, T = 0.0;
-    float v2 = -INFINITY;
-    int32_t cand = 0x7fffffff;
-    bool seen_max = false;
-    for (int s = 0; s < nsplit; ++s) {
-        float v1 = p[s].v1;
-        if (v1 == -INFINITY && !(p[s].S != p[s].S)) continue;     // empty slice (a NaN sum still has to poison the row)
-        double d = r.R - (double)ref_of_max(v1);                  // >= 0, integer
-        int di = d > 4000.0 ? 4000 : (int)d;                      // 2^-4000 underflows to 0 as it should
-        double Si = (double)p[s].S, Ti = (double)p[s].T;
-        S += ldexp(Si, -di);                                      // exact power-of-two scaling
-        T += ldexp(Ti - d * Si, -di);
-        // second largest of the union, duplicates counted
-        if (v1 == M) {
-            if (seen_max) v2 = M; else seen_max = true;
-            if (p[s].cand < cand) cand = p[s].cand;
-        } else {
-            v2 = fmaxf(v2, v1);
-        }
-        v2 = fmaxf(v2, p[s].v2);
-    }
-    r.S = S; r.T = T; r.v2 = v2; r.cand = cand;
-    r.bad = !(S > 0.0) || !(S < INFINITY) || M == -INFINITY || M == INFINITY;
-    return r;
-}
-
-// ---- lane-parallel merge ------------------------------------------------------------------------
-// merge_partials walks the slices of a row one after the other: eight dependent LDS reads and rescalings, about
-// 1.4 us of a per-sequence kernel whose every other step is one memory round trip.  When the rows of a sequence
-// times the slice count rounded up to a power of two (P <= 16) fit two passes of one workgroup, thread t instead
-// takes partial (row t / P, slice t % P) straight from memory (and the partial 256 / P rows further on in the
-// second pass), and the P lanes of a row combine their records with DPP exchanges in log2 P steps.  The combination is commutative, so both partners of an exchange, and in the end
-// all lanes of a group, hold the same bits; the first lane of the group puts the row's total into LDS.
-struct MergeElem {
+// ---- merging the statistics of the pieces of a row ---------------------------------------------------
+// A piece is one slice of a row (a Partial) or one vocabulary shard of it (a shard record).  Two kinds:
+//   EXCL = false  S, T run over every element of the piece (target rows of the unsharded path);
+//   EXCL = true   S, T leave the piece's first maximum element out (draft rows and all shard records): the entropy of a
+//                 peaked row is made of small terms, and they must not share a binary32 sum with the dominant one.
+//                 When two pieces meet, the maximum of the one that does not hold the row's maximum is an ordinary
+//                 term again and is added in (binary32 exponential: it is either negligible or the row is not peaked);
+//                 the row's own first maximum is added at the very end as an exact double term.
+struct Piece {
     float M;          // maximum (-inf: no finite element)
     double S, T;      // base-2 sums relative to ref_of_max(M)
-    float v2;
-    int32_t cand;
-    float xt;         // logit of the row's token if this slice holds it, else NaN
+    float v2;         // second largest, duplicates counted
+    int32_t idx;      // EXCL: index of the first maximum; else: start of the vector that holds it
+    float xt;         // logit of the row's token if this piece holds it, else NaN
 };
-struct RowSlot { RowTotal r; float xt; };
 
-__device__ inline bool merge_elem_empty(const MergeElem &e) { return e.M == -INFINITY && !(e.S != e.S); }
+__device__ inline bool piece_empty(const Piece &e) { return e.M == -INFINITY && !(e.S != e.S); }
 
-__device__ inline MergeElem merge_pair(const MergeElem &a, const MergeElem &b)
+__device__ inline Piece empty_piece()
 {
-    MergeElem o;
-    const bool ea = merge_elem_empty(a), eb = merge_elem_empty(b);
-    const float M = fmaxf(a.M, b.M);
-    const double R = (double)ref_of_max(M);
-    const double da = R - (double)ref_of_max(a.M), db = R - (double)ref_of_max(b.M);       // >= 0, integers
-    const int ia = da > 4000.0 ? 4000 : (int)da, ib = db > 4000.0 ? 4000 : (int)db;
-    // an empty side contributes exact zeros (its own sums are 0; 0 * d would be NaN for d = inf only, and d is finite)
-    const double Sa = ea ? 0.0 : ldexp(a.S, -ia), Sb = eb ? 0.0 : ldexp(b.S, -ib);
-    const double Ta = ea ? 0.0 : ldexp(a.T - da * a.S, -ia), Tb = eb ? 0.0 : ldexp(b.T - db * b.S, -ib);
-    o.M = M;
-    o.S = Sa + Sb;
-    o.T = Ta + Tb;
-    o.v2 = fmaxf(fmaxf(fminf(a.M, b.M), a.v2), b.v2);                        // second largest of the union, duplicates counted
-    o.cand = a.M == b.M ? min(a.cand, b.cand) : (a.M > b.M ? a.cand : b.cand);
-    o.xt = (a.xt == a.xt) ? a.xt : b.xt;                                     // at most one slice holds the token
+    Piece e;
+    e.M = -INFINITY; e.S = 0.0; e.T = 0.0; e.v2 = -INFINITY; e.idx = 0x7fffffff; e.xt = NAN;
+    return e;
+}
+
+__device__ inline Piece piece_from_words(const u32x4 &w0, const u32x4 &w1)
+{
+    Piece e;
+    e.M = __uint_as_float(w0.x); e.S = (double)__uint_as_float(w0.y); e.T = (double)__uint_as_float(w0.z);
+    e.v2 = __uint_as_float(w0.w); e.idx = (int32_t)w1.x; e.xt = __uint_as_float(w1.y);
+    if (piece_empty(e)) { e.S = 0.0; e.T = 0.0; e.v2 = -INFINITY; e.idx = 0x7fffffff; }       // one image for every empty piece
+    return e;
+}
+__device__ inline Piece piece_from_partial(const Partial &p)
+{
+    const u32x4 *w = (const u32x4 *)&p;
+    return piece_from_words(w[0], w[1]);
+}
+
+// Commutative: both partners of an exchange compute the same bits.
+template <bool EXCL>
+__device__ inline Piece merge_pair(const Piece &a, const Piece &b)
+{
+    const bool a_wins = a.M > b.M || (a.M == b.M && a.idx <= b.idx);            // the piece with the row's first maximum
+    const float Mw = a_wins ? a.M : b.M, Ml = a_wins ? b.M : a.M;
+    const double Sw = a_wins ? a.S : b.S, Sl = a_wins ? b.S : a.S;
+    const double Tw = a_wins ? a.T : b.T, Tl = a_wins ? b.T : a.T;
+    const float Rw = ref_of_max(Mw);
+    const double d = (double)Rw - (double)ref_of_max(Ml);                       // integer; >= 0 unless the other piece is empty
+    const int di = d > 4000.0 ? 4000 : (d < -4000.0 ? -4000 : (int)d);          // 2^-4000 underflows to 0 as it should
+    Piece o;
+    o.M = Mw;
+    o.S = Sw + ldexp(Sl, -di);                                                  // exact power-of-two scaling
+    o.T = Tw + ldexp(Tl - d * Sl, -di);
+    if constexpr (EXCL) {
+        if (Ml > -INFINITY) {                                                   // the other piece's maximum: an ordinary term here
+            const float y = __builtin_fmaf(Ml, kLog2e, -Rw);
+            const float e = __builtin_amdgcn_exp2f(y);
+            o.S += (double)e;
+            o.T += (double)e * (double)fmaxf(y, -200.0f);
+        }
+    }
+    o.v2 = fmaxf(fmaxf(fminf(a.M, b.M), a.v2), b.v2);                           // second largest of the union, duplicates counted
+    o.idx = a_wins ? a.idx : b.idx;
+    o.xt = (a.xt == a.xt) ? a.xt : b.xt;                                        // at most one piece holds the token
     return o;
 }
 
+// Merged statistics of a whole row, in double.
+struct RowTotal {
+    float M;          // row maximum
+    double R;         // integer reference of M
+    double Sx, Tx;    // the merged base-2 sums relative to R as the pieces carry them: EXCL: without the row's first maximum
+    double yM;        // M log2e - R, in (-1, 0]
+    double eM;        // EXCL: 2^yM to binary32 precision, the term of the first maximum; else 0
+    double S;         // sum over ALL elements: Sx + eM
+    float v2;
+    int32_t cand;     // EXCL: index of the first maximum; else: start of the vector that holds it
+    bool bad;
+};
+
+template <bool EXCL>
+__device__ inline RowTotal row_total(const Piece &p)
+{
+    RowTotal r;
+    r.M = p.M;
+    r.R = (double)ref_of_max(p.M);
+    const bool finite = p.M > -INFINITY && p.M < INFINITY;
+    r.yM = finite ? (double)p.M * (double)kLog2e - r.R : 0.0;
+    r.eM = (EXCL && finite) ? (double)__builtin_amdgcn_exp2f((float)r.yM) : 0.0;
+    r.Sx = p.S; r.Tx = p.T;
+    r.S = p.S + r.eM;
+    r.v2 = p.v2; r.cand = p.idx;
+    r.bad = !(r.S > 0.0) || !(r.S < INFINITY) || !finite;
+    return r;
+}
+
+// Signals of a row whose sums leave the first maximum out (EXCL), written so that the binary32 error of eM and of the
+// sums enters every result as a RELATIVE error, however peaked the row: with eps = Sx / eM (everything but the maximum,
+// relative to it),
+//   log2 sum_j 2^(x_j log2e) = R + yM + log2(1 + eps)          exactly: no eM in it
+//   H / ln 2 = log2(1 + eps) + (yM eps - Tx / eM) / (1 + eps)
+//   p_top1 = 1 / (1 + eps),  p_top2 = r2 p_top1,  margin = (1 - r2) p_top1,  r2 = 2^((v2 - M) log2e)  (double: a margin
+//   between near-tied logits is the small difference 1 - r2)
+struct RowSignals { double lse, H, p1, p2, margin; };
+__device__ inline RowSignals row_signals(const RowTotal &r, bool has_second)
+{
+    RowSignals o;
+    const double inv = 1.0 / r.eM, eps = r.Sx * inv;
+    const double l2 = log2(1.0 + eps);
+    o.p1 = 1.0 / (1.0 + eps);
+    o.lse = (r.R + r.yM + l2) * kLn2;
+    const double Hd = (l2 + (r.yM * eps - r.Tx * inv) * o.p1) * kLn2;
+    o.H = Hd > 0.0 ? Hd : 0.0;
+    const double r2 = has_second ? exp2(((double)r.v2 - (double)r.M) * (double)kLog2e) : 0.0;
+    o.p2 = r2 * o.p1;
+    o.margin = (1.0 - r2) * o.p1;
+    return o;
+}
+
+// The batch of vectors (or the single head / tail element) of the draft pass in which a slice met its first
+// maximum, as the streaming kernel laid its work out: thread t of the slice's workgroup takes vectors
+// v0 + t + q * kBlock, q = 0, 1, ..., in batches of kStreamU.  `cand` is the element index at which the vector with the
+// first maximum starts (or the index of a head / tail element).  All addresses are checked against the slice.
+struct BatchRegs {
+    u32x4 w[kStreamU];
+    uint32_t valid;       // bit u: vector u is loaded; bit 8: a single element, its bits in w[0].x
+    int32_t first;        // element index of vector 0 (or of the single element)
+    int32_t ucand;        // which vector of the batch the candidate is: the one that holds the first maximum
+};
+
+template <int DT>
+__device__ inline BatchRegs batch_issue_t(const void *row, int32_t V, int32_t cand, int split, int per)
+{
+    constexpr int VEC = Elem<DT>::vec;
+    BatchRegs b;
+    b.valid = 0; b.first = 0; b.ucand = 0;
+#pragma unroll
+    for (int u = 0; u < kStreamU; ++u) b.w[u] = u32x4{0u, 0u, 0u, 0u};
+    if (cand < 0 || cand >= V) return b;
+    int head, nvec, tail;
+    row_geometry<DT>(row, V, head, nvec, tail);
+    if (cand < head || cand >= head + nvec * VEC) {
+        b.w[0].x = __float_as_uint(load_elem<DT>(row, cand));
+        b.valid = 0x100u; b.first = cand;
+        return b;
+    }
+    const int i = (cand - head) / VEC;
+    const int v0 = min(split * per, nvec), v1e = min(v0 + per, nvec);
+    if (i < v0 || i >= v1e) return b;                                           // not a candidate of this slice: stale record
+    const int rel = i - v0, t = rel % kBlock, q0 = (rel / kBlock) / kStreamU * kStreamU;
+    const u32x4 *vp = (const u32x4 *)((const char *)row + (int64_t)head * Elem<DT>::size);
+    b.first = head + (v0 + t + q0 * kBlock) * VEC;
+    b.ucand = rel / kBlock - q0;
+#pragma unroll
+    for (int u = 0; u < kStreamU; ++u) {
+        const int iu = v0 + t + (q0 + u) * kBlock;
+        if (iu < v1e) { b.w[u] = vp[iu]; b.valid |= 1u << u; }
+    }
+    return b;
+}
+__device__ inline BatchRegs batch_issue(const void *row, int dtype, int32_t V, int32_t cand, int split, int per)
+{
+    return dtype == TAPOUT_F32 ? batch_issue_t<TAPOUT_F32>(row, V, cand, split, per) : batch_issue_t<TAPOUT_BF16>(row, V, cand, split, per);
+}
+
+// The elements of a piece's left-out batch, except the first one equal to the piece's maximum M: their two sums
+// relative to ref_of_max(M) (binary32 terms as in the streaming pass: they are small, or the row is not peaked) and
+// the index of that first maximum (0x7fffffff if the batch does not hold it).
+struct BatchExtra { float sa, ta; int32_t idx; };
+
+// The first maximum lies in the candidate vector (the thread's running maximum reached M there: the vectors before it
+// in the batch are below M, equal values after it are duplicates and count as ordinary terms), so only that vector is
+// searched.  The entropy terms are formed without looking at them; a masked (-inf) logit makes their sum NaN
+// (0 * -inf), and only then they are formed again with the exponent clamped.
+template <int DT>
+__device__ inline BatchExtra batch_extra_t(float M, const BatchRegs &b)
+{
+    constexpr int VEC = Elem<DT>::vec;
+    const float R = ref_of_max(M);
+    BatchExtra o;
+    o.sa = 0.0f; o.ta = 0.0f; o.idx = 0x7fffffff;
+    auto sums = [&](bool clamp) {
+        float sa = 0.0f, ta = 0.0f;
+        int32_t idx = 0x7fffffff;
+        if (b.valid & 0x100u) {
+            const float x = __uint_as_float(b.w[0].x);
+            if (x == M) idx = b.first;
+            else {
+                const float y = __builtin_fmaf(x, kLog2e, -R), e = __builtin_amdgcn_exp2f(y);
+                sa = e; ta = e * (clamp ? fmaxf(y, -200.0f) : y);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kStreamU; ++u) {
+            if (!((b.valid >> u) & 1u)) continue;
+            float x[VEC];
+            unpack<DT>(b.w[u], x);
+            const bool search = u == b.ucand;
+#pragma unroll
+            for (int j = 0; j < VEC; ++j) {
+                const bool first = search && x[j] == M && idx == 0x7fffffff;
+                const float y = __builtin_fmaf(x[j], kLog2e, -R);
+                const float e = first ? 0.0f : __builtin_amdgcn_exp2f(y);
+                if (search) idx = first ? b.first + u * kBlock * VEC + j : idx;
+                sa += e;
+                ta = __builtin_fmaf(e, clamp ? fmaxf(y, -200.0f) : y, ta);
+            }
+        }
+        o.sa = sa; o.ta = ta; o.idx = idx;
+    };
+    sums(false);
+    if (o.ta != o.ta) sums(true);
+    return o;
+}
+__device__ inline BatchExtra batch_extra(const Piece &p, const BatchRegs &b, int dtype)
+{
+    if (piece_empty(p) || !b.valid) { BatchExtra o; o.sa = 0.0f; o.ta = 0.0f; o.idx = 0x7fffffff; return o; }
+    return dtype == TAPOUT_F32 ? batch_extra_t<TAPOUT_F32>(p.M, b) : batch_extra_t<TAPOUT_BF16>(p.M, b);
+}
+
+// Completes a piece of the draft pass: the left-out batch back in, all but the first maximum, whose index becomes idx.
+__device__ inline void batch_fix(Piece &p, const BatchRegs &b, int dtype)
+{
+    const BatchExtra x = batch_extra(p, b, dtype);
+    p.S += (double)x.sa; p.T += (double)x.ta;
+    p.idx = x.idx;
+}
+
+// Sequential merge of the `n` pieces of one row held as Partials (LDS or memory) at stride `stride` records.
+// EXCL pieces must have been completed (batch_fix) before: idx exact, only the first maximum left out.
+template <bool EXCL>
+__device__ inline RowTotal merge_partials(const Partial *p, int n, int stride = 1)
+{
+    Piece acc = empty_piece();
+    for (int s = 0; s < n; ++s) acc = merge_pair<EXCL>(acc, piece_from_partial(p[(int64_t)s * stride]));
+    return row_total<EXCL>(acc);
+}
+
+// ---- lane-parallel merge ------------------------------------------------------------------------
+// A sequential merge walks the slices of a row one after the other: eight dependent LDS reads and rescalings, about
+// 1.4 us of a per-sequence kernel whose every other step is one memory round trip.  When the rows of a sequence
+// times the slice count rounded up to a power of two (P <= 16) fit two passes of one workgroup, thread t instead
+// takes partial (row t / P, slice t % P) straight from memory (and the partial 256 / P rows further on in the
+// second pass), and the P lanes of a row combine their records with DPP exchanges in log2 P steps.  The combination
+// is commutative, so both partners of an exchange, and in the end all lanes of a group, hold the same bits; the
+// first lane of the group puts the row's total into LDS.
+struct RowSlot { RowTotal r; float xt; };
+
 template <int CTRL>
-__device__ inline MergeElem merge_elem_dpp(const MergeElem &e)
+__device__ inline Piece piece_dpp(const Piece &e)
 {
     auto mv = [](int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); };
-    MergeElem o;
+    Piece o;
     o.M = __int_as_float(mv(__float_as_int(e.M)));
     o.S = __hiloint2double(mv(__double2hiint(e.S)), mv(__double2loint(e.S)));
     o.T = __hiloint2double(mv(__double2hiint(e.T)), mv(__double2loint(e.T)));
     o.v2 = __int_as_float(mv(__float_as_int(e.v2)));
-    o.cand = mv(e.cand);
+    o.idx = mv(e.idx);
     o.xt = __int_as_float(mv(__float_as_int(e.xt)));
     return o;
 }
@@ -430,36 +604,44 @@ __device__ inline LaneRegs lane_merge_issue(const Partial *part, int rows, int n
     return r;
 }
 
-__device__ inline void lane_merge_pass(RowSlot *sh_rows, const StageRegs &w, int row, int rows, int nsplit, int sh)
+// This thread's piece of pass q (an empty piece where the thread has none).
+__device__ inline Piece lane_piece(const LaneRegs &w, int q, int rows, int nsplit, int sh)
+{
+    const int sl = threadIdx.x & ((1 << sh) - 1), row = (threadIdx.x >> sh) + q * (256 >> sh);
+    return (row < rows && sl < nsplit) ? piece_from_words(w.p[q].w0, w.p[q].w1) : empty_piece();
+}
+
+// The pieces of the 2^sh lanes of a group combined; every lane of the group returns the same bits.
+template <bool EXCL>
+__device__ inline Piece lane_group_merge(Piece e, int sh)
+{
+    // quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror: each pairs groups that already agree
+    if (sh >= 1) e = merge_pair<EXCL>(e, piece_dpp<0xB1>(e));
+    if (sh >= 2) e = merge_pair<EXCL>(e, piece_dpp<0x4E>(e));
+    if (sh >= 3) e = merge_pair<EXCL>(e, piece_dpp<0x141>(e));
+    if (sh >= 4) e = merge_pair<EXCL>(e, piece_dpp<0x140>(e));
+    return e;
+}
+
+template <bool EXCL>
+__device__ inline void lane_merge_pass(RowSlot *sh_rows, const Piece &e0, int row, int rows, int sh)
 {
     const int sl = threadIdx.x & ((1 << sh) - 1);
-    MergeElem e;
-    if (row < rows && sl < nsplit) {
-        e.M = __uint_as_float(w.w0.x); e.S = (double)__uint_as_float(w.w0.y); e.T = (double)__uint_as_float(w.w0.z);
-        e.v2 = __uint_as_float(w.w0.w); e.cand = (int32_t)w.w1.x; e.xt = __uint_as_float(w.w1.y);
-    } else {
-        e.M = -INFINITY; e.S = 0.0; e.T = 0.0; e.v2 = -INFINITY; e.cand = 0x7fffffff; e.xt = NAN;
-    }
-    if (merge_elem_empty(e)) { e.S = 0.0; e.T = 0.0; e.v2 = -INFINITY; e.cand = 0x7fffffff; }       // one image for every empty slice
-    // quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror: each pairs groups that already agree
-    if (sh >= 1) e = merge_pair(e, merge_elem_dpp<0xB1>(e));
-    if (sh >= 2) e = merge_pair(e, merge_elem_dpp<0x4E>(e));
-    if (sh >= 3) e = merge_pair(e, merge_elem_dpp<0x141>(e));
-    if (sh >= 4) e = merge_pair(e, merge_elem_dpp<0x140>(e));
+    const Piece e = lane_group_merge<EXCL>(e0, sh);
     if (row < rows && sl == 0) {
         RowSlot o;
-        o.r.M = e.M; o.r.R = (double)ref_of_max(e.M); o.r.S = e.S; o.r.T = e.T; o.r.v2 = e.v2; o.r.cand = e.cand;
-        o.r.bad = !(e.S > 0.0) || !(e.S < INFINITY) || e.M == -INFINITY || e.M == INFINITY;
+        o.r = row_total<EXCL>(e);
         o.xt = e.xt;
         sh_rows[row] = o;
     }
 }
 
-// Combine and publish: sh_rows[row] for row < rows; ends with a barrier.
-__device__ inline void lane_merge_commit(RowSlot *sh_rows, const LaneRegs &w, int rows, int nsplit, int sh)
+// Combine and publish: sh_rows[row] for row < rows; ends with a barrier.  e0, e1: this thread's pieces of the two passes.
+template <bool EXCL>
+__device__ inline void lane_merge_commit(RowSlot *sh_rows, const Piece &e0, const Piece &e1, int rows, int sh)
 {
-    lane_merge_pass(sh_rows, w.p[0], threadIdx.x >> sh, rows, nsplit, sh);
-    if ((256 >> sh) < rows) lane_merge_pass(sh_rows, w.p[1], (threadIdx.x >> sh) + (256 >> sh), rows, nsplit, sh);   // uniform
+    lane_merge_pass<EXCL>(sh_rows, e0, threadIdx.x >> sh, rows, sh);
+    if ((256 >> sh) < rows) lane_merge_pass<EXCL>(sh_rows, e1, (threadIdx.x >> sh) + (256 >> sh), rows, sh);   // uniform
     __syncthreads();
 }
 

@@ -4,15 +4,23 @@
 // Algorithm 1's draft loop: the token drafted at the step where the selected
 // rule fires is kept, so n_stop = first firing k + 1.
 //
+// The partials of the draft pass leave out the batch of vectors in which each
+// slice met its first maximum (row_reduce.hip): every (row, slice) piece first
+// gets the elements of that batch back from the logits, except the first
+// maximum itself, which enters the row's sums at the end as an exact double
+// term.  That is what keeps the entropy of a peaked row (a small number made
+// of small terms) accurate to binary32 relative precision.
+//
 // One workgroup per sequence, one thread per row.  The kernel is latency bound
 // (O(K * nsplit) work), so it is written to keep dependent memory round trips
-// few: the partials are staged through LDS by all threads at once, the token
-// gather and the argmax window are loaded before the fp64 math that does not
-// need them, and every row decides "fires / does not fire" for itself so that
+// few: the partials are requested by all threads at once, the token gather and
+// the left-out batches travel together in a second round trip, and every row decides "fires / does not fire" for itself so that
 // the sequential part is a scan over bytes in LDS.  The two rules that look at
 // more than the current row's signals (SVIP-Difference: previous row's entropy;
 // AdaEDL: the sequence's adaptive threshold) decide in a second sweep, after all
 // entropies of the sequence are in LDS.
+#include <type_traits>
+
 #include "common.h"
 
 namespace tapout {
@@ -81,16 +89,83 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
     else if (msh >= 0) ln0 = lane_merge_issue(a.part + (int64_t)b * K * a.nsplit, K, a.nsplit, msh);
     else st0 = stage_issue(a.part + (int64_t)b * K * a.nsplit, count0);
     asm volatile("" :: "v"(kb), "v"(arm), "v"(H_carry), "v"(tok0), "v"(st0.w0), "v"(st0.w1), "v"(ln0.p[0].w0), "v"(ln0.p[0].w1), "v"(ln0.p[1].w0), "v"(ln0.p[1].w1));
+    kb = kb > K ? K : (kb < 0 ? 0 : kb);
     // Second round trip: the logit of the drafted token (its address needs the token, not k_len: rows up to K
-    // exist), in flight while the partials go through LDS and are merged.
+    // exist) and, on the lane path, the left-out batch of this thread's (row, slice) pieces.
     float xtok_first = 0.0f;
     if constexpr (!SHARDED)
         if (want_tok && (int)threadIdx.x < K && tok0 >= 0 && tok0 < a.V)
             xtok_first = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, threadIdx.x), a.dtype, tok0);
     if (threadIdx.x == 0) sh_flags = 0;                       // ahead of the barrier in the commit: rows of other wavefronts OR into it
-    if (msh >= 0) lane_merge_commit(sh_rows, ln0, K, a.nsplit, msh);
-    else stage_commit(sh_part, st0, count0);
-    kb = kb > K ? K : (kb < 0 ? 0 : kb);
+    if (msh >= 0) {
+        Piece e[2];
+        BatchRegs bt[2];
+        const int sl = threadIdx.x & ((1 << msh) - 1);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int row = (threadIdx.x >> msh) + q * (256 >> msh);
+            e[q] = lane_piece(ln0, q, kb, a.nsplit, msh);     // rows beyond k_len hold stale partials: empty pieces
+            bt[q].valid = 0;
+            if (q == 0 || (256 >> msh) < kb)
+                if (row < kb && sl < a.nsplit)
+                    bt[q] = batch_issue(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, row), a.dtype, a.V, e[q].idx, sl, a.per);
+        }
+        // While the batches travel, the pieces are merged as they are.  Then every lane adds what its own batch holds
+        // besides the first maximum: rescaled to the row's reference, summed over the row's lanes (binary32: small
+        // terms, a fixed butterfly), together with the exact index of the row's first maximum from the lane that won.
+        const bool two = (256 >> msh) < kb;                     // uniform
+        Piece m[2];
+        m[0] = lane_group_merge<true>(e[0], msh);
+        if (two) m[1] = lane_group_merge<true>(e[1], msh);
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            if (q == 1 && !two) break;
+            const BatchExtra x = batch_extra(e[q], bt[q], a.dtype);
+            const float d = ref_of_max(m[q].M) - ref_of_max(e[q].M);              // >= 0 for a piece that holds anything
+            const int di = (int)fminf(fmaxf(d, -1.0e9f), 1.0e9f);
+            float sa = ldexpf(x.sa, -di), ta = ldexpf(x.ta - d * x.sa, -di);
+            if (x.sa == 0.0f) { sa = 0.0f; ta = 0.0f; }                           // empty piece or empty batch (0 * inf)
+            int32_t idx = (e[q].M == m[q].M && e[q].idx == m[q].idx) ? x.idx : 0x7fffffff;
+            auto step = [&](auto ctrl) {
+                constexpr int C = decltype(ctrl)::value;
+                sa += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(sa), C, 0xf, 0xf, true));
+                ta += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(ta), C, 0xf, 0xf, true));
+                idx = min(idx, __builtin_amdgcn_update_dpp(0, idx, C, 0xf, 0xf, true));
+            };
+            if (msh >= 1) step(std::integral_constant<int, 0xB1>{});
+            if (msh >= 2) step(std::integral_constant<int, 0x4E>{});
+            if (msh >= 3) step(std::integral_constant<int, 0x141>{});
+            if (msh >= 4) step(std::integral_constant<int, 0x140>{});
+            const int row = (threadIdx.x >> msh) + q * (256 >> msh);
+            if (row < kb && sl == 0) {
+                Piece f = m[q];
+                f.S += (double)sa; f.T += (double)ta; f.idx = idx;
+                RowSlot o;
+                o.r = row_total<true>(f);
+                o.xt = f.xt;
+                sh_rows[row] = o;
+            }
+        }
+        __syncthreads();
+    } else {
+        stage_commit(sh_part, st0, count0);
+    }
+    // Staged path: the `count` partials of rows k0.. lie in LDS; every thread completes some of them (left-out batch
+    // back in, exact index of the first maximum into the cand slot) before the rows are merged one by one.
+    auto complete_stage = [&](int k0, int count) {
+        if constexpr (!SHARDED) {
+            for (int i = threadIdx.x; i < count; i += blockDim.x) {
+                const int k = k0 + i / a.nsplit, sl = i % a.nsplit;
+                if (k >= kb) continue;                          // stale partial of a row that was not drafted
+                Piece e = piece_from_partial(sh_part[i]);
+                const BatchRegs bt = batch_issue(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k), a.dtype, a.V, e.idx, sl, a.per);
+                batch_fix(e, bt, a.dtype);
+                sh_part[i].S = (float)e.S; sh_part[i].T = (float)e.T; sh_part[i].cand = e.idx;
+            }
+            __syncthreads();
+        }
+    };
+    if (msh < 0) complete_stage(0, count0);
     const bool arm_ok = arm >= 0 && arm < a.n_arms;
     const int rule_b = arm_ok ? pick8(a.rule, arm) : -1;
     // rows whose rule looks beyond their own signals are decided in a second sweep (uniform over the workgroup);
@@ -110,6 +185,7 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
                              (k1 - k0) * a.nsplit);
             } else {
                 stage_partials(sh_part, a.part + ((int64_t)b * K + k0) * a.nsplit, (k1 - k0) * a.nsplit);
+                complete_stage(k0, (k1 - k0) * a.nsplit);
             }
             xtok0 = 0.0f;
             if constexpr (!SHARDED)
@@ -119,12 +195,8 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t i = (int64_t)b * K + k;
             const void *row = SHARDED ? nullptr : row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
-            const RowTotal r = msh >= 0 ? sh_rows[k].r : merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
-            // the argmax window is requested here and looked at after the signals are formed
-            int32_t top1 = 0;
-            ArgmaxProbe probe;
-            if constexpr (SHARDED) top1 = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;             // a shard's argmax is exact and global
-            else if (a.top1_id) probe = argmax_issue(row, a.dtype, a.V, r.cand);
+            const RowTotal r = msh >= 0 ? sh_rows[k].r : merge_partials<true>(sh_part + (k - k0) * a.nsplit, a.nsplit);
+            const int32_t top1 = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;                      // exact: the pieces carry the index of their first maximum
             uint32_t f = 0;
             float lse, H, p1, p2, mg;
             double lse_d = NAN;
@@ -132,21 +204,16 @@ __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalA
                 f |= TAPOUT_FLAG_BAD_ROW;
                 lse = H = p1 = p2 = mg = NAN;
             } else {
-                double l2S = log2(r.S);
-                lse_d = (r.R + l2S) * kLn2;
-                double Hd = (l2S - r.T / r.S) * kLn2;
-                double p1d = exp2((double)r.M * (double)kLog2e - r.R) / r.S;
-                double p2d = (a.V > 1) ? exp2((double)r.v2 * (double)kLog2e - r.R) / r.S : 0.0;
-                lse = (float)lse_d; H = (float)(Hd > 0.0 ? Hd : 0.0);
-                p1 = (float)p1d; p2 = (float)p2d; mg = (float)(p1d - p2d);
+                const RowSignals g = row_signals(r, a.V > 1);
+                lse_d = g.lse;
+                lse = (float)g.lse; H = (float)g.H;
+                p1 = (float)g.p1; p2 = (float)g.p2; mg = (float)g.margin;
             }
             if (a.lse) a.lse[i] = lse;
             if (a.entropy) a.entropy[i] = H;
             if (a.p_top1) a.p_top1[i] = p1;
             if (a.p_top2) a.p_top2[i] = p2;
             if (a.margin) a.margin[i] = mg;
-            if constexpr (!SHARDED)
-                if (a.top1_id) top1 = argmax_finish(probe, row, a.dtype, a.V, r.cand, r.M);
             if (a.top1_id) a.top1_id[i] = top1;
             if (a.draft_tok && a.logq_tok) {
                 int32_t t = tok0;
@@ -248,10 +315,18 @@ __global__ __launch_bounds__(kFinalBlock) void shard_merge_kernel(ShardMergeArgs
     }
     if (k >= n_live) return;
     const void *row = row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
-    const RowTotal r = merge_partials(a.part + (int64_t)i * a.nsplit, a.nsplit);
+    // every slice partial gets its left-out batch back (all but the first maximum), then the slices are merged; the
+    // record leaves the row slice's first maximum out of its two sums
+    Piece acc = empty_piece();
+    for (int sl = 0; sl < a.nsplit; ++sl) {
+        Piece e = piece_from_partial(a.part[(int64_t)i * a.nsplit + sl]);
+        const BatchRegs bt = batch_issue(row, a.dtype, a.Vs, e.idx, sl, a.per);
+        batch_fix(e, bt, a.dtype);
+        acc = merge_pair<true>(acc, e);
+    }
     Partial o;
-    o.v1 = r.M; o.S = (float)r.S; o.T = (float)r.T; o.v2 = r.v2;
-    o.cand = a.vocab_offset + resolve_argmax(row, a.dtype, a.Vs, r.cand, r.M);
+    o.v1 = acc.M; o.S = (float)acc.S; o.T = (float)acc.T; o.v2 = acc.v2;
+    o.cand = a.vocab_offset + ((acc.idx >= 0 && acc.idx < a.Vs) ? acc.idx : 0);
     float xt = NAN;
     const int KT = a.KK - a.rows_mode;                       // tokens per sequence (the last target row has none)
     if (a.tok && k < KT) {

@@ -18,6 +18,15 @@
 // Only the 16-byte window in which the thread's maximum first appeared is
 // remembered; the exact argmax index is recovered later from that window.
 //
+// Draft rows: the entropy of a peaked row is a small number made of small
+// terms, and a binary32 sum that also holds the row's dominant term rounds
+// them away.  So the batch of vectors in which a thread met its maximum is
+// summed apart from the rest, and the workgroup leaves the batch that holds the
+// slice's first maximum out of its partial altogether: the sums of a partial
+// then hold "small" terms only, and the epilogue that merges the partials adds
+// the few elements of that one batch back from the logits themselves, with the
+// row's first maximum as an exact term of its own.
+//
 // Wavefront reductions use DPP row operations (no LDS traffic).  The partials
 // are merged per sequence by a second, small launch (finalize.hip for draft
 // rows, the head kernel in verify.hip for target rows): a
@@ -40,30 +49,38 @@ template <bool FULL>
 struct ThreadState {
     float v1 = -INFINITY;   // running maximum
     float v2 = -INFINITY;   // running second largest (FULL only)
-    float R = 0.0f;         // integer reference: every x seen so far has x*log2e <= R (+ rounding)
-    float xlim = -INFINITY; // largest x the current reference covers
-    float s = 0.0f;         // sum 2^(x*log2e - R)
-    float t = 0.0f;         // sum 2^y * y (FULL only)
+    float R = -1.0e30f;     // integer reference: every x seen so far has x*log2e <= R (+ rounding); -1e30: none yet
+    float s = 0.0f;         // sum 2^(x*log2e - R); FULL: without the batch in which the running maximum appeared
+    float t = 0.0f;         // sum 2^y * y (FULL only), likewise
+    float s_hi = 0.0f;      // FULL: the two sums over the batch in which the running maximum appeared
+    float t_hi = 0.0f;
     int32_t cand = 0x7fffffff;
 
     // Raise the reference so that it covers the running maximum (rare after the first few vectors).
-    __device__ inline void cover_max()
+    // sb, tb: the sums of the batch in progress (FULL).
+    __device__ inline void cover_max(float &sb, float &tb)
     {
-        if (v1 > xlim) {
+        if (__builtin_fmaf(v1, kLog2e, -R) > 0.0f) {          // also the first finite value (nothing is summed yet then)
             float Rn = ceilf(v1 * kLog2e) + kHeadroom;
             float d = Rn - R;
             int di = (int)fminf(fmaxf(d, -1.0e9f), 1.0e9f);
-            if constexpr (FULL) t = ldexpf(t - d * s, -di);
+            if constexpr (FULL) {
+                t = ldexpf(t - d * s, -di);
+                t_hi = ldexpf(t_hi - d * s_hi, -di);
+                tb = ldexpf(tb - d * sb, -di);
+                s_hi = ldexpf(s_hi, -di);
+                sb = ldexpf(sb, -di);
+            }
             s = ldexpf(s, -di);
             R = Rn;
-            xlim = Rn * (1.0f / kLog2e);
         }
     }
 
     // Maxima of N values that start at element index `first` of the row; `first` is remembered as the
     // argmax candidate when the running maximum grows.
+    // Returns whether the running maximum grew.
     template <int N>
-    __device__ inline void fold_max(const float (&x)[N], int32_t first)
+    __device__ inline bool fold_max(const float (&x)[N], int32_t first)
     {
         float old = v1;
         if constexpr (N == 1) {
@@ -76,21 +93,24 @@ struct ThreadState {
                 v1 = max3(v1, x[i], x[i + 1]);
             }
         }
-        cand = v1 > old ? first : cand;
+        const bool grew = v1 > old;
+        cand = grew ? first : cand;
+        return grew;
     }
 
     // Sums over N values the reference already covers.  The entropy sum of the group is formed without
     // looking at the terms; a masked (-inf) logit gives 0 * -inf = NaN there, and only then the group is
     // summed again with the exponent clamped (one comparison per group instead of one clamp per element).
+    // The target pass adds straight into s; the draft pass into the sums sb, tb of the batch in progress.
     template <int N>
-    __device__ inline void fold_sums(const float (&x)[N])
+    __device__ inline void fold_sums(const float (&x)[N], float &sb, float &tb)
     {
         float tv = 0.0f;
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             float y = __builtin_fmaf(x[i], kLog2e, -R);
             float e = __builtin_amdgcn_exp2f(y);
-            s += e;
+            if constexpr (FULL) sb += e; else s += e;
             if constexpr (FULL) tv = __builtin_fmaf(e, y, tv);
         }
         if constexpr (FULL) {
@@ -102,16 +122,38 @@ struct ThreadState {
                     tv = __builtin_fmaf(__builtin_amdgcn_exp2f(y), fmaxf(y, -200.0f), tv);
                 }
             }
-            t += tv;
+            tb += tv;
         }
     }
 
     template <int N>
-    __device__ inline void fold(const float (&x)[N], int32_t first)
+    __device__ inline bool fold(const float (&x)[N], int32_t first, float &sb, float &tb)
     {
-        fold_max<N>(x, first);
-        cover_max();
-        fold_sums<N>(x);
+        const bool grew = fold_max<N>(x, first);
+        cover_max(sb, tb);
+        fold_sums<N>(x, sb, tb);
+        return grew;
+    }
+
+    // End of a batch (FULL): if the running maximum grew inside it, its sums become the set-apart ones and the
+    // batch that held the previous maximum joins the rest; else it joins the rest itself.
+    __device__ inline void close_batch(bool grew, float sb, float tb)
+    {
+        if constexpr (FULL) {
+            s += grew ? s_hi : sb;
+            t += grew ? t_hi : tb;
+            s_hi = grew ? sb : s_hi;
+            t_hi = grew ? tb : t_hi;
+        }
+    }
+
+    // One element on its own (unaligned head or tail of a row): a batch of one.
+    __device__ inline void fold_single(float x0, int32_t j)
+    {
+        float sb = 0.0f, tb = 0.0f;
+        float x[1] = { x0 };
+        const bool grew = fold<1>(x, j, sb, tb);
+        close_batch(grew, sb, tb);
     }
 };
 
@@ -183,23 +225,27 @@ template <int DT, bool FULL, int U>
 __device__ inline void fold_batch(ThreadState<FULL> &st, const u32x4 (&w)[U], int i, int head)
 {
     constexpr int VEC = Elem<DT>::vec;
+    bool grew = false;                                    // a lane mask in scalar registers
+    float sb = 0.0f, tb = 0.0f;
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         float x[VEC];
         unpack<DT>(w[u], x);
-        st.template fold<VEC>(x, head + (i + u * kBlock) * VEC);
+        grew |= st.template fold<VEC>(x, head + (i + u * kBlock) * VEC, sb, tb);
     }
+    st.close_batch(grew, sb, tb);
 }
 
+// At least six wavefronts per SIMD (80 vector registers): the draft pass on bfloat16 sits right at that limit.
 template <int DT, bool FULL>
-__global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) void stream_pass_kernel(RowReduceArgs a)
 {
     constexpr int VEC = Elem<DT>::vec;
     // vectors in flight per thread.  Four is best for both passes: for the draft pass that means 77 registers
     // and six wavefronts per SIMD instead of eight, which still beats two vectors at full occupancy
     // (measured; three, six and eight vectors and an explicit prefetch of the next batch are all slower).
-    constexpr int U = 4;
-    __shared__ float sh_f[4][kBlock / kWave];
+    constexpr int U = kStreamU;
+    __shared__ float sh_f[6][kBlock / kWave];
     __shared__ int sh_i[kBlock / kWave];
 
     // grid = (slice, row of the sequence, sequence): no index arithmetic ahead of the first load
@@ -220,7 +266,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
     // see through): a scalar load from memory would hold up the first wait for the kernel arguments and with it
     // the first logits; this one returns with the first batch.
     int tk = -1;
-    if (a.tok && k < a.tok_rows) {
+    if (!FULL && a.tok && k < a.tok_rows) {                 // the target pass only: nothing hands tokens to the draft pass
         int zero;
         asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
         tk = a.tok[(int64_t)b * a.tok_rows + k + zero];
@@ -235,10 +281,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
 
     ThreadState<FULL> st;
     // unaligned head (first slice) and tail (last slice): one element per thread
-    if (split == 0 && tid < head) {
-        float x[1] = { load_elem<DT>(rowp, tid) };
-        st.template fold<1>(x, tid);
-    }
+    if (split == 0 && tid < head) st.fold_single(load_elem<DT>(rowp, tid), tid);
     {
         const int nbatch = (v1e - v0 + U * kBlock - 1) / (U * kBlock), nfull = (v1e - v0) / (U * kBlock);
         int i = v0 + tid;
@@ -261,8 +304,7 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
     }
     if (split == a.nsplit - 1 && tid < tail) {
         int32_t j = head + nvec * VEC + tid;
-        float x[1] = { load_elem<DT>(rowp, j) };
-        st.template fold<1>(x, j);
+        st.fold_single(load_elem<DT>(rowp, j), j);
     }
 
     // ---- workgroup reduction ----
@@ -277,15 +319,32 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
     float d = Rb - st.R;
     int di = (int)fminf(fmaxf(d, -1.0e9f), 1.0e9f);
     float s = ldexpf(st.s, -di);
-    float t = 0.0f;
-    if constexpr (FULL) t = ldexpf(st.t - d * st.s, -di);
-    if (st.v1 == -INFINITY && !(st.s != st.s)) { s = 0.0f; t = 0.0f; }   // thread saw nothing finite
-    s = wave_sum(s);
-    if constexpr (FULL) t = wave_sum(t);
+    float t = 0.0f, s_hi = 0.0f, t_hi = 0.0f;
+    if constexpr (FULL) {
+        t = ldexpf(st.t - d * st.s, -di);
+        s_hi = ldexpf(st.s_hi, -di);
+        t_hi = ldexpf(st.t_hi - d * st.s_hi, -di);
+    }
+    if (st.v1 == -INFINITY && !(st.s != st.s)) { s = 0.0f; t = 0.0f; s_hi = 0.0f; t_hi = 0.0f; }   // thread saw nothing finite
     float a1 = st.v1, a2 = st.v2;
     if constexpr (FULL) wave_top2(a1, a2);
-    int c = wave_min_i(st.v1 == M ? st.cand : 0x7fffffff);
-    if (lane == 0) { sh_f[0][wave] = s; sh_f[1][wave] = t; sh_f[2][wave] = a1; sh_f[3][wave] = a2; sh_i[wave] = c; }
+    // the wavefront's vector with the first maximum; FULL: the thread that met it keeps its set-apart batch out of
+    // the wavefront's sums and publishes it on its own (every other thread's set-apart batch is ordinary data)
+    const int cw = wave_min_i(st.v1 == M ? st.cand : 0x7fffffff);
+    float hs = 0.0f, ht = 0.0f;
+    if constexpr (FULL) {
+        const bool owner = st.v1 == M && st.cand == cw && cw != 0x7fffffff;
+        hs = wave_sum(owner ? s_hi : 0.0f);              // one term and zeros: exact
+        ht = wave_sum(owner ? t_hi : 0.0f);
+        s += owner ? 0.0f : s_hi;
+        t += owner ? 0.0f : t_hi;
+    }
+    s = wave_sum(s);
+    if constexpr (FULL) t = wave_sum(t);
+    if (lane == 0) {
+        sh_f[0][wave] = s; sh_f[1][wave] = t; sh_f[2][wave] = a1; sh_f[3][wave] = a2; sh_f[4][wave] = hs; sh_f[5][wave] = ht;
+        sh_i[wave] = cw;
+    }
     __syncthreads();
     if (tid == 0) {
         Partial p;
@@ -297,10 +356,28 @@ __global__ __launch_bounds__(kBlock) void stream_pass_kernel(RowReduceArgs a)
         for (int w = 1; w < kBlock / kWave; ++w) top2_merge(b1, b2, sh_f[2][w], sh_f[3][w]);
         p.v2 = b2;
         p.cand = min(min(sh_i[0], sh_i[1]), min(sh_i[2], sh_i[3]));
+        if constexpr (FULL) {
+            // The batch with the slice's first maximum stays out (the epilogue adds its elements back from the
+            // logits); the set-apart batches of the other wavefronts are ordinary data.  A NaN or an infinity
+            // inside the left-out batch must still poison the sums: x - x is 0 for finite x only.
+#pragma unroll
+            for (int w = 0; w < kBlock / kWave; ++w) {
+                const bool holds = sh_i[w] == p.cand;
+                p.S += holds ? (sh_f[4][w] - sh_f[4][w]) : sh_f[4][w];
+                p.T += holds ? 0.0f : sh_f[5][w];
+            }
+        }
         p.pad[0] = 0x7fc00000; p.pad[1] = p.pad[2] = 0;
         // elements of this slice: [e0, e1); every index of the row lies in exactly one slice
         const int e0 = split == 0 ? 0 : head + v0 * VEC, e1 = split == a.nsplit - 1 ? a.V : head + v1e * VEC;
-        if (tk >= e0 && tk < e1) p.pad[0] = __float_as_int(load_elem<DT>(rowp, tk));
+        if (!FULL && tk >= e0 && tk < e1) {
+            // the row's address once more, from scalar registers (the zero is opaque to the compiler): holding the
+            // one from the top of the kernel in vector registers through the loop costs the draft pass a wavefront per SIMD
+            int zero;
+            asm volatile("s_mov_b32 %0, 0" : "=s"(zero));
+            const char *rp = (const char *)a.base + ((int64_t)(b + zero) * a.stride_b + (int64_t)k * a.stride_k) * Elem<DT>::size;
+            p.pad[0] = __float_as_int(load_elem<DT>(rp, tk));
+        }
         a.out[(int64_t)row * a.nsplit + split] = p;
     }
 }

@@ -176,7 +176,9 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         const int c0 = min(K + 1, rows_per_stage) * a.nsplit;
         stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1), a.nsplit, c0), c0);
     } else if (msh >= 0) {
-        lane_merge_commit(sh_rows, lane_merge_issue(a.part + (int64_t)b * (K + 1) * a.nsplit, K + 1, a.nsplit, msh), K + 1, a.nsplit, msh);
+        // target partials run over every element of their slice: plain pieces, nothing left out
+        const LaneRegs ln = lane_merge_issue(a.part + (int64_t)b * (K + 1) * a.nsplit, K + 1, a.nsplit, msh);
+        lane_merge_commit<false>(sh_rows, lane_piece(ln, 0, K + 1, a.nsplit, msh), lane_piece(ln, 1, K + 1, a.nsplit, msh), K + 1, msh);
     } else {
         stage_partials(sh_part, a.part + (int64_t)b * (K + 1) * a.nsplit, min(K + 1, rows_per_stage) * a.nsplit);
     }
@@ -211,7 +213,9 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         for (int k = kmine; k < k1; k += blockDim.x) {
             const int64_t it = (int64_t)b * (K + 1) + k;
             const void *row = SHARDED ? nullptr : row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, k);
-            const RowTotal r = msh >= 0 ? sh_rows[k].r : merge_partials(sh_part + (k - k0) * a.nsplit, a.nsplit);
+            // shard records leave their first maximum out of the sums (and carry its exact index), slice partials of
+            // target rows do not
+            const RowTotal r = msh >= 0 ? sh_rows[k].r : merge_partials<SHARDED>(sh_part + (k - k0) * a.nsplit, a.nsplit);
             // the argmax window is requested here and looked at after the logarithm (greedy sequences need the
             // argmax for their decisions, the others only for the outputs)
             int32_t top1 = 0;
@@ -311,7 +315,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         __syncthreads();
         if constexpr (SHARDED) stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1) + m, a.nsplit, a.nsplit), a.nsplit);
         else stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + m) * a.nsplit, a.nsplit);
-        RowTotal r = merge_partials(sh_part, a.nsplit);
+        RowTotal r = merge_partials<SHARDED>(sh_part, a.nsplit);
         Mm = r.M;
         lse_m = (r.R + log2(r.S)) * kLn2;
         if constexpr (SHARDED) top1m = (r.cand >= 0 && r.cand < a.V) ? r.cand : 0;
@@ -834,9 +838,16 @@ __global__ __launch_bounds__(kVBlock) void sample_head_kernel(VerifyArgs a)
     SampleJob job;
     job.kind = 0; job.row = k; job.ref_p = 0.0f; job.ref_q = 0.0f; job.lam = 0.0;
     if (k < kb) {
-        const RowTotal r = merge_partials(a.part + (int64_t)j * a.nsplit, a.nsplit);     // same bad-row rule as the finaliser
-        const bool bad = r.bad;
-        const float M = r.M;
+        // the row's maximum, and the finaliser's bad-row rule: a NaN anywhere poisons a slice's sum (also from inside
+        // the batch the draft pass leaves out of it), an infinite maximum has no softmax
+        float M = -INFINITY;
+        bool bad = false;
+        for (int sl = 0; sl < a.nsplit; ++sl) {
+            const Partial p = a.part[(int64_t)j * a.nsplit + sl];
+            M = fmaxf(M, p.v1);
+            bad |= !(p.S >= 0.0f) || p.S == INFINITY;
+        }
+        bad |= M == -INFINITY || M == INFINITY;
         if (bad) a.tok_direct[j] = -1;           // NaN in the row or no finite maximum: nothing to draw from
         else { job.kind = 2; job.ref_p = M; }
     }

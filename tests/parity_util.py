@@ -9,12 +9,13 @@ Tolerances (written here once, used by every parity test):
                floor = 1 for log-domain values (lse, log p(tok), log q(tok)): an
                absolute error of a log-probability IS the relative error of the
                probability.
-               floor = 0.1 for entropy and margin.  Both are differences of
-               O(1) binary32 quantities (H = ln S - T/S with terms of a few nats;
-               margin = p1 - p2), so their error is absolute, about 2^-23 times
-               those terms (~1e-6); a relative bound cannot hold as H or the
-               margin go to 0.  The floors sit well below the values any stop
-               rule compares against (H = 0.36, margin = 0.2).
+               floor = 1e-3 for entropy and margin as well: the library keeps
+               the row maximum's term out of its binary32 sums (it enters as an
+               exact double term at the end), so the entropy of a peaked row and
+               a margin between near-tied probabilities keep binary32 relative
+               precision down to values far below any threshold a stop rule
+               compares against (test_peaked_rows_keep_relative_precision
+               measures it).
   integers     top-1 ids, stop positions, accepted lengths, emitted tokens are
                bit-exact, except where the ORACLE marks the deciding comparison
                as a near tie: a stop signal within TAU (relative) of its
@@ -48,7 +49,7 @@ def assert_stats_close(name, gpu, ref, mask=None, tau=TAU):
     ref = np.asarray(ref, np.float64)
     if mask is not None:
         gpu, ref = gpu[mask], ref[mask]
-    floor = 1.0 if name in LOG_KEYS else (0.1 if name in ("entropy", "margin") else 1e-3)
+    floor = 1.0 if name in LOG_KEYS else 1e-3
     both_nan = np.isnan(gpu) & np.isnan(ref)
     same_inf = np.isinf(ref) & (gpu == ref)
     with np.errstate(invalid="ignore"):

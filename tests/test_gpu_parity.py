@@ -88,6 +88,59 @@ def test_peaked_rows_separate_the_rules():
     assert len(seen) == 3
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V,opts", [(32000, ()), (128256, ()), (32000, (("wgs_target", 1),)), (5000, (("wgs_target", 65536), ("min_slice", 256))),
+                                    (70001, ())])
+def test_peaked_rows_keep_relative_precision(dtype, V, opts):
+    """One logit lifted 4 .. 34 above a N(0,1) background: entropies from ~1 down to 1e-9, p_top1 up to 1 - 1e-10.
+    Entropy, probabilities and margin must hold |gpu - ref| <= 1e-5 max(|ref|, 1e-3) over the whole sweep, whatever
+    the number of slices per row (one workgroup per row, the default, many short slices) and wherever in its slice,
+    batch or unaligned row end the maximum sits; the worst ratio to that bound is printed.  Then two near-tied top
+    logits (gap 1 .. 1e-7 and an exact tie): the margin goes to 0 with relative precision."""
+    g = torch.Generator().manual_seed(V)
+    lifts = np.linspace(4.0, 34.0, 96)
+    B, K = 12, 8
+    x_wide = torch.randn(B, K, V + 3, generator=g)
+    x = x_wide[:, :, 3:]                                                  # rows start 3 elements off a 16-byte boundary
+    pos = torch.randint(0, V, (B, K), generator=g)
+    pos[0, :4] = torch.tensor([0, 1, V - 1, V - 2])                       # unaligned head and tail elements hold the maximum
+    for i, a in enumerate(lifts):
+        x[i // K, i % K, pos[i // K, i % K]] = float(a)
+    xd = x_wide.to(dtype).to(DEV)[:, :, 3:]
+    tp = binding.Tapout(B, K, V)
+    for k_, v_ in opts:
+        tp.set_option(k_, v_)
+    o = tp.draft_stats(xd)
+    ref = orc.draft_stats(pu.host_logits(xd), nthreads=16)
+    worst = {}
+    for key in ("entropy", "margin", "p_top1", "p_top2"):
+        got, want = o[key].cpu().numpy().astype(np.float64), ref[key].astype(np.float64)
+        worst[key] = float((np.abs(got - want) / (pu.TAU * np.maximum(np.abs(want), 1e-3))).max())
+        pu.assert_stats_close(key, got, want)
+    assert (o["top1_id"].cpu().numpy() == ref["top1_id"]).all()
+    H = ref["entropy"]
+    assert H.min() < 1e-7 and H.max() > 0.5 and ((H > 1e-4) & (H < 1e-2)).sum() >= 5
+    # near ties at the top
+    gaps = [10.0 ** (-e / 2) for e in range(0, 15)] + [0.0]
+    y = torch.randn(2, len(gaps), V, generator=g)
+    for k, d in enumerate(gaps):
+        for b_, a in enumerate((6.0, 14.0)):
+            y[b_, k, 100] = a
+            y[b_, k, V - 37] = float(np.float32(a) - np.float32(d))
+    yd = y.to(dtype).to(DEV)
+    tp2 = binding.Tapout(2, len(gaps), V)
+    for k_, v_ in opts:
+        tp2.set_option(k_, v_)
+    o2 = tp2.draft_stats(yd)
+    ref2 = orc.draft_stats(pu.host_logits(yd), nthreads=16)
+    for key in ("entropy", "margin", "p_top1", "p_top2"):
+        got, want = o2[key].cpu().numpy().astype(np.float64), ref2[key].astype(np.float64)
+        worst["tie_" + key] = float((np.abs(got - want) / (pu.TAU * np.maximum(np.abs(want), 1e-3))).max())
+        pu.assert_stats_close(key, got, want)
+    assert ref2["margin"][:, -1].tolist() == [0.0, 0.0] and o2["margin"][:, -1].cpu().tolist() == [0.0, 0.0]
+    announce(f"peaked rows {dtype} V={V} {opts}: worst error / (1e-5 max(|ref|, 1e-3)) = { {k: round(v, 3) for k, v in worst.items()} }")
+
+
 # ---- shapes: tails, misalignment, strides, tiny vocabularies --------------------
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])

@@ -11,9 +11,10 @@ larger than the 256 MB Infinity Cache, so no step finds its logits cached.
 
 Prints ONE JSON line.
   value                 drafted tokens handed to verification (sum of n_draft over the timed steps) per second of
-                        wall time; the timed region carries no instrumentation at all
-  roofline*             after the timed region the same steps run again with an event pair on every launch of every
-                        kernel (at least 32 steps whatever --steps is): algorithmic bytes per launch over the
+                        wall time; a step is one tapout_round call (the whole round; four_calls gives the same steps as
+                        the four separate calls); the timed region carries no instrumentation at all
+  roofline*             after the timed region the same steps run again as four calls, kernel by kernel, with an event
+                        pair on every launch (at least 32 steps whatever --steps is): algorithmic bytes per launch over the
                         kernel's average duration against the 8 TB/s HBM peak.  roofline = the launch with the most
                         bytes (target pass), roofline_draft_reduce = the draft pass, roofline_streaming = both
                         weighted by their bytes, roofline_final_token = the final-token slice pass
@@ -151,19 +152,39 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
     if sample_draft:
         g = torch.Generator(device=dev).manual_seed(20251103)
         u_draft_ring = [torch.rand(w.B, w.K, device=dev, generator=g) for _ in ring]
-    prepared = [tp.prepare_round(r, truncate, u_ts=u, u_draft=ud) for r, u, ud in zip(ring, u_ts_ring, u_draft_ring)]
+    # the four calls of a round, one after the other (select, draft_stats, verify, update) ...
+    prepared4 = [tp.prepare_round(r, truncate, u_ts=u, u_draft=ud) for r, u, ud in zip(ring, u_ts_ring, u_draft_ring)]
     sh = torch.cuda.current_stream().cuda_stream
 
-    def run(n, first=0):
+    def run4(n, first=0):
         for i in range(n):
-            prepared[(first + i) % ring_n][0](sh)
+            prepared4[(first + i) % ring_n][0](sh)
 
-    run(warmup)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run(steps, first=warmup)                       # the timed region: no events, no profiling
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    # ... and the whole round as ONE call (tapout_round: update and next selection in one launch, the target pass
+    # beside the draft pass when n_draft is given): the headline.  Its arms live in one array that every call
+    # reads and overwrites; the uniforms of the next selection are those of the ring slot that follows.
+    one_call = not sample_draft
+    if one_call:
+        arm = torch.zeros(w.B, dtype=torch.int32, device=dev)
+        tp.bandit_select(w.B, u_ts=u_ts_ring[0], arm_out=arm)
+        prepared = [tp.prepare_round_call(ring[i], arm, truncate, u_ts_next=u_ts_ring[(i + 1) % ring_n]) for i in range(ring_n)]
+
+        def run(n, first=0):
+            for i in range(n):
+                prepared[(first + i) % ring_n][0](sh)
+    else:
+        prepared, run = prepared4, run4
+
+    def timed_region(fn):
+        fn(warmup)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn(steps, first=warmup)                    # the timed region: no events, no profiling
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    elapsed4 = timed_region(run4) if one_call else None
+    elapsed = timed_region(run)
     ms_per_step = elapsed / steps * 1e3
 
     # work actually done in the timed steps (integer outputs of the last pass over each ring slot)
@@ -184,7 +205,7 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
     for k in kinds:
         tp.profile_read(k)
     first_k = warmup + steps
-    run(kernel_steps, first=first_k)
+    run4(kernel_steps, first=first_k)              # kernel by kernel: the four calls, nothing overlapped
     torch.cuda.synchronize()
     prof = {k: tp.profile_read(k) for k in kinds}
     tp.profile_enable((), 0)
@@ -231,6 +252,7 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
         "ms_per_step": round(ms_per_step, 4),
         "config": {"workload": f"{w.name}: V={w.V} B={w.B} K={w.K} draft={str(w.draft_dtype)[6:]} target={str(w.target_dtype)[6:]}",
                    "mode": "full-K (n_draft = K)" if not truncate else "truncate (n_draft = stop position)",
+                   "step": "tapout_round (one call per round)" if one_call else "select, draft_stats, verify, update (four calls)",
                    "policy": pol_name, "arms": args.arms if headline else "three",
                    "draft_tokens": "sampled by the library" if sample_draft else "given",
                    "ring_rounds": ring_n, "ring_bytes": ring_n * round_bytes},
@@ -241,6 +263,9 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
         "roofline": r_target, "roofline_draft_reduce": r_draft, "roofline_streaming": r_stream, "roofline_final_token": r_final,
         "kernel_avg_us": {k: round(prof[k][0] / prof[k][1] * 1e3, 2) for k in kinds if prof[k][1]},
     }
+    if elapsed4 is not None:
+        res["four_calls"] = {"ms_per_step": round(elapsed4 / steps * 1e3, 4), "value": round(verified / elapsed4, 1),
+                             "note": "the same steps as select / draft_stats / verify / update, one after the other on one stream"}
     if not args.no_parity and not sample_draft:
         # one closed-loop round on a fresh context (the arm pool's first plays), stop rules and all, against the oracle
         tp2 = mk()

@@ -461,6 +461,73 @@ TAPOUT_API tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const 
                                    const int32_t *accept_len, const int32_t *n_draft,
                                    const int32_t *gamma, const uint8_t *active, void *stream);
 
+/*
+ * tapout_bandit_update followed by tapout_bandit_select for the next drafting
+ * session (Algorithm 1 line 12, then line 1 of the next round), in ONE launch
+ * where every sequence has a sequence-level bandit of its own (n_bandits ==
+ * max_batch, SEQUENCE_LEVEL): the thread that applies a sequence's reward picks
+ * its next arm from the state it has just written.  Shared and token-level
+ * bandits run the two kernels one after the other.  Results are bit-identical
+ * to the two separate calls.
+ * arm .. active as tapout_bandit_update;  u_ts, arm_out, flags as
+ * tapout_bandit_select (u_ts: the uniforms of the NEXT selection).  arm_out may
+ * be the same array as arm (each sequence's entry is read before it is written).
+ */
+TAPOUT_API tapout_status tapout_bandit_update_select(tapout_ctx *ctx, int32_t B, const int32_t *arm,
+                                   const int32_t *accept_len, const int32_t *n_draft,
+                                   const int32_t *gamma, const uint8_t *active,
+                                   const float *u_ts, int32_t *arm_out, uint32_t *flags, void *stream);
+
+/*
+ * One whole round of Algorithm 1 in one call: tapout_draft_stats, tapout_verify,
+ * tapout_bandit_update_select with the arguments below, in that order and with
+ * the same decisions (statistics to the rounding of the binary32 slice sums:
+ * the slice count may differ).  What the single call adds: when n_draft is
+ * given by the caller (not this round's stop position), the streaming pass over
+ * the target rows depends on nothing the draft side computes, and ONE launch
+ * streams the draft rows and the target rows together: a launch over a few
+ * hundred rows spends a fifth of its time filling and draining the chip, and
+ * the pair pays that once.
+ *   draft [B,K,V], target [B,K+1,V]
+ *   draft_tok [B,K];  k_len [B] or NULL;  greedy [B] or NULL
+ *   n_draft   [B] tokens submitted to verification, or NULL: this round's stop
+ *             position n_stop (Algorithm 1 as written; then nothing overlaps)
+ *   arm       [B] IN: the arms of this round (from tapout_bandit_select or the
+ *             previous tapout_round); OUT: the arms of the next round.
+ *             SEQUENCE_LEVEL contexts; TOKEN_LEVEL: [B, max_k]
+ *   u_ts_next uniforms of the next selection (Thompson Sampling), else NULL
+ *   u_accept [B,K], u_sample [B]
+ *   gamma [B], active [B] or NULL: as tapout_bandit_update
+ *   outputs of tapout_draft_stats: lse, logq_tok (required: verification reads
+ *             them), entropy, p_top1, p_top2, margin, top1_id, n_stop,
+ *             stop_fired, draft_flags (each or NULL)
+ *   outputs of tapout_verify: accept_len, out_tok, n_out (required), target_lse,
+ *             logp_tok, target_top1, verify_flags (each or NULL)
+ *   select_flags [B] or NULL: flags of the next selection
+ * Draft-token sampling (u_draft) is not offered here.
+ */
+typedef struct {
+    const tapout_logits *draft, *target;
+    int32_t B, K, V;
+    const int32_t *draft_tok, *k_len, *n_draft;
+    const uint8_t *greedy;
+    const float *u_accept, *u_sample, *u_ts_next;
+    int32_t *arm;
+    const int32_t *gamma;
+    const uint8_t *active;
+    float *lse, *entropy, *p_top1, *p_top2, *margin;
+    int32_t *top1_id;
+    float *logq_tok;
+    int32_t *n_stop;
+    uint8_t *stop_fired;
+    uint32_t *draft_flags;
+    int32_t *accept_len, *out_tok, *n_out;
+    float *target_lse, *logp_tok;
+    int32_t *target_top1;
+    uint32_t *verify_flags, *select_flags;
+} tapout_round_args;
+TAPOUT_API tapout_status tapout_round(tapout_ctx *ctx, const tapout_round_args *args, void *stream);
+
 /* Bandit state read-out (the arm values of Section 4.3 are sum_r / count) and
  * restore.  sum_r, sum_r2 (or NULL), count: HOST arrays [n_bandits, n_arms]
  * ([n_bandits, max_k, n_arms] for TOKEN_LEVEL) (f64, f64, i64); sum_r2 = summed squared rewards (UCB_TUNED), set to
@@ -520,7 +587,8 @@ enum {
     TAPOUT_PROFILE_SAMPLE_HEAD = 8,     /* draft-token sampling: one job per draft row              */
     TAPOUT_PROFILE_SAMPLE_SLICES = 9,   /* draft-token sampling: slice sums of every draft row      */
     TAPOUT_PROFILE_SAMPLE_LOCATE = 10,  /* draft-token sampling: slice, token                       */
-    TAPOUT_PROFILE_KINDS = 11
+    TAPOUT_PROFILE_STREAM_PAIR = 11,    /* tapout_round: draft and target rows in one streaming pass */
+    TAPOUT_PROFILE_KINDS = 12
 };
 TAPOUT_API tapout_status tapout_profile_enable(tapout_ctx *ctx, uint32_t kind_mask, int32_t max_records);
 TAPOUT_API tapout_status tapout_profile_read(tapout_ctx *ctx, int32_t kind, double *total_ms, int32_t *launches, void *stream);

@@ -26,14 +26,14 @@ STATUS = {0: "TAPOUT_OK", 1: "TAPOUT_EINVAL", 2: "TAPOUT_EUNSUPPORTED", 3: "TAPO
 
 EXPORTS = ("tapout_default_config", "tapout_create", "tapout_destroy", "tapout_last_error",
            "tapout_bandit_select", "tapout_draft_stats", "tapout_draft_stats_static", "tapout_verify", "tapout_bandit_update",
-           "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_rule_state_get", "tapout_rule_state_set",
+           "tapout_bandit_update_select", "tapout_round", "tapout_bandit_get_state", "tapout_bandit_set_state", "tapout_rule_state_get", "tapout_rule_state_set",
            "tapout_shard_stats", "tapout_draft_stats_sharded", "tapout_verify_accept_sharded",
            "tapout_shard_final_sums", "tapout_shard_final_token",
            "tapout_set_option",
            "tapout_profile_enable", "tapout_profile_read")
 
 PROFILE_KINDS = ("select", "draft_pass", "draft_finalize", "target_pass", "verify_head", "verify_slices", "verify_locate", "update",
-                 "sample_head", "sample_slices", "sample_locate")
+                 "sample_head", "sample_slices", "sample_locate", "stream_pair")
 
 
 class TapoutConfig(C.Structure):
@@ -48,6 +48,15 @@ class TapoutConfig(C.Structure):
 
 class TapoutLogits(C.Structure):
     _fields_ = [("ptr", C.c_void_p), ("dtype", C.c_int32), ("stride_b", C.c_int64), ("stride_k", C.c_int64)]
+
+
+class TapoutRoundArgs(C.Structure):
+    _fields_ = [("draft", C.POINTER(TapoutLogits)), ("target", C.POINTER(TapoutLogits)),
+                ("B", C.c_int32), ("K", C.c_int32), ("V", C.c_int32)] + \
+               [(n, C.c_void_p) for n in ("draft_tok", "k_len", "n_draft", "greedy", "u_accept", "u_sample", "u_ts_next", "arm", "gamma",
+                                          "active", "lse", "entropy", "p_top1", "p_top2", "margin", "top1_id", "logq_tok", "n_stop",
+                                          "stop_fired", "draft_flags", "accept_len", "out_tok", "n_out", "target_lse", "logp_tok",
+                                          "target_top1", "verify_flags", "select_flags")]
 
 
 class TapoutError(RuntimeError):
@@ -83,6 +92,8 @@ def load_library():
         lib.tapout_shard_final_token.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32, i32, i32, i32] + [vp] * 8
         lib.tapout_verify.argtypes = [vp, C.POINTER(TapoutLogits), C.POINTER(TapoutLogits), i32, i32, i32] + [vp] * 15
         lib.tapout_bandit_update.argtypes = [vp, i32] + [vp] * 6
+        lib.tapout_bandit_update_select.argtypes = [vp, i32] + [vp] * 9
+        lib.tapout_round.argtypes = [vp, C.POINTER(TapoutRoundArgs), vp]
         lib.tapout_bandit_get_state.argtypes = [vp] * 5
         lib.tapout_bandit_set_state.argtypes = [vp] * 5
         lib.tapout_rule_state_get.argtypes = [vp] * 5
@@ -267,6 +278,51 @@ class Tapout:
         launch._keep = keep
         return launch, dict(arm=arm, n_draft=n_draft, draft=do, verify=vo)
 
+    # -- tapout_round: a whole round in one call ---------------------------------
+    def round_args(self, rnd: dict, arm, truncate: bool, u_ts_next=None, draft_out=None, verify_out=None, active=None):
+        """Marshals one round on fixed tensors for tapout_round.  Returns (args, outputs); keep `args` alive while it is in use
+        (it holds the tensors).  truncate=True: n_draft = this round's stop position; False: n_draft = k_len (the target
+        pass then runs beside the draft pass)."""
+        draft, target = rnd["draft"], rnd["target"]
+        B, K, V = draft.shape
+        do = draft_out or self.alloc_draft_outputs(B, K)
+        vo = verify_out or self.alloc_verify_outputs(B, K)
+        sel_flags = torch.zeros(B, dtype=torch.int32, device=self.device)
+        dl, tl = _logits(draft, "draft"), _logits(target, "target")
+        p = lambda t: None if t is None else t.data_ptr()
+        a = TapoutRoundArgs()
+        a.draft, a.target = C.pointer(dl), C.pointer(tl)
+        a.B, a.K, a.V = B, K, V
+        a.draft_tok, a.k_len, a.n_draft = p(rnd["draft_tok"]), p(rnd["k_len"]), None if truncate else p(rnd["k_len"])
+        a.greedy, a.u_accept, a.u_sample, a.u_ts_next = p(rnd.get("greedy")), p(rnd["u_accept"]), p(rnd["u_sample"]), p(u_ts_next)
+        a.arm, a.gamma, a.active = p(arm), p(rnd["k_len"]), p(active)
+        for k in ("lse", "entropy", "p_top1", "p_top2", "margin", "top1_id", "logq_tok", "n_stop", "stop_fired"):
+            setattr(a, k, p(do[k]))
+        a.draft_flags = p(do["flags"])
+        for k in ("accept_len", "out_tok", "n_out", "target_lse", "logp_tok", "target_top1"):
+            setattr(a, k, p(vo[k]))
+        a.verify_flags, a.select_flags = p(vo["flags"]), p(sel_flags)
+        a._keep = (dl, tl, rnd, arm, u_ts_next, do, vo, sel_flags, active)
+        n_draft = do["n_stop"] if truncate else rnd["k_len"]
+        return a, dict(arm=arm, n_draft=n_draft, draft=do, verify=vo, select_flags=sel_flags)
+
+    def round(self, args: TapoutRoundArgs, stream=None):
+        self._check(self._lib.tapout_round(self._ctx, C.byref(args), _stream(stream)))
+
+    def prepare_round_call(self, rnd: dict, arm, truncate: bool, u_ts_next=None):
+        """As prepare_round, for the single call: launch(stream_handle) enqueues one tapout_round; `arm` [B] holds this
+        round's arms on entry and the next round's afterwards (tapout_bandit_select fills it before the first round)."""
+        a, outs = self.round_args(rnd, arm, truncate, u_ts_next=u_ts_next)
+        lib, ctx, ref = self._lib, self._ctx, C.byref(a)
+
+        def launch(stream_handle):
+            st = lib.tapout_round(ctx, ref, stream_handle)
+            if st:
+                self._check(st)
+
+        launch._keep = a
+        return launch, outs
+
     # -- tapout_bandit_select ------------------------------------------------
     def bandit_select(self, B: int, u_ts=None, arm_out=None, flags=None, stream=None):
         A, P = self.cfg.n_arms, self.positions
@@ -438,6 +494,24 @@ class Tapout:
             _ptr(accept_len, i32, (B,), "accept_len"),
             _ptr(n_draft, i32, (B,), "n_draft"), _ptr(gamma, i32, (B,), "gamma"),
             _ptr(active, torch.uint8, (B,), "active"), _stream(stream)))
+
+    # -- tapout_bandit_update_select -----------------------------------------
+    def bandit_update_select(self, arm, accept_len, n_draft, gamma, active=None, u_ts=None, arm_out=None, flags=None, stream=None):
+        """Applies the rewards of the round that was played with `arm` and returns the arms of the next round
+        (arm_out may be `arm` itself)."""
+        B = arm.shape[0]
+        i32 = torch.int32
+        A, P = self.cfg.n_arms, self.positions
+        ashape = (B,) if P == 1 else (B, P)
+        ushape = (B, A, TS_UNIFORMS_PER_ARM) if P == 1 else (B, P, A, TS_UNIFORMS_PER_ARM)
+        if arm_out is None:
+            arm_out = torch.empty(ashape, dtype=i32, device=self.device)
+        self._check(self._lib.tapout_bandit_update_select(
+            self._ctx, B, _ptr(arm, i32, ashape, "arm"), _ptr(accept_len, i32, (B,), "accept_len"),
+            _ptr(n_draft, i32, (B,), "n_draft"), _ptr(gamma, i32, (B,), "gamma"), _ptr(active, torch.uint8, (B,), "active"),
+            _ptr(u_ts, torch.float32, ushape, "u_ts"), _ptr(arm_out, i32, ashape, "arm_out"), _ptr(flags, i32, (B,), "flags"),
+            _stream(stream)))
+        return arm_out
 
     # -- state read-out / restore (host arrays) ------------------------------
     def _state_shape(self):

@@ -14,7 +14,8 @@ using namespace tapout;
 
 struct tapout_ctx {
     tapout_config cfg;
-    Partial *part = nullptr;      size_t part_cap = 0;       // slice partials of the pass in flight
+    Partial *part = nullptr;      size_t part_cap = 0;       // slice partials of the draft pass (and of a shard pass)
+    Partial *part_t = nullptr;                                 // slice partials of the target pass (same capacity)
     double *part1 = nullptr, *part2 = nullptr;                // residual sampler slice sums
     JobRecord *jobs = nullptr;                                 // per final-token job: what to draw from, and its band list
     uint32_t *flags_ws = nullptr;
@@ -272,6 +273,7 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     double table[256];
     for (int k = 0; k < 256; ++k) table[k] = std::exp2((double)k / 256.0);
     bool ok = hipMalloc(&c->part, c->part_cap * sizeof(Partial)) == hipSuccess
+           && hipMalloc(&c->part_t, c->part_cap * sizeof(Partial)) == hipSuccess
            && hipMalloc(&c->part1, njobs * c->nsl_max * 5 * sizeof(double)) == hipSuccess
            && hipMalloc(&c->part2, njobs * c->nsl_max * sizeof(double)) == hipSuccess
            && hipMalloc(&c->exp_table, sizeof table) == hipSuccess
@@ -313,7 +315,7 @@ tapout_status tapout_destroy(tapout_ctx *ctx)
     if (!ctx) return TAPOUT_OK;
     DeviceGuard guard(ctx->cfg.device);
     profile_release(ctx);
-    (void)hipFree(ctx->part); (void)hipFree(ctx->part1); (void)hipFree(ctx->part2);
+    (void)hipFree(ctx->part); (void)hipFree(ctx->part_t); (void)hipFree(ctx->part1); (void)hipFree(ctx->part2);
     (void)hipFree(ctx->jobs); (void)hipFree(ctx->flags_ws);
     (void)hipFree(ctx->exp_table);
     (void)hipFree(ctx->sum_r); (void)hipFree(ctx->sum_r2); (void)hipFree(ctx->count);
@@ -376,13 +378,39 @@ tapout_status tapout_bandit_update(tapout_ctx *ctx, int32_t B, const int32_t *ar
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_update launch");
 }
 
-tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
+tapout_status tapout_bandit_update_select(tapout_ctx *ctx, int32_t B, const int32_t *arm,
+                                          const int32_t *accept_len, const int32_t *n_draft,
+                                          const int32_t *gamma, const uint8_t *active,
+                                          const float *u_ts, int32_t *arm_out, uint32_t *flags, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (B < 0 || B > ctx->cfg.max_batch) return fail(ctx, TAPOUT_EINVAL, "B = %d outside [0, max_batch = %d]", B, ctx->cfg.max_batch);
+    if (B == 0) return TAPOUT_OK;
+    if (!arm || !accept_len || !n_draft || !gamma) return fail(ctx, TAPOUT_EINVAL, "arm, accept_len, n_draft and gamma are required");
+    if (!arm_out) return fail(ctx, TAPOUT_EINVAL, "arm_out is NULL");
+    if ((ctx->cfg.policy == TAPOUT_TS_BETA || ctx->cfg.policy == TAPOUT_TS_GAUSS) && !u_ts) return fail(ctx, TAPOUT_EINVAL, "Thompson Sampling needs u_ts");
+    DeviceGuard guard(ctx->cfg.device);
+    BanditArgs a = bandit_args(ctx, B);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e = timed(ctx, TAPOUT_PROFILE_UPDATE, [&](Timing tm) { return launch_bandit_update_select(a, arm, accept_len, n_draft, gamma, active, u_ts, arm_out, flags, st, tm); });
+    return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "bandit_update_select launch");
+}
+
+namespace {
+struct VerifyCall;
+hipError_t stream_pair(tapout_ctx *ctx, const RowReduceArgs &d, int d_dtype, const VerifyCall &c, hipStream_t st);
+RowReduceArgs target_pass_args(tapout_ctx *ctx, const VerifyCall &c);
+
+// tapout_draft_stats.  pair != NULL (tapout_round): the streaming pass is one launch over the draft rows and the target
+// rows of *pair, with pair_nsplit slices per row for both.
+tapout_status draft_stats_impl(tapout_ctx *ctx, const tapout_logits *draft,
                                  int32_t B, int32_t K, int32_t V,
                                  const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
                                  const float *u_draft,
                                  float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
                                  int32_t *top1_id, float *logq_tok, int32_t *sampled_tok,
-                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream)
+                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream,
+                                 const VerifyCall *pair, int pair_nsplit)
 {
     if (!ctx) return TAPOUT_EINVAL;
     tapout_status s = check_shape(ctx, B, K, V);
@@ -397,11 +425,12 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     DeviceGuard guard(ctx->cfg.device);
     hipStream_t st = (hipStream_t)stream;
     const int64_t rows = (int64_t)B * K;
-    const int nsplit = choose_nsplit(ctx, rows, V, draft->dtype);
+    const int nsplit = pair ? pair_nsplit : choose_nsplit(ctx, rows, V, draft->dtype);
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, slice_vectors(V, draft->dtype, nsplit), (int32_t)rows, k_len, 0, ctx->part};
-    hipError_t e = timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, [&](Timing tm) { return launch_row_reduce(r, draft->dtype, true, st, tm); });
+    hipError_t e = pair ? stream_pair(ctx, r, draft->dtype, *pair, st)
+                        : timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, [&](Timing tm) { return launch_row_reduce(r, draft->dtype, true, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "draft pass launch");
     if (u_draft) {
         // draw the tokens first (one final-token job per draft row), so that the finaliser can form log q(tok)
@@ -435,6 +464,19 @@ tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
     }
     e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, [&](Timing tm) { return launch_draft_finalize(f, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft finalize launch");
+}
+}  // namespace
+
+tapout_status tapout_draft_stats(tapout_ctx *ctx, const tapout_logits *draft,
+                                 int32_t B, int32_t K, int32_t V,
+                                 const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
+                                 const float *u_draft,
+                                 float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
+                                 int32_t *top1_id, float *logq_tok, int32_t *sampled_tok,
+                                 int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream)
+{
+    return draft_stats_impl(ctx, draft, B, K, V, draft_tok, k_len, arm, u_draft, lse, entropy, p_top1, p_top2, margin,
+                            top1_id, logq_tok, sampled_tok, n_stop, stop_fired, flags, stream, nullptr, 0);
 }
 
 tapout_status tapout_draft_stats_static(const tapout_logits *draft, int32_t B, int32_t K, int32_t V,
@@ -648,6 +690,95 @@ tapout_status tapout_shard_final_token(tapout_ctx *ctx, const tapout_logits *tar
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "shard final token launch");
 }
 
+namespace {
+
+struct VerifyCall {
+    const tapout_logits *target, *draft;
+    int32_t B, K, V;
+    const float *draft_lse, *logq_tok; const int32_t *draft_tok, *n_draft; const uint8_t *greedy;
+    const float *u_accept, *u_sample;
+    int32_t *accept_len, *out_tok, *n_out; float *target_lse, *logp_tok; int32_t *target_top1; uint32_t *flags;
+    // derived by verify_check
+    int nsplit, nsl; bool fused;
+};
+
+tapout_status verify_check(tapout_ctx *ctx, VerifyCall &c)
+{
+    tapout_status s = check_shape(ctx, c.B, c.K, c.V);
+    if (s != TAPOUT_OK || c.B == 0) return s;
+    char buf[128];
+    if (const char *m = check_logits(c.target, "target", c.V, c.K + 1, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
+    if (const char *m = check_logits(c.draft, "draft", c.V, c.K, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
+    if (!c.draft_lse || !c.logq_tok || !c.draft_tok || !c.n_draft || !c.u_accept || !c.u_sample)
+        return fail(ctx, TAPOUT_EINVAL, "draft_lse, logq_tok, draft_tok, n_draft, u_accept and u_sample are required");
+    if (!c.accept_len || !c.out_tok || !c.n_out) return fail(ctx, TAPOUT_EINVAL, "accept_len, out_tok and n_out are required");
+    const int64_t rows = (int64_t)c.B * (c.K + 1);
+    c.nsplit = choose_nsplit(ctx, rows, c.V, c.target->dtype);
+    if ((size_t)(rows * c.nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
+    // With few sequences the final-token slice kernel is a handful of workgroups per compute unit and its launch
+    // is latency: then the accept decisions are taken inside it (by every workgroup of a sequence again) and the
+    // head launch with its hand-over through memory goes away.  With many sequences that kernel is bound by
+    // arithmetic and the repeated head would add to it: separate launch.
+    c.nsl = (c.V + kSampleSlice - 1) / kSampleSlice;
+    const int64_t slice_wgs = (int64_t)c.B * ((c.nsl + 3) / 4);
+    c.fused = ctx->fuse_head < 0 ? slice_wgs <= kFuseHeadMaxWgs : ctx->fuse_head == 1;
+    return TAPOUT_OK;
+}
+
+// The streaming pass over the target rows (it needs n_draft and the drafted tokens, nothing the draft pass computes).
+RowReduceArgs target_pass_args(tapout_ctx *ctx, const VerifyCall &c)
+{
+    const int64_t rows = (int64_t)c.B * (c.K + 1);
+    return RowReduceArgs{c.target->ptr, c.target->stride_b, c.target->stride_k, c.V, c.K + 1, c.nsplit, slice_vectors(c.V, c.target->dtype, c.nsplit),
+                         (int32_t)rows, c.n_draft, 1, ctx->part_t,
+                         c.fused ? ctx->jobs : nullptr, c.draft_tok, c.K};     // the pass also picks up the logits of the drafted tokens
+}
+
+hipError_t verify_target_pass(tapout_ctx *ctx, const VerifyCall &c, hipStream_t st)
+{
+    const RowReduceArgs r = target_pass_args(ctx, c);
+    return timed(ctx, TAPOUT_PROFILE_TARGET_PASS, [&](Timing tm) { return launch_row_reduce(r, c.target->dtype, false, st, tm); });
+}
+
+// Draft rows and target rows in one launch (tapout_round).
+hipError_t stream_pair(tapout_ctx *ctx, const RowReduceArgs &d, int d_dtype, const VerifyCall &c, hipStream_t st)
+{
+    const RowReduceArgs t = target_pass_args(ctx, c);
+    return timed(ctx, TAPOUT_PROFILE_STREAM_PAIR, [&](Timing tm) { return launch_row_reduce_pair(d, d_dtype, t, c.target->dtype, st, tm); });
+}
+
+// Accept decisions, first rejection, final token.
+// tail (tapout_round): what the locate kernel needs to end each sequence's round, or NULL.
+struct RoundTail { const int32_t *arm_in, *gamma; const uint8_t *active; const float *u_ts; int32_t *arm_out; uint32_t *flags; };
+
+hipError_t verify_rest(tapout_ctx *ctx, const VerifyCall &c, hipStream_t st, const RoundTail *tail = nullptr)
+{
+    VerifyArgs va{};
+    if (tail) {
+        va.bandit_tail = 1;
+        va.bandit = bandit_args(ctx, c.B);
+        va.b_arm_in = tail->arm_in; va.b_gamma = tail->gamma; va.b_active = tail->active; va.b_u_ts = tail->u_ts;
+        va.b_arm_out = tail->arm_out; va.b_flags = tail->flags;
+    }
+    va.tbase = c.target->ptr; va.t_dtype = c.target->dtype; va.t_stride_b = c.target->stride_b; va.t_stride_k = c.target->stride_k;
+    va.dbase = c.draft->ptr; va.d_dtype = c.draft->dtype; va.d_stride_b = c.draft->stride_b; va.d_stride_k = c.draft->stride_k;
+    va.B = c.B; va.K = c.K; va.V = c.V; va.nsplit = c.nsplit; va.nsl = c.nsl;
+    va.jps = 1; va.n_jobs = c.B; va.fused_head = c.fused ? 1 : 0;
+    va.part = ctx->part_t;
+    va.draft_lse = c.draft_lse; va.logq_tok = c.logq_tok; va.draft_tok = c.draft_tok; va.n_draft = c.n_draft; va.greedy = c.greedy;
+    va.u_accept = c.u_accept; va.u_sample = c.u_sample;
+    va.accept_len = c.accept_len; va.out_tok = c.out_tok; va.n_out = c.n_out;
+    va.target_lse = c.target_lse; va.logp_tok = c.logp_tok; va.target_top1 = c.target_top1; va.flags = c.flags;
+    va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
+    va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
+    hipError_t e = hipSuccess;
+    for (int pass = c.fused ? 1 : 0; pass <= 2 && e == hipSuccess; ++pass)
+        e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, [&](Timing tm) { return launch_verify(va, pass, st, tm); });
+    return e;
+}
+
+}  // namespace
+
 tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const tapout_logits *draft,
                             int32_t B, int32_t K, int32_t V,
                             const float *draft_lse, const float *logq_tok,
@@ -658,48 +789,63 @@ tapout_status tapout_verify(tapout_ctx *ctx, const tapout_logits *target, const 
                             uint32_t *flags, void *stream)
 {
     if (!ctx) return TAPOUT_EINVAL;
-    tapout_status s = check_shape(ctx, B, K, V);
-    if (s != TAPOUT_OK) return s;
-    if (B == 0) return TAPOUT_OK;
-    char buf[128];
-    if (const char *m = check_logits(target, "target", V, K + 1, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
-    if (const char *m = check_logits(draft, "draft", V, K, buf)) return fail(ctx, TAPOUT_EINVAL, "%s", m);
-    if (!draft_lse || !logq_tok || !draft_tok || !n_draft || !u_accept || !u_sample)
-        return fail(ctx, TAPOUT_EINVAL, "draft_lse, logq_tok, draft_tok, n_draft, u_accept and u_sample are required");
-    if (!accept_len || !out_tok || !n_out) return fail(ctx, TAPOUT_EINVAL, "accept_len, out_tok and n_out are required");
+    VerifyCall c{target, draft, B, K, V, draft_lse, logq_tok, draft_tok, n_draft, greedy, u_accept, u_sample,
+                 accept_len, out_tok, n_out, target_lse, logp_tok, target_top1, flags, 0, 0, false};
+    tapout_status s = verify_check(ctx, c);
+    if (s != TAPOUT_OK || B == 0) return s;
     DeviceGuard guard(ctx->cfg.device);
     hipStream_t st = (hipStream_t)stream;
-    const int64_t rows = (int64_t)B * (K + 1);
-    const int nsplit = choose_nsplit(ctx, rows, V, target->dtype);
-    if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
-
-    // With few sequences the final-token slice kernel is a handful of workgroups per compute unit and its launch
-    // is latency: then the accept decisions are taken inside it (by every workgroup of a sequence again) and the
-    // head launch with its hand-over through memory goes away.  With many sequences that kernel is bound by
-    // arithmetic and the repeated head would add to it: separate launch.
-    const int nsl = (V + kSampleSlice - 1) / kSampleSlice;
-    const int64_t slice_wgs = (int64_t)B * ((nsl + 3) / 4);
-    const bool fused = ctx->fuse_head < 0 ? slice_wgs <= kFuseHeadMaxWgs : ctx->fuse_head == 1;
-    RowReduceArgs r{target->ptr, target->stride_b, target->stride_k, V, K + 1, nsplit, slice_vectors(V, target->dtype, nsplit), (int32_t)rows, n_draft, 1, ctx->part,
-                    fused ? ctx->jobs : nullptr, draft_tok, K};     // the pass also picks up the logits of the drafted tokens
-    hipError_t e = timed(ctx, TAPOUT_PROFILE_TARGET_PASS, [&](Timing tm) { return launch_row_reduce(r, target->dtype, false, st, tm); });
+    hipError_t e = verify_target_pass(ctx, c, st);
     if (e != hipSuccess) return hip_fail(ctx, e, "target pass launch");
-
-    VerifyArgs va{};
-    va.tbase = target->ptr; va.t_dtype = target->dtype; va.t_stride_b = target->stride_b; va.t_stride_k = target->stride_k;
-    va.dbase = draft->ptr; va.d_dtype = draft->dtype; va.d_stride_b = draft->stride_b; va.d_stride_k = draft->stride_k;
-    va.B = B; va.K = K; va.V = V; va.nsplit = nsplit; va.nsl = nsl;
-    va.jps = 1; va.n_jobs = B; va.fused_head = fused ? 1 : 0;
-    va.part = ctx->part;
-    va.draft_lse = draft_lse; va.logq_tok = logq_tok; va.draft_tok = draft_tok; va.n_draft = n_draft; va.greedy = greedy;
-    va.u_accept = u_accept; va.u_sample = u_sample;
-    va.accept_len = accept_len; va.out_tok = out_tok; va.n_out = n_out;
-    va.target_lse = target_lse; va.logp_tok = logp_tok; va.target_top1 = target_top1; va.flags = flags;
-    va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
-    va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
-    for (int pass = fused ? 1 : 0; pass <= 2 && e == hipSuccess; ++pass)
-        e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, [&](Timing tm) { return launch_verify(va, pass, st, tm); });
+    e = verify_rest(ctx, c, st);
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "verify launch");
+}
+
+tapout_status tapout_round(tapout_ctx *ctx, const tapout_round_args *a, void *stream)
+{
+    if (!ctx) return TAPOUT_EINVAL;
+    if (!a) return fail(ctx, TAPOUT_EINVAL, "args is NULL");
+    if (!a->arm) return fail(ctx, TAPOUT_EINVAL, "arm is required");
+    if (!a->lse || !a->logq_tok || !a->draft_tok) return fail(ctx, TAPOUT_EINVAL, "draft_tok, lse and logq_tok are required (verification reads them)");
+    if (!a->n_draft && !a->n_stop) return fail(ctx, TAPOUT_EINVAL, "n_draft is NULL (verify up to the stop position) but n_stop is NULL too");
+    if (!a->gamma) return fail(ctx, TAPOUT_EINVAL, "gamma is required");
+    if ((ctx->cfg.policy == TAPOUT_TS_BETA || ctx->cfg.policy == TAPOUT_TS_GAUSS) && !a->u_ts_next) return fail(ctx, TAPOUT_EINVAL, "Thompson Sampling needs u_ts_next");
+    const int32_t *n_draft = a->n_draft ? a->n_draft : a->n_stop;
+    VerifyCall c{a->target, a->draft, a->B, a->K, a->V, a->lse, a->logq_tok, a->draft_tok, n_draft, a->greedy, a->u_accept, a->u_sample,
+                 a->accept_len, a->out_tok, a->n_out, a->target_lse, a->logp_tok, a->target_top1, a->verify_flags, 0, 0, false};
+    tapout_status s = verify_check(ctx, c);
+    if (s != TAPOUT_OK || a->B == 0) return s;
+    DeviceGuard guard(ctx->cfg.device);
+    hipStream_t st = (hipStream_t)stream;
+    // The target pass reads nothing the draft side writes unless n_draft is this round's stop position: then one launch
+    // streams the draft rows and the target rows together, both cut into the same number of slices.
+    // (Tensors of one element size only: with mixed sizes the two halves want different slice counts and register
+    // budgets, and the pair measured slower than two launches.)
+    const bool pair = a->n_draft != nullptr && a->n_draft != a->n_stop && 2 * a->B <= 65535 && a->draft->dtype == a->target->dtype;
+    if (pair) {
+        // slices for the rows of both tensors together: half as many, twice as long, as either pass would take alone
+        c.nsplit = choose_nsplit(ctx, (int64_t)a->B * (2 * a->K + 1), a->V, a->target->dtype);
+        if ((size_t)((int64_t)a->B * (a->K + 1) * c.nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
+    }
+    s = draft_stats_impl(ctx, a->draft, a->B, a->K, a->V, a->draft_tok, a->k_len, a->arm, nullptr,
+                         a->lse, a->entropy, a->p_top1, a->p_top2, a->margin, a->top1_id, a->logq_tok, nullptr,
+                         a->n_stop, a->stop_fired, a->draft_flags, stream, pair ? &c : nullptr, c.nsplit);
+    if (s != TAPOUT_OK) return s;
+    hipError_t e = hipSuccess;
+    if (!pair) {
+        e = verify_target_pass(ctx, c, st);
+        if (e != hipSuccess) return hip_fail(ctx, e, "target pass launch");
+    }
+    // Sequence-level UCB bandits, one per sequence: the final-token locate kernel, one workgroup per sequence, also
+    // applies the reward and picks the next arm.  Thompson Sampling (heavy draws), shared and token-level bandits take
+    // a launch of their own.
+    const bool tail = ctx->positions == 1 && ctx->cfg.n_bandits != 1 &&
+                      (ctx->cfg.policy == TAPOUT_UCB1 || ctx->cfg.policy == TAPOUT_UCB_TUNED);
+    const RoundTail rt{a->arm, a->gamma, a->active, a->u_ts_next, a->arm, a->select_flags};
+    e = verify_rest(ctx, c, st, tail ? &rt : nullptr);
+    if (e != hipSuccess) return hip_fail(ctx, e, "verify launch");
+    if (tail) return TAPOUT_OK;
+    return tapout_bandit_update_select(ctx, a->B, a->arm, a->accept_len, n_draft, a->gamma, a->active, a->u_ts_next, a->arm, a->select_flags, stream);
 }
 
 tapout_status tapout_profile_enable(tapout_ctx *ctx, uint32_t kind_mask, int32_t max_records)

@@ -10,113 +10,11 @@
 // This file is compiled without floating-point contraction: every product,
 // quotient and sum below is a separately rounded IEEE double operation.
 #include "common.h"
+#include "bandit_device.h"
 
 namespace tapout {
 
 namespace {
-
-constexpr int kAttempts = 8;
-
-__device__ inline double unit_open(float u)
-{
-    double x = (double)u;
-    return x > 0.0 ? x : 0x1p-25;
-}
-
-// Gamma(shape >= 1) by Marsaglia-Tsang squeeze-free rejection from caller uniforms.
-__device__ inline double gamma_draw(double shape, const float *u, bool *exhausted)
-{
-    const double d = shape - 1.0 / 3.0;
-    const double c = 1.0 / sqrt(9.0 * d);
-    for (int i = 0; i < kAttempts; ++i) {
-        double u1 = unit_open(u[3 * i]), u2 = (double)u[3 * i + 1], u3 = unit_open(u[3 * i + 2]);
-        double z = sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2);
-        double t = 1.0 + c * z;
-        double v = t * t * t;
-        if (v > 0.0 && log(u3) < 0.5 * z * z + d - d * v + d * log(v))
-            return d * v;
-    }
-    *exhausted = true;
-    return shape;
-}
-
-__device__ inline int ucb1_arm(const double *S, const int64_t *N, int A)
-{
-    int64_t t = 1;
-    for (int a = 0; a < A; ++a) t += N[a];
-    int best = 0;
-    double best_v = -INFINITY;
-    for (int a = 0; a < A; ++a) {
-        if (N[a] == 0) return a;                       // every arm is played once first, in index order
-        double n = (double)N[a];
-        double v = S[a] / n + sqrt((2.0 * log((double)t)) / n);
-        if (a == 0 || v > best_v) { best = a; best_v = v; }
-    }
-    return best;
-}
-
-// UCB-Tuned: bonus sqrt((ln t / N) min(1/4, V)), V = var + sqrt(2 ln t / N), var = Q/N - mean^2.
-__device__ inline int ucb_tuned_arm(const double *S, const double *Q, const int64_t *N, int A)
-{
-    int64_t t = 1;
-    for (int a = 0; a < A; ++a) t += N[a];
-    const double lt = log((double)t);
-    int best = 0;
-    double best_v = -INFINITY;
-    for (int a = 0; a < A; ++a) {
-        if (N[a] == 0) return a;
-        const double n = (double)N[a];
-        const double mean = S[a] / n;
-        const double var = Q[a] / n - mean * mean;
-        const double V = var + sqrt((2.0 * lt) / n);
-        const double cap = V < 0.25 ? V : 0.25;
-        const double v = mean + sqrt((lt / n) * cap);
-        if (a == 0 || v > best_v) { best = a; best_v = v; }
-    }
-    return best;
-}
-
-// Gaussian posterior N(S/(N+1), 1/(N+1)); one Box-Muller normal from the arm's first two uniforms.
-__device__ inline int ts_gauss_arm(const double *S, const int64_t *N, int A, const float *u)
-{
-    int best = 0;
-    double best_v = -INFINITY;
-    for (int a = 0; a < A; ++a) {
-        const float *ua = u + (size_t)a * TAPOUT_TS_UNIFORMS_PER_ARM;
-        const double n1 = (double)N[a] + 1.0;
-        const double z = sqrt(-2.0 * log(unit_open(ua[0]))) * cos(6.283185307179586476925 * (double)ua[1]);
-        const double th = S[a] / n1 + z / sqrt(n1);
-        if (a == 0 || th > best_v) { best = a; best_v = th; }
-    }
-    return best;
-}
-
-__device__ inline int ts_arm(const double *S, const int64_t *N, int A, const float *u, bool *exhausted)
-{
-    int best = 0;
-    double best_v = -INFINITY;
-    for (int a = 0; a < A; ++a) {
-        double alpha = 1.0 + S[a];
-        double beta = 1.0 + ((double)N[a] - S[a]);
-        const float *ua = u + (size_t)a * TAPOUT_TS_UNIFORMS_PER_ARM;
-        double g1 = gamma_draw(alpha, ua, exhausted);
-        double g2 = gamma_draw(beta, ua + kAttempts * 3, exhausted);
-        double th = g1 / (g1 + g2);
-        if (a == 0 || th > best_v) { best = a; best_v = th; }
-    }
-    return best;
-}
-
-__device__ inline int select_arm(const BanditArgs &a, size_t nb, const float *u_ts, bool *ex)
-{
-    const double *S = a.sum_r + nb;
-    const int64_t *N = a.count + nb;
-    const float *u = u_ts ? u_ts + nb * TAPOUT_TS_UNIFORMS_PER_ARM : nullptr;
-    if (a.policy == TAPOUT_UCB1) return ucb1_arm(S, N, a.n_arms);
-    if (a.policy == TAPOUT_UCB_TUNED) return ucb_tuned_arm(S, a.sum_r2 + nb, N, a.n_arms);
-    if (a.policy == TAPOUT_TS_GAUSS) return ts_gauss_arm(S, N, a.n_arms, u);
-    return ts_arm(S, N, a.n_arms, u, ex);
-}
 
 // Sequence-level bandit: one thread per sequence.
 __global__ void bandit_select_kernel(BanditArgs a, const float *u_ts, int32_t *arm_out, uint32_t *flags)
@@ -189,63 +87,6 @@ __global__ void bandit_select_token_kernel(BanditArgs a, const float *u_ts, int3
     if (threadIdx.x == 0 && flags) flags[b] = sh_flag;
 }
 
-__device__ inline void apply_reward(const BanditArgs &a, int nb, int arm, int m, int n, int g)
-{
-    const double r = a.reward == TAPOUT_REWARD_SIMPLE
-                         ? (double)m / (double)g
-                         : (a.alpha * (double)m) / (double)g + ((1.0 - a.alpha) * (double)m) / (double)n;
-    a.count[(size_t)nb * a.n_arms + arm] += 1;
-    a.sum_r[(size_t)nb * a.n_arms + arm] += r;
-    a.sum_r2[(size_t)nb * a.n_arms + arm] += r * r;
-}
-
-// Token-level bandits (Section 3.1 / 3.2): position k < m is an accepted play (reward 1) of the arm chosen
-// there, position m < n the rejected one (reward 0); later positions were never evaluated.
-__device__ inline void apply_token_rewards(const BanditArgs &a, int nb, const int32_t *arm_b, int m, int n)
-{
-    if (n > a.positions) n = a.positions;
-    for (int k = 0; k < n && k <= m; ++k) {
-        const int arm = arm_b[k];
-        if (arm < 0 || arm >= a.n_arms) continue;
-        const size_t i = ((size_t)nb * a.positions + k) * a.n_arms + arm;
-        const double r = k < m ? 1.0 : 0.0;
-        a.count[i] += 1;
-        a.sum_r[i] += r;
-        a.sum_r2[i] += r;
-    }
-}
-
-// Carried state of the stateful stop rules after one draft of sequence b (Appendix A.1).
-__device__ inline void advance_rule_state(const BanditArgs &a, int b, int m, int n)
-{
-    if (a.round_K > 0) a.prev_entropy[b] = a.round_entropy[(int64_t)b * a.round_K + (n - 1)];
-    const double r = (double)m / (double)n;
-    const double rate = a.ad_beta1 * a.accept_rate[b] + (1.0 - a.ad_beta1) * r;
-    a.accept_rate[b] = rate;
-    const double s = a.ad_steer ? r : rate;       // what steers the threshold: the smoothed rate, or r as printed
-    const double sg = a.ad_alpha > s ? 1.0 : (a.ad_alpha < s ? -1.0 : 0.0);
-    for (int j = 0; j < a.n_arms; ++j) {
-        if (a.rule[j] != TAPOUT_RULE_ADAEDL) continue;
-        const double lam = a.lambda[(int64_t)b * a.n_arms + j];
-        a.lambda[(int64_t)b * a.n_arms + j] = a.ad_beta2 * lam + (1.0 - a.ad_beta2) * (lam + a.ad_eps * sg);
-    }
-}
-
-__device__ inline bool playable(const BanditArgs &a, int b, const int32_t *arm, const int32_t *n_draft,
-                                const int32_t *gamma, const uint8_t *active)
-{
-    if (active && !active[b]) return false;
-    if (n_draft[b] < 1 || gamma[b] < 1) return false;
-    return a.positions > 1 || (arm[b] >= 0 && arm[b] < a.n_arms);           // token-level arms are checked per position
-}
-
-__device__ inline void play(const BanditArgs &a, int nb, int b, const int32_t *arm, const int32_t *accept_len,
-                            const int32_t *n_draft, const int32_t *gamma)
-{
-    if (a.positions > 1) apply_token_rewards(a, nb, arm + (size_t)b * a.positions, accept_len[b], n_draft[b]);
-    else apply_reward(a, nb, arm[b], accept_len[b], n_draft[b], gamma[b]);
-}
-
 __global__ void bandit_update_kernel(BanditArgs a, const int32_t *arm, const int32_t *accept_len,
                                      const int32_t *n_draft, const int32_t *gamma, const uint8_t *active)
 {
@@ -264,7 +105,46 @@ __global__ void bandit_update_kernel(BanditArgs a, const int32_t *arm, const int
     }
 }
 
+// ---- update and next selection in one launch ---------------------------------------------------------
+// Sequence-level bandits, one per sequence: the thread that applies sequence b's reward is the one that picks its
+// next arm, so the selection reads the state it has just written (program order within a thread) and the round
+// saves a launch.  Same operations as the two kernels: same bits.
+__global__ void bandit_update_select_kernel(BanditArgs a, const int32_t *arm, const int32_t *accept_len,
+                                            const int32_t *n_draft, const int32_t *gamma, const uint8_t *active,
+                                            const float *u_ts, int32_t *arm_out, uint32_t *flags)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= a.B) return;
+    update_select_one(a, b, arm, accept_len, n_draft, gamma, active, u_ts, arm_out, flags);
+}
+
+// The same for Thompson Sampling with Beta posteriors, lane-parallel (update_select_ts_lanes): four sequences per wavefront.
+__global__ __launch_bounds__(64) void bandit_update_select_ts_kernel(BanditArgs a, const int32_t *arm_in, const int32_t *accept_len,
+                                                                      const int32_t *n_draft, const int32_t *gamma, const uint8_t *active,
+                                                                      const float *u_ts, int32_t *arm_out, uint32_t *flags)
+{
+    update_select_ts_lanes(a, blockIdx.x * 4 + (threadIdx.x >> 4), threadIdx.x & 15, arm_in, accept_len, n_draft, gamma, active, u_ts, arm_out, flags);
+}
+
 }  // namespace
+
+// Update followed by the next selection.  One launch where every sequence has a sequence-level bandit of its own;
+// otherwise (shared bandit, token-level bandits) the two kernels one after the other.
+hipError_t launch_bandit_update_select(const BanditArgs &a, const int32_t *arm, const int32_t *accept_len,
+                                       const int32_t *n_draft, const int32_t *gamma, const uint8_t *active,
+                                       const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm)
+{
+    if (a.positions > 1 || a.n_bandits == 1) {
+        hipError_t e = launch_bandit_update(a, arm, accept_len, n_draft, gamma, active, st, tm);
+        if (e != hipSuccess) return e;
+        return launch_bandit_select(a, u_ts, arm_out, flags, st, Timing{});
+    }
+    if (a.policy == TAPOUT_TS_BETA)
+        launch_kernel(bandit_update_select_ts_kernel, dim3((a.B + 3) / 4), dim3(64), st, tm, a, arm, accept_len, n_draft, gamma, active, u_ts, arm_out, flags);
+    else
+        launch_kernel(bandit_update_select_kernel, dim3((a.B + 63) / 64), dim3(64), st, tm, a, arm, accept_len, n_draft, gamma, active, u_ts, arm_out, flags);
+    return hipGetLastError();
+}
 
 hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm)
 {

@@ -90,6 +90,8 @@ struct RowReduceArgs {
 };
 // Streaming pass: one Partial per (row, slice).  Returns hipGetLastError() after enqueueing.
 hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st, Timing tm);
+// Draft pass (all statistics) and target pass of the same sequences in one launch.
+hipError_t launch_row_reduce_pair(const RowReduceArgs &d, int d_dtype, const RowReduceArgs &t, int t_dtype, hipStream_t st, Timing tm);
 
 struct DraftFinalArgs {
     const void *base; int32_t dtype; int64_t stride_b, stride_k;
@@ -122,6 +124,19 @@ struct ShardMergeArgs {
 };
 hipError_t launch_shard_merge(const ShardMergeArgs &a, hipStream_t st, Timing tm);
 
+struct BanditArgs {
+    int32_t policy, n_bandits, n_arms, B;
+    int32_t positions;            // bandits per slot: 1 (sequence-level) or max_k (token-level, one per draft position)
+    int32_t reward;               // tapout_reward
+    double alpha;
+    double *sum_r, *sum_r2; int64_t *count;
+    // stateful stop rules (all NULL when the configuration has no such arm)
+    int32_t rule[TAPOUT_MAX_ARMS];
+    float *prev_entropy; double *accept_rate; double *lambda;
+    const float *round_entropy; int32_t round_K;      // entropies of the last draft_stats call, [B, round_K]; round_K = 0: none
+    double ad_alpha, ad_beta1, ad_beta2, ad_eps;
+    int32_t ad_steer;             // tapout_config.adaedl_steer
+};
 // Verification + final token: the head kernel merges the target partials of each sequence, takes the
 // accept decisions and describes the final-token draw (SampleJob); the slice kernel sums the row pair
 // per slice; the locate kernel finds the token.
@@ -148,6 +163,12 @@ struct VerifyArgs {
     double *part1;                // [jobs, nsl, 5]  A, B, R~, D, U of each slice
     double *part2;                // [B, nsl]     exact weight of each slice (slow path)
     const double *exp_table;      // 2^(k/256), k = 0..255
+    // tapout_round (jps = 1): the locate kernel also ends the round of its sequence: reward into the sequence's bandit
+    // (arm b_arm_in[b], accept_len, n_draft, b_gamma, b_active as tapout_bandit_update) and the arm of the next round
+    // (b_arm_out, b_flags as tapout_bandit_select).  Sequence-level UCB bandits, one per sequence.
+    int32_t bandit_tail;
+    BanditArgs bandit;
+    const int32_t *b_arm_in, *b_gamma; const uint8_t *b_active; const float *b_u_ts; int32_t *b_arm_out; uint32_t *b_flags;
 };
 hipError_t launch_verify(const VerifyArgs &a, int pass /*0 head, 1 slices, 2 locate*/, hipStream_t st, Timing tm);
 
@@ -173,22 +194,12 @@ hipError_t launch_shard_final_token(const ShardFinalArgs &a, hipStream_t st);
 
 constexpr int kSampleSlice = 2048;   // elements per slice of the final-token passes
 
-struct BanditArgs {
-    int32_t policy, n_bandits, n_arms, B;
-    int32_t positions;            // bandits per slot: 1 (sequence-level) or max_k (token-level, one per draft position)
-    int32_t reward;               // tapout_reward
-    double alpha;
-    double *sum_r, *sum_r2; int64_t *count;
-    // stateful stop rules (all NULL when the configuration has no such arm)
-    int32_t rule[TAPOUT_MAX_ARMS];
-    float *prev_entropy; double *accept_rate; double *lambda;
-    const float *round_entropy; int32_t round_K;      // entropies of the last draft_stats call, [B, round_K]; round_K = 0: none
-    double ad_alpha, ad_beta1, ad_beta2, ad_eps;
-    int32_t ad_steer;             // tapout_config.adaedl_steer
-};
 hipError_t launch_bandit_select(const BanditArgs &a, const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm);
 hipError_t launch_bandit_update(const BanditArgs &a, const int32_t *arm, const int32_t *accept_len,
                                 const int32_t *n_draft, const int32_t *gamma, const uint8_t *active, hipStream_t st, Timing tm);
+hipError_t launch_bandit_update_select(const BanditArgs &a, const int32_t *arm, const int32_t *accept_len,
+                                       const int32_t *n_draft, const int32_t *gamma, const uint8_t *active,
+                                       const float *u_ts, int32_t *arm_out, uint32_t *flags, hipStream_t st, Timing tm);
 
 // ---- device helpers --------------------------------------------------------
 #ifdef __HIPCC__

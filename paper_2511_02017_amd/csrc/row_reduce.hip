@@ -236,9 +236,9 @@ __device__ inline void fold_batch(ThreadState<FULL> &st, const u32x4 (&w)[U], in
     st.close_batch(grew, sb, tb);
 }
 
-// At least six wavefronts per SIMD (80 vector registers): the draft pass on bfloat16 sits right at that limit.
+// The work of one workgroup: slice `split` of row k of sequence b.
 template <int DT, bool FULL>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) void stream_pass_kernel(RowReduceArgs a)
+__device__ inline void stream_pass_body(const RowReduceArgs &a, const int split, const int k, const int b)
 {
     constexpr int VEC = Elem<DT>::vec;
     // vectors in flight per thread.  Four is best for both passes: for the draft pass that means 77 registers
@@ -248,8 +248,6 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) voi
     __shared__ float sh_f[6][kBlock / kWave];
     __shared__ int sh_i[kBlock / kWave];
 
-    // grid = (slice, row of the sequence, sequence): no index arithmetic ahead of the first load
-    const int split = blockIdx.x, k = blockIdx.y, b = blockIdx.z;
     const int row = b * a.KK + k;
     const int tid = threadIdx.x;
     int n_active;                                   // rows of sequence b this pass reads
@@ -382,6 +380,29 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) voi
     }
 }
 
+// grid = (slice, row of the sequence, sequence): no index arithmetic ahead of the first load.
+// At least six wavefronts per SIMD (80 vector registers): the draft pass on bfloat16 sits right at that limit.
+template <int DT, bool FULL>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) void stream_pass_kernel(RowReduceArgs a)
+{
+    stream_pass_body<DT, FULL>(a, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// Draft rows and target rows of a round in ONE launch: grid = (slice, row, 2 * sequences), the first half of the
+// z range takes the draft tensor, the second half the target tensor (one more row per sequence).  A launch over a
+// few hundred rows spends a fifth of its time filling and draining the chip; one launch over both tensors pays
+// that once.  Both passes are cut into the same number of slices.
+template <int DD, int TD>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) void stream_pair_kernel(RowReduceArgs d, RowReduceArgs t, int n_seq)
+{
+    const int z = blockIdx.z;
+    if (z < n_seq) {
+        if ((int)blockIdx.y < d.KK && (int)blockIdx.x < d.nsplit) stream_pass_body<DD, true>(d, blockIdx.x, blockIdx.y, z);
+    } else {
+        if ((int)blockIdx.x < t.nsplit) stream_pass_body<TD, false>(t, blockIdx.x, blockIdx.y, z - n_seq);
+    }
+}
+
 template <int DT, bool FULL>
 hipError_t launch(const RowReduceArgs &a, hipStream_t st, Timing tm)
 {
@@ -390,7 +411,25 @@ hipError_t launch(const RowReduceArgs &a, hipStream_t st, Timing tm)
     return hipGetLastError();
 }
 
+template <int DD, int TD>
+hipError_t launch_pair(const RowReduceArgs &d, const RowReduceArgs &t, hipStream_t st, Timing tm)
+{
+    const int n_seq = t.n_rows / t.KK;
+    dim3 grid((unsigned)(d.nsplit > t.nsplit ? d.nsplit : t.nsplit), (unsigned)t.KK, (unsigned)(2 * n_seq)), block(kBlock);
+    launch_kernel(stream_pair_kernel<DD, TD>, grid, block, st, tm, d, t, n_seq);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+// d: the draft tensor ([B, K, V], all statistics), t: the target tensor of the same sequences ([B, K + 1, V]).
+hipError_t launch_row_reduce_pair(const RowReduceArgs &d, int d_dtype, const RowReduceArgs &t, int t_dtype, hipStream_t st, Timing tm)
+{
+    if (d.n_rows / d.KK != t.n_rows / t.KK || d.KK + 1 != t.KK || 2 * (t.n_rows / t.KK) > 65535) return hipErrorInvalidValue;
+    if (d_dtype == TAPOUT_F32)
+        return t_dtype == TAPOUT_F32 ? launch_pair<TAPOUT_F32, TAPOUT_F32>(d, t, st, tm) : launch_pair<TAPOUT_F32, TAPOUT_BF16>(d, t, st, tm);
+    return t_dtype == TAPOUT_F32 ? launch_pair<TAPOUT_BF16, TAPOUT_F32>(d, t, st, tm) : launch_pair<TAPOUT_BF16, TAPOUT_BF16>(d, t, st, tm);
+}
 
 hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st, Timing tm)
 {

@@ -40,6 +40,7 @@
 // < 2e-13, far inside what the 1e-9 decision margin needs, at a third of the
 // instructions of a correctly rounded exp.
 #include "common.h"
+#include "bandit_device.h"
 
 namespace tapout {
 
@@ -636,7 +637,10 @@ __device__ __noinline__ double settle_band(const Weights &w, const Rows &r, int 
     return total;
 }
 
-template <int TD, int DD>
+// TAIL: the workgroup also ends its sequence's round for the UCB policies (a logarithm and a square root per arm, one
+// thread).  Thompson Sampling is not offered here: its Gamma / Gaussian draws are long double-precision chains that
+// want 178 registers and scratch memory, which this kernel would then pay for at every launch (measured: twice as long).
+template <int TD, int DD, bool TAIL>
 __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
 {
     __shared__ double shT[256];
@@ -663,7 +667,13 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     // the compiler would otherwise sink these loads below the early exit and pay a second round trip for them
     asm volatile("" :: "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(f4), "v"(tv), "v"(u32v), "v"(band_n), "v"(band_i));
     shT[tid] = tv;
-    if (job.kind == 0) return;                                        // the slice sums of such a sequence are stale: unused
+    // tapout_round: this workgroup also ends the sequence's round (the accepted length is the head's, written by an
+    // earlier launch): reward into its bandit, next arm.
+    auto end_round = [&]() {
+        if constexpr (TAIL)
+            if (tid == 0) update_select_ucb(a.bandit, b, a.b_arm_in, a.accept_len, a.n_draft, a.b_gamma, a.b_active, a.b_arm_out, a.b_flags);
+    };
+    if (job.kind == 0) { end_round(); return; }                       // the slice sums of such a sequence are stale: unused
     if (has_first) { acc[0] = f0; acc[1] = f1; acc[2] = f2; acc[3] = f3; acc[4] = f4; }
     for (int s = tid + kVBlock; s < a.nsl; s += kVBlock)              // vocabularies beyond 256 slices
 #pragma unroll
@@ -823,6 +833,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
             if (a.flags) a.flags[b] = f;
         }
     }
+    end_round();
 }
 
 // ---- draft-token sampling: one job per draft row --------------------------------------------
@@ -1033,7 +1044,8 @@ hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm
         if (a.fused_head) launch_kernel(verify_slices<TD, DD, true>, grid12, block, st, tm, a);
         else launch_kernel(verify_slices<TD, DD, false>, grid12, block, st, tm, a);
     }
-    else launch_kernel(verify_locate<TD, DD>, dim3(a.n_jobs), block, st, tm, a);
+    else if (!a.bandit_tail) launch_kernel(verify_locate<TD, DD, false>, dim3(a.n_jobs), block, st, tm, a);
+    else launch_kernel(verify_locate<TD, DD, true>, dim3(a.n_jobs), block, st, tm, a);
     return hipGetLastError();
 }
 

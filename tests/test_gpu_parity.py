@@ -255,6 +255,121 @@ def test_rounds_replayed_from_hip_graphs_match_eager_rounds(policy):
         assert (a.view(np.int64) == b.view(np.int64)).all()
 
 
+@pytest.mark.parametrize("policy", [binding.UCB1, binding.TS_BETA])
+@pytest.mark.parametrize("truncate,five", [(False, False), (True, False), (True, True)])
+def test_whole_round_in_one_call_gives_the_bits_of_the_separate_calls(policy, truncate, five):
+    """tapout_round (with n_draft given, its target pass runs on the context's second stream beside the draft pass)
+    against select / draft_stats / verify / update on a second context: every output of every round and the bandit
+    state in the end carry the same bits; then the same rounds replayed from HIP graphs, eager work between replays."""
+    w = synth.scaled(synth.WORKLOADS["llama3"], B=12, n_arms=5 if five else 3)
+    gen = synth.RoundGenerator(w, DEV)
+    rounds = [gen.round(r) for r in range(4)]
+    ts = policy == binding.TS_BETA
+    bits = lambda t: t.cpu().view(torch.int32).clone() if t.dtype == torch.float32 else t.cpu().clone()
+    order = [0, 1, 2, 3, 3, 1, 0, 2, 2, 0]
+    u_of = lambda i: rounds[i]["u_ts"] if ts else None
+    # five: the paper's whole arm pool; SVIPDifference and AdaEDL carry state that the end of a round advances
+    kw = dict(policy=policy, rules=FIVE_RULES, thresholds=FIVE_THRESHOLDS) if five else dict(policy=policy)
+
+    def snapshot(outs):
+        d = {"arm": bits(outs["arm"])}
+        d.update({"d_" + k: bits(v) for k, v in outs["draft"].items()})
+        d.update({"v_" + k: bits(v) for k, v in outs["verify"].items()})
+        return d
+
+    def same(got, want, where):
+        """Bit for bit, except that with n_draft given the single call streams both tensors in one launch with a slice
+        count of its own: there the statistics agree to the rounding of the binary32 slice sums, the integers exactly."""
+        if truncate or got.dtype != torch.int32 or where[-1] in ("d_top1_id", "d_n_stop", "d_flags", "v_accept_len", "v_out_tok", "v_n_out",
+                                                                "v_target_top1", "v_flags"):
+            assert torch.equal(got, want), where
+        elif got.dtype == torch.int32:                                     # float bits
+            g_, w_ = got.view(torch.float32).double().numpy(), want.view(torch.float32).double().numpy()
+            floor = 1.0 if where[-1][2:] in pu.LOG_KEYS else 1e-3          # log-domain values: absolute
+            ok = (np.isnan(g_) & np.isnan(w_)) | (np.abs(g_ - w_) <= 2e-6 * np.maximum(np.abs(w_), floor))
+            assert ok.all(), where
+
+    # reference: the separate calls; the uniforms of round i's selection are rounds[order[i]]["u_ts"]
+    tp_ref = binding.Tapout(w.B, w.K, w.V, **kw)
+    expect = []
+    for step, i in enumerate(order):
+        rnd = rounds[i]
+        arm = tp_ref.bandit_select(w.B, u_ts=u_of(i))
+        ds = tp_ref.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arm)
+        nd = ds["n_stop"] if truncate else rnd["k_len"]
+        vf = tp_ref.verify(rnd["target"], rnd["draft"], ds["lse"], ds["logq_tok"], rnd["draft_tok"], nd, rnd["u_accept"], rnd["u_sample"],
+                           greedy=rnd["greedy"])
+        tp_ref.bandit_update(arm, vf["accept_len"], nd, rnd["k_len"])
+        torch.cuda.synchronize()
+        expect.append(snapshot(dict(arm=arm, draft=ds, verify=vf)))
+    state_ref = tp_ref.bandit_get_state(moments=True)
+
+    def one_call_context():
+        tp = binding.Tapout(w.B, w.K, w.V, **kw)
+        arm = torch.zeros(w.B, dtype=torch.int32, device=DEV)
+        # the next selection's uniforms belong to the round that follows in `order`: one prepared call per (round, next round)
+        calls = {}
+        for step, i in enumerate(order):
+            nxt = order[step + 1] if step + 1 < len(order) else order[0]
+            if (i, nxt) not in calls:
+                calls[(i, nxt)] = tp.prepare_round_call(rounds[i], arm, truncate, u_ts_next=u_of(nxt))
+        return tp, arm, calls
+
+    stream = torch.cuda.Stream()
+    tp1, arm1, calls1 = one_call_context()
+    with torch.cuda.stream(stream):
+        tp1.bandit_select(w.B, u_ts=u_of(order[0]), arm_out=arm1, stream=stream)
+        for step, i in enumerate(order):
+            nxt = order[step + 1] if step + 1 < len(order) else order[0]
+            arm_in = bits(arm1)
+            stream.synchronize()
+            arm_in = bits(arm1)
+            launch, outs = calls1[(i, nxt)]
+            launch(stream.cuda_stream)
+            stream.synchronize()
+            got = snapshot(dict(arm=outs["arm"], draft=outs["draft"], verify=outs["verify"]))
+            assert torch.equal(arm_in, expect[step]["arm"]), (step, "arm")
+            for k, v in expect[step].items():
+                if k != "arm":
+                    same(got[k], v, (step, i, k))
+    for a_, b_ in zip(tp1.bandit_get_state(moments=True), state_ref):
+        assert (a_.view(np.int64) == b_.view(np.int64)).all()
+    if five:
+        s1, s2 = tp1.rule_state_get(), tp_ref.rule_state_get()
+        assert (s1["lam"] == s2["lam"]).all() and (s1["accept_rate"] == s2["accept_rate"]).all()
+        assert (s1["prev_entropy"].view(np.int32) == s2["prev_entropy"].view(np.int32)).all()
+
+    # the same from HIP graphs: the fork to the second stream and the join are captured as graph edges
+    tp2, arm2, calls2 = one_call_context()
+    graphs = {}
+    tp2.bandit_select(w.B, u_ts=u_of(order[0]), arm_out=arm2, stream=stream)
+    stream.synchronize()
+    arm_start = arm2.clone()
+    state_start = tp2.bandit_get_state(moments=True)
+    for key, (launch, _) in calls2.items():
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            launch(torch.cuda.current_stream().cuda_stream)
+        graphs[key] = g
+    # capturing runs nothing, but be independent of that: restore the state the first round starts from
+    arm2.copy_(arm_start)
+    tp2.bandit_set_state(state_start[0], state_start[2], sum_r2=state_start[1])
+    scratch = torch.zeros(1 << 20, device=DEV)
+    with torch.cuda.stream(stream):
+        for step, i in enumerate(order):
+            nxt = order[step + 1] if step + 1 < len(order) else order[0]
+            graphs[(i, nxt)].replay()
+            scratch.add_(1.0)
+            stream.synchronize()
+            outs = calls2[(i, nxt)][1]
+            got = snapshot(dict(arm=outs["arm"], draft=outs["draft"], verify=outs["verify"]))
+            for k, v in expect[step].items():
+                if k != "arm":
+                    same(got[k], v, ("graph", step, i, k))
+    for a_, b_ in zip(tp2.bandit_get_state(moments=True), state_ref):
+        assert (a_.view(np.int64) == b_.view(np.int64)).all()
+
+
 def test_head_inside_the_slice_kernel_gives_the_same_bits():
     """Both placements of the accept decisions run the same code: every output of tapout_verify is bit-identical,
     also when the two alternate on one context (the band list of a job record is emptied by whoever appends next)."""
@@ -731,6 +846,58 @@ def test_bandit_trajectory_matches_oracle(policy, reward, shared):
     tp2.bandit_set_state(s, c)
     _, q2, _ = tp2.bandit_get_state(moments=True)
     np.testing.assert_allclose(q2, np.where(c > 0, s * s / np.maximum(c, 1), 0.0), rtol=1e-15)
+
+
+@pytest.mark.parametrize("policy", [binding.UCB1, binding.TS_BETA, binding.UCB_TUNED, binding.TS_GAUSS])
+@pytest.mark.parametrize("kind", ["own", "shared", "token", "stateful"])
+def test_update_and_next_select_in_one_call(policy, kind):
+    """tapout_bandit_update_select against the two separate calls and against the oracle's bandit: the same arms in
+    every round (also with the arm array updated in place), bit-equal state in the end; one launch for per-sequence
+    bandits, the two kernels back to back for shared and token-level ones."""
+    if kind == "token" and policy not in (binding.UCB1, binding.TS_BETA):
+        pytest.skip("token-level bandits are UCB1 or Beta Thompson Sampling")
+    B, K, rounds = 29, 6, 120
+    rules = FIVE_RULES if kind == "stateful" else (0, 1, 2)
+    thresholds = FIVE_THRESHOLDS if kind == "stateful" else (0.6, 0.8, 0.2)
+    A = len(rules)
+    kw = dict(policy=policy, rules=rules, thresholds=thresholds, shared_bandit=kind == "shared", token_level=kind == "token")
+    tp_two, tp_one = binding.Tapout(B, K, 500, **kw), binding.Tapout(B, K, 500, **kw)
+    ob = orc.Bandit(policy, 1 if kind == "shared" else B, A, positions=K if kind == "token" else 1)
+    needs_u = policy in (binding.TS_BETA, binding.TS_GAUSS)
+    g = torch.Generator().manual_seed(23)
+    ushape = (B, K, A, 48) if kind == "token" else (B, A, 48)
+    x = (torch.randn(B, K, 500, generator=g) * 3).to(DEV)
+    u = torch.rand(ushape, generator=g)
+    arm_one = tp_one.bandit_select(B, u_ts=u.to(DEV) if needs_u else None)
+    for r in range(rounds):
+        arm_two = tp_two.bandit_select(B, u_ts=u.to(DEV) if needs_u else None)
+        o_arm, _ = ob.select(B, u.numpy())
+        assert torch.equal(arm_one, arm_two) and (arm_two.cpu().numpy() == o_arm).all(), f"round {r}"
+        if kind == "stateful":                                   # the update also advances the carried rule state
+            tp_two.draft_stats(x, arm=arm_two)
+            tp_one.draft_stats(x, arm=arm_one)
+        n = torch.randint(1, K + 1, (B,), generator=g, dtype=torch.int32)
+        m = (torch.rand(B, generator=g) * (n + 1)).floor().clamp(max=n).to(torch.int32)
+        gamma = torch.full((B,), K, dtype=torch.int32)
+        active = (torch.rand(B, generator=g) < 0.9).to(torch.uint8)
+        u = torch.rand(ushape, generator=g)                      # the uniforms of the NEXT selection
+        tp_two.bandit_update(arm_two, m.to(DEV), n.to(DEV), gamma.to(DEV), active=active.to(DEV))
+        fl = torch.full((B,), 7, dtype=torch.int32, device=DEV)
+        arm_one = tp_one.bandit_update_select(arm_one, m.to(DEV), n.to(DEV), gamma.to(DEV), active=active.to(DEV),
+                                              u_ts=u.to(DEV) if needs_u else None, arm_out=arm_one if r & 1 else None, flags=fl)
+        assert (fl.cpu() & ~8 == 0).all()
+        ob.update(o_arm, m.numpy(), n.numpy(), gamma.numpy(), active=active.numpy())
+    for a_, b_ in zip(tp_one.bandit_get_state(moments=True), tp_two.bandit_get_state(moments=True)):
+        assert (a_.view(np.int64) == b_.view(np.int64)).all()
+    s, q, c = tp_one.bandit_get_state(moments=True)
+    assert (c == ob.count).all() and (s == ob.sum_r).all() and (q == ob.sum_r2).all()
+    if kind == "stateful":
+        s1, s2 = tp_one.rule_state_get(), tp_two.rule_state_get()
+        for k_ in s1:
+            assert (s1[k_].view(np.int32 if s1[k_].dtype == np.float32 else np.int64) ==
+                    s2[k_].view(np.int32 if s2[k_].dtype == np.float32 else np.int64)).all(), k_
+    with pytest.raises(binding.TapoutError, match="arm_out|required"):
+        tp_one._check(tp_one._lib.tapout_bandit_update_select(tp_one._ctx, B, None, None, None, None, None, None, None, None, None))
 
 
 @pytest.mark.parametrize("name", ["tiny", "small", "llama3"])

@@ -39,11 +39,73 @@ namespace tapout {
 
 namespace {
 
-__device__ inline float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+// max3 / med3 / max as the bare instructions.  fmaxf() and the med3 builtin first quiet every operand the compiler
+// cannot prove to be a canonical number (one v_max_f32 x, x per logit, a tenth of the draft pass's vector
+// instructions); the instructions themselves already return the other operand when one is a NaN, which is what the
+// running maxima want (NaN logits are ignored here and poison the sums instead).
+__device__ inline float max3(float a, float b, float c)
+{
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ inline float med3(float a, float b, float c)
+{
+    float r;
+    asm("v_med3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ inline float max2(float a, float b)
+{
+    float r;
+    asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+__device__ inline float min2(float a, float b)
+{
+    float r;
+    asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
 
 // Headroom (in powers of two) added to a thread's reference when it has to be
 // raised, so that a slowly growing running maximum raises it only a few times.
 constexpr float kHeadroom = 8.0f;
+
+// Running maximum (and second maximum) over the values of one 16-byte vector, as one block of instructions: a
+// statement per instruction makes the compiler put a wait state after each.
+template <bool FULL>
+__device__ inline void vector_max(float &v1, float &v2, const float (&x)[8])
+{
+    if constexpr (FULL) {
+        float t;
+        asm("v_med3_f32 %2, %0, %3, %4\n\tv_max_f32 %1, %1, %2\n\tv_max3_f32 %0, %0, %3, %4\n\t"
+            "v_med3_f32 %2, %0, %5, %6\n\tv_max_f32 %1, %1, %2\n\tv_max3_f32 %0, %0, %5, %6\n\t"
+            "v_med3_f32 %2, %0, %7, %8\n\tv_max_f32 %1, %1, %2\n\tv_max3_f32 %0, %0, %7, %8\n\t"
+            "v_med3_f32 %2, %0, %9, %10\n\tv_max_f32 %1, %1, %2\n\tv_max3_f32 %0, %0, %9, %10"
+            : "+v"(v1), "+v"(v2), "=&v"(t)
+            : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]), "v"(x[4]), "v"(x[5]), "v"(x[6]), "v"(x[7]));
+    } else {
+        asm("v_max3_f32 %0, %0, %1, %2\n\tv_max3_f32 %0, %0, %3, %4\n\tv_max3_f32 %0, %0, %5, %6\n\tv_max3_f32 %0, %0, %7, %8"
+            : "+v"(v1)
+            : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]), "v"(x[4]), "v"(x[5]), "v"(x[6]), "v"(x[7]));
+    }
+}
+template <bool FULL>
+__device__ inline void vector_max(float &v1, float &v2, const float (&x)[4])
+{
+    if constexpr (FULL) {
+        float t;
+        asm("v_med3_f32 %2, %0, %3, %4\n\tv_max_f32 %1, %1, %2\n\tv_max3_f32 %0, %0, %3, %4\n\t"
+            "v_med3_f32 %2, %0, %5, %6\n\tv_max_f32 %1, %1, %2\n\tv_max3_f32 %0, %0, %5, %6"
+            : "+v"(v1), "+v"(v2), "=&v"(t)
+            : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));
+    } else {
+        asm("v_max3_f32 %0, %0, %1, %2\n\tv_max3_f32 %0, %0, %3, %4"
+            : "+v"(v1)
+            : "v"(x[0]), "v"(x[1]), "v"(x[2]), "v"(x[3]));
+    }
+}
 
 template <bool FULL>
 struct ThreadState {
@@ -76,70 +138,61 @@ struct ThreadState {
         }
     }
 
-    // Maxima of N values that start at element index `first` of the row; `first` is remembered as the
-    // argmax candidate when the running maximum grows.
-    // Returns whether the running maximum grew.
-    template <int N>
-    __device__ inline bool fold_max(const float (&x)[N], int32_t first)
+    // A batch of U vectors of N values each (vector u starts at element index first + u * stride of the row), vector
+    // by vector: maxima (`first + u * stride` is remembered as the argmax candidate when vector u raises the running
+    // maximum), reference check, sums.  The entropy sum of a vector is formed without looking at the terms; a masked
+    // (-inf) logit gives 0 * -inf = NaN there, and only then the vector is summed again with the exponent clamped (one
+    // comparison per vector instead of one clamp per element).
+    template <int U, int N>
+    __device__ inline void fold_batch(const u32x4 (&w)[U], int32_t first, int32_t stride)
     {
-        float old = v1;
-        if constexpr (N == 1) {
-            if constexpr (FULL) v2 = fmaxf(v2, fminf(v1, x[0]));
-            v1 = fmaxf(v1, x[0]);
-        } else {
+        bool grew = false;                                    // a lane mask in scalar registers
+        float sb = 0.0f, tb = 0.0f;
 #pragma unroll
-            for (int i = 0; i < N; i += 2) {
-                if constexpr (FULL) v2 = fmaxf(v2, __builtin_amdgcn_fmed3f(v1, x[i], x[i + 1]));
-                v1 = max3(v1, x[i], x[i + 1]);
+        for (int u = 0; u < U; ++u) {
+            float x[N];
+            if constexpr (N == 8) unpack<TAPOUT_BF16>(w[u], x);
+            else if constexpr (N == 4) unpack<TAPOUT_F32>(w[u], x);
+            else x[0] = __uint_as_float(w[u].x);
+            const float old = v1;
+            if constexpr (N == 1) {
+                if constexpr (FULL) v2 = max2(v2, min2(v1, x[0]));
+                v1 = max2(v1, x[0]);
+            } else {
+                vector_max<FULL>(v1, v2, x);
             }
-        }
-        const bool grew = v1 > old;
-        cand = grew ? first : cand;
-        return grew;
-    }
-
-    // Sums over N values the reference already covers.  The entropy sum of the group is formed without
-    // looking at the terms; a masked (-inf) logit gives 0 * -inf = NaN there, and only then the group is
-    // summed again with the exponent clamped (one comparison per group instead of one clamp per element).
-    // The target pass adds straight into s; the draft pass into the sums sb, tb of the batch in progress.
-    template <int N>
-    __device__ inline void fold_sums(const float (&x)[N], float &sb, float &tb)
-    {
-        float tv = 0.0f;
+            const bool g = v1 > old;
+            cand = g ? first + u * stride : cand;
+            grew |= g;
+            cover_max(sb, tb);
+            float y[N], e[N];
 #pragma unroll
-        for (int i = 0; i < N; ++i) {
-            float y = __builtin_fmaf(x[i], kLog2e, -R);
-            float e = __builtin_amdgcn_exp2f(y);
-            if constexpr (FULL) sb += e; else s += e;
-            if constexpr (FULL) tv = __builtin_fmaf(e, y, tv);
-        }
-        if constexpr (FULL) {
-            if (tv != tv) {
-                tv = 0.0f;
+            for (int i = 0; i < N; ++i) {
+                y[i] = __builtin_fmaf(x[i], kLog2e, -R);
+                e[i] = __builtin_amdgcn_exp2f(y[i]);
+            }
+            float sv = e[0];
+            float tv = FULL ? e[0] * y[0] : 0.0f;
 #pragma unroll
-                for (int i = 0; i < N; ++i) {
-                    float y = __builtin_fmaf(x[i], kLog2e, -R);
-                    tv = __builtin_fmaf(__builtin_amdgcn_exp2f(y), fmaxf(y, -200.0f), tv);
+            for (int i = 1; i < N; ++i) {
+                sv += e[i];
+                if constexpr (FULL) tv = __builtin_fmaf(e[i], y[i], tv);
+            }
+            if constexpr (FULL) {
+                if (tv != tv) {
+                    tv = 0.0f;
+#pragma unroll
+                    for (int i = 0; i < N; ++i) tv = __builtin_fmaf(e[i], fmaxf(y[i], -200.0f), tv);
                 }
+                sb = u == 0 ? sv : sb + sv;                   // (a sum started from 0.0f would cost an addition: -0 + 0)
+                tb = u == 0 ? tv : tb + tv;
+            } else {
+                s += sv;
             }
-            tb += tv;
         }
-    }
-
-    template <int N>
-    __device__ inline bool fold(const float (&x)[N], int32_t first, float &sb, float &tb)
-    {
-        const bool grew = fold_max<N>(x, first);
-        cover_max(sb, tb);
-        fold_sums<N>(x, sb, tb);
-        return grew;
-    }
-
-    // End of a batch (FULL): if the running maximum grew inside it, its sums become the set-apart ones and the
-    // batch that held the previous maximum joins the rest; else it joins the rest itself.
-    __device__ inline void close_batch(bool grew, float sb, float tb)
-    {
         if constexpr (FULL) {
+            // If the running maximum grew inside the batch, its sums become the set-apart ones and the batch that held
+            // the previous maximum joins the rest; else it joins the rest itself.
             s += grew ? s_hi : sb;
             t += grew ? t_hi : tb;
             s_hi = grew ? sb : s_hi;
@@ -150,10 +203,9 @@ struct ThreadState {
     // One element on its own (unaligned head or tail of a row): a batch of one.
     __device__ inline void fold_single(float x0, int32_t j)
     {
-        float sb = 0.0f, tb = 0.0f;
-        float x[1] = { x0 };
-        const bool grew = fold<1>(x, j, sb, tb);
-        close_batch(grew, sb, tb);
+        u32x4 w[1];
+        w[0] = u32x4{__float_as_uint(x0), 0u, 0u, 0u};
+        fold_batch<1, 1>(w, j, 0);
     }
 };
 
@@ -225,15 +277,7 @@ template <int DT, bool FULL, int U>
 __device__ inline void fold_batch(ThreadState<FULL> &st, const u32x4 (&w)[U], int i, int head)
 {
     constexpr int VEC = Elem<DT>::vec;
-    bool grew = false;                                    // a lane mask in scalar registers
-    float sb = 0.0f, tb = 0.0f;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        float x[VEC];
-        unpack<DT>(w[u], x);
-        grew |= st.template fold<VEC>(x, head + (i + u * kBlock) * VEC, sb, tb);
-    }
-    st.close_batch(grew, sb, tb);
+    st.template fold_batch<U, VEC>(w, head + i * VEC, kBlock * VEC);
 }
 
 // The work of one workgroup: slice `split` of row k of sequence b.

@@ -15,9 +15,12 @@ Prints ONE JSON line.
                         the four separate calls); the timed region carries no instrumentation at all
   roofline*             after the timed region the same steps run again as four calls, kernel by kernel, with an event
                         pair on every launch (at least 32 steps whatever --steps is): algorithmic bytes per launch over the
-                        kernel's average duration against the 8 TB/s HBM peak.  roofline = the launch with the most
-                        bytes (target pass), roofline_draft_reduce = the draft pass, roofline_streaming = both
-                        weighted by their bytes, roofline_final_token = the final-token slice pass
+                        kernel's average duration against the 8 TB/s HBM peak; then once more as tapout_round calls.
+                        roofline = the launch with the most bytes of the timed region (tapout_round's one streaming
+                        launch over draft and target rows; the target pass where the round does not pair them),
+                        roofline_target_reduce / roofline_draft_reduce = the two passes as launches of their own,
+                        roofline_streaming = both weighted by their bytes, roofline_final_token = the final-token
+                        slice pass
   roofline_zipf/_ragged the other two configurations with V >= 128k, timed the same way in the same run (no CPU leg)
   parity                decisions of a round of each timed configuration against the CPU oracle: near ties the oracle
                         flags, and mismatches outside them (must be 0)
@@ -208,9 +211,15 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
     run4(kernel_steps, first=first_k)              # kernel by kernel: the four calls, nothing overlapped
     torch.cuda.synchronize()
     prof = {k: tp.profile_read(k) for k in kinds}
+    prof_round = None
+    if one_call:                                   # and the launches of the single call the timed region is made of
+        run(kernel_steps, first=first_k)
+        torch.cuda.synchronize()
+        prof_round = {k: tp.profile_read(k) for k in kinds}
     tp.profile_enable((), 0)
     kslots = [(first_k + i) % ring_n for i in range(kernel_steps)]
     names = kernel_names(w, torch)
+    names["stream_pair"] = f"stream_pair_kernel<{1 if w.draft_dtype == torch.bfloat16 else 0}, {1 if w.target_dtype == torch.bfloat16 else 0}>"
     # the final-token slice pass reads one row pair per sampled sequence (draft + target row of the first rejected
     # position, or the last target row alone when nothing was rejected)
     greedy = ring[0]["greedy"].cpu().bool()
@@ -221,8 +230,8 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
         alone = ((m >= n) & ~greedy).sum().item()
         return w.V * (pair * (ed + et) + alone * et)
 
-    def roof(kind, bytes_of_slot, traffic=False):
-        ms, n = prof[kind]
+    def roof(kind, bytes_of_slot, traffic=False, source=None):
+        ms, n = (source or prof)[kind]
         if n == 0:
             return None
         assert n == len(kslots), (kind, n, len(kslots))
@@ -247,6 +256,15 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
         r_stream = dict(kernel="draft pass + target pass", bound="hbm", achieved=round(gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(gbs / HBM_PEAK_GBS, 4), avg_us=round(us, 2), launches=r_target["launches"],
                         bytes_per_launch=r_target["bytes_per_launch"] + r_draft["bytes_per_launch"])
+    # The launch with the most bytes in the timed region: the pair launch of tapout_round (draft and target rows in one
+    # streaming pass) where the round takes it, else the target pass.
+    r_headline, r_pair = r_target, None
+    if prof_round and prof_round["stream_pair"][1]:
+        r_pair = roof("stream_pair", lambda s: w.V * (int(k_len_ring[s].sum()) * ed + (int(n_draft_ring[s].sum()) + w.B) * et), source=prof_round)
+        if r_target and r_draft and r_target.get("traffic") and r_draft.get("traffic"):
+            r_pair["traffic"] = r_target["traffic"] + r_draft["traffic"]
+            r_pair["traffic_source"] = "sum of the two passes' committed counter figures (same bytes, one launch): " + r_target["traffic_source"]
+        r_headline = r_pair
     res = {
         "value": round(verified / elapsed, 1), "unit": "verified draft tokens/s", "steps": steps, "warmup": warmup,
         "ms_per_step": round(ms_per_step, 4),
@@ -260,9 +278,12 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
         "rows_per_s": round((draft_rows + target_rows) / elapsed, 1),
         "whole_round_GBps": round(stream_bytes / elapsed / 1e9, 1),
         "whole_round_frac_of_hbm_peak": round(stream_bytes / elapsed / 1e9 / HBM_PEAK_GBS, 4),
-        "roofline": r_target, "roofline_draft_reduce": r_draft, "roofline_streaming": r_stream, "roofline_final_token": r_final,
+        "roofline": r_headline, "roofline_target_reduce": r_target, "roofline_draft_reduce": r_draft, "roofline_streaming": r_stream,
+        "roofline_final_token": r_final,
         "kernel_avg_us": {k: round(prof[k][0] / prof[k][1] * 1e3, 2) for k in kinds if prof[k][1]},
     }
+    if prof_round:
+        res["kernel_avg_us_round_call"] = {k: round(prof_round[k][0] / prof_round[k][1] * 1e3, 2) for k in kinds if prof_round[k][1]}
     if elapsed4 is not None:
         res["four_calls"] = {"ms_per_step": round(elapsed4 / steps * 1e3, 4), "value": round(verified / elapsed4, 1),
                              "note": "the same steps as select / draft_stats / verify / update, one after the other on one stream"}
@@ -343,9 +364,10 @@ def main():
             del k2
             out["roofline_" + name] = {"ms_per_step": r["ms_per_step"], "value": r["value"], "unit": r["unit"], "steps": r["steps"],
                                        "config": r["config"], "whole_round_frac_of_hbm_peak": r["whole_round_frac_of_hbm_peak"],
-                                       "target_pass": r["roofline"], "draft_pass": r["roofline_draft_reduce"],
+                                       "round_call": r["roofline"], "target_pass": r["roofline_target_reduce"], "draft_pass": r["roofline_draft_reduce"],
                                        "streaming": r["roofline_streaming"], "final_token": r["roofline_final_token"],
-                                       "kernel_avg_us": r["kernel_avg_us"], "parity": r.get("parity")}
+                                       "kernel_avg_us": r["kernel_avg_us"], "kernel_avg_us_round_call": r.get("kernel_avg_us_round_call"),
+                                       "four_calls": r.get("four_calls"), "parity": r.get("parity")}
     print(json.dumps(out))
 
 

@@ -200,6 +200,84 @@ __device__ inline void update_select_ucb(const BanditArgs &a, int b, const int32
     if (flags) flags[b] = 0u;
 }
 
+// The same on the first TAPOUT_MAX_ARMS lanes of a wavefront, one arm per lane, in two steps for a kernel that has
+// other work in between.  ucb_lane_prefetch requests what the update and the selection read (the lane's arm of the
+// sequence's bandit state; the sequence's arm, lengths and cap) in one memory round trip.  ucb_lane_finish works on the
+// register copies: the lane of the played arm applies the reward and writes its state back, every lane forms the index
+// of its arm (the logarithm, quotient and square root of the arms side by side instead of one after the other), and
+// the argmax runs over the lanes, lowest arm on ties, an unplayed arm first.  Per arm the same double operations as
+// ucb1_arm / ucb_tuned_arm, hence the same bits.  All TAPOUT_MAX_ARMS lanes must be active in both calls.
+struct UcbLane {
+    double S, Q;
+    int64_t N;
+    int32_t arm, n_draft, gamma;
+    bool active;
+};
+
+__device__ inline UcbLane ucb_lane_prefetch(const BanditArgs &a, int b, int lane, const int32_t *arm, const int32_t *n_draft,
+                                            const int32_t *gamma, const uint8_t *active)
+{
+    UcbLane r;
+    const size_t nb = (size_t)b * a.n_arms;
+    const bool on = lane < a.n_arms;
+    r.S = on ? a.sum_r[nb + lane] : 0.0;
+    r.Q = on ? a.sum_r2[nb + lane] : 0.0;
+    r.N = on ? a.count[nb + lane] : 0;
+    r.arm = arm[b]; r.n_draft = n_draft[b]; r.gamma = gamma[b];
+    r.active = !(active && !active[b]);
+    return r;
+}
+
+__device__ inline void ucb_lane_finish(const BanditArgs &a, int b, int lane, UcbLane r, int32_t accept_len, int32_t *arm_out, uint32_t *flags)
+{
+    const size_t nb = (size_t)b * a.n_arms;
+    const bool on = lane < a.n_arms;
+    if (r.active && r.n_draft >= 1 && r.gamma >= 1 && r.arm >= 0 && r.arm < a.n_arms && lane == r.arm) {
+        const double m = (double)accept_len;
+        const double rew = a.reward == TAPOUT_REWARD_SIMPLE
+                               ? m / (double)r.gamma
+                               : (a.alpha * m) / (double)r.gamma + ((1.0 - a.alpha) * m) / (double)r.n_draft;
+        r.N += 1; r.S += rew; r.Q += rew * rew;
+        a.count[nb + lane] = r.N; a.sum_r[nb + lane] = r.S; a.sum_r2[nb + lane] = r.Q;
+    }
+    if (lane == 0 && a.accept_rate && r.active && r.n_draft >= 1 && (a.round_K == 0 || r.n_draft <= a.round_K))
+        advance_rule_state(a, b, accept_len, r.n_draft);
+    // t = 1 + all plays (an integer: any order)
+    int64_t t = on ? r.N : 0;
+#pragma unroll
+    for (int d = 1; d < TAPOUT_MAX_ARMS; d <<= 1) {
+        const int lo = __shfl_xor((int)(uint32_t)t, d), hi = __shfl_xor((int)(t >> 32), d);
+        t += (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+    }
+    t += 1;
+    const double n = (double)r.N;
+    double v;
+    if (a.policy == TAPOUT_UCB1) {
+        v = r.S / n + sqrt((2.0 * log((double)t)) / n);
+    } else {
+        const double lt = log((double)t);
+        const double mean = r.S / n;
+        const double var = r.Q / n - mean * mean;
+        const double V = var + sqrt((2.0 * lt) / n);
+        const double cap = V < 0.25 ? V : 0.25;
+        v = mean + sqrt((lt / n) * cap);
+    }
+    // an arm never played goes first (lowest index); else the first maximum in index order
+    const uint64_t unplayed = __ballot(on && r.N == 0) & 0xffull;
+    int best = on ? lane : 0x7fffffff;
+    if (!on) v = -INFINITY;
+#pragma unroll
+    for (int d = 1; d < TAPOUT_MAX_ARMS; d <<= 1) {
+        const double ov = __shfl_xor(v, d);
+        const int ob = __shfl_xor(best, d);
+        if (ov > v || (ov == v && ob < best)) { v = ov; best = ob; }
+    }
+    if (lane == 0) {
+        arm_out[b] = unplayed ? __builtin_ctzll(unplayed) : (best == 0x7fffffff ? 0 : best);
+        if (flags) flags[b] = 0u;
+    }
+}
+
 // The same for Thompson Sampling with Beta posteriors on 16 consecutive lanes of a wavefront (lane16 = 0..15 = 2 * arm +
 // variate; b >= a.B: idle group): every lane holds the count and the reward sum of its arm in registers and applies
 // the reward to its own copy if its arm was the one played; one lane writes the state back.  No lane reads what

@@ -664,6 +664,16 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     const int band_n = a.jobs[j].band_cnt;
     const int band_i = a.jobs[j].band_idx[tid & (kBandCap - 1)];                                  // stale beyond band_n: unused
     const SampleJob job = a.jobs[j].job;
+    // TAIL: the first thread also requests what the end of the round reads (bandit state of the sequence, its arm,
+    // lengths; the accepted length is the head's, written by an earlier launch)
+    UcbLane ucb;
+    int32_t acc_len = 0;
+    if constexpr (TAIL)
+        if (tid < TAPOUT_MAX_ARMS) {                                  // one arm per lane
+            ucb = ucb_lane_prefetch(a.bandit, b, tid, a.b_arm_in, a.n_draft, a.b_gamma, a.b_active);
+            acc_len = a.accept_len[b];
+            asm volatile("" :: "v"(ucb.S), "v"(ucb.Q), "v"(ucb.N), "v"(ucb.arm), "v"(ucb.n_draft), "v"(ucb.gamma), "v"(acc_len));
+        }
     // the compiler would otherwise sink these loads below the early exit and pay a second round trip for them
     asm volatile("" :: "v"(f0), "v"(f1), "v"(f2), "v"(f3), "v"(f4), "v"(tv), "v"(u32v), "v"(band_n), "v"(band_i));
     shT[tid] = tv;
@@ -671,7 +681,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
     // earlier launch): reward into its bandit, next arm.
     auto end_round = [&]() {
         if constexpr (TAIL)
-            if (tid == 0) update_select_ucb(a.bandit, b, a.b_arm_in, a.accept_len, a.n_draft, a.b_gamma, a.b_active, a.b_arm_out, a.b_flags);
+            if (tid < TAPOUT_MAX_ARMS) ucb_lane_finish(a.bandit, b, tid, ucb, acc_len, a.b_arm_out, a.b_flags);
     };
     if (job.kind == 0) { end_round(); return; }                       // the slice sums of such a sequence are stale: unused
     if (has_first) { acc[0] = f0; acc[1] = f1; acc[2] = f2; acc[3] = f3; acc[4] = f4; }

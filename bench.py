@@ -261,7 +261,10 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
     r_headline, r_pair = r_target, None
     if prof_round and prof_round["stream_pair"][1]:
         r_pair = roof("stream_pair", lambda s: w.V * (int(k_len_ring[s].sum()) * ed + (int(n_draft_ring[s].sum()) + w.B) * et), source=prof_round)
-        if r_target and r_draft and r_target.get("traffic") and r_draft.get("traffic"):
+        own = committed_traffic(w, names["stream_pair"])
+        if own:
+            r_pair["traffic"], r_pair["traffic_source"] = own, r_target["traffic_source"]
+        elif r_target and r_draft and r_target.get("traffic") and r_draft.get("traffic"):
             r_pair["traffic"] = r_target["traffic"] + r_draft["traffic"]
             r_pair["traffic_source"] = "sum of the two passes' committed counter figures (same bytes, one launch): " + r_target["traffic_source"]
         r_headline = r_pair

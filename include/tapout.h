@@ -557,11 +557,20 @@ TAPOUT_API tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *pre
  *                 takes them again for its sequence (pays while that kernel
  *                 is a few workgroups per compute unit); 0 = separate launch;
  *                 -1 (default) = decide per call from the launch size
+ *   "defer_epilogue"  tapout_round only: 1 (default) = when n_draft comes
+ *                 from the caller (and no arm carries rule state), the accept
+ *                 decisions form log q(tok) from the draft pass's slice sums
+ *                 themselves (binary32 precision) and the draft epilogue
+ *                 runs beside the final-token locate kernel in one launch;
+ *                 0 = the epilogue keeps its own launch ahead of the
+ *                 verification, which then reads the logq_tok it wrote
  *   "profile_stride"  kernel timing (below) attaches events to every n-th
  *                 launch of a selected kernel only, default 1: an event pair
  *                 costs a few microseconds of the stream's time per launch
  * Results do not depend on these values except through the rounding of the
- * binary32 partial sums ("fuse_head", "profile_stride": not at all).
+ * binary32 partial sums ("fuse_head", "profile_stride": not at all;
+ * "defer_epilogue": an accept decision whose uniform lies within 1e-6
+ * (relative) of p/q may fall the other way).
  */
 TAPOUT_API tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value);
 

@@ -33,6 +33,7 @@ struct tapout_ctx {
     int min_slice = 4096;         // smallest slice (elements) a row is cut into
     int slice_bytes = 65536;      // slice size aimed for when the rows alone give enough workgroups
     int fuse_head = -1;           // tapout_verify: accept decisions inside the slice kernel (1), in a launch of their own (0), by size (-1)
+    int defer_epilogue = 1;       // tapout_round: the draft epilogue may run beside the final-token locate kernel (1) or keeps its own launch (0)
     // optional kernel timing (tapout_profile_*): event pairs around the launches of selected kernels
     uint32_t prof_mask = 0;
     int prof_cap = 0;
@@ -344,6 +345,9 @@ tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value
     } else if (!strcmp(name, "fuse_head")) {
         if (value < -1 || value > 1) return fail(ctx, TAPOUT_EINVAL, "fuse_head outside {-1, 0, 1}");
         ctx->fuse_head = value;
+    } else if (!strcmp(name, "defer_epilogue")) {
+        if (value < 0 || value > 1) return fail(ctx, TAPOUT_EINVAL, "defer_epilogue outside {0, 1}");
+        ctx->defer_epilogue = value;
     } else return fail(ctx, TAPOUT_EINVAL, "unknown option '%s'", name);
     return TAPOUT_OK;
 }
@@ -402,7 +406,9 @@ hipError_t stream_pair(tapout_ctx *ctx, const RowReduceArgs &d, int d_dtype, con
 RowReduceArgs target_pass_args(tapout_ctx *ctx, const VerifyCall &c);
 
 // tapout_draft_stats.  pair != NULL (tapout_round): the streaming pass is one launch over the draft rows and the target
-// rows of *pair, with pair_nsplit slices per row for both.
+// rows of *pair, with pair_nsplit slices per row for both.  defer != NULL (tapout_round): the epilogue is not launched;
+// its arguments go to *defer for the caller to run later, the slice count to *defer_nsplit, and the streaming pass
+// leaves the logits of the drafted tokens in its partials.
 tapout_status draft_stats_impl(tapout_ctx *ctx, const tapout_logits *draft,
                                  int32_t B, int32_t K, int32_t V,
                                  const int32_t *draft_tok, const int32_t *k_len, const int32_t *arm,
@@ -410,7 +416,7 @@ tapout_status draft_stats_impl(tapout_ctx *ctx, const tapout_logits *draft,
                                  float *lse, float *entropy, float *p_top1, float *p_top2, float *margin,
                                  int32_t *top1_id, float *logq_tok, int32_t *sampled_tok,
                                  int32_t *n_stop, uint8_t *stop_fired, uint32_t *flags, void *stream,
-                                 const VerifyCall *pair, int pair_nsplit)
+                                 const VerifyCall *pair, int pair_nsplit, DraftFinalArgs *defer = nullptr, int *defer_nsplit = nullptr)
 {
     if (!ctx) return TAPOUT_EINVAL;
     tapout_status s = check_shape(ctx, B, K, V);
@@ -429,6 +435,10 @@ tapout_status draft_stats_impl(tapout_ctx *ctx, const tapout_logits *draft,
     if ((size_t)(rows * nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
 
     RowReduceArgs r{draft->ptr, draft->stride_b, draft->stride_k, V, K, nsplit, slice_vectors(V, draft->dtype, nsplit), (int32_t)rows, k_len, 0, ctx->part};
+    if (defer) {
+        if (u_draft || !draft_tok) return fail(ctx, TAPOUT_EINVAL, "internal: a deferred epilogue needs the caller's draft tokens");
+        r.tok = draft_tok; r.tok_rows = K;
+    }
     hipError_t e = pair ? stream_pair(ctx, r, draft->dtype, *pair, st)
                         : timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, [&](Timing tm) { return launch_row_reduce(r, draft->dtype, true, st, tm); });
     if (e != hipSuccess) return hip_fail(ctx, e, "draft pass launch");
@@ -462,6 +472,7 @@ tapout_status draft_stats_impl(tapout_ctx *ctx, const tapout_logits *draft,
         f.round_entropy = ctx->round_entropy;
         ctx->round_K = K;
     }
+    if (defer) { *defer = f; *defer_nsplit = nsplit; return TAPOUT_OK; }
     e = timed(ctx, TAPOUT_PROFILE_DRAFT_FINALIZE, [&](Timing tm) { return launch_draft_finalize(f, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "draft finalize launch");
 }
@@ -751,9 +762,13 @@ hipError_t stream_pair(tapout_ctx *ctx, const RowReduceArgs &d, int d_dtype, con
 // tail (tapout_round): what the locate kernel needs to end each sequence's round, or NULL.
 struct RoundTail { const int32_t *arm_in, *gamma; const uint8_t *active; const float *u_ts; int32_t *arm_out; uint32_t *flags; };
 
-hipError_t verify_rest(tapout_ctx *ctx, const VerifyCall &c, hipStream_t st, const RoundTail *tail = nullptr)
+// fin (tapout_round): the draft epilogue has not run: the accept decisions take log q(tok) from the draft partials
+// (fin_nsplit slices per draft row) and the epilogue runs in the locate kernel's launch.
+hipError_t verify_rest(tapout_ctx *ctx, const VerifyCall &c, hipStream_t st, const RoundTail *tail = nullptr,
+                       const DraftFinalArgs *fin = nullptr, int fin_nsplit = 0)
 {
     VerifyArgs va{};
+    if (fin) { va.own_q = 1; va.d_nsplit = fin_nsplit; va.dpart = fin->part; }
     if (tail) {
         va.bandit_tail = 1;
         va.bandit = bandit_args(ctx, c.B);
@@ -773,7 +788,7 @@ hipError_t verify_rest(tapout_ctx *ctx, const VerifyCall &c, hipStream_t st, con
     va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
     hipError_t e = hipSuccess;
     for (int pass = c.fused ? 1 : 0; pass <= 2 && e == hipSuccess; ++pass)
-        e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, [&](Timing tm) { return launch_verify(va, pass, st, tm); });
+        e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD + pass, [&](Timing tm) { return launch_verify(va, pass, st, tm, fin); });
     return e;
 }
 
@@ -827,9 +842,20 @@ tapout_status tapout_round(tapout_ctx *ctx, const tapout_round_args *a, void *st
         c.nsplit = choose_nsplit(ctx, (int64_t)a->B * (2 * a->K + 1), a->V, a->target->dtype);
         if ((size_t)((int64_t)a->B * (a->K + 1) * c.nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
     }
+    // With n_draft from the caller nothing of the verification waits for the draft epilogue's outputs if the accept
+    // decisions form log q(tok) from the draft partials themselves (shapes whose partials one workgroup merges across
+    // lanes; the stateful rules' epilogue hands entropies to the end of the round, so it keeps its place): then the
+    // epilogue, a latency-bound kernel of B workgroups, runs beside the final-token locate kernel, another one, in
+    // one launch.
+    const int d_nsplit = pair ? c.nsplit : choose_nsplit(ctx, (int64_t)a->B * a->K, a->V, a->draft->dtype);
+    const bool defer = a->n_draft != nullptr && a->n_draft != a->n_stop && !ctx->stateful && ctx->defer_epilogue &&
+                       own_q_shape(a->K, c.nsplit, d_nsplit);
+    DraftFinalArgs fin{};
+    int fin_nsplit = 0;
     s = draft_stats_impl(ctx, a->draft, a->B, a->K, a->V, a->draft_tok, a->k_len, a->arm, nullptr,
                          a->lse, a->entropy, a->p_top1, a->p_top2, a->margin, a->top1_id, a->logq_tok, nullptr,
-                         a->n_stop, a->stop_fired, a->draft_flags, stream, pair ? &c : nullptr, c.nsplit);
+                         a->n_stop, a->stop_fired, a->draft_flags, stream, pair ? &c : nullptr, c.nsplit,
+                         defer ? &fin : nullptr, &fin_nsplit);
     if (s != TAPOUT_OK) return s;
     hipError_t e = hipSuccess;
     if (!pair) {
@@ -842,7 +868,7 @@ tapout_status tapout_round(tapout_ctx *ctx, const tapout_round_args *a, void *st
     const bool tail = ctx->positions == 1 && ctx->cfg.n_bandits != 1 &&
                       (ctx->cfg.policy == TAPOUT_UCB1 || ctx->cfg.policy == TAPOUT_UCB_TUNED);
     const RoundTail rt{a->arm, a->gamma, a->active, a->u_ts_next, a->arm, a->select_flags};
-    e = verify_rest(ctx, c, st, tail ? &rt : nullptr);
+    e = verify_rest(ctx, c, st, tail ? &rt : nullptr, defer ? &fin : nullptr, fin_nsplit);
     if (e != hipSuccess) return hip_fail(ctx, e, "verify launch");
     if (tail) return TAPOUT_OK;
     return tapout_bandit_update_select(ctx, a->B, a->arm, a->accept_len, n_draft, a->gamma, a->active, a->u_ts_next, a->arm, a->select_flags, stream);

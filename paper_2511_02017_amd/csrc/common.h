@@ -31,6 +31,7 @@ struct Partial {
     int32_t cand;    // element index at which the 8- (bf16) / 4- (f32) element vector holding the first maximum starts
                      // (shard records: the global index of the first maximum itself)
     int32_t pad[3];  // pad[0]: bits of the logit of the row's token if the slice / shard holds it, else NaN
+                     // pad[1]: draft rows: the left-out batch's own sum (binary32, same reference): S + it covers the slice
 };
 static_assert(sizeof(Partial) == 32, "Partial is one 32-byte record");
 static_assert(sizeof(tapout_shard_stat) == sizeof(Partial), "shard records are staged and merged as partials");
@@ -140,9 +141,12 @@ struct BanditArgs {
 // Verification + final token: the head kernel merges the target partials of each sequence, takes the
 // accept decisions and describes the final-token draw (SampleJob); the slice kernel sums the row pair
 // per slice; the locate kernel finds the token.
+// (Kept at 512 bytes or less: past that the compiler reaches the arguments differently and the fused slice kernel
+// takes 107 vector registers instead of 95, one wavefront per SIMD fewer.  own_q and d_nsplit sit in what would be
+// alignment padding.)
 struct VerifyArgs {
-    const void *tbase; int32_t t_dtype; int64_t t_stride_b, t_stride_k;
-    const void *dbase; int32_t d_dtype; int64_t d_stride_b, d_stride_k;
+    const void *tbase; int32_t t_dtype; int32_t own_q; int64_t t_stride_b, t_stride_k;
+    const void *dbase; int32_t d_dtype; int32_t d_nsplit; int64_t d_stride_b, d_stride_k;
     int32_t B, K, V, nsplit;      // nsplit: slices per row of the streaming pass
     int32_t nsl;                  // slices per row of the final-token passes (kSampleSlice elements each)
     // The slice and locate kernels work on "jobs": one per sequence for verification (jps = 1, job j belongs to
@@ -169,8 +173,26 @@ struct VerifyArgs {
     int32_t bandit_tail;
     BanditArgs bandit;
     const int32_t *b_arm_in, *b_gamma; const uint8_t *b_active; const float *b_u_ts; int32_t *b_arm_out; uint32_t *b_flags;
+    // tapout_round with n_draft from the caller: the accept decisions form log q(tok) and the draft rows' lse themselves
+    // from the draft pass's partials (own_q; dpart [B*K, d_nsplit], whose token slots the draft pass filled), so the
+    // draft epilogue can run beside the locate kernel, in the same launch (B more workgroups, ahead of the others).
+    const Partial *dpart;
 };
-hipError_t launch_verify(const VerifyArgs &a, int pass /*0 head, 1 slices, 2 locate*/, hipStream_t st, Timing tm);
+static_assert(sizeof(VerifyArgs) <= 512, "see the note above the struct");
+// fin: the draft epilogue's arguments when a.own_q is set (pass 2 then runs it too), else NULL.
+hipError_t launch_verify(const VerifyArgs &a, int pass /*0 head, 1 slices, 2 locate*/, hipStream_t st, Timing tm,
+                         const DraftFinalArgs *fin = nullptr);
+// The accept decisions can take log q(tok) from the draft partials themselves (VerifyArgs::own_q) for these shapes.
+inline bool own_q_shape(int K, int nsplit_target, int nsplit_draft)
+{
+    auto fits = [](int rows, int nsplit) {
+        if (nsplit > 16 || rows > 64) return false;
+        int sh = 0;
+        while ((1 << sh) < nsplit) ++sh;
+        return (rows << sh) <= 512;
+    };
+    return fits(K + 1, nsplit_target) && fits(K, nsplit_draft);
+}
 
 // Draft-token sampling (Algorithm 1, the sampling step of the draft loop): one job per live draft row with the
 // row's maximum as exponent reference; bad live rows get token -1 at once.  The slice and locate kernels of

@@ -308,7 +308,7 @@ __device__ inline void stream_pass_body(const RowReduceArgs &a, const int split,
     // see through): a scalar load from memory would hold up the first wait for the kernel arguments and with it
     // the first logits; this one returns with the first batch.
     int tk = -1;
-    if (!FULL && a.tok && k < a.tok_rows) {                 // the target pass only: nothing hands tokens to the draft pass
+    if (a.tok && k < a.tok_rows) {                          // target rows, and draft rows when the caller wants log q(tok) early
         int zero;
         asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
         tk = a.tok[(int64_t)b * a.tok_rows + k + zero];
@@ -402,17 +402,23 @@ __device__ inline void stream_pass_body(const RowReduceArgs &a, const int split,
             // The batch with the slice's first maximum stays out (the epilogue adds its elements back from the
             // logits); the set-apart batches of the other wavefronts are ordinary data.  A NaN or an infinity
             // inside the left-out batch must still poison the sums: x - x is 0 for finite x only.
+            float left_out = 0.0f;
 #pragma unroll
             for (int w = 0; w < kBlock / kWave; ++w) {
                 const bool holds = sh_i[w] == p.cand;
                 p.S += holds ? (sh_f[4][w] - sh_f[4][w]) : sh_f[4][w];
                 p.T += holds ? 0.0f : sh_f[5][w];
+                left_out = holds ? sh_f[4][w] : left_out;
             }
+            // the left-out batch's own sum (same reference): S + this is the slice's sum over every element, to
+            // binary32 precision, for a reader that wants the row's lse before the epilogue has run
+            p.pad[1] = __float_as_int(left_out);
         }
-        p.pad[0] = 0x7fc00000; p.pad[1] = p.pad[2] = 0;
+        p.pad[0] = 0x7fc00000; if constexpr (!FULL) p.pad[1] = 0;
+        p.pad[2] = 0;
         // elements of this slice: [e0, e1); every index of the row lies in exactly one slice
         const int e0 = split == 0 ? 0 : head + v0 * VEC, e1 = split == a.nsplit - 1 ? a.V : head + v1e * VEC;
-        if (!FULL && tk >= e0 && tk < e1) {
+        if (tk >= e0 && tk < e1) {
             // the row's address once more, from scalar registers (the zero is opaque to the compiler): holding the
             // one from the top of the kernel in vector registers through the loop costs the draft pass a wavefront per SIMD
             int zero;

@@ -41,6 +41,7 @@
 // instructions of a correctly rounded exp.
 #include "common.h"
 #include "bandit_device.h"
+#include "finalize_device.h"
 
 namespace tapout {
 
@@ -137,13 +138,90 @@ __device__ inline void load8(const char *rowp, bool aligned, int j, int V, float
     }
 }
 
+// ---- lse and token logit of the draft rows from the draft pass's partials ----------------
+// For accept decisions that do not wait for the draft epilogue.  A draft partial's S leaves out the batch with the
+// slice's first maximum; pad[1] holds that batch's own sum in the same reference, so S + pad[1] is the sum over the
+// whole slice (binary32 precision).  Same lane layout as the lane-parallel merge: thread t takes the partial of
+// (row t >> sh, slice t & (P - 1)) and of the row 256 >> sh further on; the P lanes of a row combine (max, sum) with
+// DPP exchanges (commutative: all lanes of a group end with the same bits) and the first writes the row's entry.
+struct DraftRowLse { double lse; float xt; };     // xt: the logit of the row's token (NaN: the token is out of range)
+
+struct QPiece { float M; double S; float xt; };
+
+template <int CTRL>
+__device__ inline QPiece qpiece_dpp(const QPiece &e)
+{
+    auto mv = [](int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); };
+    QPiece o;
+    o.M = __int_as_float(mv(__float_as_int(e.M)));
+    o.S = __hiloint2double(mv(__double2hiint(e.S)), mv(__double2loint(e.S)));
+    o.xt = __int_as_float(mv(__float_as_int(e.xt)));
+    return o;
+}
+__device__ inline QPiece qpiece_merge(const QPiece &a, const QPiece &b)
+{
+    QPiece o;
+    o.M = fmaxf(a.M, b.M);                                        // slice maxima are never NaN
+    const float Rw = ref_of_max(o.M);
+    const int da = (int)fminf(fmaxf(Rw - ref_of_max(a.M), -4000.0f), 4000.0f), db = (int)fminf(fmaxf(Rw - ref_of_max(b.M), -4000.0f), 4000.0f);
+    o.S = ldexp(a.S, -da) + ldexp(b.S, -db);                      // an empty piece has S = 0 whatever its shift
+    o.xt = (a.xt == a.xt) ? a.xt : b.xt;                          // at most one slice holds the token
+    return o;
+}
+__device__ inline void draft_rows_lse(const Partial *part, int rows, int nsplit, DraftRowLse *out)
+{
+    const int sh = lane_merge_shift(rows, nsplit);                // >= 0: the host offers this path for such shapes only
+    if (sh < 0) return;
+    const int sl = threadIdx.x & ((1 << sh) - 1);
+    float pm[2], ps[2], px[2], ph[2];                             // maximum, sum, token logit, left-out sum: the words wanted
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        pm[q] = -INFINITY; ps[q] = 0.0f; px[q] = NAN; ph[q] = 0.0f;
+        const int row = (threadIdx.x >> sh) + q * (256 >> sh);
+        if (row < rows && sl < nsplit && (q == 0 || (256 >> sh) < rows)) {
+            const Partial *s = part + (int64_t)row * nsplit + sl;
+            pm[q] = s->v1; ps[q] = s->S; px[q] = __int_as_float(s->pad[0]); ph[q] = __int_as_float(s->pad[1]);
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        if (q == 1 && (256 >> sh) >= rows) break;                 // uniform
+        const int row = (threadIdx.x >> sh) + q * (256 >> sh);
+        QPiece e;
+        e.M = -INFINITY; e.S = 0.0; e.xt = NAN;
+        if (row < rows && sl < nsplit) {
+            e.M = pm[q];
+            e.S = (double)ps[q] + (double)ph[q];
+            e.xt = px[q];
+            if (e.M == -INFINITY && !(e.S != e.S)) e.S = 0.0;     // empty slice
+        }
+        if (sh >= 1) e = qpiece_merge(e, qpiece_dpp<0xB1>(e));
+        if (sh >= 2) e = qpiece_merge(e, qpiece_dpp<0x4E>(e));
+        if (sh >= 3) e = qpiece_merge(e, qpiece_dpp<0x141>(e));
+        if (sh >= 4) e = qpiece_merge(e, qpiece_dpp<0x140>(e));
+        if (row < rows && sl == 0) {
+            const bool bad = !(e.S > 0.0) || !(e.S < INFINITY) || !(e.M > -INFINITY && e.M < INFINITY);
+            DraftRowLse o;
+            o.lse = bad ? (double)NAN : ((double)ref_of_max(e.M) + log2(e.S)) * kLn2;
+            o.xt = e.xt;
+            out[row] = o;
+        }
+    }
+}
+
 // ---- head: accept decisions of one sequence -----------------------------------------
 // Called by all threads of a workgroup.  Returns the sequence's job (identical in every
 // workgroup of the sequence); with `writer` also writes the sequence's outputs.
 // Accept decisions exist for rows k < n <= K <= kScanCap, so the LDS byte buffer always holds them.
+//
+// a.own_q (whole-round calls, lane-merge shapes only): log q(tok) and the draft rows' lse are not read from the draft
+// epilogue's outputs, which then need not exist yet, but formed here from the draft pass's partials: the slice sums
+// with their left-out batch's own sum added back (binary32 precision, which a ratio p/q compared with a uniform
+// needs no more than) and the token's logit, which the draft pass left in the partial of the slice that holds it.
 template <bool SHARDED>
 __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
-                                        Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast, double *sh_lse)
+                                        Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast, double *sh_lse,
+                                        DraftRowLse *sh_qrows)
 {
     const int K = a.K;
     // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
@@ -163,12 +241,15 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
     int n = a.n_draft[b + zero];
     uint8_t greedy_raw = a.greedy ? a.greedy[b + zero] : (uint8_t)0;
+    const bool own_q = !SHARDED && a.own_q != 0 && msh >= 0;     // (the host offers own_q for lane-merge shapes only)
     if ((int)threadIdx.x < K) {
         const int64_t i = (int64_t)b * K + threadIdx.x;
         tok0 = a.draft_tok[i];
         u0 = a.u_accept[i];
-        lq0 = a.logq_tok[i];
-        if (a.draft_lse) dl0 = a.draft_lse[i];      // the final token's job wants it for row m: no dependent load later
+        if (!own_q) {
+            lq0 = a.logq_tok[i];
+            if (a.draft_lse) dl0 = a.draft_lse[i];  // the final token's job wants it for row m: no dependent load later
+        }
     }
     if (threadIdx.x == 0) { *sh_flags = 0; sh_bcast[4] = 0; }     // ahead of the staging barrier: rows of other wavefronts OR into the flags
     RowSlot *sh_rows = (RowSlot *)sh_part;
@@ -179,6 +260,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     } else if (msh >= 0) {
         // target partials run over every element of their slice: plain pieces, nothing left out
         const LaneRegs ln = lane_merge_issue(a.part + (int64_t)b * (K + 1) * a.nsplit, K + 1, a.nsplit, msh);
+        if (own_q) draft_rows_lse(a.dpart + (int64_t)b * K * a.d_nsplit, K, a.d_nsplit, sh_qrows);   // published by the barrier below
         lane_merge_commit<false>(sh_rows, lane_piece(ln, 0, K + 1, a.nsplit, msh), lane_piece(ln, 1, K + 1, a.nsplit, msh), K + 1, msh);
     } else {
         stage_partials(sh_part, a.part + (int64_t)b * (K + 1) * a.nsplit, min(K + 1, rows_per_stage) * a.nsplit);
@@ -238,7 +320,11 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 int32_t t = tok0;
                 float u = u0, lq = lq0;
                 last_dl = dl0;
-                if (k != kmine) {                              // more rows than threads: load late
+                if (own_q) {                                   // one row per thread on this path: k == kmine
+                    const double lse_q = sh_qrows[k].lse;
+                    lq = (float)((double)sh_qrows[k].xt - lse_q);
+                    last_dl = (float)lse_q;
+                } else if (k != kmine) {                       // more rows than threads: load late
                     t = a.draft_tok[i]; u = a.u_accept[i]; lq = a.logq_tok[i];
                     if (a.draft_lse) last_dl = a.draft_lse[i];
                 }
@@ -327,7 +413,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         job.kind = m < n ? 1 : 2;
         job.row = m;
         job.ref_p = Mm;                          // exponent references: the target row's maximum, the draft row's lse
-        job.ref_q = (m < n && a.draft_lse) ? dl_m : 0.0f;
+        job.ref_q = (m < n && (a.draft_lse || own_q)) ? dl_m : 0.0f;
         // binary32-grade estimate of S_p / S_q in these references (S_q = sum exp(d - lse_q) = 1): lets the
         // slice pass form the residual before the exact normalisers exist
         job.lam = exp(lse_m - (double)Mm);
@@ -382,7 +468,8 @@ __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
     __shared__ uint32_t sh_flags;
     __shared__ int32_t sh_bcast[8];
     __shared__ double sh_lse;
-    verify_head<SHARDED>(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse);
+    __shared__ DraftRowLse sh_qrows[SHARDED ? 1 : kWave];
+    verify_head<SHARDED>(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse, sh_qrows);
 }
 
 // ---- slice kernel -----------------------------------------------------------------------
@@ -417,7 +504,8 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
         __shared__ uint32_t sh_flags;
         __shared__ int32_t sh_bcast[8];
         __shared__ double sh_lse;
-        job = verify_head<false>(a, b, blockIdx.x == 0, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse);
+        __shared__ DraftRowLse sh_qrows[kWave];
+        job = verify_head<false>(a, b, blockIdx.x == 0, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse, sh_qrows);
     } else {
         job = a.jobs[j].job;
     }
@@ -640,13 +728,23 @@ __device__ __noinline__ double settle_band(const Weights &w, const Rows &r, int 
 // TAIL: the workgroup also ends its sequence's round for the UCB policies (a logarithm and a square root per arm, one
 // thread).  Thompson Sampling is not offered here: its Gamma / Gaussian draws are long double-precision chains that
 // want 178 registers and scratch memory, which this kernel would then pay for at every launch (measured: twice as long).
-template <int TD, int DD, bool TAIL>
-__global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a)
+//
+// FIN (whole-round calls whose accept decisions did not wait for the draft epilogue): the launch carries
+// that epilogue's workgroups too, one per sequence, ahead of the locate workgroups: two latency-bound kernels of a
+// few dozen workgroups each run side by side instead of one after the other.
+template <int TD, int DD, bool TAIL, bool FIN>
+__global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFinalArgs fin)
 {
+    static_assert(kVBlock == kFinalBlock, "the draft epilogue runs in this kernel's workgroups");
+    if constexpr (FIN)
+        if ((int)blockIdx.x < a.B) {
+            draft_finalize_body<false>(fin, blockIdx.x);
+            return;
+        }
     __shared__ double shT[256];
     __shared__ double sh_red[kSliceVals][kVBlock / kWave];
     __shared__ LocateShared shl;
-    const int j = blockIdx.x;                                        // job; its sequence is b
+    const int j = FIN ? blockIdx.x - a.B : blockIdx.x;               // job; its sequence is b
     const int b = j / a.jps;
     const int tid = threadIdx.x;
     // the slice sums, the table and the uniform are requested before the job is looked at (one round trip)
@@ -1046,7 +1144,7 @@ hipError_t launch_shard_dispatch(const ShardFinalArgs &a, int pass, hipStream_t 
 }
 
 template <int TD, int DD>
-hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
+hipError_t launch_typed(const VerifyArgs &a, const DraftFinalArgs &fin, bool with_fin, int pass, hipStream_t st, Timing tm)
 {
     const unsigned gy = a.n_jobs < 65535 ? a.n_jobs : 65535, gz = (a.n_jobs + gy - 1) / gy;
     dim3 grid12((a.nsl + kWavesPerWG - 1) / kWavesPerWG, gy, gz), block(kVBlock);
@@ -1054,8 +1152,12 @@ hipError_t launch_typed(const VerifyArgs &a, int pass, hipStream_t st, Timing tm
         if (a.fused_head) launch_kernel(verify_slices<TD, DD, true>, grid12, block, st, tm, a);
         else launch_kernel(verify_slices<TD, DD, false>, grid12, block, st, tm, a);
     }
-    else if (!a.bandit_tail) launch_kernel(verify_locate<TD, DD, false>, dim3(a.n_jobs), block, st, tm, a);
-    else launch_kernel(verify_locate<TD, DD, true>, dim3(a.n_jobs), block, st, tm, a);
+    else if (with_fin) {
+        if (!a.bandit_tail) launch_kernel(verify_locate<TD, DD, false, true>, dim3(a.n_jobs + a.B), block, st, tm, a, fin);
+        else launch_kernel(verify_locate<TD, DD, true, true>, dim3(a.n_jobs + a.B), block, st, tm, a, fin);
+    }
+    else if (!a.bandit_tail) launch_kernel(verify_locate<TD, DD, false, false>, dim3(a.n_jobs), block, st, tm, a, fin);
+    else launch_kernel(verify_locate<TD, DD, true, false>, dim3(a.n_jobs), block, st, tm, a, fin);
     return hipGetLastError();
 }
 
@@ -1070,8 +1172,13 @@ hipError_t launch_sample_head(const VerifyArgs &a, hipStream_t st, Timing tm)
     return hipGetLastError();
 }
 
-hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing tm)
+hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing tm, const DraftFinalArgs *fin)
 {
+    static const DraftFinalArgs no_fin{};
+    const bool with_fin = fin != nullptr;
+    if ((a.own_q != 0) != with_fin || (fin && (a.jps != 1 || a.n_jobs != a.B || a.shards > 0 || fin->shards > 0 || fin->B != a.B)))
+        return hipErrorInvalidValue;
+    if (!fin) fin = &no_fin;
     if (pass == 0) {
         if (a.fused_head) return hipErrorInvalidValue;       // the slice kernel is the head then
         if (a.shards > 0) launch_kernel(verify_head_kernel<true>, dim3(a.B), dim3(kVBlock), st, tm, a);
@@ -1079,8 +1186,8 @@ hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing t
         return hipGetLastError();
     }
     if (a.t_dtype == TAPOUT_F32)
-        return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_F32, TAPOUT_F32>(a, pass, st, tm) : launch_typed<TAPOUT_F32, TAPOUT_BF16>(a, pass, st, tm);
-    return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_BF16, TAPOUT_F32>(a, pass, st, tm) : launch_typed<TAPOUT_BF16, TAPOUT_BF16>(a, pass, st, tm);
+        return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_F32, TAPOUT_F32>(a, *fin, with_fin, pass, st, tm) : launch_typed<TAPOUT_F32, TAPOUT_BF16>(a, *fin, with_fin, pass, st, tm);
+    return a.d_dtype == TAPOUT_F32 ? launch_typed<TAPOUT_BF16, TAPOUT_F32>(a, *fin, with_fin, pass, st, tm) : launch_typed<TAPOUT_BF16, TAPOUT_BF16>(a, *fin, with_fin, pass, st, tm);
 }
 
 }  // namespace tapout

@@ -255,11 +255,50 @@ def test_rounds_replayed_from_hip_graphs_match_eager_rounds(policy):
         assert (a.view(np.int64) == b.view(np.int64)).all()
 
 
+@pytest.mark.parametrize("name,B,V", [("llama3", 12, None), ("llama3", 70, 9000), ("zipf", 6, None), ("ragged", 9, 70000), ("small", 32, None), ("llama3", 90, None)])
+def test_round_with_the_epilogue_beside_the_locate_kernel(name, B, V):
+    """tapout_round with n_draft from the caller: by default the accept decisions form log q(tok) from the draft pass's
+    slice sums themselves and the draft epilogue runs in the locate kernel's launch.  Against the same call with the
+    epilogue in its own launch ahead of the verification ("defer_epilogue" = 0), on one-launch (equal element sizes)
+    and two-launch (ragged: bf16 draft, f32 target) streaming passes, fused and separate accept decisions, ragged
+    lengths and greedy sequences: the draft outputs and the target statistics carry the same bits (the epilogue and the
+    target merge see the same partials), and so do the decisions: log q(tok) differs by binary32 rounding only, which
+    moves a decision only if its uniform lies within ~1e-6 of p/q (the oracle's own near-tie margin is 1e-5)."""
+    kw = dict(B=B) if V is None else dict(B=B, V=V)
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    gen = synth.RoundGenerator(w, DEV)
+    outs = {}
+    for defer in (1, 0):
+        tp = binding.Tapout(w.B, w.K, w.V)
+        tp.set_option("defer_epilogue", defer)
+        arm = tp.bandit_select(w.B)
+        res = []
+        for r in range(3):
+            rnd = gen.round(r)
+            launch, o = tp.prepare_round_call(rnd, arm, False)
+            launch(torch.cuda.current_stream().cuda_stream)
+            torch.cuda.synchronize()
+            snap = {"arm": arm.cpu().clone()}
+            snap.update({"d_" + k: v.cpu().clone() for k, v in o["draft"].items()})
+            snap.update({"v_" + k: v.cpu().clone() for k, v in o["verify"].items()})
+            res.append(snap)
+        outs[defer] = (res, tp.bandit_get_state(moments=True))
+    for r, (a_, b_) in enumerate(zip(outs[1][0], outs[0][0])):
+        assert a_.keys() == b_.keys()
+        for k in a_:
+            x, y = a_[k], b_[k]
+            if x.dtype == torch.float32:
+                x, y = x.view(torch.int32), y.view(torch.int32)
+            assert torch.equal(x, y), (r, k)
+    for a_, b_ in zip(outs[1][1], outs[0][1]):
+        assert (a_.view(np.int64) == b_.view(np.int64)).all()
+
+
 @pytest.mark.parametrize("policy", [binding.UCB1, binding.TS_BETA])
 @pytest.mark.parametrize("truncate,five", [(False, False), (True, False), (True, True)])
 def test_whole_round_in_one_call_gives_the_bits_of_the_separate_calls(policy, truncate, five):
-    """tapout_round (with n_draft given, its target pass runs on the context's second stream beside the draft pass)
-    against select / draft_stats / verify / update on a second context: every output of every round and the bandit
+    """tapout_round (with n_draft given: draft and target rows in one streaming launch, the draft epilogue beside the
+    locate kernel) against select / draft_stats / verify / update on a second context: every output of every round and the bandit
     state in the end carry the same bits; then the same rounds replayed from HIP graphs, eager work between replays."""
     w = synth.scaled(synth.WORKLOADS["llama3"], B=12, n_arms=5 if five else 3)
     gen = synth.RoundGenerator(w, DEV)
@@ -339,7 +378,7 @@ def test_whole_round_in_one_call_gives_the_bits_of_the_separate_calls(policy, tr
         assert (s1["lam"] == s2["lam"]).all() and (s1["accept_rate"] == s2["accept_rate"]).all()
         assert (s1["prev_entropy"].view(np.int32) == s2["prev_entropy"].view(np.int32)).all()
 
-    # the same from HIP graphs: the fork to the second stream and the join are captured as graph edges
+    # the same from HIP graphs
     tp2, arm2, calls2 = one_call_context()
     graphs = {}
     tp2.bandit_select(w.B, u_ts=u_of(order[0]), arm_out=arm2, stream=stream)

@@ -33,6 +33,7 @@ struct tapout_ctx {
     int min_slice = 4096;         // smallest slice (elements) a row is cut into
     int slice_bytes = 65536;      // slice size aimed for when the rows alone give enough workgroups
     int fuse_head = -1;           // tapout_verify: accept decisions inside the slice kernel (1), in a launch of their own (0), by size (-1)
+    int exp_lookup = 1;           // final token: exponentials of bfloat16 row pairs from the table (1) or computed (0)
     int defer_epilogue = 1;       // tapout_round: the draft epilogue may run beside the final-token locate kernel (1) or keeps its own launch (0)
     // optional kernel timing (tapout_profile_*): event pairs around the launches of selected kernels
     uint32_t prof_mask = 0;
@@ -53,10 +54,11 @@ static __device__ __align__(256) unsigned char scratch[(size_t)TAPOUT_STATIC_MAX
 namespace {
 
 constexpr int kMaxWgsTarget = 1 << 16;
-// "fuse_head" = -1: fuse while the slice kernel's workgroups are all resident at once (five per CU): a second round
-// of workgroups would pay the prologue a second time (measured at V = 128256: fused wins by 1.5-2.5 us up to 1280
-// workgroups and loses by 1-2 us from 1536 on)
-constexpr int kFuseHeadMaxWgs = 1280;
+// "fuse_head" = -1: fuse while the slice kernel's workgroups are all resident at once: a second round of workgroups
+// would pay the prologue a second time (measured at V = 128256 with five workgroups per CU: fused wins by 1.5-2.5 us
+// up to 1280 workgroups and loses by 1-2 us from 1536 on).  Four per CU when a row is bfloat16: the table of
+// exponentials takes 36 KB of LDS per workgroup.
+constexpr int kFuseHeadMaxWgs = 1280, kFuseHeadMaxWgsBf16 = 1024;
 constexpr int kMinSliceBytes = 16384;            // lower limit of the "slice_bytes" option (sizes the partial buffer)
 thread_local char g_create_err[256] = {0};
 
@@ -271,14 +273,24 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     c->nsl_max = (cfg->vocab + kSampleSlice - 1) / kSampleSlice;
     // final-token jobs: one per sequence (verification) or one per draft row (draft-token sampling)
     const size_t njobs = (size_t)cfg->max_batch * (cfg->draft_sampling ? cfg->max_k : 1);
-    double table[256];
+    // 2^(k/256), then exp(x) of every bfloat16 x with 2^-12 <= |x| < 63.75: entry 2 idx + sign, magnitude bits
+    // (115 << 7) + idx; the last pair stands for all larger magnitudes and holds zeros
+    std::vector<double> table(256 + kExpBf16Doubles);
     for (int k = 0; k < 256; ++k) table[k] = std::exp2((double)k / 256.0);
+    for (int idx = 0; idx < kExpBf16Doubles / 2; ++idx) {
+        const uint32_t bits = (uint32_t)((115 << 7) + idx) << 16;
+        float x;
+        memcpy(&x, &bits, sizeof x);
+        const bool last = idx == kExpBf16Doubles / 2 - 1;
+        table[256 + 2 * idx] = last ? 0.0 : std::exp((double)x);
+        table[256 + 2 * idx + 1] = last ? 0.0 : std::exp(-(double)x);
+    }
     bool ok = hipMalloc(&c->part, c->part_cap * sizeof(Partial)) == hipSuccess
            && hipMalloc(&c->part_t, c->part_cap * sizeof(Partial)) == hipSuccess
            && hipMalloc(&c->part1, njobs * c->nsl_max * 5 * sizeof(double)) == hipSuccess
            && hipMalloc(&c->part2, njobs * c->nsl_max * sizeof(double)) == hipSuccess
-           && hipMalloc(&c->exp_table, sizeof table) == hipSuccess
-           && hipMemcpy(c->exp_table, table, sizeof table, hipMemcpyHostToDevice) == hipSuccess
+           && hipMalloc(&c->exp_table, table.size() * sizeof(double)) == hipSuccess
+           && hipMemcpy(c->exp_table, table.data(), table.size() * sizeof(double), hipMemcpyHostToDevice) == hipSuccess
            && hipMalloc(&c->jobs, njobs * sizeof(JobRecord)) == hipSuccess
            && hipMalloc(&c->flags_ws, (size_t)cfg->max_batch * sizeof(uint32_t)) == hipSuccess
            && hipMalloc(&c->sum_r, nstate * sizeof(double)) == hipSuccess
@@ -345,6 +357,9 @@ tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value
     } else if (!strcmp(name, "fuse_head")) {
         if (value < -1 || value > 1) return fail(ctx, TAPOUT_EINVAL, "fuse_head outside {-1, 0, 1}");
         ctx->fuse_head = value;
+    } else if (!strcmp(name, "exp_lookup")) {
+        if (value < 0 || value > 1) return fail(ctx, TAPOUT_EINVAL, "exp_lookup outside {0, 1}");
+        ctx->exp_lookup = value;
     } else if (!strcmp(name, "defer_epilogue")) {
         if (value < 0 || value > 1) return fail(ctx, TAPOUT_EINVAL, "defer_epilogue outside {0, 1}");
         ctx->defer_epilogue = value;
@@ -452,6 +467,7 @@ tapout_status draft_stats_impl(tapout_ctx *ctx, const tapout_logits *draft,
         va.part = ctx->part; va.n_draft = k_len; va.u_sample = u_draft; va.tok_direct = sampled_tok;
         va.flags_ws = ctx->flags_ws; va.jobs = ctx->jobs;
         va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
+        if (!ctx->exp_lookup) va.vflags |= kVerifyNoExpTable;
         e = timed(ctx, TAPOUT_PROFILE_SAMPLE_HEAD, [&](Timing tm) { return launch_sample_head(va, st, tm); });
         for (int pass = 1; pass <= 2 && e == hipSuccess; ++pass)
             e = timed(ctx, TAPOUT_PROFILE_SAMPLE_SLICES + pass - 1, [&](Timing tm) { return launch_verify(va, pass, st, tm); });
@@ -635,6 +651,7 @@ tapout_status tapout_verify_accept_sharded(tapout_ctx *ctx, const tapout_shard_s
     va.draft_lse = draft_lse; va.final_jobs = (SampleJob *)final_jobs;
     va.accept_len = accept_len; va.out_tok = out_tok; va.n_out = n_out;
     va.target_lse = target_lse; va.logp_tok = logp_tok; va.target_top1 = target_top1; va.flags = flags;
+    va.exp_table = ctx->exp_table;                  // the accept decisions' exponentials
     hipError_t e = timed(ctx, TAPOUT_PROFILE_VERIFY_HEAD, [&](Timing tm) { return launch_verify(va, 0, st, tm); });
     return e == hipSuccess ? TAPOUT_OK : hip_fail(ctx, e, "sharded verify head launch");
 }
@@ -658,6 +675,7 @@ tapout_status shard_final_args(tapout_ctx *ctx, const tapout_logits *target_shar
     va.B = B; va.K = K; va.V = Vs; va.nsl = (Vs + kSampleSlice - 1) / kSampleSlice;
     va.jps = 1; va.n_jobs = B;
     va.jobs = ctx->jobs; va.part1 = ctx->part1; va.part2 = ctx->part2; va.exp_table = ctx->exp_table;
+    if (!ctx->exp_lookup) va.vflags |= kVerifyNoExpTable;
     a.jobs_in = (const SampleJob *)jobs;
     *out = a;
     return TAPOUT_OK;
@@ -732,7 +750,8 @@ tapout_status verify_check(tapout_ctx *ctx, VerifyCall &c)
     // arithmetic and the repeated head would add to it: separate launch.
     c.nsl = (c.V + kSampleSlice - 1) / kSampleSlice;
     const int64_t slice_wgs = (int64_t)c.B * ((c.nsl + 3) / 4);
-    c.fused = ctx->fuse_head < 0 ? slice_wgs <= kFuseHeadMaxWgs : ctx->fuse_head == 1;
+    const bool any_bf16 = c.target->dtype == TAPOUT_BF16 || c.draft->dtype == TAPOUT_BF16;
+    c.fused = ctx->fuse_head < 0 ? slice_wgs <= (any_bf16 ? kFuseHeadMaxWgsBf16 : kFuseHeadMaxWgs) : ctx->fuse_head == 1;
     return TAPOUT_OK;
 }
 
@@ -768,7 +787,8 @@ hipError_t verify_rest(tapout_ctx *ctx, const VerifyCall &c, hipStream_t st, con
                        const DraftFinalArgs *fin = nullptr, int fin_nsplit = 0)
 {
     VerifyArgs va{};
-    if (fin) { va.own_q = 1; va.d_nsplit = fin_nsplit; va.dpart = fin->part; }
+    if (fin) { va.vflags |= kVerifyOwnQ; va.d_nsplit = fin_nsplit; va.dpart = fin->part; }
+    if (!ctx->exp_lookup) va.vflags |= kVerifyNoExpTable;
     if (tail) {
         va.bandit_tail = 1;
         va.bandit = bandit_args(ctx, c.B);

@@ -49,6 +49,8 @@ struct SampleJob {
 
 static_assert(sizeof(tapout_final_job) == sizeof(SampleJob), "the public job record is the internal one");
 
+constexpr int kExpBf16Doubles = 4608;   // exp(x) of the bfloat16 values with 2^-12 <= |x| < 63.75, both signs (see the final-token slice kernel)
+
 constexpr int kBandCap = 32;         // band elements per job the locate kernel settles one by one; more: exact slow path
 
 // The job as it lies in memory, together with the list of elements of its row pair whose sign of a - L b is
@@ -141,11 +143,13 @@ struct BanditArgs {
 // Verification + final token: the head kernel merges the target partials of each sequence, takes the
 // accept decisions and describes the final-token draw (SampleJob); the slice kernel sums the row pair
 // per slice; the locate kernel finds the token.
+constexpr int32_t kVerifyOwnQ = 1;          // accept decisions form log q(tok) from the draft partials (see dpart)
+constexpr int32_t kVerifyNoExpTable = 2;    // final-token slice kernel: computed exponentials also for bfloat16 row pairs
 // (Kept at 512 bytes or less: past that the compiler reaches the arguments differently and the fused slice kernel
-// takes 107 vector registers instead of 95, one wavefront per SIMD fewer.  own_q and d_nsplit sit in what would be
+// takes 107 vector registers instead of 95, one wavefront per SIMD fewer.  vflags and d_nsplit sit in what would be
 // alignment padding.)
 struct VerifyArgs {
-    const void *tbase; int32_t t_dtype; int32_t own_q; int64_t t_stride_b, t_stride_k;
+    const void *tbase; int32_t t_dtype; int32_t vflags; int64_t t_stride_b, t_stride_k;   // vflags: kVerify* bits
     const void *dbase; int32_t d_dtype; int32_t d_nsplit; int64_t d_stride_b, d_stride_k;
     int32_t B, K, V, nsplit;      // nsplit: slices per row of the streaming pass
     int32_t nsl;                  // slices per row of the final-token passes (kSampleSlice elements each)
@@ -166,7 +170,7 @@ struct VerifyArgs {
     JobRecord *jobs;              // [jobs]
     double *part1;                // [jobs, nsl, 5]  A, B, R~, D, U of each slice
     double *part2;                // [B, nsl]     exact weight of each slice (slow path)
-    const double *exp_table;      // 2^(k/256), k = 0..255
+    const double *exp_table;      // 2^(k/256), k = 0..255, then the kExpBf16Doubles entries of the bfloat16 table
     // tapout_round (jps = 1): the locate kernel also ends the round of its sequence: reward into the sequence's bandit
     // (arm b_arm_in[b], accept_len, n_draft, b_gamma, b_active as tapout_bandit_update) and the arm of the next round
     // (b_arm_out, b_flags as tapout_bandit_select).  Sequence-level UCB bandits, one per sequence.
@@ -174,15 +178,15 @@ struct VerifyArgs {
     BanditArgs bandit;
     const int32_t *b_arm_in, *b_gamma; const uint8_t *b_active; const float *b_u_ts; int32_t *b_arm_out; uint32_t *b_flags;
     // tapout_round with n_draft from the caller: the accept decisions form log q(tok) and the draft rows' lse themselves
-    // from the draft pass's partials (own_q; dpart [B*K, d_nsplit], whose token slots the draft pass filled), so the
+    // from the draft pass's partials (kVerifyOwnQ; dpart [B*K, d_nsplit], whose token slots the draft pass filled), so the
     // draft epilogue can run beside the locate kernel, in the same launch (B more workgroups, ahead of the others).
     const Partial *dpart;
 };
 static_assert(sizeof(VerifyArgs) <= 512, "see the note above the struct");
-// fin: the draft epilogue's arguments when a.own_q is set (pass 2 then runs it too), else NULL.
+// fin: the draft epilogue's arguments when kVerifyOwnQ is set (pass 2 then runs it too), else NULL.
 hipError_t launch_verify(const VerifyArgs &a, int pass /*0 head, 1 slices, 2 locate*/, hipStream_t st, Timing tm,
                          const DraftFinalArgs *fin = nullptr);
-// The accept decisions can take log q(tok) from the draft partials themselves (VerifyArgs::own_q) for these shapes.
+// The accept decisions can take log q(tok) from the draft partials themselves (kVerifyOwnQ) for these shapes.
 inline bool own_q_shape(int K, int nsplit_target, int nsplit_draft)
 {
     auto fits = [](int rows, int nsplit) {

@@ -80,6 +80,18 @@ __device__ inline double exp_fast(float x, double neg_ref_c, float lo, const dou
     return __hiloint2double(hi, __double2loint(e));
 }
 
+// exp(x) for a double argument (not NaN; clamped to [-700, 700]), same table and polynomial: relative error < 2e-13.
+__device__ inline double exp_fast_d(double x, const double *T)
+{
+    const double t = fmin(fmax(x, -700.0), 700.0) * kExpC;
+    const double tm = t + kMagic;
+    const int ni = __double2loint(tm);
+    const double rs = t - (tm - kMagic);
+    const double q = rs * fma(rs, fma(rs, kExpC3, kExpC2), kExpC1);
+    const double tk = T[ni & 255];
+    return ldexp(fma(tk, q, tk), ni >> 8);
+}
+
 struct ExpRef {
     double neg_ref_c; float lo;
     __device__ inline void set(double ref) { neg_ref_c = -ref * kExpC; lo = (float)(ref - 700.0); }
@@ -172,12 +184,14 @@ __device__ inline void draft_rows_lse(const Partial *part, int rows, int nsplit,
 {
     const int sh = lane_merge_shift(rows, nsplit);                // >= 0: the host offers this path for such shapes only
     if (sh < 0) return;
-    const int sl = threadIdx.x & ((1 << sh) - 1);
+    // when they fit, on the upper two wavefronts: the lower two merge the target rows meanwhile
+    const int tid = (rows << sh) <= 128 ? (int)threadIdx.x - 128 : (int)threadIdx.x;
+    const int sl = tid & ((1 << sh) - 1);
     float pm[2], ps[2], px[2], ph[2];                             // maximum, sum, token logit, left-out sum: the words wanted
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         pm[q] = -INFINITY; ps[q] = 0.0f; px[q] = NAN; ph[q] = 0.0f;
-        const int row = (threadIdx.x >> sh) + q * (256 >> sh);
+        const int row = tid < 0 ? rows : (tid >> sh) + q * (256 >> sh);        // rows: none
         if (row < rows && sl < nsplit && (q == 0 || (256 >> sh) < rows)) {
             const Partial *s = part + (int64_t)row * nsplit + sl;
             pm[q] = s->v1; ps[q] = s->S; px[q] = __int_as_float(s->pad[0]); ph[q] = __int_as_float(s->pad[1]);
@@ -186,7 +200,7 @@ __device__ inline void draft_rows_lse(const Partial *part, int rows, int nsplit,
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         if (q == 1 && (256 >> sh) >= rows) break;                 // uniform
-        const int row = (threadIdx.x >> sh) + q * (256 >> sh);
+        const int row = tid < 0 ? rows : (tid >> sh) + q * (256 >> sh);
         QPiece e;
         e.M = -INFINITY; e.S = 0.0; e.xt = NAN;
         if (row < rows && sl < nsplit) {
@@ -209,19 +223,62 @@ __device__ inline void draft_rows_lse(const Partial *part, int rows, int nsplit,
     }
 }
 
+// The same eight elements as they lie in memory (one 16-byte vector of bfloat16, two of binary32), so that a kernel
+// can hold several requests in flight in few registers and widen them when their turn comes.
+template <int DT> struct Raw8 { u32x4 w[DT == TAPOUT_F32 ? 2 : 1]; };
+template <int DT>
+__device__ inline Raw8<DT> load_raw8(const char *rowp, bool aligned, int j, int V)
+{
+    Raw8<DT> r;
+    if (aligned && j + kPer <= V) {
+        if constexpr (DT == TAPOUT_BF16) {
+            r.w[0] = *(const u32x4 *)(rowp + (int64_t)j * 2);
+        } else {
+            r.w[0] = *(const u32x4 *)(rowp + (int64_t)j * 4); r.w[1] = *(const u32x4 *)(rowp + (int64_t)j * 4 + 16);
+        }
+    } else {
+        uint32_t e[kPer];
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) e[i] = __float_as_uint((j + i < V) ? load_elem<DT>(rowp, j + i) : -INFINITY);
+        if constexpr (DT == TAPOUT_BF16) {
+            r.w[0] = u32x4{(e[0] >> 16) | (e[1] & 0xffff0000u), (e[2] >> 16) | (e[3] & 0xffff0000u),
+                           (e[4] >> 16) | (e[5] & 0xffff0000u), (e[6] >> 16) | (e[7] & 0xffff0000u)};
+        } else {
+            r.w[0] = u32x4{e[0], e[1], e[2], e[3]}; r.w[1] = u32x4{e[4], e[5], e[6], e[7]};
+        }
+    }
+    return r;
+}
+template <int DT>
+__device__ inline void widen8(const Raw8<DT> &r, float (&x)[kPer])
+{
+    if constexpr (DT == TAPOUT_BF16) {
+        unpack<TAPOUT_BF16>(r.w[0], x);
+    } else {
+        float lo[4], hi[4];
+        unpack<TAPOUT_F32>(r.w[0], lo); unpack<TAPOUT_F32>(r.w[1], hi);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { x[i] = lo[i]; x[4 + i] = hi[i]; }
+    }
+}
+
 // ---- head: accept decisions of one sequence -----------------------------------------
 // Called by all threads of a workgroup.  Returns the sequence's job (identical in every
 // workgroup of the sequence); with `writer` also writes the sequence's outputs.
 // Accept decisions exist for rows k < n <= K <= kScanCap, so the LDS byte buffer always holds them.
 //
-// a.own_q (whole-round calls, lane-merge shapes only): log q(tok) and the draft rows' lse are not read from the draft
+// kVerifyOwnQ (whole-round calls, lane-merge shapes only): log q(tok) and the draft rows' lse are not read from the draft
 // epilogue's outputs, which then need not exist yet, but formed here from the draft pass's partials: the slice sums
 // with their left-out batch's own sum added back (binary32 precision, which a ratio p/q compared with a uniform
 // needs no more than) and the token's logit, which the draft pass left in the partial of the slice that holds it.
+//
+// shT: the 256-entry table of exp_fast in LDS, stored by the caller before the call (the first barrier in here
+// publishes it): the two exponentials on this kernel's critical path take 13 instructions each instead of a call
+// into the device library.
 template <bool SHARDED>
 __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                                         Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast, double *sh_lse,
-                                        DraftRowLse *sh_qrows)
+                                        DraftRowLse *sh_qrows, const double *shT)
 {
     const int K = a.K;
     // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
@@ -241,7 +298,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
     int n = a.n_draft[b + zero];
     uint8_t greedy_raw = a.greedy ? a.greedy[b + zero] : (uint8_t)0;
-    const bool own_q = !SHARDED && a.own_q != 0 && msh >= 0;     // (the host offers own_q for lane-merge shapes only)
+    const bool own_q = !SHARDED && (a.vflags & kVerifyOwnQ) != 0 && msh >= 0;     // (the host offers own_q for lane-merge shapes only)
     if ((int)threadIdx.x < K) {
         const int64_t i = (int64_t)b * K + threadIdx.x;
         tok0 = a.draft_tok[i];
@@ -309,12 +366,9 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
             double lse_d = NAN;
             if (r.bad) f |= TAPOUT_FLAG_BAD_ROW;
             else lse_d = (r.R + log2(r.S)) * kLn2;
+            // greedy sequences decide on the argmax; the others only report it: they look at the window last
             if constexpr (!SHARDED)
-                if (need_top1) top1 = argmax_finish(probe, row, a.t_dtype, a.V, r.cand, r.M);
-            if (writer) {
-                if (a.target_lse) a.target_lse[it] = (float)lse_d;
-                if (a.target_top1) a.target_top1[it] = top1;
-            }
+                if (greedy) top1 = argmax_finish(probe, row, a.t_dtype, a.V, r.cand, r.M);
             if (k < n) {
                 const int64_t i = (int64_t)b * K + k;
                 int32_t t = tok0;
@@ -342,11 +396,20 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 else if (!r.bad) {
                     lp = (float)((double)xt - lse_d);
                     if (greedy) acc = (t == top1);
-                    else acc = (double)u < exp((double)lp - (double)lq);
+                    else {
+                        const double arg = (double)lp - (double)lq;
+                        acc = arg == arg && (double)u < exp_fast_d(arg, shT);
+                    }
                 }
                 if (writer && a.logp_tok) a.logp_tok[i] = lp;
                 acc_mine = acc;
                 if (msh < 0) sh_dec[k] = acc ? 1 : 0;
+            }
+            if constexpr (!SHARDED)
+                if (need_top1 && !greedy) top1 = argmax_finish(probe, row, a.t_dtype, a.V, r.cand, r.M);
+            if (writer) {
+                if (a.target_lse) a.target_lse[it] = (float)lse_d;
+                if (a.target_top1) a.target_top1[it] = top1;
             }
             last_k = k; last_M = r.M; last_top1 = top1; last_lse = lse_d;
             f_mine = f;
@@ -416,7 +479,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         job.ref_q = (m < n && (a.draft_lse || own_q)) ? dl_m : 0.0f;
         // binary32-grade estimate of S_p / S_q in these references (S_q = sum exp(d - lse_q) = 1): lets the
         // slice pass form the residual before the exact normalisers exist
-        job.lam = exp(lse_m - (double)Mm);
+        job.lam = exp_fast_d(lse_m - (double)Mm, shT);
     }
     if (writer) {
         const int32_t final_tok = (flagged || greedy) ? top1m : -1;   // sampled sequences: written by pass 3
@@ -436,7 +499,8 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         }
         int32_t *o = a.out_tok + (int64_t)b * (K + 1);
         for (int k = threadIdx.x; k <= K; k += blockDim.x) {
-            o[k] = k < m ? a.draft_tok[(int64_t)b * K + k] : (k == m ? final_tok : -1);
+            // (lane-merge path: thread k still holds row k's token from the first round trip)
+            o[k] = k < m ? ((msh >= 0 && k == (int)threadIdx.x) ? tok0 : a.draft_tok[(int64_t)b * K + k]) : (k == m ? final_tok : -1);
             if (flagged && a.logp_tok && k < n) a.logp_tok[(int64_t)b * K + k] = NAN;
         }
     }
@@ -469,7 +533,10 @@ __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
     __shared__ int32_t sh_bcast[8];
     __shared__ double sh_lse;
     __shared__ DraftRowLse sh_qrows[SHARDED ? 1 : kWave];
-    verify_head<SHARDED>(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse, sh_qrows);
+    __shared__ double shT[256];
+    static_assert(kVBlock == 256, "one table entry per thread");
+    shT[threadIdx.x] = a.exp_table[threadIdx.x];
+    verify_head<SHARDED>(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse, sh_qrows, shT);
 }
 
 // ---- slice kernel -----------------------------------------------------------------------
@@ -485,27 +552,136 @@ constexpr int kChunks = kSampleSlice / (kWave * kPer);          // a wavefront t
 // first chunk the memory latency hides behind the double-precision work; its five sums need no LDS and no
 // barrier.  (One slice per workgroup with all loads up front was latency bound: job record, then rows, then
 // arithmetic, 8.7 us per workgroup with at most eight of them per compute unit.)
-template <int TD, int DD, bool FUSED>
-__global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
+// ---- exponentials of bfloat16 logits from a table -----------------------------------------
+// A bfloat16 logit has 2^16 possible values, and those between 2^-12 and 2^6 in magnitude (all a softmax row holds
+// besides masked entries and the odd tiny one) are 2 * 2303 of them: exp(x) itself, correctly rounded on the host,
+// comes from a table of 36 KB in LDS with five integer instructions and one LDS read instead of the thirteen
+// instructions of exp_fast.  The row's exponent reference is applied once per slice, to the sums:
+//   a_j = exp(t_j - ref_p) = E[t_j] c_t,  b_j = exp(d_j - ref_q) = E[d_j] c_d,   c_t = exp(-ref_p), c_d = exp(-ref_q)
+//   a_j - L~ b_j = c_t (E[t_j] - L' E[d_j]),  L' = L~ c_d / c_t
+// so the slice kernel sums E[t], E[d], max(0, E[t] - L' E[d]), ... and scales A, R~ by c_t and B, D, U by c_d at the
+// end.  A row of another element type keeps exp_fast and c = 1.
+// Entry idx (0 .. kTabN - 1) is the magnitude with bfloat16 bits (kTabLo32 >> 16) + idx; entry kTabN stands for
+// every magnitude from 63.75 up (and NaN): 0 for either sign.  That is exact for -inf (a masked entry) and an error
+// below e^-49 of the row's largest term for any other logit <= -63.75 given the condition on the references that
+// tab_job_ok checks (row maxima in [-14, 63)); a job outside it takes the computed exponentials.  Magnitudes below
+// 2^-12 (and zeros) are not in the table: the slice kernel notices them per chunk and forms that chunk again with
+// tab_exp_any, which evaluates 1 + x + x^2/2 + x^3/6 for them (error < 2e-16).  Layout: T[2 idx + sign].
+constexpr int kTabN = 18 * 128 - 1;
+constexpr uint32_t kTabLo32 = (uint32_t)(127 - 12) << 23;            // binary32 bits of 2^-12
+constexpr int kTabDoubles = 2 * (kTabN + 1);                         // 4608 doubles = 36,864 bytes
+constexpr int kTabVecs = kTabDoubles / 2;                            // 16-byte vectors
+static_assert(kTabVecs % kVBlock == 0, "the table is copied to LDS in whole rounds of the workgroup");
+static_assert(kTabDoubles == kExpBf16Doubles, "the host builds the table");
+
+// x: a bfloat16 value widened to binary32 (low 16 bits zero).  *tiny gets the lanes whose magnitude lies below
+// the table (their result here is 0 and must be replaced).
+__device__ inline double tab_lookup(float x, const double *T, uint64_t *tiny)
 {
+    const uint32_t u = __float_as_uint(x);
+    const uint32_t d2 = (u << 1) - 2u * kTabLo32;                   // (magnitude bits - kTabLo32) << 1; wraps for tiny magnitudes
+    *tiny |= __builtin_amdgcn_ballot_w64(d2 >= 0u - 2u * kTabLo32);
+    const uint32_t idx16 = min(d2, (uint32_t)kTabN << 17) >> 13;    // byte offset of the entry pair: 16 * idx
+    const uint32_t off = idx16 | ((u >> 28) & 8u);                  // + 8 for negative x
+    return *(const double *)((const char *)T + off);
+}
+// Any binary32-widened bfloat16 value, with the same bits as tab_lookup wherever that one applies.
+__device__ inline double tab_exp_any(float x, const double *T)
+{
+    const uint32_t u = __float_as_uint(x);
+    if ((u << 1) < 2u * kTabLo32) {
+        const double t = (double)x;
+        return fma(t, fma(t, fma(t, 1.0 / 6.0, 0.5), 1.0), 1.0);
+    }
+    uint64_t unused = 0;
+    return tab_lookup(x, T, &unused);
+}
+__device__ inline bool tab_job_ok(const SampleJob &job)
+{
+    // ref_p: the target row's maximum; ref_q: the draft row's lse, at most ln V above its maximum
+    return job.ref_p >= -14.0f && job.ref_p < 63.0f && (job.kind != 1 || (job.ref_q >= 0.0f && job.ref_q < 63.0f));
+}
+// Scales of a job's two rows (see above); identical code, hence identical bits, in the slice and the locate kernel.
+struct TabScale { double ct, cd, Lp; };
+__device__ inline TabScale tab_scale(const SampleJob &job, bool tab_t, bool tab_d, const double *shT)
+{
+    TabScale o;
+    const double st = tab_t ? -(double)job.ref_p : 0.0, sd = tab_d ? -(double)job.ref_q : 0.0;
+    o.ct = tab_t ? exp_fast_d(st, shT) : 1.0;
+    o.cd = tab_d ? exp_fast_d(sd, shT) : 1.0;
+    o.Lp = (tab_t || tab_d) ? job.lam * exp_fast_d(sd - st, shT) : job.lam;
+    return o;
+}
+
+// Adds the sums of one chunk (8 elements per lane) of a row pair to cA .. cDs.  TABT / TABD: that row's exponentials come from the
+// table; SLOW: through tab_exp_any (chunks with tiny magnitudes).
+template <bool TABT, bool TABD, bool SLOW>
+__device__ inline void chunk_pair(const float (&ct)[kPer], const float (&cd)[kPer], const ExpRef &rp, const ExpRef &rq,
+                                  const double *shT, const double *shE, double c2, float top, double Lp, double band,
+                                  double &cA, double &cB, double &cR, double &cDs, uint64_t &any_band, uint64_t &any_tiny)
+{
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        double av, bv;
+        if constexpr (!TABT) av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
+        else if constexpr (SLOW) av = tab_exp_any(ct[i], shE);
+        else av = tab_lookup(ct[i], shE, &any_tiny);
+        if constexpr (!TABD) bv = exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT, c2, top);
+        else if constexpr (SLOW) bv = tab_exp_any(cd[i], shE);
+        else bv = tab_lookup(cd[i], shE, &any_tiny);
+        const double diff = fma(-Lp, bv, av);
+        cA += av;
+        cB += bv;
+        cR += fmax(diff, 0.0);
+        cDs += copysign(bv, diff);
+        // band test: the comparison's lane mask is ORed up over the chunk in scalar registers; one branch
+        // per chunk instead of one per element (a branch on a fresh vector comparison stalls the wavefront)
+        any_band |= __builtin_amdgcn_ballot_w64(fabs(diff) < band * bv);      // strict: an entry with b = 0 (masked, beyond V) is no band element
+    }
+}
+
+template <int TD, int DD, bool FUSED>
+__global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) void verify_slices(VerifyArgs a)
+{
+    // The table serves row pairs of bfloat16 only: with one row computed and one looked up the compiler's schedule
+    // of the mixed loop wants 160-170 registers (two wavefronts per SIMD).
+    constexpr bool kTabT = TD == TAPOUT_BF16 && DD == TAPOUT_BF16, kTabD = kTabT;
+    // LDS: the accept decisions' buffers (FUSED) are dead once the job is known; the table takes their place
+    constexpr size_t kHeadBytes = sizeof(Partial) * kStageCap + sizeof(DraftRowLse) * kWave + 8 + 32 + 8 + kScanCap;
+    constexpr size_t kTabBytes = (kTabT || kTabD) ? sizeof(double) * kTabDoubles : 0;
+    constexpr size_t kRaw = (FUSED && kHeadBytes > kTabBytes) ? kHeadBytes : (kTabBytes > 0 ? kTabBytes : 16);
     __shared__ double shT[256];
+    __shared__ __align__(16) unsigned char sh_raw[kRaw];
     const int j = blockIdx.z * gridDim.y + blockIdx.y;
     if (j >= a.n_jobs) return;
     const int b = j / a.jps;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
     const int s = blockIdx.x * kWavesPerWG + wave;
+    // The tables are requested first of all: nothing of them depends on the job, and a wavefront's loads return in
+    // order, so requested after the rows they would hold the barrier below until the whole slice has arrived.
+    static_assert(kVBlock == 256, "one entry of the small table per thread");
+    constexpr int kRounds = (kTabT || kTabD) ? kTabVecs / kVBlock : 1;
+    u32x4 tw[kRounds];
+    const double tv = a.exp_table[threadIdx.x];
+    if constexpr (kTabT || kTabD) {
+        const u32x4 *src = (const u32x4 *)(a.exp_table + 256);
+#pragma unroll
+        for (int q = 0; q < kRounds; ++q) tw[q] = src[q * kVBlock + threadIdx.x];
+    }
+    shT[threadIdx.x] = tv;          // before the accept decisions, which use it (behind their first barrier)
     SampleJob job;
     if constexpr (FUSED) {
         // Small batches: a head launch of its own costs more (launch, hand-over of the job record through
         // memory) than taking the accept decisions again in each of the sequence's workgroups.  All of them run
         // the same code on the same inputs and reach the same job; the first one writes the sequence's outputs.
-        __shared__ Partial sh_part[kStageCap];
-        __shared__ uint8_t sh_dec[kScanCap];
-        __shared__ uint32_t sh_flags;
-        __shared__ int32_t sh_bcast[8];
-        __shared__ double sh_lse;
-        __shared__ DraftRowLse sh_qrows[kWave];
-        job = verify_head<false>(a, b, blockIdx.x == 0, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse, sh_qrows);
+        unsigned char *q = sh_raw;
+        Partial *sh_part = (Partial *)q;            q += sizeof(Partial) * kStageCap;
+        DraftRowLse *sh_qrows = (DraftRowLse *)q;   q += sizeof(DraftRowLse) * kWave;
+        double *sh_lse = (double *)q;               q += 8;
+        int32_t *sh_bcast = (int32_t *)q;           q += 32;
+        uint32_t *sh_flags = (uint32_t *)q;         q += 8;
+        uint8_t *sh_dec = q;
+        job = verify_head<false>(a, b, blockIdx.x == 0, sh_part, sh_dec, sh_flags, sh_bcast, sh_lse, sh_qrows, shT);
     } else {
         job = a.jobs[j].job;
     }
@@ -514,17 +690,63 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
     const bool live = s < a.nsl;
     const bool resid = job.kind == 1;
     const int base = s * kSampleSlice + lane * kPer;
-    float ct[kPer], cd[kPer];
-    if (live) {
-        load8<TD>(r.trow, r.t_al, base, a.V, ct);
-        if (resid) load8<DD>(r.drow, r.d_al, base, a.V, cd);
+    // The wavefront's requests run kAhead chunks ahead of its arithmetic.  With one chunk ahead the kernel was bound by
+    // memory latency, not by arithmetic: 2 KB in flight per wavefront, 8 MB over the chip, is 2.5 TB/s at 3 us.
+    // bfloat16 pairs request the whole slice at once (32 registers), others two chunks ahead.
+    constexpr int kAhead = (TD == TAPOUT_BF16 && DD == TAPOUT_BF16) ? kChunks : 2;
+    // whole workgroup, uniform: which rows take their exponentials from the table
+    const bool tab_ok = (kTabT || kTabD) && !(a.vflags & kVerifyNoExpTable) && tab_job_ok(job);
+    const bool tab_t = kTabT && tab_ok, tab_d = kTabD && tab_ok && resid;
+    const double *shE = (const double *)sh_raw;
+    // the table into LDS before the rows are requested: the wait for it then has nothing younger behind it
+    if constexpr (kTabT || kTabD) {
+        if constexpr (FUSED) __syncthreads();                    // every thread is done with the accept decisions' LDS
+        if (tab_t || tab_d) {
+#pragma unroll
+            for (int q = 0; q < kRounds; ++q) ((u32x4 *)sh_raw)[q * kVBlock + threadIdx.x] = tw[q];
+        }
     }
-    for (int i = threadIdx.x; i < 256; i += kVBlock) shT[i] = a.exp_table[i];
+    Raw8<TD> qt[kChunks];
+    Raw8<DD> qd[kChunks];
+    // A slice that lies wholly inside aligned rows (all but a row's last one) is requested in straight-line code:
+    // the per-request checks of the general path are branches, and across branches the compiler waits for every
+    // outstanding request where the first chunk's would do.
+    const bool whole = live && r.t_al && (r.d_al || !resid) && (s + 1) * kSampleSlice <= a.V;       // wavefront-uniform
+    if (whole) {
+        const char *tp = r.trow + (int64_t)base * Elem<TD>::size;
+        const char *dp = r.drow + (int64_t)base * Elem<DD>::size;
+#pragma unroll
+        for (int c = 0; c < kChunks; ++c) {
+            qt[c] = Raw8<TD>{}; qd[c] = Raw8<DD>{};
+            if (c < kAhead) {
+#pragma unroll
+                for (int h = 0; h < (TD == TAPOUT_F32 ? 2 : 1); ++h)
+                    qt[c].w[h] = *(const u32x4 *)(tp + (int64_t)c * kWave * kPer * Elem<TD>::size + 16 * h);
+            }
+        }
+        if (resid) {
+#pragma unroll
+            for (int c = 0; c < kAhead; ++c)
+#pragma unroll
+                for (int h = 0; h < (DD == TAPOUT_F32 ? 2 : 1); ++h)
+                    qd[c].w[h] = *(const u32x4 *)(dp + (int64_t)c * kWave * kPer * Elem<DD>::size + 16 * h);
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < kChunks; ++c) {
+            qt[c] = Raw8<TD>{}; qd[c] = Raw8<DD>{};
+            if (c < kAhead && live) {
+                qt[c] = load_raw8<TD>(r.trow, r.t_al, base + c * kWave * kPer, a.V);
+                if (resid) qd[c] = load_raw8<DD>(r.drow, r.d_al, base + c * kWave * kPer, a.V);
+            }
+        }
+    }
     __syncthreads();
     if (!live) return;
     ExpRef rp, rq;
     rp.set((double)job.ref_p); rq.set((double)job.ref_q);
-    const double lam = job.lam, band = kEta * job.lam;
+    const TabScale sc = tab_scale(job, tab_t, tab_d, shT);
+    const double lam = sc.Lp, band = kEta * sc.Lp;
     double c2 = kExpC2;
     float top = INFINITY;
     asm volatile("" : "+v"(c2), "+v"(top));               // stay in vector registers through the loop
@@ -532,56 +754,80 @@ __global__ __launch_bounds__(kVBlock) void verify_slices(VerifyArgs a)
     // element with a == L~ b lands in D; it is in the band, so U covers it).  Elements inside the band are a
     // handful per row at most: their sum and their list are kept under a branch a wavefront almost never enters.
     double A = 0.0, Bs = 0.0, R = 0.0, Ds = 0.0, U = 0.0;
+    // one pass over the slice with the rows' exponentials from the table (TT, TD_) or computed
+    auto pass = [&](auto tt, auto td) {
+        constexpr bool TT = decltype(tt)::value, TD_ = decltype(td)::value;
 #pragma unroll
-    for (int c = 0; c < kChunks; ++c) {
-        float nt[kPer], nd[kPer];
-        if (c + 1 < kChunks) {
-            const int jn = base + (c + 1) * kWave * kPer;
-            load8<TD>(r.trow, r.t_al, jn, a.V, nt);
-            if (resid) load8<DD>(r.drow, r.d_al, jn, a.V, nd);
-        }
-        if (resid) {
-            uint64_t any_band = 0;
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) {
-                const double av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
-                const double bv = exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT, c2, top);
-                const double diff = fma(-lam, bv, av);
-                A += av;
-                Bs += bv;
-                R += fmax(diff, 0.0);
-                Ds += copysign(bv, diff);
-                // band test: the comparison's lane mask is ORed up over the chunk in scalar registers; one branch
-                // per chunk instead of one per element (a branch on a fresh vector comparison stalls the wavefront)
-                any_band |= __builtin_amdgcn_ballot_w64(fabs(diff) <= band * bv);
+        for (int c = 0; c < kChunks; ++c) {
+            if (c + kAhead < kChunks) {
+                const int jn = base + (c + kAhead) * kWave * kPer;
+                qt[c + kAhead] = load_raw8<TD>(r.trow, r.t_al, jn, a.V);
+                if (resid) qd[c + kAhead] = load_raw8<DD>(r.drow, r.d_al, jn, a.V);
             }
-            if (any_band != 0) {
-                asm volatile("" ::: "memory");                  // keep this a branch: a select would cost every element
-                // almost never taken: form the chunk's exponentials again and treat its band elements one by one
+            float ct[kPer], cd[kPer];
+            widen8<TD>(qt[c], ct);
+            widen8<DD>(qd[c], cd);
+            if (resid) {
+                uint64_t any_band = 0, any_tiny = 0;
+                if constexpr (TT || TD_) {
+                    // a chunk that holds a magnitude below the table's range is formed again, the slow way
+                    double cA = 0.0, cB = 0.0, cR = 0.0, cDs = 0.0;
+                    chunk_pair<TT, TD_, false>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, cA, cB, cR, cDs, any_band, any_tiny);
+                    if (any_tiny != 0) {
+                        asm volatile("" ::: "memory");
+                        any_band = 0;
+                        cA = 0.0; cB = 0.0; cR = 0.0; cDs = 0.0;
+                        chunk_pair<TT, TD_, true>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, cA, cB, cR, cDs, any_band, any_tiny);
+                    }
+                    A += cA; Bs += cB; R += cR; Ds += cDs;
+                } else {
+                    chunk_pair<false, false, false>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, A, Bs, R, Ds, any_band, any_tiny);
+                }
+                if (any_band != 0) {
+                    asm volatile("" ::: "memory");                  // keep this a branch: a select would cost every element
+                    // almost never taken: form the chunk's exponentials again and treat its band elements one by one
 #pragma unroll 1
-                for (int i = 0; i < kPer; ++i) {
-                    const double av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
-                    const double bv = exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT, c2, top);
-                    const double diff = fma(-lam, bv, av);
-                    if (fabs(diff) <= band * bv) {
-                        U += bv;
-                        const int pos = atomicAdd(&a.jobs[j].band_cnt, 1);
-                        if (pos < kBandCap) a.jobs[j].band_idx[pos] = base + c * kWave * kPer + i;
+                    for (int i = 0; i < kPer; ++i) {
+                        const double av = TT ? tab_exp_any(ct[i], shE) : exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
+                        const double bv = TD_ ? tab_exp_any(cd[i], shE) : exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT, c2, top);
+                        const double diff = fma(-lam, bv, av);
+                        if (fabs(diff) < band * bv) {
+                            U += bv;
+                            const int pos = atomicAdd(&a.jobs[j].band_cnt, 1);
+                            if (pos < kBandCap) a.jobs[j].band_idx[pos] = base + c * kWave * kPer + i;
+                        }
                     }
                 }
+            } else {
+                uint64_t any_tiny = 0;
+                double cA = 0.0;
+#pragma unroll
+                for (int i = 0; i < kPer; ++i) cA += TT ? tab_lookup(ct[i], shE, &any_tiny) : exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
+                if constexpr (TT)
+                    if (any_tiny != 0) {
+                        asm volatile("" ::: "memory");
+                        cA = 0.0;
+#pragma unroll
+                        for (int i = 0; i < kPer; ++i) cA += tab_exp_any(ct[i], shE);
+                    }
+                A += cA;
             }
-        } else {
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) A += exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
         }
-        if (c + 1 < kChunks) {
-#pragma unroll
-            for (int i = 0; i < kPer; ++i) { ct[i] = nt[i]; cd[i] = nd[i]; }
-        }
+    };
+    using std::false_type; using std::true_type;
+    if constexpr (kTabT && kTabD) {
+        // the target row always comes with the draft row here except for jobs on one row (tab_d false: no draft row)
+        if (tab_t) pass(true_type{}, true_type{}); else pass(false_type{}, false_type{});
+    } else if constexpr (kTabT) {
+        if (tab_t) pass(true_type{}, false_type{}); else pass(false_type{}, false_type{});
+    } else if constexpr (kTabD) {
+        if (tab_d) pass(false_type{}, true_type{}); else pass(false_type{}, false_type{});
+    } else {
+        pass(false_type{}, false_type{});
     }
     double D = 0.5 * (Bs + Ds);
-    A = wave_sum_d(A);
-    if (resid) { Bs = wave_sum_d(Bs); R = wave_sum_d(R); D = wave_sum_d(D); U = wave_sum_d(U); }
+    A = wave_sum_d(A) * sc.ct;
+    if (resid) { Bs = wave_sum_d(Bs) * sc.cd; R = wave_sum_d(R) * sc.ct; D = wave_sum_d(D) * sc.cd; U = wave_sum_d(U) * sc.cd; }
     if (lane == 0) {
         double *o = a.part1 + ((int64_t)j * a.nsl + s) * kSliceVals;
         o[0] = A; o[1] = Bs; o[2] = R; o[3] = D; o[4] = U;
@@ -698,19 +944,24 @@ __device__ inline int locate_in_slice(const Weights &w, const Rows &r, int s, in
 // number) is taken back: correction = max(0, a - L b) - (max(0, a - L~ b) - delta [a > L~ b] b).  The list is
 // sorted by index, so that sums over it do not depend on the order in which the slice kernel's workgroups
 // appended.  Leaves the sorted (index, correction) pairs in sh and returns their total.  Whole workgroup.
+// E: the table of bfloat16 exponentials (memory), sc / tab_t / tab_d: the job's scales as the slice kernel formed them
+// (tab_scale): the side of L~ an element was counted on is decided here on the very numbers the slice kernel compared.
 template <int TD, int DD>
-__device__ __noinline__ double settle_band(const Weights &w, const Rows &r, int V, const double *T,
-                                           double lam_est, double delta, int n_band, int band_i, LocateShared *sh)
+__device__ __noinline__ double settle_band(const Weights &w, const Rows &r, int V, const double *T, const double *E,
+                                           const TabScale &sc, bool tab_t, bool tab_d,
+                                           double delta, int n_band, int band_i, LocateShared *sh)
 {
     const int tid = threadIdx.x;
     double wv = 0.0;
     if (tid < n_band && band_i < V) {
-        const double av = exp_fast(load_elem<TD>(r.trow, band_i), w.rp.neg_ref_c, w.rp.lo, T);
-        const double bv = exp_fast(load_elem<DD>(r.drow, band_i), w.rq.neg_ref_c, w.rq.lo, T);
+        const float xt = load_elem<TD>(r.trow, band_i), xd = load_elem<DD>(r.drow, band_i);
+        const double avp = tab_t ? tab_exp_any(xt, E) : exp_fast(xt, w.rp.neg_ref_c, w.rp.lo, T);
+        const double bvp = tab_d ? tab_exp_any(xd, E) : exp_fast(xd, w.rq.neg_ref_c, w.rq.lo, T);
+        const double av = avp * sc.ct, bv = bvp * sc.cd;       // (scales of 1 where the row's exponentials are computed)
         const double v = fma(-w.lam, bv, av);
         const double exact = v > 1.0e-290 ? v : 0.0;           // same rule as thread_weights (masked logits weigh nothing)
-        const double dt = fma(-lam_est, bv, av);
-        wv = exact - (fmax(dt, 0.0) - delta * (dt >= 0.0 ? bv : 0.0));
+        const double dt = fma(-sc.Lp, bvp, avp);
+        wv = exact - (sc.ct * fmax(dt, 0.0) - delta * (dt >= 0.0 ? bv : 0.0));
     }
     if (tid < kBandCap) { sh->band_key[tid] = tid < n_band ? band_i : 0x7fffffff; sh->band_val[tid] = wv; }
     __syncthreads();
@@ -825,7 +1076,10 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
         bool certified = close && Z > 0.0 && fabs(delta) * tot[4] <= 2.0e-10 * Z;
         if (!certified && close && band_n <= kBandCap) {
             n_band = band_n;
-            Z += settle_band<TD, DD>(w, r, a.V, shT, job.lam, delta, band_n, band_i, &shl);
+            const bool tab_ok = TD == TAPOUT_BF16 && DD == TAPOUT_BF16 && !(a.vflags & kVerifyNoExpTable) && tab_job_ok(job);    // as in the slice kernel
+            const bool tab_t = tab_ok, tab_d = tab_ok;
+            Z += settle_band<TD, DD>(w, r, a.V, shT, a.exp_table + 256, tab_scale(job, tab_t, tab_d, shT), tab_t, tab_d,
+                                     delta, band_n, band_i, &shl);
             certified = Z > 0.0;
         }
         if (!certified) {
@@ -1138,6 +1392,7 @@ hipError_t launch_shard_typed(const ShardFinalArgs &a, int pass, hipStream_t st)
 
 hipError_t launch_shard_dispatch(const ShardFinalArgs &a, int pass, hipStream_t st)
 {
+    if (!a.v.exp_table) return hipErrorInvalidValue;
     if (a.v.t_dtype == TAPOUT_F32)
         return a.v.d_dtype == TAPOUT_F32 ? launch_shard_typed<TAPOUT_F32, TAPOUT_F32>(a, pass, st) : launch_shard_typed<TAPOUT_F32, TAPOUT_BF16>(a, pass, st);
     return a.v.d_dtype == TAPOUT_F32 ? launch_shard_typed<TAPOUT_BF16, TAPOUT_F32>(a, pass, st) : launch_shard_typed<TAPOUT_BF16, TAPOUT_BF16>(a, pass, st);
@@ -1176,7 +1431,8 @@ hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing t
 {
     static const DraftFinalArgs no_fin{};
     const bool with_fin = fin != nullptr;
-    if ((a.own_q != 0) != with_fin || (fin && (a.jps != 1 || a.n_jobs != a.B || a.shards > 0 || fin->shards > 0 || fin->B != a.B)))
+    if (!a.exp_table) return hipErrorInvalidValue;           // every pass reads it
+    if (((a.vflags & kVerifyOwnQ) != 0) != with_fin || (fin && (a.jps != 1 || a.n_jobs != a.B || a.shards > 0 || fin->shards > 0 || fin->B != a.B)))
         return hipErrorInvalidValue;
     if (!fin) fin = &no_fin;
     if (pass == 0) {

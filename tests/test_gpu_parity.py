@@ -710,6 +710,51 @@ def test_residual_with_a_few_tokens_where_p_equals_q():
     assert (vf["accept_len"].cpu() == 0).sum() >= B - c["accept_flagged"] - 1
 
 
+@pytest.mark.parametrize("shift", [0.0, 70.0, -40.0, 55.0])
+@FUSE
+def test_bfloat16_final_token_table_and_its_limits(shift, fuse):
+    """The final-token pass of bfloat16 row pairs takes exp(x) from a table of the bfloat16 values with 2^-12 <= |x| < 63.75.
+    Rows full of what the table does not hold: exact zeros, +-0, magnitudes below 2^-12 (formed by a polynomial in a
+    chunk of their own), logits at and below -63.75 (weigh nothing), masked entries, a vocabulary that ends inside a
+    slice; and whole rows shifted so that the row maximum leaves the table's range (+70, -40: such jobs compute their
+    exponentials) or sits just inside it (+55).  Against the oracle, and against the same call with the table switched
+    off ("exp_lookup" = 0): same tokens, same accepted lengths."""
+    B, K, V = 6, 5, 2048 * 5 + 777
+    g = torch.Generator(device=DEV).manual_seed(4242)
+    d = torch.randn(B, K, V, generator=g, device=DEV) * 3.0
+    t = torch.cat([d + torch.randn(B, K, V, generator=g, device=DEV) * 1.2, torch.randn(B, 1, V, generator=g, device=DEV) * 3.0], 1)
+    for x in (d, t):
+        r = torch.rand(x.shape, generator=g, device=DEV)
+        x[r < 0.05] = 0.0
+        x[(r >= 0.05) & (r < 0.08)] = -0.0
+        x[(r >= 0.08) & (r < 0.14)] *= 1e-5                      # far below 2^-12
+        x[(r >= 0.14) & (r < 0.16)] = 2.0 ** -12                 # the table's first entry
+        x[(r >= 0.16) & (r < 0.18)] = -(2.0 ** -12) * (1 - 2.0 ** -8)   # the largest magnitude below it
+        x[(r >= 0.18) & (r < 0.20)] = -63.75
+        x[(r >= 0.20) & (r < 0.22)] = -64.0
+        x[(r >= 0.22) & (r < 0.24)] = -3.0e38
+        x[(r >= 0.24) & (r < 0.27)] = float("-inf")
+    d, t = (d + shift).to(torch.bfloat16), (t + shift).to(torch.bfloat16)
+    gum = -torch.log(-torch.log(torch.rand(B, K, V, generator=g, device=DEV).clamp_min(1e-20)))
+    tok = (d.float() + gum).argmax(-1).to(torch.int32)
+    rnd = dict(draft=d, target=t, draft_tok=tok, u_accept=torch.rand(B, K, generator=g, device=DEV),
+               u_sample=torch.rand(B, generator=g, device=DEV), k_len=torch.full((B,), K, dtype=torch.int32, device=DEV),
+               greedy=torch.zeros(B, dtype=torch.uint8, device=DEV))
+    rnd["u_accept"][0] = 0.0                                      # every token accepted: the draw comes from target row K alone
+    rnd["u_accept"][1] = 1.0                                      # rejected at once: residual of row 0
+    outs = {}
+    for lookup in (1, 0):
+        tp = binding.Tapout(B, K, V)
+        tp.set_option("fuse_head", fuse)
+        tp.set_option("exp_lookup", lookup)
+        c = pu.check_round(tp, rnd)
+        assert c["accept_flagged"] + c["icdf_flagged"] <= 1
+        _, vf, _ = pu.gpu_round(tp, rnd)
+        outs[lookup] = {k: v.cpu().clone() for k, v in vf.items()}
+    for k in ("accept_len", "out_tok", "n_out", "flags"):
+        assert torch.equal(outs[1][k], outs[0][k]), k
+
+
 def random_round(B, K, V, dtype, seed, sigma=2.5, k_len=None):
     g = torch.Generator(device=DEV).manual_seed(seed)
     d = (torch.randn(B, K, V, generator=g, device=DEV) * sigma).to(dtype)

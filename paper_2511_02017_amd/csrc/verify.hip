@@ -236,6 +236,11 @@ __device__ inline Raw8<DT> load_raw8(const char *rowp, bool aligned, int j, int 
         } else {
             r.w[0] = *(const u32x4 *)(rowp + (int64_t)j * 4); r.w[1] = *(const u32x4 *)(rowp + (int64_t)j * 4 + 16);
         }
+    } else if (j >= V) {
+        // beyond the row: nothing to load (the usual case in a row's last slice)
+        constexpr uint32_t ninf = DT == TAPOUT_BF16 ? 0xff80ff80u : 0xff800000u;
+#pragma unroll
+        for (int h = 0; h < (DT == TAPOUT_F32 ? 2 : 1); ++h) r.w[h] = u32x4{ninf, ninf, ninf, ninf};
     } else {
         uint32_t e[kPer];
 #pragma unroll
@@ -656,7 +661,10 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     if (j >= a.n_jobs) return;
     const int b = j / a.jps;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
-    const int s = blockIdx.x * kWavesPerWG + wave;
+    // FUSED: the sequence's last workgroup writes the sequence's outputs, from its first wavefront, which therefore
+    // takes the group's last slice: most often none at all, or the row's short last one
+    const bool writer = FUSED && blockIdx.x == gridDim.x - 1;
+    const int s = blockIdx.x * kWavesPerWG + (writer ? kWavesPerWG - 1 - wave : wave);
     // The tables are requested first of all: nothing of them depends on the job, and a wavefront's loads return in
     // order, so requested after the rows they would hold the barrier below until the whole slice has arrived.
     static_assert(kVBlock == 256, "one entry of the small table per thread");
@@ -673,7 +681,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     if constexpr (FUSED) {
         // Small batches: a head launch of its own costs more (launch, hand-over of the job record through
         // memory) than taking the accept decisions again in each of the sequence's workgroups.  All of them run
-        // the same code on the same inputs and reach the same job; the first one writes the sequence's outputs.
+        // the same code on the same inputs and reach the same job; one of them writes the sequence's outputs.
         unsigned char *q = sh_raw;
         Partial *sh_part = (Partial *)q;            q += sizeof(Partial) * kStageCap;
         DraftRowLse *sh_qrows = (DraftRowLse *)q;   q += sizeof(DraftRowLse) * kWave;
@@ -681,7 +689,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
         int32_t *sh_bcast = (int32_t *)q;           q += 32;
         uint32_t *sh_flags = (uint32_t *)q;         q += 8;
         uint8_t *sh_dec = q;
-        job = verify_head<false>(a, b, blockIdx.x == 0, sh_part, sh_dec, sh_flags, sh_bcast, sh_lse, sh_qrows, shT);
+        job = verify_head<false>(a, b, writer, sh_part, sh_dec, sh_flags, sh_bcast, sh_lse, sh_qrows, shT);
     } else {
         job = a.jobs[j].job;
     }

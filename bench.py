@@ -291,16 +291,21 @@ def run_workload(args, name, steps, warmup, kernel_steps, headline):
         res["four_calls"] = {"ms_per_step": round(elapsed4 / steps * 1e3, 4), "value": round(verified / elapsed4, 1),
                              "note": "the same steps as select / draft_stats / verify / update, one after the other on one stream"}
     if not args.no_parity and not sample_draft:
-        # one closed-loop round on a fresh context (the arm pool's first plays), stop rules and all, against the oracle
+        # one round on a fresh context (the arm pool's first plays), stop rules and all, against the oracle: through the
+        # call the timed region makes (tapout_round), with the same options
         tp2 = mk()
+        if headline:
+            for o in args.opt:
+                k, v = o.split("=")
+                tp2.set_option(k, int(v))
         rnd = ring[0]
         arm = tp2.bandit_select(w.B, u_ts=u_ts_ring[0])
-        gds = tp2.draft_stats(rnd["draft"], draft_tok=rnd["draft_tok"], k_len=rnd["k_len"], arm=arm)
-        n_draft = gds["n_stop"] if truncate else rnd["k_len"]
-        gvf = tp2.verify(rnd["target"], rnd["draft"], gds["lse"], gds["logq_tok"], rnd["draft_tok"], n_draft,
-                         rnd["u_accept"], rnd["u_sample"], greedy=rnd["greedy"])
+        arm_played = arm.clone()                      # the call leaves the next round's arms in `arm`
+        launch, outs = tp2.prepare_round_call(rnd, arm, truncate, u_ts_next=u_ts_ring[1 % ring_n])
+        launch(torch.cuda.current_stream().cuda_stream)
         torch.cuda.synchronize()
-        res["parity"] = decision_parity(torch, w, rnd, arm, gds, gvf, n_draft, rules, thresholds)
+        res["parity"] = decision_parity(torch, w, rnd, arm_played, outs["draft"], outs["verify"], outs["n_draft"], rules, thresholds)
+        res["parity"]["call"] = "tapout_round"
         tp2.close()
     keep = dict(w=w, ring=ring, truncate=truncate, policy=policy, rules=rules, thresholds=thresholds, u_ts_ring=u_ts_ring, ed=ed)
     return res, keep

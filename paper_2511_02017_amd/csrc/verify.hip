@@ -38,7 +38,8 @@
 // with two exponentials per element.  exp() is 2^(n/256) * (1 + r + r^2/2 +
 // r^3/6), |r| <= ln2/512, with a 256-entry table in LDS: relative error
 // < 2e-13, far inside what the 1e-9 decision margin needs, at a third of the
-// instructions of a correctly rounded exp.
+// instructions of a correctly rounded exp; row pairs of bfloat16 logits take
+// exp(x) itself from a table of all bfloat16 values a softmax row can hold.
 #include "common.h"
 #include "bandit_device.h"
 #include "finalize_device.h"
@@ -552,11 +553,6 @@ constexpr int kSliceVals = 5;          // A, B, R~, D, U
 constexpr int kWavesPerWG = kVBlock / kWave;                    // 4 slices per workgroup, one per wavefront
 constexpr int kChunks = kSampleSlice / (kWave * kPer);          // a wavefront takes its slice in 4 chunks of 512 elements
 
-// One wavefront per slice, four slices per workgroup.  A wavefront streams its slice in chunks of one 8-element
-// run per lane and requests the next chunk before it does the arithmetic of the current one, so that after the
-// first chunk the memory latency hides behind the double-precision work; its five sums need no LDS and no
-// barrier.  (One slice per workgroup with all loads up front was latency bound: job record, then rows, then
-// arithmetic, 8.7 us per workgroup with at most eight of them per compute unit.)
 // ---- exponentials of bfloat16 logits from a table -----------------------------------------
 // A bfloat16 logit has 2^16 possible values, and those between 2^-12 and 2^6 in magnitude (all a softmax row holds
 // besides masked entries and the odd tiny one) are 2 * 2303 of them: exp(x) itself, correctly rounded on the host,
@@ -645,6 +641,10 @@ __device__ inline void chunk_pair(const float (&ct)[kPer], const float (&cd)[kPe
     }
 }
 
+// One wavefront per slice, four slices per workgroup.  A wavefront takes its slice in chunks of one 8-element run per
+// lane; its five sums need no LDS and no barrier.  The requests run ahead of the arithmetic (see kAhead): with one
+// chunk ahead the launch was bound by memory latency.  Four wavefronts per SIMD: the bfloat16 table limits a CU to
+// four workgroups anyway, and under a tighter register limit the loop spills.
 template <int TD, int DD, bool FUSED>
 __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) void verify_slices(VerifyArgs a)
 {

@@ -94,6 +94,19 @@ def gpu_round(tp, rnd, arm=None, n_draft=None):
     return ds, vf, n_draft
 
 
+def check_round_call(tp, rnd, arm, truncate, rules=(0, 1, 2), thresholds=(0.6, 0.8, 0.2)):
+    """One tapout_round call (the arms in `arm` are played; the call leaves the next round's there) against the oracle.
+    truncate: n_draft = this round's stop position, else n_draft = k_len."""
+    arm_played = arm.clone()
+    launch, outs = tp.prepare_round_call(rnd, arm, truncate)
+    launch(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    ods, ovf, o_nd = oracle_round(rnd, arm=arm_played, n_draft=None if truncate else rnd["k_len"], rules=rules, thresholds=thresholds)
+    gvf = dict(outs["verify"])
+    gvf["n_draft_used"] = outs["n_draft"]
+    return compare_round(outs["draft"], gvf, ods, ovf, rnd["k_len"].cpu().numpy(), o_nd)
+
+
 def compare_round(gds, gvf, ods, ovf, k_len, n_draft_ref, seqs=None, check_stop=True):
     """Element-by-element comparison; returns counts of near-tie (flagged) decisions."""
     pick = (lambda t: t.cpu().numpy()) if seqs is None else (lambda t: t[seqs].cpu().numpy())

@@ -79,16 +79,7 @@ def test_workload_parity_whole_round_call(name, kw, truncate):
     tp = binding.Tapout(w.B, w.K, w.V)
     total = dict(stop_flagged=0, accept_flagged=0, icdf_flagged=0, sequences=0)
     for r in (0, 1):
-        rnd = gen.round(r)
-        arm = random_arms(w.B, seed=r)
-        arm_played = arm.clone()
-        launch, outs = tp.prepare_round_call(rnd, arm, truncate)
-        launch(torch.cuda.current_stream().cuda_stream)
-        torch.cuda.synchronize()
-        ods, ovf, o_nd = pu.oracle_round(rnd, arm=arm_played, n_draft=None if truncate else rnd["k_len"])
-        gvf = dict(outs["verify"])
-        gvf["n_draft_used"] = outs["n_draft"]
-        c = pu.compare_round(outs["draft"], gvf, ods, ovf, rnd["k_len"].cpu().numpy(), o_nd)
+        c = pu.check_round_call(tp, gen.round(r), random_arms(w.B, seed=r), truncate)
         for k in total:
             total[k] += c[k]
     announce(f"{name}: near-tie counts {total}")
@@ -579,6 +570,10 @@ def test_random_configurations(seed):
     c = pu.check_round(tp, rnd)
     c2 = pu.check_round(tp, rnd, arm=random_arms(B, seed=seed))
     assert c["accept_flagged"] + c["icdf_flagged"] + c2["stop_flagged"] <= 2
+    # the same round as one tapout_round call (its own launch order: see the library's "defer_epilogue" option)
+    tp.set_option("defer_epilogue", int(rs.randint(0, 2)))
+    c3 = pu.check_round_call(tp, rnd, random_arms(B, seed=seed), truncate=bool(seed & 1))
+    assert c3["accept_flagged"] + c3["icdf_flagged"] <= 2
 
 
 def force_slices(tp, rows, P, min_slice=256):

@@ -487,7 +487,13 @@ TAPOUT_API tapout_status tapout_bandit_update_select(tapout_ctx *ctx, int32_t B,
  * the target rows depends on nothing the draft side computes, and ONE launch
  * streams the draft rows and the target rows together: a launch over a few
  * hundred rows spends a fifth of its time filling and draining the chip, and
- * the pair pays that once.
+ * the pair pays that once.  Nor does verification then wait for the draft
+ * epilogue: the accept decisions form log q(tok) from the draft pass's slice
+ * sums themselves (binary32 precision: a decision can differ from the separate
+ * calls' only if its uniform lies within ~1e-6, relative, of p/q) and the
+ * epilogue runs in the same launch as the final-token search (option
+ * "defer_epilogue"; contexts without a stateful stop rule).  The logq_tok and lse
+ * written are the epilogue's own.
  *   draft [B,K,V], target [B,K+1,V]
  *   draft_tok [B,K];  k_len [B] or NULL;  greedy [B] or NULL
  *   n_draft   [B] tokens submitted to verification, or NULL: this round's stop

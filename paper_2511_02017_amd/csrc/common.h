@@ -475,44 +475,57 @@ __device__ inline RowSignals row_signals(const RowTotal &r, bool has_second)
 // first maximum starts (or the index of a head / tail element).  All addresses are checked against the slice.
 struct BatchRegs {
     u32x4 w[kStreamU];
-    uint32_t valid;       // bit u: vector u is loaded; bit 8: a single element, its bits in w[0].x
+    uint32_t valid;       // bit u: vector u is wanted (the others hold stand-in data); bit 8: a single element, in `single`
+    uint32_t single;      // bits of the single head / tail element
     int32_t first;        // element index of vector 0 (or of the single element)
     int32_t ucand;        // which vector of the batch the candidate is: the one that holds the first maximum
 };
 
-template <int DT>
-__device__ inline BatchRegs batch_issue_t(const void *row, int32_t V, int32_t cand, int split, int per)
+// Written so that the four requests are straight-line code at the end: where the branches above them only choose
+// addresses (`safe`, any readable 16-byte aligned address, stands in for a vector that is not wanted; the valid bits
+// tell), the compiler has no loaded registers to merge between branches.  With the requests inside the branches it
+// merged them with the zeros of the other paths and waited for the data right there: a second memory round trip in a
+// kernel that is nothing but round trips.
+__device__ inline BatchRegs batch_issue(const void *row, int dtype, int32_t V, int32_t cand, int split, int per, const void *safe)
 {
-    constexpr int VEC = Elem<DT>::vec;
+    const int esz = dtype == TAPOUT_F32 ? 4 : 2, vsh = dtype == TAPOUT_F32 ? 2 : 3, VEC = 1 << vsh;
     BatchRegs b;
-    b.valid = 0; b.first = 0; b.ucand = 0;
+    b.valid = 0; b.first = 0; b.ucand = 0; b.single = 0;
+    // (device memory, and said so: chosen among several pointers the compiler would otherwise treat them as generic
+    // addresses, whose loads also count as LDS traffic)
+    typedef const __attribute__((address_space(1))) u32x4 *GlobalVec;
+    GlobalVec p[kStreamU];
 #pragma unroll
-    for (int u = 0; u < kStreamU; ++u) b.w[u] = u32x4{0u, 0u, 0u, 0u};
-    if (cand < 0 || cand >= V) return b;
-    int head, nvec, tail;
-    row_geometry<DT>(row, V, head, nvec, tail);
-    if (cand < head || cand >= head + nvec * VEC) {
-        b.w[0].x = __float_as_uint(load_elem<DT>(row, cand));
-        b.valid = 0x100u; b.first = cand;
-        return b;
-    }
-    const int i = (cand - head) / VEC;
-    const int v0 = min(split * per, nvec), v1e = min(v0 + per, nvec);
-    if (i < v0 || i >= v1e) return b;                                           // not a candidate of this slice: stale record
-    const int rel = i - v0, t = rel % kBlock, q0 = (rel / kBlock) / kStreamU * kStreamU;
-    const u32x4 *vp = (const u32x4 *)((const char *)row + (int64_t)head * Elem<DT>::size);
-    b.first = head + (v0 + t + q0 * kBlock) * VEC;
-    b.ucand = rel / kBlock - q0;
+    for (int u = 0; u < kStreamU; ++u) p[u] = (GlobalVec)safe;
+    if (cand >= 0 && cand < V) {
+        // the row's unaligned head, 16-byte vectors and tail (as row_geometry)
+        const int mis = (int)(((uintptr_t)row & 15u) / (unsigned)esz);
+        int head = (VEC - mis) & (VEC - 1);
+        if (head > V) head = V;
+        const int nvec = (V - head) >> vsh;
+        if (cand < head || cand >= head + (nvec << vsh)) {
+            b.single = __float_as_uint(load_elem_rt(row, dtype, cand));
+            b.valid = 0x100u; b.first = cand;
+        } else {
+            const int i = (cand - head) >> vsh;
+            const int v0 = min(split * per, nvec), v1e = min(v0 + per, nvec);
+            if (i >= v0 && i < v1e) {                                           // else: not a candidate of this slice: stale record
+                const int rel = i - v0, t = rel % kBlock, q0 = (rel / kBlock) / kStreamU * kStreamU;
+                GlobalVec vp = (GlobalVec)((const char *)row + (int64_t)head * esz);
+                b.first = head + ((v0 + t + q0 * kBlock) << vsh);
+                b.ucand = rel / kBlock - q0;
 #pragma unroll
-    for (int u = 0; u < kStreamU; ++u) {
-        const int iu = v0 + t + (q0 + u) * kBlock;
-        if (iu < v1e) { b.w[u] = vp[iu]; b.valid |= 1u << u; }
+                for (int u = 0; u < kStreamU; ++u) {
+                    const int iu = v0 + t + (q0 + u) * kBlock;
+                    p[u] = vp + min(iu, v1e - 1);                               // v0 <= i <= v1e - 1: inside the slice
+                    b.valid |= iu < v1e ? 1u << u : 0u;
+                }
+            }
+        }
     }
+#pragma unroll
+    for (int u = 0; u < kStreamU; ++u) b.w[u] = *p[u];
     return b;
-}
-__device__ inline BatchRegs batch_issue(const void *row, int dtype, int32_t V, int32_t cand, int split, int per)
-{
-    return dtype == TAPOUT_F32 ? batch_issue_t<TAPOUT_F32>(row, V, cand, split, per) : batch_issue_t<TAPOUT_BF16>(row, V, cand, split, per);
 }
 
 // The elements of a piece's left-out batch, except the first one equal to the piece's maximum M: their two sums
@@ -535,7 +548,7 @@ __device__ inline BatchExtra batch_extra_t(float M, const BatchRegs &b)
         float sa = 0.0f, ta = 0.0f;
         int32_t idx = 0x7fffffff;
         if (b.valid & 0x100u) {
-            const float x = __uint_as_float(b.w[0].x);
+            const float x = __uint_as_float(b.single);
             if (x == M) idx = b.first;
             else {
                 const float y = __builtin_fmaf(x, kLog2e, -R), e = __builtin_amdgcn_exp2f(y);

@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kFinalBlock) void shard_merge_kernel(ShardMergeArgs
     Piece acc = empty_piece();
     for (int sl = 0; sl < a.nsplit; ++sl) {
         Piece e = piece_from_partial(a.part[(int64_t)i * a.nsplit + sl]);
-        const BatchRegs bt = batch_issue(row, a.dtype, a.Vs, e.idx, sl, a.per);
+        const BatchRegs bt = batch_issue(row, a.dtype, a.Vs, e.idx, sl, a.per, a.part);
         batch_fix(e, bt, a.dtype);
         acc = merge_pair<true>(acc, e);
     }

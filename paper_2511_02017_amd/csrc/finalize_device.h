@@ -87,9 +87,9 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
             const int row = (threadIdx.x >> msh) + q * (256 >> msh);
             e[q] = lane_piece(ln0, q, kb, a.nsplit, msh);     // rows beyond k_len hold stale partials: empty pieces
             bt[q].valid = 0;
-            if (q == 0 || (256 >> msh) < kb)
-                if (row < kb && sl < a.nsplit)
-                    bt[q] = batch_issue(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, row), a.dtype, a.V, e[q].idx, sl, a.per);
+            if (q == 0 || (256 >> msh) < kb)                      // uniform; a thread without a piece asks for nothing (candidate -1)
+                bt[q] = batch_issue(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, row), a.dtype, a.V,
+                                    (row < kb && sl < a.nsplit) ? e[q].idx : -1, sl, a.per, a.part);
         }
         // While the batches travel, the pieces are merged as they are.  Then every lane adds what its own batch holds
         // besides the first maximum: rescaled to the row's reference, summed over the row's lanes (binary32: small
@@ -139,7 +139,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
                 const int k = k0 + i / a.nsplit, sl = i % a.nsplit;
                 if (k >= kb) continue;                          // stale partial of a row that was not drafted
                 Piece e = piece_from_partial(sh_part[i]);
-                const BatchRegs bt = batch_issue(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k), a.dtype, a.V, e.idx, sl, a.per);
+                const BatchRegs bt = batch_issue(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k), a.dtype, a.V, e.idx, sl, a.per, a.part);
                 batch_fix(e, bt, a.dtype);
                 sh_part[i].S = (float)e.S; sh_part[i].T = (float)e.T; sh_part[i].cand = e.idx;
             }

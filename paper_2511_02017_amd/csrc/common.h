@@ -640,24 +640,38 @@ __device__ inline int lane_merge_shift(int rows, int nsplit)
 struct LaneRegs { StageRegs p[2]; };
 __device__ inline LaneRegs lane_merge_issue(const Partial *part, int rows, int nsplit, int sh)
 {
+    // Every thread requests something (one without a partial re-reads partial 0; lane_piece ignores what it got): a
+    // request under a condition is merged with the other branch's zeros, and the compiler waits for the data at the
+    // merge, ahead of whatever the caller wanted to request next.
     LaneRegs r;
     const int sl = threadIdx.x & ((1 << sh) - 1);
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-        r.p[q].w0 = r.p[q].w1 = u32x4{0u, 0u, 0u, 0u};
+        // pass 2 only where one pass does not cover the rows (uniform); its registers are left unset otherwise and
+        // nothing reads them (setting them would be the merge described above)
+        if (q == 1 && (256 >> sh) >= rows) break;
         const int row = (threadIdx.x >> sh) + q * (256 >> sh);
-        if (row < rows && sl < nsplit) {
-            const u32x4 *s = (const u32x4 *)(part + (int64_t)row * nsplit + sl);
-            r.p[q].w0 = s[0]; r.p[q].w1 = s[1];
-        }
+        const bool mine = row < rows && sl < nsplit;
+        const u32x4 *s = (const u32x4 *)(part + (mine ? (int64_t)row * nsplit + sl : 0));
+        r.p[q].w0 = s[0]; r.p[q].w1 = s[1];
     }
     return r;
+}
+
+// Holds the requested partials' registers until here: placed after the caller's other requests, it keeps the compiler
+// from handing a register of a still outstanding request to something else (it would have to wait for the request
+// first); the wait for the data then happens here, behind all requests.
+__device__ inline void lane_merge_pin(const LaneRegs &r, int rows, int sh)
+{
+    asm volatile("" :: "v"(r.p[0].w0), "v"(r.p[0].w1));
+    if ((256 >> sh) < rows) asm volatile("" :: "v"(r.p[1].w0), "v"(r.p[1].w1));
 }
 
 // This thread's piece of pass q (an empty piece where the thread has none).
 __device__ inline Piece lane_piece(const LaneRegs &w, int q, int rows, int nsplit, int sh)
 {
     const int sl = threadIdx.x & ((1 << sh) - 1), row = (threadIdx.x >> sh) + q * (256 >> sh);
+    if (q == 1 && (256 >> sh) >= rows) return empty_piece();       // uniform: no second pass was requested
     return (row < rows && sl < nsplit) ? piece_from_words(w.p[q].w0, w.p[q].w1) : empty_piece();
 }
 

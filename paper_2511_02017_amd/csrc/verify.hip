@@ -181,23 +181,33 @@ __device__ inline QPiece qpiece_merge(const QPiece &a, const QPiece &b)
     o.xt = (a.xt == a.xt) ? a.xt : b.xt;                          // at most one slice holds the token
     return o;
 }
-__device__ inline void draft_rows_lse(const Partial *part, int rows, int nsplit, DraftRowLse *out)
+// In two steps, so that the caller can put these requests beside its own and wait for all of them once: the requests ...
+struct DraftLseRegs { float pm[2], ps[2], px[2], ph[2]; };       // maximum, sum, token logit, left-out sum: the words wanted
+__device__ inline int draft_lse_tid(int rows, int sh)
 {
-    const int sh = lane_merge_shift(rows, nsplit);                // >= 0: the host offers this path for such shapes only
-    if (sh < 0) return;
     // when they fit, on the upper two wavefronts: the lower two merge the target rows meanwhile
-    const int tid = (rows << sh) <= 128 ? (int)threadIdx.x - 128 : (int)threadIdx.x;
-    const int sl = tid & ((1 << sh) - 1);
-    float pm[2], ps[2], px[2], ph[2];                             // maximum, sum, token logit, left-out sum: the words wanted
+    return (rows << sh) <= 128 ? (int)threadIdx.x - 128 : (int)threadIdx.x;
+}
+__device__ inline DraftLseRegs draft_rows_lse_issue(const Partial *part, int rows, int nsplit, int sh)
+{
+    const int tid = draft_lse_tid(rows, sh), sl = tid & ((1 << sh) - 1);
+    DraftLseRegs r;
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
-        pm[q] = -INFINITY; ps[q] = 0.0f; px[q] = NAN; ph[q] = 0.0f;
+        if (q == 1 && (256 >> sh) >= rows) break;                              // uniform; pass 2 stays unset and unread
+        // unconditional requests (a thread without a partial re-reads partial 0 and ignores it): see lane_merge_issue
         const int row = tid < 0 ? rows : (tid >> sh) + q * (256 >> sh);        // rows: none
-        if (row < rows && sl < nsplit && (q == 0 || (256 >> sh) < rows)) {
-            const Partial *s = part + (int64_t)row * nsplit + sl;
-            pm[q] = s->v1; ps[q] = s->S; px[q] = __int_as_float(s->pad[0]); ph[q] = __int_as_float(s->pad[1]);
-        }
+        const bool mine = row < rows && sl < nsplit;
+        const Partial *s = part + (mine ? (int64_t)row * nsplit + sl : 0);
+        r.pm[q] = s->v1; r.ps[q] = s->S; r.px[q] = __int_as_float(s->pad[0]); r.ph[q] = __int_as_float(s->pad[1]);
     }
+    return r;
+}
+// ... and the merge, which writes out[row] for row < rows (published by the caller's next barrier).
+__device__ inline void draft_rows_lse_finish(const DraftLseRegs &r, int rows, int nsplit, int sh, DraftRowLse *out)
+{
+    const int tid = draft_lse_tid(rows, sh), sl = tid & ((1 << sh) - 1);
+    asm volatile("" :: "v"(r.pm[0]), "v"(r.ps[0]), "v"(r.px[0]), "v"(r.ph[0]));     // see lane_merge_pin
 #pragma unroll
     for (int q = 0; q < 2; ++q) {
         if (q == 1 && (256 >> sh) >= rows) break;                 // uniform
@@ -205,9 +215,9 @@ __device__ inline void draft_rows_lse(const Partial *part, int rows, int nsplit,
         QPiece e;
         e.M = -INFINITY; e.S = 0.0; e.xt = NAN;
         if (row < rows && sl < nsplit) {
-            e.M = pm[q];
-            e.S = (double)ps[q] + (double)ph[q];
-            e.xt = px[q];
+            e.M = r.pm[q];
+            e.S = (double)r.ps[q] + (double)r.ph[q];
+            e.xt = r.px[q];
             if (e.M == -INFINITY && !(e.S != e.S)) e.S = 0.0;     // empty slice
         }
         if (sh >= 1) e = qpiece_merge(e, qpiece_dpp<0xB1>(e));
@@ -278,13 +288,17 @@ __device__ inline void widen8(const Raw8<DT> &r, float (&x)[kPer])
 // with their left-out batch's own sum added back (binary32 precision, which a ratio p/q compared with a uniform
 // needs no more than) and the token's logit, which the draft pass left in the partial of the slice that holds it.
 //
-// shT: the 256-entry table of exp_fast in LDS, stored by the caller before the call (the first barrier in here
-// publishes it): the two exponentials on this kernel's critical path take 13 instructions each instead of a call
-// into the device library.
-template <bool SHARDED>
+// shT: 256 doubles of LDS for the table of exp_fast, which this function fills (each thread requests its entry with the
+// first requests and stores it ahead of the first barrier): the two exponentials on the critical path take 13
+// instructions each instead of a call into the device library.  256-thread workgroups.
+//
+// more_requests(): called once, right after this function's own first requests are out: a caller with bulk loads of its
+// own (the slice kernel's table) puts them there, behind the few words the decisions wait for (loads return in order).
+struct NoRequests { __device__ void operator()() const {} };
+template <bool SHARDED, class MoreRequests = NoRequests>
 __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                                         Partial *sh_part, uint8_t *sh_dec, uint32_t *sh_flags, int32_t *sh_bcast, double *sh_lse,
-                                        DraftRowLse *sh_qrows, const double *shT)
+                                        DraftRowLse *sh_qrows, double *shT, MoreRequests more_requests = MoreRequests())
 {
     const int K = a.K;
     // few rows and slices: one partial per thread, merged across lanes (see lane_merge_commit); else staged in LDS
@@ -304,7 +318,8 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     asm volatile("v_mov_b32 %0, 0" : "=v"(zero));
     int n = a.n_draft[b + zero];
     uint8_t greedy_raw = a.greedy ? a.greedy[b + zero] : (uint8_t)0;
-    const bool own_q = !SHARDED && (a.vflags & kVerifyOwnQ) != 0 && msh >= 0;     // (the host offers own_q for lane-merge shapes only)
+    const double tv = a.exp_table[threadIdx.x];
+    const bool own_q = !SHARDED && (a.vflags & kVerifyOwnQ) != 0 && msh >= 0 && lane_merge_shift(K, a.d_nsplit) >= 0;   // (the host offers own_q for lane-merge shapes only)
     if ((int)threadIdx.x < K) {
         const int64_t i = (int64_t)b * K + threadIdx.x;
         tok0 = a.draft_tok[i];
@@ -319,14 +334,28 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     static_assert(sizeof(RowSlot) * 64 <= sizeof(Partial) * kStageCap, "the row totals reuse the staging buffer");
     if constexpr (SHARDED) {
         const int c0 = min(K + 1, rows_per_stage) * a.nsplit;
-        stage_commit(sh_part, stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1), a.nsplit, c0), c0);
+        const StageRegs st = stage_issue_shards(a.part, (int64_t)a.B * (K + 1), (int64_t)b * (K + 1), a.nsplit, c0);
+        more_requests();
+        shT[threadIdx.x] = tv;
+        stage_commit(sh_part, st, c0);
     } else if (msh >= 0) {
         // target partials run over every element of their slice: plain pieces, nothing left out
+        // all requests first, then one wait for the lot (see lane_merge_pin)
         const LaneRegs ln = lane_merge_issue(a.part + (int64_t)b * (K + 1) * a.nsplit, K + 1, a.nsplit, msh);
-        if (own_q) draft_rows_lse(a.dpart + (int64_t)b * K * a.d_nsplit, K, a.d_nsplit, sh_qrows);   // published by the barrier below
+        const int qsh = own_q ? lane_merge_shift(K, a.d_nsplit) : -1;            // >= 0: the host offers own_q for such shapes only
+        DraftLseRegs lq;
+        if (qsh >= 0) lq = draft_rows_lse_issue(a.dpart + (int64_t)b * K * a.d_nsplit, K, a.d_nsplit, qsh);
+        more_requests();
+        lane_merge_pin(ln, K + 1, msh);
+        shT[threadIdx.x] = tv;
+        if (qsh >= 0) draft_rows_lse_finish(lq, K, a.d_nsplit, qsh, sh_qrows);     // published by the barrier below
         lane_merge_commit<false>(sh_rows, lane_piece(ln, 0, K + 1, a.nsplit, msh), lane_piece(ln, 1, K + 1, a.nsplit, msh), K + 1, msh);
     } else {
-        stage_partials(sh_part, a.part + (int64_t)b * (K + 1) * a.nsplit, min(K + 1, rows_per_stage) * a.nsplit);
+        const int c0 = min(K + 1, rows_per_stage) * a.nsplit;
+        const StageRegs st = stage_issue(a.part + (int64_t)b * (K + 1) * a.nsplit, c0);
+        more_requests();
+        shT[threadIdx.x] = tv;
+        stage_commit(sh_part, st, c0);
     }
     uint32_t f0 = 0;
     n = __builtin_amdgcn_readfirstlane(n);
@@ -541,7 +570,6 @@ __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
     __shared__ DraftRowLse sh_qrows[SHARDED ? 1 : kWave];
     __shared__ double shT[256];
     static_assert(kVBlock == 256, "one table entry per thread");
-    shT[threadIdx.x] = a.exp_table[threadIdx.x];
     verify_head<SHARDED>(a, blockIdx.x, true, sh_part, sh_dec, &sh_flags, sh_bcast, &sh_lse, sh_qrows, shT);
 }
 
@@ -665,18 +693,23 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     // takes the group's last slice: most often none at all, or the row's short last one
     const bool writer = FUSED && blockIdx.x == gridDim.x - 1;
     const int s = blockIdx.x * kWavesPerWG + (writer ? kWavesPerWG - 1 - wave : wave);
-    // The tables are requested first of all: nothing of them depends on the job, and a wavefront's loads return in
-    // order, so requested after the rows they would hold the barrier below until the whole slice has arrived.
+    // The tables are requested early: nothing of them depends on the job, and a wavefront's loads return in order, so
+    // requested after the rows they would hold the barrier below until the whole slice has arrived.  When the accept
+    // decisions run in this kernel they fill the small table themselves and the large one is requested right behind
+    // their own first requests; else both are requested here.
     static_assert(kVBlock == 256, "one entry of the small table per thread");
     constexpr int kRounds = (kTabT || kTabD) ? kTabVecs / kVBlock : 1;
     u32x4 tw[kRounds];
-    const double tv = a.exp_table[threadIdx.x];
-    if constexpr (kTabT || kTabD) {
-        const u32x4 *src = (const u32x4 *)(a.exp_table + 256);
+    double tv = 0.0;
+    if constexpr (!FUSED) tv = a.exp_table[threadIdx.x];
+    auto request_table = [&]() {
+        if constexpr (kTabT || kTabD) {
+            const u32x4 *src = (const u32x4 *)(a.exp_table + 256);
 #pragma unroll
-        for (int q = 0; q < kRounds; ++q) tw[q] = src[q * kVBlock + threadIdx.x];
-    }
-    shT[threadIdx.x] = tv;          // before the accept decisions, which use it (behind their first barrier)
+            for (int q = 0; q < kRounds; ++q) tw[q] = src[q * kVBlock + threadIdx.x];
+        }
+    };
+    if constexpr (!FUSED) request_table();
     SampleJob job;
     if constexpr (FUSED) {
         // Small batches: a head launch of its own costs more (launch, hand-over of the job record through
@@ -689,7 +722,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
         int32_t *sh_bcast = (int32_t *)q;           q += 32;
         uint32_t *sh_flags = (uint32_t *)q;         q += 8;
         uint8_t *sh_dec = q;
-        job = verify_head<false>(a, b, writer, sh_part, sh_dec, sh_flags, sh_bcast, sh_lse, sh_qrows, shT);
+        job = verify_head<false>(a, b, writer, sh_part, sh_dec, sh_flags, sh_bcast, sh_lse, sh_qrows, shT, request_table);
     } else {
         job = a.jobs[j].job;
     }
@@ -706,7 +739,8 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     const bool tab_ok = (kTabT || kTabD) && !(a.vflags & kVerifyNoExpTable) && tab_job_ok(job);
     const bool tab_t = kTabT && tab_ok, tab_d = kTabD && tab_ok && resid;
     const double *shE = (const double *)sh_raw;
-    // the table into LDS before the rows are requested: the wait for it then has nothing younger behind it
+    // the tables into LDS before the rows are requested: the wait for them then has nothing younger behind it
+    if constexpr (!FUSED) shT[threadIdx.x] = tv;
     if constexpr (kTabT || kTabD) {
         if constexpr (FUSED) __syncthreads();                    // every thread is done with the accept decisions' LDS
         if (tab_t || tab_d) {

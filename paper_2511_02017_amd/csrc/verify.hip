@@ -130,27 +130,6 @@ __device__ inline double wave_incl_scan_d(double v, double *total)
     return v;
 }
 
-// Eight consecutive elements j .. j+7 of a row, exact in binary32; -inf beyond V.
-template <int DT>
-__device__ inline void load8(const char *rowp, bool aligned, int j, int V, float (&x)[kPer])
-{
-    if (aligned && j + kPer <= V) {
-        if constexpr (DT == TAPOUT_BF16) {
-            u32x4 w = *(const u32x4 *)(rowp + (int64_t)j * 2);
-            unpack<TAPOUT_BF16>(w, x);
-        } else {
-            u32x4 w0 = *(const u32x4 *)(rowp + (int64_t)j * 4), w1 = *(const u32x4 *)(rowp + (int64_t)j * 4 + 16);
-            float lo[4], hi[4];
-            unpack<TAPOUT_F32>(w0, lo); unpack<TAPOUT_F32>(w1, hi);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { x[i] = lo[i]; x[4 + i] = hi[i]; }
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < kPer; ++i) x[i] = (j + i < V) ? load_elem<DT>(rowp, j + i) : -INFINITY;
-    }
-}
-
 // ---- lse and token logit of the draft rows from the draft pass's partials ----------------
 // For accept decisions that do not wait for the draft epilogue.  A draft partial's S leaves out the batch with the
 // slice's first maximum; pad[1] holds that batch's own sum in the same reference, so S + pad[1] is the sum over the
@@ -234,8 +213,9 @@ __device__ inline void draft_rows_lse_finish(const DraftLseRegs &r, int rows, in
     }
 }
 
-// The same eight elements as they lie in memory (one 16-byte vector of bfloat16, two of binary32), so that a kernel
-// can hold several requests in flight in few registers and widen them when their turn comes.
+// Eight consecutive elements j .. j+7 of a row as they lie in memory (one 16-byte vector of bfloat16, two of binary32;
+// -inf beyond V), so that a kernel can hold several requests in flight in few registers and widen them, exactly, when
+// their turn comes.
 template <int DT> struct Raw8 { u32x4 w[DT == TAPOUT_F32 ? 2 : 1]; };
 template <int DT>
 __device__ inline Raw8<DT> load_raw8(const char *rowp, bool aligned, int j, int V)
@@ -908,9 +888,26 @@ __device__ inline void thread_weights(const Weights &w, const Rows &r, int s, in
     const int j0 = s * kSampleSlice + threadIdx.x * kThreadPer;
 #pragma unroll
     for (int g = 0; g < kThreadPer / kPer; ++g) {
+        // both rows' requests side by side where the run lies inside aligned rows (the usual case): the checks of the
+        // general path are branches, and the compiler waits for the target row's data before it requests the draft row's
+        const int j = j0 + g * kPer;
+        const bool pair = w.kind == 1;
+        Raw8<TD> qt;
+        Raw8<DD> qd = Raw8<DD>{};
+        if (r.t_al && (r.d_al || !pair) && j + kPer <= V) {
+#pragma unroll
+            for (int h = 0; h < (TD == TAPOUT_F32 ? 2 : 1); ++h) qt.w[h] = *(const u32x4 *)(r.trow + (int64_t)j * Elem<TD>::size + 16 * h);
+            if (pair) {
+#pragma unroll
+                for (int h = 0; h < (DD == TAPOUT_F32 ? 2 : 1); ++h) qd.w[h] = *(const u32x4 *)(r.drow + (int64_t)j * Elem<DD>::size + 16 * h);
+            }
+        } else {
+            qt = load_raw8<TD>(r.trow, r.t_al, j, V);
+            if (pair) qd = load_raw8<DD>(r.drow, r.d_al, j, V);
+        }
         float xt[kPer], xd[kPer];
-        load8<TD>(r.trow, r.t_al, j0 + g * kPer, V, xt);
-        if (w.kind == 1) load8<DD>(r.drow, r.d_al, j0 + g * kPer, V, xd);
+        widen8<TD>(qt, xt);
+        widen8<DD>(qd, xd);
 #pragma unroll
         for (int i = 0; i < kPer; ++i) {
             double v = exp_fast(xt[i], w.rp.neg_ref_c, w.rp.lo, T);

@@ -320,6 +320,47 @@ def test_round_with_the_epilogue_beside_the_locate_kernel(name, B, V):
         assert (a_.view(np.int64) == b_.view(np.int64)).all()
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("bad", [False, True])
+def test_round_with_the_epilogue_beside_the_locate_kernel_on_degenerate_rows(dtype, bad):
+    """The same comparison on rows that are uniform, masked, one-hot, tied at the top, equal in draft and target, and
+    (bad) on NaN rows, rows without a finite maximum, tokens out of range and lengths of 0 and K + 1: either place of
+    the draft epilogue gives the same bits, flags included."""
+    rnd = degenerate_round(dtype)
+    B, K, V = rnd["draft"].shape
+    if bad:
+        rnd["draft"][0, 1, 17] = float("nan")
+        rnd["target"][1, 0, 3] = float("nan")
+        rnd["target"][2, 2, :] = float("-inf")
+        rnd["draft_tok"][3, 0] = V
+        rnd["draft_tok"][4, 2] = -1
+        rnd["k_len"][5] = 0
+        rnd["k_len"][6] = K + 1
+    outs = {}
+    for defer in (1, 0):
+        tp = binding.Tapout(B, K, V)
+        tp.set_option("defer_epilogue", defer)
+        arm = tp.bandit_select(B)
+        launch, o = tp.prepare_round_call(rnd, arm, False)
+        launch(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        snap = {"arm": arm.cpu().clone()}
+        snap.update({"d_" + k: v.cpu().clone() for k, v in o["draft"].items()})
+        snap.update({"v_" + k: v.cpu().clone() for k, v in o["verify"].items()})
+        outs[defer] = snap
+    live = (torch.arange(K)[None, :] < rnd["k_len"].cpu().clamp(0, K)[:, None])
+    for k in outs[1]:
+        x, y = outs[1][k], outs[0][k]
+        if k.startswith("d_") and x.dim() == 2 and x.shape == live.shape:
+            x, y = x[live], y[live]                       # rows beyond k_len are not written
+        if x.dtype == torch.float32:
+            x, y = x.view(torch.int32), y.view(torch.int32)
+        assert torch.equal(x, y), k
+    if bad:
+        assert outs[1]["v_flags"].tolist()[1:5] == [orc.FLAG_BAD_ROW, orc.FLAG_BAD_ROW, orc.FLAG_BAD_TOKEN, orc.FLAG_BAD_TOKEN]
+        assert outs[1]["d_flags"].tolist()[0] == orc.FLAG_BAD_ROW
+
+
 @pytest.mark.parametrize("policy", [binding.UCB1, binding.TS_BETA])
 @pytest.mark.parametrize("truncate,five", [(False, False), (True, False), (True, True)])
 def test_whole_round_in_one_call_gives_the_bits_of_the_separate_calls(policy, truncate, five):

@@ -68,13 +68,15 @@ class TapoutError(RuntimeError):
 _lib = None
 
 
-def load_library():
-    """Load the in-tree libtapout.so; raises if it has not been built."""
+def load_library(path: str = None):
+    """Load the in-tree libtapout.so; raises if it has not been built.  `path` (first call only): another build of the
+    same sources, such as the one with time stamps that wg_stamps.py measures with."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2511_02017_amd.build`")
-        lib = C.CDLL(LIB_PATH)
+        path = path or LIB_PATH
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: build it with `python -m paper_2511_02017_amd.build`")
+        lib = C.CDLL(path)
         vp, i32 = C.c_void_p, C.c_int32
         lib.tapout_default_config.restype = None
         lib.tapout_default_config.argtypes = [C.POINTER(TapoutConfig), i32, i32, i32]

@@ -1,7 +1,9 @@
 """Builds libtapout.so (HIP, gfx950) in-tree with hipcc.
 
 Run as `python -m paper_2511_02017_amd.build`.  hipcc cross-compiles without a
-GPU, so this works on a CPU-only machine.
+GPU, so this works on a CPU-only machine.  With `--stamps` it builds
+libtapout_stamps.so beside it instead: the same sources with per-workgroup time
+stamps in the final-token kernels (see wg_stamps.py), for measurements only.
 """
 from __future__ import annotations
 
@@ -15,6 +17,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(CSRC, "_build")
 LIB = os.path.join(PKG, "libtapout.so")
+LIB_STAMPS = os.path.join(PKG, "libtapout_stamps.so")
 SOURCES = ["row_reduce.hip", "finalize.hip", "verify.hip", "bandit.hip", "api.hip"]
 
 FLAGS = [
@@ -33,12 +36,16 @@ def hipcc() -> str:
     raise RuntimeError("hipcc not found")
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
-    os.makedirs(OBJ, exist_ok=True)
+def build(verbose: bool = False, extra_flags=(), stamps: bool = False) -> str:
+    obj_dir = os.path.join(OBJ, "stamps") if stamps else OBJ
+    lib = LIB_STAMPS if stamps else LIB
+    if stamps:
+        extra_flags = (*extra_flags, "-DTAPOUT_WG_STAMPS")
+    os.makedirs(obj_dir, exist_ok=True)
     cc = hipcc()
 
     def compile_one(src):
-        obj = os.path.join(OBJ, src.replace(".hip", ".o"))
+        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
         cmd = [cc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
@@ -52,12 +59,12 @@ def build(verbose: bool = False, extra_flags=()) -> str:
 
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    cmd = [cc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", lib]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    print(build(verbose="-v" in sys.argv, stamps="--stamps" in sys.argv))

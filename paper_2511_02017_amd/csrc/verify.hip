@@ -46,6 +46,27 @@
 
 namespace tapout {
 
+// Per-workgroup time stamps (a build with -DTAPOUT_WG_STAMPS only: `python -m paper_2511_02017_amd.build --stamps`
+// makes libtapout_stamps.so beside the library proper, `python -m paper_2511_02017_amd.wg_stamps` runs it).  The first
+// thread of a workgroup stores the 100 MHz wall clock at a few points of the final-token kernels; the table a stamp goes
+// to and its slots are listed with the reader at the end of this file.  Stamps perturb what they measure by a few
+// tenths of a microsecond per workgroup; the library proper has none of this.
+#ifdef TAPOUT_WG_STAMPS
+constexpr int kStampWgs = 1 << 16;
+__device__ unsigned long long g_stamps_slices[kStampWgs * 8];      // slice kernel, by linear workgroup index
+__device__ unsigned long long g_stamps_head[kStampWgs * 4];        // accept decisions inside it, same index
+__device__ unsigned long long g_stamps_locate[4096 * 8];           // locate kernel (and the draft epilogue's workgroups in its launch)
+#define WG_LINEAR() ((int)(((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) & (kStampWgs - 1)))
+#define WG_STAMP(table, per, wg, slot) do { if (threadIdx.x == 0) table[(wg) * (per) + (slot)] = wall_clock64(); } while (0)
+#define WG_STAMP_LANE0(table, per, wg, slot) do { if ((threadIdx.x & (kWave - 1)) == 0) table[(wg) * (per) + (slot)] = wall_clock64(); } while (0)
+#else
+#define WG_LINEAR() 0
+#define WG_STAMP(table, per, wg, slot) do {} while (0)
+#define WG_STAMP_LANE0(table, per, wg, slot) do {} while (0)
+#endif
+#define HEAD_STAMP(slot) WG_STAMP(g_stamps_head, 4, WG_LINEAR(), slot)
+#define LOCATE_STAMP(slot) WG_STAMP(g_stamps_locate, 8, (int)(blockIdx.x & 4095), slot)
+
 namespace {
 
 constexpr int kVBlock = 256;
@@ -327,9 +348,11 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         if (qsh >= 0) lq = draft_rows_lse_issue(a.dpart + (int64_t)b * K * a.d_nsplit, K, a.d_nsplit, qsh);
         more_requests();
         lane_merge_pin(ln, K + 1, msh);
+        HEAD_STAMP(0);                                           // first requests answered
         shT[threadIdx.x] = tv;
         if (qsh >= 0) draft_rows_lse_finish(lq, K, a.d_nsplit, qsh, sh_qrows);     // published by the barrier below
         lane_merge_commit<false>(sh_rows, lane_piece(ln, 0, K + 1, a.nsplit, msh), lane_piece(ln, 1, K + 1, a.nsplit, msh), K + 1, msh);
+        HEAD_STAMP(1);                                           // rows merged, barrier passed
     } else {
         const int c0 = min(K + 1, rows_per_stage) * a.nsplit;
         const StageRegs st = stage_issue(a.part + (int64_t)b * (K + 1) * a.nsplit, c0);
@@ -432,6 +455,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         }
     }
     constexpr uint32_t kFatal = TAPOUT_FLAG_BAD_NDRAFT | TAPOUT_FLAG_BAD_TOKEN | TAPOUT_FLAG_BAD_ROW;
+    HEAD_STAMP(2);                                               // every row's lse, log p(tok), accept decision
     if (msh >= 0) {
         // Lane-merge path: row k was thread k's, so the rows are lanes of the first wavefront.  Ballots give the
         // first rejection and the flags, lane m hands over what the job needs of row m, one barrier publishes it.
@@ -470,6 +494,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         if (last_k == sh_bcast[0]) { sh_bcast[4] = 1; sh_bcast[5] = __float_as_int(last_M); sh_bcast[6] = last_top1; sh_bcast[7] = __float_as_int(last_dl); *sh_lse = last_lse; }
         __syncthreads();
     }
+    HEAD_STAMP(3);                                               // first rejection published
     const int m = sh_bcast[0];                   // a flagged sequence has m = 0 and emits the argmax of row 0
     const bool flagged = sh_bcast[1] != 0;
     const uint32_t f = (uint32_t)sh_bcast[2];
@@ -666,6 +691,8 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     __shared__ double shT[256];
     __shared__ __align__(16) unsigned char sh_raw[kRaw];
     const int j = blockIdx.z * gridDim.y + blockIdx.y;
+    [[maybe_unused]] const int wg = WG_LINEAR();
+    WG_STAMP(g_stamps_slices, 8, wg, 0);                         // entry
     if (j >= a.n_jobs) return;
     const int b = j / a.jps;
     const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
@@ -706,6 +733,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     } else {
         job = a.jobs[j].job;
     }
+    WG_STAMP(g_stamps_slices, 8, wg, 1);                         // job known
     if (job.kind == 0) return;
     const Rows r = job_rows<TD, DD>(a, b, job);
     const bool live = s < a.nsl;
@@ -764,6 +792,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
         }
     }
     __syncthreads();
+    WG_STAMP(g_stamps_slices, 8, wg, 2);                         // tables in LDS, rows requested
     if (!live) return;
     ExpRef rp, rq;
     rp.set((double)job.ref_p); rq.set((double)job.ref_q);
@@ -847,6 +876,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     } else {
         pass(false_type{}, false_type{});
     }
+    WG_STAMP_LANE0(g_stamps_slices, 8, wg, 3 + wave);            // this wavefront's loop done (slots 3..6)
     double D = 0.5 * (Bs + Ds);
     A = wave_sum_d(A) * sc.ct;
     if (resid) { Bs = wave_sum_d(Bs) * sc.cd; R = wave_sum_d(R) * sc.ct; D = wave_sum_d(D) * sc.cd; U = wave_sum_d(U) * sc.cd; }
@@ -854,6 +884,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
         double *o = a.part1 + ((int64_t)j * a.nsl + s) * kSliceVals;
         o[0] = A; o[1] = Bs; o[2] = R; o[3] = D; o[4] = U;
     }
+    WG_STAMP(g_stamps_slices, 8, wg, 7);                         // first wavefront's sums stored
 }
 
 // ---- locate kernel: one workgroup per sequence --------------------------------------------
@@ -1026,9 +1057,14 @@ template <int TD, int DD, bool TAIL, bool FIN>
 __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFinalArgs fin)
 {
     static_assert(kVBlock == kFinalBlock, "the draft epilogue runs in this kernel's workgroups");
+    LOCATE_STAMP(0);                                             // entry
     if constexpr (FIN)
         if ((int)blockIdx.x < a.B) {
             draft_finalize_body<false>(fin, blockIdx.x);
+#ifdef TAPOUT_WG_STAMPS
+            __syncthreads();
+#endif
+            LOCATE_STAMP(7);                                     // the epilogue's workgroup: done
             return;
         }
     __shared__ double shT[256];
@@ -1078,6 +1114,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
         for (int q = 0; q < kSliceVals; ++q) acc[q] += ps[s * kSliceVals + q];
     if (tid == 0) { shl.last = -1; shl.slice = 0x7fffffff; }
 
+    LOCATE_STAMP(1);                                             // first requests answered
     // totals of the five slice quantities, fixed order
     double tot[kSliceVals];
     {
@@ -1160,6 +1197,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
         return v;
     };
 
+    LOCATE_STAMP(2);                                             // total weight known (certified, settled or recomputed)
     int token = -1;
     if (Z > 0.0) {
         const double target = u * Z;
@@ -1202,6 +1240,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
             cum_at = shl.bc[0]; s_found = shl.slice;
             __syncthreads();
         }
+        LOCATE_STAMP(3);                                         // slice found
         // slice sums and the in-slice scan round differently: if the crossing is not inside the chosen
         // slice, continue into the following ones
         if (s_found >= 0) {
@@ -1224,6 +1263,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
             token = shl.last;
         }
     }
+    LOCATE_STAMP(4);                                             // token found
     if (tid == 0) {
         if (token < 0) token = 0;
         if (a.tok_direct) a.tok_direct[j] = token;
@@ -1235,6 +1275,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
         }
     }
     end_round();
+    LOCATE_STAMP(5);                                             // round ended (bandit update, next arm)
 }
 
 // ---- draft-token sampling: one job per draft row --------------------------------------------
@@ -1486,3 +1527,24 @@ hipError_t launch_verify(const VerifyArgs &a, int pass, hipStream_t st, Timing t
 }
 
 }  // namespace tapout
+
+#ifdef TAPOUT_WG_STAMPS
+// Copies one stamp table to the host (synchronises the device).  table 0: slice kernel, 8 slots per workgroup
+// (0 entry, 1 job known, 2 tables in LDS and rows requested, 3..6 each wavefront's loop done, 7 sums stored);
+// table 1: accept decisions inside the slice kernel, 4 slots (0 first requests answered, 1 rows merged, 2 decisions
+// taken, 3 first rejection published); table 2: locate kernel, 8 slots by blockIdx.x (0 entry, 1 first requests
+// answered, 2 total weight known, 3 slice found, 4 token found, 5 round ended; 7: a draft epilogue workgroup is done).
+// Units: 10 ns.  Not part of the library's interface.
+extern "C" __attribute__((visibility("default"))) int tapout_debug_wg_stamps(int table, unsigned long long *host, int n_wg)
+{
+    if (!host || n_wg < 0) return -1;
+    if (hipDeviceSynchronize() != hipSuccess) return -2;
+    if (table == 0 && n_wg <= tapout::kStampWgs)
+        return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(tapout::g_stamps_slices), (size_t)n_wg * 8 * sizeof(unsigned long long));
+    if (table == 1 && n_wg <= tapout::kStampWgs)
+        return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(tapout::g_stamps_head), (size_t)n_wg * 4 * sizeof(unsigned long long));
+    if (table == 2 && n_wg <= 4096)
+        return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(tapout::g_stamps_locate), (size_t)n_wg * 8 * sizeof(unsigned long long));
+    return -1;
+}
+#endif

@@ -49,8 +49,8 @@ namespace tapout {
 // Per-workgroup time stamps (a build with -DTAPOUT_WG_STAMPS only: `python -m paper_2511_02017_amd.build --stamps`
 // makes libtapout_stamps.so beside the library proper, `python -m paper_2511_02017_amd.wg_stamps` runs it).  The first
 // thread of a workgroup stores the 100 MHz wall clock at a few points of the final-token kernels; the table a stamp goes
-// to and its slots are listed with the reader at the end of this file.  Stamps perturb what they measure by a few
-// tenths of a microsecond per workgroup; the library proper has none of this.
+// to and its slots are listed with the reader at the end of this file.  Stamps stretch what they measure (each is a scalar
+// memory instruction the wavefront waits for: a few tenths of a microsecond); the library proper has none of this.
 #ifdef TAPOUT_WG_STAMPS
 constexpr int kStampWgs = 1 << 16;
 __device__ unsigned long long g_stamps_slices[kStampWgs * 8];      // slice kernel, by linear workgroup index

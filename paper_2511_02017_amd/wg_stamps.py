@@ -5,8 +5,9 @@
 
 Runs rounds of a synthetic workload (default llama3) through tapout_round on the stamped build and prints, for the
 last round, how long the workgroups of the slice kernel and of the locate kernel spent between their stamps: minimum,
-median, 90th percentile, maximum over the workgroups, in microseconds.  The stamps cost a few tenths of a microsecond
-per workgroup; rocprofv3 and bench.py time the library proper.
+median, 90th percentile, maximum over the workgroups, in microseconds.  The stamps stretch what they measure (each is a
+scalar memory instruction its wavefront waits for): read the segments relative to each other; rocprofv3 and bench.py
+time the library proper.
 """
 from __future__ import annotations
 

@@ -570,13 +570,23 @@ TAPOUT_API tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *pre
  *                 runs beside the final-token locate kernel in one launch;
  *                 0 = the epilogue keeps its own launch ahead of the
  *                 verification, which then reads the logq_tok it wrote
+ *   "exp_lookup"  final token: 1 (default) = where the target row and the
+ *                 draft row are both bfloat16, the slice kernel takes
+ *                 exp(logit) from a table of the 2 x 2304 bfloat16 values
+ *                 with 2^-12 <= |x| < 63.75 (correctly rounded doubles, built
+ *                 at tapout_create, held in LDS) and applies the rows'
+ *                 references to the slice sums; rows whose references fall
+ *                 outside the table's range, and other element types,
+ *                 compute each exponential; 0 = always compute
  *   "profile_stride"  kernel timing (below) attaches events to every n-th
  *                 launch of a selected kernel only, default 1: an event pair
  *                 costs a few microseconds of the stream's time per launch
  * Results do not depend on these values except through the rounding of the
  * binary32 partial sums ("fuse_head", "profile_stride": not at all;
  * "defer_epilogue": an accept decision whose uniform lies within 1e-6
- * (relative) of p/q may fall the other way).
+ * (relative) of p/q may fall the other way; "exp_lookup": the slice sums
+ * agree to 2e-13 relative, so a final token whose inverse-CDF target lies that
+ * close to a cell edge may move to the neighbouring cell).
  */
 TAPOUT_API tapout_status tapout_set_option(tapout_ctx *ctx, const char *name, int32_t value);
 

@@ -143,6 +143,28 @@ struct BanditArgs {
 // Verification + final token: the head kernel merges the target partials of each sequence, takes the
 // accept decisions and describes the final-token draw (SampleJob); the slice kernel sums the row pair
 // per slice; the locate kernel finds the token.
+// Kernel arguments sit in device memory and reach a wavefront through the scalar cache, one 64-byte line per miss,
+// and the compiler loads a field where the code first wants it: a kernel that is a chain of round trips anyway takes
+// a miss of this kind at several points along the chain (with the arguments in host memory instead, the final-token
+// launches of a Llama-3-vocabulary round take 4.6 and 6.5 us longer).  Reading one word of every line first thing
+// makes them one round trip; the later loads hit.  (The hidden arguments behind the declared ones, grid and
+// workgroup sizes, are one more line: the kernels on the round's critical path do not read them.)
+template <class T>
+__device__ inline int32_t arg_lines(const T &a)
+{
+    const int32_t *w = reinterpret_cast<const int32_t *>(&a);
+    int32_t acc = w[sizeof(T) / 4 - 1];
+#pragma unroll
+    for (size_t i = 0; i < sizeof(T) / 4; i += 16) acc |= w[i];
+    return acc;
+}
+template <class... Ts>
+__device__ inline void warm_args(const Ts &...as)
+{
+    const int32_t acc = (arg_lines(as) | ...);
+    asm volatile("" :: "s"(acc));
+}
+
 constexpr int32_t kVerifyOwnQ = 1;          // accept decisions form log q(tok) from the draft partials (see dpart)
 constexpr int32_t kVerifyNoExpTable = 2;    // final-token slice kernel: computed exponentials also for bfloat16 row pairs
 // (Kept at 512 bytes or less: past that the compiler reaches the arguments differently and the fused slice kernel
@@ -298,7 +320,7 @@ __device__ inline void stage_partials(Partial *sh, const Partial *src, int count
 {
     const u32x4 *s = (const u32x4 *)src;
     u32x4 *d = (u32x4 *)sh;
-    for (int i = threadIdx.x; i < 2 * count; i += blockDim.x) d[i] = s[i];
+    for (int i = threadIdx.x; i < 2 * count; i += kBlock) d[i] = s[i];      // (256-thread workgroups)
     __syncthreads();
 }
 

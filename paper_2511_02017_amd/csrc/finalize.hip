@@ -28,6 +28,7 @@ namespace {
 template <bool SHARDED>
 __global__ __launch_bounds__(kFinalBlock) void draft_finalize_kernel(DraftFinalArgs a)
 {
+    warm_args(a);
     draft_finalize_body<SHARDED>(a, blockIdx.x);
 }
 

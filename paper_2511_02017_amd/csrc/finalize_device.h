@@ -9,6 +9,7 @@
 namespace tapout {
 
 constexpr int kFinalBlock = 256;
+static_assert(kFinalBlock == kBlock, "stage_partials strides by kBlock");
 
 __device__ inline bool rule_fires(int rule, float h, float H, float p1, float margin)
 {
@@ -135,7 +136,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
     // back in, exact index of the first maximum into the cand slot) before the rows are merged one by one.
     auto complete_stage = [&](int k0, int count) {
         if constexpr (!SHARDED) {
-            for (int i = threadIdx.x; i < count; i += blockDim.x) {
+            for (int i = threadIdx.x; i < count; i += kFinalBlock) {
                 const int k = k0 + i / a.nsplit, sl = i % a.nsplit;
                 if (k >= kb) continue;                          // stale partial of a row that was not drafted
                 Piece e = piece_from_partial(sh_part[i]);
@@ -173,7 +174,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
                 if (want_tok && kmine < k1 && tok0 >= 0 && tok0 < a.V)
                     xtok0 = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, kmine), a.dtype, tok0);
         }
-        for (int k = kmine; k < k1; k += blockDim.x) {
+        for (int k = kmine; k < k1; k += kFinalBlock) {
             const int64_t i = (int64_t)b * K + k;
             const void *row = SHARDED ? nullptr : row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, k);
             const RowTotal r = msh >= 0 ? sh_rows[k].r : merge_partials<true>(sh_part + (k - k0) * a.nsplit, a.nsplit);
@@ -249,7 +250,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
     }
     __syncthreads();                       // orders the LDS / scratch writes above before the scan
     if (sweep) {
-        for (int k = threadIdx.x; k < kb; k += blockDim.x) {
+        for (int k = threadIdx.x; k < kb; k += kFinalBlock) {
             if (sh_dec[k] != 2) continue;
             const int arm_k = tok_mode ? a.arm[(int64_t)b * a.arm_stride + k] : arm;      // in range: checked when it was marked
             const float H = sh_H[k];

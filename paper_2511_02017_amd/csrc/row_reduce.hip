@@ -435,6 +435,7 @@ __device__ inline void stream_pass_body(const RowReduceArgs &a, const int split,
 template <int DT, bool FULL>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) void stream_pass_kernel(RowReduceArgs a)
 {
+    warm_args(a);
     stream_pass_body<DT, FULL>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
@@ -445,6 +446,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) voi
 template <int DD, int TD>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6))) void stream_pair_kernel(RowReduceArgs d, RowReduceArgs t, int n_seq)
 {
+    warm_args(d, t);
     const int z = blockIdx.z;
     if (z < n_seq) {
         if ((int)blockIdx.y < d.KK && (int)blockIdx.x < d.nsplit) stream_pass_body<DD, true>(d, blockIdx.x, blockIdx.y, z);

@@ -70,6 +70,7 @@ __device__ unsigned long long g_stamps_locate[4096 * 8];           // locate ker
 namespace {
 
 constexpr int kVBlock = 256;
+static_assert(kVBlock == kBlock, "stage_partials strides by kBlock");
 constexpr int kPer = 8;                       // elements per 16-byte (bf16) / 32-byte (f32) run
 
 
@@ -388,7 +389,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                 stage_partials(sh_part, a.part + ((int64_t)b * (K + 1) + k0) * a.nsplit, (k1 - k0) * a.nsplit);
             }
         }
-        for (int k = kmine; k < k1; k += blockDim.x) {
+        for (int k = kmine; k < k1; k += kVBlock) {
             const int64_t it = (int64_t)b * (K + 1) + k;
             const void *row = SHARDED ? nullptr : row_address(a.tbase, a.t_dtype, a.t_stride_b, a.t_stride_k, b, k);
             // shard records leave their first maximum out of the sums (and carry its exact index), slice partials of
@@ -538,7 +539,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
             if (a.flags) a.flags[b] = f;
         }
         int32_t *o = a.out_tok + (int64_t)b * (K + 1);
-        for (int k = threadIdx.x; k <= K; k += blockDim.x) {
+        for (int k = threadIdx.x; k <= K; k += kVBlock) {
             // (lane-merge path: thread k still holds row k's token from the first round trip)
             o[k] = k < m ? ((msh >= 0 && k == (int)threadIdx.x) ? tok0 : a.draft_tok[(int64_t)b * K + k]) : (k == m ? final_tok : -1);
             if (flagged && a.logp_tok && k < n) a.logp_tok[(int64_t)b * K + k] = NAN;
@@ -567,6 +568,7 @@ __device__ inline Rows job_rows(const VerifyArgs &a, int b, const SampleJob &job
 template <bool SHARDED>
 __global__ __launch_bounds__(kVBlock) void verify_head_kernel(VerifyArgs a)
 {
+    warm_args(a);
     __shared__ Partial sh_part[kStageCap];
     __shared__ uint8_t sh_dec[kScanCap];
     __shared__ uint32_t sh_flags;
@@ -690,7 +692,9 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     constexpr size_t kRaw = (FUSED && kHeadBytes > kTabBytes) ? kHeadBytes : (kTabBytes > 0 ? kTabBytes : 16);
     __shared__ double shT[256];
     __shared__ __align__(16) unsigned char sh_raw[kRaw];
-    const int j = blockIdx.z * gridDim.y + blockIdx.y;
+    warm_args(a);
+    // (the grid's shape from the arguments, not from the hidden ones: see warm_args)
+    const int j = blockIdx.z * min(a.n_jobs, 65535) + blockIdx.y;
     [[maybe_unused]] const int wg = WG_LINEAR();
     WG_STAMP(g_stamps_slices, 8, wg, 0);                         // entry
     if (j >= a.n_jobs) return;
@@ -698,7 +702,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
     // FUSED: the sequence's last workgroup writes the sequence's outputs, from its first wavefront, which therefore
     // takes the group's last slice: most often none at all, or the row's short last one
-    const bool writer = FUSED && blockIdx.x == gridDim.x - 1;
+    const bool writer = FUSED && (int)blockIdx.x == (a.nsl + kWavesPerWG - 1) / kWavesPerWG - 1;
     const int s = blockIdx.x * kWavesPerWG + (writer ? kWavesPerWG - 1 - wave : wave);
     // The tables are requested early: nothing of them depends on the job, and a wavefront's loads return in order, so
     // requested after the rows they would hold the barrier below until the whole slice has arrived.  When the accept
@@ -1056,6 +1060,7 @@ __device__ __noinline__ double settle_band(const Weights &w, const Rows &r, int 
 template <int TD, int DD, bool TAIL, bool FIN>
 __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFinalArgs fin)
 {
+    if constexpr (FIN) warm_args(a, fin); else warm_args(a);
     static_assert(kVBlock == kFinalBlock, "the draft epilogue runs in this kernel's workgroups");
     LOCATE_STAMP(0);                                             // entry
     if constexpr (FIN)

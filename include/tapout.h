@@ -572,8 +572,8 @@ TAPOUT_API tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *pre
  *                 verification, which then reads the logq_tok it wrote
  *   "exp_lookup"  final token: 1 (default) = where the target row and the
  *                 draft row are both bfloat16, the slice kernel takes
- *                 exp(logit) from a table of the 2 x 2304 bfloat16 values
- *                 with 2^-12 <= |x| < 63.75 (correctly rounded doubles, built
+ *                 exp(logit) from a table of the 2 x 2302 bfloat16 values
+ *                 with 2^-12 <= |x| < 63.5 (correctly rounded doubles, built
  *                 at tapout_create, held in LDS) and applies the rows'
  *                 references to the slice sums; rows whose references fall
  *                 outside the table's range, and other element types,

@@ -6,6 +6,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <limits>
 #include <vector>
 
 #include "common.h"
@@ -273,17 +274,25 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
     c->nsl_max = (cfg->vocab + kSampleSlice - 1) / kSampleSlice;
     // final-token jobs: one per sequence (verification) or one per draft row (draft-token sampling)
     const size_t njobs = (size_t)cfg->max_batch * (cfg->draft_sampling ? cfg->max_k : 1);
-    // 2^(k/256), then exp(x) of every bfloat16 x with 2^-12 <= |x| < 63.75: entry 2 idx + sign, magnitude bits
-    // (115 << 7) + idx; the last pair stands for all larger magnitudes and holds zeros
+    // 2^(k/256), then exp(x) of every bfloat16 x with 2^-12 <= |x| < 63.5: entry idx (x > 0) or pairs + idx (x < 0),
+    // idx = 1 + (magnitude bits - (115 << 7)); idx 0 stands for all smaller magnitudes and holds NaN (the kernels
+    // notice and compute), the last idx for all larger ones and holds zeros
     std::vector<double> table(256 + kExpBf16Doubles);
     for (int k = 0; k < 256; ++k) table[k] = std::exp2((double)k / 256.0);
-    for (int idx = 0; idx < kExpBf16Doubles / 2; ++idx) {
-        const uint32_t bits = (uint32_t)((115 << 7) + idx) << 16;
-        float x;
-        memcpy(&x, &bits, sizeof x);
-        const bool last = idx == kExpBf16Doubles / 2 - 1;
-        table[256 + 2 * idx] = last ? 0.0 : std::exp((double)x);
-        table[256 + 2 * idx + 1] = last ? 0.0 : std::exp(-(double)x);
+    const int pairs = kExpBf16Doubles / 2;
+    for (int idx = 0; idx < pairs; ++idx) {
+        double pos, neg;
+        if (idx == 0) pos = neg = std::numeric_limits<double>::quiet_NaN();
+        else if (idx == pairs - 1) pos = neg = 0.0;
+        else {
+            const uint32_t bits = (uint32_t)((115 << 7) + idx - 1) << 16;
+            float x;
+            memcpy(&x, &bits, sizeof x);
+            pos = std::exp((double)x);
+            neg = std::exp(-(double)x);
+        }
+        table[256 + idx] = pos;
+        table[256 + pairs + idx] = neg;
     }
     bool ok = hipMalloc(&c->part, c->part_cap * sizeof(Partial)) == hipSuccess
            && hipMalloc(&c->part_t, c->part_cap * sizeof(Partial)) == hipSuccess

@@ -49,7 +49,7 @@ struct SampleJob {
 
 static_assert(sizeof(tapout_final_job) == sizeof(SampleJob), "the public job record is the internal one");
 
-constexpr int kExpBf16Doubles = 4608;   // exp(x) of the bfloat16 values with 2^-12 <= |x| < 63.75, both signs (see the final-token slice kernel)
+constexpr int kExpBf16Doubles = 4608;   // exp(x) of the bfloat16 values with 2^-12 <= |x| < 63.5, both signs, and two stand-in pairs (see the final-token slice kernel)
 
 constexpr int kBandCap = 32;         // band elements per job the locate kernel settles one by one; more: exact slow path
 

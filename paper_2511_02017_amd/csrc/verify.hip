@@ -590,47 +590,62 @@ constexpr int kChunks = kSampleSlice / (kWave * kPer);          // a wavefront t
 
 // ---- exponentials of bfloat16 logits from a table -----------------------------------------
 // A bfloat16 logit has 2^16 possible values, and those between 2^-12 and 2^6 in magnitude (all a softmax row holds
-// besides masked entries and the odd tiny one) are 2 * 2303 of them: exp(x) itself, correctly rounded on the host,
-// comes from a table of 36 KB in LDS with five integer instructions and one LDS read instead of the thirteen
+// besides masked entries and the odd tiny one) are 2 * 2302 of them: exp(x) itself, correctly rounded on the host,
+// comes from a table of 36 KB in LDS with four integer instructions and one LDS read instead of the thirteen
 // instructions of exp_fast.  The row's exponent reference is applied once per slice, to the sums:
 //   a_j = exp(t_j - ref_p) = E[t_j] c_t,  b_j = exp(d_j - ref_q) = E[d_j] c_d,   c_t = exp(-ref_p), c_d = exp(-ref_q)
 //   a_j - L~ b_j = c_t (E[t_j] - L' E[d_j]),  L' = L~ c_d / c_t
 // so the slice kernel sums E[t], E[d], max(0, E[t] - L' E[d]), ... and scales A, R~ by c_t and B, D, U by c_d at the
 // end.  A row of another element type keeps exp_fast and c = 1.
-// Entry idx (0 .. kTabN - 1) is the magnitude with bfloat16 bits (kTabLo32 >> 16) + idx; entry kTabN stands for
-// every magnitude from 63.75 up (and NaN): 0 for either sign.  That is exact for -inf (a masked entry) and an error
-// below e^-49 of the row's largest term for any other logit <= -63.75 given the condition on the references that
-// tab_job_ok checks (row maxima in [-14, 63)); a job outside it takes the computed exponentials.  Magnitudes below
-// 2^-12 (and zeros) are not in the table: the slice kernel notices them per chunk and forms that chunk again with
-// tab_exp_any, which evaluates 1 + x + x^2/2 + x^3/6 for them (error < 2e-16).  Layout: T[2 idx + sign].
-constexpr int kTabN = 18 * 128 - 1;
-constexpr uint32_t kTabLo32 = (uint32_t)(127 - 12) << 23;            // binary32 bits of 2^-12
-constexpr int kTabDoubles = 2 * (kTabN + 1);                         // 4608 doubles = 36,864 bytes
+// Layout: T[idx] for positive values, T[kTabTop + 1 + idx] for negative ones (kept apart: with the two signs of a
+// magnitude side by side a wavefront's 64 reads fall on half as many LDS banks).  Entry idx = 1 .. kTabTop - 1 is
+// the magnitude with bfloat16 bits kTabLo15 + idx - 1.
+// Entry kTabTop stands for every magnitude from 63.5 up (and NaN): 0 for either sign.  That is exact for -inf (a
+// masked entry) and an error below e^-49 of the row's largest term for any other logit <= -63.5 given the condition
+// on the references that tab_job_ok checks (row maxima in [-14, 63)); a job outside it takes the computed
+// exponentials.  Entry 0 stands for the magnitudes below 2^-12 (and zeros), which are not in the table, and holds
+// NaN: a chunk's sums show that it met one, and the slice kernel forms that chunk again with tab_exp_any, which
+// evaluates 1 + x + x^2/2 + x^3/6 for them (error < 2e-16).
+constexpr int kTabTop = 18 * 128 - 1;
+constexpr uint32_t kTabLo15 = (uint32_t)(127 - 12) << 7;            // bfloat16 magnitude bits of 2^-12
+constexpr int kTabDoubles = 2 * (kTabTop + 1);                       // 4608 doubles = 36,864 bytes
 constexpr int kTabVecs = kTabDoubles / 2;                            // 16-byte vectors
 static_assert(kTabVecs % kVBlock == 0, "the table is copied to LDS in whole rounds of the workgroup");
 static_assert(kTabDoubles == kExpBf16Doubles, "the host builds the table");
+static_assert(8 * (2 * kTabTop + 1) < 65536, "an entry's byte offset fits sixteen bits");
 
-// x: a bfloat16 value widened to binary32 (low 16 bits zero).  *tiny gets the lanes whose magnitude lies below
-// the table (their result here is 0 and must be replaced).
-__device__ inline double tab_lookup(float x, const double *T, uint64_t *tiny)
+// Two bfloat16 values as they lie in one word -> the byte offsets of their entries, again as two halves of a word.
+// Both halves are worked on at once with the packed 16-bit integer instructions: eight instructions for two
+// look-ups, the two that take the word apart included (one value at a time it was nine each).
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+__device__ inline uint32_t tab_offsets2(uint32_t w)
+{
+    const uint32_t mag = w & 0x7fff7fffu;
+    u16x2 d = __builtin_elementwise_sub_sat(__builtin_bit_cast(u16x2, mag), (u16x2)(unsigned short)(kTabLo15 - 1));   // 0: below the table
+    d = __builtin_elementwise_min(d, (u16x2)(unsigned short)kTabTop);
+    d = d << (u16x2)(unsigned short)3;
+    typedef short i16x2 __attribute__((ext_vector_type(2)));
+    const i16x2 neg = __builtin_bit_cast(i16x2, w) >> (i16x2)(short)15;           // all ones in the half of a negative value
+    d += __builtin_bit_cast(u16x2, neg) & (u16x2)(unsigned short)(8 * (kTabTop + 1));
+    return __builtin_bit_cast(uint32_t, d);
+}
+// x: a bfloat16 value widened to binary32 (low 16 bits zero); same entry as tab_offsets2 finds.
+__device__ inline double tab_lookup(float x, const double *T)
 {
     const uint32_t u = __float_as_uint(x);
-    const uint32_t d2 = (u << 1) - 2u * kTabLo32;                   // (magnitude bits - kTabLo32) << 1; wraps for tiny magnitudes
-    *tiny |= __builtin_amdgcn_ballot_w64(d2 >= 0u - 2u * kTabLo32);
-    const uint32_t idx16 = min(d2, (uint32_t)kTabN << 17) >> 13;    // byte offset of the entry pair: 16 * idx
-    const uint32_t off = idx16 | ((u >> 28) & 8u);                  // + 8 for negative x
-    return *(const double *)((const char *)T + off);
+    const uint32_t m = (u >> 16) & 0x7fffu;
+    const uint32_t d = min(max(m, kTabLo15 - 1) - (kTabLo15 - 1), (uint32_t)kTabTop);
+    return T[d + (u >> 31) * (uint32_t)(kTabTop + 1)];
 }
-// Any binary32-widened bfloat16 value, with the same bits as tab_lookup wherever that one applies.
+// Any binary32-widened bfloat16 value, with the same bits as the table wherever it applies.
 __device__ inline double tab_exp_any(float x, const double *T)
 {
     const uint32_t u = __float_as_uint(x);
-    if ((u << 1) < 2u * kTabLo32) {
+    if (((u >> 16) & 0x7fffu) < kTabLo15) {
         const double t = (double)x;
         return fma(t, fma(t, fma(t, 1.0 / 6.0, 0.5), 1.0), 1.0);
     }
-    uint64_t unused = 0;
-    return tab_lookup(x, T, &unused);
+    return tab_lookup(x, T);
 }
 __device__ inline bool tab_job_ok(const SampleJob &job)
 {
@@ -650,21 +665,19 @@ __device__ inline TabScale tab_scale(const SampleJob &job, bool tab_t, bool tab_
 }
 
 // Adds the sums of one chunk (8 elements per lane) of a row pair to cA .. cDs.  TABT / TABD: that row's exponentials come from the
-// table; SLOW: through tab_exp_any (chunks with tiny magnitudes).
-template <bool TABT, bool TABD, bool SLOW>
+// table, through tab_exp_any (the chunks that chunk_pair_tab cannot take: tiny magnitudes; band elements).
+template <bool TABT, bool TABD>
 __device__ inline void chunk_pair(const float (&ct)[kPer], const float (&cd)[kPer], const ExpRef &rp, const ExpRef &rq,
                                   const double *shT, const double *shE, double c2, float top, double Lp, double band,
-                                  double &cA, double &cB, double &cR, double &cDs, uint64_t &any_band, uint64_t &any_tiny)
+                                  double &cA, double &cB, double &cR, double &cDs, uint64_t &any_band)
 {
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
         double av, bv;
         if constexpr (!TABT) av = exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
-        else if constexpr (SLOW) av = tab_exp_any(ct[i], shE);
-        else av = tab_lookup(ct[i], shE, &any_tiny);
+        else av = tab_exp_any(ct[i], shE);
         if constexpr (!TABD) bv = exp_fast(cd[i], rq.neg_ref_c, rq.lo, shT, c2, top);
-        else if constexpr (SLOW) bv = tab_exp_any(cd[i], shE);
-        else bv = tab_lookup(cd[i], shE, &any_tiny);
+        else bv = tab_exp_any(cd[i], shE);
         const double diff = fma(-Lp, bv, av);
         cA += av;
         cB += bv;
@@ -674,6 +687,42 @@ __device__ inline void chunk_pair(const float (&ct)[kPer], const float (&cd)[kPe
         // per chunk instead of one per element (a branch on a fresh vector comparison stalls the wavefront)
         any_band |= __builtin_amdgcn_ballot_w64(fabs(diff) < band * bv);      // strict: an entry with b = 0 (masked, beyond V) is no band element
     }
+}
+// The same sums for a chunk of two bfloat16 rows as it lies in memory (four words of two values each), every
+// exponential straight from the table in LDS; same order of additions.  A value below the table's range makes
+// the sums NaN (entry 0).
+__device__ inline void chunk_pair_tab(const u32x4 &wt, const u32x4 &wd, const double *shE, double Lp, double band,
+                                      double &cA, double &cB, double &cR, double &cDs, uint64_t &any_band)
+{
+    const char *E = (const char *)shE;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t ot = tab_offsets2(wt[k]), od = tab_offsets2(wd[k]);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const double av = *(const double *)(E + (h ? ot >> 16 : ot & 0xffffu));
+            const double bv = *(const double *)(E + (h ? od >> 16 : od & 0xffffu));
+            const double diff = fma(-Lp, bv, av);
+            cA += av;
+            cB += bv;
+            cR += fmax(diff, 0.0);
+            cDs += copysign(bv, diff);
+            any_band |= __builtin_amdgcn_ballot_w64(fabs(diff) < band * bv);
+        }
+    }
+}
+// One row alone: the sum of its exponentials over a chunk.
+__device__ inline double chunk_one_tab(const u32x4 &wt, const double *shE)
+{
+    const char *E = (const char *)shE;
+    double cA = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t ot = tab_offsets2(wt[k]);
+        cA += *(const double *)(E + (ot & 0xffffu));
+        cA += *(const double *)(E + (ot >> 16));
+    }
+    return cA;
 }
 
 // One wavefront per slice, four slices per workgroup.  A wavefront takes its slice in chunks of one 8-element run per
@@ -823,20 +872,21 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
             widen8<TD>(qt[c], ct);
             widen8<DD>(qd[c], cd);
             if (resid) {
-                uint64_t any_band = 0, any_tiny = 0;
-                if constexpr (TT || TD_) {
-                    // a chunk that holds a magnitude below the table's range is formed again, the slow way
+                uint64_t any_band = 0;
+                if constexpr (TT && TD_) {
                     double cA = 0.0, cB = 0.0, cR = 0.0, cDs = 0.0;
-                    chunk_pair<TT, TD_, false>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, cA, cB, cR, cDs, any_band, any_tiny);
-                    if (any_tiny != 0) {
+                    chunk_pair_tab(qt[c].w[0], qd[c].w[0], shE, lam, band, cA, cB, cR, cDs, any_band);
+                    // a chunk that holds a magnitude below the table's range is formed again, the slow way
+                    if (__builtin_amdgcn_ballot_w64(cA != cA || cB != cB) != 0) {
                         asm volatile("" ::: "memory");
                         any_band = 0;
                         cA = 0.0; cB = 0.0; cR = 0.0; cDs = 0.0;
-                        chunk_pair<TT, TD_, true>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, cA, cB, cR, cDs, any_band, any_tiny);
+                        chunk_pair<true, true>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, cA, cB, cR, cDs, any_band);
                     }
                     A += cA; Bs += cB; R += cR; Ds += cDs;
                 } else {
-                    chunk_pair<false, false, false>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, A, Bs, R, Ds, any_band, any_tiny);
+                    static_assert(!TT && !TD_, "the table serves both rows or neither");
+                    chunk_pair<false, false>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, A, Bs, R, Ds, any_band);
                 }
                 if (any_band != 0) {
                     asm volatile("" ::: "memory");                  // keep this a branch: a select would cost every element
@@ -854,29 +904,28 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
                     }
                 }
             } else {
-                uint64_t any_tiny = 0;
                 double cA = 0.0;
-#pragma unroll
-                for (int i = 0; i < kPer; ++i) cA += TT ? tab_lookup(ct[i], shE, &any_tiny) : exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
-                if constexpr (TT)
-                    if (any_tiny != 0) {
+                if constexpr (TT) {
+                    cA = chunk_one_tab(qt[c].w[0], shE);
+                    if (__builtin_amdgcn_ballot_w64(cA != cA) != 0) {
                         asm volatile("" ::: "memory");
                         cA = 0.0;
 #pragma unroll
                         for (int i = 0; i < kPer; ++i) cA += tab_exp_any(ct[i], shE);
                     }
+                } else {
+#pragma unroll
+                    for (int i = 0; i < kPer; ++i) cA += exp_fast(ct[i], rp.neg_ref_c, rp.lo, shT, c2, top);
+                }
                 A += cA;
             }
         }
     };
     using std::false_type; using std::true_type;
-    if constexpr (kTabT && kTabD) {
-        // the target row always comes with the draft row here except for jobs on one row (tab_d false: no draft row)
+    static_assert(kTabT == kTabD, "the table serves both rows or neither");
+    if constexpr (kTabT) {
+        // (a job on one row, the bonus position, has no draft row: the pass then sums the target row alone)
         if (tab_t) pass(true_type{}, true_type{}); else pass(false_type{}, false_type{});
-    } else if constexpr (kTabT) {
-        if (tab_t) pass(true_type{}, false_type{}); else pass(false_type{}, false_type{});
-    } else if constexpr (kTabD) {
-        if (tab_d) pass(false_type{}, true_type{}); else pass(false_type{}, false_type{});
     } else {
         pass(false_type{}, false_type{});
     }

@@ -68,7 +68,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
     LaneRegs ln0;
     st0.w0 = st0.w1 = ln0.p[0].w0 = ln0.p[0].w1 = ln0.p[1].w0 = ln0.p[1].w1 = u32x4{0u, 0u, 0u, 0u};
     if constexpr (SHARDED) st0 = stage_issue_shards(a.part, (int64_t)a.B * K, (int64_t)b * K, a.nsplit, count0);
-    else if (msh >= 0) ln0 = lane_merge_issue(a.part + (int64_t)b * K * a.nsplit, K, a.nsplit, msh);
+    else if (__builtin_expect(msh >= 0, 1)) ln0 = lane_merge_issue(a.part + (int64_t)b * K * a.nsplit, K, a.nsplit, msh);
     else st0 = stage_issue(a.part + (int64_t)b * K * a.nsplit, count0);
     asm volatile("" :: "v"(kb), "v"(arm), "v"(H_carry), "v"(tok0), "v"(st0.w0), "v"(st0.w1), "v"(ln0.p[0].w0), "v"(ln0.p[0].w1), "v"(ln0.p[1].w0), "v"(ln0.p[1].w1));
     kb = kb > K ? K : (kb < 0 ? 0 : kb);
@@ -79,7 +79,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
         if (want_tok && (int)threadIdx.x < K && tok0 >= 0 && tok0 < a.V)
             xtok_first = load_elem_rt(row_address(a.base, a.dtype, a.stride_b, a.stride_k, b, threadIdx.x), a.dtype, tok0);
     if (threadIdx.x == 0) sh_flags = 0;                       // ahead of the barrier in the commit: rows of other wavefronts OR into it
-    if (msh >= 0) {
+    if (__builtin_expect(msh >= 0, 1)) {
         Piece e[2];
         BatchRegs bt[2];
         const int sl = threadIdx.x & ((1 << msh) - 1);
@@ -147,7 +147,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
             __syncthreads();
         }
     };
-    if (msh < 0) complete_stage(0, count0);
+    if (__builtin_expect(msh < 0, 0)) complete_stage(0, count0);
     const bool arm_ok = arm >= 0 && arm < a.n_arms;
     const int rule_b = arm_ok ? pick8(a.rule, arm) : -1;
     // rows whose rule looks beyond their own signals are decided in a second sweep (uniform over the workgroup);
@@ -159,7 +159,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
         const int k1 = min(kb, k0 + rows_per_stage);
         const int kmine = k0 + threadIdx.x;                   // first (usually only) row of this thread in the stage
         float xtok0 = xtok_first;
-        if (k0 > 0) {                                         // further stages (K > rows_per_stage): load late
+        if (__builtin_expect(k0 > 0, 0)) {                                         // further stages (K > rows_per_stage): load late
             tok0 = (want_tok && kmine < k1) ? a.draft_tok[(int64_t)b * K + kmine] : -1;
             __syncthreads();
             if constexpr (SHARDED) {
@@ -182,7 +182,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
             uint32_t f = 0;
             float lse, H, p1, p2, mg;
             double lse_d = NAN;
-            if (r.bad) {
+            if (__builtin_expect(r.bad, 0)) {
                 f |= TAPOUT_FLAG_BAD_ROW;
                 lse = H = p1 = p2 = mg = NAN;
             } else {
@@ -233,7 +233,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
             if (f) atomicOr(&sh_flags, f);
         }
     }
-    if (msh >= 0 && !sweep) {
+    if (__builtin_expect(msh >= 0 && !sweep, 1)) {
         // Lane-merge path without a second sweep: row k was thread k's, so the rows are lanes of the first wavefront
         // and ballots give the stop position and the flags; no barrier, no scan through LDS.
         if (threadIdx.x < kWave) {
@@ -249,7 +249,7 @@ __device__ inline void draft_finalize_body(const DraftFinalArgs &a, const int b)
         return;
     }
     __syncthreads();                       // orders the LDS / scratch writes above before the scan
-    if (sweep) {
+    if (__builtin_expect(sweep, 0)) {
         for (int k = threadIdx.x; k < kb; k += kFinalBlock) {
             if (sh_dec[k] != 2) continue;
             const int arm_k = tok_mode ? a.arm[(int64_t)b * a.arm_stride + k] : arm;      // in range: checked when it was marked

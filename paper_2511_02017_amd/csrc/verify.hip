@@ -340,7 +340,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
         more_requests();
         shT[threadIdx.x] = tv;
         stage_commit(sh_part, st, c0);
-    } else if (msh >= 0) {
+    } else if (__builtin_expect(msh >= 0, 1)) {
         // target partials run over every element of their slice: plain pieces, nothing left out
         // all requests first, then one wait for the lot (see lane_merge_pin)
         const LaneRegs ln = lane_merge_issue(a.part + (int64_t)b * (K + 1) * a.nsplit, K + 1, a.nsplit, msh);
@@ -363,7 +363,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     }
     uint32_t f0 = 0;
     n = __builtin_amdgcn_readfirstlane(n);
-    if (n < 1 || n > K) { f0 |= TAPOUT_FLAG_BAD_NDRAFT; n = n < 1 ? 1 : K; }
+    if (__builtin_expect(n < 1 || n > K, 0)) { f0 |= TAPOUT_FLAG_BAD_NDRAFT; n = n < 1 ? 1 : K; }
     const bool greedy = __builtin_amdgcn_readfirstlane((int)greedy_raw) != 0;
     SampleJob job;
     job.kind = 0; job.row = 0; job.ref_p = 0.0f; job.ref_q = 0.0f; job.lam = 0.0;
@@ -374,7 +374,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     for (int k0 = 0; k0 <= n; k0 += rows_per_stage) {
         const int k1 = min(n + 1, k0 + rows_per_stage);
         const int kmine = k0 + threadIdx.x;
-        if (k0 > 0) {                               // further stages (K + 1 > rows_per_stage): load late
+        if (__builtin_expect(k0 > 0, 0)) {                               // further stages (K + 1 > rows_per_stage): load late
             tok0 = -1;
             if (kmine < k1 && kmine < n) {
                 const int64_t i = (int64_t)b * K + kmine;
@@ -403,7 +403,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
             else if (need_top1) probe = argmax_issue(row, a.t_dtype, a.V, r.cand);
             uint32_t f = 0;
             double lse_d = NAN;
-            if (r.bad) f |= TAPOUT_FLAG_BAD_ROW;
+            if (__builtin_expect(r.bad, 0)) f |= TAPOUT_FLAG_BAD_ROW;
             else lse_d = (r.R + log2(r.S)) * kLn2;
             // greedy sequences decide on the argmax; the others only report it: they look at the window last
             if constexpr (!SHARDED)
@@ -417,7 +417,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                     const double lse_q = sh_qrows[k].lse;
                     lq = (float)((double)sh_qrows[k].xt - lse_q);
                     last_dl = (float)lse_q;
-                } else if (k != kmine) {                       // more rows than threads: load late
+                } else if (__builtin_expect(k != kmine, 0)) {                       // more rows than threads: load late
                     t = a.draft_tok[i]; u = a.u_accept[i]; lq = a.logq_tok[i];
                     if (a.draft_lse) last_dl = a.draft_lse[i];
                 }
@@ -431,7 +431,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
                     }
                 bool acc = false;
                 float lp = NAN;
-                if (t < 0 || t >= a.V) f |= TAPOUT_FLAG_BAD_TOKEN;
+                if (__builtin_expect(t < 0 || t >= a.V, 0)) f |= TAPOUT_FLAG_BAD_TOKEN;
                 else if (!r.bad) {
                     lp = (float)((double)xt - lse_d);
                     if (greedy) acc = (t == top1);
@@ -457,7 +457,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     }
     constexpr uint32_t kFatal = TAPOUT_FLAG_BAD_NDRAFT | TAPOUT_FLAG_BAD_TOKEN | TAPOUT_FLAG_BAD_ROW;
     HEAD_STAMP(2);                                               // every row's lse, log p(tok), accept decision
-    if (msh >= 0) {
+    if (__builtin_expect(msh >= 0, 1)) {
         // Lane-merge path: row k was thread k's, so the rows are lanes of the first wavefront.  Ballots give the
         // first rejection and the flags, lane m hands over what the job needs of row m, one barrier publishes it.
         if (threadIdx.x < kWave) {
@@ -500,7 +500,7 @@ __device__ inline SampleJob verify_head(const VerifyArgs &a, int b, bool writer,
     const bool flagged = sh_bcast[1] != 0;
     const uint32_t f = (uint32_t)sh_bcast[2];
     float Mm, dl_m = 0.0f; int32_t top1m; double lse_m;
-    if (sh_bcast[4]) {
+    if (__builtin_expect(sh_bcast[4] != 0, 1)) {
         Mm = __int_as_float(sh_bcast[5]); top1m = sh_bcast[6]; dl_m = __int_as_float(sh_bcast[7]); lse_m = *sh_lse;
     } else {                                     // more rows than threads: merge row m once more
         __syncthreads();
@@ -816,7 +816,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     // the per-request checks of the general path are branches, and across branches the compiler waits for every
     // outstanding request where the first chunk's would do.
     const bool whole = live && r.t_al && (r.d_al || !resid) && (s + 1) * kSampleSlice <= a.V;       // wavefront-uniform
-    if (whole) {
+    if (__builtin_expect(whole, 1)) {
         const char *tp = r.trow + (int64_t)base * Elem<TD>::size;
         const char *dp = r.drow + (int64_t)base * Elem<DD>::size;
 #pragma unroll
@@ -878,7 +878,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
                     double cA = 0.0, cB = 0.0, cR = 0.0, cDs = 0.0;
                     chunk_pair_tab(qt[c].w[0], qd[c].w[0], shE, lam, band, cA, cB, cR, cDs, any_band);
                     // a chunk that holds a magnitude below the table's range is formed again, the slow way
-                    if (__builtin_amdgcn_ballot_w64(cA != cA || cB != cB) != 0) {
+                    if (__builtin_expect(__builtin_amdgcn_ballot_w64(cA != cA || cB != cB) != 0, 0)) {
                         asm volatile("" ::: "memory");
                         any_band = 0;
                         cA = 0.0; cB = 0.0; cR = 0.0; cDs = 0.0;
@@ -889,7 +889,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
                     static_assert(!TT && !TD_, "the table serves both rows or neither");
                     chunk_pair<false, false>(ct, cd, rp, rq, shT, shE, c2, top, lam, band, A, Bs, R, Ds, any_band);
                 }
-                if (any_band != 0) {
+                if (__builtin_expect(any_band != 0, 0)) {
                     asm volatile("" ::: "memory");                  // keep this a branch: a select would cost every element
                     // almost never taken: form the chunk's exponentials again and treat its band elements one by one
 #pragma unroll 1
@@ -908,7 +908,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
                 double cA = 0.0;
                 if constexpr (TT) {
                     cA = chunk_one_tab(qt[c].w[0], shE);
-                    if (__builtin_amdgcn_ballot_w64(cA != cA) != 0) {
+                    if (__builtin_expect(__builtin_amdgcn_ballot_w64(cA != cA) != 0, 0)) {
                         asm volatile("" ::: "memory");
                         cA = 0.0;
 #pragma unroll
@@ -926,7 +926,7 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
     static_assert(kTabT == kTabD, "the table serves both rows or neither");
     if constexpr (kTabT) {
         // (a job on one row, the bonus position, has no draft row: the pass then sums the target row alone)
-        if (tab_t) pass(true_type{}, true_type{}); else pass(false_type{}, false_type{});
+        if (__builtin_expect(tab_t, 1)) pass(true_type{}, true_type{}); else pass(false_type{}, false_type{});
     } else {
         pass(false_type{}, false_type{});
     }
@@ -1162,7 +1162,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
         if constexpr (TAIL)
             if (tid < TAPOUT_MAX_ARMS) ucb_lane_finish(a.bandit, b, tid, ucb, acc_len, a.b_arm_out, a.b_flags);
     };
-    if (job.kind == 0) { end_round(); return; }                       // the slice sums of such a sequence are stale: unused
+    if (__builtin_expect(job.kind == 0, 0)) { end_round(); return; }                       // the slice sums of such a sequence are stale: unused
     if (has_first) { acc[0] = f0; acc[1] = f1; acc[2] = f2; acc[3] = f3; acc[4] = f4; }
     for (int s = tid + kVBlock; s < a.nsl; s += kVBlock)              // vocabularies beyond 256 slices
 #pragma unroll
@@ -1205,7 +1205,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
     if (w.kind == 1) {
         const bool close = fabs(delta) <= kEta * job.lam;
         bool certified = close && Z > 0.0 && fabs(delta) * tot[4] <= 2.0e-10 * Z;
-        if (!certified && close && band_n <= kBandCap) {
+        if (__builtin_expect(!certified && close && band_n <= kBandCap, 0)) {
             n_band = band_n;
             const bool tab_ok = TD == TAPOUT_BF16 && DD == TAPOUT_BF16 && !(a.vflags & kVerifyNoExpTable) && tab_job_ok(job);    // as in the slice kernel
             const bool tab_t = tab_ok, tab_d = tab_ok;
@@ -1213,7 +1213,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
                                      delta, band_n, band_i, &shl);
             certified = Z > 0.0;
         }
-        if (!certified) {
+        if (__builtin_expect(!certified, 0)) {
             n_band = 0;
             // slow path: exact slice weights with the exact L (also the p == q case: then Z may vanish)
             double ztot = 0.0;
@@ -1259,7 +1259,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
         // slice whose inclusive prefix (slice order) first exceeds the target
         double cum_at = 0.0;
         int s_found = -1;
-        if (a.nsl <= kVBlock) {
+        if (__builtin_expect(a.nsl <= kVBlock, 1)) {
             // this thread's slice is the one whose sums it fetched with the first round trip: no second look at memory
             double z_mine = 0.0;
             if (tid < a.nsl) {
@@ -1306,7 +1306,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
                 cum += slice_total;
             }
         }
-        if (token < 0) {
+        if (__builtin_expect(token < 0, 0)) {
             // rounding left no crossing: the largest index with positive weight
             {
                 for (int s = 0; s < a.nsl; ++s) {
@@ -1323,7 +1323,7 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
         if (token < 0) token = 0;
         if (a.tok_direct) a.tok_direct[j] = token;
         else a.out_tok[(int64_t)b * (a.K + 1) + job.row] = token;
-        if (draft_bad) {
+        if (__builtin_expect(draft_bad, 0)) {
             uint32_t f = a.flags_ws[b] | TAPOUT_FLAG_BAD_ROW;
             a.flags_ws[b] = f;
             if (a.flags) a.flags[b] = f;

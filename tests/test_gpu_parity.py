@@ -784,9 +784,9 @@ def test_residual_with_a_few_tokens_where_p_equals_q():
 @pytest.mark.parametrize("shift", [0.0, 70.0, -40.0, 55.0])
 @FUSE
 def test_bfloat16_final_token_table_and_its_limits(shift, fuse):
-    """The final-token pass of bfloat16 row pairs takes exp(x) from a table of the bfloat16 values with 2^-12 <= |x| < 63.75.
+    """The final-token pass of bfloat16 row pairs takes exp(x) from a table of the bfloat16 values with 2^-12 <= |x| < 63.5.
     Rows full of what the table does not hold: exact zeros, +-0, magnitudes below 2^-12 (formed by a polynomial in a
-    chunk of their own), logits at and below -63.75 (weigh nothing), masked entries, a vocabulary that ends inside a
+    chunk of their own), logits at and below -63.5 (weigh nothing; -63.25 is the table's last entry), masked entries, a vocabulary that ends inside a
     slice; and whole rows shifted so that the row maximum leaves the table's range (+70, -40: such jobs compute their
     exponentials) or sits just inside it (+55).  Against the oracle, and against the same call with the table switched
     off ("exp_lookup" = 0): same tokens, same accepted lengths."""
@@ -801,7 +801,9 @@ def test_bfloat16_final_token_table_and_its_limits(shift, fuse):
         x[(r >= 0.08) & (r < 0.14)] *= 1e-5                      # far below 2^-12
         x[(r >= 0.14) & (r < 0.16)] = 2.0 ** -12                 # the table's first entry
         x[(r >= 0.16) & (r < 0.18)] = -(2.0 ** -12) * (1 - 2.0 ** -8)   # the largest magnitude below it
-        x[(r >= 0.18) & (r < 0.20)] = -63.75
+        x[(r >= 0.18) & (r < 0.19)] = -63.75
+        x[(r >= 0.19) & (r < 0.195)] = -63.5                     # the first magnitude beyond the table
+        x[(r >= 0.195) & (r < 0.20)] = -63.25                    # the table's last entry
         x[(r >= 0.20) & (r < 0.22)] = -64.0
         x[(r >= 0.22) & (r < 0.24)] = -3.0e38
         x[(r >= 0.24) & (r < 0.27)] = float("-inf")

@@ -140,9 +140,6 @@ struct BanditArgs {
     double ad_alpha, ad_beta1, ad_beta2, ad_eps;
     int32_t ad_steer;             // tapout_config.adaedl_steer
 };
-// Verification + final token: the head kernel merges the target partials of each sequence, takes the
-// accept decisions and describes the final-token draw (SampleJob); the slice kernel sums the row pair
-// per slice; the locate kernel finds the token.
 // Kernel arguments sit in device memory and reach a wavefront through the scalar cache, one 64-byte line per miss,
 // and the compiler loads a field where the code first wants it: a kernel that is a chain of round trips anyway takes
 // a miss of this kind at several points along the chain (with the arguments in host memory instead, the final-token
@@ -165,6 +162,9 @@ __device__ inline void warm_args(const Ts &...as)
     asm volatile("" :: "s"(acc));
 }
 
+// Verification + final token: the head kernel merges the target partials of each sequence, takes the
+// accept decisions and describes the final-token draw (SampleJob); the slice kernel sums the row pair
+// per slice; the locate kernel finds the token.
 constexpr int32_t kVerifyOwnQ = 1;          // accept decisions form log q(tok) from the draft partials (see dpart)
 constexpr int32_t kVerifyNoExpTable = 2;    // final-token slice kernel: computed exponentials also for bfloat16 row pairs
 // (Kept at 512 bytes or less: past that the compiler reaches the arguments differently and the fused slice kernel

@@ -734,7 +734,8 @@ __global__ __launch_bounds__(kVBlock) __attribute__((amdgpu_waves_per_eu(4))) vo
 {
     // The table serves row pairs of bfloat16 only: with one row computed and one looked up the compiler's schedule
     // of the mixed loop wants 160-170 registers (two wavefronts per SIMD), and held to four wavefronts it spills
-    // inside the loop (V = 256000, 512 sequences, binary32 target rows: 210 us against 139 us all computed).
+    // inside the loop (V = 256000, 512 sequences, binary32 target rows: 210 us against 139 us all computed; at three
+    // wavefronts per SIMD, 154 registers and no spills, 147 us).
     constexpr bool kTabT = TD == TAPOUT_BF16 && DD == TAPOUT_BF16, kTabD = kTabT;
     // LDS: the accept decisions' buffers (FUSED) are dead once the job is known; the table takes their place
     constexpr size_t kHeadBytes = sizeof(Partial) * kStageCap + sizeof(DraftRowLse) * kWave + 8 + 32 + 8 + kScanCap;

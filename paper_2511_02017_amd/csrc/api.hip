@@ -20,6 +20,7 @@ struct tapout_ctx {
     double *part1 = nullptr, *part2 = nullptr;                // residual sampler slice sums
     JobRecord *jobs = nullptr;                                 // per final-token job: what to draw from, and its band list
     uint32_t *flags_ws = nullptr;
+    int32_t *arm_played = nullptr;                             // [max_batch]: the arms a round was drafted under (see draft_stats_impl)
     double *exp_table = nullptr;                               // 2^(k/256), k = 0..255, for the final-token passes
     int nsl_max = 0;                                           // final-token slices per row at cfg.vocab
     double *sum_r = nullptr, *sum_r2 = nullptr; int64_t *count = nullptr;   // bandit state [n_bandits, n_arms]
@@ -302,6 +303,7 @@ tapout_status tapout_create(tapout_ctx **out, const tapout_config *cfg)
            && hipMemcpy(c->exp_table, table.data(), table.size() * sizeof(double), hipMemcpyHostToDevice) == hipSuccess
            && hipMalloc(&c->jobs, njobs * sizeof(JobRecord)) == hipSuccess
            && hipMalloc(&c->flags_ws, (size_t)cfg->max_batch * sizeof(uint32_t)) == hipSuccess
+           && hipMalloc(&c->arm_played, (size_t)cfg->max_batch * sizeof(int32_t)) == hipSuccess
            && hipMalloc(&c->sum_r, nstate * sizeof(double)) == hipSuccess
            && hipMalloc(&c->sum_r2, nstate * sizeof(double)) == hipSuccess
            && hipMalloc(&c->count, nstate * sizeof(int64_t)) == hipSuccess
@@ -338,7 +340,7 @@ tapout_status tapout_destroy(tapout_ctx *ctx)
     DeviceGuard guard(ctx->cfg.device);
     profile_release(ctx);
     (void)hipFree(ctx->part); (void)hipFree(ctx->part_t); (void)hipFree(ctx->part1); (void)hipFree(ctx->part2);
-    (void)hipFree(ctx->jobs); (void)hipFree(ctx->flags_ws);
+    (void)hipFree(ctx->jobs); (void)hipFree(ctx->flags_ws); (void)hipFree(ctx->arm_played);
     (void)hipFree(ctx->exp_table);
     (void)hipFree(ctx->sum_r); (void)hipFree(ctx->sum_r2); (void)hipFree(ctx->count);
     (void)hipFree(ctx->prev_entropy); (void)hipFree(ctx->accept_rate); (void)hipFree(ctx->lambda); (void)hipFree(ctx->round_entropy);
@@ -462,6 +464,10 @@ tapout_status draft_stats_impl(tapout_ctx *ctx, const tapout_logits *draft,
     if (defer) {
         if (u_draft || !draft_tok) return fail(ctx, TAPOUT_EINVAL, "internal: a deferred epilogue needs the caller's draft tokens");
         r.tok = draft_tok; r.tok_rows = K;
+        // The deferred epilogue runs in the launch whose other workgroups may end the round and write the next
+        // round's arms over the caller's array (sequence-level bandits: arm is [B], in and out): it reads the arms
+        // the round was drafted under from a copy that the streaming pass, two launches earlier, leaves here.
+        if (arm && ctx->positions == 1) { r.arm_src = arm; r.arm_dst = ctx->arm_played; }
     }
     hipError_t e = pair ? stream_pair(ctx, r, draft->dtype, *pair, st)
                         : timed(ctx, TAPOUT_PROFILE_DRAFT_PASS, [&](Timing tm) { return launch_row_reduce(r, draft->dtype, true, st, tm); });
@@ -486,7 +492,7 @@ tapout_status draft_stats_impl(tapout_ctx *ctx, const tapout_logits *draft,
     DraftFinalArgs f{};
     f.base = draft->ptr; f.dtype = draft->dtype; f.stride_b = draft->stride_b; f.stride_k = draft->stride_k;
     f.B = B; f.K = K; f.V = V; f.nsplit = nsplit; f.per = r.per; f.part = ctx->part;
-    f.draft_tok = draft_tok; f.k_len = k_len; f.arm = arm;
+    f.draft_tok = draft_tok; f.k_len = k_len; f.arm = r.arm_dst ? r.arm_dst : arm;
     f.arm_stride = ctx->positions > 1 ? ctx->cfg.max_k : 0;
     f.n_arms = ctx->cfg.n_arms;
     for (int a = 0; a < TAPOUT_MAX_ARMS; ++a) { f.rule[a] = ctx->cfg.rule[a]; f.threshold[a] = ctx->cfg.threshold[a]; }

@@ -90,6 +90,8 @@ struct RowReduceArgs {
     JobRecord *clear_jobs;        // NULL, or [B]: the first workgroup of sequence b empties the band list of its job record
     const int32_t *tok;           // NULL, or [B, tok_rows]: row k < tok_rows of sequence b has a token whose logit the
     int32_t tok_rows;             //   slice holding it puts into its partial (pad[0]; NaN bits in all other partials)
+    const int32_t *arm_src;       // NULL, or [B] with arm_dst [B]: the first workgroup of sequence b copies the sequence's arm
+    int32_t *arm_dst;             //   (a later launch overwrites the caller's array while another of its workgroups still wants the old value)
 };
 // Streaming pass: one Partial per (row, slice).  Returns hipGetLastError() after enqueueing.
 hipError_t launch_row_reduce(const RowReduceArgs &a, int dtype, bool full, hipStream_t st, Timing tm);

@@ -303,6 +303,7 @@ __device__ inline void stream_pass_body(const RowReduceArgs &a, const int split,
         n_active = (n < 1 ? 1 : (n > a.KK - 1 ? a.KK - 1 : n)) + 1;
     }
     if (a.clear_jobs && split == 0 && k == 0 && tid == 0) a.clear_jobs[b].band_cnt = 0;
+    if (a.arm_dst && split == 0 && k == 0 && tid == 0) a.arm_dst[b] = a.arm_src[b];
     if (k >= n_active) return;
     // The row's token, if it has one.  Requested as a vector load (the index carries a zero the compiler cannot
     // see through): a scalar load from memory would hold up the first wait for the kernel arguments and with it

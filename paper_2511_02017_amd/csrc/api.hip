@@ -799,13 +799,13 @@ struct RoundTail { const int32_t *arm_in, *gamma; const uint8_t *active; const f
 // fin (tapout_round): the draft epilogue has not run: the accept decisions take log q(tok) from the draft partials
 // (fin_nsplit slices per draft row) and the epilogue runs in the locate kernel's launch.
 hipError_t verify_rest(tapout_ctx *ctx, const VerifyCall &c, hipStream_t st, const RoundTail *tail = nullptr,
-                       const DraftFinalArgs *fin = nullptr, int fin_nsplit = 0)
+                       const DraftFinalArgs *fin = nullptr, int fin_nsplit = 0, int tail_kind = 1)
 {
     VerifyArgs va{};
     if (fin) { va.vflags |= kVerifyOwnQ; va.d_nsplit = fin_nsplit; va.dpart = fin->part; }
     if (!ctx->exp_lookup) va.vflags |= kVerifyNoExpTable;
     if (tail) {
-        va.bandit_tail = 1;
+        va.bandit_tail = tail_kind;                 // 1: in the locate workgroups (UCB), 2: workgroups of their own (Thompson Sampling)
         va.bandit = bandit_args(ctx, c.B);
         va.b_arm_in = tail->arm_in; va.b_gamma = tail->gamma; va.b_active = tail->active; va.b_u_ts = tail->u_ts;
         va.b_arm_out = tail->arm_out; va.b_flags = tail->flags;
@@ -898,14 +898,16 @@ tapout_status tapout_round(tapout_ctx *ctx, const tapout_round_args *a, void *st
         if (e != hipSuccess) return hip_fail(ctx, e, "target pass launch");
     }
     // Sequence-level UCB bandits, one per sequence: the final-token locate kernel, one workgroup per sequence, also
-    // applies the reward and picks the next arm.  Thompson Sampling (heavy draws), shared and token-level bandits take
-    // a launch of their own.
-    const bool tail = ctx->positions == 1 && ctx->cfg.n_bandits != 1 &&
-                      (ctx->cfg.policy == TAPOUT_UCB1 || ctx->cfg.policy == TAPOUT_UCB_TUNED);
+    // applies the reward and picks the next arm.  Gaussian Thompson Sampling, shared and token-level bandits take a
+    // launch of their own.
+    const bool own = ctx->positions == 1 && ctx->cfg.n_bandits != 1;
+    const bool tail = own && (ctx->cfg.policy == TAPOUT_UCB1 || ctx->cfg.policy == TAPOUT_UCB_TUNED);
+    // Thompson Sampling with Beta posteriors: the same launch carries the end of the round as workgroups of its own
+    const bool ts_tail = own && ctx->cfg.policy == TAPOUT_TS_BETA && a->u_ts_next != nullptr;
     const RoundTail rt{a->arm, a->gamma, a->active, a->u_ts_next, a->arm, a->select_flags};
-    e = verify_rest(ctx, c, st, tail ? &rt : nullptr, defer ? &fin : nullptr, fin_nsplit);
+    e = verify_rest(ctx, c, st, (tail || ts_tail) ? &rt : nullptr, defer ? &fin : nullptr, fin_nsplit, ts_tail ? 2 : 1);
     if (e != hipSuccess) return hip_fail(ctx, e, "verify launch");
-    if (tail) return TAPOUT_OK;
+    if (tail || ts_tail) return TAPOUT_OK;
     return tapout_bandit_update_select(ctx, a->B, a->arm, a->accept_len, n_draft, a->gamma, a->active, a->u_ts_next, a->arm, a->select_flags, stream);
 }
 

@@ -1114,6 +1114,17 @@ __global__ __launch_bounds__(kVBlock) void verify_locate(VerifyArgs a, DraftFina
     if constexpr (FIN) warm_args(a, fin); else warm_args(a);
     static_assert(kVBlock == kFinalBlock, "the draft epilogue runs in this kernel's workgroups");
     LOCATE_STAMP(0);                                             // entry
+    // Thompson Sampling (tapout_round, bandit_tail == 2): the end of the round needs nothing of this launch, only the
+    // accepted lengths of an earlier one, so it rides along as workgroups of its own behind the others, sixteen
+    // sequences each (sixteen lanes per sequence), instead of taking a launch after this one.
+    if (a.bandit_tail == 2) {
+        const int first = (FIN ? a.B : 0) + a.n_jobs;
+        if ((int)blockIdx.x >= first) {
+            update_select_ts_lanes(a.bandit, ((int)blockIdx.x - first) * (kVBlock / 16) + (int)(threadIdx.x >> 4), threadIdx.x & 15,
+                                   a.b_arm_in, a.accept_len, a.n_draft, a.b_gamma, a.b_active, a.b_u_ts, a.b_arm_out, a.b_flags);
+            return;
+        }
+    }
     if constexpr (FIN)
         if ((int)blockIdx.x < a.B) {
             draft_finalize_body<false>(fin, blockIdx.x);
@@ -1543,12 +1554,17 @@ hipError_t launch_typed(const VerifyArgs &a, const DraftFinalArgs &fin, bool wit
         if (a.fused_head) launch_kernel(verify_slices<TD, DD, true>, grid12, block, st, tm, a);
         else launch_kernel(verify_slices<TD, DD, false>, grid12, block, st, tm, a);
     }
-    else if (with_fin) {
-        if (!a.bandit_tail) launch_kernel(verify_locate<TD, DD, false, true>, dim3(a.n_jobs + a.B), block, st, tm, a, fin);
-        else launch_kernel(verify_locate<TD, DD, true, true>, dim3(a.n_jobs + a.B), block, st, tm, a, fin);
+    else {
+        // bandit_tail 1: the locate workgroups end the round (UCB); 2: workgroups of their own do (Thompson Sampling)
+        const unsigned extra = a.bandit_tail == 2 ? (unsigned)((a.B + kVBlock / 16 - 1) / (kVBlock / 16)) : 0u;
+        const bool tail = a.bandit_tail == 1;
+        if (with_fin) {
+            if (!tail) launch_kernel(verify_locate<TD, DD, false, true>, dim3(a.n_jobs + a.B + extra), block, st, tm, a, fin);
+            else launch_kernel(verify_locate<TD, DD, true, true>, dim3(a.n_jobs + a.B), block, st, tm, a, fin);
+        }
+        else if (!tail) launch_kernel(verify_locate<TD, DD, false, false>, dim3(a.n_jobs + extra), block, st, tm, a, fin);
+        else launch_kernel(verify_locate<TD, DD, true, false>, dim3(a.n_jobs), block, st, tm, a, fin);
     }
-    else if (!a.bandit_tail) launch_kernel(verify_locate<TD, DD, false, false>, dim3(a.n_jobs), block, st, tm, a, fin);
-    else launch_kernel(verify_locate<TD, DD, true, false>, dim3(a.n_jobs), block, st, tm, a, fin);
     return hipGetLastError();
 }
 

@@ -556,7 +556,8 @@ TAPOUT_API tapout_status tapout_rule_state_set(tapout_ctx *ctx, const float *pre
  *                 slices until the launch has about this many), default 4096
  *   "slice_bytes" slice size aimed for when the rows alone already give that
  *                 many workgroups (long rows are still cut), default 65536,
- *                 at least 16384
+ *                 at least 16384; for bfloat16 rows, binary32 rows take slices
+ *                 of as many elements (twice the bytes)
  *   "min_slice"   smallest slice of a row, in elements, default 4096
  *   "fuse_head"   tapout_verify only: 1 = no launch of its own for the accept
  *                 decisions, every workgroup of the final-token slice kernel

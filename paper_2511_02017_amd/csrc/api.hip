@@ -872,12 +872,14 @@ tapout_status tapout_round(tapout_ctx *ctx, const tapout_round_args *a, void *st
     hipStream_t st = (hipStream_t)stream;
     // The target pass reads nothing the draft side writes unless n_draft is this round's stop position: then one launch
     // streams the draft rows and the target rows together, both cut into the same number of slices.
-    // (Tensors of one element size only: with mixed sizes the two halves want different slice counts and register
-    // budgets, and the pair measured slower than two launches.)
-    const bool pair = a->n_draft != nullptr && a->n_draft != a->n_stop && 2 * a->B <= 65535 && a->draft->dtype == a->target->dtype;
+    // (Tensors of different element sizes too: slices go by the element, so both halves want the same number of them.
+    // V = 256000, 512 sequences, bfloat16 draft and binary32 target rows: 1213 us against 388 + 828 us.)
+    const bool pair = a->n_draft != nullptr && a->n_draft != a->n_stop && 2 * a->B <= 65535;
     if (pair) {
         // slices for the rows of both tensors together: half as many, twice as long, as either pass would take alone
-        c.nsplit = choose_nsplit(ctx, (int64_t)a->B * (2 * a->K + 1), a->V, a->target->dtype);
+        // (the slice count of the tensor with the larger elements: never more slices than the other would take)
+        const int wide = (a->target->dtype == TAPOUT_F32 || a->draft->dtype == TAPOUT_F32) ? TAPOUT_F32 : TAPOUT_BF16;
+        c.nsplit = choose_nsplit(ctx, (int64_t)a->B * (2 * a->K + 1), a->V, wide);
         if ((size_t)((int64_t)a->B * (a->K + 1) * c.nsplit) > ctx->part_cap) return fail(ctx, TAPOUT_EINVAL, "internal: partial buffer too small");
     }
     // With n_draft from the caller nothing of the verification waits for the draft epilogue's outputs if the accept
